@@ -1,0 +1,118 @@
+"""Seeded synthetic inputs shared by the tests, the smoke check and the benchmark.
+
+This module holds no arithmetic of the method: it only draws Llama-shaped key / value / query
+tensors with the outlier structure the workloads call for and narrows them to 16 bits.  The
+16-bit tensor *is* the input; both the HIP path and the CPU oracle receive the same bytes.
+
+Recipe (stands in for the paper's LongBench / GSM8k activations, Sec. 4.1, which need model
+weights and datasets that are not available here):
+  keys   ~ N(0,1); per (layer, kv head) ``n_outlier`` of the d channels get a constant offset
+           drawn from N(20, sigma=2); optionally ``n_drift`` further channels get +slope*t;
+  values ~ N(0,1);   queries ~ N(0,1).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+F16, BF16 = 0, 1
+
+
+def f32_to_bits16(x: np.ndarray, dtype: int) -> np.ndarray:
+    """Narrow float32 to 16-bit patterns (round to nearest even), as uint16."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    if dtype == F16:
+        return x.astype(np.float16).view(np.uint16)
+    u = x.view(np.uint32)
+    rounded = u + (np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1)))
+    return (rounded >> np.uint32(16)).astype(np.uint16)
+
+
+def bits16_to_f32(b: np.ndarray, dtype: int) -> np.ndarray:
+    b = np.ascontiguousarray(b, dtype=np.uint16)
+    if dtype == F16:
+        return b.view(np.float16).astype(np.float32)
+    return (b.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def channel_structure(seed: int, H: int, d: int, n_outlier: int = 4, n_drift: int = 0):
+    """Per kv head: outlier channel ids + offsets, and drift channel ids (disjoint)."""
+    rng = np.random.default_rng(seed)
+    off = np.zeros((H, d), dtype=np.float32)
+    drift = np.zeros((H, d), dtype=np.float32)
+    for h in range(H):
+        perm = rng.permutation(d)
+        oc = perm[:n_outlier]
+        off[h, oc] = rng.normal(20.0, 2.0, size=n_outlier).astype(np.float32)
+        if n_drift:
+            drift[h, perm[n_outlier:n_outlier + n_drift]] = 1.0
+    return off, drift
+
+
+def make_kv(seed: int, B: int, T: int, H: int, d: int, dtype: int, n_outlier: int = 4,
+            n_drift: int = 0, slope: float = 0.01, t0: int = 0):
+    """K, V as uint16 [B, T, H, d] (token-major, the layout an append call takes)."""
+    rng = np.random.default_rng(seed)
+    off, drift = channel_structure(seed + 7919, H, d, n_outlier, n_drift)
+    k = rng.standard_normal((B, T, H, d), dtype=np.float32)
+    v = rng.standard_normal((B, T, H, d), dtype=np.float32)
+    k += off[None, None]
+    if n_drift:
+        t = (np.arange(T, dtype=np.float32) + np.float32(t0))[None, :, None, None]
+        k += np.float32(slope) * t * drift[None, None]
+    return f32_to_bits16(k, dtype), f32_to_bits16(v, dtype)
+
+
+def make_q(seed: int, B: int, Hq: int, d: int, dtype: int) -> np.ndarray:
+    rng = np.random.default_rng(seed + 104729)
+    return f32_to_bits16(rng.standard_normal((B, Hq, d), dtype=np.float32), dtype)
+
+
+def layer_bits(seed: int, n_layers: int, scheme: str = "mixed248"):
+    """Per-layer bit map.  'mixed248': u<0.25 -> 8, u<0.625 -> 4, else 2 (about a quarter of
+    the layers at 8 bits).  'mixed24_8ends': 8-bit on the first and last two layers, the rest
+    50/50 from {2,4}."""
+    rng = np.random.default_rng(seed)
+    u = rng.random(n_layers)
+    if scheme == "mixed248":
+        bits = np.where(u < 0.25, 8, np.where(u < 0.625, 4, 2))
+    elif scheme == "mixed24_8ends":
+        bits = np.where(u < 0.5, 4, 2)
+        bits[:2] = 8
+        bits[-2:] = 8
+    else:
+        raise ValueError(scheme)
+    return [int(b) for b in bits]
+
+
+# ---------------------------------------------------------------------------- device-side draws
+
+
+def make_kv_torch(seed: int, B: int, T: int, H: int, d: int, dtype: int, device, n_outlier: int = 4,
+                  n_drift: int = 0, slope: float = 0.01, t0: int = 0):
+    """Same recipe drawn on the device for shapes too large to ship from the host.
+    Returns torch tensors [B, T, H, d] of the 16-bit dtype."""
+    import torch
+
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed)
+    tdt = torch.float16 if dtype == F16 else torch.bfloat16
+    off, drift = channel_structure(seed + 7919, H, d, n_outlier, n_drift)
+    off_t = torch.from_numpy(off).to(device)
+    k = torch.randn((B, T, H, d), generator=gen, device=device, dtype=torch.float32)
+    k += off_t[None, None]
+    if n_drift:
+        t = (torch.arange(T, device=device, dtype=torch.float32) + float(t0))[None, :, None, None]
+        k += float(slope) * t * torch.from_numpy(drift).to(device)[None, None]
+    k16 = k.to(tdt)
+    del k
+    v16 = torch.randn((B, T, H, d), generator=gen, device=device, dtype=torch.float32).to(tdt)
+    return k16, v16
+
+
+def make_q_torch(seed: int, B: int, Hq: int, d: int, dtype: int, device):
+    import torch
+
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed + 104729)
+    tdt = torch.float16 if dtype == F16 else torch.bfloat16
+    return torch.randn((B, Hq, d), generator=gen, device=device, dtype=torch.float32).to(tdt)

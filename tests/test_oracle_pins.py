@@ -1,0 +1,465 @@
+"""Pins for the CPU oracle: each part is nailed to something the paper or arithmetic fixes,
+never to the oracle's own formula.  CPU only."""
+import os
+
+import numpy as np
+import pytest
+
+from paper_2506_04642_amd import synth
+
+K, V = 0, 1
+F16, BF16 = 0, 1
+CHAN, CROSS, NONE = 0, 1, 2
+
+
+# ------------------------------------------------------------------ P1: 16-bit conversions
+
+
+def test_f16_widen_exhaustive_matches_numpy(oracle):
+    pats = np.arange(65536, dtype=np.uint16)
+    want = pats.view(np.float16).astype(np.float32)
+    got = oracle.widen(pats, F16)
+    finite = np.isfinite(want)
+    assert np.array_equal(got[finite].view(np.uint32), want[finite].view(np.uint32))
+    assert np.all(np.isnan(got[np.isnan(want)]))
+    assert np.array_equal(got[np.isinf(want)], want[np.isinf(want)])
+
+
+def test_bf16_widen_is_a_shift(oracle):
+    pats = np.arange(0, 65536, 7, dtype=np.uint16)
+    want = (pats.astype(np.uint32) << 16).view(np.float32)
+    got = oracle.widen(pats, BF16)
+    ok = ~np.isnan(want)
+    assert np.array_equal(got[ok].view(np.uint32), want[ok].view(np.uint32))
+
+
+def test_f16_narrow_roundtrip_exhaustive(oracle):
+    for h in range(65536):
+        f = np.uint16(h).view(np.float16)
+        if np.isnan(f):
+            continue
+        for mode in ("rne", "down", "up"):
+            assert oracle.f32_to_f16(float(f), mode) == h, (h, mode)
+
+
+def test_f16_rne_matches_numpy_on_random_floats(oracle):
+    rng = np.random.default_rng(1)
+    mags = np.concatenate([
+        rng.standard_normal(60000) * 10.0 ** rng.integers(-9, 5, 60000),
+        rng.uniform(-7e4, 7e4, 20000),
+        (rng.integers(0, 2048, 20000) + 0.5) * 2.0 ** rng.integers(-26, 5, 20000),  # exact ties
+    ]).astype(np.float32)
+    with np.errstate(over="ignore"):
+        want = mags.astype(np.float16).view(np.uint16)
+    for f, w in zip(mags, want):
+        assert oracle.f32_to_f16(float(f), "rne") == int(w), float(f)
+
+
+def test_f16_directed_rounding_brackets_and_is_adjacent(oracle):
+    rng = np.random.default_rng(2)
+    xs = (rng.standard_normal(40000) * 10.0 ** rng.integers(-8, 4, 40000)).astype(np.float32)
+    for f in xs:
+        f = float(f)
+        lo, hi = oracle.f32_to_f16(f, "down"), oracle.f32_to_f16(f, "up")
+        flo, fhi = float(np.uint16(lo).view(np.float16)), float(np.uint16(hi).view(np.float16))
+        assert flo <= f <= fhi
+        if flo != fhi:
+            # adjacent representable numbers: nothing of binary16 lies strictly between
+            nxt = float(np.nextafter(np.float16(flo), np.float16(np.inf)))
+            assert nxt == fhi
+        else:
+            assert flo == f
+
+
+# ------------------------------------------------------------------ P2: quantiser
+
+
+def _block(seed, G, H, d, dtype, outliers=4):
+    k, v = synth.make_kv(seed, 1, G, H, d, dtype, n_outlier=outliers)
+    return k[0], v[0]
+
+
+@pytest.mark.parametrize("dtype", [F16, BF16])
+@pytest.mark.parametrize("bits", [2, 4, 8])
+@pytest.mark.parametrize("mode", [CHAN, CROSS, NONE])
+@pytest.mark.parametrize("which", [K, V])
+def test_reconstruction_error_bound(oracle, dtype, bits, mode, which):
+    """|x - x^| <= scale/2 per element after the mean is re-added (up to binary32 rounding of the
+    few operations involved): the property a min/max uniform quantiser must have."""
+    G, H, d, Gc = 32, 4, 128, 32
+    xk, xv = _block(10 + bits, G, H, d, dtype)
+    x = xk if which == K else xv
+    enc = oracle.encode_block(x, dtype, Gc, bits, mode, which)
+    xhat = oracle.decode_block(enc, Gc, mode, which).astype(np.float64)
+    xt = np.transpose(synth.bits16_to_f32(x, dtype), (1, 0, 2)).astype(np.float64)  # [H,G,d]
+    s = enc["scale"].view(np.float16).astype(np.float64)
+    z = enc["zero"].view(np.float16).astype(np.float64)
+    if which == K:
+        s_el, z_el = s[:, None, :], z[:, None, :]
+    else:
+        s_el, z_el = np.repeat(s, Gc, axis=2), np.repeat(z, Gc, axis=2)
+    qmax = 2 ** bits - 1
+    mean = np.zeros_like(xt)
+    if mode == CHAN:
+        mean = enc["mean"].view(np.float16).astype(np.float64)[:, None, :] + 0 * xt
+    elif mode == CROSS:
+        mean = enc["mean"].view(np.float16).astype(np.float64)[None, :, :] + 0 * xt
+    eps = 2.0 ** -21 * (np.abs(xt) + np.abs(mean) + np.abs(z_el) + qmax * s_el)
+    assert np.all(np.abs(xt - xhat) <= s_el / 2 + eps)
+    assert enc["codes"].max() <= qmax
+    # the range is used: every group reaches the bottom and (unless constant) the top code, give
+    # or take the one step that rounding zero down / scale up to binary16 can cost
+    codes = enc["codes"]
+    if which == K:
+        assert np.all(codes.min(axis=1) <= 1)
+        assert np.all((codes.max(axis=1) >= qmax - 1) | (s == 0))
+    else:
+        cg = codes.reshape(H, G, d // Gc, Gc)
+        assert np.all(cg.min(axis=3) <= 1)
+        assert np.all((cg.max(axis=3) >= qmax - 1) | (s == 0))
+
+
+def test_hand_example_two_bit(oracle):
+    """Deviations {0,1,2,3} at 2 bits: zero = 0, scale = 1, codes = {0,1,2,3} (exact numbers)."""
+    G, H, d, Gc = 16, 1, 128, 32
+    x = np.zeros((G, H, d), dtype=np.float32)
+    x[:, 0, :] = (np.arange(G) % 4)[:, None]
+    xb = synth.f32_to_bits16(x, F16)
+    enc = oracle.encode_block(xb, F16, Gc, 2, NONE, K)
+    assert np.all(enc["scale"].view(np.float16) == 1.0)
+    assert np.all(enc["zero"].view(np.float16) == 0.0)
+    assert np.array_equal(enc["codes"][0], (np.arange(G) % 4)[:, None] * np.ones((1, d), dtype=np.uint8))
+    # values: per-token groups over channels; a token's 32-channel group holding 0..3
+    xv = np.zeros((G, H, d), dtype=np.float32)
+    xv[:, 0, :] = (np.arange(d) % 4)[None, :] + 5.0
+    enc = oracle.encode_block(synth.f32_to_bits16(xv, F16), F16, Gc, 2, NONE, V)
+    assert np.all(enc["scale"].view(np.float16) == 1.0)
+    assert np.all(enc["zero"].view(np.float16) == 5.0)
+    assert np.array_equal(enc["codes"][0, 3], (np.arange(d) % 4).astype(np.uint8))
+
+
+def test_hand_example_four_bit_ties_to_even(oracle):
+    """Deviations 0, 0.5, 1.5, 2.5, 15 at 4 bits: scale 1, zero 0; the halves round to even."""
+    G, H, d, Gc = 16, 1, 128, 128
+    vals = np.array([0, 0.5, 1.5, 2.5, 15, 3.5, 7, 8] * 2, dtype=np.float32)
+    x = np.zeros((G, H, d), dtype=np.float32)
+    x[:, 0, :] = vals[:, None]
+    enc = oracle.encode_block(synth.f32_to_bits16(x, F16), F16, Gc, 4, NONE, K)
+    assert np.all(enc["scale"].view(np.float16) == 1.0)
+    want = np.array([0, 0, 2, 2, 15, 4, 7, 8] * 2, dtype=np.uint8)
+    assert np.array_equal(enc["codes"][0, :, 17], want)
+
+
+def test_constant_group_is_exact(oracle):
+    G, H, d, Gc = 32, 2, 128, 32
+    x = np.full((G, H, d), 3.25, dtype=np.float32)
+    xb = synth.f32_to_bits16(x, BF16)
+    for which in (K, V):
+        for mode in (CHAN, CROSS, NONE):
+            enc = oracle.encode_block(xb, BF16, Gc, 4, mode, which)
+            assert np.all(enc["codes"] == 0)
+            assert np.all(enc["scale"] == 0)
+            xhat = oracle.decode_block(enc, Gc, mode, which)
+            assert np.all(xhat == 3.25)
+
+
+def test_mean_is_the_arithmetic_mean(oracle):
+    """Eq. 1-2 read as a mean: against numpy float64 means, to half a binary16 ulp."""
+    G, H, d, Gc = 32, 8, 128, 32
+    xk, _ = _block(77, G, H, d, BF16)
+    xf = synth.bits16_to_f32(xk, BF16).astype(np.float64)  # [G,H,d]
+    enc = oracle.encode_block(xk, BF16, Gc, 4, CHAN, K)
+    m = enc["mean"].view(np.float16).astype(np.float64)  # [H,d]
+    want = xf.mean(axis=0)
+    assert np.all(np.abs(m - want) <= np.abs(want) * 2.0 ** -11 + 1e-6)
+    enc = oracle.encode_block(xk, BF16, Gc, 4, CROSS, K)
+    m = enc["mean"].view(np.float16).astype(np.float64)  # [G,d]
+    want = xf.mean(axis=1)
+    assert np.all(np.abs(m - want) <= np.abs(want) * 2.0 ** -11 + 1e-6)
+
+
+def test_sign_convention_deviation_is_x_minus_mean(oracle):
+    """With the mean re-added the reconstruction must land near x, not near 2*mean - x."""
+    G, H, d, Gc = 32, 2, 128, 32
+    x = np.zeros((G, H, d), dtype=np.float32)
+    x[:, 0, :] = np.linspace(10, 12, G)[:, None]
+    x[:, 1, :] = np.linspace(-3, -1, G)[:, None]
+    xb = synth.f32_to_bits16(x, F16)
+    for mode in (CHAN, CROSS):
+        enc = oracle.encode_block(xb, F16, Gc, 8, mode, K)
+        xhat = oracle.decode_block(enc, Gc, mode, K)
+        xt = np.transpose(synth.bits16_to_f32(xb, F16), (1, 0, 2))
+        assert np.max(np.abs(xhat - xt)) < 0.02
+
+
+# ------------------------------------------------------------------ P3: storage accounting
+
+
+def _golden_rows():
+    path = os.path.join(os.path.dirname(__file__), "golden", "memory_budget.txt")
+    rows = []
+    for line in open(path):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        name, H, d, G, bitmap, val, prec = line.split()
+        bits = []
+        for part in bitmap.split(","):
+            b, n = part.split("x")
+            bits += [int(b)] * int(n)
+        rows.append((name, int(H), int(d), int(G), bits, float(val), float(prec)))
+    return rows
+
+
+def test_memory_budget_matches_the_papers_printed_values(oracle):
+    """Sec. 3 worked example (~29 %) and the 0.27 budget of Tables 1, 2 and 5."""
+    for name, H, d, G, bits, val, prec in _golden_rows():
+        got = oracle.kv_bytes_ratio(H, d, G, G, bits, CROSS)
+        assert abs(got - val) <= prec, (name, got)
+    # and exactly the closed form 1/H + b/16 + 2/G
+    assert oracle.kv_bytes_ratio(32, 128, 128, 128, [4], CROSS) == 1 / 32 + 4 / 16 + 2 / 128
+    assert oracle.kv_bytes_ratio(32, 128, 128, 128, [4] * 24 + [2] * 8, CROSS) == pytest.approx(0.265625)
+    assert oracle.kv_bytes_ratio(8, 128, 32, 32, [4], CROSS) == 1 / 8 + 4 / 16 + 2 / 32
+    # per-channel block mean: codes b/16 + (scale, zero, mean) per group
+    assert oracle.kv_bytes_ratio(8, 128, 32, 32, [4], CHAN) == 176 / 512
+    assert oracle.kv_bytes_ratio(8, 128, 32, 32, [2], CHAN) == 112 / 512
+    assert oracle.kv_bytes_ratio(8, 128, 32, 32, [8], CHAN) == 304 / 512
+    assert oracle.kv_bytes_ratio(8, 128, 64, 64, [2], CHAN) == 88 / 512
+
+
+# ------------------------------------------------------------------ P4: exact recovery
+
+
+def test_cross_head_single_head_recovers_f16_exactly(oracle):
+    """With one head the cross-head mean is the activation itself: deviation 0, x^ == x."""
+    G, H, d, Gc = 32, 1, 128, 32
+    xk, xv = _block(5, G, H, d, F16)
+    for which, x in ((K, xk), (V, xv)):
+        enc = oracle.encode_block(x, F16, Gc, 2, CROSS, which)
+        assert np.all(enc["codes"] == 0) and np.all(enc["scale"] == 0)
+        xhat = oracle.decode_block(enc, Gc, CROSS, which)
+        assert np.array_equal(xhat[0], synth.bits16_to_f32(x, F16)[:, 0, :])
+
+
+def test_sixteen_bit_layer_returns_the_input_bits(oracle):
+    cfg = oracle.OracleConfig(1, 2, 8, 2, 128, 128, 32, 32, 32, BF16, CHAN, [16], [16])
+    cache = oracle.OracleCache(cfg)
+    k, v = synth.make_kv(3, 2, 77, 2, 128, BF16)
+    cache.append(0, k, v)
+    assert cache.packed_len(0) == 64 and cache.resid_len(0) == 13
+    for b in range(2):
+        kh = cache.reconstruct(0, b, K)  # [H,T,d]
+        assert np.array_equal(kh, np.transpose(synth.bits16_to_f32(k[b], BF16), (1, 0, 2)))
+        vh = cache.reconstruct(0, b, V)
+        assert np.array_equal(vh, np.transpose(synth.bits16_to_f32(v[b], BF16), (1, 0, 2)))
+
+
+# ------------------------------------------------------------------ P5: what mean-centring buys
+
+
+def test_channel_shift_moves_only_the_mean_for_keys(oracle):
+    """Adding an exactly representable per-channel constant to the keys leaves codes and scale
+    unchanged under the per-channel block mean; only mean (and nothing else) absorbs it."""
+    G, H, d, Gc = 32, 2, 128, 32
+    rng = np.random.default_rng(4)
+    # multiples of 1/4 in [-4, 4): block sums and means (multiples of 2^-7) stay exact in
+    # binary16 both before and after a shift by 8
+    base = rng.integers(-16, 16, size=(G, H, d)).astype(np.float32) / 4.0
+    shift = np.zeros((1, H, d), dtype=np.float32)
+    shift[0, :, ::9] = 8.0
+    a = oracle.encode_block(synth.f32_to_bits16(base, F16), F16, Gc, 4, CHAN, K)
+    b = oracle.encode_block(synth.f32_to_bits16(base + shift, F16), F16, Gc, 4, CHAN, K)
+    assert np.array_equal(a["codes"], b["codes"])
+    assert np.array_equal(a["scale"], b["scale"])
+    assert np.array_equal(a["zero"], b["zero"])
+    dm = b["mean"].view(np.float16).astype(np.float32) - a["mean"].view(np.float16).astype(np.float32)
+    assert np.array_equal(dm, shift[0])
+
+
+def test_mean_centring_shrinks_value_scales_under_outlier_channels(oracle):
+    """Sec. 1 / Fig. 2, qualitatively: with outlier channels the per-token value groups are far
+    tighter once the channel mean is removed."""
+    G, H, d, Gc = 32, 2, 128, 32
+    xk, _ = _block(6, G, H, d, F16)  # keys carry the outlier channels; quantise them V-style
+    s_none = oracle.encode_block(xk, F16, Gc, 4, NONE, V)["scale"].view(np.float16).astype(np.float32)
+    s_chan = oracle.encode_block(xk, F16, Gc, 4, CHAN, V)["scale"].view(np.float16).astype(np.float32)
+    assert s_chan.max() < 0.5 * s_none.max()
+    assert s_chan.mean() < s_none.mean()
+
+
+# ------------------------------------------------------------------ P6: attention
+
+
+def _numpy_attention(q, k, v):
+    s = (q @ k.T) / np.sqrt(q.shape[1])
+    s = s - s.max(axis=1, keepdims=True)
+    p = np.exp(s)
+    p /= p.sum(axis=1, keepdims=True)
+    return p @ v
+
+
+@pytest.mark.parametrize("T,d,g", [(1, 8, 1), (5, 8, 3), (64, 128, 4), (37, 128, 8)])
+def test_attention_is_textbook_softmax_attention(oracle, T, d, g):
+    rng = np.random.default_rng(T * 100 + d)
+    q = rng.standard_normal((g, d))
+    k = rng.standard_normal((T, d)).astype(np.float32)
+    v = rng.standard_normal((T, d)).astype(np.float32)
+    got = oracle.attention(q, k, v)
+    want = _numpy_attention(q, k.astype(np.float64), v.astype(np.float64))
+    assert np.max(np.abs(got - want)) < 1e-12
+
+
+def test_attention_is_invariant_to_token_order(oracle):
+    """Eq. 9-10 concatenate raw and reconstructed tokens; softmax attention does not care about
+    the order of (k, v) pairs."""
+    rng = np.random.default_rng(9)
+    q = rng.standard_normal((2, 16))
+    k = rng.standard_normal((40, 16)).astype(np.float32)
+    v = rng.standard_normal((40, 16)).astype(np.float32)
+    perm = rng.permutation(40)
+    assert np.max(np.abs(oracle.attention(q, k, v) - oracle.attention(q, k[perm], v[perm]))) < 1e-13
+
+
+def test_attention_handles_large_scores_without_overflow(oracle):
+    q = np.full((1, 8), 60.0)
+    k = np.stack([np.full(8, 50.0), np.full(8, -50.0)]).astype(np.float32)
+    v = np.stack([np.ones(8), -np.ones(8)]).astype(np.float32)
+    out = oracle.attention(q, k, v)
+    assert np.allclose(out, 1.0)
+
+
+@pytest.mark.parametrize("g,mode", [(1, CHAN), (4, CHAN), (8, CROSS), (4, NONE)])
+def test_cache_attention_equals_numpy_on_the_decoded_cache(oracle, g, mode):
+    """The cache's attend() against numpy attention applied to its own reconstruction, with the
+    grouped-query mapping: query head i reads kv head i // g."""
+    Hkv, d, T = 2, 128, 77
+    cfg = oracle.OracleConfig(1, 2, Hkv * g, Hkv, d, 128, 32, 32, 32, BF16, mode, [4], [4])
+    cache = oracle.OracleCache(cfg)
+    k, v = synth.make_kv(11, 2, T, Hkv, d, BF16)
+    cache.append(0, k, v)
+    q = synth.make_q(11, 2, Hkv * g, d, BF16)
+    out = cache.attend(0, q)
+    qf = synth.bits16_to_f32(q, BF16).astype(np.float64)
+    for b in range(2):
+        kh = cache.reconstruct(0, b, K).astype(np.float64)
+        vh = cache.reconstruct(0, b, V).astype(np.float64)
+        for i in range(Hkv * g):
+            want = _numpy_attention(qf[b, i:i + 1], kh[i // g], vh[i // g])
+            assert np.max(np.abs(out[b, i] - want[0])) < 1e-12
+    # and it stays close to attention over the unquantised inputs (sanity of the whole chain)
+    kf = synth.bits16_to_f32(k, BF16).astype(np.float64)
+    vf = synth.bits16_to_f32(v, BF16).astype(np.float64)
+    ref = _numpy_attention(qf[0, 0:1], kf[0, :, 0, :], vf[0, :, 0, :])
+    assert np.max(np.abs(out[0, 0] - ref[0])) < 0.15
+
+
+# ------------------------------------------------------------------ P7: residual policy
+
+
+@pytest.mark.parametrize("T", [1, 31, 32, 33, 64, 77])
+@pytest.mark.parametrize("R", [32, 64])
+def test_bulk_append_equals_single_token_appends(oracle, T, R):
+    H, d = 2, 128
+    cfg = oracle.OracleConfig(1, 1, 2, H, d, 128, 32, 32, R, F16, CHAN, [4], [2])
+    k, v = synth.make_kv(20 + T, 1, T, H, d, F16)
+    a, b = oracle.OracleCache(cfg), oracle.OracleCache(cfg)
+    a.append(0, k, v)
+    for t in range(T):
+        b.append(0, k[:, t:t + 1], v[:, t:t + 1])
+    ia, ib = a.layer_image(0), b.layer_image(0)
+    assert np.array_equal(ia["bytes"], ib["bytes"]) and np.array_equal(ia["valid"], ib["valid"])
+    assert a.packed_len(0) == (T // R) * R and a.resid_len(0) == T % R
+    # uneven chunks too
+    c = oracle.OracleCache(cfg)
+    cut = [0, T // 3, T // 3 + 1, T]
+    for i in range(3):
+        if cut[i + 1] > cut[i]:
+            c.append(0, k[:, cut[i]:cut[i + 1]], v[:, cut[i]:cut[i + 1]])
+    assert np.array_equal(c.layer_image(0)["bytes"], ia["bytes"])
+
+
+def test_append_beyond_capacity_is_refused(oracle):
+    cfg = oracle.OracleConfig(1, 1, 1, 1, 128, 64, 32, 32, 32, F16, CHAN, [4], [4])
+    cache = oracle.OracleCache(cfg)
+    k, v = synth.make_kv(1, 1, 65, 1, 128, F16)
+    with pytest.raises(OverflowError):
+        cache.append(0, k, v)
+
+
+# ------------------------------------------------------------------ P9: more bits, less error
+
+
+@pytest.mark.parametrize("mode", [CHAN, CROSS, NONE])
+def test_error_falls_with_bits(oracle, mode):
+    G, H, d, Gc = 32, 8, 128, 32
+    xk, xv = _block(31, G, H, d, BF16)
+    for which, x in ((K, xk), (V, xv)):
+        xt = np.transpose(synth.bits16_to_f32(x, BF16), (1, 0, 2)).astype(np.float64)
+        errs = []
+        for bits in (2, 4, 8):
+            enc = oracle.encode_block(x, BF16, Gc, bits, mode, which)
+            errs.append(np.linalg.norm(oracle.decode_block(enc, Gc, mode, which) - xt))
+        assert errs[0] > errs[1] > errs[2]
+
+
+# ------------------------------------------------------------------ packing
+
+
+@pytest.mark.parametrize("which", [K, V])
+@pytest.mark.parametrize("bits", [2, 4, 8])
+@pytest.mark.parametrize("G", [32, 64, 128])
+def test_pack_is_a_bijection_onto_the_block_bytes(oracle, which, bits, G):
+    d = 128
+    rng = np.random.default_rng(bits * 10 + G)
+    codes = rng.integers(0, 2 ** bits, size=(G, d), dtype=np.uint8)
+    packed = oracle.pack_codes(codes, which, bits)
+    assert packed.size == G * d * bits // 8
+    assert np.array_equal(oracle.unpack_codes(packed, which, bits, G, d), codes)
+    full = oracle.pack_codes(np.full((G, d), 2 ** bits - 1, dtype=np.uint8), which, bits)
+    assert np.all(full == 0xFF)  # every bit of the block belongs to exactly one code
+    # a single code lights exactly `bits` bits
+    one = np.zeros((G, d), dtype=np.uint8)
+    one[G - 3, 77] = 2 ** bits - 1
+    assert int(np.unpackbits(oracle.pack_codes(one, which, bits)).sum()) == bits
+
+
+def test_pack_positions_follow_the_documented_tiling(oracle):
+    """Spot values worked by hand from the storage format's rule (16x16 tiles, a line's 16 slots
+    in 2*bits bytes, 8/bits tiles per 16-byte piece, 16 pieces per line group)."""
+    d, G = 128, 32
+
+    def where(which, bits, t, c):
+        one = np.zeros((G, d), dtype=np.uint8)
+        one[t, c] = 1
+        p = oracle.pack_codes(one, which, bits)
+        byte = int(np.flatnonzero(p)[0])
+        return byte, int(np.log2(p[byte]))
+
+    # keys, 8-bit: token 17 (tile 1, line 1), channel 70 (group 4 -> half 1, quarter 0, slot 6)
+    assert where(K, 8, 17, 70) == ((((1 * 2 + 1) * 4 + 0) * 16 + 1) * 16 + 6, 0)
+    # keys, 4-bit: token 5, channel 53 (group 3 -> quarter 1, sub 1, slot 5)
+    assert where(K, 4, 5, 53) == (((0 * 4 + 1) * 16 + 5) * 16 + 8 + 2, 4)
+    # keys, 2-bit: token 21 (tile 1 -> pair 0, second), channel 127 (group 7 -> quarter 3, sub 1, slot 15)
+    assert where(K, 2, 21, 127) == (((0 * 4 + 3) * 16 + 5) * 16 + 8 + 4 + 3, 6)
+    # values, 8-bit: channel 33 (tile 2, line 1), token 18 (tile 1, slot 2)
+    assert where(V, 8, 18, 33) == (((2 * 2 + 1) * 16 + 1) * 16 + 2, 0)
+    # values, 4-bit: channel 50 (tile 3 -> pair 1, sub 1, line 2), token 7
+    assert where(V, 4, 7, 50) == (((1 * 2 + 0) * 16 + 2) * 16 + 8 + 3, 4)
+    # values, 2-bit: channel 100 (tile 6 -> quad 1, sub 2, line 4), token 30 (tile 1, slot 14)
+    assert where(V, 2, 30, 100) == (((1 * 2 + 1) * 16 + 4) * 16 + 8 + 3, 4)
+
+
+def test_layer_image_places_records_where_the_format_says(oracle):
+    cfg = oracle.OracleConfig(1, 2, 4, 2, 128, 64, 32, 32, 32, BF16, CHAN, [4], [4])
+    cache = oracle.OracleCache(cfg)
+    assert cache.record_bytes(0) == 5632  # 176 bytes per token, 32 tokens
+    k, v = synth.make_kv(8, 2, 45, 2, 128, BF16)
+    cache.append(0, k, v)
+    img = cache.layer_image(0)
+    # one block per unit is defined, plus 13 raw residual rows for K and for V
+    assert int(img["valid"].sum()) == 4 * 5632 + 2 * 4 * 13 * 256
+    from oracle.tada import record_layout
+    lay = record_layout(cfg, 0)
+    # the raw residual of unit (b=1,h=0), token 3 sits at its documented offset
+    off = lay["k_resid_off"] + (1 * 2 + 0) * 32 * 256 + 3 * 256
+    assert np.array_equal(img["bytes"][off:off + 256].view(np.uint16), k[1, 32 + 3, 0])
