@@ -1,0 +1,179 @@
+/*
+ * tadakv.h -- C ABI of the MI355X-native TaDA KV-cache hot path (arxiv 2506.04642).
+ *
+ * What the library does
+ *   kv_quant_append : Algorithm 1, step 8 (KVCache.update) together with the compression that
+ *                     steps 3 and 5 produce: mean-centring (Sec. 3.1, Eq. 1-2), deviation
+ *                     (Sec. 3.2, Eq. 3-4), group quantisation of the deviations to the layer's
+ *                     bit width with 16-bit scale / zero metadata (Sec. 3 memory formula; the
+ *                     S and M outputs of Algorithm 1), bit-packing, and the raw buffer of recent
+ *                     "residual" tokens (Sec. 3.3, Eq. 9-10).
+ *   kv_decode_attn  : Algorithm 1, step 9 (TaDAFlashAttn): softmax attention of one decode query
+ *                     per sequence over the whole cache (Eq. 5-6), reconstructing keys and values
+ *                     from mean + quantised deviation inside the kernel (Eq. 7-8), split over the
+ *                     sequence with a log-sum-exp merge (flash decoding, App. A).
+ *   per-layer bits  : one bit width in {2,4,8} (or 16 = stored raw) per layer for keys and for
+ *                     values (Sec. 3.3 "Searching for quantization precision", App. B); the map is
+ *                     an input here, the search that produces it is not part of this library.
+ *
+ * Conventions
+ *   - Every function returns KV_OK (0) or a negative kv_status.  Nothing throws or aborts.
+ *   - "host" pointers are ordinary process memory; "device" pointers are HIP device memory of the
+ *     GPU that is current when the call is made.  The library never allocates or frees device
+ *     memory and never synchronises: work is enqueued on the given hipStream_t (passed as void*,
+ *     NULL = the default stream) and ordered by it.
+ *   - All arguments are validated on the host before anything is enqueued; on error nothing has
+ *     been enqueued and the cache is unchanged.
+ *   - Sequence lengths are tracked on the host and are uniform across the batch.
+ *   - One cache must be used by one thread at a time.
+ *   - head_dim must be 128.
+ */
+#ifndef TADAKV_H
+#define TADAKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    KV_OK = 0,
+    KV_E_NULL = -1,       /* a required pointer is NULL */
+    KV_E_BAD_CONFIG = -2, /* shape / group / dtype / mode outside what is supported */
+    KV_E_BAD_BITS = -3,   /* a layer's bit width is not one of 2, 4, 8, 16 */
+    KV_E_BAD_LAYER = -4,  /* layer index out of range */
+    KV_E_CAPACITY = -5,   /* append would exceed max_tokens */
+    KV_E_WORKSPACE = -6,  /* workspace NULL or smaller than kv_workspace_bytes */
+    KV_E_ALIGN = -7,      /* a device pointer or stride is not aligned as required */
+    KV_E_HIP = -8,        /* a kernel launch failed (hipGetLastError) */
+    KV_E_EMPTY = -9,      /* attention over a cache that holds no token */
+    KV_E_UNSUPPORTED = -10 /* valid configuration whose GPU path is not built yet */
+} kv_status;
+
+typedef enum { KV_F16 = 0, KV_BF16 = 1 } kv_dtype;
+
+/* Which axis the mean is taken over before the deviation is quantised.
+ *   KV_MEAN_CHANNEL_BLOCK : per (kv head, channel) over each block of group_tokens tokens;
+ *                           stored as head_dim binary16 values per (sequence, kv head, block).
+ *   KV_MEAN_CROSS_HEAD    : over the kv heads, per (token, channel): Eq. 1-2 of the paper;
+ *                           stored as one binary16 row per (sequence, token), shared by all heads.
+ *   KV_MEAN_NONE          : no centring (plain group quantisation). */
+typedef enum { KV_MEAN_CHANNEL_BLOCK = 0, KV_MEAN_CROSS_HEAD = 1, KV_MEAN_NONE = 2 } kv_mean_mode;
+
+typedef struct {
+    int32_t n_layers;
+    int32_t batch;          /* sequences; all have the same length */
+    int32_t n_q_heads;      /* multiple of n_kv_heads; query head i reads kv head i / (Hq/Hkv) */
+    int32_t n_kv_heads;
+    int32_t head_dim;       /* 128 */
+    int32_t max_tokens;     /* capacity per sequence, multiple of group_tokens */
+    int32_t group_tokens;   /* G : tokens per key group = tokens per flushed block: 32, 64 or 128 */
+    int32_t group_channels; /* Gc: channels per value group: 32, 64 or 128 */
+    int32_t resid_cap;      /* R : raw tokens buffered before a flush; positive multiple of G */
+    int32_t dtype;          /* kv_dtype of k, v, q inputs and of the raw residual */
+    int32_t mean_mode;      /* kv_mean_mode */
+    const uint8_t *k_bits;  /* host, [n_layers], each 2, 4, 8 or 16 */
+    const uint8_t *v_bits;  /* host, [n_layers]; the paper uses the same width for both */
+} kv_config;                /* copied by kv_cache_create; the caller keeps its arrays */
+
+/* Byte offsets inside one layer's device buffer (see kv_cache_describe).
+ * Layer buffer = records [batch*n_kv_heads][max_tokens/G] of rec_bytes each
+ *              | cross-head mean plane [batch][max_tokens/G][2 (K,V)][G][head_dim] binary16
+ *                (KV_MEAN_CROSS_HEAD only)
+ *              | raw key residual [batch*n_kv_heads][R][head_dim] | raw value residual, same shape.
+ * Record (one sequence, one kv head, one block of G tokens), offsets relative to the record:
+ *   k_codes | k_scale[head_dim] | k_zero[head_dim] | k_mean[head_dim]
+ *   | v_codes | v_meta[G][head_dim/Gc]{scale,zero} | v_mean[head_dim]
+ * all metadata binary16; the mean fields exist only for KV_MEAN_CHANNEL_BLOCK; a 16-bit side
+ * stores its G x head_dim raw rows in the codes field and has no metadata.  Absent fields are -1.
+ * Codes are stored as 16 x 16 tiles (keys: token x channel; values: channel x token): a tile row's
+ * 16 codes take 2*bits bytes, little-endian within the byte run; a 16-byte piece holds the same
+ * row of 8/bits tiles; 16 pieces (rows 0..15) are consecutive. */
+typedef struct {
+    int32_t k_bits, v_bits;
+    int64_t rec_bytes;
+    int64_t k_codes, k_scale, k_zero, k_mean;
+    int64_t v_codes, v_meta, v_mean;
+    int64_t xmean_off, k_resid_off, v_resid_off;
+    int64_t layer_bytes;
+} kv_layer_layout;
+
+typedef struct kv_cache kv_cache; /* opaque host-side descriptor */
+
+/* Size of layer `layer`'s device buffer for this configuration.  cfg, bytes: host. */
+kv_status kv_cache_bytes(const kv_config *cfg, int32_t layer, size_t *bytes);
+
+/* Size of the split-K workspace kv_decode_attn needs for any length up to max_tokens. */
+kv_status kv_workspace_bytes(const kv_config *cfg, size_t *bytes);
+
+/* Build the host descriptor.  layer_dev_ptrs: host array of n_layers device pointers, each at
+ * least kv_cache_bytes(layer) long and 256-byte aligned; the caller owns them and must keep them
+ * alive until kv_cache_destroy.  No device work is enqueued.  All lengths start at 0. */
+kv_status kv_cache_create(const kv_config *cfg, void *const *layer_dev_ptrs, kv_cache **out);
+
+/* Free the host descriptor (never the device buffers). */
+kv_status kv_cache_destroy(kv_cache *cache);
+
+/* Forget the contents of one layer (layer < 0: all layers).  Host bookkeeping only. */
+kv_status kv_cache_reset(kv_cache *cache, int32_t layer);
+
+/* Current lengths of a layer: tokens in packed blocks, tokens in the raw residual. */
+kv_status kv_cache_len(const kv_cache *cache, int32_t layer, int32_t *packed, int32_t *resid);
+
+/* Offsets of a layer's buffer, so raw bytes can be compared with an independent packer. */
+kv_status kv_cache_describe(const kv_cache *cache, int32_t layer, kv_layer_layout *out);
+
+/* Append n_new tokens to every sequence of `layer`.
+ *   k_new, v_new : device, 16-bit elements of cfg.dtype, logical shape [batch, n_new, n_kv_heads,
+ *                  head_dim]; element (b,t,h,c) at index b*stride_b + t*stride_t + h*stride_h + c
+ *                  (strides in elements; rows of head_dim are contiguous; every row 16-byte aligned).
+ *                  Keys are post-RoPE.  The buffers may be reused once the stream has passed the call.
+ * Semantics are those of n_new single-token appends: tokens enter the raw residual; whenever it
+ * holds R tokens all R are compressed as R/G blocks and the residual restarts empty.
+ * n_new == 0 is a no-op.  KV_E_CAPACITY if packed + resid + n_new > max_tokens. */
+kv_status kv_quant_append(kv_cache *cache, int32_t layer, const void *k_new, const void *v_new,
+                          int32_t n_new, int64_t stride_b, int64_t stride_t, int64_t stride_h,
+                          void *stream);
+
+/* One decode step of attention for `layer` over all tokens currently cached (packed + residual).
+ *   q    : device, [batch, n_q_heads, head_dim], 16-bit cfg.dtype, contiguous, post-RoPE
+ *   out  : device, [batch, n_q_heads, head_dim] float32, contiguous
+ *   workspace : device, at least kv_workspace_bytes, 256-byte aligned; contents are scratch.
+ * Scores are scaled by 1/sqrt(head_dim).  KV_E_EMPTY if the layer holds no token. */
+kv_status kv_decode_attn(const kv_cache *cache, int32_t layer, const void *q, float *out,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+/* The two halves of kv_decode_attn, exposed so that a profiler can bracket them separately:
+ * _split writes per-split partial (max, sum, output) into the workspace, _merge combines them
+ * into `out`.  Calling _split then _merge with the same arguments equals kv_decode_attn. */
+kv_status kv_decode_attn_split(const kv_cache *cache, int32_t layer, const void *q,
+                               void *workspace, size_t workspace_bytes, void *stream);
+kv_status kv_decode_attn_merge(const kv_cache *cache, int32_t layer, float *out,
+                               const void *workspace, size_t workspace_bytes, void *stream);
+
+/* Number of sequence splits kv_decode_attn uses for `layer` at its current length. */
+kv_status kv_decode_splits(const kv_cache *cache, int32_t layer, int32_t *n_splits);
+
+/* Bytes kv_decode_attn must read and write for `layer` at its current length: packed codes,
+ * scale / zero / mean metadata, raw residual rows, q in, out.  Excludes the split workspace. */
+kv_status kv_decode_bytes(const kv_cache *cache, int32_t layer, size_t *bytes);
+
+/* Select the decode kernel family: 0 = automatic (fastest available for the layer),
+ * 1 = portable vector-ALU kernels, 2 = matrix-core (MFMA) kernels where supported.
+ * Returns KV_E_BAD_CONFIG for other values.  Affects later calls on this cache only. */
+kv_status kv_set_decode_path(kv_cache *cache, int32_t path);
+
+/* Force the number of sequence splits of later decode calls on this cache (clamped to the number
+ * of blocks); 0 restores the automatic choice.  The workspace must then hold
+ * batch * n_q_heads * n_splits * 132 floats, which may exceed kv_workspace_bytes.
+ * KV_E_BAD_CONFIG if n_splits < 0 or > 256. */
+kv_status kv_set_decode_splits(kv_cache *cache, int32_t n_splits);
+
+const char *kv_strerror(kv_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TADAKV_H */

@@ -1,0 +1,244 @@
+"""ctypes binding of libtadakv.so: the same names as include/tadakv.h, argument marshalling only.
+
+Every step of the hot path runs in the library's HIP kernels.  There is no fallback: if the
+library has not been built, importing this module raises.  PyTorch appears only in ``KVCache``,
+a convenience holder that allocates the device buffers (torch tensors) and passes their pointers
+and the current HIP stream to the C ABI.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtadakv.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        "libtadakv.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+        "(or paper_2506_04642_amd/build.py) first; there is no fallback path")
+
+_lib = ctypes.CDLL(LIB_PATH)
+
+KV_OK = 0
+KV_E_NULL, KV_E_BAD_CONFIG, KV_E_BAD_BITS, KV_E_BAD_LAYER, KV_E_CAPACITY = -1, -2, -3, -4, -5
+KV_E_WORKSPACE, KV_E_ALIGN, KV_E_HIP, KV_E_EMPTY, KV_E_UNSUPPORTED = -6, -7, -8, -9, -10
+KV_F16, KV_BF16 = 0, 1
+KV_MEAN_CHANNEL_BLOCK, KV_MEAN_CROSS_HEAD, KV_MEAN_NONE = 0, 1, 2
+
+EXPORTS = [
+    "kv_cache_bytes", "kv_workspace_bytes", "kv_cache_create", "kv_cache_destroy", "kv_cache_reset",
+    "kv_cache_len", "kv_cache_describe", "kv_quant_append", "kv_decode_attn", "kv_decode_attn_split",
+    "kv_decode_attn_merge", "kv_decode_splits", "kv_decode_bytes", "kv_set_decode_path", "kv_set_decode_splits", "kv_strerror",
+]
+
+
+class kv_config(ctypes.Structure):
+    _fields_ = [
+        ("n_layers", ctypes.c_int32), ("batch", ctypes.c_int32), ("n_q_heads", ctypes.c_int32),
+        ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("max_tokens", ctypes.c_int32),
+        ("group_tokens", ctypes.c_int32), ("group_channels", ctypes.c_int32), ("resid_cap", ctypes.c_int32),
+        ("dtype", ctypes.c_int32), ("mean_mode", ctypes.c_int32),
+        ("k_bits", ctypes.POINTER(ctypes.c_uint8)), ("v_bits", ctypes.POINTER(ctypes.c_uint8)),
+    ]
+
+
+class kv_layer_layout(ctypes.Structure):
+    _fields_ = [("k_bits", ctypes.c_int32), ("v_bits", ctypes.c_int32)] + [
+        (n, ctypes.c_int64) for n in (
+            "rec_bytes", "k_codes", "k_scale", "k_zero", "k_mean", "v_codes", "v_meta", "v_mean",
+            "xmean_off", "k_resid_off", "v_resid_off", "layer_bytes")]
+
+
+_vp = ctypes.c_void_p
+_i32 = ctypes.c_int32
+_i64 = ctypes.c_int64
+_szp = ctypes.POINTER(ctypes.c_size_t)
+_cfgp = ctypes.POINTER(kv_config)
+
+_lib.kv_cache_bytes.argtypes = [_cfgp, _i32, _szp]
+_lib.kv_workspace_bytes.argtypes = [_cfgp, _szp]
+_lib.kv_cache_create.argtypes = [_cfgp, ctypes.POINTER(_vp), ctypes.POINTER(_vp)]
+_lib.kv_cache_destroy.argtypes = [_vp]
+_lib.kv_cache_reset.argtypes = [_vp, _i32]
+_lib.kv_cache_len.argtypes = [_vp, _i32, ctypes.POINTER(_i32), ctypes.POINTER(_i32)]
+_lib.kv_cache_describe.argtypes = [_vp, _i32, ctypes.POINTER(kv_layer_layout)]
+_lib.kv_quant_append.argtypes = [_vp, _i32, _vp, _vp, _i32, _i64, _i64, _i64, _vp]
+_lib.kv_decode_attn.argtypes = [_vp, _i32, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+_lib.kv_decode_attn_split.argtypes = [_vp, _i32, _vp, _vp, ctypes.c_size_t, _vp]
+_lib.kv_decode_attn_merge.argtypes = [_vp, _i32, _vp, _vp, ctypes.c_size_t, _vp]
+_lib.kv_decode_splits.argtypes = [_vp, _i32, ctypes.POINTER(_i32)]
+_lib.kv_decode_bytes.argtypes = [_vp, _i32, _szp]
+_lib.kv_set_decode_path.argtypes = [_vp, _i32]
+_lib.kv_set_decode_splits.argtypes = [_vp, _i32]
+_lib.kv_strerror.argtypes = [_i32]
+_lib.kv_strerror.restype = ctypes.c_char_p
+for _n in EXPORTS:
+    if _n != "kv_strerror":
+        getattr(_lib, _n).restype = _i32
+
+
+class KVError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: %s (%d)" % (where, kv_strerror(status), status))
+
+
+def kv_strerror(status: int) -> str:
+    return _lib.kv_strerror(status).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != KV_OK:
+        raise KVError(status, where)
+
+
+def make_config(n_layers, batch, n_q_heads, n_kv_heads, head_dim, max_tokens, group_tokens,
+                group_channels, resid_cap, dtype, mean_mode, k_bits: Sequence[int],
+                v_bits: Sequence[int]) -> kv_config:
+    """Fill a kv_config; the bit arrays are kept alive on the returned object."""
+    kb = (ctypes.c_uint8 * len(k_bits))(*k_bits)
+    vb = (ctypes.c_uint8 * len(v_bits))(*v_bits)
+    cfg = kv_config(n_layers, batch, n_q_heads, n_kv_heads, head_dim, max_tokens, group_tokens,
+                    group_channels, resid_cap, dtype, mean_mode,
+                    ctypes.cast(kb, ctypes.POINTER(ctypes.c_uint8)),
+                    ctypes.cast(vb, ctypes.POINTER(ctypes.c_uint8)))
+    cfg._keep = (kb, vb)
+    return cfg
+
+
+# ---- thin wrappers, one per C entry point (raw status codes are turned into KVError)
+
+
+def kv_cache_bytes(cfg: kv_config, layer: int) -> int:
+    n = ctypes.c_size_t()
+    _check(_lib.kv_cache_bytes(ctypes.byref(cfg), layer, ctypes.byref(n)), "kv_cache_bytes")
+    return n.value
+
+
+def kv_workspace_bytes(cfg: kv_config) -> int:
+    n = ctypes.c_size_t()
+    _check(_lib.kv_workspace_bytes(ctypes.byref(cfg), ctypes.byref(n)), "kv_workspace_bytes")
+    return n.value
+
+
+def kv_cache_create(cfg: kv_config, layer_ptrs: Sequence[int]) -> int:
+    arr = (_vp * len(layer_ptrs))(*layer_ptrs)
+    out = _vp()
+    _check(_lib.kv_cache_create(ctypes.byref(cfg), arr, ctypes.byref(out)), "kv_cache_create")
+    return out.value
+
+
+def kv_cache_destroy(cache: int) -> None:
+    _check(_lib.kv_cache_destroy(cache), "kv_cache_destroy")
+
+
+def kv_cache_reset(cache: int, layer: int = -1) -> None:
+    _check(_lib.kv_cache_reset(cache, layer), "kv_cache_reset")
+
+
+def kv_cache_len(cache: int, layer: int):
+    p, r = _i32(), _i32()
+    _check(_lib.kv_cache_len(cache, layer, ctypes.byref(p), ctypes.byref(r)), "kv_cache_len")
+    return p.value, r.value
+
+
+def kv_cache_describe(cache: int, layer: int) -> kv_layer_layout:
+    out = kv_layer_layout()
+    _check(_lib.kv_cache_describe(cache, layer, ctypes.byref(out)), "kv_cache_describe")
+    return out
+
+
+def kv_quant_append(cache: int, layer: int, k_ptr: int, v_ptr: int, n_new: int, stride_b: int,
+                    stride_t: int, stride_h: int, stream: int = 0) -> None:
+    _check(_lib.kv_quant_append(cache, layer, k_ptr, v_ptr, n_new, stride_b, stride_t, stride_h, stream),
+           "kv_quant_append")
+
+
+def kv_decode_attn(cache: int, layer: int, q_ptr: int, out_ptr: int, ws_ptr: int, ws_bytes: int,
+                   stream: int = 0) -> None:
+    _check(_lib.kv_decode_attn(cache, layer, q_ptr, out_ptr, ws_ptr, ws_bytes, stream), "kv_decode_attn")
+
+
+def kv_decode_attn_split(cache: int, layer: int, q_ptr: int, ws_ptr: int, ws_bytes: int, stream: int = 0) -> None:
+    _check(_lib.kv_decode_attn_split(cache, layer, q_ptr, ws_ptr, ws_bytes, stream), "kv_decode_attn_split")
+
+
+def kv_decode_attn_merge(cache: int, layer: int, out_ptr: int, ws_ptr: int, ws_bytes: int, stream: int = 0) -> None:
+    _check(_lib.kv_decode_attn_merge(cache, layer, out_ptr, ws_ptr, ws_bytes, stream), "kv_decode_attn_merge")
+
+
+def kv_decode_splits(cache: int, layer: int) -> int:
+    n = _i32()
+    _check(_lib.kv_decode_splits(cache, layer, ctypes.byref(n)), "kv_decode_splits")
+    return n.value
+
+
+def kv_decode_bytes(cache: int, layer: int) -> int:
+    n = ctypes.c_size_t()
+    _check(_lib.kv_decode_bytes(cache, layer, ctypes.byref(n)), "kv_decode_bytes")
+    return n.value
+
+
+def kv_set_decode_path(cache: int, path: int) -> None:
+    _check(_lib.kv_set_decode_path(cache, path), "kv_set_decode_path")
+
+
+def kv_set_decode_splits(cache: int, n_splits: int) -> None:
+    _check(_lib.kv_set_decode_splits(cache, n_splits), "kv_set_decode_splits")
+
+
+# ---- memory / stream plumbing
+
+
+class KVCache:
+    """Owns the device buffers (torch uint8 tensors) of a cache and forwards calls to the C ABI
+    on torch's current HIP stream.  No arithmetic happens here."""
+
+    def __init__(self, cfg: kv_config, device="cuda:0", zero: bool = True):
+        import torch
+
+        self.torch = torch
+        self.cfg = cfg
+        self.device = torch.device(device)
+        alloc = torch.zeros if zero else torch.empty
+        self.layers = [alloc(kv_cache_bytes(cfg, l), dtype=torch.uint8, device=self.device)
+                       for l in range(cfg.n_layers)]
+        self.ws_bytes = kv_workspace_bytes(cfg)
+        self.workspace = torch.empty(self.ws_bytes, dtype=torch.uint8, device=self.device)
+        self.handle: Optional[int] = kv_cache_create(cfg, [t.data_ptr() for t in self.layers])
+
+    def close(self):
+        if self.handle:
+            kv_cache_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _stream(self) -> int:
+        return self.torch.cuda.current_stream(self.device).cuda_stream
+
+    def append(self, layer: int, k_new, v_new) -> None:
+        """k_new, v_new: device tensors [B, n_new, Hkv, d], 16-bit, last dim contiguous."""
+        assert k_new.shape == v_new.shape and k_new.stride() == v_new.stride()
+        assert k_new.stride(3) == 1 and k_new.element_size() == 2
+        kv_quant_append(self.handle, layer, k_new.data_ptr(), v_new.data_ptr(), k_new.shape[1],
+                        k_new.stride(0), k_new.stride(1), k_new.stride(2), self._stream())
+
+    def attend(self, layer: int, q, out=None):
+        """q: device [B, Hq, d] 16-bit contiguous -> float32 [B, Hq, d]."""
+        torch = self.torch
+        assert q.is_contiguous()
+        if out is None:
+            out = torch.empty(q.shape, dtype=torch.float32, device=self.device)
+        kv_decode_attn(self.handle, layer, q.data_ptr(), out.data_ptr(), self.workspace.data_ptr(),
+                       self.ws_bytes, self._stream())
+        return out
+
+    def lengths(self, layer: int):
+        return kv_cache_len(self.handle, layer)

@@ -1,0 +1,281 @@
+// Quantise-and-append kernels (gfx950).
+//
+// flush_block_kernel compresses one block of G tokens of one (sequence, kv head) for keys or for
+// values: mean-centring (arxiv 2506.04642 Sec. 3.1, Eq. 1-2, taken here per channel over the
+// block), deviation (Sec. 3.2, Eq. 3-4), asymmetric min/max group quantisation of the deviation
+// with binary16 scale / zero (the S and M of Algorithm 1), and bit-packing into the tiled
+// storage format.  Keys are grouped per channel over the block's tokens, values per token over
+// groups of Gc channels.
+//
+// The arithmetic is IEEE binary32, one rounding per operation in a fixed order (this file is
+// compiled with -ffp-contract=off), so that the bytes written are reproducible bit for bit:
+//   mean  = f16_rne( (x_0 + x_1 + ... + x_{G-1}) / G )        sequential sum in token order
+//   D     = x - mean
+//   zero  = f16_round_down(min D)   scale = f16_round_up((max D - zero) / qmax)
+//   code  = clamp(rint((D - zero) / scale), 0, qmax)          0 when scale == 0
+//
+// resid_copy_kernel stores raw 16-bit tokens in the residual buffer (Sec. 3.3).
+#include "tadakv_internal.h"
+#include <hip/hip_fp16.h>
+
+namespace tadakv {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kRowPad = kHeadDim + 1; // floats per LDS row: column walks hit distinct banks
+
+__device__ __forceinline__ float widen16(uint16_t v, int dtype)
+{
+    if (dtype == 1) return __uint_as_float((uint32_t)v << 16); // bfloat16
+    return __half2float(__ushort_as_half(v));
+}
+
+__device__ __forceinline__ uint16_t f16_rne(float f) { return __half_as_ushort(__float2half_rn(f)); }
+__device__ __forceinline__ float f16_val(uint16_t h) { return __half2float(__ushort_as_half(h)); }
+
+// largest binary16 <= f
+__device__ __forceinline__ uint16_t f16_down(float f)
+{
+    uint16_t h = f16_rne(f);
+    if (f16_val(h) > f) {
+        if ((h & 0x7FFFu) == 0) h = 0x8001u;
+        else h = (h & 0x8000u) ? (uint16_t)(h + 1) : (uint16_t)(h - 1);
+    }
+    return h;
+}
+// smallest binary16 >= f
+__device__ __forceinline__ uint16_t f16_up(float f)
+{
+    uint16_t h = f16_rne(f);
+    if (f16_val(h) < f) {
+        if ((h & 0x7FFFu) == 0) h = 0x0001u;
+        else h = (h & 0x8000u) ? (uint16_t)(h - 1) : (uint16_t)(h + 1);
+    }
+    return h;
+}
+
+__device__ __forceinline__ void group_meta(float mn, float mx, int qmax, uint16_t &s16, uint16_t &z16,
+                                           float &s, float &z)
+{
+    if (mn == 0.0f) mn = 0.0f; // -0 -> +0
+    if (mx == 0.0f) mx = 0.0f;
+    z16 = f16_down(mn);
+    z = f16_val(z16);
+    float rng = mx - z;
+    float s32 = rng / (float)qmax;
+    s16 = f16_up(s32);
+    s = f16_val(s16);
+}
+
+__device__ __forceinline__ uint32_t quant_code(float dev, float s, float z, int qmax)
+{
+    if (s == 0.0f) return 0u;
+    float u = (dev - z) / s;
+    float r = rintf(u);
+    r = r < 0.0f ? 0.0f : r;
+    r = r > (float)qmax ? (float)qmax : r;
+    return (uint32_t)r;
+}
+
+// Row of 128 16-bit elements that holds token `ci` of the concatenation
+// [old residual (r_old tokens) | new tokens] for unit (b, h).
+__device__ __forceinline__ const uint16_t *src_row(const AppendArgs &a, int which, int b, int h, int ci)
+{
+    const int u = b * a.n_kv_heads + h;
+    if (ci < a.r_old) {
+        const long long off = (which == 0 ? a.geom.k_resid_off : a.geom.v_resid_off) +
+                              ((long long)u * a.geom.R + ci) * (kHeadDim * 2);
+        return (const uint16_t *)(a.layer + off);
+    }
+    const uint16_t *base = which == 0 ? a.k_new : a.v_new;
+    return base + (long long)b * a.stride_b + (long long)(ci - a.r_old) * a.stride_t + (long long)h * a.stride_h;
+}
+
+// (token, channel) of the first code of packed word w and whether the word runs along
+// channels (keys) or tokens (values); a word holds 32/bits codes.
+__device__ __forceinline__ void word_origin(int which, int bits, int G, int w, int &t0, int &c0)
+{
+    const int piece = w >> 2, wi = w & 3;
+    const int n = piece & 15;
+    if (which == 0) {
+        if (bits == 8) {
+            const int j = (piece >> 4) & 3, hh = (piece >> 6) & 1, tt = piece >> 7;
+            t0 = tt * 16 + n;
+            c0 = (hh * 4 + j) * 16 + wi * 4;
+        } else if (bits == 4) {
+            const int j = (piece >> 4) & 3, tt = piece >> 6;
+            t0 = tt * 16 + n;
+            c0 = (j * 2 + (wi >> 1)) * 16 + (wi & 1) * 8;
+        } else {
+            const int j = (piece >> 4) & 3, tp = piece >> 6;
+            t0 = (tp * 2 + (wi >> 1)) * 16 + n;
+            c0 = (j * 2 + (wi & 1)) * 16;
+        }
+    } else {
+        const int nt = G >> 4;
+        const int q = piece >> 4; // = ctile_group * nt + tt
+        const int tt = q % nt, cgp = q / nt;
+        if (bits == 8) {
+            c0 = cgp * 16 + n;
+            t0 = tt * 16 + wi * 4;
+        } else if (bits == 4) {
+            c0 = (cgp * 2 + (wi >> 1)) * 16 + n;
+            t0 = tt * 16 + (wi & 1) * 8;
+        } else {
+            c0 = (cgp * 4 + wi) * 16 + n;
+            t0 = tt * 16;
+        }
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void flush_block_kernel(AppendArgs a)
+{
+    extern __shared__ float lds[];
+    const LayerGeom &gm = a.geom;
+    const int G = gm.G;
+    float *x = lds;                                        // [G][kRowPad]
+    unsigned char *cb = (unsigned char *)(lds + G * kRowPad); // [G][128] codes
+
+    const int fb = blockIdx.x, u = blockIdx.y, which = blockIdx.z;
+    const int b = u / a.n_kv_heads, h = u % a.n_kv_heads;
+    const int tid = threadIdx.x;
+    const int bits = which == 0 ? gm.k_bits : gm.v_bits;
+    unsigned char *rec = a.layer + ((long long)u * gm.NB + (a.first_block + fb)) * gm.rec_bytes;
+    unsigned char *codes_out = rec + (which == 0 ? gm.k_codes : gm.v_codes);
+
+    if (bits == 16) {
+        // stored raw: G rows of 256 bytes
+        for (int i = tid; i < G * 16; i += kThreads) {
+            const int t = i >> 4, ch = i & 15;
+            const uint4 v = *(const uint4 *)(src_row(a, which, b, h, fb * G + t) + ch * 8);
+            *(uint4 *)(codes_out + (long long)t * 256 + ch * 16) = v;
+        }
+        return;
+    }
+
+    // 1. load the block, widened to binary32
+    for (int i = tid; i < G * 16; i += kThreads) {
+        const int t = i >> 4, ch = i & 15;
+        const uint4 v = *(const uint4 *)(src_row(a, which, b, h, fb * G + t) + ch * 8);
+        const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
+        float *dst = x + t * kRowPad + ch * 8;
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+            dst[2 * k] = widen16((uint16_t)(wv[k] & 0xFFFFu), gm.dtype);
+            dst[2 * k + 1] = widen16((uint16_t)(wv[k] >> 16), gm.dtype);
+        }
+    }
+    __syncthreads();
+
+    const int qmax = (1 << bits) - 1;
+    const bool centre = gm.mean_mode == 0; // per-channel block mean
+
+    if (tid < kHeadDim) {
+        const int c = tid;
+        float m = 0.0f;
+        if (centre) {
+            float acc = 0.0f;
+            for (int t = 0; t < G; t++) acc = acc + x[t * kRowPad + c];
+            const float m32 = acc / (float)G;
+            const uint16_t m16 = f16_rne(m32);
+            m = f16_val(m16);
+            *(uint16_t *)(rec + (which == 0 ? gm.k_mean : gm.v_mean) + c * 2) = m16;
+        }
+        if (which == 0) {
+            float mn = x[c] - m, mx = mn;
+            x[c] = mn;
+            for (int t = 1; t < G; t++) {
+                const float dv = x[t * kRowPad + c] - m;
+                x[t * kRowPad + c] = dv;
+                mn = dv < mn ? dv : mn;
+                mx = dv > mx ? dv : mx;
+            }
+            uint16_t s16, z16;
+            float s, z;
+            group_meta(mn, mx, qmax, s16, z16, s, z);
+            *(uint16_t *)(rec + gm.k_scale + c * 2) = s16;
+            *(uint16_t *)(rec + gm.k_zero + c * 2) = z16;
+            for (int t = 0; t < G; t++)
+                cb[t * kHeadDim + c] = (unsigned char)quant_code(x[t * kRowPad + c], s, z, qmax);
+        } else if (centre) {
+            for (int t = 0; t < G; t++) x[t * kRowPad + c] = x[t * kRowPad + c] - m;
+        }
+    }
+    __syncthreads();
+
+    if (which == 1) {
+        const int ng = kHeadDim / gm.Gc;
+        for (int gi = tid; gi < G * ng; gi += kThreads) {
+            const int t = gi % G, gam = gi / G;
+            const float *row = x + t * kRowPad + gam * gm.Gc;
+            float mn = row[0], mx = row[0];
+            for (int i = 1; i < gm.Gc; i++) {
+                const float dv = row[i];
+                mn = dv < mn ? dv : mn;
+                mx = dv > mx ? dv : mx;
+            }
+            uint16_t s16, z16;
+            float s, z;
+            group_meta(mn, mx, qmax, s16, z16, s, z);
+            *(uint32_t *)(rec + gm.v_meta + (t * ng + gam) * 4) = (uint32_t)s16 | ((uint32_t)z16 << 16);
+            unsigned char *crow = cb + t * kHeadDim + gam * gm.Gc;
+            for (int i = 0; i < gm.Gc; i++) crow[i] = (unsigned char)quant_code(row[i], s, z, qmax);
+        }
+        __syncthreads();
+    }
+
+    // pack: one 32-bit word = 32/bits consecutive codes along channels (keys) or tokens (values)
+    const int n_words = G * kHeadDim * bits / 32;
+    const int per = 32 / bits;
+    for (int w = tid; w < n_words; w += kThreads) {
+        int t0, c0;
+        word_origin(which, bits, G, w, t0, c0);
+        uint32_t word = 0;
+        if (which == 0) {
+            for (int e = 0; e < per; e++) word |= (uint32_t)cb[t0 * kHeadDim + c0 + e] << (bits * e);
+        } else {
+            for (int e = 0; e < per; e++) word |= (uint32_t)cb[(t0 + e) * kHeadDim + c0] << (bits * e);
+        }
+        ((uint32_t *)codes_out)[w] = word;
+    }
+}
+
+// Raw tail: input tokens [copy_src, copy_src + copy_n) -> residual rows [copy_dst, ...).
+__global__ __launch_bounds__(kThreads) void resid_copy_kernel(AppendArgs a)
+{
+    const int u = blockIdx.y;
+    const int b = u / a.n_kv_heads, h = u % a.n_kv_heads;
+    const int i = blockIdx.x * 8 + (threadIdx.x >> 5);
+    if (i >= a.copy_n) return;
+    const int lane = threadIdx.x & 31, which = lane >> 4, ch = lane & 15;
+    const uint16_t *base = which == 0 ? a.k_new : a.v_new;
+    const uint16_t *src = base + (long long)b * a.stride_b + (long long)(a.copy_src + i) * a.stride_t +
+                          (long long)h * a.stride_h + ch * 8;
+    const long long off = (which == 0 ? a.geom.k_resid_off : a.geom.v_resid_off) +
+                          ((long long)u * a.geom.R + a.copy_dst + i) * (kHeadDim * 2) + ch * 16;
+    *(uint4 *)(a.layer + off) = *(const uint4 *)src;
+}
+
+} // namespace
+
+hipError_t launch_flush(const AppendArgs &a, hipStream_t s)
+{
+    const int U = a.batch * a.n_kv_heads;
+    const size_t lds = (size_t)a.geom.G * kRowPad * sizeof(float) + (size_t)a.geom.G * kHeadDim;
+    // grid.y is limited to 65535 entries
+    if (U > 65535) return hipErrorInvalidValue;
+    dim3 grid(a.n_flush_blocks, U, 2);
+    hipLaunchKernelGGL(flush_block_kernel, grid, dim3(kThreads), lds, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_resid_copy(const AppendArgs &a, hipStream_t s)
+{
+    const int U = a.batch * a.n_kv_heads;
+    if (U > 65535) return hipErrorInvalidValue;
+    dim3 grid((a.copy_n + 7) / 8, U, 1);
+    hipLaunchKernelGGL(resid_copy_kernel, grid, dim3(kThreads), 0, s, a);
+    return hipGetLastError();
+}
+
+} // namespace tadakv

@@ -1,0 +1,436 @@
+// Host side of libtadakv: argument validation, layer geometry, length bookkeeping (the residual
+// policy of Sec. 3.3 of arxiv 2506.04642) and dispatch of the HIP kernels.  No device memory is
+// allocated here and nothing synchronises.
+#include "../../include/tadakv.h"
+#include "tadakv_internal.h"
+
+#include <new>
+#include <vector>
+
+using namespace tadakv;
+
+struct kv_cache {
+    kv_config cfg;
+    std::vector<uint8_t> k_bits, v_bits;
+    std::vector<unsigned char *> layers;
+    std::vector<LayerGeom> geom;
+    std::vector<int> packed, resid; // tokens
+    int decode_path = 0;
+    int forced_splits = 0;
+};
+
+namespace {
+
+long long align_up(long long n, long long a) { return (n + a - 1) / a * a; }
+
+bool bits_ok(int b) { return b == 2 || b == 4 || b == 8 || b == 16; }
+
+kv_status check_config(const kv_config *c)
+{
+    if (!c) return KV_E_NULL;
+    if (!c->k_bits || !c->v_bits) return KV_E_NULL;
+    if (c->n_layers <= 0 || c->batch <= 0 || c->n_kv_heads <= 0 || c->n_q_heads <= 0) return KV_E_BAD_CONFIG;
+    if (c->head_dim != kHeadDim) return KV_E_BAD_CONFIG;
+    if (c->n_q_heads % c->n_kv_heads) return KV_E_BAD_CONFIG;
+    if (c->n_q_heads / c->n_kv_heads > kMaxGroupQ) return KV_E_BAD_CONFIG;
+    if (!(c->group_tokens == 32 || c->group_tokens == 64 || c->group_tokens == 128)) return KV_E_BAD_CONFIG;
+    if (!(c->group_channels == 32 || c->group_channels == 64 || c->group_channels == 128)) return KV_E_BAD_CONFIG;
+    if (c->max_tokens <= 0 || c->max_tokens % c->group_tokens) return KV_E_BAD_CONFIG;
+    if (c->resid_cap <= 0 || c->resid_cap % c->group_tokens || c->resid_cap > c->max_tokens) return KV_E_BAD_CONFIG;
+    if (!(c->dtype == KV_F16 || c->dtype == KV_BF16)) return KV_E_BAD_CONFIG;
+    if (!(c->mean_mode == KV_MEAN_CHANNEL_BLOCK || c->mean_mode == KV_MEAN_CROSS_HEAD ||
+          c->mean_mode == KV_MEAN_NONE))
+        return KV_E_BAD_CONFIG;
+    for (int l = 0; l < c->n_layers; l++)
+        if (!bits_ok(c->k_bits[l]) || !bits_ok(c->v_bits[l])) return KV_E_BAD_BITS;
+    for (int l = 0; l < c->n_layers; l++) // one raw side next to one packed side: no kernel yet
+        if ((c->k_bits[l] == 16) != (c->v_bits[l] == 16)) return KV_E_UNSUPPORTED;
+    return KV_OK;
+}
+
+// The storage format of one layer (documented in tadakv.h next to kv_layer_layout).
+LayerGeom make_geom(const kv_config &c, int layer)
+{
+    LayerGeom g{};
+    const int d = c.head_dim, G = c.group_tokens, Gc = c.group_channels;
+    g.k_bits = c.k_bits[layer];
+    g.v_bits = c.v_bits[layer];
+    g.G = G;
+    g.Gc = Gc;
+    g.R = c.resid_cap;
+    g.NB = c.max_tokens / G;
+    g.mean_mode = c.mean_mode;
+    g.dtype = c.dtype;
+    const bool cm = c.mean_mode == KV_MEAN_CHANNEL_BLOCK;
+    int off = 0;
+    g.k_scale = g.k_zero = g.k_mean = g.v_meta = g.v_mean = -1;
+    g.k_codes = off;
+    off += G * d * g.k_bits / 8;
+    if (g.k_bits != 16) {
+        g.k_scale = off; off += d * 2;
+        g.k_zero = off;  off += d * 2;
+        if (cm) { g.k_mean = off; off += d * 2; }
+    }
+    g.v_codes = off;
+    off += G * d * g.v_bits / 8;
+    if (g.v_bits != 16) {
+        g.v_meta = off; off += G * (d / Gc) * 4;
+        if (cm) { g.v_mean = off; off += d * 2; }
+    }
+    g.rec_bytes = align_up(off, 256);
+    const long long U = (long long)c.batch * c.n_kv_heads;
+    long long total = align_up(U * g.NB * g.rec_bytes, 256);
+    g.xmean_off = total;
+    if (c.mean_mode == KV_MEAN_CROSS_HEAD)
+        total = align_up(total + (long long)c.batch * g.NB * 2 * G * d * 2, 256);
+    g.k_resid_off = total;
+    total = align_up(total + U * c.resid_cap * d * 2, 256);
+    g.v_resid_off = total;
+    total = align_up(total + U * c.resid_cap * d * 2, 256);
+    g.layer_bytes = total;
+    return g;
+}
+
+// Sequence splits for a layer holding n_blocks packed blocks and r raw tokens: enough
+// workgroups to cover the 256 compute units several times over, but never fewer than a handful
+// of blocks per split so that the per-split prologue and the merge stay small.
+void choose_splits(const kv_config &c, int n_blocks, int r, int *n_splits, int *blocks_per_split)
+{
+    const long long U = (long long)c.batch * c.n_kv_heads;
+    const int units_of_work = n_blocks + (r > 0 ? 1 : 0);
+    const int min_blocks = (c.group_tokens >= 64) ? 4 : 8; // >= 256 tokens per split
+    long long want = (2048 + U - 1) / U;                    // ~8 workgroups per compute unit
+    long long cap = (units_of_work + min_blocks - 1) / min_blocks;
+    long long ns = want < cap ? want : cap;
+    if (ns < 1) ns = 1;
+    if (ns > kMaxSplits) ns = kMaxSplits;
+    int bps = (int)((units_of_work + ns - 1) / ns);
+    if (bps < 1) bps = 1;
+    ns = (units_of_work + bps - 1) / bps; // no empty split
+    if (ns < 1) ns = 1;
+    *n_splits = (int)ns;
+    *blocks_per_split = bps;
+}
+
+size_t workspace_need(const kv_config &c, int n_splits)
+{
+    return (size_t)c.batch * c.n_q_heads * n_splits * kPartialStride * sizeof(float);
+}
+
+kv_status layer_ok(const kv_cache *k, int layer)
+{
+    if (!k) return KV_E_NULL;
+    if (layer < 0 || layer >= k->cfg.n_layers) return KV_E_BAD_LAYER;
+    return KV_OK;
+}
+
+kv_status fill_decode(const kv_cache *k, int layer, DecodeArgs *a)
+{
+    const kv_config &c = k->cfg;
+    a->geom = k->geom[layer];
+    a->layer = k->layers[layer];
+    a->n_kv_heads = c.n_kv_heads;
+    a->n_q_heads = c.n_q_heads;
+    a->batch = c.batch;
+    a->g = c.n_q_heads / c.n_kv_heads;
+    a->n_blocks = k->packed[layer] / c.group_tokens;
+    a->r = k->resid[layer];
+    if (a->n_blocks == 0 && a->r == 0) return KV_E_EMPTY;
+    choose_splits(c, a->n_blocks, a->r, &a->n_splits, &a->blocks_per_split);
+    if (k->forced_splits > 0) {
+        const int work = a->n_blocks + (a->r > 0 ? 1 : 0);
+        int ns = k->forced_splits < work ? k->forced_splits : work;
+        a->blocks_per_split = (work + ns - 1) / ns;
+        a->n_splits = (work + a->blocks_per_split - 1) / a->blocks_per_split;
+    }
+    return KV_OK;
+}
+
+bool use_mfma(const kv_cache *k, const DecodeArgs &a)
+{
+    if (k->decode_path == 1) return false;
+    return decode_mfma_supported(a);
+}
+
+} // namespace
+
+extern "C" {
+
+const char *kv_strerror(kv_status s)
+{
+    switch (s) {
+    case KV_OK: return "ok";
+    case KV_E_NULL: return "null pointer";
+    case KV_E_BAD_CONFIG: return "unsupported configuration";
+    case KV_E_BAD_BITS: return "bit width must be 2, 4, 8 or 16";
+    case KV_E_BAD_LAYER: return "layer index out of range";
+    case KV_E_CAPACITY: return "append exceeds max_tokens";
+    case KV_E_WORKSPACE: return "workspace missing or too small";
+    case KV_E_ALIGN: return "misaligned pointer or stride";
+    case KV_E_HIP: return "kernel launch failed";
+    case KV_E_EMPTY: return "cache holds no token";
+    case KV_E_UNSUPPORTED: return "configuration has no GPU path yet";
+    }
+    return "unknown status";
+}
+
+kv_status kv_cache_bytes(const kv_config *cfg, int32_t layer, size_t *bytes)
+{
+    if (!bytes) return KV_E_NULL;
+    kv_status st = check_config(cfg);
+    if (st != KV_OK) return st;
+    if (layer < 0 || layer >= cfg->n_layers) return KV_E_BAD_LAYER;
+    *bytes = (size_t)make_geom(*cfg, layer).layer_bytes;
+    return KV_OK;
+}
+
+kv_status kv_workspace_bytes(const kv_config *cfg, size_t *bytes)
+{
+    if (!bytes) return KV_E_NULL;
+    kv_status st = check_config(cfg);
+    if (st != KV_OK) return st;
+    // the split count grows with the length; take the largest over all reachable lengths
+    int worst = 1;
+    const int NB = cfg->max_tokens / cfg->group_tokens;
+    for (int nb = 0; nb <= NB; nb++) {
+        int ns, bps;
+        choose_splits(*cfg, nb, 1, &ns, &bps);
+        if (ns > worst) worst = ns;
+    }
+    *bytes = workspace_need(*cfg, worst);
+    return KV_OK;
+}
+
+kv_status kv_cache_create(const kv_config *cfg, void *const *layer_dev_ptrs, kv_cache **out)
+{
+    if (!out || !layer_dev_ptrs) return KV_E_NULL;
+    kv_status st = check_config(cfg);
+    if (st != KV_OK) return st;
+    for (int l = 0; l < cfg->n_layers; l++) {
+        if (!layer_dev_ptrs[l]) return KV_E_NULL;
+        if ((uintptr_t)layer_dev_ptrs[l] % 256) return KV_E_ALIGN;
+    }
+    kv_cache *k = new (std::nothrow) kv_cache();
+    if (!k) return KV_E_BAD_CONFIG;
+    k->cfg = *cfg;
+    k->k_bits.assign(cfg->k_bits, cfg->k_bits + cfg->n_layers);
+    k->v_bits.assign(cfg->v_bits, cfg->v_bits + cfg->n_layers);
+    k->cfg.k_bits = k->k_bits.data();
+    k->cfg.v_bits = k->v_bits.data();
+    for (int l = 0; l < cfg->n_layers; l++) {
+        k->layers.push_back((unsigned char *)layer_dev_ptrs[l]);
+        k->geom.push_back(make_geom(k->cfg, l));
+    }
+    k->packed.assign(cfg->n_layers, 0);
+    k->resid.assign(cfg->n_layers, 0);
+    *out = k;
+    return KV_OK;
+}
+
+kv_status kv_cache_destroy(kv_cache *cache)
+{
+    if (!cache) return KV_E_NULL;
+    delete cache;
+    return KV_OK;
+}
+
+kv_status kv_cache_reset(kv_cache *cache, int32_t layer)
+{
+    if (!cache) return KV_E_NULL;
+    if (layer >= cache->cfg.n_layers) return KV_E_BAD_LAYER;
+    for (int l = 0; l < cache->cfg.n_layers; l++)
+        if (layer < 0 || l == layer) cache->packed[l] = cache->resid[l] = 0;
+    return KV_OK;
+}
+
+kv_status kv_cache_len(const kv_cache *cache, int32_t layer, int32_t *packed, int32_t *resid)
+{
+    kv_status st = layer_ok(cache, layer);
+    if (st != KV_OK) return st;
+    if (!packed || !resid) return KV_E_NULL;
+    *packed = cache->packed[layer];
+    *resid = cache->resid[layer];
+    return KV_OK;
+}
+
+kv_status kv_cache_describe(const kv_cache *cache, int32_t layer, kv_layer_layout *out)
+{
+    kv_status st = layer_ok(cache, layer);
+    if (st != KV_OK) return st;
+    if (!out) return KV_E_NULL;
+    const LayerGeom &g = cache->geom[layer];
+    out->k_bits = g.k_bits;
+    out->v_bits = g.v_bits;
+    out->rec_bytes = g.rec_bytes;
+    out->k_codes = g.k_codes;
+    out->k_scale = g.k_scale;
+    out->k_zero = g.k_zero;
+    out->k_mean = g.k_mean;
+    out->v_codes = g.v_codes;
+    out->v_meta = g.v_meta;
+    out->v_mean = g.v_mean;
+    out->xmean_off = g.xmean_off;
+    out->k_resid_off = g.k_resid_off;
+    out->v_resid_off = g.v_resid_off;
+    out->layer_bytes = g.layer_bytes;
+    return KV_OK;
+}
+
+kv_status kv_quant_append(kv_cache *cache, int32_t layer, const void *k_new, const void *v_new,
+                          int32_t n_new, int64_t stride_b, int64_t stride_t, int64_t stride_h,
+                          void *stream)
+{
+    kv_status st = layer_ok(cache, layer);
+    if (st != KV_OK) return st;
+    if (n_new < 0) return KV_E_BAD_CONFIG;
+    if (n_new == 0) return KV_OK;
+    if (!k_new || !v_new) return KV_E_NULL;
+    const kv_config &c = cache->cfg;
+    if (((uintptr_t)k_new % 16) || ((uintptr_t)v_new % 16)) return KV_E_ALIGN;
+    if (stride_b % 8 || stride_t % 8 || stride_h % 8) return KV_E_ALIGN;
+    if (stride_h < c.head_dim || stride_t < 0 || stride_b < 0) return KV_E_BAD_CONFIG;
+    const long long have = (long long)cache->packed[layer] + cache->resid[layer];
+    if (have + n_new > c.max_tokens) return KV_E_CAPACITY;
+    if (c.mean_mode == KV_MEAN_CROSS_HEAD &&
+        (cache->geom[layer].k_bits != 16 || cache->geom[layer].v_bits != 16))
+        return KV_E_UNSUPPORTED;
+
+    const int G = c.group_tokens, R = c.resid_cap;
+    const int r_old = cache->resid[layer];
+    const long long total = (long long)r_old + n_new;
+    const long long n_flush_tok = total / R * R;
+    AppendArgs a{};
+    a.geom = cache->geom[layer];
+    a.layer = cache->layers[layer];
+    a.k_new = (const uint16_t *)k_new;
+    a.v_new = (const uint16_t *)v_new;
+    a.stride_b = stride_b;
+    a.stride_t = stride_t;
+    a.stride_h = stride_h;
+    a.n_kv_heads = c.n_kv_heads;
+    a.batch = c.batch;
+    a.r_old = r_old;
+    a.first_block = cache->packed[layer] / G;
+    a.n_flush_blocks = (int)(n_flush_tok / G);
+    if (n_flush_tok > 0) {
+        a.copy_src = (int)(n_flush_tok - r_old);
+        a.copy_dst = 0;
+        a.copy_n = (int)(total - n_flush_tok);
+    } else {
+        a.copy_src = 0;
+        a.copy_dst = r_old;
+        a.copy_n = n_new;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    if (a.n_flush_blocks > 0 && launch_flush(a, s) != hipSuccess) return KV_E_HIP;
+    if (a.copy_n > 0 && launch_resid_copy(a, s) != hipSuccess) return KV_E_HIP;
+    cache->packed[layer] += (int)n_flush_tok;
+    cache->resid[layer] = (int)(total - n_flush_tok);
+    return KV_OK;
+}
+
+kv_status kv_decode_splits(const kv_cache *cache, int32_t layer, int32_t *n_splits)
+{
+    kv_status st = layer_ok(cache, layer);
+    if (st != KV_OK) return st;
+    if (!n_splits) return KV_E_NULL;
+    DecodeArgs a{};
+    st = fill_decode(cache, layer, &a);
+    if (st != KV_OK) return st;
+    *n_splits = a.n_splits;
+    return KV_OK;
+}
+
+kv_status kv_decode_bytes(const kv_cache *cache, int32_t layer, size_t *bytes)
+{
+    kv_status st = layer_ok(cache, layer);
+    if (st != KV_OK) return st;
+    if (!bytes) return KV_E_NULL;
+    const kv_config &c = cache->cfg;
+    const LayerGeom &g = cache->geom[layer];
+    const size_t U = (size_t)c.batch * c.n_kv_heads, d = c.head_dim;
+    const size_t nb = cache->packed[layer] / c.group_tokens;
+    size_t rec = 0; // bytes of a record that carry information (no padding)
+    rec += (size_t)g.G * d * g.k_bits / 8;
+    if (g.k_bits != 16) rec += 2 * d * 2 + (g.k_mean >= 0 ? d * 2 : 0);
+    rec += (size_t)g.G * d * g.v_bits / 8;
+    if (g.v_bits != 16) rec += (size_t)g.G * (d / g.Gc) * 4 + (g.v_mean >= 0 ? d * 2 : 0);
+    size_t total = U * nb * rec;
+    if (c.mean_mode == KV_MEAN_CROSS_HEAD) {
+        size_t sides = (g.k_bits != 16) + (g.v_bits != 16);
+        total += (size_t)c.batch * nb * sides * g.G * d * 2;
+    }
+    total += U * (size_t)cache->resid[layer] * d * 2 * 2;
+    total += (size_t)c.batch * c.n_q_heads * d * (2 + 4);
+    *bytes = total;
+    return KV_OK;
+}
+
+kv_status kv_set_decode_path(kv_cache *cache, int32_t path)
+{
+    if (!cache) return KV_E_NULL;
+    if (path < 0 || path > 2) return KV_E_BAD_CONFIG;
+    cache->decode_path = path;
+    return KV_OK;
+}
+
+kv_status kv_set_decode_splits(kv_cache *cache, int32_t n_splits)
+{
+    if (!cache) return KV_E_NULL;
+    if (n_splits < 0 || n_splits > kMaxSplits) return KV_E_BAD_CONFIG;
+    cache->forced_splits = n_splits;
+    return KV_OK;
+}
+
+kv_status kv_decode_attn_split(const kv_cache *cache, int32_t layer, const void *q,
+                               void *workspace, size_t workspace_bytes, void *stream)
+{
+    kv_status st = layer_ok(cache, layer);
+    if (st != KV_OK) return st;
+    if (!q) return KV_E_NULL;
+    if ((uintptr_t)q % 16) return KV_E_ALIGN;
+    DecodeArgs a{};
+    st = fill_decode(cache, layer, &a);
+    if (st != KV_OK) return st;
+    if (!workspace || workspace_bytes < workspace_need(cache->cfg, a.n_splits)) return KV_E_WORKSPACE;
+    if ((uintptr_t)workspace % 256) return KV_E_ALIGN;
+    if (cache->cfg.mean_mode == KV_MEAN_CROSS_HEAD && (a.geom.k_bits != 16 || a.geom.v_bits != 16))
+        return KV_E_UNSUPPORTED;
+    a.q = (const uint16_t *)q;
+    a.ws = (float *)workspace;
+    a.out = nullptr;
+    hipStream_t s = (hipStream_t)stream;
+    if (cache->decode_path == 2 && !decode_mfma_supported(a)) return KV_E_UNSUPPORTED;
+    hipError_t e = use_mfma(cache, a) ? launch_decode_split_mfma(a, s) : launch_decode_split_valu(a, s);
+    return e == hipSuccess ? KV_OK : KV_E_HIP;
+}
+
+kv_status kv_decode_attn_merge(const kv_cache *cache, int32_t layer, float *out,
+                               const void *workspace, size_t workspace_bytes, void *stream)
+{
+    kv_status st = layer_ok(cache, layer);
+    if (st != KV_OK) return st;
+    if (!out) return KV_E_NULL;
+    if ((uintptr_t)out % 16) return KV_E_ALIGN;
+    DecodeArgs a{};
+    st = fill_decode(cache, layer, &a);
+    if (st != KV_OK) return st;
+    if (!workspace || workspace_bytes < workspace_need(cache->cfg, a.n_splits)) return KV_E_WORKSPACE;
+    if ((uintptr_t)workspace % 256) return KV_E_ALIGN;
+    a.q = nullptr;
+    a.ws = (float *)const_cast<void *>(workspace);
+    a.out = out;
+    return launch_decode_merge(a, (hipStream_t)stream) == hipSuccess ? KV_OK : KV_E_HIP;
+}
+
+kv_status kv_decode_attn(const kv_cache *cache, int32_t layer, const void *q, float *out,
+                         void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!out) return KV_E_NULL;
+    if ((uintptr_t)out % 16) return KV_E_ALIGN;
+    kv_status st = kv_decode_attn_split(cache, layer, q, workspace, workspace_bytes, stream);
+    if (st != KV_OK) return st;
+    return kv_decode_attn_merge(cache, layer, out, workspace, workspace_bytes, stream);
+}
+
+} // extern "C"

@@ -1,0 +1,57 @@
+// Internal declarations shared by the host-side ABI and the HIP kernels of libtadakv.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tadakv {
+
+constexpr int kHeadDim = 128;
+constexpr int kMaxGroupQ = 8;       // query heads per kv head the kernels are sized for
+constexpr int kPartialStride = 132; // floats per (unit, split, q head): O[128], max, sum, pad
+constexpr int kMaxSplits = 256;
+
+// Geometry of one layer's buffer; byte offsets, -1 where a field is absent.
+struct LayerGeom {
+    int k_bits, v_bits;
+    int G, Gc, R, NB;     // group_tokens, group_channels, resid_cap, blocks per sequence
+    int mean_mode, dtype;
+    long long rec_bytes;
+    int k_codes, k_scale, k_zero, k_mean;
+    int v_codes, v_meta, v_mean;
+    long long xmean_off, k_resid_off, v_resid_off, layer_bytes;
+};
+
+struct AppendArgs {
+    LayerGeom geom;
+    unsigned char *layer;   // device base of the layer buffer
+    const uint16_t *k_new;  // device
+    const uint16_t *v_new;
+    long long stride_b, stride_t, stride_h; // elements
+    int n_kv_heads, batch;
+    int r_old;          // residual tokens before the call
+    int first_block;    // index of the first block this call writes
+    int n_flush_blocks; // blocks to compress
+    int copy_src, copy_dst, copy_n; // raw tail: input tokens [copy_src, copy_src+copy_n) -> residual[copy_dst..]
+};
+
+struct DecodeArgs {
+    LayerGeom geom;
+    const unsigned char *layer;
+    const uint16_t *q;   // [batch][Hq][128]
+    float *ws;           // partials [U][n_splits][g][kPartialStride]
+    float *out;          // [batch][Hq][128]
+    int n_kv_heads, n_q_heads, batch, g;
+    int n_blocks;        // packed blocks in the layer
+    int r;               // residual tokens
+    int n_splits;
+    int blocks_per_split;
+};
+
+hipError_t launch_flush(const AppendArgs &a, hipStream_t s);
+hipError_t launch_resid_copy(const AppendArgs &a, hipStream_t s);
+hipError_t launch_decode_split_valu(const DecodeArgs &a, hipStream_t s);
+hipError_t launch_decode_split_mfma(const DecodeArgs &a, hipStream_t s);
+bool decode_mfma_supported(const DecodeArgs &a);
+hipError_t launch_decode_merge(const DecodeArgs &a, hipStream_t s);
+
+} // namespace tadakv

@@ -1,0 +1,128 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and every argument error is caught before anything is enqueued."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def kv():
+    from paper_2506_04642_amd import binding
+
+    return binding
+
+
+def _cfg(kv, **over):
+    base = dict(n_layers=2, batch=2, n_q_heads=8, n_kv_heads=2, head_dim=128, max_tokens=256,
+                group_tokens=32, group_channels=32, resid_cap=32, dtype=kv.KV_BF16,
+                mean_mode=kv.KV_MEAN_CHANNEL_BLOCK, k_bits=[4, 2], v_bits=[4, 2])
+    base.update(over)
+    return kv.make_config(**base)
+
+
+def test_every_declared_function_is_exported(kv):
+    text = open(os.path.join(ROOT, "include", "tadakv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(kv_[a-z_]+)\s*\(", text))
+    assert declared, "no declarations found"
+    assert declared == set(kv.EXPORTS)
+    lib = ctypes.CDLL(kv.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_sizes_follow_the_record_format(kv):
+    cfg = _cfg(kv)
+    U, NB = 4, 8
+    # 4-bit, G=Gc=32, per-channel block mean: 176 bytes per token -> 5632-byte records
+    assert kv.kv_cache_bytes(cfg, 0) == U * NB * 5632 + 2 * U * 32 * 256
+    assert kv.kv_cache_bytes(cfg, 1) == U * NB * 3584 + 2 * U * 32 * 256
+    assert kv.kv_workspace_bytes(cfg) >= 2 * 8 * 132 * 4
+    cfg16 = _cfg(kv, k_bits=[16, 16], v_bits=[16, 16])
+    assert kv.kv_cache_bytes(cfg16, 0) == U * NB * 2 * 32 * 256 + 2 * U * 32 * 256
+
+
+@pytest.mark.parametrize("over,status", [
+    (dict(head_dim=64), "KV_E_BAD_CONFIG"),
+    (dict(n_q_heads=7), "KV_E_BAD_CONFIG"),
+    (dict(n_q_heads=32, n_kv_heads=2), "KV_E_BAD_CONFIG"),
+    (dict(group_tokens=48), "KV_E_BAD_CONFIG"),
+    (dict(group_channels=16), "KV_E_BAD_CONFIG"),
+    (dict(max_tokens=250), "KV_E_BAD_CONFIG"),
+    (dict(resid_cap=48), "KV_E_BAD_CONFIG"),
+    (dict(resid_cap=0), "KV_E_BAD_CONFIG"),
+    (dict(dtype=5), "KV_E_BAD_CONFIG"),
+    (dict(mean_mode=9), "KV_E_BAD_CONFIG"),
+    (dict(batch=0), "KV_E_BAD_CONFIG"),
+    (dict(k_bits=[4, 3]), "KV_E_BAD_BITS"),
+    (dict(v_bits=[1, 2]), "KV_E_BAD_BITS"),
+    (dict(k_bits=[16, 2]), "KV_E_UNSUPPORTED"),
+])
+def test_bad_configs_are_refused(kv, over, status):
+    with pytest.raises(kv.KVError) as e:
+        kv.kv_cache_bytes(_cfg(kv, **over), 0)
+    assert e.value.status == getattr(kv, status)
+
+
+def test_null_and_range_errors(kv):
+    cfg = _cfg(kv)
+    n = ctypes.c_size_t()
+    assert kv._lib.kv_cache_bytes(None, 0, ctypes.byref(n)) == kv.KV_E_NULL
+    assert kv._lib.kv_cache_bytes(ctypes.byref(cfg), 0, None) == kv.KV_E_NULL
+    assert kv._lib.kv_cache_bytes(ctypes.byref(cfg), 2, ctypes.byref(n)) == kv.KV_E_BAD_LAYER
+    assert kv._lib.kv_workspace_bytes(ctypes.byref(cfg), None) == kv.KV_E_NULL
+    out = ctypes.c_void_p()
+    assert kv._lib.kv_cache_create(ctypes.byref(cfg), None, ctypes.byref(out)) == kv.KV_E_NULL
+    ptrs = (ctypes.c_void_p * 2)(0x10000, 0)
+    assert kv._lib.kv_cache_create(ctypes.byref(cfg), ptrs, ctypes.byref(out)) == kv.KV_E_NULL
+    ptrs = (ctypes.c_void_p * 2)(0x10000, 0x10010)
+    assert kv._lib.kv_cache_create(ctypes.byref(cfg), ptrs, ctypes.byref(out)) == kv.KV_E_ALIGN
+    assert kv._lib.kv_cache_destroy(None) == kv.KV_E_NULL
+
+
+def test_call_errors_are_caught_before_any_launch(kv):
+    """Fake (never dereferenced) device addresses: every call below must fail on the host."""
+    cfg = _cfg(kv)
+    h = kv.kv_cache_create(cfg, [0x100000, 0x200000])
+    try:
+        assert kv.kv_cache_len(h, 0) == (0, 0)
+        lay = kv.kv_cache_describe(h, 0)
+        assert lay.rec_bytes == 5632 and lay.k_codes == 0 and lay.k_scale == 2048
+        assert lay.v_codes == 2048 + 768 and lay.v_meta == lay.v_codes + 2048 and lay.v_mean == lay.v_meta + 512
+        lib = kv._lib
+        K, V, Q, O, W = 0x300000, 0x400000, 0x500000, 0x600000, 0x700000
+        assert lib.kv_quant_append(h, 5, K, V, 1, 1024, 256, 128, None) == kv.KV_E_BAD_LAYER
+        assert lib.kv_quant_append(h, 0, None, V, 1, 1024, 256, 128, None) == kv.KV_E_NULL
+        assert lib.kv_quant_append(h, 0, K + 2, V, 1, 1024, 256, 128, None) == kv.KV_E_ALIGN
+        assert lib.kv_quant_append(h, 0, K, V, 1, 1024, 252, 128, None) == kv.KV_E_ALIGN
+        assert lib.kv_quant_append(h, 0, K, V, 1, 1024, 256, 64, None) == kv.KV_E_BAD_CONFIG
+        assert lib.kv_quant_append(h, 0, K, V, 257, 257 * 256, 256, 128, None) == kv.KV_E_CAPACITY
+        assert lib.kv_quant_append(h, 0, K, V, -1, 1024, 256, 128, None) == kv.KV_E_BAD_CONFIG
+        assert lib.kv_quant_append(h, 0, K, V, 0, 1024, 256, 128, None) == kv.KV_OK  # no-op
+        assert kv.kv_cache_len(h, 0) == (0, 0)
+        assert lib.kv_decode_attn(h, 0, Q, O, W, 1 << 20, None) == kv.KV_E_EMPTY
+        assert lib.kv_decode_attn(h, 0, Q, None, W, 1 << 20, None) == kv.KV_E_NULL
+        assert lib.kv_decode_attn(h, 9, Q, O, W, 1 << 20, None) == kv.KV_E_BAD_LAYER
+        assert lib.kv_set_decode_path(h, 7) == kv.KV_E_BAD_CONFIG
+        assert lib.kv_set_decode_splits(h, 1000) == kv.KV_E_BAD_CONFIG
+        assert lib.kv_set_decode_splits(h, 4) == kv.KV_OK
+        n = ctypes.c_int32()
+        assert lib.kv_decode_splits(h, 0, ctypes.byref(n)) == kv.KV_E_EMPTY
+        assert lib.kv_cache_reset(h, 3) == kv.KV_E_BAD_LAYER
+        assert lib.kv_cache_reset(h, -1) == kv.KV_OK
+    finally:
+        kv.kv_cache_destroy(h)
+
+
+def test_strerror_names_every_status(kv):
+    seen = set()
+    for s in range(0, -11, -1):
+        msg = kv.kv_strerror(s)
+        assert msg and msg != "unknown status"
+        seen.add(msg)
+    assert len(seen) == 11
+    assert kv.kv_strerror(-99) == "unknown status"

@@ -1,0 +1,195 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
+Packed codes and metadata must match bit for bit; attention within 2e-3 max-abs."""
+import numpy as np
+import pytest
+
+from paper_2506_04642_amd import synth
+from parity_util import append_both, check_attention, check_bytes, make_pair, to_dev
+
+pytestmark = pytest.mark.gpu
+
+F16, BF16 = 0, 1
+CHAN, CROSS, NONE = 0, 1, 2
+
+
+@pytest.fixture(scope="module")
+def kv():
+    import torch
+
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_2506_04642_amd import binding
+
+    return binding
+
+
+# ------------------------------------------------------------------ config 0: one head, fp16
+
+
+@pytest.mark.parametrize("T", [1, 31, 32, 33, 1024, 1037])
+def test_single_head_fp16_4bit(kv, oracle, T):
+    print("case single_head T=%d" % T, flush=True)
+    gpu, orc = make_pair(kv, oracle, T_max=2048, dtype=F16, k_bits=(4,))
+    k, v = synth.make_kv(100 + T, 1, T, 1, 128, F16)
+    append_both(gpu, orc, 0, k, v, F16)
+    check_bytes(gpu, orc, 0)
+    check_attention(gpu, orc, 0, synth.make_q(100 + T, 1, 1, 128, F16), F16)
+
+
+# ------------------------------------------------------------------ config 1: Llama-3-8B layer
+
+
+@pytest.mark.parametrize("T", [8192, 8193, 8205])
+def test_llama8b_layer_bf16_4bit(kv, oracle, T):
+    print("case llama8b_layer T=%d" % T, flush=True)
+    gpu, orc = make_pair(kv, oracle, B=1, Hq=32, Hkv=8, T_max=8192 + 32, dtype=BF16, k_bits=(4,))
+    k, v = synth.make_kv(1000, 1, T, 8, 128, BF16)
+    # bulk prefill of T-1 tokens, then one decode step: append 1, attend
+    append_both(gpu, orc, 0, k, v, BF16, chunks=[T - 1, 1])
+    check_bytes(gpu, orc, 0)
+    check_attention(gpu, orc, 0, synth.make_q(1000, 1, 32, 128, BF16), BF16)
+
+
+# ------------------------------------------------------------------ sweep of formats
+
+
+@pytest.mark.parametrize("bits", [2, 4, 8, 16])
+@pytest.mark.parametrize("dtype", [F16, BF16])
+@pytest.mark.parametrize("G,Gc", [(32, 32), (64, 64), (128, 32), (32, 128)])
+def test_bit_widths_and_groups(kv, oracle, bits, dtype, G, Gc):
+    print("case widths bits=%d dtype=%d G=%d Gc=%d" % (bits, dtype, G, Gc), flush=True)
+    T = 3 * G + 5
+    gpu, orc = make_pair(kv, oracle, B=2, Hq=8, Hkv=2, T_max=4 * G, G=G, Gc=Gc, dtype=dtype, k_bits=(bits,))
+    k, v = synth.make_kv(7 * bits + G, 2, T, 2, 128, dtype)
+    append_both(gpu, orc, 0, k, v, dtype)
+    check_bytes(gpu, orc, 0)
+    check_attention(gpu, orc, 0, synth.make_q(bits + G, 2, 8, 128, dtype), dtype)
+
+
+@pytest.mark.parametrize("kb,vb", [(2, 4), (4, 2), (8, 2), (4, 8)])
+def test_different_widths_for_keys_and_values(kv, oracle, kb, vb):
+    print("case kv_widths kb=%d vb=%d" % (kb, vb), flush=True)
+    gpu, orc = make_pair(kv, oracle, B=1, Hq=4, Hkv=1, T_max=256, dtype=BF16, k_bits=(kb,), v_bits=(vb,))
+    k, v = synth.make_kv(kb * 10 + vb, 1, 200, 1, 128, BF16)
+    append_both(gpu, orc, 0, k, v, BF16)
+    check_bytes(gpu, orc, 0)
+    check_attention(gpu, orc, 0, synth.make_q(3, 1, 4, 128, BF16), BF16)
+
+
+@pytest.mark.parametrize("mode", [CHAN, NONE])
+@pytest.mark.parametrize("g", [1, 2, 4, 8])
+def test_mean_modes_and_query_groups(kv, oracle, mode, g):
+    print("case modes mode=%d g=%d" % (mode, g), flush=True)
+    Hkv = 2
+    gpu, orc = make_pair(kv, oracle, B=2, Hq=Hkv * g, Hkv=Hkv, T_max=512, dtype=BF16, mode=mode, k_bits=(4,))
+    k, v = synth.make_kv(50 + g, 2, 300, Hkv, 128, BF16)
+    append_both(gpu, orc, 0, k, v, BF16)
+    check_bytes(gpu, orc, 0)
+    check_attention(gpu, orc, 0, synth.make_q(g, 2, Hkv * g, 128, BF16), BF16)
+
+
+def test_mixed_layer_map(kv, oracle):
+    print("case mixed_layer_map", flush=True)
+    bits = (8, 4, 2, 16, 2, 4)
+    gpu, orc = make_pair(kv, oracle, L=6, B=2, Hq=8, Hkv=2, T_max=256, dtype=BF16, k_bits=bits)
+    for l in range(6):
+        k, v = synth.make_kv(200 + l, 2, 150, 2, 128, BF16)
+        append_both(gpu, orc, l, k, v, BF16)
+    for l in range(6):
+        check_bytes(gpu, orc, l)
+        check_attention(gpu, orc, l, synth.make_q(l, 2, 8, 128, BF16), BF16)
+
+
+# ------------------------------------------------------------------ append semantics
+
+
+@pytest.mark.parametrize("R", [32, 64])
+def test_single_token_appends_equal_bulk(kv, oracle, R):
+    print("case single_appends R=%d" % R, flush=True)
+    T = 77
+    gpu, orc = make_pair(kv, oracle, B=2, Hq=4, Hkv=2, T_max=128, R=R, dtype=F16, k_bits=(4,), v_bits=(2,))
+    k, v = synth.make_kv(9, 2, T, 2, 128, F16)
+    append_both(gpu, orc, 0, k, v, F16, chunks=[1] * T)
+    check_bytes(gpu, orc, 0)
+    q = synth.make_q(9, 2, 4, 128, F16)
+    check_attention(gpu, orc, 0, q, F16)
+    # uneven chunks through a second pair must give the same bytes
+    gpu2, orc2 = make_pair(kv, oracle, B=2, Hq=4, Hkv=2, T_max=128, R=R, dtype=F16, k_bits=(4,), v_bits=(2,))
+    append_both(gpu2, orc2, 0, k, v, F16, chunks=[5, 40, 0, 31, 1])
+    check_bytes(gpu2, orc2, 0)
+
+
+def test_strided_input_views(kv, oracle):
+    """k_new / v_new given as strided views (a slice of a larger [B, T, 3H, d] projection)."""
+    import torch
+
+    print("case strided_views", flush=True)
+    gpu, orc = make_pair(kv, oracle, B=2, Hq=4, Hkv=2, T_max=128, dtype=BF16, k_bits=(4,))
+    k, v = synth.make_kv(12, 2, 70, 2, 128, BF16)
+    big_k = torch.zeros((2, 70, 6, 128), dtype=torch.bfloat16, device="cuda:0")
+    big_v = torch.zeros_like(big_k)
+    big_k[:, :, 2:4] = to_dev(k, BF16)
+    big_v[:, :, 2:4] = to_dev(v, BF16)
+    gpu.append(0, big_k[:, :, 2:4], big_v[:, :, 2:4])
+    orc.append(0, k, v)
+    check_bytes(gpu, orc, 0)
+
+
+def test_capacity_and_empty_errors(kv, oracle):
+    print("case capacity_errors", flush=True)
+    gpu, orc = make_pair(kv, oracle, T_max=64, dtype=F16, k_bits=(4,))
+    q = to_dev(synth.make_q(1, 1, 1, 128, F16), F16)
+    with pytest.raises(kv.KVError) as e:
+        gpu.attend(0, q)
+    assert e.value.status == kv.KV_E_EMPTY
+    k, v = synth.make_kv(1, 1, 65, 1, 128, F16)
+    with pytest.raises(kv.KVError) as e:
+        gpu.append(0, to_dev(k, F16), to_dev(v, F16))
+    assert e.value.status == kv.KV_E_CAPACITY
+    assert gpu.lengths(0) == (0, 0)
+    gpu.append(0, to_dev(k[:, :64], F16), to_dev(v[:, :64], F16))
+    assert gpu.lengths(0) == (64, 0)
+
+
+# ------------------------------------------------------------------ split-K merge
+
+
+def test_result_does_not_depend_on_the_split_count(kv, oracle):
+    """The log-sum-exp merge is an identity: 1, 2, 7 or 64 splits give the same attention."""
+    import torch
+
+    print("case split_independence", flush=True)
+    gpu, orc = make_pair(kv, oracle, B=1, Hq=4, Hkv=1, T_max=4096, dtype=BF16, k_bits=(4,))
+    k, v = synth.make_kv(33, 1, 2048 + 9, 1, 128, BF16)
+    append_both(gpu, orc, 0, k, v, BF16)
+    q = synth.make_q(33, 1, 4, 128, BF16)
+    gpu.workspace = torch.empty(4 * 64 * 132 * 4 * 2, dtype=torch.uint8, device="cuda:0")
+    gpu.ws_bytes = gpu.workspace.numel()
+    outs = []
+    for ns in (1, 2, 7, 64):
+        kv.kv_set_decode_splits(gpu.handle, ns)
+        assert kv.kv_decode_splits(gpu.handle, 0) <= ns
+        check_attention(gpu, orc, 0, q, BF16)
+        outs.append(gpu.attend(0, to_dev(q, BF16)).cpu().numpy())
+    for o in outs[1:]:
+        assert np.max(np.abs(o - outs[0])) < 1e-5
+
+
+def test_repeat_calls_are_bitwise_reproducible(kv, oracle):
+    print("case reproducible", flush=True)
+    gpu, orc = make_pair(kv, oracle, B=2, Hq=8, Hkv=2, T_max=1024, dtype=BF16, k_bits=(2,))
+    k, v = synth.make_kv(44, 2, 1000, 2, 128, BF16)
+    append_both(gpu, orc, 0, k, v, BF16)
+    q = to_dev(synth.make_q(44, 2, 8, 128, BF16), BF16)
+    a = gpu.attend(0, q).cpu().numpy()
+    b = gpu.attend(0, q).cpu().numpy()
+    assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+
+
+def test_drifting_channel_means(kv, oracle):
+    """Keys whose channel means drift along the sequence (the reasoning-style workload)."""
+    print("case drift", flush=True)
+    gpu, orc = make_pair(kv, oracle, B=1, Hq=8, Hkv=2, T_max=2048, dtype=BF16, k_bits=(2,))
+    k, v = synth.make_kv(55, 1, 2000, 2, 128, BF16, n_drift=8, slope=0.01)
+    append_both(gpu, orc, 0, k, v, BF16)
+    check_bytes(gpu, orc, 0)
+    check_attention(gpu, orc, 0, synth.make_q(55, 1, 8, 128, BF16), BF16)
