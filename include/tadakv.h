@@ -173,6 +173,9 @@ kv_status kv_set_decode_splits(kv_cache *cache, int32_t n_splits);
 
 const char *kv_strerror(kv_status s);
 
+/* Text of the HIP error behind the calling thread's most recent KV_E_HIP ("no error" if none). */
+const char *kv_last_hip_error(void);
+
 #ifdef __cplusplus
 }
 #endif

@@ -30,7 +30,7 @@ KV_MEAN_CHANNEL_BLOCK, KV_MEAN_CROSS_HEAD, KV_MEAN_NONE = 0, 1, 2
 EXPORTS = [
     "kv_cache_bytes", "kv_workspace_bytes", "kv_cache_create", "kv_cache_destroy", "kv_cache_reset",
     "kv_cache_len", "kv_cache_describe", "kv_quant_append", "kv_decode_attn", "kv_decode_attn_split",
-    "kv_decode_attn_merge", "kv_decode_splits", "kv_decode_bytes", "kv_set_decode_path", "kv_set_decode_splits", "kv_strerror",
+    "kv_decode_attn_merge", "kv_decode_splits", "kv_decode_bytes", "kv_set_decode_path", "kv_set_decode_splits", "kv_strerror", "kv_last_hip_error",
 ]
 
 
@@ -74,19 +74,26 @@ _lib.kv_set_decode_path.argtypes = [_vp, _i32]
 _lib.kv_set_decode_splits.argtypes = [_vp, _i32]
 _lib.kv_strerror.argtypes = [_i32]
 _lib.kv_strerror.restype = ctypes.c_char_p
+_lib.kv_last_hip_error.argtypes = []
+_lib.kv_last_hip_error.restype = ctypes.c_char_p
 for _n in EXPORTS:
-    if _n != "kv_strerror":
+    if _n not in ("kv_strerror", "kv_last_hip_error"):
         getattr(_lib, _n).restype = _i32
 
 
 class KVError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
-        super().__init__("%s: %s (%d)" % (where, kv_strerror(status), status))
+        detail = " [%s]" % kv_last_hip_error() if status == KV_E_HIP else ""
+        super().__init__("%s: %s (%d)%s" % (where, kv_strerror(status), status, detail))
 
 
 def kv_strerror(status: int) -> str:
     return _lib.kv_strerror(status).decode()
+
+
+def kv_last_hip_error() -> str:
+    return _lib.kv_last_hip_error().decode()
 
 
 def _check(status: int, where: str) -> None:

@@ -341,8 +341,9 @@ template <int KB, int VB> hipError_t launch_one(const DecodeArgs &a, hipStream_t
         granted = lds;
     }
     dim3 grid(a.n_splits, a.batch * a.n_kv_heads);
+    (void)hipGetLastError(); // drop any stale error left by earlier runtime calls of this thread
     hipLaunchKernelGGL((decode_split_valu_kernel<KB, VB>), grid, dim3(kThreads), lds, s, a);
-    return hipGetLastError();
+    return note_launch(hipGetLastError());
 }
 
 } // namespace
@@ -364,8 +365,9 @@ hipError_t launch_decode_split_valu(const DecodeArgs &a, hipStream_t s)
 hipError_t launch_decode_merge(const DecodeArgs &a, hipStream_t s)
 {
     dim3 grid(a.batch * a.n_q_heads);
+    (void)hipGetLastError(); // drop any stale error left by earlier runtime calls of this thread
     hipLaunchKernelGGL(merge_kernel, grid, dim3(128), 0, s, a);
-    return hipGetLastError();
+    return note_launch(hipGetLastError());
 }
 
 // matrix-core path: not built yet

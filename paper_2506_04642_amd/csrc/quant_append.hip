@@ -265,8 +265,9 @@ hipError_t launch_flush(const AppendArgs &a, hipStream_t s)
     // grid.y is limited to 65535 entries
     if (U > 65535) return hipErrorInvalidValue;
     dim3 grid(a.n_flush_blocks, U, 2);
+    (void)hipGetLastError(); // drop any stale error left by earlier runtime calls of this thread
     hipLaunchKernelGGL(flush_block_kernel, grid, dim3(kThreads), lds, s, a);
-    return hipGetLastError();
+    return note_launch(hipGetLastError());
 }
 
 hipError_t launch_resid_copy(const AppendArgs &a, hipStream_t s)
@@ -274,8 +275,9 @@ hipError_t launch_resid_copy(const AppendArgs &a, hipStream_t s)
     const int U = a.batch * a.n_kv_heads;
     if (U > 65535) return hipErrorInvalidValue;
     dim3 grid((a.copy_n + 7) / 8, U, 1);
+    (void)hipGetLastError(); // drop any stale error left by earlier runtime calls of this thread
     hipLaunchKernelGGL(resid_copy_kernel, grid, dim3(kThreads), 0, s, a);
-    return hipGetLastError();
+    return note_launch(hipGetLastError());
 }
 
 } // namespace tadakv

@@ -154,7 +154,18 @@ bool use_mfma(const kv_cache *k, const DecodeArgs &a)
 
 } // namespace
 
+namespace tadakv {
+static thread_local hipError_t g_last_hip = hipSuccess;
+hipError_t note_launch(hipError_t e)
+{
+    if (e != hipSuccess) g_last_hip = e;
+    return e;
+}
+} // namespace tadakv
+
 extern "C" {
+
+const char *kv_last_hip_error(void) { return hipGetErrorString(tadakv::g_last_hip); }
 
 const char *kv_strerror(kv_status s)
 {

@@ -47,6 +47,9 @@ struct DecodeArgs {
     int blocks_per_split;
 };
 
+// records the outcome of a launch for kv_last_hip_error and passes it through
+hipError_t note_launch(hipError_t e);
+
 hipError_t launch_flush(const AppendArgs &a, hipStream_t s);
 hipError_t launch_resid_copy(const AppendArgs &a, hipStream_t s);
 hipError_t launch_decode_split_valu(const DecodeArgs &a, hipStream_t s);
