@@ -1,0 +1,237 @@
+"""Benchmark of the TaDA KV-cache hot path on one MI355X.
+
+Workload (the full-cache configuration of the baseline): Llama-3-8B shape, 32 layers, 32 query /
+8 kv heads, head_dim 128, batch 16, context 32768, bf16, group size 32, per-layer bit map seeded
+from {2,4,8} with about a quarter of the layers at 8 bits, per-channel block mean.  The cache is
+filled by bulk quantise-append (untimed warm-up of the state, reported separately), then one
+"step" = for every layer: append one new token per sequence, then decode attention over the whole
+cache.  Inputs are resident in HBM before the timed region starts.
+
+Prints ONE JSON line.  `value` is the decode-attention algorithmic bytes of the timed steps divided
+by the wall time of those steps (appends included), in GB/s.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=32)
+    ap.add_argument("--warmup", type=int, default=4)
+    ap.add_argument("--context", type=int, default=32768)
+    ap.add_argument("--batch", type=int, default=16)
+    ap.add_argument("--layers", type=int, default=32)
+    ap.add_argument("--path", type=int, default=0, help="0 auto, 1 vector-ALU kernels, 2 matrix-core kernels")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding or collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2506_04642_amd import binding as kv
+    from paper_2506_04642_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    L, B, Hq, Hkv, d, G = args.layers, args.batch, 32, 8, 128, 32
+    T0 = args.context
+    K, W = args.steps, args.warmup
+    n_dec = K + W
+    max_tokens = (T0 + n_dec + 8 + G - 1) // G * G
+    bits = synth.layer_bits(2000, L, "mixed248")
+    cfg = kv.make_config(L, B, Hq, Hkv, d, max_tokens, G, G, G, kv.KV_BF16, kv.KV_MEAN_CHANNEL_BLOCK, bits, bits)
+    cache = kv.KVCache(cfg, device=dev, zero=False)
+    kv.kv_set_decode_path(cache.handle, args.path)
+    stream = torch.cuda.current_stream(dev)
+
+    # ---- fill: bulk quantise-append in chunks, inputs drawn on the device
+    sample_layers = {}
+    for b_ in (2, 4, 8):
+        if b_ in bits:
+            sample_layers[bits.index(b_)] = b_
+    host_kv = {}
+    chunk = 4096
+    fill_ms = 0.0
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for l in range(L):
+        keep = l in sample_layers and not args.no_cpu_baseline
+        hk, hv = [], []
+        for t0 in range(0, T0, chunk):
+            n = min(chunk, T0 - t0)
+            k, v = synth.make_kv_torch(2000 * 1000 + l * 64 + t0 // chunk, B, n, Hkv, d, synth.BF16, dev)
+            ev0.record(stream)
+            cache.append(l, k, v)
+            ev1.record(stream)
+            ev1.synchronize()
+            fill_ms += ev0.elapsed_time(ev1)
+            if keep:
+                hk.append(k[0:1].cpu())
+                hv.append(v[0:1].cpu())
+            del k, v
+        if keep:
+            host_kv[l] = (torch.cat(hk, 1), torch.cat(hv, 1))
+    bulk_tokens = L * B * T0
+
+    # ---- decode inputs (resident before timing)
+    k_dec = [synth.make_kv_torch(77000 + l, B, n_dec, Hkv, d, synth.BF16, dev) for l in range(L)]
+    q_dec = [synth.make_q_torch(88000 + l, B, Hq, d, synth.BF16, dev) for l in range(L)]
+    out = torch.empty((B, Hq, d), dtype=torch.float32, device=dev)
+    ws, wsb = cache.workspace.data_ptr(), cache.ws_bytes
+    sp = stream.cuda_stream
+
+    def step(s, events=None):
+        nbytes = 0
+        for l in range(L):
+            kd, vd = k_dec[l]
+            cache.append(l, kd[:, s:s + 1], vd[:, s:s + 1])
+            if events is not None:
+                e0, e1 = events[l]
+                e0.record(stream)
+            kv.kv_decode_attn_split(cache.handle, l, q_dec[l].data_ptr(), ws, wsb, sp)
+            if events is not None:
+                e1.record(stream)
+            kv.kv_decode_attn_merge(cache.handle, l, out.data_ptr(), ws, wsb, sp)
+            nbytes += kv.kv_decode_bytes(cache.handle, l)
+        return nbytes
+
+    for s in range(W):
+        step(s)
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly K steps, HIP events around every split kernel on the launch stream
+    evs = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(L)]
+           for _ in range(K)]
+    layer_bytes = [0] * L
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    total_bytes = 0
+    for s in range(K):
+        total_bytes += step(W + s, evs[s])
+    torch.cuda.synchronize()
+    t_end = time.perf_counter()
+    wall = t_end - t_start
+    for l in range(L):
+        layer_bytes[l] = kv.kv_decode_bytes(cache.handle, l)
+
+    split_ms = np.array([[evs[s][l][0].elapsed_time(evs[s][l][1]) for l in range(L)] for s in range(K)])
+    per_bits = {}
+    for b_ in sorted(set(bits)):
+        idx = [l for l in range(L) if bits[l] == b_]
+        ms = float(split_ms[:, idx].mean())
+        byts = float(np.mean([layer_bytes[l] for l in idx]))
+        per_bits[str(b_)] = {"layers": len(idx), "avg_ms": round(ms, 5), "bytes": int(byts),
+                             "GBps": round(byts / ms / 1e6, 1), "frac": round(byts / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+    achieved = float(sum(layer_bytes)) / float(split_ms.mean(axis=0).sum()) / 1e6
+
+    # ---- single-token append cost, measured apart from the timed region
+    torch.cuda.synchronize()
+    app_t0 = time.perf_counter()
+    # (host-side only bookkeeping would be skipped by a no-op; use the real call on spare capacity)
+    spare = max_tokens - (T0 + n_dec)
+    n_app = min(spare, 8)
+    for s in range(n_app):
+        for l in range(L):
+            kd, vd = k_dec[l]
+            cache.append(l, kd[:, s:s + 1], vd[:, s:s + 1])
+    torch.cuda.synchronize()
+    app_s = time.perf_counter() - app_t0
+
+    result = {
+        "metric": "decode_attn_effective_hbm_GBps",
+        "value": round(total_bytes / wall / 1e9, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": round(wall / K * 1e3, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int8+f32" if args.path != 1 else "f32",
+        "data": "synthetic",
+        "config": {"workload": "llama3-8b-shaped full cache: 32 layers, 32q/8kv heads, head_dim 128, "
+                               "batch %d, context %d, bf16, G=Gc=32, mixed {2,4,8}-bit layer map (seed 2000), "
+                               "per-channel block mean" % (B, T0),
+                   "layers": L, "batch": B, "context": T0, "bit_map": bits, "decode_path": args.path},
+        "pct_of_hbm_peak": round(total_bytes / wall / 1e9 / HBM_PEAK_GBPS * 100, 2),
+        "decode_tokens_per_s": round(B * K / wall, 1),
+        "quant_append": {
+            "bulk_tokens_per_s": round(bulk_tokens / (fill_ms / 1e3), 1),
+            "bulk_input_GBps": round(bulk_tokens * Hkv * d * 2 * 2 / (fill_ms / 1e3) / 1e9, 1),
+            "single_token_tokens_per_s": round(B * n_app / app_s, 1) if n_app else None,
+            "single_token_us_per_layer_call": round(app_s / max(n_app * L, 1) * 1e6, 2) if n_app else None,
+        },
+        "roofline": {"bound": "hbm", "kernel": "decode split kernel (all layers, weighted by layer)",
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None, "per_bits": per_bits},
+    }
+
+    # ---- CPU oracle on a bounded sample of the same workload (rank 0, one core)
+    if not args.no_cpu_baseline and host_kv:
+        import oracle
+
+        ocfg_bits = [sample_layers[l] for l in sorted(sample_layers)]
+        nl = len(ocfg_bits)
+        ocfg = oracle.OracleConfig(nl, 1, Hq, Hkv, d, max_tokens, G, G, G, oracle.tada.BF16,
+                                   oracle.tada.MEAN_CHANNEL_BLOCK, ocfg_bits, ocfg_bits)
+        orc = oracle.OracleCache(ocfg)
+        enc_s = att_s = 0.0
+        att_bytes = 0
+        worst = 0.0
+        for i, l in enumerate(sorted(sample_layers)):
+            hk, hv = host_kv[l]
+            k16 = hk.view(torch.int16).numpy().view(np.uint16)
+            v16 = hv.view(torch.int16).numpy().view(np.uint16)
+            t0 = time.perf_counter()
+            orc.append(i, k16, v16)
+            enc_s += time.perf_counter() - t0
+            # replay the decode tokens that the GPU cache has seen, so both hold the same state
+            seen = W + K + n_app
+            kd, vd = k_dec[l]
+            order = list(range(W + K)) + list(range(n_app))
+            for s in order[:seen]:
+                orc.append(i, kd[0:1, s:s + 1].cpu().view(torch.int16).numpy().view(np.uint16),
+                           vd[0:1, s:s + 1].cpu().view(torch.int16).numpy().view(np.uint16))
+            q16 = q_dec[l][0:1].cpu().view(torch.int16).numpy().view(np.uint16)
+            t0 = time.perf_counter()
+            want = orc.attend(i, q16)
+            att_s += time.perf_counter() - t0
+            got = cache.attend(l, q_dec[l])
+            torch.cuda.synchronize()
+            worst = max(worst, float(np.max(np.abs(got[0].cpu().numpy().astype(np.float64) - want[0]))))
+            att_bytes += kv.kv_decode_bytes(cache.handle, l) // B
+        result["cpu_baseline"] = {
+            "value": round(att_bytes / att_s / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": "batch element 0 (8 kv-head units, full context) of one layer per bit width %s: "
+                      "decode attention %.2f s; its quantise-append %.2f s = %.0f tokens/s"
+                      % (ocfg_bits, att_s, enc_s, nl * T0 / enc_s),
+            "quant_append_tokens_per_s": round(nl * T0 / enc_s, 1),
+            "gpu_vs_oracle_max_abs_err": worst,
+        }
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
