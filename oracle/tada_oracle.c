@@ -271,47 +271,56 @@ int orc_decode_block(const uint8_t *codes, const uint16_t *scale, const uint16_t
 
 /*
  * Physical position of the code of (token t, channel c) inside one head's packed block.
- * A block is cut into 16 x 16 tiles of codes ("line" x "slot"); a line's 16 slots sit in
- * 2*bits consecutive bytes, slot e at bit offset bits*e (little-endian).  Sixteen bytes
- * hold the same line of 8/bits tiles; sixteen such pieces (lines 0..15) are consecutive.
- * Keys: line = token, slot = channel.  Values: line = channel, slot = token.
+ * A block is cut into 16 x 16 tiles of codes ("line" x "slot").  A line's 16 slots sit in
+ * 2*bits consecutive bytes, i.e. bits/2 32-bit words of 32/bits slots each.  Inside a word the
+ * slots are byte-interleaved: the word's slot number 4*f + y (y = 0..3) is field f of byte y,
+ * field f being bits [bits*f, bits*f + bits) of that byte.  Sixteen bytes ("piece") hold the
+ * same line of 8/bits tiles; sixteen pieces (lines 0..15) are consecutive.
+ * Keys: line = token, slot = channel; a piece holds channel tiles (2j, 2j+1) at 4 bits, those
+ * two tiles for two consecutive token tiles at 2 bits, and one tile at 8 bits, where pieces
+ * are ordered (token tile, tile parity, j).  Values: line = channel, slot = token.
  * d must be 128 (eight channel tiles).  G is a multiple of 16 (32 for 2-bit keys).
  */
+static void slot_in_line(int bits, int e, size_t *byte_in_line, int *shift)
+{
+    const int per_word = 32 / bits;          /* slots per 32-bit word */
+    const int word = e / per_word, r = e % per_word;
+    *byte_in_line = (size_t)word * 4 + (size_t)(r % 4);
+    *shift = bits * (r / 4);
+}
+
 static void code_position(int which, int bits, int G, int t, int c, size_t *byte, int *shift)
 {
-    size_t piece, within;
+    size_t piece, tile_off, in_line;
+    const int line_bytes = 2 * bits; /* bytes of one tile line */
     if (which == ORC_K) {
         int tt = t / 16, n = t % 16, cg = c / 16, e = c % 16;
+        slot_in_line(bits, e, &in_line, shift);
         if (bits == 8) {
-            piece = ((size_t)(tt * 2 + cg / 4) * 4 + cg % 4) * 16 + n;
-            within = e;
-            *shift = 0;
+            piece = ((size_t)(tt * 2 + cg % 2) * 4 + cg / 2) * 16 + n;
+            tile_off = 0;
         } else if (bits == 4) {
             piece = ((size_t)tt * 4 + cg / 2) * 16 + n;
-            within = (cg % 2) * 8 + e / 2;
-            *shift = 4 * (e % 2);
+            tile_off = (size_t)(cg % 2) * line_bytes;
         } else {
             piece = ((size_t)(tt / 2) * 4 + cg / 2) * 16 + n;
-            within = (tt % 2) * 8 + (cg % 2) * 4 + e / 4;
-            *shift = 2 * (e % 4);
+            tile_off = (size_t)((tt % 2) * 2 + cg % 2) * line_bytes;
         }
     } else {
         int tt = t / 16, e = t % 16, ct = c / 16, n = c % 16, nt = G / 16;
+        slot_in_line(bits, e, &in_line, shift);
         if (bits == 8) {
             piece = ((size_t)ct * nt + tt) * 16 + n;
-            within = e;
-            *shift = 0;
+            tile_off = 0;
         } else if (bits == 4) {
             piece = ((size_t)(ct / 2) * nt + tt) * 16 + n;
-            within = (ct % 2) * 8 + e / 2;
-            *shift = 4 * (e % 2);
+            tile_off = (size_t)(ct % 2) * line_bytes;
         } else {
             piece = ((size_t)(ct / 4) * nt + tt) * 16 + n;
-            within = (ct % 4) * 4 + e / 4;
-            *shift = 2 * (e % 4);
+            tile_off = (size_t)(ct % 4) * line_bytes;
         }
     }
-    *byte = piece * 16 + within;
+    *byte = piece * 16 + tile_off + in_line;
 }
 
 /* codes [G][d] of one head -> packed [G*d*bits/8] bytes */

@@ -17,6 +17,7 @@ UNITS = [
     ("tadakv_abi.cpp", ["-x", "hip"]),
     ("quant_append.hip", ["-ffp-contract=off"]),
     ("decode_valu.hip", []),
+    ("decode_mfma.hip", []),
 ]
 
 

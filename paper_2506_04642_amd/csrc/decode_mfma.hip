@@ -1,0 +1,578 @@
+// Decode attention over the packed cache on the matrix cores (gfx950, v_mfma_i32_16x16x64_i8).
+//
+// What is computed is the same as in the vector-ALU kernel (arxiv 2506.04642 Eq. 5-8, flash
+// decoding of App. A): per block
+//   score_t = ( sum_c (q_c s_c) code_tc + sum_c q_c (z_c + m_c) ) / sqrt(d)
+//   o_c     = sum_t (p_t s_tg) code_tc + sum_t p_t z_tg + m_c sum_t p_t
+// but the two contractions over codes run as int8 matrix products.  The small operand
+// (q_c s_c per block, p_t s_tg per 64-token chunk) is converted to 23-bit fixed point against a
+// power-of-two bound and split into three signed bytes ("limbs"); the 16 rows of the matrix
+// instruction hold (query head, limb) for up to four query heads.  The codes are the other
+// operand: one shift and one mask turn a 32-bit word of the cache into four int8 codes, which is
+// why the storage format interleaves fields bytewise.  Products and sums are exact in int32; the
+// only rounding is the fixed-point conversion (relative 2^-23 of the chunk's largest weight).
+//
+// Work split: one workgroup (4 waves) per (sequence, kv head, split).  Each wave owns every
+// fourth 64-token chunk of the split and keeps its own online-softmax state; the four states are
+// merged through LDS at the end and one partial (max, sum, output) per query head is written for
+// the cross-split merge kernel.  Waves never synchronise inside the main loop: every LDS buffer
+// in the loop is private to a wave.
+//
+// Lane roles inside a wave (lane = 16*row + n, quad position a = n & 3, quad index vq = n >> 2):
+//   matrix output      lane (row, n): query head `row`, limbs in the four accumulator registers;
+//                      column n = token n of a 16-token tile (keys) or channel n of a 16-channel
+//                      tile (values).
+//   key-side producer  lane (row, vq, a): head `row`, channels 32*vq + 16*ph + 4*a + {0..3}, ph=0,1.
+//   matrix operands    lane (row, n): operand row / column n, 16 consecutive k-slots of group `row`.
+#include "tadakv_internal.h"
+#include <hip/hip_fp16.h>
+
+namespace tadakv {
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+
+constexpr int kThreads = 256;
+constexpr float kScoreScale = 0.08838834764831845f * 1.4426950408889634f; // log2(e) / sqrt(128)
+constexpr uint32_t kM4 = 0x0F0F0F0Fu, kM2 = 0x03030303u;
+
+template <int CTRL> __device__ __forceinline__ uint32_t dpp_u(uint32_t x)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xF, 0xF, true);
+}
+template <int CTRL> __device__ __forceinline__ float dpp_f(float x)
+{
+    return __uint_as_float(dpp_u<CTRL>(__float_as_uint(x)));
+}
+// quad_perm [1,0,3,2] = 0xB1, [2,3,0,1] = 0x4E, row_half_mirror = 0x141, row_mirror = 0x140
+__device__ __forceinline__ float row_sum(float x)
+{
+    x += dpp_f<0xB1>(x);
+    x += dpp_f<0x4E>(x);
+    x += dpp_f<0x141>(x);
+    x += dpp_f<0x140>(x);
+    return x;
+}
+__device__ __forceinline__ float row_max(float x)
+{
+    x = fmaxf(x, dpp_f<0xB1>(x));
+    x = fmaxf(x, dpp_f<0x4E>(x));
+    x = fmaxf(x, dpp_f<0x141>(x));
+    x = fmaxf(x, dpp_f<0x140>(x));
+    return x;
+}
+
+__device__ __forceinline__ float widen16(uint16_t v, int dtype)
+{
+    if (dtype == 1) return __uint_as_float((uint32_t)v << 16);
+    return __half2float(__ushort_as_half(v));
+}
+__device__ __forceinline__ float h_lo(uint32_t w) { return __half2float(__ushort_as_half((uint16_t)(w & 0xFFFFu))); }
+__device__ __forceinline__ float h_hi(uint32_t w) { return __half2float(__ushort_as_half((uint16_t)(w >> 16))); }
+__device__ __forceinline__ half2_t as_h2(uint32_t w) { return __builtin_bit_cast(half2_t, w); }
+
+// power of two strictly above x (x >= 0), never below 2^lo_exp; and its reciprocal
+__device__ __forceinline__ void pow2_above(float x, float floor_v, float &p, float &inv)
+{
+    const uint32_t b = (__float_as_uint(fmaxf(x, floor_v)) & 0x7F800000u) + 0x00800000u;
+    p = __uint_as_float(b);
+    inv = __uint_as_float(0x7F000000u - b);
+}
+
+// signed-byte limbs of a 32-bit integer: bytes l0..l3 with n = sum l_k 256^k, l_k in [-128,127]
+__device__ __forceinline__ uint32_t limbs(int n) { return ((uint32_t)n + 0x80808080u) ^ 0x80808080u; }
+
+// waits for this wave's outstanding LDS traffic and keeps the compiler from moving LDS accesses
+// across; enough to hand data between lanes of one wave through LDS
+__device__ __forceinline__ void wave_lds_fence() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
+__device__ __forceinline__ v4i mfma(v4i a, v4i b, v4i c)
+{
+    return __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, c, 0, 0, 0);
+}
+
+// running softmax state of one lane: head `row`; O for channels 16*ct + n
+struct State {
+    float M, l;      // running max (exp2 domain), lane-partial sum of weights
+    float O[8];      // output accumulators
+    float Zp[4];     // lane-partial sum_t p_t z_{t,gamma}
+};
+
+// Online-softmax bookkeeping for one chunk of up to 64 tokens: s[k] is the score (exp2 domain)
+// of token 16k + n or -inf.  Returns p[k] relative to the chunk's own max, and the factors
+// alpha (old state) and wc (this chunk) that bring both to the new running max.
+__device__ __forceinline__ void softmax_chunk(const float (&s)[4], State &st, float (&p)[4], float &alpha,
+                                              float &wc)
+{
+    float mc = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
+    mc = row_max(mc);
+    const float m_new = fmaxf(st.M, mc);
+    alpha = exp2f(st.M - m_new);
+    wc = exp2f(mc - m_new);
+    st.M = m_new;
+#pragma unroll
+    for (int k = 0; k < 4; k++) p[k] = exp2f(s[k] - mc);
+    st.l = st.l * alpha + wc * ((p[0] + p[1]) + (p[2] + p[3]));
+}
+
+template <int B, int G, int GC>
+__global__ __launch_bounds__(kThreads) void decode_split_mfma_kernel(DecodeArgs a)
+{
+    constexpr int NBC = 64 / G;            // blocks per 64-token chunk
+    constexpr int TPB = G / 16;            // 16-token tiles per block
+    constexpr int NG = kHeadDim / GC;      // value scale groups
+    constexpr int TPG = GC / 16;           // channel tiles per value scale group
+    constexpr int NKL = (B == 4) ? 4 : (B == 2 ? 2 : 8); // key code loads per chunk
+    constexpr int NVL = (B == 4) ? 4 : (B == 2 ? 2 : 8); // value code loads per chunk
+    constexpr int AK_DW = NBC * 2 * 256;   // dwords of key operands per wave
+    constexpr int AV_DW = NG * 256;        // dwords of value operands per wave
+    constexpr int WAVE_DW = 2048;          // 8 KiB of LDS per wave
+    static_assert(AK_DW + AV_DW <= WAVE_DW, "LDS layout");
+
+    __shared__ __attribute__((aligned(16))) uint32_t lds_all[4 * WAVE_DW];
+
+    const LayerGeom &gm = a.geom;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int row = lane >> 4, n = lane & 15, qa = lane & 3, vq = (lane >> 2) & 3;
+    uint32_t *lds = lds_all + wave * WAVE_DW;
+    uint32_t *ak = lds, *av = lds + AK_DW;
+
+    const int sp = blockIdx.x, u = blockIdx.y;
+    const int b = u / a.n_kv_heads, h = u % a.n_kv_heads;
+    const int g = a.g;
+    const bool has_kmean = gm.k_mean >= 0, has_vmean = gm.v_mean >= 0;
+
+    // rows 4i+3 of the operands (the unused fourth limb) must read as zero
+    for (int i = lane; i < WAVE_DW; i += 64) lds[i] = 0u;
+
+    // ---- query of head `row`: this lane's eight channels, as fixed-point factors and as halves
+    float qf[2][4];      // 2^22 q / qb  (qb = power of two above max |q| of the head): exact
+    half2_t qh[2][2];    // q as binary16 pairs for the zero / mean dot products
+    float inv_kf_base;   // qb 2^-22 log2(e)/sqrt(d): undoes the fixed point, up to the scale bound
+    {
+        const uint16_t *qp = a.q + ((long long)b * a.n_q_heads + h * g + (row < g ? row : 0)) * kHeadDim;
+        float qmax = 0.0f;
+#pragma unroll
+        for (int ph = 0; ph < 2; ph++)
+#pragma unroll
+            for (int y = 0; y < 4; y++) {
+                const int c = 32 * vq + 16 * ph + 4 * qa + y;
+                qf[ph][y] = row < g ? widen16(qp[c], gm.dtype) : 0.0f;
+                qmax = fmaxf(qmax, fabsf(qf[ph][y]));
+            }
+        qmax = row_max(qmax);
+        float qb, inv_qb;
+        pow2_above(qmax, 0x1p-60f, qb, inv_qb);
+        inv_kf_base = qb * 0x1p-22f * kScoreScale;
+#pragma unroll
+        for (int ph = 0; ph < 2; ph++) {
+            qh[ph][0] = half2_t{(_Float16)qf[ph][0], (_Float16)qf[ph][1]};
+            qh[ph][1] = half2_t{(_Float16)qf[ph][2], (_Float16)qf[ph][3]};
+#pragma unroll
+            for (int y = 0; y < 4; y++) qf[ph][y] *= inv_qb * 0x1p22f;
+        }
+    }
+    {
+        State st;
+        st.M = -INFINITY;
+        st.l = 0.0f;
+#pragma unroll
+        for (int k = 0; k < 8; k++) st.O[k] = 0.0f;
+#pragma unroll
+        for (int k = 0; k < 4; k++) st.Zp[k] = 0.0f;
+
+        wave_lds_fence();
+
+        // ---- range of this split
+        const int work = a.n_blocks + (a.r > 0 ? 1 : 0);
+        const int w0 = sp * a.blocks_per_split;
+        int w1 = w0 + a.blocks_per_split;
+        if (w1 > work) w1 = work;
+        const int b_end = w1 < a.n_blocks ? w1 : a.n_blocks;
+        const int n_chunks = (b_end - w0 + NBC - 1) / NBC;
+        const unsigned char *unit_base = a.layer + (long long)u * gm.NB * gm.rec_bytes;
+
+        const uint32_t sel1 = (qa & 1) ? 0x03070105u : 0x06020400u;
+        const uint32_t sel2 = (qa & 2) ? 0x03020706u : 0x05040100u;
+
+        for (int ci = wave; ci < n_chunks; ci += 4) {
+            const int blk0 = w0 + ci * NBC;
+            // records of the chunk's blocks (an absent second block re-reads the first; its
+            // tokens are masked below)
+            const unsigned char *rec[NBC];
+            bool blk_ok[NBC];
+#pragma unroll
+            for (int bi = 0; bi < NBC; bi++) {
+                blk_ok[bi] = blk0 + bi < b_end;
+                rec[bi] = unit_base + (long long)(blk_ok[bi] ? blk0 + bi : blk0) * gm.rec_bytes;
+            }
+            // block and tile-in-block of chunk tile `row` (this lane's token group on the value side)
+            const unsigned char *rec_row = rec[row / TPB];
+            const int tt_row = row % TPB;
+
+            // ---- loads
+            uint4 kc[NKL], vc[NVL];
+#pragma unroll
+            for (int i = 0; i < NKL; i++) {
+                int bi, off;
+                if (B == 4) { bi = i / TPB; off = (i % TPB) * 64; }
+                else if (B == 2) { bi = (2 * i) / TPB; off = (((2 * i) % TPB) / 2) * 64; }
+                else { bi = (i / 2) / TPB; off = (((i / 2) % TPB) * 2 + (i & 1)) * 64; }
+                kc[i] = *(const uint4 *)(rec[bi] + gm.k_codes + (off + lane) * 16);
+            }
+#pragma unroll
+            for (int i = 0; i < NVL; i++)
+                vc[i] = *(const uint4 *)(rec_row + gm.v_codes + ((i * TPB + tt_row) * 16 + n) * 16);
+            uint32_t vm[4][NG];
+#pragma unroll
+            for (int k = 0; k < 4; k++) {
+                const unsigned char *p = rec[k / TPB] + gm.v_meta + (((k % TPB) * 16 + n) * NG) * 4;
+                if (NG == 4) {
+                    const uint4 t = *(const uint4 *)p;
+                    vm[k][0] = t.x; vm[k][1 % NG] = t.y; vm[k][2 % NG] = t.z; vm[k][3 % NG] = t.w;
+                } else {
+                    const uint2 t = *(const uint2 *)p;
+                    vm[k][0] = t.x; vm[k][1 % NG] = t.y;
+                }
+            }
+            uint2 ks[NBC][2], kz[NBC][2], km[NBC][2];
+#pragma unroll
+            for (int bi = 0; bi < NBC; bi++)
+#pragma unroll
+                for (int ph = 0; ph < 2; ph++) {
+                    const int co = (32 * vq + 16 * ph + 4 * qa) * 2;
+                    ks[bi][ph] = *(const uint2 *)(rec[bi] + gm.k_scale + co);
+                    kz[bi][ph] = *(const uint2 *)(rec[bi] + gm.k_zero + co);
+                    km[bi][ph] = has_kmean ? *(const uint2 *)(rec[bi] + gm.k_mean + co) : uint2{0u, 0u};
+                }
+            uint16_t vmean[NBC][8];
+#pragma unroll
+            for (int bi = 0; bi < NBC; bi++)
+#pragma unroll
+                for (int ct = 0; ct < 8; ct++)
+                    vmean[bi][ct] = has_vmean ? *(const uint16_t *)(rec[bi] + gm.v_mean + (16 * ct + n) * 2) : (uint16_t)0;
+
+            // ---- key side: q*scale as limbs -> LDS; zero/mean term
+            float inv_kf[NBC], beta[NBC];
+#pragma unroll
+            for (int bi = 0; bi < NBC; bi++) {
+                float sf[2][4];
+#pragma unroll
+                for (int ph = 0; ph < 2; ph++) {
+                    sf[ph][0] = h_lo(ks[bi][ph].x); sf[ph][1] = h_hi(ks[bi][ph].x);
+                    sf[ph][2] = h_lo(ks[bi][ph].y); sf[ph][3] = h_hi(ks[bi][ph].y);
+                }
+                float smax = fmaxf(fmaxf(fmaxf(sf[0][0], sf[0][1]), fmaxf(sf[0][2], sf[0][3])),
+                                   fmaxf(fmaxf(sf[1][0], sf[1][1]), fmaxf(sf[1][2], sf[1][3])));
+                smax = row_max(smax);
+                float sb, inv_sb;
+                pow2_above(smax, 0x1p-40f, sb, inv_sb);
+                inv_kf[bi] = inv_kf_base * sb;
+                float bacc = 0.0f;
+#pragma unroll
+                for (int ph = 0; ph < 2; ph++) {
+                    uint32_t X[4];
+#pragma unroll
+                    for (int y = 0; y < 4; y++) X[y] = limbs(__float2int_rn(qf[ph][y] * (sf[ph][y] * inv_sb)));
+                    const uint32_t U = __builtin_amdgcn_perm(X[1], X[0], 0x05010400u);
+                    const uint32_t U2 = __builtin_amdgcn_perm(X[1], X[0], 0x07030602u);
+                    const uint32_t W = __builtin_amdgcn_perm(X[3], X[2], 0x05010400u);
+                    const uint32_t W2 = __builtin_amdgcn_perm(X[3], X[2], 0x07030602u);
+                    const uint32_t Y0 = __builtin_amdgcn_perm(W, U, 0x05040100u);
+                    const uint32_t Y1 = __builtin_amdgcn_perm(W, U, 0x07060302u);
+                    const uint32_t Y2 = __builtin_amdgcn_perm(W2, U2, 0x05040100u);
+                    uint32_t *dst = ak + bi * 512 + ((ph * 4 + vq) * 16 + 4 * row) * 4 + qa;
+                    dst[0] = Y0;
+                    dst[4] = Y1;
+                    dst[8] = Y2;
+                    bacc = __builtin_amdgcn_fdot2(qh[ph][0], as_h2(kz[bi][ph].x), bacc, false);
+                    bacc = __builtin_amdgcn_fdot2(qh[ph][1], as_h2(kz[bi][ph].y), bacc, false);
+                    bacc = __builtin_amdgcn_fdot2(qh[ph][0], as_h2(km[bi][ph].x), bacc, false);
+                    bacc = __builtin_amdgcn_fdot2(qh[ph][1], as_h2(km[bi][ph].y), bacc, false);
+                }
+                beta[bi] = row_sum(bacc) * kScoreScale;
+            }
+            wave_lds_fence();
+
+            // ---- key matrix products -> scores
+            float s[4];
+#pragma unroll
+            for (int k = 0; k < 4; k++) {
+                const int bi = k / TPB;
+                const v4i a0 = *(const v4i *)(ak + bi * 512 + ((0 * 4 + row) * 16 + n) * 4);
+                const v4i a1 = *(const v4i *)(ak + bi * 512 + ((1 * 4 + row) * 16 + n) * 4);
+                v4i acc = {0, 0, 0, 0};
+                if (B == 4) {
+                    const uint4 w = kc[k];
+                    const v4i b0 = {(int)(w.x & kM4), (int)((w.x >> 4) & kM4), (int)(w.y & kM4), (int)((w.y >> 4) & kM4)};
+                    const v4i b1 = {(int)(w.z & kM4), (int)((w.z >> 4) & kM4), (int)(w.w & kM4), (int)((w.w >> 4) & kM4)};
+                    acc = mfma(a0, b0, acc);
+                    acc = mfma(a1, b1, acc);
+                } else if (B == 2) {
+                    const uint4 w = kc[k >> 1];
+                    const uint32_t w0_ = (k & 1) ? w.z : w.x, w1_ = (k & 1) ? w.w : w.y;
+                    const v4i b0 = {(int)(w0_ & kM2), (int)((w0_ >> 2) & kM2), (int)((w0_ >> 4) & kM2), (int)((w0_ >> 6) & kM2)};
+                    const v4i b1 = {(int)(w1_ & kM2), (int)((w1_ >> 2) & kM2), (int)((w1_ >> 4) & kM2), (int)((w1_ >> 6) & kM2)};
+                    acc = mfma(a0, b0, acc);
+                    acc = mfma(a1, b1, acc);
+                } else {
+                    const uint4 wa = kc[2 * k], wb = kc[2 * k + 1];
+                    const v4i lo0 = {(int)(wa.x & kM4), (int)(wa.y & kM4), (int)(wa.z & kM4), (int)(wa.w & kM4)};
+                    const v4i hi0 = {(int)((wa.x >> 4) & kM4), (int)((wa.y >> 4) & kM4), (int)((wa.z >> 4) & kM4), (int)((wa.w >> 4) & kM4)};
+                    const v4i lo1 = {(int)(wb.x & kM4), (int)(wb.y & kM4), (int)(wb.z & kM4), (int)(wb.w & kM4)};
+                    const v4i hi1 = {(int)((wb.x >> 4) & kM4), (int)((wb.y >> 4) & kM4), (int)((wb.z >> 4) & kM4), (int)((wb.w >> 4) & kM4)};
+                    v4i alo = {0, 0, 0, 0}, ahi = {0, 0, 0, 0};
+                    alo = mfma(a0, lo0, alo);
+                    alo = mfma(a1, lo1, alo);
+                    ahi = mfma(a0, hi0, ahi);
+                    ahi = mfma(a1, hi1, ahi);
+                    acc = alo + ahi * 16;
+                }
+                const float dotv = (float)acc.x + 256.0f * (float)acc.y + 65536.0f * (float)acc.z;
+                s[k] = blk_ok[bi] ? dotv * inv_kf[bi] + beta[bi] : -INFINITY;
+            }
+
+            // ---- softmax bookkeeping
+            float p[4], alpha, wc;
+            softmax_chunk(s, st, p, alpha, wc);
+
+            // ---- value side: p*scale as limbs -> LDS; zero term
+            float vs[4][NG];
+            float svmax = 0.0f;
+#pragma unroll
+            for (int k = 0; k < 4; k++)
+#pragma unroll
+                for (int gam = 0; gam < NG; gam++) {
+                    vs[k][gam] = h_lo(vm[k][gam]);
+                    svmax = fmaxf(svmax, vs[k][gam]);
+                }
+            svmax = row_max(svmax);
+            float sbv, inv_sbv;
+            pow2_above(svmax, 0x1p-40f, sbv, inv_sbv);
+            const float vf = inv_sbv * 0x1p22f;
+            const float o_scale = wc * sbv * 0x1p-22f;
+#pragma unroll
+            for (int gam = 0; gam < NG; gam++) {
+                float zsum = 0.0f;
+#pragma unroll
+                for (int k = 0; k < 4; k++) {
+                    zsum += p[k] * h_hi(vm[k][gam]);
+                    const uint32_t X = limbs(__float2int_rn(p[k] * (vs[k][gam] * vf)));
+                    // byte transpose across the quad: lane with quad position L ends up with limb L
+                    // of the quad's four consecutive tokens
+                    const uint32_t P = dpp_u<0xB1>(X);
+                    const uint32_t T = __builtin_amdgcn_perm(P, X, sel1);
+                    const uint32_t Q = dpp_u<0x4E>(T);
+                    const uint32_t Y = __builtin_amdgcn_perm(Q, T, sel2);
+                    av[(gam * 4 + k) * 64 + (4 * row + qa) * 4 + vq] = Y;
+                }
+                st.Zp[gam] = st.Zp[gam] * alpha + wc * zsum;
+            }
+            float psum_b[NBC];
+#pragma unroll
+            for (int bi = 0; bi < NBC; bi++) {
+                float t = 0.0f;
+#pragma unroll
+                for (int k = bi * TPB; k < (bi + 1) * TPB; k++) t += p[k];
+                psum_b[bi] = has_vmean ? row_sum(t) * wc : 0.0f;
+            }
+            wave_lds_fence();
+
+            // ---- value matrix products -> output accumulators
+            v4i avr[NG];
+#pragma unroll
+            for (int gam = 0; gam < NG; gam++) avr[gam] = *(const v4i *)(av + gam * 256 + (row * 16 + n) * 4);
+#pragma unroll
+            for (int ct = 0; ct < 8; ct++) {
+                const v4i aop = avr[ct / TPG];
+                v4i acc = {0, 0, 0, 0};
+                if (B == 4) {
+                    const uint4 w = vc[ct >> 1];
+                    const uint32_t w0_ = (ct & 1) ? w.z : w.x, w1_ = (ct & 1) ? w.w : w.y;
+                    const v4i bo = {(int)(w0_ & kM4), (int)((w0_ >> 4) & kM4), (int)(w1_ & kM4), (int)((w1_ >> 4) & kM4)};
+                    acc = mfma(aop, bo, acc);
+                } else if (B == 2) {
+                    const uint4 w = vc[ct >> 2];
+                    const uint32_t ww = (ct & 3) == 0 ? w.x : ((ct & 3) == 1 ? w.y : ((ct & 3) == 2 ? w.z : w.w));
+                    const v4i bo = {(int)(ww & kM2), (int)((ww >> 2) & kM2), (int)((ww >> 4) & kM2), (int)((ww >> 6) & kM2)};
+                    acc = mfma(aop, bo, acc);
+                } else {
+                    const uint4 w = vc[ct];
+                    const v4i lo = {(int)(w.x & kM4), (int)(w.y & kM4), (int)(w.z & kM4), (int)(w.w & kM4)};
+                    const v4i hi = {(int)((w.x >> 4) & kM4), (int)((w.y >> 4) & kM4), (int)((w.z >> 4) & kM4), (int)((w.w >> 4) & kM4)};
+                    v4i alo = {0, 0, 0, 0}, ahi = {0, 0, 0, 0};
+                    alo = mfma(aop, lo, alo);
+                    ahi = mfma(aop, hi, ahi);
+                    acc = alo + ahi * 16;
+                }
+                const float dotv = (float)acc.x + 256.0f * (float)acc.y + 65536.0f * (float)acc.z;
+                float o = st.O[ct] * alpha + dotv * o_scale;
+#pragma unroll
+                for (int bi = 0; bi < NBC; bi++)
+                    o += __half2float(__ushort_as_half(vmean[bi][ct])) * psum_b[bi];
+                st.O[ct] = o;
+            }
+        }
+
+        // ---- raw residual tokens (Sec. 3.3): wave 0 of the split that owns them
+        const bool has_resid = w1 > a.n_blocks && a.r > 0;
+        if (has_resid) {
+            __syncthreads(); // every wave is out of its main loop; wave 0 may take all of LDS
+            if (wave == 0) {
+                unsigned char *L = (unsigned char *)lds_all;
+                constexpr int RS = 264; // bytes per staged row (33 * 8)
+                unsigned char *kraw = L, *vraw = L + 32 * RS;
+                float *qs = (float *)(L + 64 * RS);       // [4][128]
+                float *spart = qs + 4 * 128;               // [2][4][32]
+                float *pl = spart + 2 * 4 * 32;            // [4][32]
+                // q of the unit (undo the fixed-point scaling: exact)
+#pragma unroll
+                for (int ph = 0; ph < 2; ph++) {
+                    qs[row * 128 + 32 * vq + 16 * ph + 4 * qa + 0] = (float)qh[ph][0].x;
+                    qs[row * 128 + 32 * vq + 16 * ph + 4 * qa + 1] = (float)qh[ph][0].y;
+                    qs[row * 128 + 32 * vq + 16 * ph + 4 * qa + 2] = (float)qh[ph][1].x;
+                    qs[row * 128 + 32 * vq + 16 * ph + 4 * qa + 3] = (float)qh[ph][1].y;
+                }
+                const unsigned char *kr = a.layer + gm.k_resid_off + (long long)u * gm.R * 256;
+                const unsigned char *vr = a.layer + gm.v_resid_off + (long long)u * gm.R * 256;
+                for (int t0 = 0; t0 < a.r; t0 += 32) {
+                    const int nt = a.r - t0 < 32 ? a.r - t0 : 32;
+                    wave_lds_fence();
+                    for (int i = lane; i < nt * 16; i += 64) {
+                        const int t = i >> 4, ch = i & 15;
+                        const uint4 kv_ = *(const uint4 *)(kr + (long long)(t0 + t) * 256 + ch * 16);
+                        const uint4 vv_ = *(const uint4 *)(vr + (long long)(t0 + t) * 256 + ch * 16);
+                        *(uint2 *)(kraw + t * RS + ch * 16) = uint2{kv_.x, kv_.y};
+                        *(uint2 *)(kraw + t * RS + ch * 16 + 8) = uint2{kv_.z, kv_.w};
+                        *(uint2 *)(vraw + t * RS + ch * 16) = uint2{vv_.x, vv_.y};
+                        *(uint2 *)(vraw + t * RS + ch * 16 + 8) = uint2{vv_.z, vv_.w};
+                    }
+                    wave_lds_fence();
+                    {
+                        const int t = lane & 31, half = lane >> 5;
+                        float d4[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+                        if (t < nt) {
+                            for (int c = half * 64; c < half * 64 + 64; c += 2) {
+                                const uint32_t w = *(const uint32_t *)(kraw + t * RS + c * 2);
+                                const float k0 = widen16((uint16_t)(w & 0xFFFFu), gm.dtype);
+                                const float k1 = widen16((uint16_t)(w >> 16), gm.dtype);
+#pragma unroll
+                                for (int i = 0; i < 4; i++) d4[i] += qs[i * 128 + c] * k0 + qs[i * 128 + c + 1] * k1;
+                            }
+#pragma unroll
+                            for (int i = 0; i < 4; i++) spart[(half * 4 + i) * 32 + t] = d4[i];
+                        }
+                    }
+                    wave_lds_fence();
+                    float s[4], p[4], alpha, wc;
+#pragma unroll
+                    for (int k = 0; k < 4; k++) {
+                        const int t = n + 16 * k;
+                        s[k] = (k < 2 && t < nt) ? (spart[row * 32 + t] + spart[(4 + row) * 32 + t]) * kScoreScale
+                                                 : -INFINITY;
+                    }
+                    softmax_chunk(s, st, p, alpha, wc);
+#pragma unroll
+                    for (int k = 0; k < 2; k++)
+                        if (n + 16 * k < nt) pl[row * 32 + n + 16 * k] = p[k];
+                    wave_lds_fence();
+                    float add[8];
+#pragma unroll
+                    for (int ct = 0; ct < 8; ct++) add[ct] = 0.0f;
+                    for (int t = 0; t < nt; t++) {
+                        const float pv = pl[row * 32 + t];
+#pragma unroll
+                        for (int ct = 0; ct < 8; ct++)
+                            add[ct] += pv * widen16(*(const uint16_t *)(vraw + t * RS + (16 * ct + n) * 2), gm.dtype);
+                    }
+#pragma unroll
+                    for (int ct = 0; ct < 8; ct++) st.O[ct] = st.O[ct] * alpha + wc * add[ct];
+#pragma unroll
+                    for (int gam = 0; gam < 4; gam++) st.Zp[gam] *= alpha;
+                }
+            }
+            __syncthreads();
+        }
+
+        // ---- finish the wave's state and merge the four waves
+        st.l = row_sum(st.l);
+#pragma unroll
+        for (int gam = 0; gam < NG; gam++) {
+            const float z = row_sum(st.Zp[gam]);
+#pragma unroll
+            for (int ct = gam * TPG; ct < (gam + 1) * TPG; ct++) st.O[ct] += z;
+        }
+        float *mine = (float *)lds; // this wave's 8 KiB: [10][64] floats
+        wave_lds_fence();
+        mine[0 * 64 + lane] = st.M;
+        mine[1 * 64 + lane] = st.l;
+#pragma unroll
+        for (int ct = 0; ct < 8; ct++) mine[(2 + ct) * 64 + lane] = st.O[ct];
+        __syncthreads();
+        if (wave == 0 && row < g) {
+            const float *all = (const float *)lds_all;
+            float Mw[4], M = -INFINITY;
+#pragma unroll
+            for (int w = 0; w < 4; w++) {
+                Mw[w] = all[w * WAVE_DW + lane];
+                M = fmaxf(M, Mw[w]);
+            }
+            float lsum = 0.0f, o[8];
+#pragma unroll
+            for (int ct = 0; ct < 8; ct++) o[ct] = 0.0f;
+#pragma unroll
+            for (int w = 0; w < 4; w++) {
+                const float wt = exp2f(Mw[w] - M); // a wave that saw no token has max -inf: weight 0
+                lsum += all[w * WAVE_DW + 64 + lane] * wt;
+#pragma unroll
+                for (int ct = 0; ct < 8; ct++) o[ct] += all[w * WAVE_DW + (2 + ct) * 64 + lane] * wt;
+            }
+            float *dst = a.ws + (((long long)u * a.n_splits + sp) * g + row) * kPartialStride;
+#pragma unroll
+            for (int ct = 0; ct < 8; ct++) dst[16 * ct + n] = o[ct];
+            if (n == 0) {
+                dst[kHeadDim] = M;
+                dst[kHeadDim + 1] = lsum;
+            }
+        }
+    }
+}
+
+template <int B, int G, int GC> hipError_t launch_one(const DecodeArgs &a, hipStream_t s)
+{
+    dim3 grid(a.n_splits, a.batch * a.n_kv_heads);
+    (void)hipGetLastError(); // drop any stale error left by earlier runtime calls of this thread
+    hipLaunchKernelGGL((decode_split_mfma_kernel<B, G, GC>), grid, dim3(kThreads), 0, s, a);
+    return note_launch(hipGetLastError());
+}
+
+} // namespace
+
+bool decode_mfma_supported(const DecodeArgs &a)
+{
+    const LayerGeom &g = a.geom;
+    if (g.k_bits != g.v_bits) return false;
+    if (!(g.k_bits == 2 || g.k_bits == 4 || g.k_bits == 8)) return false;
+    if (!((g.G == 32 && g.Gc == 32) || (g.G == 64 && g.Gc == 64))) return false;
+    if (a.g > 4) return false;
+    if (g.mean_mode == 1) return false; // cross-head mean: not on this path
+    if (a.batch * a.n_kv_heads > 65535) return false;
+    return true;
+}
+
+hipError_t launch_decode_split_mfma(const DecodeArgs &a, hipStream_t s)
+{
+    if (!decode_mfma_supported(a)) return hipErrorInvalidValue;
+    const int bits = a.geom.k_bits;
+    if (a.geom.G == 32) {
+        if (bits == 2) return launch_one<2, 32, 32>(a, s);
+        if (bits == 4) return launch_one<4, 32, 32>(a, s);
+        return launch_one<8, 32, 32>(a, s);
+    }
+    if (bits == 2) return launch_one<2, 64, 64>(a, s);
+    if (bits == 4) return launch_one<4, 64, 64>(a, s);
+    return launch_one<8, 64, 64>(a, s);
+}
+
+} // namespace tadakv

@@ -43,7 +43,7 @@ __device__ __forceinline__ float wave_sum(float v)
 template <int B> __device__ __forceinline__ int k_word(int t, int c0)
 {
     const int tt = t >> 4, n = t & 15, cg = c0 >> 4;
-    if (B == 8) return ((((tt * 2 + (cg >> 2)) * 4 + (cg & 3)) * 16 + n) << 2) + ((c0 & 15) >> 2);
+    if (B == 8) return ((((tt * 2 + (cg & 1)) * 4 + (cg >> 1)) * 16 + n) << 2) + ((c0 & 15) >> 2);
     if (B == 4) return (((tt * 4 + (cg >> 1)) * 16 + n) << 2) + (cg & 1) * 2 + ((c0 & 15) >> 3);
     if (B == 2) return ((((tt >> 1) * 4 + (cg >> 1)) * 16 + n) << 2) + (tt & 1) * 2 + (cg & 1);
     return t * 64 + (c0 >> 1); // raw 16-bit rows
@@ -122,7 +122,8 @@ __device__ __forceinline__ void process_block(const DecodeArgs &a, const Smem &s
             } else {
 #pragma unroll
                 for (int e = 0; e < per; e++)
-                    s += qrow[c0 + e] * (float)((w >> ((KB & 15) * e)) & ((1u << (KB & 15)) - 1u));
+                    s += qrow[c0 + e] *
+                         (float)((w >> (8 * (e & 3) + (KB & 15) * (e >> 2))) & ((1u << (KB & 15)) - 1u));
             }
         }
         sm.part[(half * g + i) * G + t] = s;
@@ -201,7 +202,8 @@ __device__ __forceinline__ void process_block(const DecodeArgs &a, const Smem &s
                 const uint32_t w = sm.vc[v_word<VB == 16 ? 8 : VB>(t0, c, nt)];
 #pragma unroll
                 for (int e = 0; e < per; e++) {
-                    const float code = (float)((w >> ((VB & 15) * e)) & ((1u << (VB & 15)) - 1u));
+                    const float code =
+                        (float)((w >> (8 * (e & 3) + (VB & 15) * (e >> 2))) & ((1u << (VB & 15)) - 1u));
 #pragma unroll
                     for (int k = 0; k < kMaxGroupQ / 2; k++) {
                         const int i = hsel + 2 * k;
@@ -369,9 +371,5 @@ hipError_t launch_decode_merge(const DecodeArgs &a, hipStream_t s)
     hipLaunchKernelGGL(merge_kernel, grid, dim3(128), 0, s, a);
     return note_launch(hipGetLastError());
 }
-
-// matrix-core path: not built yet
-bool decode_mfma_supported(const DecodeArgs &) { return false; }
-hipError_t launch_decode_split_mfma(const DecodeArgs &, hipStream_t) { return hipErrorNotSupported; }
 
 } // namespace tadakv

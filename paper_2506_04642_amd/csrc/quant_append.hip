@@ -99,9 +99,9 @@ __device__ __forceinline__ void word_origin(int which, int bits, int G, int w, i
     const int n = piece & 15;
     if (which == 0) {
         if (bits == 8) {
-            const int j = (piece >> 4) & 3, hh = (piece >> 6) & 1, tt = piece >> 7;
+            const int j = (piece >> 4) & 3, par = (piece >> 6) & 1, tt = piece >> 7;
             t0 = tt * 16 + n;
-            c0 = (hh * 4 + j) * 16 + wi * 4;
+            c0 = (j * 2 + par) * 16 + wi * 4;
         } else if (bits == 4) {
             const int j = (piece >> 4) & 3, tt = piece >> 6;
             t0 = tt * 16 + n;
@@ -224,7 +224,9 @@ __global__ __launch_bounds__(kThreads) void flush_block_kernel(AppendArgs a)
         __syncthreads();
     }
 
-    // pack: one 32-bit word = 32/bits consecutive codes along channels (keys) or tokens (values)
+    // pack: one 32-bit word = 32/bits consecutive codes along channels (keys) or tokens (values),
+    // byte-interleaved: the word's code number 4f + y is field f (bits [bits*f, bits*f+bits)) of
+    // byte y, so that one shift and one mask turn a word into four consecutive codes as bytes
     const int n_words = G * kHeadDim * bits / 32;
     const int per = 32 / bits;
     for (int w = tid; w < n_words; w += kThreads) {
@@ -232,9 +234,11 @@ __global__ __launch_bounds__(kThreads) void flush_block_kernel(AppendArgs a)
         word_origin(which, bits, G, w, t0, c0);
         uint32_t word = 0;
         if (which == 0) {
-            for (int e = 0; e < per; e++) word |= (uint32_t)cb[t0 * kHeadDim + c0 + e] << (bits * e);
+            for (int e = 0; e < per; e++)
+                word |= (uint32_t)cb[t0 * kHeadDim + c0 + e] << (8 * (e & 3) + bits * (e >> 2));
         } else {
-            for (int e = 0; e < per; e++) word |= (uint32_t)cb[(t0 + e) * kHeadDim + c0] << (bits * e);
+            for (int e = 0; e < per; e++)
+                word |= (uint32_t)cb[(t0 + e) * kHeadDim + c0] << (8 * (e & 3) + bits * (e >> 2));
         }
         ((uint32_t *)codes_out)[w] = word;
     }

@@ -5,6 +5,7 @@ import numpy as np
 from paper_2506_04642_amd import synth
 
 ATTN_TOL = 2e-3  # max-abs error of the attention output against the binary64 oracle
+DECODE_PATH = 0  # 0 automatic, 1 vector-ALU kernels, 2 matrix-core kernels (set by the tests)
 
 
 def to_dev(bits16: np.ndarray, dtype: int, device="cuda:0"):
@@ -20,7 +21,9 @@ def make_pair(kv, oracle, *, L=1, B=1, Hq=1, Hkv=1, T_max=1024, G=32, Gc=32, R=N
     R = G if R is None else R
     cfg = kv.make_config(L, B, Hq, Hkv, 128, T_max, G, Gc, R, dtype, mode, list(k_bits), list(v_bits))
     ocfg = oracle.OracleConfig(L, B, Hq, Hkv, 128, T_max, G, Gc, R, dtype, mode, list(k_bits), list(v_bits))
-    return kv.KVCache(cfg, zero=zero), oracle.OracleCache(ocfg)
+    gpu = kv.KVCache(cfg, zero=zero)
+    kv.kv_set_decode_path(gpu.handle, DECODE_PATH)
+    return gpu, oracle.OracleCache(ocfg)
 
 
 def append_both(gpu, orc, layer, k_bits16, v_bits16, dtype, chunks=None):

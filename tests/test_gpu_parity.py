@@ -4,6 +4,7 @@ import numpy as np
 import pytest
 
 from paper_2506_04642_amd import synth
+import parity_util
 from parity_util import append_both, check_attention, check_bytes, make_pair, to_dev
 
 pytestmark = pytest.mark.gpu
@@ -20,6 +21,15 @@ def kv():
     from paper_2506_04642_amd import binding
 
     return binding
+
+
+@pytest.fixture(autouse=True, params=[1, 0], ids=["valu", "auto"])
+def decode_path(request):
+    """Every case runs on the vector-ALU kernels and on the automatic choice (matrix-core kernels
+    wherever they support the configuration)."""
+    parity_util.DECODE_PATH = request.param
+    yield request.param
+    parity_util.DECODE_PATH = 0
 
 
 # ------------------------------------------------------------------ config 0: one head, fp16

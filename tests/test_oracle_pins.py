@@ -435,18 +435,19 @@ def test_pack_positions_follow_the_documented_tiling(oracle):
         byte = int(np.flatnonzero(p)[0])
         return byte, int(np.log2(p[byte]))
 
-    # keys, 8-bit: token 17 (tile 1, line 1), channel 70 (group 4 -> half 1, quarter 0, slot 6)
-    assert where(K, 8, 17, 70) == ((((1 * 2 + 1) * 4 + 0) * 16 + 1) * 16 + 6, 0)
-    # keys, 4-bit: token 5, channel 53 (group 3 -> quarter 1, sub 1, slot 5)
-    assert where(K, 4, 5, 53) == (((0 * 4 + 1) * 16 + 5) * 16 + 8 + 2, 4)
-    # keys, 2-bit: token 21 (tile 1 -> pair 0, second), channel 127 (group 7 -> quarter 3, sub 1, slot 15)
-    assert where(K, 2, 21, 127) == (((0 * 4 + 3) * 16 + 5) * 16 + 8 + 4 + 3, 6)
+    # Inside a word, slot 4f + y is field f of byte y (byte-interleaved).
+    # keys, 8-bit: token 17 (tile 1, line 1), channel 70 (tile 4 -> parity 0, j 2; slot 6 -> word 1, byte 2)
+    assert where(K, 8, 17, 70) == ((((1 * 2 + 0) * 4 + 2) * 16 + 1) * 16 + 4 + 2, 0)
+    # keys, 4-bit: token 5, channel 53 (tile 3 -> j 1, second tile; slot 5 -> word 0, field 1 of byte 1)
+    assert where(K, 4, 5, 53) == (((0 * 4 + 1) * 16 + 5) * 16 + 8 + 1, 4)
+    # keys, 2-bit: token 21 (tile 1 -> pair 0, second), channel 127 (tile 7 -> j 3, second; slot 15 -> field 3 of byte 3)
+    assert where(K, 2, 21, 127) == (((0 * 4 + 3) * 16 + 5) * 16 + (1 * 2 + 1) * 4 + 3, 6)
     # values, 8-bit: channel 33 (tile 2, line 1), token 18 (tile 1, slot 2)
     assert where(V, 8, 18, 33) == (((2 * 2 + 1) * 16 + 1) * 16 + 2, 0)
-    # values, 4-bit: channel 50 (tile 3 -> pair 1, sub 1, line 2), token 7
+    # values, 4-bit: channel 50 (tile 3 -> pair 1, second; line 2), token 7 (slot 7 -> field 1 of byte 3)
     assert where(V, 4, 7, 50) == (((1 * 2 + 0) * 16 + 2) * 16 + 8 + 3, 4)
-    # values, 2-bit: channel 100 (tile 6 -> quad 1, sub 2, line 4), token 30 (tile 1, slot 14)
-    assert where(V, 2, 30, 100) == (((1 * 2 + 1) * 16 + 4) * 16 + 8 + 3, 4)
+    # values, 2-bit: channel 100 (tile 6 -> quad 1, third; line 4), token 30 (tile 1, slot 14 -> field 3 of byte 2)
+    assert where(V, 2, 30, 100) == (((1 * 2 + 1) * 16 + 4) * 16 + 2 * 4 + 2, 6)
 
 
 def test_layer_image_places_records_where_the_format_says(oracle):
