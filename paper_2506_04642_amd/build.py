@@ -17,7 +17,8 @@ UNITS = [
     ("tadakv_abi.cpp", ["-x", "hip"]),
     ("quant_append.hip", ["-ffp-contract=off"]),
     ("decode_valu.hip", []),
-    ("decode_mfma.hip", []),
+    # matrix-instruction results go straight to ordinary vector registers
+    ("decode_mfma.hip", ["-mllvm", "-amdgpu-mfma-vgpr-form"]),
 ]
 
 

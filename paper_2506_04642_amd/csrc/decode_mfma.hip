@@ -63,6 +63,22 @@ __device__ __forceinline__ float row_max(float x)
     return x;
 }
 
+__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b)
+{
+    typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+    const us2 x = __builtin_bit_cast(us2, a), y = __builtin_bit_cast(us2, b);
+    const us2 m = __builtin_elementwise_max(x, y);
+    return __builtin_bit_cast(uint32_t, m);
+}
+__device__ __forceinline__ uint32_t row_pk_max_u16(uint32_t x)
+{
+    x = pk_max_u16(x, dpp_u<0xB1>(x));
+    x = pk_max_u16(x, dpp_u<0x4E>(x));
+    x = pk_max_u16(x, dpp_u<0x141>(x));
+    x = pk_max_u16(x, dpp_u<0x140>(x));
+    return x;
+}
+
 __device__ __forceinline__ float widen16(uint16_t v, int dtype)
 {
     if (dtype == 1) return __uint_as_float((uint32_t)v << 16);
@@ -80,8 +96,6 @@ __device__ __forceinline__ void pow2_above(float x, float floor_v, float &p, flo
     inv = __uint_as_float(0x7F000000u - b);
 }
 
-// signed-byte limbs of a 32-bit integer: bytes l0..l3 with n = sum l_k 256^k, l_k in [-128,127]
-__device__ __forceinline__ uint32_t limbs(int n) { return ((uint32_t)n + 0x80808080u) ^ 0x80808080u; }
 
 // waits for this wave's outstanding LDS traffic and keeps the compiler from moving LDS accesses
 // across; enough to hand data between lanes of one wave through LDS
@@ -116,7 +130,7 @@ __device__ __forceinline__ void softmax_chunk(const float (&s)[4], State &st, fl
     st.l = st.l * alpha + wc * ((p[0] + p[1]) + (p[2] + p[3]));
 }
 
-template <int B, int G, int GC>
+template <int B, int G, int GC, bool MEAN>
 __global__ __launch_bounds__(kThreads) void decode_split_mfma_kernel(DecodeArgs a)
 {
     constexpr int NBC = 64 / G;            // blocks per 64-token chunk
@@ -133,7 +147,8 @@ __global__ __launch_bounds__(kThreads) void decode_split_mfma_kernel(DecodeArgs 
     __shared__ __attribute__((aligned(16))) uint32_t lds_all[4 * WAVE_DW];
 
     const LayerGeom &gm = a.geom;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6); // wave-uniform: lets addresses live in scalars
     const int row = lane >> 4, n = lane & 15, qa = lane & 3, vq = (lane >> 2) & 3;
     uint32_t *lds = lds_all + wave * WAVE_DW;
     uint32_t *ak = lds, *av = lds + AK_DW;
@@ -141,15 +156,16 @@ __global__ __launch_bounds__(kThreads) void decode_split_mfma_kernel(DecodeArgs 
     const int sp = blockIdx.x, u = blockIdx.y;
     const int b = u / a.n_kv_heads, h = u % a.n_kv_heads;
     const int g = a.g;
-    const bool has_kmean = gm.k_mean >= 0, has_vmean = gm.v_mean >= 0;
+    constexpr bool has_kmean = MEAN, has_vmean = MEAN; // per-channel block means present
 
     // rows 4i+3 of the operands (the unused fourth limb) must read as zero
     for (int i = lane; i < WAVE_DW; i += 64) lds[i] = 0u;
 
     // ---- query of head `row`: this lane's eight channels, as fixed-point factors and as halves
-    float qf[2][4];      // 2^22 q / qb  (qb = power of two above max |q| of the head): exact
-    half2_t qh[2][2];    // q as binary16 pairs for the zero / mean dot products
-    float inv_kf_base;   // qb 2^-22 log2(e)/sqrt(d): undoes the fixed point, up to the scale bound
+    float qf[2][4];      // q of this lane's eight channels, widened (exact)
+    half2_t qh[2][2];    // the same as binary16 pairs for the zero / mean dot products
+    float three_qb;      // 3 qb, qb = power of two above max |q| of the head
+    float inv_kf_base;   // qb 2^-22 log2(e)/sqrt(d): one fixed-point step, up to the scale bound
     {
         const uint16_t *qp = a.q + ((long long)b * a.n_q_heads + h * g + (row < g ? row : 0)) * kHeadDim;
         float qmax = 0.0f;
@@ -164,13 +180,12 @@ __global__ __launch_bounds__(kThreads) void decode_split_mfma_kernel(DecodeArgs 
         qmax = row_max(qmax);
         float qb, inv_qb;
         pow2_above(qmax, 0x1p-60f, qb, inv_qb);
+        three_qb = 3.0f * qb;
         inv_kf_base = qb * 0x1p-22f * kScoreScale;
 #pragma unroll
         for (int ph = 0; ph < 2; ph++) {
             qh[ph][0] = half2_t{(_Float16)qf[ph][0], (_Float16)qf[ph][1]};
             qh[ph][1] = half2_t{(_Float16)qf[ph][2], (_Float16)qf[ph][3]};
-#pragma unroll
-            for (int y = 0; y < 4; y++) qf[ph][y] *= inv_qb * 0x1p22f;
         }
     }
     {
@@ -257,24 +272,29 @@ __global__ __launch_bounds__(kThreads) void decode_split_mfma_kernel(DecodeArgs 
             float inv_kf[NBC], beta[NBC];
 #pragma unroll
             for (int bi = 0; bi < NBC; bi++) {
-                float sf[2][4];
-#pragma unroll
-                for (int ph = 0; ph < 2; ph++) {
-                    sf[ph][0] = h_lo(ks[bi][ph].x); sf[ph][1] = h_hi(ks[bi][ph].x);
-                    sf[ph][2] = h_lo(ks[bi][ph].y); sf[ph][3] = h_hi(ks[bi][ph].y);
-                }
-                float smax = fmaxf(fmaxf(fmaxf(sf[0][0], sf[0][1]), fmaxf(sf[0][2], sf[0][3])),
-                                   fmaxf(fmaxf(sf[1][0], sf[1][1]), fmaxf(sf[1][2], sf[1][3])));
-                smax = row_max(smax);
+                // scales are non-negative binary16 values: their bit patterns order like the values,
+                // so the largest is found with packed 16-bit integer maxima on the raw words
+                uint32_t smw = pk_max_u16(pk_max_u16(ks[bi][0].x, ks[bi][0].y), pk_max_u16(ks[bi][1].x, ks[bi][1].y));
+                smw = row_pk_max_u16(smw);
+                const float smax = fmaxf(h_lo(smw), h_hi(smw));
                 float sb, inv_sb;
                 pow2_above(smax, 0x1p-40f, sb, inv_sb);
                 inv_kf[bi] = inv_kf_base * sb;
+                // Adding 3 qb sb (1.5 * 2^E with 2^E = 2 qb sb > 2 |q s|) puts round(q s / ulp) into
+                // the low mantissa bits of the sum, ulp = qb sb 2^-22: one fused multiply-add per
+                // element does the scaling, the rounding and the float -> integer conversion.
+                const float magic = three_qb * sb;
+                const uint32_t cfix = 0x80808080u - __float_as_uint(magic);
                 float bacc = 0.0f;
 #pragma unroll
                 for (int ph = 0; ph < 2; ph++) {
                     uint32_t X[4];
 #pragma unroll
-                    for (int y = 0; y < 4; y++) X[y] = limbs(__float2int_rn(qf[ph][y] * (sf[ph][y] * inv_sb)));
+                    for (int y = 0; y < 4; y++) {
+                        const uint32_t sw = (y & 2) ? ks[bi][ph].y : ks[bi][ph].x;
+                        const float sv = (y & 1) ? h_hi(sw) : h_lo(sw);
+                        X[y] = (__float_as_uint(__builtin_fmaf(qf[ph][y], sv, magic)) + cfix) ^ 0x80808080u;
+                    }
                     const uint32_t U = __builtin_amdgcn_perm(X[1], X[0], 0x05010400u);
                     const uint32_t U2 = __builtin_amdgcn_perm(X[1], X[0], 0x07030602u);
                     const uint32_t W = __builtin_amdgcn_perm(X[3], X[2], 0x05010400u);
@@ -338,19 +358,16 @@ __global__ __launch_bounds__(kThreads) void decode_split_mfma_kernel(DecodeArgs 
             softmax_chunk(s, st, p, alpha, wc);
 
             // ---- value side: p*scale as limbs -> LDS; zero term
-            float vs[4][NG];
-            float svmax = 0.0f;
+            uint32_t svw = 0u; // low halves: largest value scale of the chunk (high halves: unused)
 #pragma unroll
             for (int k = 0; k < 4; k++)
 #pragma unroll
-                for (int gam = 0; gam < NG; gam++) {
-                    vs[k][gam] = h_lo(vm[k][gam]);
-                    svmax = fmaxf(svmax, vs[k][gam]);
-                }
-            svmax = row_max(svmax);
+                for (int gam = 0; gam < NG; gam++) svw = pk_max_u16(svw, vm[k][gam]);
+            svw = row_pk_max_u16(svw);
             float sbv, inv_sbv;
-            pow2_above(svmax, 0x1p-40f, sbv, inv_sbv);
-            const float vf = inv_sbv * 0x1p22f;
+            pow2_above(h_lo(svw), 0x1p-40f, sbv, inv_sbv);
+            const float vmagic = 3.0f * sbv; // p <= 1, scale < sbv: same construction as on the key side
+            const uint32_t vfix = 0x80808080u - __float_as_uint(vmagic);
             const float o_scale = wc * sbv * 0x1p-22f;
 #pragma unroll
             for (int gam = 0; gam < NG; gam++) {
@@ -358,7 +375,7 @@ __global__ __launch_bounds__(kThreads) void decode_split_mfma_kernel(DecodeArgs 
 #pragma unroll
                 for (int k = 0; k < 4; k++) {
                     zsum += p[k] * h_hi(vm[k][gam]);
-                    const uint32_t X = limbs(__float2int_rn(p[k] * (vs[k][gam] * vf)));
+                    const uint32_t X = (__float_as_uint(__builtin_fmaf(p[k], h_lo(vm[k][gam]), vmagic)) + vfix) ^ 0x80808080u;
                     // byte transpose across the quad: lane with quad position L ends up with limb L
                     // of the quad's four consecutive tokens
                     const uint32_t P = dpp_u<0xB1>(X);
@@ -539,12 +556,17 @@ __global__ __launch_bounds__(kThreads) void decode_split_mfma_kernel(DecodeArgs 
     }
 }
 
-template <int B, int G, int GC> hipError_t launch_one(const DecodeArgs &a, hipStream_t s)
+template <int B, int G, int GC, bool MEAN> hipError_t launch_mean(const DecodeArgs &a, hipStream_t s)
 {
     dim3 grid(a.n_splits, a.batch * a.n_kv_heads);
     (void)hipGetLastError(); // drop any stale error left by earlier runtime calls of this thread
-    hipLaunchKernelGGL((decode_split_mfma_kernel<B, G, GC>), grid, dim3(kThreads), 0, s, a);
+    hipLaunchKernelGGL((decode_split_mfma_kernel<B, G, GC, MEAN>), grid, dim3(kThreads), 0, s, a);
     return note_launch(hipGetLastError());
+}
+
+template <int B, int G, int GC> hipError_t launch_one(const DecodeArgs &a, hipStream_t s)
+{
+    return a.geom.mean_mode == 0 ? launch_mean<B, G, GC, true>(a, s) : launch_mean<B, G, GC, false>(a, s);
 }
 
 } // namespace
