@@ -34,6 +34,7 @@ def parse():
     ap.add_argument("--batch", type=int, default=16)
     ap.add_argument("--layers", type=int, default=32)
     ap.add_argument("--path", type=int, default=0, help="0 auto, 1 vector-ALU kernels, 2 matrix-core kernels")
+    ap.add_argument("--splits", type=int, default=0, help="force the sequence split count (0 = automatic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     return ap.parse_args()
 
@@ -64,6 +65,10 @@ def main():
     cfg = kv.make_config(L, B, Hq, Hkv, d, max_tokens, G, G, G, kv.KV_BF16, kv.KV_MEAN_CHANNEL_BLOCK, bits, bits)
     cache = kv.KVCache(cfg, device=dev, zero=False)
     kv.kv_set_decode_path(cache.handle, args.path)
+    if args.splits:
+        kv.kv_set_decode_splits(cache.handle, args.splits)
+        cache.ws_bytes = max(cache.ws_bytes, B * Hq * args.splits * 132 * 4)
+        cache.workspace = torch.empty(cache.ws_bytes, dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream(dev)
 
     # ---- fill: bulk quantise-append in chunks, inputs drawn on the device

@@ -12,11 +12,17 @@
 // why the storage format interleaves fields bytewise.  Products and sums are exact in int32; the
 // only rounding is the fixed-point conversion (relative 2^-23 of the chunk's largest weight).
 //
-// Work split: one workgroup (4 waves) per (sequence, kv head, split).  Each wave owns every
-// fourth 64-token chunk of the split and keeps its own online-softmax state; the four states are
+// Work split: one workgroup (NW waves) per (sequence, kv head, split).  Each wave owns every
+// NW-th 64-token chunk of the split and keeps its own online-softmax state; the states are
 // merged through LDS at the end and one partial (max, sum, output) per query head is written for
 // the cross-split merge kernel.  Waves never synchronise inside the main loop: every LDS buffer
 // in the loop is private to a wave.
+//
+// Memory pipeline: the records of a chunk are contiguous in the cache, so a chunk is fetched as
+// one linear run of 16-byte pieces straight into the wave's LDS staging buffer
+// (global_load_lds_dwordx4, no vector registers involved).  A wave copies the staged chunk into
+// registers, immediately issues the fetch of its next chunk into the same buffer, and only then
+// computes, so the HBM latency of chunk i+1 is covered by the arithmetic of chunk i.
 //
 // Lane roles inside a wave (lane = 16*row + n, quad position a = n & 3, quad index vq = n >> 2):
 //   matrix output      lane (row, n): query head `row`, limbs in the four accumulator registers;
@@ -33,7 +39,7 @@ namespace {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 
-constexpr int kThreads = 256;
+constexpr int kWavesPerBlock = 4;
 constexpr float kScoreScale = 0.08838834764831845f * 1.4426950408889634f; // log2(e) / sqrt(128)
 constexpr uint32_t kM4 = 0x0F0F0F0Fu, kM2 = 0x03030303u;
 
@@ -130,28 +136,77 @@ __device__ __forceinline__ void softmax_chunk(const float (&s)[4], State &st, fl
     st.l = st.l * alpha + wc * ((p[0] + p[1]) + (p[2] + p[3]));
 }
 
-template <int B, int G, int GC, bool MEAN>
-__global__ __launch_bounds__(kThreads) void decode_split_mfma_kernel(DecodeArgs a)
+// Record layout for one template instance; must agree with the layer geometry built on the host.
+template <int B, int G, int GC, bool MEAN> struct RecLayout {
+    static constexpr int KC = G * kHeadDim * B / 8;          // bytes of key (and of value) codes
+    static constexpr int K_CODES = 0;
+    static constexpr int K_SCALE = KC;
+    static constexpr int K_ZERO = KC + 256;
+    static constexpr int K_MEAN = KC + 512;
+    static constexpr int V_CODES = KC + 512 + (MEAN ? 256 : 0);
+    static constexpr int V_META = V_CODES + KC;
+    static constexpr int V_MEAN = V_META + G * (kHeadDim / GC) * 4;
+    static constexpr int REC = (V_MEAN + (MEAN ? 256 : 0) + 255) / 256 * 256;
+    static bool matches(const LayerGeom &g)
+    {
+        return g.rec_bytes == REC && g.k_codes == K_CODES && g.k_scale == K_SCALE && g.k_zero == K_ZERO &&
+               (!MEAN || g.k_mean == K_MEAN) && g.v_codes == V_CODES && g.v_meta == V_META &&
+               (!MEAN || g.v_mean == V_MEAN);
+    }
+};
+
+// Fetch NBYTES (multiple of 16) from src to the LDS address dst; both wave-uniform.  Lane l moves
+// the 16-byte pieces l, l + 64, ...; completion is tracked by the vector-memory counter.
+template <int NBYTES>
+__device__ __forceinline__ void stage_issue(const unsigned char *src, uint32_t *dst, int lane)
 {
+    typedef const __attribute__((address_space(1))) void *gptr_t;
+    typedef __attribute__((address_space(3))) void *lptr_t;
+#pragma unroll
+    for (int base = 0; base < NBYTES; base += 4096) {
+        gptr_t gp = (gptr_t)(src + base + lane * 16);
+        lptr_t lp = (lptr_t)(dst + base / 4);
+        // the immediate offset applies to the global and to the LDS address alike
+        if (base + 0 * 1024 + 1024 <= NBYTES) __builtin_amdgcn_global_load_lds(gp, lp, 16, 0, 0);
+        else if (base + 0 * 1024 < NBYTES && base + lane * 16 < NBYTES) __builtin_amdgcn_global_load_lds(gp, lp, 16, 0, 0);
+        if (base + 1 * 1024 + 1024 <= NBYTES) __builtin_amdgcn_global_load_lds(gp, lp, 16, 1024, 0);
+        else if (base + 1 * 1024 < NBYTES && base + 1024 + lane * 16 < NBYTES) __builtin_amdgcn_global_load_lds(gp, lp, 16, 1024, 0);
+        if (base + 2 * 1024 + 1024 <= NBYTES) __builtin_amdgcn_global_load_lds(gp, lp, 16, 2048, 0);
+        else if (base + 2 * 1024 < NBYTES && base + 2048 + lane * 16 < NBYTES) __builtin_amdgcn_global_load_lds(gp, lp, 16, 2048, 0);
+        if (base + 3 * 1024 + 1024 <= NBYTES) __builtin_amdgcn_global_load_lds(gp, lp, 16, 3072, 0);
+        else if (base + 3 * 1024 < NBYTES && base + 3072 + lane * 16 < NBYTES) __builtin_amdgcn_global_load_lds(gp, lp, 16, 3072, 0);
+    }
+}
+__device__ __forceinline__ void stage_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+template <int B, int G, int GC, bool MEAN, int NW>
+__global__ __launch_bounds__(64 * NW) void decode_split_mfma_kernel(DecodeArgs a)
+{
+    typedef RecLayout<B, G, GC, MEAN> RL;
     constexpr int NBC = 64 / G;            // blocks per 64-token chunk
     constexpr int TPB = G / 16;            // 16-token tiles per block
     constexpr int NG = kHeadDim / GC;      // value scale groups
     constexpr int TPG = GC / 16;           // channel tiles per value scale group
-    constexpr int NKL = (B == 4) ? 4 : (B == 2 ? 2 : 8); // key code loads per chunk
-    constexpr int NVL = (B == 4) ? 4 : (B == 2 ? 2 : 8); // value code loads per chunk
-    constexpr int AK_DW = NBC * 2 * 256;   // dwords of key operands per wave
-    constexpr int AV_DW = NG * 256;        // dwords of value operands per wave
-    constexpr int WAVE_DW = 2048;          // 8 KiB of LDS per wave
-    static_assert(AK_DW + AV_DW <= WAVE_DW, "LDS layout");
+    constexpr int NKL = (B == 4) ? 4 : (B == 2 ? 2 : 8); // key code pieces per lane and chunk
+    constexpr int NVL = (B == 4) ? 4 : (B == 2 ? 2 : 8); // value code pieces per lane and chunk
+    constexpr int REC = RL::REC;
+    constexpr int CB = NBC * REC;          // bytes of one chunk
+    constexpr int STAGE_DW = CB / 4;       // staging buffer of a wave
+    constexpr int OPER_DW = 1024;          // 4 KiB: key operands, later reused for value operands
+    static_assert(NBC * 2 * 256 <= OPER_DW && NG * 256 <= OPER_DW, "operand scratch");
+    constexpr int WAVE_DW = STAGE_DW + OPER_DW;
+    constexpr int RESID_DW = 20480 / 4;    // the residual pass of wave 0 takes this much of the block's LDS
+    constexpr int LDS_DW = NW * WAVE_DW > RESID_DW ? NW * WAVE_DW : RESID_DW;
 
-    __shared__ __attribute__((aligned(16))) uint32_t lds_all[4 * WAVE_DW];
+    __shared__ __attribute__((aligned(16))) uint32_t lds_all[LDS_DW];
 
     const LayerGeom &gm = a.geom;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6); // wave-uniform: lets addresses live in scalars
     const int row = lane >> 4, n = lane & 15, qa = lane & 3, vq = (lane >> 2) & 3;
     uint32_t *lds = lds_all + wave * WAVE_DW;
-    uint32_t *ak = lds, *av = lds + AK_DW;
+    uint32_t *stage = lds;                 // the chunk as it lies in the cache
+    uint32_t *ak = lds + STAGE_DW, *av = ak;
 
     const int sp = blockIdx.x, u = blockIdx.y;
     const int b = u / a.n_kv_heads, h = u % a.n_kv_heads;
@@ -159,7 +214,35 @@ __global__ __launch_bounds__(kThreads) void decode_split_mfma_kernel(DecodeArgs 
     constexpr bool has_kmean = MEAN, has_vmean = MEAN; // per-channel block means present
 
     // rows 4i+3 of the operands (the unused fourth limb) must read as zero
-    for (int i = lane; i < WAVE_DW; i += 64) lds[i] = 0u;
+    for (int i = lane; i < OPER_DW; i += 64) ak[i] = 0u;
+
+    // ---- chunks of this split: the splits of a unit interleave chunk by chunk (split sp, wave w
+    // takes chunks sp + n_splits * (w + NW * k)), so that together they sweep the unit's records
+    // front to back as one moving window instead of as n_splits far-apart streams
+    const int b_end = a.n_blocks;
+    const int chunks_total = (a.n_blocks + NBC - 1) / NBC;
+    const int ns = a.n_splits;
+    // local chunk j of this split is the unit's chunk sp + ns * j
+    const int n_chunks = sp < chunks_total ? (chunks_total - sp + ns - 1) / ns : 0;
+    const int w0 = sp * NBC;          // first block of local chunk 0
+    const int cstride = ns * NBC;     // blocks between consecutive local chunks
+    const unsigned char *unit_base = a.layer + (long long)u * gm.NB * gm.rec_bytes;
+
+    auto issue = [&](int ci) {
+        const int blk0 = w0 + ci * cstride;
+        const unsigned char *src = unit_base + (long long)blk0 * REC;
+        if (NBC == 1 || blk0 + 1 < b_end) {
+            stage_issue<CB>(src, stage, lane);
+        } else {
+            // the chunk's second block does not exist: stage the first one twice so that the
+            // (masked) arithmetic on the second half still sees finite numbers
+            stage_issue<REC>(src, stage, lane);
+            stage_issue<REC>(src, stage + (NBC - 1) * (REC / 4), lane);
+        }
+    };
+    if (wave < n_chunks) issue(wave);
+
+
 
     // ---- query of head `row`: this lane's eight channels, as fixed-point factors and as halves
     float qf[2][4];      // q of this lane's eight channels, widened (exact)
@@ -199,34 +282,21 @@ __global__ __launch_bounds__(kThreads) void decode_split_mfma_kernel(DecodeArgs 
 
         wave_lds_fence();
 
-        // ---- range of this split
-        const int work = a.n_blocks + (a.r > 0 ? 1 : 0);
-        const int w0 = sp * a.blocks_per_split;
-        int w1 = w0 + a.blocks_per_split;
-        if (w1 > work) w1 = work;
-        const int b_end = w1 < a.n_blocks ? w1 : a.n_blocks;
-        const int n_chunks = (b_end - w0 + NBC - 1) / NBC;
-        const unsigned char *unit_base = a.layer + (long long)u * gm.NB * gm.rec_bytes;
-
         const uint32_t sel1 = (qa & 1) ? 0x03070105u : 0x06020400u;
         const uint32_t sel2 = (qa & 2) ? 0x03020706u : 0x05040100u;
 
-        for (int ci = wave; ci < n_chunks; ci += 4) {
-            const int blk0 = w0 + ci * NBC;
-            // records of the chunk's blocks (an absent second block re-reads the first; its
-            // tokens are masked below)
-            const unsigned char *rec[NBC];
+        for (int ci = wave; ci < n_chunks; ci += NW) {
+            const int blk0 = w0 + ci * cstride;
             bool blk_ok[NBC];
 #pragma unroll
-            for (int bi = 0; bi < NBC; bi++) {
-                blk_ok[bi] = blk0 + bi < b_end;
-                rec[bi] = unit_base + (long long)(blk_ok[bi] ? blk0 + bi : blk0) * gm.rec_bytes;
-            }
+            for (int bi = 0; bi < NBC; bi++) blk_ok[bi] = blk0 + bi < b_end;
             // block and tile-in-block of chunk tile `row` (this lane's token group on the value side)
-            const unsigned char *rec_row = rec[row / TPB];
+            const unsigned char *sb8 = (const unsigned char *)stage;
+            const unsigned char *rec_row = sb8 + (row / TPB) * REC;
             const int tt_row = row % TPB;
 
-            // ---- loads
+            // ---- staged chunk -> registers
+            stage_wait();
             uint4 kc[NKL], vc[NVL];
 #pragma unroll
             for (int i = 0; i < NKL; i++) {
@@ -234,15 +304,15 @@ __global__ __launch_bounds__(kThreads) void decode_split_mfma_kernel(DecodeArgs 
                 if (B == 4) { bi = i / TPB; off = (i % TPB) * 64; }
                 else if (B == 2) { bi = (2 * i) / TPB; off = (((2 * i) % TPB) / 2) * 64; }
                 else { bi = (i / 2) / TPB; off = (((i / 2) % TPB) * 2 + (i & 1)) * 64; }
-                kc[i] = *(const uint4 *)(rec[bi] + gm.k_codes + (off + lane) * 16);
+                kc[i] = *(const uint4 *)(sb8 + bi * REC + RL::K_CODES + (off + lane) * 16);
             }
 #pragma unroll
             for (int i = 0; i < NVL; i++)
-                vc[i] = *(const uint4 *)(rec_row + gm.v_codes + ((i * TPB + tt_row) * 16 + n) * 16);
+                vc[i] = *(const uint4 *)(rec_row + RL::V_CODES + ((i * TPB + tt_row) * 16 + n) * 16);
             uint32_t vm[4][NG];
 #pragma unroll
             for (int k = 0; k < 4; k++) {
-                const unsigned char *p = rec[k / TPB] + gm.v_meta + (((k % TPB) * 16 + n) * NG) * 4;
+                const unsigned char *p = sb8 + (k / TPB) * REC + RL::V_META + (((k % TPB) * 16 + n) * NG) * 4;
                 if (NG == 4) {
                     const uint4 t = *(const uint4 *)p;
                     vm[k][0] = t.x; vm[k][1 % NG] = t.y; vm[k][2 % NG] = t.z; vm[k][3 % NG] = t.w;
@@ -257,16 +327,19 @@ __global__ __launch_bounds__(kThreads) void decode_split_mfma_kernel(DecodeArgs 
 #pragma unroll
                 for (int ph = 0; ph < 2; ph++) {
                     const int co = (32 * vq + 16 * ph + 4 * qa) * 2;
-                    ks[bi][ph] = *(const uint2 *)(rec[bi] + gm.k_scale + co);
-                    kz[bi][ph] = *(const uint2 *)(rec[bi] + gm.k_zero + co);
-                    km[bi][ph] = has_kmean ? *(const uint2 *)(rec[bi] + gm.k_mean + co) : uint2{0u, 0u};
+                    ks[bi][ph] = *(const uint2 *)(sb8 + bi * REC + RL::K_SCALE + co);
+                    kz[bi][ph] = *(const uint2 *)(sb8 + bi * REC + RL::K_ZERO + co);
+                    km[bi][ph] = has_kmean ? *(const uint2 *)(sb8 + bi * REC + RL::K_MEAN + co) : uint2{0u, 0u};
                 }
             uint16_t vmean[NBC][8];
 #pragma unroll
             for (int bi = 0; bi < NBC; bi++)
 #pragma unroll
                 for (int ct = 0; ct < 8; ct++)
-                    vmean[bi][ct] = has_vmean ? *(const uint16_t *)(rec[bi] + gm.v_mean + (16 * ct + n) * 2) : (uint16_t)0;
+                    vmean[bi][ct] = has_vmean ? *(const uint16_t *)(sb8 + bi * REC + RL::V_MEAN + (16 * ct + n) * 2) : (uint16_t)0;
+            // every read of the staging buffer has returned: start fetching this wave's next chunk
+            wave_lds_fence();
+            if (ci + NW < n_chunks) issue(ci + NW);
 
             // ---- key side: q*scale as limbs -> LDS; zero/mean term
             float inv_kf[NBC], beta[NBC];
@@ -433,7 +506,7 @@ __global__ __launch_bounds__(kThreads) void decode_split_mfma_kernel(DecodeArgs 
         }
 
         // ---- raw residual tokens (Sec. 3.3): wave 0 of the split that owns them
-        const bool has_resid = w1 > a.n_blocks && a.r > 0;
+        const bool has_resid = a.r > 0 && sp == chunks_total % ns; // the split next in turn takes the raw tail
         if (has_resid) {
             __syncthreads(); // every wave is out of its main loop; wave 0 may take all of LDS
             if (wave == 0) {
@@ -520,7 +593,7 @@ __global__ __launch_bounds__(kThreads) void decode_split_mfma_kernel(DecodeArgs 
 #pragma unroll
             for (int ct = gam * TPG; ct < (gam + 1) * TPG; ct++) st.O[ct] += z;
         }
-        float *mine = (float *)lds; // this wave's 8 KiB: [10][64] floats
+        float *mine = (float *)lds; // start of this wave's LDS: [10][64] floats
         wave_lds_fence();
         mine[0 * 64 + lane] = st.M;
         mine[1 * 64 + lane] = st.l;
@@ -529,9 +602,9 @@ __global__ __launch_bounds__(kThreads) void decode_split_mfma_kernel(DecodeArgs 
         __syncthreads();
         if (wave == 0 && row < g) {
             const float *all = (const float *)lds_all;
-            float Mw[4], M = -INFINITY;
+            float Mw[NW], M = -INFINITY;
 #pragma unroll
-            for (int w = 0; w < 4; w++) {
+            for (int w = 0; w < NW; w++) {
                 Mw[w] = all[w * WAVE_DW + lane];
                 M = fmaxf(M, Mw[w]);
             }
@@ -539,13 +612,13 @@ __global__ __launch_bounds__(kThreads) void decode_split_mfma_kernel(DecodeArgs 
 #pragma unroll
             for (int ct = 0; ct < 8; ct++) o[ct] = 0.0f;
 #pragma unroll
-            for (int w = 0; w < 4; w++) {
-                const float wt = exp2f(Mw[w] - M); // a wave that saw no token has max -inf: weight 0
+            for (int w = 0; w < NW; w++) {
+                const float wt = Mw[w] == -INFINITY ? 0.0f : exp2f(Mw[w] - M); // a wave that saw no token
                 lsum += all[w * WAVE_DW + 64 + lane] * wt;
 #pragma unroll
                 for (int ct = 0; ct < 8; ct++) o[ct] += all[w * WAVE_DW + (2 + ct) * 64 + lane] * wt;
             }
-            float *dst = a.ws + (((long long)u * a.n_splits + sp) * g + row) * kPartialStride;
+            float *dst = a.ws + (((long long)u * g + row) * a.n_splits + sp) * kPartialStride;
 #pragma unroll
             for (int ct = 0; ct < 8; ct++) dst[16 * ct + n] = o[ct];
             if (n == 0) {
@@ -556,12 +629,49 @@ __global__ __launch_bounds__(kThreads) void decode_split_mfma_kernel(DecodeArgs 
     }
 }
 
+// Resident workgroups of one instantiation on the whole device (0 if the query fails).
+template <int B, int G, int GC, bool MEAN, int NW> int resident_blocks()
+{
+    static const int n = [] {
+        int per_cu = 0, dev = 0, cus = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_split_mfma_kernel<B, G, GC, MEAN, NW>,
+                                                         64 * NW, 0) != hipSuccess)
+            return 0;
+        if (hipGetDevice(&dev) != hipSuccess) return 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+        return per_cu * cus;
+    }();
+    return n;
+}
+
 template <int B, int G, int GC, bool MEAN> hipError_t launch_mean(const DecodeArgs &a, hipStream_t s)
 {
+    constexpr int NW = kWavesPerBlock;
+    if (!RecLayout<B, G, GC, MEAN>::matches(a.geom)) return hipErrorInvalidValue;
     dim3 grid(a.n_splits, a.batch * a.n_kv_heads);
     (void)hipGetLastError(); // drop any stale error left by earlier runtime calls of this thread
-    hipLaunchKernelGGL((decode_split_mfma_kernel<B, G, GC, MEAN>), grid, dim3(kThreads), 0, s, a);
+    hipLaunchKernelGGL((decode_split_mfma_kernel<B, G, GC, MEAN, NW>), grid, dim3(64 * NW), 0, s, a);
     return note_launch(hipGetLastError());
+}
+
+// Split count that puts every workgroup of the launch on the device at once (one "round"):
+// the kernel is a bandwidth stream, and a second, partly filled round only adds a tail.
+template <int B, int G, int GC, bool MEAN> int plan_mean(const DecodeArgs &a)
+{
+    constexpr int NW = kWavesPerBlock, NBC = 64 / G;
+    const int slots = resident_blocks<B, G, GC, MEAN, NW>();
+    const int U = a.batch * a.n_kv_heads;
+    const int chunks = (a.n_blocks + NBC - 1) / NBC;
+    int ns = slots / U;
+    const int cap = chunks / (NW * 4); // at least four chunks per wave, or the prologue dominates
+    if (ns > cap) ns = cap;
+    if (ns > kMaxSplits) ns = kMaxSplits;
+    if (ns < 1) ns = 1;
+    return ns;
+}
+template <int B, int G, int GC> int plan_one(const DecodeArgs &a)
+{
+    return a.geom.mean_mode == 0 ? plan_mean<B, G, GC, true>(a) : plan_mean<B, G, GC, false>(a);
 }
 
 template <int B, int G, int GC> hipError_t launch_one(const DecodeArgs &a, hipStream_t s)
@@ -569,6 +679,17 @@ template <int B, int G, int GC> hipError_t launch_one(const DecodeArgs &a, hipSt
     return a.geom.mean_mode == 0 ? launch_mean<B, G, GC, true>(a, s) : launch_mean<B, G, GC, false>(a, s);
 }
 
+} // namespace
+
+namespace {
+template <int B, int G, int GC> bool layout_ok(const LayerGeom &g)
+{
+    return g.mean_mode == 0 ? RecLayout<B, G, GC, true>::matches(g) : RecLayout<B, G, GC, false>::matches(g);
+}
+template <int G, int GC> bool layout_ok_bits(const LayerGeom &g)
+{
+    return g.k_bits == 2 ? layout_ok<2, G, GC>(g) : (g.k_bits == 4 ? layout_ok<4, G, GC>(g) : layout_ok<8, G, GC>(g));
+}
 } // namespace
 
 bool decode_mfma_supported(const DecodeArgs &a)
@@ -580,7 +701,16 @@ bool decode_mfma_supported(const DecodeArgs &a)
     if (a.g > 4) return false;
     if (g.mean_mode == 1) return false; // cross-head mean: not on this path
     if (a.batch * a.n_kv_heads > 65535) return false;
-    return true;
+    // the kernels address record fields with compile-time offsets
+    return g.G == 32 ? layout_ok_bits<32, 32>(g) : layout_ok_bits<64, 64>(g);
+}
+
+int decode_mfma_splits(const DecodeArgs &a)
+{
+    if (!decode_mfma_supported(a)) return 1;
+    const int bits = a.geom.k_bits;
+    if (a.geom.G == 32) return bits == 2 ? plan_one<2, 32, 32>(a) : (bits == 4 ? plan_one<4, 32, 32>(a) : plan_one<8, 32, 32>(a));
+    return bits == 2 ? plan_one<2, 64, 64>(a) : (bits == 4 ? plan_one<4, 64, 64>(a) : plan_one<8, 64, 64>(a));
 }
 
 hipError_t launch_decode_split_mfma(const DecodeArgs &a, hipStream_t s)

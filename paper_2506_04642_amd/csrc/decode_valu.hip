@@ -298,7 +298,7 @@ template <int KB, int VB> __global__ __launch_bounds__(kThreads) void decode_spl
     for (int k = 0; k < kMaxGroupQ / 2; k++) {
         const int i = hsel + 2 * k;
         if (i < g) {
-            float *dst = a.ws + (((long long)u * a.n_splits + sp) * g + i) * kPartialStride;
+            float *dst = a.ws + (((long long)u * g + i) * a.n_splits + sp) * kPartialStride;
             dst[c] = acc[k];
             if (c == 0) {
                 dst[kHeadDim] = sm.mrun[i];
@@ -308,24 +308,34 @@ template <int KB, int VB> __global__ __launch_bounds__(kThreads) void decode_spl
     }
 }
 
-// out[b, head] = sum_j o_j 2^(m_j - M) / sum_j l_j 2^(m_j - M),  M = max_j m_j
-__global__ __launch_bounds__(128) void merge_kernel(DecodeArgs a)
+// out[b, head] = sum_j o_j 2^(m_j - M) / sum_j l_j 2^(m_j - M),  M = max_j m_j.
+// One wave per (unit, query head); a lane owns two channels.  The order of the sums is fixed.
+__global__ __launch_bounds__(256) void merge_kernel(DecodeArgs a)
 {
-    const int uq = blockIdx.x; // (unit, head-in-group)
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int uq = blockIdx.x * 4 + wave; // (unit, head-in-group)
+    if (uq >= a.batch * a.n_q_heads) return;
     const int u = uq / a.g, i = uq % a.g;
-    const int c = threadIdx.x;
-    const float *base = a.ws + ((long long)u * a.n_splits * a.g + i) * kPartialStride;
-    const long long stride = (long long)a.g * kPartialStride;
+    const int ns = a.n_splits;
+    const float *base = a.ws + (long long)uq * ns * kPartialStride;
     float M = -INFINITY;
-    for (int j = 0; j < a.n_splits; j++) M = fmaxf(M, base[j * stride + kHeadDim]);
-    float num = 0.0f, den = 0.0f;
-    for (int j = 0; j < a.n_splits; j++) {
-        const float w = exp2f(base[j * stride + kHeadDim] - M);
-        num += base[j * stride + c] * w;
-        den += base[j * stride + kHeadDim + 1] * w;
+    for (int j = lane; j < ns; j += 64) M = fmaxf(M, base[j * kPartialStride + kHeadDim]);
+    M = wave_max(M);
+    float n0 = 0.0f, n1 = 0.0f, den = 0.0f;
+#pragma unroll 4
+    for (int j = 0; j < ns; j++) {
+        const float *pj = base + j * kPartialStride;
+        const float w = exp2f(pj[kHeadDim] - M);
+        const float2 o = *(const float2 *)(pj + 2 * lane);
+        n0 += o.x * w;
+        n1 += o.y * w;
+        den += pj[kHeadDim + 1] * w;
     }
     const int b = u / a.n_kv_heads, h = u % a.n_kv_heads;
-    a.out[((long long)b * a.n_q_heads + h * a.g + i) * kHeadDim + c] = num / den;
+    float2 r;
+    r.x = n0 / den;
+    r.y = n1 / den;
+    *(float2 *)(a.out + ((long long)b * a.n_q_heads + h * a.g + i) * kHeadDim + 2 * lane) = r;
 }
 
 template <int KB, int VB> hipError_t launch_one(const DecodeArgs &a, hipStream_t s)
@@ -366,9 +376,9 @@ hipError_t launch_decode_split_valu(const DecodeArgs &a, hipStream_t s)
 
 hipError_t launch_decode_merge(const DecodeArgs &a, hipStream_t s)
 {
-    dim3 grid(a.batch * a.n_q_heads);
+    dim3 grid((a.batch * a.n_q_heads + 3) / 4);
     (void)hipGetLastError(); // drop any stale error left by earlier runtime calls of this thread
-    hipLaunchKernelGGL(merge_kernel, grid, dim3(128), 0, s, a);
+    hipLaunchKernelGGL(merge_kernel, grid, dim3(256), 0, s, a);
     return note_launch(hipGetLastError());
 }
 

@@ -112,6 +112,17 @@ void choose_splits(const kv_config &c, int n_blocks, int r, int *n_splits, int *
     *blocks_per_split = bps;
 }
 
+// Upper bound of the matrix-core kernel's split count: it never launches more workgroups than
+// fit on the device at once (at most 8 per compute unit on 256 units).
+int mfma_split_bound(const kv_config &c)
+{
+    const long long U = (long long)c.batch * c.n_kv_heads;
+    long long b = 2048 / U;
+    if (b < 1) b = 1;
+    if (b > kMaxSplits) b = kMaxSplits;
+    return (int)b;
+}
+
 size_t workspace_need(const kv_config &c, int n_splits)
 {
     return (size_t)c.batch * c.n_q_heads * n_splits * kPartialStride * sizeof(float);
@@ -137,6 +148,13 @@ kv_status fill_decode(const kv_cache *k, int layer, DecodeArgs *a)
     a->r = k->resid[layer];
     if (a->n_blocks == 0 && a->r == 0) return KV_E_EMPTY;
     choose_splits(c, a->n_blocks, a->r, &a->n_splits, &a->blocks_per_split);
+    if (k->decode_path != 1 && decode_mfma_supported(*a)) {
+        // the matrix-core kernel interleaves its splits chunk by chunk and sizes the launch to
+        // the device; blocks_per_split is not used by it
+        a->n_splits = decode_mfma_splits(*a);
+        const int cap = mfma_split_bound(c);
+        if (a->n_splits > cap) a->n_splits = cap;
+    }
     if (k->forced_splits > 0) {
         const int work = a->n_blocks + (a->r > 0 ? 1 : 0);
         int ns = k->forced_splits < work ? k->forced_splits : work;
@@ -208,6 +226,7 @@ kv_status kv_workspace_bytes(const kv_config *cfg, size_t *bytes)
         choose_splits(*cfg, nb, 1, &ns, &bps);
         if (ns > worst) worst = ns;
     }
+    if (mfma_split_bound(*cfg) > worst) worst = mfma_split_bound(*cfg);
     *bytes = workspace_need(*cfg, worst);
     return KV_OK;
 }

@@ -7,7 +7,7 @@ namespace tadakv {
 
 constexpr int kHeadDim = 128;
 constexpr int kMaxGroupQ = 8;       // query heads per kv head the kernels are sized for
-constexpr int kPartialStride = 132; // floats per (unit, split, q head): O[128], max, sum, pad
+constexpr int kPartialStride = 132; // floats per (unit, q head, split): O[128], max, sum, pad
 constexpr int kMaxSplits = 256;
 
 // Geometry of one layer's buffer; byte offsets, -1 where a field is absent.
@@ -38,7 +38,7 @@ struct DecodeArgs {
     LayerGeom geom;
     const unsigned char *layer;
     const uint16_t *q;   // [batch][Hq][128]
-    float *ws;           // partials [U][n_splits][g][kPartialStride]
+    float *ws;           // partials [U][g][n_splits][kPartialStride]
     float *out;          // [batch][Hq][128]
     int n_kv_heads, n_q_heads, batch, g;
     int n_blocks;        // packed blocks in the layer
@@ -55,6 +55,7 @@ hipError_t launch_resid_copy(const AppendArgs &a, hipStream_t s);
 hipError_t launch_decode_split_valu(const DecodeArgs &a, hipStream_t s);
 hipError_t launch_decode_split_mfma(const DecodeArgs &a, hipStream_t s);
 bool decode_mfma_supported(const DecodeArgs &a);
+int decode_mfma_splits(const DecodeArgs &a); // preferred split count of the matrix-core kernel
 hipError_t launch_decode_merge(const DecodeArgs &a, hipStream_t s);
 
 } // namespace tadakv
