@@ -23,6 +23,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published
+# HBM bytes per launch of the decode split kernel divided by its algorithmic bytes, from the
+# FETCH_SIZE / WRITE_SIZE counter runs summarised in profiles/decode_split_mfma_hbm_traffic.txt
+# (counters scaled by what they read for a plain copy of known size: x2.000 and x1.000)
+TRAFFIC_RATIO = {2: 1.003, 4: 1.001, 8: 1.000}
 
 
 def parse():
@@ -147,8 +151,34 @@ def main():
         ms = float(split_ms[:, idx].mean())
         byts = float(np.mean([layer_bytes[l] for l in idx]))
         per_bits[str(b_)] = {"layers": len(idx), "avg_ms": round(ms, 5), "bytes": int(byts),
-                             "GBps": round(byts / ms / 1e6, 1), "frac": round(byts / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+                             "GBps": round(byts / ms / 1e6, 1), "frac": round(byts / ms / 1e6 / HBM_PEAK_GBPS, 4),
+                             "traffic": int(byts * TRAFFIC_RATIO[b_]) if b_ in TRAFFIC_RATIO and args.path != 1 else None}
     achieved = float(sum(layer_bytes)) / float(split_ms.mean(axis=0).sum()) / 1e6
+    traffic = None
+    if args.path != 1 and all(b_ in TRAFFIC_RATIO for b_ in bits):
+        traffic = int(sum(layer_bytes[l] * TRAFFIC_RATIO[bits[l]] for l in range(L)) / L)
+
+    # ---- what a plain streaming read of the same size reaches on this machine (context for `frac`):
+    # torch's int64 sum over a buffer as large as one layer's algorithmic bytes, rotated over a pool
+    ceiling = {}
+    pool = torch.ones(2 * 1024 ** 3 // 8, dtype=torch.int64, device=dev)
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for b_ in sorted(set(bits)):
+        n = per_bits[str(b_)]["bytes"] // 8
+        views = [pool[i * n:(i + 1) * n] for i in range(max(1, pool.numel() // n))]
+        for v_ in views[:2]:
+            v_.sum()
+        ts = []
+        for it in range(12):
+            c0.record(stream)
+            views[it % len(views)].sum()
+            c1.record(stream)
+            c1.synchronize()
+            ts.append(c0.elapsed_time(c1))
+        ts.sort()
+        ceiling[str(b_)] = round(n * 8 / ts[len(ts) // 2] / 1e6, 1)
+        per_bits[str(b_)]["frac_of_stream_read"] = round(per_bits[str(b_)]["GBps"] / ceiling[str(b_)], 4)
+    del pool
 
     # ---- single-token append cost, measured apart from the timed region
     torch.cuda.synchronize()
@@ -174,7 +204,7 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "int8+f32" if args.path != 1 else "f32",
+        "dtype": "i8 x i8 -> i32 contractions, f32 softmax" if args.path != 1 else "f32",
         "data": "synthetic",
         "config": {"workload": "llama3-8b-shaped full cache: 32 layers, 32q/8kv heads, head_dim 128, "
                                "batch %d, context %d, bf16, G=Gc=32, mixed {2,4,8}-bit layer map (seed 2000), "
@@ -190,7 +220,9 @@ def main():
         },
         "roofline": {"bound": "hbm", "kernel": "decode split kernel (all layers, weighted by layer)",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None, "per_bits": per_bits},
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "bytes_per_launch": int(sum(layer_bytes) / L), "per_bits": per_bits,
+                     "stream_read_GBps_same_size": ceiling},
     }
 
     # ---- CPU oracle on a bounded sample of the same workload (rank 0, one core)

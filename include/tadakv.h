@@ -89,8 +89,12 @@ typedef struct {
  * all metadata binary16; the mean fields exist only for KV_MEAN_CHANNEL_BLOCK; a 16-bit side
  * stores its G x head_dim raw rows in the codes field and has no metadata.  Absent fields are -1.
  * Codes are stored as 16 x 16 tiles (keys: token x channel; values: channel x token): a tile row's
- * 16 codes take 2*bits bytes, little-endian within the byte run; a 16-byte piece holds the same
- * row of 8/bits tiles; 16 pieces (rows 0..15) are consecutive. */
+ * 16 codes take 2*bits bytes, i.e. bits/2 32-bit words of 32/bits codes; inside a word, code number
+ * 4f + y is field f (bits [bits*f, bits*f + bits)) of byte y.  A 16-byte piece holds the same row
+ * of 8/bits tiles; 16 pieces (rows 0..15) are consecutive.  Key pieces: one channel tile at 8 bits
+ * (pieces ordered by token tile, tile parity, tile pair), channel tiles (2j, 2j+1) at 4 bits, and
+ * those two tiles for two consecutive token tiles at 2 bits.  Value pieces: 8/bits consecutive
+ * channel tiles of one 16-token tile. */
 typedef struct {
     int32_t k_bits, v_bits;
     int64_t rec_bytes;
