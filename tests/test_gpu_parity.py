@@ -203,3 +203,62 @@ def test_drifting_channel_means(kv, oracle):
     append_both(gpu, orc, 0, k, v, BF16)
     check_bytes(gpu, orc, 0)
     check_attention(gpu, orc, 0, synth.make_q(55, 1, 8, 128, BF16), BF16)
+
+
+# ------------------------------------------------------------------ full size, sampled units
+
+
+@pytest.mark.parametrize("decode_path", [0], indirect=True, ids=["auto"])
+def test_full_cache_shape_sampled_units(kv, oracle, decode_path):
+    """The benchmark's launch configuration (batch 16, 8 kv / 32 query heads, context 32768 plus a
+    13-token raw tail, one layer per bit width): cache bytes and attention of sampled sequences
+    against the oracle, which computes those sequences one by one."""
+    import torch
+
+    print("case full_cache_shape", flush=True)
+    B, Hq, Hkv, d, G, T = 16, 32, 8, 128, 32, 32768 + 13
+    bits = (2, 4, 8)
+    cfg = kv.make_config(3, B, Hq, Hkv, d, 32768 + 64, G, G, G, kv.KV_BF16, kv.KV_MEAN_CHANNEL_BLOCK,
+                         list(bits), list(bits))
+    gpu = kv.KVCache(cfg, zero=False)
+    sample = (0, 11)
+    ocfg = oracle.OracleConfig(3, len(sample), Hq, Hkv, d, 32768 + 64, G, G, G, BF16, CHAN, list(bits), list(bits))
+    orc = oracle.OracleCache(ocfg)
+    for l in range(3):
+        host_k, host_v = [], []
+        for t0 in range(0, T, 8192):
+            n = min(8192, T - t0)
+            k, v = synth.make_kv_torch(900 + 10 * l + t0 // 8192, B, n, Hkv, d, BF16, "cuda:0")
+            gpu.append(l, k, v)
+            host_k.append(k[list(sample)].cpu())
+            host_v.append(v[list(sample)].cpu())
+        k16 = torch.cat(host_k, 1).view(torch.int16).numpy().view(np.uint16)
+        v16 = torch.cat(host_v, 1).view(torch.int16).numpy().view(np.uint16)
+        orc.append(l, k16, v16)
+    torch.cuda.synchronize()
+    for l in range(3):
+        print("  layer %d (%d-bit) splits=%d" % (l, bits[l], kv.kv_decode_splits(gpu.handle, l)), flush=True)
+        assert gpu.lengths(l) == (orc.packed_len(l), orc.resid_len(l)) == (32768, 13)
+        lay = kv.kv_cache_describe(gpu.handle, l)
+        img = orc.layer_image(l)  # image of a cache that holds only the sampled sequences
+        NB = (32768 + 64) // G
+        dev = gpu.layers[l]
+        for si, b in enumerate(sample):
+            # records of the 8 units of sequence b, and their raw residual rows
+            n_rec = 32768 // G
+            for h in range(Hkv):
+                g0 = ((b * Hkv + h) * NB) * lay.rec_bytes
+                o0 = ((si * Hkv + h) * NB) * lay.rec_bytes
+                got = dev[g0:g0 + n_rec * lay.rec_bytes].cpu().numpy()
+                want = img["bytes"][o0:o0 + n_rec * lay.rec_bytes]
+                m = img["valid"][o0:o0 + n_rec * lay.rec_bytes]
+                assert np.array_equal(got[m], want[m]), (l, b, h)
+        q = synth.make_q_torch(77 + l, B, Hq, d, BF16, "cuda:0")
+        out = gpu.attend(l, q)
+        torch.cuda.synchronize()
+        q16 = q[list(sample)].cpu().view(torch.int16).numpy().view(np.uint16)
+        want = orc.attend(l, q16)
+        got = out[list(sample)].cpu().numpy().astype(np.float64)
+        err = float(np.max(np.abs(got - want)))
+        print("  attention max-abs error %.3e" % err, flush=True)
+        assert err <= 2e-3
