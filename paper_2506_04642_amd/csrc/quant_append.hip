@@ -67,10 +67,19 @@ __device__ __forceinline__ void group_meta(float mn, float mx, int qmax, uint16_
     s = f16_val(s16);
 }
 
-__device__ __forceinline__ uint32_t quant_code(float dev, float s, float z, int qmax)
+// code = clamp(rint((dev - z) / s), 0, qmax).  The quotient is formed with the group's
+// reciprocal r = 1/s (one IEEE division per group) and one fused correction step:
+//   q = x r;  e = fma(-q, s, x);  q' = fma(e, r, q)
+// which equals the correctly rounded x / s whenever r is the correctly rounded reciprocal and
+// the significand of s is not all ones (Markstein's division theorem); s is a binary16 value,
+// so its binary32 significand has at most 11 leading bits set.
+__device__ __forceinline__ uint32_t quant_code(float dev, float s, float rs, float z, int qmax)
 {
     if (s == 0.0f) return 0u;
-    float u = (dev - z) / s;
+    const float xv = dev - z;
+    const float q = xv * rs;
+    const float e = __builtin_fmaf(-q, s, xv);
+    const float u = __builtin_fmaf(e, rs, q);
     float r = rintf(u);
     r = r < 0.0f ? 0.0f : r;
     r = r > (float)qmax ? (float)qmax : r;
@@ -169,7 +178,13 @@ __global__ __launch_bounds__(kThreads) void flush_block_kernel(AppendArgs a)
 
     const int qmax = (1 << bits) - 1;
     const bool centre = gm.mean_mode == 0; // per-channel block mean
+    const int ng = kHeadDim / gm.Gc;
+    const int v_items = G * ng * 2; // value groups x two threads each
+    float *meanv = (float *)(cb + G * kHeadDim);   // [128] channel means
+    float *mm = meanv + kHeadDim;                  // [2][max(256, v_items)] partial minima, maxima
+    const int mm_n = v_items > kThreads ? v_items : kThreads;
 
+    // 2. channel mean over the block's tokens: sequential sum in token order, one thread per channel
     if (tid < kHeadDim) {
         const int c = tid;
         float m = 0.0f;
@@ -181,48 +196,80 @@ __global__ __launch_bounds__(kThreads) void flush_block_kernel(AppendArgs a)
             m = f16_val(m16);
             *(uint16_t *)(rec + (which == 0 ? gm.k_mean : gm.v_mean) + c * 2) = m16;
         }
-        if (which == 0) {
-            float mn = x[c] - m, mx = mn;
-            x[c] = mn;
-            for (int t = 1; t < G; t++) {
-                const float dv = x[t * kRowPad + c] - m;
-                x[t * kRowPad + c] = dv;
-                mn = dv < mn ? dv : mn;
-                mx = dv > mx ? dv : mx;
-            }
-            uint16_t s16, z16;
-            float s, z;
-            group_meta(mn, mx, qmax, s16, z16, s, z);
-            *(uint16_t *)(rec + gm.k_scale + c * 2) = s16;
-            *(uint16_t *)(rec + gm.k_zero + c * 2) = z16;
-            for (int t = 0; t < G; t++)
-                cb[t * kHeadDim + c] = (unsigned char)quant_code(x[t * kRowPad + c], s, z, qmax);
-        } else if (centre) {
-            for (int t = 0; t < G; t++) x[t * kRowPad + c] = x[t * kRowPad + c] - m;
-        }
+        meanv[c] = m;
     }
     __syncthreads();
 
+    // 3. deviation; every thread owns half of a channel's tokens
+    {
+        const int c = tid & 127, half = tid >> 7;
+        const int t_lo = half * (G / 2), t_hi = t_lo + G / 2;
+        const float m = meanv[c];
+        float mn = INFINITY, mx = -INFINITY;
+        for (int t = t_lo; t < t_hi; t++) {
+            const float dv = x[t * kRowPad + c] - m;
+            x[t * kRowPad + c] = dv;
+            mn = dv < mn ? dv : mn;
+            mx = dv > mx ? dv : mx;
+        }
+        if (which == 0) {
+            mm[tid] = mn;
+            mm[mm_n + tid] = mx;
+        }
+        __syncthreads();
+        if (which == 0) {
+            // keys: one group per channel over all tokens of the block (extrema are order-free)
+            const float o_mn = mm[tid ^ 128], o_mx = mm[mm_n + (tid ^ 128)];
+            mn = o_mn < mn ? o_mn : mn;
+            mx = o_mx > mx ? o_mx : mx;
+            uint16_t s16, z16;
+            float sc, z;
+            group_meta(mn, mx, qmax, s16, z16, sc, z);
+            if (half == 0) {
+                *(uint16_t *)(rec + gm.k_scale + c * 2) = s16;
+                *(uint16_t *)(rec + gm.k_zero + c * 2) = z16;
+            }
+            const float r = sc != 0.0f ? 1.0f / sc : 0.0f;
+            for (int t = t_lo; t < t_hi; t++)
+                cb[t * kHeadDim + c] = (unsigned char)quant_code(x[t * kRowPad + c], sc, r, z, qmax);
+        }
+    }
+
     if (which == 1) {
-        const int ng = kHeadDim / gm.Gc;
-        for (int gi = tid; gi < G * ng; gi += kThreads) {
-            const int t = gi % G, gam = gi / G;
-            const float *row = x + t * kRowPad + gam * gm.Gc;
+        // values: one group per (token, channel group); two threads per group, half the channels each
+        const int hw = gm.Gc / 2;
+        for (int idx = tid; idx < v_items; idx += kThreads) {
+            const int t = idx % G, rest = idx / G, gam = rest % ng, half = rest / ng;
+            const float *row = x + t * kRowPad + gam * gm.Gc + half * hw;
             float mn = row[0], mx = row[0];
-            for (int i = 1; i < gm.Gc; i++) {
+            for (int i = 1; i < hw; i++) {
                 const float dv = row[i];
                 mn = dv < mn ? dv : mn;
                 mx = dv > mx ? dv : mx;
             }
-            uint16_t s16, z16;
-            float s, z;
-            group_meta(mn, mx, qmax, s16, z16, s, z);
-            *(uint32_t *)(rec + gm.v_meta + (t * ng + gam) * 4) = (uint32_t)s16 | ((uint32_t)z16 << 16);
-            unsigned char *crow = cb + t * kHeadDim + gam * gm.Gc;
-            for (int i = 0; i < gm.Gc; i++) crow[i] = (unsigned char)quant_code(row[i], s, z, qmax);
+            mm[idx] = mn;
+            mm[mm_n + idx] = mx;
         }
         __syncthreads();
+        for (int idx = tid; idx < v_items; idx += kThreads) {
+            const int t = idx % G, rest = idx / G, gam = rest % ng, half = rest / ng;
+            const int other = half ? idx - G * ng : idx + G * ng;
+            float mn = mm[idx], mx = mm[mm_n + idx];
+            const float o_mn = mm[other], o_mx = mm[mm_n + other];
+            mn = o_mn < mn ? o_mn : mn;
+            mx = o_mx > mx ? o_mx : mx;
+            uint16_t s16, z16;
+            float sc, z;
+            group_meta(mn, mx, qmax, s16, z16, sc, z);
+            if (half == 0)
+                *(uint32_t *)(rec + gm.v_meta + (t * ng + gam) * 4) = (uint32_t)s16 | ((uint32_t)z16 << 16);
+            const float r = sc != 0.0f ? 1.0f / sc : 0.0f;
+            const float *row = x + t * kRowPad + gam * gm.Gc + half * hw;
+            unsigned char *crow = cb + t * kHeadDim + gam * gm.Gc + half * hw;
+            for (int i = 0; i < hw; i++) crow[i] = (unsigned char)quant_code(row[i], sc, r, z, qmax);
+        }
     }
+    __syncthreads();
 
     // pack: one 32-bit word = 32/bits consecutive codes along channels (keys) or tokens (values),
     // byte-interleaved: the word's code number 4f + y is field f (bits [bits*f, bits*f+bits)) of
@@ -265,7 +312,9 @@ __global__ __launch_bounds__(kThreads) void resid_copy_kernel(AppendArgs a)
 hipError_t launch_flush(const AppendArgs &a, hipStream_t s)
 {
     const int U = a.batch * a.n_kv_heads;
-    const size_t lds = (size_t)a.geom.G * kRowPad * sizeof(float) + (size_t)a.geom.G * kHeadDim;
+    const int v_items = a.geom.G * (kHeadDim / a.geom.Gc) * 2;
+    const size_t lds = (size_t)a.geom.G * kRowPad * sizeof(float) + (size_t)a.geom.G * kHeadDim +
+                       kHeadDim * sizeof(float) + 2 * (size_t)(v_items > kThreads ? v_items : kThreads) * sizeof(float);
     // grid.y is limited to 65535 entries
     if (U > 65535) return hipErrorInvalidValue;
     dim3 grid(a.n_flush_blocks, U, 2);
