@@ -58,8 +58,9 @@ template <int B> __device__ __forceinline__ int v_word(int t0, int c, int nt)
 }
 
 struct Smem {
-    float *qf, *qs, *part, *ps, *pz, *psum, *alpha, *mrun, *lrun, *bpart, *vmean;
+    float *qf, *qs, *part, *ps, *pz, *psum, *alpha, *mrun, *lrun, *bpart, *vmean, *pp;
     uint32_t *kc, *vc, *vmeta;
+    uint16_t *xk, *xv; // cross-head mean tiles [G][128] of the block (keys, values)
 };
 
 // One block (or one chunk of raw tokens) of one unit.  KB/VB = 16 means raw rows.
@@ -68,7 +69,8 @@ __device__ __forceinline__ void process_block(const DecodeArgs &a, const Smem &s
                                               const unsigned char *kcodes, const unsigned char *kscale,
                                               const unsigned char *kzero, const unsigned char *kmean,
                                               const unsigned char *vcodes, const unsigned char *vmeta,
-                                              const unsigned char *vmean, float (&acc)[kMaxGroupQ / 2])
+                                              const unsigned char *vmean, const unsigned char *xmean_k,
+                                              const unsigned char *xmean_v, float (&acc)[kMaxGroupQ / 2])
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = a.g;
@@ -84,6 +86,13 @@ __device__ __forceinline__ void process_block(const DecodeArgs &a, const Smem &s
         for (int i = tid; i < kbytes / 16; i += kThreads) ((uint4 *)sm.kc)[i] = ((const uint4 *)kcodes)[i];
         const int vbytes = (VB == 16) ? ntok * 256 : a.geom.G * kHeadDim * VB / 8;
         for (int i = tid; i < vbytes / 16; i += kThreads) ((uint4 *)sm.vc)[i] = ((const uint4 *)vcodes)[i];
+        if (xmean_k) {
+            // cross-head mean (Eq. 1-2): one binary16 row per token, shared by all kv heads
+            for (int i = tid; i < a.geom.G * 16; i += kThreads) {
+                ((uint4 *)sm.xk)[i] = ((const uint4 *)xmean_k)[i];
+                ((uint4 *)sm.xv)[i] = ((const uint4 *)xmean_v)[i];
+            }
+        }
         if (VB != 16) {
             for (int i = tid; i < a.geom.G * ng; i += kThreads) sm.vmeta[i] = ((const uint32_t *)vmeta)[i];
             if (tid < kHeadDim) sm.vmean[tid] = vmean ? f16_val(((const uint16_t *)vmean)[tid]) : 0.0f;
@@ -126,6 +135,11 @@ __device__ __forceinline__ void process_block(const DecodeArgs &a, const Smem &s
                          (float)((w >> (8 * (e & 3) + (KB & 15) * (e >> 2))) & ((1u << (KB & 15)) - 1u));
             }
         }
+        if (KB != 16 && xmean_k) {
+            const float *qraw = sm.qf + i * kHeadDim;
+            const uint16_t *mrow = sm.xk + t * kHeadDim;
+            for (int c = half * 64; c < half * 64 + 64; c++) s += qraw[c] * f16_val(mrow[c]);
+        }
         sm.part[(half * g + i) * G + t] = s;
     }
     __syncthreads();
@@ -155,6 +169,7 @@ __device__ __forceinline__ void process_block(const DecodeArgs &a, const Smem &s
             if (t < ntok) {
                 const float p = exp2f(sv[k] - m_new);
                 psum += p;
+                sm.pp[i * G + t] = p;
                 if (VB == 16) {
                     sm.ps[i * G + t] = p;
                 } else {
@@ -212,6 +227,16 @@ __device__ __forceinline__ void process_block(const DecodeArgs &a, const Smem &s
                 }
             }
         }
+        if (VB != 16 && xmean_v) {
+            for (int t = 0; t < ntok; t++) {
+                const float mv = f16_val(sm.xv[t * kHeadDim + c]);
+#pragma unroll
+                for (int k = 0; k < kMaxGroupQ / 2; k++) {
+                    const int i = hsel + 2 * k;
+                    if (i < g) add[k] += sm.pp[i * G + t] * mv;
+                }
+            }
+        }
 #pragma unroll
         for (int k = 0; k < kMaxGroupQ / 2; k++) {
             const int i = hsel + 2 * k;
@@ -242,11 +267,14 @@ template <int KB, int VB> __global__ __launch_bounds__(kThreads) void decode_spl
     sm.lrun = p;   p += kMaxGroupQ;
     sm.bpart = p;  p += kMaxGroupQ * 2;
     sm.vmean = p;  p += kHeadDim;
+    sm.pp = p;     p += g * G;
     sm.vmeta = (uint32_t *)p; p += G * 4;
     // staging sized for the widest case: 8-bit codes of a block, or 32 raw 16-bit rows
     const int code_words = G * kHeadDim * 8 / 32 > 32 * 64 ? G * kHeadDim * 8 / 32 : 32 * 64;
     sm.kc = (uint32_t *)p; p += code_words;
-    sm.vc = (uint32_t *)p;
+    sm.vc = (uint32_t *)p; p += code_words;
+    sm.xk = (uint16_t *)p; p += (gm.mean_mode == 1 ? G * kHeadDim / 2 : 0);
+    sm.xv = (uint16_t *)p;
 
     const int sp = blockIdx.x, u = blockIdx.y;
     const int b = u / a.n_kv_heads, h = u % a.n_kv_heads;
@@ -274,11 +302,15 @@ template <int KB, int VB> __global__ __launch_bounds__(kThreads) void decode_spl
         if (KB == 16) {
             for (int t0 = 0; t0 < G; t0 += 32)
                 process_block<16, 16>(a, sm, 32, rec + gm.k_codes + t0 * 256, nullptr, nullptr, nullptr,
-                                      rec + gm.v_codes + t0 * 256, nullptr, nullptr, acc);
+                                      rec + gm.v_codes + t0 * 256, nullptr, nullptr, nullptr, nullptr, acc);
         } else {
+            const unsigned char *xm = gm.mean_mode == 1
+                                          ? a.layer + gm.xmean_off + ((long long)b * gm.NB + j) * 2 * G * kHeadDim * 2
+                                          : nullptr;
             process_block<KB, VB>(a, sm, G, rec + gm.k_codes, rec + gm.k_scale, rec + gm.k_zero,
                                   gm.k_mean >= 0 ? rec + gm.k_mean : nullptr, rec + gm.v_codes,
-                                  rec + gm.v_meta, gm.v_mean >= 0 ? rec + gm.v_mean : nullptr, acc);
+                                  rec + gm.v_meta, gm.v_mean >= 0 ? rec + gm.v_mean : nullptr, xm,
+                                  xm ? xm + G * kHeadDim * 2 : nullptr, acc);
         }
     }
     if (w1 > a.n_blocks && a.r > 0) {
@@ -287,7 +319,7 @@ template <int KB, int VB> __global__ __launch_bounds__(kThreads) void decode_spl
         for (int t0 = 0; t0 < a.r; t0 += 32) {
             const int n = a.r - t0 < 32 ? a.r - t0 : 32;
             process_block<16, 16>(a, sm, n, kr + t0 * 256, nullptr, nullptr, nullptr, vr + t0 * 256,
-                                  nullptr, nullptr, acc);
+                                  nullptr, nullptr, nullptr, nullptr, acc);
         }
     }
     __syncthreads();
@@ -342,7 +374,8 @@ template <int KB, int VB> hipError_t launch_one(const DecodeArgs &a, hipStream_t
 {
     const int g = a.g, G = a.geom.G;
     size_t floats = 2 * kMaxGroupQ * kHeadDim + 2 * g * G + g * G * 4 + kMaxGroupQ * 4 + 4 * kMaxGroupQ +
-                    kMaxGroupQ * 2 + kHeadDim + G * 4;
+                    kMaxGroupQ * 2 + kHeadDim + g * G + G * 4;
+    if (a.geom.mean_mode == 1) floats += G * kHeadDim; // two binary16 mean tiles
     const size_t code_words = (size_t)G * kHeadDim * 8 / 32 > 32 * 64 ? (size_t)G * kHeadDim * 8 / 32 : 32 * 64;
     const size_t lds = (floats + 2 * code_words) * 4;
     static size_t granted = 0;

@@ -204,9 +204,16 @@ __global__ __launch_bounds__(kThreads) void flush_block_kernel(AppendArgs a)
     {
         const int c = tid & 127, half = tid >> 7;
         const int t_lo = half * (G / 2), t_hi = t_lo + G / 2;
-        const float m = meanv[c];
+        const float mch = meanv[c];
+        // cross-head mode: the mean of (token, channel) over the kv heads, written by
+        // xhead_mean_kernel just before this launch
+        const uint16_t *xm = gm.mean_mode == 1
+                                 ? (const uint16_t *)(a.layer + gm.xmean_off) +
+                                       (((long long)b * gm.NB + (a.first_block + fb)) * 2 + which) * G * kHeadDim
+                                 : nullptr;
         float mn = INFINITY, mx = -INFINITY;
         for (int t = t_lo; t < t_hi; t++) {
+            const float m = xm ? f16_val(xm[t * kHeadDim + c]) : mch;
             const float dv = x[t * kRowPad + c] - m;
             x[t * kRowPad + c] = dv;
             mn = dv < mn ? dv : mn;
@@ -291,6 +298,31 @@ __global__ __launch_bounds__(kThreads) void flush_block_kernel(AppendArgs a)
     }
 }
 
+// Cross-head mean (Eq. 1-2): for every token of a block and every channel, the mean over the kv
+// heads, m = f16_rne((x_0 + x_1 + ... + x_{H-1}) / H) with the sum taken in head order.
+// grid (blocks to flush, batch, K|V); written to the layer's mean plane.
+__global__ __launch_bounds__(kThreads) void xhead_mean_kernel(AppendArgs a)
+{
+    const LayerGeom &gm = a.geom;
+    const int G = gm.G, H = a.n_kv_heads;
+    const int fb = blockIdx.x, b = blockIdx.y, which = blockIdx.z;
+    const int bits = which == 0 ? gm.k_bits : gm.v_bits;
+    if (bits == 16) return;
+    uint16_t *dst = (uint16_t *)(a.layer + gm.xmean_off) +
+                    (((long long)b * gm.NB + (a.first_block + fb)) * 2 + which) * G * kHeadDim;
+    for (int i = threadIdx.x; i < G * (kHeadDim / 2); i += kThreads) {
+        const int t = i / (kHeadDim / 2), cp = i % (kHeadDim / 2);
+        float acc0 = 0.0f, acc1 = 0.0f;
+        for (int h = 0; h < H; h++) {
+            const uint32_t w = *(const uint32_t *)(src_row(a, which, b, h, fb * G + t) + 2 * cp);
+            acc0 = acc0 + widen16((uint16_t)(w & 0xFFFFu), gm.dtype);
+            acc1 = acc1 + widen16((uint16_t)(w >> 16), gm.dtype);
+        }
+        const uint32_t m0 = f16_rne(acc0 / (float)H), m1 = f16_rne(acc1 / (float)H);
+        *(uint32_t *)(dst + t * kHeadDim + 2 * cp) = m0 | (m1 << 16);
+    }
+}
+
 // Raw tail: input tokens [copy_src, copy_src + copy_n) -> residual rows [copy_dst, ...).
 __global__ __launch_bounds__(kThreads) void resid_copy_kernel(AppendArgs a)
 {
@@ -317,8 +349,14 @@ hipError_t launch_flush(const AppendArgs &a, hipStream_t s)
                        kHeadDim * sizeof(float) + 2 * (size_t)(v_items > kThreads ? v_items : kThreads) * sizeof(float);
     // grid.y is limited to 65535 entries
     if (U > 65535) return hipErrorInvalidValue;
-    dim3 grid(a.n_flush_blocks, U, 2);
     (void)hipGetLastError(); // drop any stale error left by earlier runtime calls of this thread
+    if (a.geom.mean_mode == 1) {
+        if (a.batch > 65535) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(xhead_mean_kernel, dim3(a.n_flush_blocks, a.batch, 2), dim3(kThreads), 0, s, a);
+        hipError_t e = note_launch(hipGetLastError());
+        if (e != hipSuccess) return e;
+    }
+    dim3 grid(a.n_flush_blocks, U, 2);
     hipLaunchKernelGGL(flush_block_kernel, grid, dim3(kThreads), lds, s, a);
     return note_launch(hipGetLastError());
 }

@@ -321,10 +321,6 @@ kv_status kv_quant_append(kv_cache *cache, int32_t layer, const void *k_new, con
     if (stride_h < c.head_dim || stride_t < 0 || stride_b < 0) return KV_E_BAD_CONFIG;
     const long long have = (long long)cache->packed[layer] + cache->resid[layer];
     if (have + n_new > c.max_tokens) return KV_E_CAPACITY;
-    if (c.mean_mode == KV_MEAN_CROSS_HEAD &&
-        (cache->geom[layer].k_bits != 16 || cache->geom[layer].v_bits != 16))
-        return KV_E_UNSUPPORTED;
-
     const int G = c.group_tokens, R = c.resid_cap;
     const int r_old = cache->resid[layer];
     const long long total = (long long)r_old + n_new;
@@ -424,8 +420,8 @@ kv_status kv_decode_attn_split(const kv_cache *cache, int32_t layer, const void 
     if (st != KV_OK) return st;
     if (!workspace || workspace_bytes < workspace_need(cache->cfg, a.n_splits)) return KV_E_WORKSPACE;
     if ((uintptr_t)workspace % 256) return KV_E_ALIGN;
-    if (cache->cfg.mean_mode == KV_MEAN_CROSS_HEAD && (a.geom.k_bits != 16 || a.geom.v_bits != 16))
-        return KV_E_UNSUPPORTED;
+    if (cache->cfg.mean_mode == KV_MEAN_CROSS_HEAD && a.geom.k_bits != 16 && a.geom.G > 64)
+        return KV_E_UNSUPPORTED; // the cross-head mean tiles of a 128-token block do not fit the kernel's LDS
     a.q = (const uint16_t *)q;
     a.ws = (float *)workspace;
     a.out = nullptr;

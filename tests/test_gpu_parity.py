@@ -85,7 +85,7 @@ def test_different_widths_for_keys_and_values(kv, oracle, kb, vb):
     check_attention(gpu, orc, 0, synth.make_q(3, 1, 4, 128, BF16), BF16)
 
 
-@pytest.mark.parametrize("mode", [CHAN, NONE])
+@pytest.mark.parametrize("mode", [CHAN, NONE, CROSS])
 @pytest.mark.parametrize("g", [1, 2, 4, 8])
 def test_mean_modes_and_query_groups(kv, oracle, mode, g):
     print("case modes mode=%d g=%d" % (mode, g), flush=True)
@@ -262,3 +262,33 @@ def test_full_cache_shape_sampled_units(kv, oracle, decode_path):
         err = float(np.max(np.abs(got - want)))
         print("  attention max-abs error %.3e" % err, flush=True)
         assert err <= 2e-3
+
+
+# ------------------------------------------------------------------ cross-head mean (Eq. 1-2 as printed)
+
+
+@pytest.mark.parametrize("bits", [2, 4, 8])
+@pytest.mark.parametrize("Hkv,g", [(1, 1), (8, 4), (2, 8)])
+@pytest.mark.parametrize("G", [32, 64])
+def test_cross_head_mean(kv, oracle, bits, Hkv, g, G):
+    """The paper's own centring: the mean over the kv heads, one binary16 row per token shared by
+    all heads.  With a single kv head the deviation is zero and the cache recovers fp16 inputs."""
+    print("case cross_head bits=%d Hkv=%d g=%d G=%d" % (bits, Hkv, g, G), flush=True)
+    T = 3 * G + 7
+    gpu, orc = make_pair(kv, oracle, B=2, Hq=Hkv * g, Hkv=Hkv, T_max=4 * G, G=G, Gc=G, dtype=F16, mode=CROSS,
+                         k_bits=(bits,))
+    k, v = synth.make_kv(300 + bits + Hkv, 2, T, Hkv, 128, F16)
+    append_both(gpu, orc, 0, k, v, F16, chunks=[2 * G + 3, 1, 1, G - 5 + 7])
+    check_bytes(gpu, orc, 0)
+    check_attention(gpu, orc, 0, synth.make_q(bits, 2, Hkv * g, 128, F16), F16)
+
+
+def test_cross_head_mean_mixed_layers_bf16(kv, oracle):
+    print("case cross_head_mixed", flush=True)
+    bits = (4, 16, 2)
+    gpu, orc = make_pair(kv, oracle, L=3, B=1, Hq=32, Hkv=8, T_max=512, dtype=BF16, mode=CROSS, k_bits=bits)
+    for l in range(3):
+        k, v = synth.make_kv(400 + l, 1, 300, 8, 128, BF16)
+        append_both(gpu, orc, l, k, v, BF16)
+        check_bytes(gpu, orc, l)
+        check_attention(gpu, orc, l, synth.make_q(l, 1, 32, 128, BF16), BF16)
