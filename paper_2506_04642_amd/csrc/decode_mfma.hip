@@ -7,10 +7,12 @@
 // but the two contractions over codes run as int8 matrix products.  The small operand
 // (q_c s_c per block, p_t s_tg per 64-token chunk) is converted to 23-bit fixed point against a
 // power-of-two bound and split into three signed bytes ("limbs"); the 16 rows of the matrix
-// instruction hold (query head, limb) for up to four query heads.  The codes are the other
-// operand: one shift and one mask turn a 32-bit word of the cache into four int8 codes, which is
-// why the storage format interleaves fields bytewise.  Products and sums are exact in int32; the
-// only rounding is the fixed-point conversion (relative 2^-23 of the chunk's largest weight).
+// instruction hold (query head, limb) for four query heads, and a kv head with more than four
+// query heads is served as two such head groups that share the unpacked codes.  The codes are
+// the other operand: one shift and one mask turn a 32-bit word of the cache into four int8
+// codes, which is why the storage format interleaves fields bytewise.  Products and sums are
+// exact in int32; the only rounding is the fixed-point conversion (relative 2^-23 of the chunk's
+// largest weight).
 //
 // Work split: one workgroup (NW waves) per (sequence, kv head, split).  Each wave owns every
 // NW-th 64-token chunk of the split and keeps its own online-softmax state; the states are
@@ -24,11 +26,11 @@
 // registers, immediately issues the fetch of its next chunk into the same buffer, and only then
 // computes, so the HBM latency of chunk i+1 is covered by the arithmetic of chunk i.
 //
-// Lane roles inside a wave (lane = 16*row + n, quad position a = n & 3, quad index vq = n >> 2):
-//   matrix output      lane (row, n): query head `row`, limbs in the four accumulator registers;
-//                      column n = token n of a 16-token tile (keys) or channel n of a 16-channel
-//                      tile (values).
-//   key-side producer  lane (row, vq, a): head `row`, channels 32*vq + 16*ph + 4*a + {0..3}, ph=0,1.
+// Lane roles inside a wave (lane = 16*row + n, quad position qa = n & 3, quad index vq = n >> 2):
+//   matrix output      lane (row, n): query head 4*hg + row, limbs in the four accumulator
+//                      registers; column n = token n of a 16-token tile (keys) or channel n of a
+//                      16-channel tile (values).
+//   key-side producer  lane (row, vq, qa): head 4*hg + row, channels 32*vq + 16*ph + 4*qa + {0..3}.
 //   matrix operands    lane (row, n): operand row / column n, 16 consecutive k-slots of group `row`.
 #include "tadakv_internal.h"
 #include <hip/hip_fp16.h>
@@ -51,7 +53,8 @@ template <int CTRL> __device__ __forceinline__ float dpp_f(float x)
 {
     return __uint_as_float(dpp_u<CTRL>(__float_as_uint(x)));
 }
-// quad_perm [1,0,3,2] = 0xB1, [2,3,0,1] = 0x4E, row_half_mirror = 0x141, row_mirror = 0x140
+// quad_perm [1,0,3,2] = 0xB1, [2,3,0,1] = 0x4E, row_half_mirror = 0x141, row_mirror = 0x140:
+// after the four steps every lane of a row of 16 holds the row's total
 __device__ __forceinline__ float row_sum(float x)
 {
     x += dpp_f<0xB1>(x);
@@ -68,7 +71,6 @@ __device__ __forceinline__ float row_max(float x)
     x = fmaxf(x, dpp_f<0x140>(x));
     return x;
 }
-
 __device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b)
 {
     typedef unsigned short us2 __attribute__((ext_vector_type(2)));
@@ -94,14 +96,13 @@ __device__ __forceinline__ float h_lo(uint32_t w) { return __half2float(__ushort
 __device__ __forceinline__ float h_hi(uint32_t w) { return __half2float(__ushort_as_half((uint16_t)(w >> 16))); }
 __device__ __forceinline__ half2_t as_h2(uint32_t w) { return __builtin_bit_cast(half2_t, w); }
 
-// power of two strictly above x (x >= 0), never below 2^lo_exp; and its reciprocal
+// power of two strictly above x (x >= 0) but at least 2 * floor_v; and its reciprocal
 __device__ __forceinline__ void pow2_above(float x, float floor_v, float &p, float &inv)
 {
     const uint32_t b = (__float_as_uint(fmaxf(x, floor_v)) & 0x7F800000u) + 0x00800000u;
     p = __uint_as_float(b);
     inv = __uint_as_float(0x7F000000u - b);
 }
-
 
 // waits for this wave's outstanding LDS traffic and keeps the compiler from moving LDS accesses
 // across; enough to hand data between lanes of one wave through LDS
@@ -111,8 +112,13 @@ __device__ __forceinline__ v4i mfma(v4i a, v4i b, v4i c)
 {
     return __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, c, 0, 0, 0);
 }
+// three signed-byte limbs (weights 1, 256, 65536) -> float; every partial value is exact
+__device__ __forceinline__ float limbs_to_float(v4i acc)
+{
+    return (float)acc.x + 256.0f * (float)acc.y + 65536.0f * (float)acc.z;
+}
 
-// running softmax state of one lane: head `row`; O for channels 16*ct + n
+// running softmax state of one lane for one query head; O for channels 16*ct + n
 struct State {
     float M, l;      // running max (exp2 domain), lane-partial sum of weights
     float O[8];      // output accumulators
@@ -179,7 +185,32 @@ __device__ __forceinline__ void stage_issue(const unsigned char *src, uint32_t *
 }
 __device__ __forceinline__ void stage_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
-template <int B, int G, int GC, bool MEAN, int NW>
+// int8 operand of the matrix instruction for the codes held in a lane
+template <int B> struct CodeOps;
+template <> struct CodeOps<4> { // two words = one tile line of 16 codes
+    static __device__ __forceinline__ v4i line(uint32_t w0, uint32_t w1)
+    {
+        return v4i{(int)(w0 & kM4), (int)((w0 >> 4) & kM4), (int)(w1 & kM4), (int)((w1 >> 4) & kM4)};
+    }
+};
+template <> struct CodeOps<2> { // one word = one tile line
+    static __device__ __forceinline__ v4i line(uint32_t w)
+    {
+        return v4i{(int)(w & kM2), (int)((w >> 2) & kM2), (int)((w >> 4) & kM2), (int)((w >> 6) & kM2)};
+    }
+};
+template <> struct CodeOps<8> { // four words = one tile line; split into nibbles to stay inside int8
+    static __device__ __forceinline__ v4i lo(uint4 w)
+    {
+        return v4i{(int)(w.x & kM4), (int)(w.y & kM4), (int)(w.z & kM4), (int)(w.w & kM4)};
+    }
+    static __device__ __forceinline__ v4i hi(uint4 w)
+    {
+        return v4i{(int)((w.x >> 4) & kM4), (int)((w.y >> 4) & kM4), (int)((w.z >> 4) & kM4), (int)((w.w >> 4) & kM4)};
+    }
+};
+
+template <int B, int G, int GC, bool MEAN, int NW, int NHG>
 __global__ __launch_bounds__(64 * NW) void decode_split_mfma_kernel(DecodeArgs a)
 {
     typedef RecLayout<B, G, GC, MEAN> RL;
@@ -192,10 +223,12 @@ __global__ __launch_bounds__(64 * NW) void decode_split_mfma_kernel(DecodeArgs a
     constexpr int REC = RL::REC;
     constexpr int CB = NBC * REC;          // bytes of one chunk
     constexpr int STAGE_DW = CB / 4;       // staging buffer of a wave
-    constexpr int OPER_DW = 1024;          // 4 KiB: key operands, later reused for value operands
-    static_assert(NBC * 2 * 256 <= OPER_DW && NG * 256 <= OPER_DW, "operand scratch");
+    // operand scratch: key operands [NBC][NHG][2 phases][64 lanes][4], later reused for the value
+    // operands [NHG][NG][64 lanes][4]
+    constexpr int AK_DW = NBC * NHG * 512, AV_DW = NHG * NG * 256;
+    constexpr int OPER_DW = AK_DW > AV_DW ? AK_DW : AV_DW;
     constexpr int WAVE_DW = STAGE_DW + OPER_DW;
-    constexpr int RESID_DW = 20480 / 4;    // the residual pass of wave 0 takes this much of the block's LDS
+    constexpr int RESID_DW = 24576 / 4;    // the residual pass of wave 0 takes this much of the block's LDS
     constexpr int LDS_DW = NW * WAVE_DW > RESID_DW ? NW * WAVE_DW : RESID_DW;
 
     __shared__ __attribute__((aligned(16))) uint32_t lds_all[LDS_DW];
@@ -211,7 +244,6 @@ __global__ __launch_bounds__(64 * NW) void decode_split_mfma_kernel(DecodeArgs a
     const int sp = blockIdx.x, u = blockIdx.y;
     const int b = u / a.n_kv_heads, h = u % a.n_kv_heads;
     const int g = a.g;
-    constexpr bool has_kmean = MEAN, has_vmean = MEAN; // per-channel block means present
 
     // rows 4i+3 of the operands (the unused fourth limb) must read as zero
     for (int i = lane; i < OPER_DW; i += 64) ak[i] = 0u;
@@ -226,7 +258,7 @@ __global__ __launch_bounds__(64 * NW) void decode_split_mfma_kernel(DecodeArgs a
     const int n_chunks = sp < chunks_total ? (chunks_total - sp + ns - 1) / ns : 0;
     const int w0 = sp * NBC;          // first block of local chunk 0
     const int cstride = ns * NBC;     // blocks between consecutive local chunks
-    const unsigned char *unit_base = a.layer + (long long)u * gm.NB * gm.rec_bytes;
+    const unsigned char *unit_base = a.layer + (long long)u * gm.NB * REC;
 
     auto issue = [&](int ci) {
         const int blk0 = w0 + ci * cstride;
@@ -242,121 +274,125 @@ __global__ __launch_bounds__(64 * NW) void decode_split_mfma_kernel(DecodeArgs a
     };
     if (wave < n_chunks) issue(wave);
 
-
-
-    // ---- query of head `row`: this lane's eight channels, as fixed-point factors and as halves
-    float qf[2][4];      // q of this lane's eight channels, widened (exact)
-    half2_t qh[2][2];    // the same as binary16 pairs for the zero / mean dot products
-    float three_qb;      // 3 qb, qb = power of two above max |q| of the head
-    float inv_kf_base;   // qb 2^-22 log2(e)/sqrt(d): one fixed-point step, up to the scale bound
-    {
-        const uint16_t *qp = a.q + ((long long)b * a.n_q_heads + h * g + (row < g ? row : 0)) * kHeadDim;
+    // ---- query of heads 4*hg + row: this lane's eight channels, widened and as binary16 pairs
+    float qf[NHG][2][4];      // q, widened (exact)
+    half2_t qh[NHG][2][2];    // the same as binary16 pairs for the zero / mean dot products
+    float three_qb[NHG];      // 3 qb, qb = power of two above max |q| of the head
+    float inv_kf_base[NHG];   // qb 2^-22 log2(e)/sqrt(d): one fixed-point step, up to the scale bound
+#pragma unroll
+    for (int hg = 0; hg < NHG; hg++) {
+        const int head = 4 * hg + row;
+        const uint16_t *qp = a.q + ((long long)b * a.n_q_heads + h * g + (head < g ? head : 0)) * kHeadDim;
         float qmax = 0.0f;
 #pragma unroll
         for (int ph = 0; ph < 2; ph++)
 #pragma unroll
             for (int y = 0; y < 4; y++) {
                 const int c = 32 * vq + 16 * ph + 4 * qa + y;
-                qf[ph][y] = row < g ? widen16(qp[c], gm.dtype) : 0.0f;
-                qmax = fmaxf(qmax, fabsf(qf[ph][y]));
+                qf[hg][ph][y] = head < g ? widen16(qp[c], gm.dtype) : 0.0f;
+                qmax = fmaxf(qmax, fabsf(qf[hg][ph][y]));
             }
         qmax = row_max(qmax);
         float qb, inv_qb;
         pow2_above(qmax, 0x1p-60f, qb, inv_qb);
-        three_qb = 3.0f * qb;
-        inv_kf_base = qb * 0x1p-22f * kScoreScale;
+        three_qb[hg] = 3.0f * qb;
+        inv_kf_base[hg] = qb * 0x1p-22f * kScoreScale;
 #pragma unroll
         for (int ph = 0; ph < 2; ph++) {
-            qh[ph][0] = half2_t{(_Float16)qf[ph][0], (_Float16)qf[ph][1]};
-            qh[ph][1] = half2_t{(_Float16)qf[ph][2], (_Float16)qf[ph][3]};
+            qh[hg][ph][0] = half2_t{(_Float16)qf[hg][ph][0], (_Float16)qf[hg][ph][1]};
+            qh[hg][ph][1] = half2_t{(_Float16)qf[hg][ph][2], (_Float16)qf[hg][ph][3]};
         }
     }
-    {
-        State st;
-        st.M = -INFINITY;
-        st.l = 0.0f;
-#pragma unroll
-        for (int k = 0; k < 8; k++) st.O[k] = 0.0f;
-#pragma unroll
-        for (int k = 0; k < 4; k++) st.Zp[k] = 0.0f;
 
+    State st[NHG];
+#pragma unroll
+    for (int hg = 0; hg < NHG; hg++) {
+        st[hg].M = -INFINITY;
+        st[hg].l = 0.0f;
+#pragma unroll
+        for (int k = 0; k < 8; k++) st[hg].O[k] = 0.0f;
+#pragma unroll
+        for (int k = 0; k < 4; k++) st[hg].Zp[k] = 0.0f;
+    }
+    wave_lds_fence();
+
+    const uint32_t sel1 = (qa & 1) ? 0x03070105u : 0x06020400u;
+    const uint32_t sel2 = (qa & 2) ? 0x03020706u : 0x05040100u;
+
+    for (int ci = wave; ci < n_chunks; ci += NW) {
+        const int blk0 = w0 + ci * cstride;
+        bool blk_ok[NBC];
+#pragma unroll
+        for (int bi = 0; bi < NBC; bi++) blk_ok[bi] = blk0 + bi < b_end;
+        // block and tile-in-block of chunk tile `row` (this lane's token group on the value side)
+        const unsigned char *sb8 = (const unsigned char *)stage;
+        const unsigned char *rec_row = sb8 + (row / TPB) * REC;
+        const int tt_row = row % TPB;
+
+        // ---- staged chunk -> registers
+        stage_wait();
+        uint4 kc[NKL], vc[NVL];
+#pragma unroll
+        for (int i = 0; i < NKL; i++) {
+            int bi, off;
+            if (B == 4) { bi = i / TPB; off = (i % TPB) * 64; }
+            else if (B == 2) { bi = (2 * i) / TPB; off = (((2 * i) % TPB) / 2) * 64; }
+            else { bi = (i / 2) / TPB; off = (((i / 2) % TPB) * 2 + (i & 1)) * 64; }
+            kc[i] = *(const uint4 *)(sb8 + bi * REC + RL::K_CODES + (off + lane) * 16);
+        }
+#pragma unroll
+        for (int i = 0; i < NVL; i++)
+            vc[i] = *(const uint4 *)(rec_row + RL::V_CODES + ((i * TPB + tt_row) * 16 + n) * 16);
+        uint32_t vm[4][NG];
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+            const unsigned char *p = sb8 + (k / TPB) * REC + RL::V_META + (((k % TPB) * 16 + n) * NG) * 4;
+            if (NG == 4) {
+                const uint4 t = *(const uint4 *)p;
+                vm[k][0] = t.x; vm[k][1 % NG] = t.y; vm[k][2 % NG] = t.z; vm[k][3 % NG] = t.w;
+            } else {
+                const uint2 t = *(const uint2 *)p;
+                vm[k][0] = t.x; vm[k][1 % NG] = t.y;
+            }
+        }
+        uint2 ks[NBC][2], kz[NBC][2], km[NBC][2];
+#pragma unroll
+        for (int bi = 0; bi < NBC; bi++)
+#pragma unroll
+            for (int ph = 0; ph < 2; ph++) {
+                const int co = (32 * vq + 16 * ph + 4 * qa) * 2;
+                ks[bi][ph] = *(const uint2 *)(sb8 + bi * REC + RL::K_SCALE + co);
+                kz[bi][ph] = *(const uint2 *)(sb8 + bi * REC + RL::K_ZERO + co);
+                km[bi][ph] = MEAN ? *(const uint2 *)(sb8 + bi * REC + RL::K_MEAN + co) : uint2{0u, 0u};
+            }
+        uint16_t vmean[NBC][8];
+#pragma unroll
+        for (int bi = 0; bi < NBC; bi++)
+#pragma unroll
+            for (int ct = 0; ct < 8; ct++)
+                vmean[bi][ct] = MEAN ? *(const uint16_t *)(sb8 + bi * REC + RL::V_MEAN + (16 * ct + n) * 2) : (uint16_t)0;
+        // every read of the staging buffer has returned: start fetching this wave's next chunk
         wave_lds_fence();
+        if (ci + NW < n_chunks) issue(ci + NW);
 
-        const uint32_t sel1 = (qa & 1) ? 0x03070105u : 0x06020400u;
-        const uint32_t sel2 = (qa & 2) ? 0x03020706u : 0x05040100u;
-
-        for (int ci = wave; ci < n_chunks; ci += NW) {
-            const int blk0 = w0 + ci * cstride;
-            bool blk_ok[NBC];
+        // ---- key side: q*scale as limbs -> LDS; zero/mean term
+        float inv_kf[NHG][NBC], beta[NHG][NBC];
 #pragma unroll
-            for (int bi = 0; bi < NBC; bi++) blk_ok[bi] = blk0 + bi < b_end;
-            // block and tile-in-block of chunk tile `row` (this lane's token group on the value side)
-            const unsigned char *sb8 = (const unsigned char *)stage;
-            const unsigned char *rec_row = sb8 + (row / TPB) * REC;
-            const int tt_row = row % TPB;
-
-            // ---- staged chunk -> registers
-            stage_wait();
-            uint4 kc[NKL], vc[NVL];
+        for (int bi = 0; bi < NBC; bi++) {
+            // scales are non-negative binary16 values: their bit patterns order like the values,
+            // so the largest is found with packed 16-bit integer maxima on the raw words
+            uint32_t smw = pk_max_u16(pk_max_u16(ks[bi][0].x, ks[bi][0].y), pk_max_u16(ks[bi][1].x, ks[bi][1].y));
+            smw = row_pk_max_u16(smw);
+            const float smax = fmaxf(h_lo(smw), h_hi(smw));
+            float sb, inv_sb;
+            pow2_above(smax, 0x1p-40f, sb, inv_sb);
 #pragma unroll
-            for (int i = 0; i < NKL; i++) {
-                int bi, off;
-                if (B == 4) { bi = i / TPB; off = (i % TPB) * 64; }
-                else if (B == 2) { bi = (2 * i) / TPB; off = (((2 * i) % TPB) / 2) * 64; }
-                else { bi = (i / 2) / TPB; off = (((i / 2) % TPB) * 2 + (i & 1)) * 64; }
-                kc[i] = *(const uint4 *)(sb8 + bi * REC + RL::K_CODES + (off + lane) * 16);
-            }
-#pragma unroll
-            for (int i = 0; i < NVL; i++)
-                vc[i] = *(const uint4 *)(rec_row + RL::V_CODES + ((i * TPB + tt_row) * 16 + n) * 16);
-            uint32_t vm[4][NG];
-#pragma unroll
-            for (int k = 0; k < 4; k++) {
-                const unsigned char *p = sb8 + (k / TPB) * REC + RL::V_META + (((k % TPB) * 16 + n) * NG) * 4;
-                if (NG == 4) {
-                    const uint4 t = *(const uint4 *)p;
-                    vm[k][0] = t.x; vm[k][1 % NG] = t.y; vm[k][2 % NG] = t.z; vm[k][3 % NG] = t.w;
-                } else {
-                    const uint2 t = *(const uint2 *)p;
-                    vm[k][0] = t.x; vm[k][1 % NG] = t.y;
-                }
-            }
-            uint2 ks[NBC][2], kz[NBC][2], km[NBC][2];
-#pragma unroll
-            for (int bi = 0; bi < NBC; bi++)
-#pragma unroll
-                for (int ph = 0; ph < 2; ph++) {
-                    const int co = (32 * vq + 16 * ph + 4 * qa) * 2;
-                    ks[bi][ph] = *(const uint2 *)(sb8 + bi * REC + RL::K_SCALE + co);
-                    kz[bi][ph] = *(const uint2 *)(sb8 + bi * REC + RL::K_ZERO + co);
-                    km[bi][ph] = has_kmean ? *(const uint2 *)(sb8 + bi * REC + RL::K_MEAN + co) : uint2{0u, 0u};
-                }
-            uint16_t vmean[NBC][8];
-#pragma unroll
-            for (int bi = 0; bi < NBC; bi++)
-#pragma unroll
-                for (int ct = 0; ct < 8; ct++)
-                    vmean[bi][ct] = has_vmean ? *(const uint16_t *)(sb8 + bi * REC + RL::V_MEAN + (16 * ct + n) * 2) : (uint16_t)0;
-            // every read of the staging buffer has returned: start fetching this wave's next chunk
-            wave_lds_fence();
-            if (ci + NW < n_chunks) issue(ci + NW);
-
-            // ---- key side: q*scale as limbs -> LDS; zero/mean term
-            float inv_kf[NBC], beta[NBC];
-#pragma unroll
-            for (int bi = 0; bi < NBC; bi++) {
-                // scales are non-negative binary16 values: their bit patterns order like the values,
-                // so the largest is found with packed 16-bit integer maxima on the raw words
-                uint32_t smw = pk_max_u16(pk_max_u16(ks[bi][0].x, ks[bi][0].y), pk_max_u16(ks[bi][1].x, ks[bi][1].y));
-                smw = row_pk_max_u16(smw);
-                const float smax = fmaxf(h_lo(smw), h_hi(smw));
-                float sb, inv_sb;
-                pow2_above(smax, 0x1p-40f, sb, inv_sb);
-                inv_kf[bi] = inv_kf_base * sb;
+            for (int hg = 0; hg < NHG; hg++) {
+                inv_kf[hg][bi] = inv_kf_base[hg] * sb;
                 // Adding 3 qb sb (1.5 * 2^E with 2^E = 2 qb sb > 2 |q s|) puts round(q s / ulp) into
                 // the low mantissa bits of the sum, ulp = qb sb 2^-22: one fused multiply-add per
                 // element does the scaling, the rounding and the float -> integer conversion.
-                const float magic = three_qb * sb;
+                const float magic = three_qb[hg] * sb;
                 const uint32_t cfix = 0x80808080u - __float_as_uint(magic);
                 float bacc = 0.0f;
 #pragma unroll
@@ -366,8 +402,9 @@ __global__ __launch_bounds__(64 * NW) void decode_split_mfma_kernel(DecodeArgs a
                     for (int y = 0; y < 4; y++) {
                         const uint32_t sw = (y & 2) ? ks[bi][ph].y : ks[bi][ph].x;
                         const float sv = (y & 1) ? h_hi(sw) : h_lo(sw);
-                        X[y] = (__float_as_uint(__builtin_fmaf(qf[ph][y], sv, magic)) + cfix) ^ 0x80808080u;
+                        X[y] = (__float_as_uint(__builtin_fmaf(qf[hg][ph][y], sv, magic)) + cfix) ^ 0x80808080u;
                     }
+                    // 4 x 4 byte transpose: limb L of the lane's four consecutive channels
                     const uint32_t U = __builtin_amdgcn_perm(X[1], X[0], 0x05010400u);
                     const uint32_t U2 = __builtin_amdgcn_perm(X[1], X[0], 0x07030602u);
                     const uint32_t W = __builtin_amdgcn_perm(X[3], X[2], 0x05010400u);
@@ -375,73 +412,77 @@ __global__ __launch_bounds__(64 * NW) void decode_split_mfma_kernel(DecodeArgs a
                     const uint32_t Y0 = __builtin_amdgcn_perm(W, U, 0x05040100u);
                     const uint32_t Y1 = __builtin_amdgcn_perm(W, U, 0x07060302u);
                     const uint32_t Y2 = __builtin_amdgcn_perm(W2, U2, 0x05040100u);
-                    uint32_t *dst = ak + bi * 512 + ((ph * 4 + vq) * 16 + 4 * row) * 4 + qa;
+                    uint32_t *dst = ak + (bi * NHG + hg) * 512 + ((ph * 4 + vq) * 16 + 4 * row) * 4 + qa;
                     dst[0] = Y0;
                     dst[4] = Y1;
                     dst[8] = Y2;
-                    bacc = __builtin_amdgcn_fdot2(qh[ph][0], as_h2(kz[bi][ph].x), bacc, false);
-                    bacc = __builtin_amdgcn_fdot2(qh[ph][1], as_h2(kz[bi][ph].y), bacc, false);
-                    bacc = __builtin_amdgcn_fdot2(qh[ph][0], as_h2(km[bi][ph].x), bacc, false);
-                    bacc = __builtin_amdgcn_fdot2(qh[ph][1], as_h2(km[bi][ph].y), bacc, false);
+                    bacc = __builtin_amdgcn_fdot2(qh[hg][ph][0], as_h2(kz[bi][ph].x), bacc, false);
+                    bacc = __builtin_amdgcn_fdot2(qh[hg][ph][1], as_h2(kz[bi][ph].y), bacc, false);
+                    bacc = __builtin_amdgcn_fdot2(qh[hg][ph][0], as_h2(km[bi][ph].x), bacc, false);
+                    bacc = __builtin_amdgcn_fdot2(qh[hg][ph][1], as_h2(km[bi][ph].y), bacc, false);
                 }
-                beta[bi] = row_sum(bacc) * kScoreScale;
+                beta[hg][bi] = row_sum(bacc) * kScoreScale;
             }
-            wave_lds_fence();
+        }
+        wave_lds_fence();
 
-            // ---- key matrix products -> scores
-            float s[4];
+        // ---- key matrix products -> scores
+        float s[NHG][4];
 #pragma unroll
-            for (int k = 0; k < 4; k++) {
-                const int bi = k / TPB;
-                const v4i a0 = *(const v4i *)(ak + bi * 512 + ((0 * 4 + row) * 16 + n) * 4);
-                const v4i a1 = *(const v4i *)(ak + bi * 512 + ((1 * 4 + row) * 16 + n) * 4);
-                v4i acc = {0, 0, 0, 0};
-                if (B == 4) {
-                    const uint4 w = kc[k];
-                    const v4i b0 = {(int)(w.x & kM4), (int)((w.x >> 4) & kM4), (int)(w.y & kM4), (int)((w.y >> 4) & kM4)};
-                    const v4i b1 = {(int)(w.z & kM4), (int)((w.z >> 4) & kM4), (int)(w.w & kM4), (int)((w.w >> 4) & kM4)};
-                    acc = mfma(a0, b0, acc);
-                    acc = mfma(a1, b1, acc);
-                } else if (B == 2) {
-                    const uint4 w = kc[k >> 1];
-                    const uint32_t w0_ = (k & 1) ? w.z : w.x, w1_ = (k & 1) ? w.w : w.y;
-                    const v4i b0 = {(int)(w0_ & kM2), (int)((w0_ >> 2) & kM2), (int)((w0_ >> 4) & kM2), (int)((w0_ >> 6) & kM2)};
-                    const v4i b1 = {(int)(w1_ & kM2), (int)((w1_ >> 2) & kM2), (int)((w1_ >> 4) & kM2), (int)((w1_ >> 6) & kM2)};
-                    acc = mfma(a0, b0, acc);
-                    acc = mfma(a1, b1, acc);
-                } else {
-                    const uint4 wa = kc[2 * k], wb = kc[2 * k + 1];
-                    const v4i lo0 = {(int)(wa.x & kM4), (int)(wa.y & kM4), (int)(wa.z & kM4), (int)(wa.w & kM4)};
-                    const v4i hi0 = {(int)((wa.x >> 4) & kM4), (int)((wa.y >> 4) & kM4), (int)((wa.z >> 4) & kM4), (int)((wa.w >> 4) & kM4)};
-                    const v4i lo1 = {(int)(wb.x & kM4), (int)(wb.y & kM4), (int)(wb.z & kM4), (int)(wb.w & kM4)};
-                    const v4i hi1 = {(int)((wb.x >> 4) & kM4), (int)((wb.y >> 4) & kM4), (int)((wb.z >> 4) & kM4), (int)((wb.w >> 4) & kM4)};
-                    v4i alo = {0, 0, 0, 0}, ahi = {0, 0, 0, 0};
-                    alo = mfma(a0, lo0, alo);
-                    alo = mfma(a1, lo1, alo);
-                    ahi = mfma(a0, hi0, ahi);
-                    ahi = mfma(a1, hi1, ahi);
-                    acc = alo + ahi * 16;
+        for (int k = 0; k < 4; k++) {
+            const int bi = k / TPB;
+            v4i a0[NHG], a1[NHG];
+#pragma unroll
+            for (int hg = 0; hg < NHG; hg++) {
+                a0[hg] = *(const v4i *)(ak + (bi * NHG + hg) * 512 + ((0 * 4 + row) * 16 + n) * 4);
+                a1[hg] = *(const v4i *)(ak + (bi * NHG + hg) * 512 + ((1 * 4 + row) * 16 + n) * 4);
+            }
+            v4i acc[NHG];
+            if (B == 4) {
+                const uint4 w = kc[k];
+                const v4i b0 = CodeOps<4>::line(w.x, w.y), b1 = CodeOps<4>::line(w.z, w.w);
+#pragma unroll
+                for (int hg = 0; hg < NHG; hg++) acc[hg] = mfma(a1[hg], b1, mfma(a0[hg], b0, v4i{0, 0, 0, 0}));
+            } else if (B == 2) {
+                const uint4 w = kc[k >> 1];
+                const v4i b0 = CodeOps<2>::line((k & 1) ? w.z : w.x), b1 = CodeOps<2>::line((k & 1) ? w.w : w.y);
+#pragma unroll
+                for (int hg = 0; hg < NHG; hg++) acc[hg] = mfma(a1[hg], b1, mfma(a0[hg], b0, v4i{0, 0, 0, 0}));
+            } else {
+                const uint4 wa = kc[2 * k], wb = kc[2 * k + 1];
+                const v4i lo0 = CodeOps<8>::lo(wa), hi0 = CodeOps<8>::hi(wa);
+                const v4i lo1 = CodeOps<8>::lo(wb), hi1 = CodeOps<8>::hi(wb);
+#pragma unroll
+                for (int hg = 0; hg < NHG; hg++) {
+                    const v4i alo = mfma(a1[hg], lo1, mfma(a0[hg], lo0, v4i{0, 0, 0, 0}));
+                    const v4i ahi = mfma(a1[hg], hi1, mfma(a0[hg], hi0, v4i{0, 0, 0, 0}));
+                    acc[hg] = alo + ahi * 16;
                 }
-                const float dotv = (float)acc.x + 256.0f * (float)acc.y + 65536.0f * (float)acc.z;
-                s[k] = blk_ok[bi] ? dotv * inv_kf[bi] + beta[bi] : -INFINITY;
             }
-
-            // ---- softmax bookkeeping
-            float p[4], alpha, wc;
-            softmax_chunk(s, st, p, alpha, wc);
-
-            // ---- value side: p*scale as limbs -> LDS; zero term
-            uint32_t svw = 0u; // low halves: largest value scale of the chunk (high halves: unused)
 #pragma unroll
-            for (int k = 0; k < 4; k++)
+            for (int hg = 0; hg < NHG; hg++)
+                s[hg][k] = blk_ok[bi] ? limbs_to_float(acc[hg]) * inv_kf[hg][bi] + beta[hg][bi] : -INFINITY;
+        }
+
+        // ---- largest value scale of the chunk (the same for every head)
+        uint32_t svw = 0u; // low halves: scales (high halves, the zeros, are ignored)
 #pragma unroll
-                for (int gam = 0; gam < NG; gam++) svw = pk_max_u16(svw, vm[k][gam]);
-            svw = row_pk_max_u16(svw);
-            float sbv, inv_sbv;
-            pow2_above(h_lo(svw), 0x1p-40f, sbv, inv_sbv);
-            const float vmagic = 3.0f * sbv; // p <= 1, scale < sbv: same construction as on the key side
-            const uint32_t vfix = 0x80808080u - __float_as_uint(vmagic);
-            const float o_scale = wc * sbv * 0x1p-22f;
+        for (int k = 0; k < 4; k++)
+#pragma unroll
+            for (int gam = 0; gam < NG; gam++) svw = pk_max_u16(svw, vm[k][gam]);
+        svw = row_pk_max_u16(svw);
+        float sbv, inv_sbv;
+        pow2_above(h_lo(svw), 0x1p-40f, sbv, inv_sbv);
+        const float vmagic = 3.0f * sbv; // p <= 1, scale < sbv: same construction as on the key side
+        const uint32_t vfix = 0x80808080u - __float_as_uint(vmagic);
+
+        // ---- softmax bookkeeping; value side: p*scale as limbs -> LDS; zero and mean terms
+        float alpha[NHG], o_scale[NHG], psum_b[NHG][NBC];
+#pragma unroll
+        for (int hg = 0; hg < NHG; hg++) {
+            float p[4], wc;
+            softmax_chunk(s[hg], st[hg], p, alpha[hg], wc);
+            o_scale[hg] = wc * sbv * 0x1p-22f;
 #pragma unroll
             for (int gam = 0; gam < NG; gam++) {
                 float zsum = 0.0f;
@@ -455,157 +496,186 @@ __global__ __launch_bounds__(64 * NW) void decode_split_mfma_kernel(DecodeArgs a
                     const uint32_t T = __builtin_amdgcn_perm(P, X, sel1);
                     const uint32_t Q = dpp_u<0x4E>(T);
                     const uint32_t Y = __builtin_amdgcn_perm(Q, T, sel2);
-                    av[(gam * 4 + k) * 64 + (4 * row + qa) * 4 + vq] = Y;
+                    av[(hg * NG + gam) * 256 + k * 64 + (4 * row + qa) * 4 + vq] = Y;
                 }
-                st.Zp[gam] = st.Zp[gam] * alpha + wc * zsum;
+                st[hg].Zp[gam] = st[hg].Zp[gam] * alpha[hg] + wc * zsum;
             }
-            float psum_b[NBC];
 #pragma unroll
             for (int bi = 0; bi < NBC; bi++) {
                 float t = 0.0f;
 #pragma unroll
                 for (int k = bi * TPB; k < (bi + 1) * TPB; k++) t += p[k];
-                psum_b[bi] = has_vmean ? row_sum(t) * wc : 0.0f;
-            }
-            wave_lds_fence();
-
-            // ---- value matrix products -> output accumulators
-            v4i avr[NG];
-#pragma unroll
-            for (int gam = 0; gam < NG; gam++) avr[gam] = *(const v4i *)(av + gam * 256 + (row * 16 + n) * 4);
-#pragma unroll
-            for (int ct = 0; ct < 8; ct++) {
-                const v4i aop = avr[ct / TPG];
-                v4i acc = {0, 0, 0, 0};
-                if (B == 4) {
-                    const uint4 w = vc[ct >> 1];
-                    const uint32_t w0_ = (ct & 1) ? w.z : w.x, w1_ = (ct & 1) ? w.w : w.y;
-                    const v4i bo = {(int)(w0_ & kM4), (int)((w0_ >> 4) & kM4), (int)(w1_ & kM4), (int)((w1_ >> 4) & kM4)};
-                    acc = mfma(aop, bo, acc);
-                } else if (B == 2) {
-                    const uint4 w = vc[ct >> 2];
-                    const uint32_t ww = (ct & 3) == 0 ? w.x : ((ct & 3) == 1 ? w.y : ((ct & 3) == 2 ? w.z : w.w));
-                    const v4i bo = {(int)(ww & kM2), (int)((ww >> 2) & kM2), (int)((ww >> 4) & kM2), (int)((ww >> 6) & kM2)};
-                    acc = mfma(aop, bo, acc);
-                } else {
-                    const uint4 w = vc[ct];
-                    const v4i lo = {(int)(w.x & kM4), (int)(w.y & kM4), (int)(w.z & kM4), (int)(w.w & kM4)};
-                    const v4i hi = {(int)((w.x >> 4) & kM4), (int)((w.y >> 4) & kM4), (int)((w.z >> 4) & kM4), (int)((w.w >> 4) & kM4)};
-                    v4i alo = {0, 0, 0, 0}, ahi = {0, 0, 0, 0};
-                    alo = mfma(aop, lo, alo);
-                    ahi = mfma(aop, hi, ahi);
-                    acc = alo + ahi * 16;
-                }
-                const float dotv = (float)acc.x + 256.0f * (float)acc.y + 65536.0f * (float)acc.z;
-                float o = st.O[ct] * alpha + dotv * o_scale;
-#pragma unroll
-                for (int bi = 0; bi < NBC; bi++)
-                    o += __half2float(__ushort_as_half(vmean[bi][ct])) * psum_b[bi];
-                st.O[ct] = o;
+                psum_b[hg][bi] = MEAN ? row_sum(t) * wc : 0.0f;
             }
         }
+        wave_lds_fence();
 
-        // ---- raw residual tokens (Sec. 3.3): wave 0 of the split that owns them
-        const bool has_resid = a.r > 0 && sp == chunks_total % ns; // the split next in turn takes the raw tail
-        if (has_resid) {
-            __syncthreads(); // every wave is out of its main loop; wave 0 may take all of LDS
-            if (wave == 0) {
-                unsigned char *L = (unsigned char *)lds_all;
-                constexpr int RS = 264; // bytes per staged row (33 * 8)
-                unsigned char *kraw = L, *vraw = L + 32 * RS;
-                float *qs = (float *)(L + 64 * RS);       // [4][128]
-                float *spart = qs + 4 * 128;               // [2][4][32]
-                float *pl = spart + 2 * 4 * 32;            // [4][32]
-                // q of the unit (undo the fixed-point scaling: exact)
+        // ---- value matrix products -> output accumulators
+        v4i avr[NHG][NG];
 #pragma unroll
-                for (int ph = 0; ph < 2; ph++) {
-                    qs[row * 128 + 32 * vq + 16 * ph + 4 * qa + 0] = (float)qh[ph][0].x;
-                    qs[row * 128 + 32 * vq + 16 * ph + 4 * qa + 1] = (float)qh[ph][0].y;
-                    qs[row * 128 + 32 * vq + 16 * ph + 4 * qa + 2] = (float)qh[ph][1].x;
-                    qs[row * 128 + 32 * vq + 16 * ph + 4 * qa + 3] = (float)qh[ph][1].y;
+        for (int hg = 0; hg < NHG; hg++)
+#pragma unroll
+            for (int gam = 0; gam < NG; gam++)
+                avr[hg][gam] = *(const v4i *)(av + (hg * NG + gam) * 256 + (row * 16 + n) * 4);
+#pragma unroll
+        for (int ct = 0; ct < 8; ct++) {
+            v4i acc[NHG];
+            if (B == 4) {
+                const uint4 w = vc[ct >> 1];
+                const v4i bo = CodeOps<4>::line((ct & 1) ? w.z : w.x, (ct & 1) ? w.w : w.y);
+#pragma unroll
+                for (int hg = 0; hg < NHG; hg++) acc[hg] = mfma(avr[hg][ct / TPG], bo, v4i{0, 0, 0, 0});
+            } else if (B == 2) {
+                const uint4 w = vc[ct >> 2];
+                const uint32_t ww = (ct & 3) == 0 ? w.x : ((ct & 3) == 1 ? w.y : ((ct & 3) == 2 ? w.z : w.w));
+                const v4i bo = CodeOps<2>::line(ww);
+#pragma unroll
+                for (int hg = 0; hg < NHG; hg++) acc[hg] = mfma(avr[hg][ct / TPG], bo, v4i{0, 0, 0, 0});
+            } else {
+                const v4i lo = CodeOps<8>::lo(vc[ct]), hi = CodeOps<8>::hi(vc[ct]);
+#pragma unroll
+                for (int hg = 0; hg < NHG; hg++) {
+                    const v4i alo = mfma(avr[hg][ct / TPG], lo, v4i{0, 0, 0, 0});
+                    const v4i ahi = mfma(avr[hg][ct / TPG], hi, v4i{0, 0, 0, 0});
+                    acc[hg] = alo + ahi * 16;
                 }
-                const unsigned char *kr = a.layer + gm.k_resid_off + (long long)u * gm.R * 256;
-                const unsigned char *vr = a.layer + gm.v_resid_off + (long long)u * gm.R * 256;
-                for (int t0 = 0; t0 < a.r; t0 += 32) {
-                    const int nt = a.r - t0 < 32 ? a.r - t0 : 32;
-                    wave_lds_fence();
-                    for (int i = lane; i < nt * 16; i += 64) {
-                        const int t = i >> 4, ch = i & 15;
-                        const uint4 kv_ = *(const uint4 *)(kr + (long long)(t0 + t) * 256 + ch * 16);
-                        const uint4 vv_ = *(const uint4 *)(vr + (long long)(t0 + t) * 256 + ch * 16);
-                        *(uint2 *)(kraw + t * RS + ch * 16) = uint2{kv_.x, kv_.y};
-                        *(uint2 *)(kraw + t * RS + ch * 16 + 8) = uint2{kv_.z, kv_.w};
-                        *(uint2 *)(vraw + t * RS + ch * 16) = uint2{vv_.x, vv_.y};
-                        *(uint2 *)(vraw + t * RS + ch * 16 + 8) = uint2{vv_.z, vv_.w};
-                    }
-                    wave_lds_fence();
-                    {
-                        const int t = lane & 31, half = lane >> 5;
-                        float d4[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-                        if (t < nt) {
-                            for (int c = half * 64; c < half * 64 + 64; c += 2) {
-                                const uint32_t w = *(const uint32_t *)(kraw + t * RS + c * 2);
-                                const float k0 = widen16((uint16_t)(w & 0xFFFFu), gm.dtype);
-                                const float k1 = widen16((uint16_t)(w >> 16), gm.dtype);
+            }
 #pragma unroll
-                                for (int i = 0; i < 4; i++) d4[i] += qs[i * 128 + c] * k0 + qs[i * 128 + c + 1] * k1;
-                            }
+            for (int hg = 0; hg < NHG; hg++) {
+                float o = st[hg].O[ct] * alpha[hg] + limbs_to_float(acc[hg]) * o_scale[hg];
 #pragma unroll
-                            for (int i = 0; i < 4; i++) spart[(half * 4 + i) * 32 + t] = d4[i];
+                for (int bi = 0; bi < NBC; bi++)
+                    o += __half2float(__ushort_as_half(vmean[bi][ct])) * psum_b[hg][bi];
+                st[hg].O[ct] = o;
+            }
+        }
+    }
+
+    // ---- raw residual tokens (Sec. 3.3): wave 0 of the split that is next in turn
+    const bool has_resid = a.r > 0 && sp == chunks_total % ns;
+    if (has_resid) {
+        __syncthreads(); // every wave is out of its main loop; wave 0 may take all of LDS
+        if (wave == 0) {
+            unsigned char *L = (unsigned char *)lds_all;
+            constexpr int RS = 264;  // bytes per staged row (33 * 8): rows start in different banks
+            constexpr int NH = 4 * NHG;
+            unsigned char *kraw = L, *vraw = L + 32 * RS;
+            float *qs = (float *)(L + 64 * RS);        // [NH][128]
+            float *spart = qs + NH * 128;               // [2][NH][32]
+            float *pl = spart + 2 * NH * 32;            // [NH][32]
+            static_assert(64 * RS + (NH * 128 + 2 * NH * 32 + NH * 32) * 4 <= RESID_DW * 4, "residual scratch");
+#pragma unroll
+            for (int hg = 0; hg < NHG; hg++)
+#pragma unroll
+                for (int ph = 0; ph < 2; ph++)
+#pragma unroll
+                    for (int y = 0; y < 4; y++)
+                        qs[(4 * hg + row) * 128 + 32 * vq + 16 * ph + 4 * qa + y] = qf[hg][ph][y];
+            const unsigned char *kr = a.layer + gm.k_resid_off + (long long)u * gm.R * 256;
+            const unsigned char *vr = a.layer + gm.v_resid_off + (long long)u * gm.R * 256;
+            for (int t0 = 0; t0 < a.r; t0 += 32) {
+                const int nt = a.r - t0 < 32 ? a.r - t0 : 32;
+                wave_lds_fence();
+                for (int i = lane; i < nt * 16; i += 64) {
+                    const int t = i >> 4, ch = i & 15;
+                    const uint4 kv_ = *(const uint4 *)(kr + (long long)(t0 + t) * 256 + ch * 16);
+                    const uint4 vv_ = *(const uint4 *)(vr + (long long)(t0 + t) * 256 + ch * 16);
+                    *(uint2 *)(kraw + t * RS + ch * 16) = uint2{kv_.x, kv_.y};
+                    *(uint2 *)(kraw + t * RS + ch * 16 + 8) = uint2{kv_.z, kv_.w};
+                    *(uint2 *)(vraw + t * RS + ch * 16) = uint2{vv_.x, vv_.y};
+                    *(uint2 *)(vraw + t * RS + ch * 16 + 8) = uint2{vv_.z, vv_.w};
+                }
+                wave_lds_fence();
+                {
+                    const int t = lane & 31, half = lane >> 5;
+                    float dn[NH];
+#pragma unroll
+                    for (int i = 0; i < NH; i++) dn[i] = 0.0f;
+                    if (t < nt) {
+                        for (int c = half * 64; c < half * 64 + 64; c += 2) {
+                            const uint32_t w = *(const uint32_t *)(kraw + t * RS + c * 2);
+                            const float k0 = widen16((uint16_t)(w & 0xFFFFu), gm.dtype);
+                            const float k1 = widen16((uint16_t)(w >> 16), gm.dtype);
+#pragma unroll
+                            for (int i = 0; i < NH; i++) dn[i] += qs[i * 128 + c] * k0 + qs[i * 128 + c + 1] * k1;
                         }
+#pragma unroll
+                        for (int i = 0; i < NH; i++) spart[(half * NH + i) * 32 + t] = dn[i];
                     }
-                    wave_lds_fence();
-                    float s[4], p[4], alpha, wc;
+                }
+                wave_lds_fence();
+                float pr[NHG][2], al[NHG], wcr[NHG];
+#pragma unroll
+                for (int hg = 0; hg < NHG; hg++) {
+                    const int head = 4 * hg + row;
+                    float s[4], p[4];
 #pragma unroll
                     for (int k = 0; k < 4; k++) {
                         const int t = n + 16 * k;
-                        s[k] = (k < 2 && t < nt) ? (spart[row * 32 + t] + spart[(4 + row) * 32 + t]) * kScoreScale
-                                                 : -INFINITY;
+                        s[k] = (k < 2 && t < nt)
+                                   ? (spart[head * 32 + t] + spart[(NH + head) * 32 + t]) * kScoreScale
+                                   : -INFINITY;
                     }
-                    softmax_chunk(s, st, p, alpha, wc);
+                    softmax_chunk(s, st[hg], p, al[hg], wcr[hg]);
+                    pr[hg][0] = p[0];
+                    pr[hg][1] = p[1];
+                }
+#pragma unroll
+                for (int hg = 0; hg < NHG; hg++)
 #pragma unroll
                     for (int k = 0; k < 2; k++)
-                        if (n + 16 * k < nt) pl[row * 32 + n + 16 * k] = p[k];
-                    wave_lds_fence();
+                        if (n + 16 * k < nt) pl[(4 * hg + row) * 32 + n + 16 * k] = pr[hg][k];
+                wave_lds_fence();
+#pragma unroll
+                for (int hg = 0; hg < NHG; hg++) {
                     float add[8];
 #pragma unroll
                     for (int ct = 0; ct < 8; ct++) add[ct] = 0.0f;
                     for (int t = 0; t < nt; t++) {
-                        const float pv = pl[row * 32 + t];
+                        const float pv = pl[(4 * hg + row) * 32 + t];
 #pragma unroll
                         for (int ct = 0; ct < 8; ct++)
                             add[ct] += pv * widen16(*(const uint16_t *)(vraw + t * RS + (16 * ct + n) * 2), gm.dtype);
                     }
 #pragma unroll
-                    for (int ct = 0; ct < 8; ct++) st.O[ct] = st.O[ct] * alpha + wc * add[ct];
+                    for (int ct = 0; ct < 8; ct++) st[hg].O[ct] = st[hg].O[ct] * al[hg] + wcr[hg] * add[ct];
 #pragma unroll
-                    for (int gam = 0; gam < 4; gam++) st.Zp[gam] *= alpha;
+                    for (int gam = 0; gam < 4; gam++) st[hg].Zp[gam] *= al[hg];
                 }
             }
-            __syncthreads();
         }
+        __syncthreads();
+    }
 
-        // ---- finish the wave's state and merge the four waves
-        st.l = row_sum(st.l);
+    // ---- finish the wave's state and merge the waves: [NHG][10][64] floats at the start of each wave's LDS
+    static_assert(NHG * 10 * 64 <= WAVE_DW, "state exchange");
+    float *mine = (float *)lds;
+    wave_lds_fence();
+#pragma unroll
+    for (int hg = 0; hg < NHG; hg++) {
+        st[hg].l = row_sum(st[hg].l);
 #pragma unroll
         for (int gam = 0; gam < NG; gam++) {
-            const float z = row_sum(st.Zp[gam]);
+            const float z = row_sum(st[hg].Zp[gam]);
 #pragma unroll
-            for (int ct = gam * TPG; ct < (gam + 1) * TPG; ct++) st.O[ct] += z;
+            for (int ct = gam * TPG; ct < (gam + 1) * TPG; ct++) st[hg].O[ct] += z;
         }
-        float *mine = (float *)lds; // start of this wave's LDS: [10][64] floats
-        wave_lds_fence();
-        mine[0 * 64 + lane] = st.M;
-        mine[1 * 64 + lane] = st.l;
+        mine[(hg * 10 + 0) * 64 + lane] = st[hg].M;
+        mine[(hg * 10 + 1) * 64 + lane] = st[hg].l;
 #pragma unroll
-        for (int ct = 0; ct < 8; ct++) mine[(2 + ct) * 64 + lane] = st.O[ct];
-        __syncthreads();
-        if (wave == 0 && row < g) {
-            const float *all = (const float *)lds_all;
+        for (int ct = 0; ct < 8; ct++) mine[(hg * 10 + 2 + ct) * 64 + lane] = st[hg].O[ct];
+    }
+    __syncthreads();
+    if (wave == 0) {
+        const float *all = (const float *)lds_all;
+#pragma unroll
+        for (int hg = 0; hg < NHG; hg++) {
+            const int head = 4 * hg + row;
+            if (head >= g) continue;
             float Mw[NW], M = -INFINITY;
 #pragma unroll
             for (int w = 0; w < NW; w++) {
-                Mw[w] = all[w * WAVE_DW + lane];
+                Mw[w] = all[w * WAVE_DW + (hg * 10 + 0) * 64 + lane];
                 M = fmaxf(M, Mw[w]);
             }
             float lsum = 0.0f, o[8];
@@ -614,11 +684,11 @@ __global__ __launch_bounds__(64 * NW) void decode_split_mfma_kernel(DecodeArgs a
 #pragma unroll
             for (int w = 0; w < NW; w++) {
                 const float wt = Mw[w] == -INFINITY ? 0.0f : exp2f(Mw[w] - M); // a wave that saw no token
-                lsum += all[w * WAVE_DW + 64 + lane] * wt;
+                lsum += all[w * WAVE_DW + (hg * 10 + 1) * 64 + lane] * wt;
 #pragma unroll
-                for (int ct = 0; ct < 8; ct++) o[ct] += all[w * WAVE_DW + (2 + ct) * 64 + lane] * wt;
+                for (int ct = 0; ct < 8; ct++) o[ct] += all[w * WAVE_DW + (hg * 10 + 2 + ct) * 64 + lane] * wt;
             }
-            float *dst = a.ws + (((long long)u * g + row) * a.n_splits + sp) * kPartialStride;
+            float *dst = a.ws + (((long long)u * g + head) * a.n_splits + sp) * kPartialStride;
 #pragma unroll
             for (int ct = 0; ct < 8; ct++) dst[16 * ct + n] = o[ct];
             if (n == 0) {
@@ -630,11 +700,11 @@ __global__ __launch_bounds__(64 * NW) void decode_split_mfma_kernel(DecodeArgs a
 }
 
 // Resident workgroups of one instantiation on the whole device (0 if the query fails).
-template <int B, int G, int GC, bool MEAN, int NW> int resident_blocks()
+template <int B, int G, int GC, bool MEAN, int NW, int NHG> int resident_blocks()
 {
     static const int n = [] {
         int per_cu = 0, dev = 0, cus = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_split_mfma_kernel<B, G, GC, MEAN, NW>,
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_split_mfma_kernel<B, G, GC, MEAN, NW, NHG>,
                                                          64 * NW, 0) != hipSuccess)
             return 0;
         if (hipGetDevice(&dev) != hipSuccess) return 0;
@@ -644,22 +714,22 @@ template <int B, int G, int GC, bool MEAN, int NW> int resident_blocks()
     return n;
 }
 
-template <int B, int G, int GC, bool MEAN> hipError_t launch_mean(const DecodeArgs &a, hipStream_t s)
+template <int B, int G, int GC, bool MEAN, int NHG> hipError_t launch_inst(const DecodeArgs &a, hipStream_t s)
 {
     constexpr int NW = kWavesPerBlock;
     if (!RecLayout<B, G, GC, MEAN>::matches(a.geom)) return hipErrorInvalidValue;
     dim3 grid(a.n_splits, a.batch * a.n_kv_heads);
     (void)hipGetLastError(); // drop any stale error left by earlier runtime calls of this thread
-    hipLaunchKernelGGL((decode_split_mfma_kernel<B, G, GC, MEAN, NW>), grid, dim3(64 * NW), 0, s, a);
+    hipLaunchKernelGGL((decode_split_mfma_kernel<B, G, GC, MEAN, NW, NHG>), grid, dim3(64 * NW), 0, s, a);
     return note_launch(hipGetLastError());
 }
 
 // Split count that puts every workgroup of the launch on the device at once (one "round"):
 // the kernel is a bandwidth stream, and a second, partly filled round only adds a tail.
-template <int B, int G, int GC, bool MEAN> int plan_mean(const DecodeArgs &a)
+template <int B, int G, int GC, bool MEAN, int NHG> int plan_inst(const DecodeArgs &a)
 {
     constexpr int NW = kWavesPerBlock, NBC = 64 / G;
-    const int slots = resident_blocks<B, G, GC, MEAN, NW>();
+    const int slots = resident_blocks<B, G, GC, MEAN, NW, NHG>();
     const int U = a.batch * a.n_kv_heads;
     const int chunks = (a.n_blocks + NBC - 1) / NBC;
     int ns = slots / U;
@@ -669,27 +739,47 @@ template <int B, int G, int GC, bool MEAN> int plan_mean(const DecodeArgs &a)
     if (ns < 1) ns = 1;
     return ns;
 }
-template <int B, int G, int GC> int plan_one(const DecodeArgs &a)
+
+// what to do with the instance selected by the layer's format
+struct DoLaunch {
+    hipStream_t s;
+    hipError_t result = hipErrorInvalidValue;
+    template <int B, int G, int GC, bool MEAN, int NHG> void run(const DecodeArgs &a) { result = launch_inst<B, G, GC, MEAN, NHG>(a, s); }
+};
+struct DoPlan {
+    int result = 1;
+    template <int B, int G, int GC, bool MEAN, int NHG> void run(const DecodeArgs &a) { result = plan_inst<B, G, GC, MEAN, NHG>(a); }
+};
+struct DoMatch {
+    bool result = false;
+    template <int B, int G, int GC, bool MEAN, int NHG> void run(const DecodeArgs &a) { result = RecLayout<B, G, GC, MEAN>::matches(a.geom); }
+};
+
+template <int B, int G, int GC, class F> void pick_mean_heads(const DecodeArgs &a, F &f)
 {
-    return a.geom.mean_mode == 0 ? plan_mean<B, G, GC, true>(a) : plan_mean<B, G, GC, false>(a);
+    const bool mean = a.geom.mean_mode == 0;
+    if (a.g <= 4) {
+        if (mean) f.template run<B, G, GC, true, 1>(a);
+        else f.template run<B, G, GC, false, 1>(a);
+    } else {
+        if (mean) f.template run<B, G, GC, true, 2>(a);
+        else f.template run<B, G, GC, false, 2>(a);
+    }
+}
+template <class F> void pick(const DecodeArgs &a, F &f)
+{
+    const int bits = a.geom.k_bits;
+    if (a.geom.G == 32) {
+        if (bits == 2) pick_mean_heads<2, 32, 32>(a, f);
+        else if (bits == 4) pick_mean_heads<4, 32, 32>(a, f);
+        else pick_mean_heads<8, 32, 32>(a, f);
+    } else {
+        if (bits == 2) pick_mean_heads<2, 64, 64>(a, f);
+        else if (bits == 4) pick_mean_heads<4, 64, 64>(a, f);
+        else pick_mean_heads<8, 64, 64>(a, f);
+    }
 }
 
-template <int B, int G, int GC> hipError_t launch_one(const DecodeArgs &a, hipStream_t s)
-{
-    return a.geom.mean_mode == 0 ? launch_mean<B, G, GC, true>(a, s) : launch_mean<B, G, GC, false>(a, s);
-}
-
-} // namespace
-
-namespace {
-template <int B, int G, int GC> bool layout_ok(const LayerGeom &g)
-{
-    return g.mean_mode == 0 ? RecLayout<B, G, GC, true>::matches(g) : RecLayout<B, G, GC, false>::matches(g);
-}
-template <int G, int GC> bool layout_ok_bits(const LayerGeom &g)
-{
-    return g.k_bits == 2 ? layout_ok<2, G, GC>(g) : (g.k_bits == 4 ? layout_ok<4, G, GC>(g) : layout_ok<8, G, GC>(g));
-}
 } // namespace
 
 bool decode_mfma_supported(const DecodeArgs &a)
@@ -698,33 +788,30 @@ bool decode_mfma_supported(const DecodeArgs &a)
     if (g.k_bits != g.v_bits) return false;
     if (!(g.k_bits == 2 || g.k_bits == 4 || g.k_bits == 8)) return false;
     if (!((g.G == 32 && g.Gc == 32) || (g.G == 64 && g.Gc == 64))) return false;
-    if (a.g > 4) return false;
+    if (a.g > 8) return false;
     if (g.mean_mode == 1) return false; // cross-head mean: not on this path
     if (a.batch * a.n_kv_heads > 65535) return false;
     // the kernels address record fields with compile-time offsets
-    return g.G == 32 ? layout_ok_bits<32, 32>(g) : layout_ok_bits<64, 64>(g);
+    DoMatch m;
+    pick(a, m);
+    return m.result;
 }
 
 int decode_mfma_splits(const DecodeArgs &a)
 {
     if (!decode_mfma_supported(a)) return 1;
-    const int bits = a.geom.k_bits;
-    if (a.geom.G == 32) return bits == 2 ? plan_one<2, 32, 32>(a) : (bits == 4 ? plan_one<4, 32, 32>(a) : plan_one<8, 32, 32>(a));
-    return bits == 2 ? plan_one<2, 64, 64>(a) : (bits == 4 ? plan_one<4, 64, 64>(a) : plan_one<8, 64, 64>(a));
+    DoPlan p;
+    pick(a, p);
+    return p.result;
 }
 
 hipError_t launch_decode_split_mfma(const DecodeArgs &a, hipStream_t s)
 {
     if (!decode_mfma_supported(a)) return hipErrorInvalidValue;
-    const int bits = a.geom.k_bits;
-    if (a.geom.G == 32) {
-        if (bits == 2) return launch_one<2, 32, 32>(a, s);
-        if (bits == 4) return launch_one<4, 32, 32>(a, s);
-        return launch_one<8, 32, 32>(a, s);
-    }
-    if (bits == 2) return launch_one<2, 64, 64>(a, s);
-    if (bits == 4) return launch_one<4, 64, 64>(a, s);
-    return launch_one<8, 64, 64>(a, s);
+    DoLaunch l;
+    l.s = s;
+    pick(a, l);
+    return l.result;
 }
 
 } // namespace tadakv

@@ -292,3 +292,61 @@ def test_cross_head_mean_mixed_layers_bf16(kv, oracle):
         append_both(gpu, orc, l, k, v, BF16)
         check_bytes(gpu, orc, l)
         check_attention(gpu, orc, l, synth.make_q(l, 1, 32, 128, BF16), BF16)
+
+
+# ------------------------------------------------------------------ matrix-core kernels, forced
+
+
+@pytest.mark.parametrize("decode_path", [2], indirect=True, ids=["mfma"])
+@pytest.mark.parametrize("bits", [2, 4, 8])
+@pytest.mark.parametrize("g", [1, 3, 4, 5, 8])
+@pytest.mark.parametrize("G,mode", [(32, CHAN), (64, CHAN), (64, NONE)])
+def test_matrix_core_kernels(kv, oracle, decode_path, bits, g, G, mode):
+    """Path 2 refuses to fall back, so these cases prove the int8 matrix-core kernels themselves:
+    one and two head groups per wave, both block sizes, with and without block means, a partial
+    last chunk and a raw tail."""
+    print("case mfma bits=%d g=%d G=%d mode=%d" % (bits, g, G, mode), flush=True)
+    Hkv = 2
+    T = 21 * G + 9  # odd block count: the last 64-token chunk of a G=32 cache is half empty
+    gpu, orc = make_pair(kv, oracle, B=2, Hq=Hkv * g, Hkv=Hkv, T_max=24 * G, G=G, Gc=G, dtype=BF16, mode=mode,
+                         k_bits=(bits,))
+    k, v = synth.make_kv(500 + bits + g, 2, T, Hkv, 128, BF16)
+    append_both(gpu, orc, 0, k, v, BF16)
+    check_bytes(gpu, orc, 0)
+    q = synth.make_q(g, 2, Hkv * g, 128, BF16)
+    check_attention(gpu, orc, 0, q, BF16)
+    for ns in (1, 3):
+        kv.kv_set_decode_splits(gpu.handle, ns)
+        check_attention(gpu, orc, 0, q, BF16)
+
+
+@pytest.mark.parametrize("decode_path", [2], indirect=True, ids=["mfma"])
+def test_long_context_70b_shape(kv, oracle, decode_path):
+    """64 query / 8 kv heads (two head groups per wave), batch 1, group size 64, a mixed layer map
+    with 8-bit ends, outlier channels: the long-context workload at a reduced context."""
+    print("case 70b_shape", flush=True)
+    bits = (8, 2, 4, 8)
+    gpu, orc = make_pair(kv, oracle, L=4, B=1, Hq=64, Hkv=8, T_max=8192 + 64, G=64, Gc=64, dtype=BF16, k_bits=bits)
+    for l in range(4):
+        k, v = synth.make_kv(600 + l, 1, 8192 + 17, 8, 128, BF16)
+        append_both(gpu, orc, l, k, v, BF16, chunks=[8192, 17])
+        check_bytes(gpu, orc, l)
+        check_attention(gpu, orc, l, synth.make_q(l, 1, 64, 128, BF16), BF16)
+
+
+@pytest.mark.parametrize("decode_path", [2, 1], indirect=True, ids=["mfma", "valu"])
+def test_prefill_then_decode_steps_with_drift(kv, oracle, decode_path):
+    """Bulk prefill, then decode steps that append one token and attend, on keys whose channel
+    means drift along the sequence; checked after every few steps and across a block flush."""
+    print("case prefill_decode", flush=True)
+    bits = (2, 8, 4)
+    gpu, orc = make_pair(kv, oracle, L=3, B=3, Hq=8, Hkv=2, T_max=1024 + 64, dtype=BF16, k_bits=bits)
+    steps = 40
+    for l in range(3):
+        k, v = synth.make_kv(700 + l, 3, 1024 + steps, 2, 128, BF16, n_drift=8, slope=0.01)
+        append_both(gpu, orc, l, k[:, :1024], v[:, :1024], BF16)
+        for s in range(steps):
+            append_both(gpu, orc, l, k[:, 1024 + s:1025 + s], v[:, 1024 + s:1025 + s], BF16)
+            if s % 13 == 0 or s in (31, 32, steps - 1):
+                check_attention(gpu, orc, l, synth.make_q(l * 100 + s, 3, 8, 128, BF16), BF16)
+        check_bytes(gpu, orc, l)
