@@ -38,6 +38,11 @@ def parse():
     ap.add_argument("--batch", type=int, default=16)
     ap.add_argument("--layers", type=int, default=32)
     ap.add_argument("--path", type=int, default=0, help="0 auto, 1 vector-ALU kernels, 2 matrix-core kernels")
+    ap.add_argument("--q-heads", type=int, default=32)
+    ap.add_argument("--kv-heads", type=int, default=8)
+    ap.add_argument("--group", type=int, default=32, help="group size G = Gc")
+    ap.add_argument("--scheme", default="mixed248", help="layer bit map: mixed248 or mixed24_8ends")
+    ap.add_argument("--seed", type=int, default=2000)
     ap.add_argument("--splits", type=int, default=0, help="force the sequence split count (0 = automatic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     return ap.parse_args()
@@ -60,12 +65,12 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
-    L, B, Hq, Hkv, d, G = args.layers, args.batch, 32, 8, 128, 32
+    L, B, Hq, Hkv, d, G = args.layers, args.batch, args.q_heads, args.kv_heads, 128, args.group
     T0 = args.context
     K, W = args.steps, args.warmup
     n_dec = K + W
     max_tokens = (T0 + n_dec + 8 + G - 1) // G * G
-    bits = synth.layer_bits(2000, L, "mixed248")
+    bits = synth.layer_bits(args.seed, L, args.scheme)
     cfg = kv.make_config(L, B, Hq, Hkv, d, max_tokens, G, G, G, kv.KV_BF16, kv.KV_MEAN_CHANNEL_BLOCK, bits, bits)
     cache = kv.KVCache(cfg, device=dev, zero=False)
     kv.kv_set_decode_path(cache.handle, args.path)
@@ -164,7 +169,7 @@ def main():
     pool = torch.ones(2 * 1024 ** 3 // 8, dtype=torch.int64, device=dev)
     c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     for b_ in sorted(set(bits)):
-        n = per_bits[str(b_)]["bytes"] // 8
+        n = min(per_bits[str(b_)]["bytes"] // 8, pool.numel())
         views = [pool[i * n:(i + 1) * n] for i in range(max(1, pool.numel() // n))]
         for v_ in views[:2]:
             v_.sum()
@@ -206,9 +211,9 @@ def main():
         "vs_baseline": None,
         "dtype": "i8 x i8 -> i32 contractions, f32 softmax" if args.path != 1 else "f32",
         "data": "synthetic",
-        "config": {"workload": "llama3-8b-shaped full cache: 32 layers, 32q/8kv heads, head_dim 128, "
-                               "batch %d, context %d, bf16, G=Gc=32, mixed {2,4,8}-bit layer map (seed 2000), "
-                               "per-channel block mean" % (B, T0),
+        "config": {"workload": "llama-shaped full cache: %d layers, %dq/%dkv heads, head_dim 128, "
+                               "batch %d, context %d, bf16, G=Gc=%d, %s layer bit map (seed %d), "
+                               "per-channel block mean" % (L, Hq, Hkv, B, T0, G, args.scheme, args.seed),
                    "layers": L, "batch": B, "context": T0, "bit_map": bits, "decode_path": args.path},
         "pct_of_hbm_peak": round(total_bytes / wall / 1e9 / HBM_PEAK_GBPS * 100, 2),
         "decode_tokens_per_s": round(B * K / wall, 1),

@@ -22,7 +22,7 @@ namespace tadakv {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kRowPad = kHeadDim + 1; // floats per LDS row: column walks hit distinct banks
+constexpr int kRowPad = kHeadDim + 4; // floats per LDS row: rows stay 16-byte aligned and start in different banks
 
 __device__ __forceinline__ float widen16(uint16_t v, int dtype)
 {
@@ -73,17 +73,16 @@ __device__ __forceinline__ void group_meta(float mn, float mx, int qmax, uint16_
 // which equals the correctly rounded x / s whenever r is the correctly rounded reciprocal and
 // the significand of s is not all ones (Markstein's division theorem); s is a binary16 value,
 // so its binary32 significand has at most 11 leading bits set.
-__device__ __forceinline__ uint32_t quant_code(float dev, float s, float rs, float z, int qmax)
+__device__ __forceinline__ uint32_t quant_code(float dev, float s, float rs, float z, float qmaxf)
 {
-    if (s == 0.0f) return 0u;
+    // A constant group has s == 0 and is given rs == 0: then dev == z, every term below is zero
+    // and the code is 0 without a special case.  The clamp never binds (0 <= dev - z and
+    // (dev - z)/s < qmax + 1/2 by construction of z and s); it is kept as one median instruction.
     const float xv = dev - z;
     const float q = xv * rs;
     const float e = __builtin_fmaf(-q, s, xv);
     const float u = __builtin_fmaf(e, rs, q);
-    float r = rintf(u);
-    r = r < 0.0f ? 0.0f : r;
-    r = r > (float)qmax ? (float)qmax : r;
-    return (uint32_t)r;
+    return (uint32_t)__builtin_amdgcn_fmed3f(rintf(u), 0.0f, qmaxf);
 }
 
 // Row of 128 16-bit elements that holds token `ci` of the concatenation
@@ -137,164 +136,212 @@ __device__ __forceinline__ void word_origin(int which, int bits, int G, int w, i
     }
 }
 
-__global__ __launch_bounds__(kThreads) void flush_block_kernel(AppendArgs a)
+// Persistent workgroups: each walks the items (block to flush, unit, K|V) it = blockIdx.x,
+// blockIdx.x + gridDim.x, ... and loads the 16-bit rows of its next item into registers before it
+// starts the arithmetic of the current one, so that HBM latency is covered by the quantiser.
+// All loops have compile-time trip counts: a thread pulls its 16..64 elements out of LDS in one
+// burst, works in registers, and writes back in one burst.
+template <int G, int GC>
+__global__ __launch_bounds__(kThreads) void flush_block_kernel(AppendArgs a, int n_items)
 {
+    constexpr int NLD = G * 16 / kThreads;   // 16-byte pieces per thread and item
+    constexpr int HT = G / 2;                // tokens per thread in the per-channel passes
+    constexpr int NGV = kHeadDim / GC;       // value groups per token
+    constexpr int HW = GC / 2;               // channels per thread in the value-group pass
+    constexpr int V_ITEMS = G * NGV * 2;     // value groups x two threads each
+    constexpr int V_PER = V_ITEMS / kThreads > 0 ? V_ITEMS / kThreads : 1;
+    constexpr int MM_N = V_ITEMS > kThreads ? V_ITEMS : kThreads;
     extern __shared__ float lds[];
     const LayerGeom &gm = a.geom;
-    const int G = gm.G;
-    float *x = lds;                                        // [G][kRowPad]
-    unsigned char *cb = (unsigned char *)(lds + G * kRowPad); // [G][128] codes
-
-    const int fb = blockIdx.x, u = blockIdx.y, which = blockIdx.z;
-    const int b = u / a.n_kv_heads, h = u % a.n_kv_heads;
+    float *x = lds;                                            // [G][kRowPad] values, then deviations
+    unsigned char *cb = (unsigned char *)(lds + G * kRowPad);  // codes: keys [G][128], values [128][G]
+    float *meanv = (float *)(cb + G * kHeadDim);               // [128] channel means
+    float *mm = meanv + kHeadDim;                              // [2][MM_N] partial minima, maxima
     const int tid = threadIdx.x;
-    const int bits = which == 0 ? gm.k_bits : gm.v_bits;
-    unsigned char *rec = a.layer + ((long long)u * gm.NB + (a.first_block + fb)) * gm.rec_bytes;
-    unsigned char *codes_out = rec + (which == 0 ? gm.k_codes : gm.v_codes);
-
-    if (bits == 16) {
-        // stored raw: G rows of 256 bytes
-        for (int i = tid; i < G * 16; i += kThreads) {
-            const int t = i >> 4, ch = i & 15;
-            const uint4 v = *(const uint4 *)(src_row(a, which, b, h, fb * G + t) + ch * 8);
-            *(uint4 *)(codes_out + (long long)t * 256 + ch * 16) = v;
-        }
-        return;
-    }
-
-    // 1. load the block, widened to binary32
-    for (int i = tid; i < G * 16; i += kThreads) {
-        const int t = i >> 4, ch = i & 15;
-        const uint4 v = *(const uint4 *)(src_row(a, which, b, h, fb * G + t) + ch * 8);
-        const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
-        float *dst = x + t * kRowPad + ch * 8;
-#pragma unroll
-        for (int k = 0; k < 4; k++) {
-            dst[2 * k] = widen16((uint16_t)(wv[k] & 0xFFFFu), gm.dtype);
-            dst[2 * k + 1] = widen16((uint16_t)(wv[k] >> 16), gm.dtype);
-        }
-    }
-    __syncthreads();
-
-    const int qmax = (1 << bits) - 1;
+    const int U = a.batch * a.n_kv_heads;
     const bool centre = gm.mean_mode == 0; // per-channel block mean
-    const int ng = kHeadDim / gm.Gc;
-    const int v_items = G * ng * 2; // value groups x two threads each
-    float *meanv = (float *)(cb + G * kHeadDim);   // [128] channel means
-    float *mm = meanv + kHeadDim;                  // [2][max(256, v_items)] partial minima, maxima
-    const int mm_n = v_items > kThreads ? v_items : kThreads;
 
-    // 2. channel mean over the block's tokens: sequential sum in token order, one thread per channel
-    if (tid < kHeadDim) {
-        const int c = tid;
-        float m = 0.0f;
-        if (centre) {
-            float acc = 0.0f;
-            for (int t = 0; t < G; t++) acc = acc + x[t * kRowPad + c];
-            const float m32 = acc / (float)G;
-            const uint16_t m16 = f16_rne(m32);
-            m = f16_val(m16);
-            *(uint16_t *)(rec + (which == 0 ? gm.k_mean : gm.v_mean) + c * 2) = m16;
+    uint4 pre[NLD];
+    auto fetch = [&](int it) {
+        const int which = it & 1, u = (it >> 1) % U, fb = (it >> 1) / U;
+        const int b = u / a.n_kv_heads, h = u % a.n_kv_heads;
+#pragma unroll
+        for (int k = 0; k < NLD; k++) {
+            const int i = tid + k * kThreads, t = i >> 4, ch = i & 15;
+            pre[k] = *(const uint4 *)(src_row(a, which, b, h, fb * G + t) + ch * 8);
         }
-        meanv[c] = m;
-    }
-    __syncthreads();
+    };
+    if ((int)blockIdx.x < n_items) fetch(blockIdx.x);
 
-    // 3. deviation; every thread owns half of a channel's tokens
-    {
-        const int c = tid & 127, half = tid >> 7;
-        const int t_lo = half * (G / 2), t_hi = t_lo + G / 2;
-        const float mch = meanv[c];
-        // cross-head mode: the mean of (token, channel) over the kv heads, written by
-        // xhead_mean_kernel just before this launch
-        const uint16_t *xm = gm.mean_mode == 1
-                                 ? (const uint16_t *)(a.layer + gm.xmean_off) +
-                                       (((long long)b * gm.NB + (a.first_block + fb)) * 2 + which) * G * kHeadDim
-                                 : nullptr;
-        float mn = INFINITY, mx = -INFINITY;
-        for (int t = t_lo; t < t_hi; t++) {
-            const float m = xm ? f16_val(xm[t * kHeadDim + c]) : mch;
-            const float dv = x[t * kRowPad + c] - m;
-            x[t * kRowPad + c] = dv;
-            mn = dv < mn ? dv : mn;
-            mx = dv > mx ? dv : mx;
+    for (int it = blockIdx.x; it < n_items; it += gridDim.x) {
+        const int which = it & 1, u = (it >> 1) % U, fb = (it >> 1) / U;
+        const int b = u / a.n_kv_heads;
+        const int bits = which == 0 ? gm.k_bits : gm.v_bits;
+        unsigned char *rec = a.layer + ((long long)u * gm.NB + (a.first_block + fb)) * gm.rec_bytes;
+        unsigned char *codes_out = rec + (which == 0 ? gm.k_codes : gm.v_codes);
+
+        if (bits == 16) {
+            // stored raw: G rows of 256 bytes
+#pragma unroll
+            for (int k = 0; k < NLD; k++) {
+                const int i = tid + k * kThreads, t = i >> 4, ch = i & 15;
+                *(uint4 *)(codes_out + (long long)t * 256 + ch * 16) = pre[k];
+            }
+            if (it + (int)gridDim.x < n_items) fetch(it + gridDim.x);
+            continue;
         }
-        if (which == 0) {
-            mm[tid] = mn;
-            mm[mm_n + tid] = mx;
+
+        // 1. the block, widened to binary32, into LDS; then start loading the next item
+#pragma unroll
+        for (int k = 0; k < NLD; k++) {
+            const int i = tid + k * kThreads, t = i >> 4, ch = i & 15;
+            const uint32_t wv[4] = {pre[k].x, pre[k].y, pre[k].z, pre[k].w};
+            float4 lo, hi;
+            lo.x = widen16((uint16_t)(wv[0] & 0xFFFFu), gm.dtype); lo.y = widen16((uint16_t)(wv[0] >> 16), gm.dtype);
+            lo.z = widen16((uint16_t)(wv[1] & 0xFFFFu), gm.dtype); lo.w = widen16((uint16_t)(wv[1] >> 16), gm.dtype);
+            hi.x = widen16((uint16_t)(wv[2] & 0xFFFFu), gm.dtype); hi.y = widen16((uint16_t)(wv[2] >> 16), gm.dtype);
+            hi.z = widen16((uint16_t)(wv[3] & 0xFFFFu), gm.dtype); hi.w = widen16((uint16_t)(wv[3] >> 16), gm.dtype);
+            *(float4 *)(x + t * kRowPad + ch * 8) = lo;
+            *(float4 *)(x + t * kRowPad + ch * 8 + 4) = hi;
+        }
+        if (it + (int)gridDim.x < n_items) fetch(it + gridDim.x);
+        __syncthreads();
+
+        const int qmax = (1 << bits) - 1;
+        const float qmaxf = (float)qmax;
+
+        // 2. channel mean over the block's tokens: sequential sum in token order, one thread per channel
+        if (tid < kHeadDim) {
+            const int c = tid;
+            float m = 0.0f;
+            if (centre) {
+                float v[G];
+#pragma unroll
+                for (int t = 0; t < G; t++) v[t] = x[t * kRowPad + c];
+                float acc = 0.0f;
+#pragma unroll
+                for (int t = 0; t < G; t++) acc = acc + v[t];
+                const float m32 = acc / (float)G;
+                const uint16_t m16 = f16_rne(m32);
+                m = f16_val(m16);
+                *(uint16_t *)(rec + (which == 0 ? gm.k_mean : gm.v_mean) + c * 2) = m16;
+            }
+            meanv[c] = m;
         }
         __syncthreads();
-        if (which == 0) {
-            // keys: one group per channel over all tokens of the block (extrema are order-free)
-            const float o_mn = mm[tid ^ 128], o_mx = mm[mm_n + (tid ^ 128)];
-            mn = o_mn < mn ? o_mn : mn;
-            mx = o_mx > mx ? o_mx : mx;
-            uint16_t s16, z16;
-            float sc, z;
-            group_meta(mn, mx, qmax, s16, z16, sc, z);
-            if (half == 0) {
-                *(uint16_t *)(rec + gm.k_scale + c * 2) = s16;
-                *(uint16_t *)(rec + gm.k_zero + c * 2) = z16;
-            }
-            const float r = sc != 0.0f ? 1.0f / sc : 0.0f;
-            for (int t = t_lo; t < t_hi; t++)
-                cb[t * kHeadDim + c] = (unsigned char)quant_code(x[t * kRowPad + c], sc, r, z, qmax);
-        }
-    }
 
-    if (which == 1) {
-        // values: one group per (token, channel group); two threads per group, half the channels each
-        const int hw = gm.Gc / 2;
-        for (int idx = tid; idx < v_items; idx += kThreads) {
-            const int t = idx % G, rest = idx / G, gam = rest % ng, half = rest / ng;
-            const float *row = x + t * kRowPad + gam * gm.Gc + half * hw;
-            float mn = row[0], mx = row[0];
-            for (int i = 1; i < hw; i++) {
-                const float dv = row[i];
-                mn = dv < mn ? dv : mn;
-                mx = dv > mx ? dv : mx;
+        // 3. deviation; every thread owns half of a channel's tokens
+        {
+            const int c = tid & 127, half = tid >> 7;
+            const int t_lo = half * HT;
+            const float mch = meanv[c];
+            // cross-head mode: the mean of (token, channel) over the kv heads, written by
+            // xhead_mean_kernel just before this launch
+            const uint16_t *xm = gm.mean_mode == 1
+                                     ? (const uint16_t *)(a.layer + gm.xmean_off) +
+                                           (((long long)b * gm.NB + (a.first_block + fb)) * 2 + which) * G * kHeadDim
+                                     : nullptr;
+            float dv[HT];
+#pragma unroll
+            for (int i = 0; i < HT; i++) dv[i] = x[(t_lo + i) * kRowPad + c];
+            float mn = INFINITY, mx = -INFINITY;
+#pragma unroll
+            for (int i = 0; i < HT; i++) {
+                const float m = xm ? f16_val(xm[(t_lo + i) * kHeadDim + c]) : mch;
+                dv[i] = dv[i] - m;
+                mn = fminf(mn, dv[i]); // a zero of either sign may win; group_meta makes it +0
+                mx = fmaxf(mx, dv[i]);
             }
-            mm[idx] = mn;
-            mm[mm_n + idx] = mx;
+            if (which == 0) {
+                // keys: one group per channel over all tokens of the block (extrema are order-free)
+                mm[tid] = mn;
+                mm[MM_N + tid] = mx;
+                __syncthreads();
+                const float o_mn = mm[tid ^ 128], o_mx = mm[MM_N + (tid ^ 128)];
+                mn = fminf(mn, o_mn);
+                mx = fmaxf(mx, o_mx);
+                uint16_t s16, z16;
+                float sc, z;
+                group_meta(mn, mx, qmax, s16, z16, sc, z);
+                if (half == 0) {
+                    *(uint16_t *)(rec + gm.k_scale + c * 2) = s16;
+                    *(uint16_t *)(rec + gm.k_zero + c * 2) = z16;
+                }
+                const float r = sc != 0.0f ? 1.0f / sc : 0.0f;
+#pragma unroll
+                for (int i = 0; i < HT; i++)
+                    cb[(t_lo + i) * kHeadDim + c] = (unsigned char)quant_code(dv[i], sc, r, z, qmaxf);
+            } else {
+#pragma unroll
+                for (int i = 0; i < HT; i++) x[(t_lo + i) * kRowPad + c] = dv[i];
+                __syncthreads();
+            }
+        }
+
+        if (which == 1) {
+            // values: one group per (token, channel group); two threads per group, half the channels
+            // each; codes go to LDS transposed ([channel][token]) because value words run along tokens
+            float dv[V_PER][HW];
+#pragma unroll
+            for (int j = 0; j < V_PER; j++) {
+                const int idx = tid + j * kThreads;
+                if (idx < V_ITEMS) {
+                    const int t = idx % G, rest = idx / G, gam = rest % NGV, half = rest / NGV;
+                    const float *row = x + t * kRowPad + gam * GC + half * HW;
+                    float mn = INFINITY, mx = -INFINITY;
+#pragma unroll
+                    for (int i = 0; i < HW; i += 4) {
+                        const float4 q4 = *(const float4 *)(row + i);
+                        dv[j][i] = q4.x; dv[j][i + 1] = q4.y; dv[j][i + 2] = q4.z; dv[j][i + 3] = q4.w;
+                    }
+#pragma unroll
+                    for (int i = 0; i < HW; i++) {
+                        mn = fminf(mn, dv[j][i]);
+                        mx = fmaxf(mx, dv[j][i]);
+                    }
+                    mm[idx] = mn;
+                    mm[MM_N + idx] = mx;
+                }
+            }
+            __syncthreads();
+#pragma unroll
+            for (int j = 0; j < V_PER; j++) {
+                const int idx = tid + j * kThreads;
+                if (idx < V_ITEMS) {
+                    const int t = idx % G, rest = idx / G, gam = rest % NGV, half = rest / NGV;
+                    const int other = half ? idx - G * NGV : idx + G * NGV;
+                    float mn = mm[idx], mx = mm[MM_N + idx];
+                    const float o_mn = mm[other], o_mx = mm[MM_N + other];
+                    mn = fminf(mn, o_mn);
+                    mx = fmaxf(mx, o_mx);
+                    uint16_t s16, z16;
+                    float sc, z;
+                    group_meta(mn, mx, qmax, s16, z16, sc, z);
+                    if (half == 0)
+                        *(uint32_t *)(rec + gm.v_meta + (t * NGV + gam) * 4) = (uint32_t)s16 | ((uint32_t)z16 << 16);
+                    const float r = sc != 0.0f ? 1.0f / sc : 0.0f;
+                    unsigned char *col = cb + (gam * GC + half * HW) * G + t;
+#pragma unroll
+                    for (int i = 0; i < HW; i++) col[i * G] = (unsigned char)quant_code(dv[j][i], sc, r, z, qmaxf);
+                }
+            }
         }
         __syncthreads();
-        for (int idx = tid; idx < v_items; idx += kThreads) {
-            const int t = idx % G, rest = idx / G, gam = rest % ng, half = rest / ng;
-            const int other = half ? idx - G * ng : idx + G * ng;
-            float mn = mm[idx], mx = mm[mm_n + idx];
-            const float o_mn = mm[other], o_mx = mm[mm_n + other];
-            mn = o_mn < mn ? o_mn : mn;
-            mx = o_mx > mx ? o_mx : mx;
-            uint16_t s16, z16;
-            float sc, z;
-            group_meta(mn, mx, qmax, s16, z16, sc, z);
-            if (half == 0)
-                *(uint32_t *)(rec + gm.v_meta + (t * ng + gam) * 4) = (uint32_t)s16 | ((uint32_t)z16 << 16);
-            const float r = sc != 0.0f ? 1.0f / sc : 0.0f;
-            const float *row = x + t * kRowPad + gam * gm.Gc + half * hw;
-            unsigned char *crow = cb + t * kHeadDim + gam * gm.Gc + half * hw;
-            for (int i = 0; i < hw; i++) crow[i] = (unsigned char)quant_code(row[i], sc, r, z, qmax);
-        }
-    }
-    __syncthreads();
 
-    // pack: one 32-bit word = 32/bits consecutive codes along channels (keys) or tokens (values),
-    // byte-interleaved: the word's code number 4f + y is field f (bits [bits*f, bits*f+bits)) of
-    // byte y, so that one shift and one mask turn a word into four consecutive codes as bytes
-    const int n_words = G * kHeadDim * bits / 32;
-    const int per = 32 / bits;
-    for (int w = tid; w < n_words; w += kThreads) {
-        int t0, c0;
-        word_origin(which, bits, G, w, t0, c0);
-        uint32_t word = 0;
-        if (which == 0) {
-            for (int e = 0; e < per; e++)
-                word |= (uint32_t)cb[t0 * kHeadDim + c0 + e] << (8 * (e & 3) + bits * (e >> 2));
-        } else {
-            for (int e = 0; e < per; e++)
-                word |= (uint32_t)cb[(t0 + e) * kHeadDim + c0] << (8 * (e & 3) + bits * (e >> 2));
+        // 4. pack.  A 32-bit word holds 32/bits consecutive codes along channels (keys) or tokens
+        // (values), byte-interleaved: code number 4f + y is field f of byte y.  In LDS those codes are
+        // consecutive bytes, so a word is built from 32-bit reads: w0 | w1 << bits | w2 << 2 bits | ...
+        const int n_words = G * kHeadDim * bits / 32;
+        const int reads = 8 / bits; // 32-bit reads of four codes per word
+        for (int w = tid; w < n_words; w += kThreads) {
+            int t0, c0;
+            word_origin(which, bits, G, w, t0, c0);
+            const uint32_t *src = (const uint32_t *)(which == 0 ? cb + t0 * kHeadDim + c0 : cb + c0 * G + t0);
+            uint32_t word = src[0];
+            for (int f = 1; f < reads; f++) word |= src[f] << (bits * f);
+            ((uint32_t *)codes_out)[w] = word;
         }
-        ((uint32_t *)codes_out)[w] = word;
+        __syncthreads(); // the next item reuses the LDS buffers
     }
 }
 
@@ -341,13 +388,42 @@ __global__ __launch_bounds__(kThreads) void resid_copy_kernel(AppendArgs a)
 
 } // namespace
 
+template <int G, int GC> hipError_t launch_flush_g(const AppendArgs &a, hipStream_t s)
+{
+    const int U = a.batch * a.n_kv_heads;
+    constexpr int v_items = G * (kHeadDim / GC) * 2;
+    constexpr size_t lds = (size_t)G * kRowPad * sizeof(float) + (size_t)G * kHeadDim + kHeadDim * sizeof(float) +
+                           2 * (size_t)(v_items > kThreads ? v_items : kThreads) * sizeof(float);
+    const long long items = (long long)a.n_flush_blocks * U * 2;
+    if (items > 0x7FFFFFFF) return hipErrorInvalidValue;
+    // as many workgroups as the device holds at once (they loop over the items)
+    static const int slots = [] {
+        int per_cu = 0, dev = 0, cus = 0;
+        if (lds > 64 * 1024 &&
+            hipFuncSetAttribute((const void *)flush_block_kernel<G, GC>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds) != hipSuccess)
+            return 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, flush_block_kernel<G, GC>, kThreads, lds) != hipSuccess ||
+            hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+            return 0;
+        return per_cu * cus;
+    }();
+    if (slots < 1) return hipErrorInvalidValue;
+    const int grid = items < slots ? (int)items : slots;
+    hipLaunchKernelGGL((flush_block_kernel<G, GC>), dim3(grid), dim3(kThreads), lds, s, a, (int)items);
+    return note_launch(hipGetLastError());
+}
+template <int G> hipError_t launch_flush_gc(const AppendArgs &a, hipStream_t s)
+{
+    if (a.geom.Gc == 32) return launch_flush_g<G, 32>(a, s);
+    if (a.geom.Gc == 64) return launch_flush_g<G, 64>(a, s);
+    return launch_flush_g<G, 128>(a, s);
+}
+
 hipError_t launch_flush(const AppendArgs &a, hipStream_t s)
 {
     const int U = a.batch * a.n_kv_heads;
-    const int v_items = a.geom.G * (kHeadDim / a.geom.Gc) * 2;
-    const size_t lds = (size_t)a.geom.G * kRowPad * sizeof(float) + (size_t)a.geom.G * kHeadDim +
-                       kHeadDim * sizeof(float) + 2 * (size_t)(v_items > kThreads ? v_items : kThreads) * sizeof(float);
-    // grid.y is limited to 65535 entries
     if (U > 65535) return hipErrorInvalidValue;
     (void)hipGetLastError(); // drop any stale error left by earlier runtime calls of this thread
     if (a.geom.mean_mode == 1) {
@@ -356,9 +432,9 @@ hipError_t launch_flush(const AppendArgs &a, hipStream_t s)
         hipError_t e = note_launch(hipGetLastError());
         if (e != hipSuccess) return e;
     }
-    dim3 grid(a.n_flush_blocks, U, 2);
-    hipLaunchKernelGGL(flush_block_kernel, grid, dim3(kThreads), lds, s, a);
-    return note_launch(hipGetLastError());
+    if (a.geom.G == 32) return launch_flush_gc<32>(a, s);
+    if (a.geom.G == 64) return launch_flush_gc<64>(a, s);
+    return launch_flush_gc<128>(a, s);
 }
 
 hipError_t launch_resid_copy(const AppendArgs &a, hipStream_t s)
