@@ -142,7 +142,7 @@ __device__ __forceinline__ void word_origin(int which, int bits, int G, int w, i
 // All loops have compile-time trip counts: a thread pulls its 16..64 elements out of LDS in one
 // burst, works in registers, and writes back in one burst.
 template <int G, int GC>
-__global__ __launch_bounds__(kThreads) void flush_block_kernel(AppendArgs a, int n_items)
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu((G == 32 && GC == 32) ? 4 : 1, 8))) void flush_block_kernel(AppendArgs a, int n_items)
 {
     constexpr int NLD = G * 16 / kThreads;   // 16-byte pieces per thread and item
     constexpr int HT = G / 2;                // tokens per thread in the per-channel passes
