@@ -211,7 +211,7 @@ template <> struct CodeOps<8> { // four words = one tile line; split into nibble
 };
 
 template <int B, int G, int GC, bool MEAN, int NW, int NHG>
-__global__ __launch_bounds__(64 * NW) void decode_split_mfma_kernel(DecodeArgs a)
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2 && NHG == 1) ? 4 : 1, 8))) void decode_split_mfma_kernel(DecodeArgs a)
 {
     typedef RecLayout<B, G, GC, MEAN> RL;
     constexpr int NBC = 64 / G;            // blocks per 64-token chunk
@@ -223,9 +223,10 @@ __global__ __launch_bounds__(64 * NW) void decode_split_mfma_kernel(DecodeArgs a
     constexpr int REC = RL::REC;
     constexpr int CB = NBC * REC;          // bytes of one chunk
     constexpr int STAGE_DW = CB / 4;       // staging buffer of a wave
-    // operand scratch: key operands [NBC][NHG][2 phases][64 lanes][4], later reused for the value
-    // operands [NHG][NG][64 lanes][4]
-    constexpr int AK_DW = NBC * NHG * 512, AV_DW = NHG * NG * 256;
+    // operand scratch, reused block after block and pass after pass: key operands of one block
+    // [NHG][2 phases][64 lanes][4], value operands of NGP scale groups [NHG][NGP][64 lanes][4]
+    constexpr int NGP = NG > 2 ? 2 : NG;
+    constexpr int AK_DW = NHG * 512, AV_DW = NHG * NGP * 256;
     constexpr int OPER_DW = AK_DW > AV_DW ? AK_DW : AV_DW;
     constexpr int WAVE_DW = STAGE_DW + OPER_DW;
     constexpr int RESID_DW = 24576 / 4;    // the residual pass of wave 0 takes this much of the block's LDS
@@ -375,8 +376,9 @@ __global__ __launch_bounds__(64 * NW) void decode_split_mfma_kernel(DecodeArgs a
         wave_lds_fence();
         if (ci + NW < n_chunks) issue(ci + NW);
 
-        // ---- key side: q*scale as limbs -> LDS; zero/mean term
-        float inv_kf[NHG][NBC], beta[NHG][NBC];
+        // ---- key side, one block at a time (the operand scratch holds one block's operands):
+        // q*scale as limbs -> LDS, zero/mean term, then the block's matrix products -> scores
+        float s[NHG][4];
 #pragma unroll
         for (int bi = 0; bi < NBC; bi++) {
             // scales are non-negative binary16 values: their bit patterns order like the values,
@@ -386,9 +388,10 @@ __global__ __launch_bounds__(64 * NW) void decode_split_mfma_kernel(DecodeArgs a
             const float smax = fmaxf(h_lo(smw), h_hi(smw));
             float sb, inv_sb;
             pow2_above(smax, 0x1p-40f, sb, inv_sb);
+            float inv_kf[NHG], beta[NHG];
 #pragma unroll
             for (int hg = 0; hg < NHG; hg++) {
-                inv_kf[hg][bi] = inv_kf_base[hg] * sb;
+                inv_kf[hg] = inv_kf_base[hg] * sb;
                 // Adding 3 qb sb (1.5 * 2^E with 2^E = 2 qb sb > 2 |q s|) puts round(q s / ulp) into
                 // the low mantissa bits of the sum, ulp = qb sb 2^-22: one fused multiply-add per
                 // element does the scaling, the rounding and the float -> integer conversion.
@@ -412,7 +415,7 @@ __global__ __launch_bounds__(64 * NW) void decode_split_mfma_kernel(DecodeArgs a
                     const uint32_t Y0 = __builtin_amdgcn_perm(W, U, 0x05040100u);
                     const uint32_t Y1 = __builtin_amdgcn_perm(W, U, 0x07060302u);
                     const uint32_t Y2 = __builtin_amdgcn_perm(W2, U2, 0x05040100u);
-                    uint32_t *dst = ak + (bi * NHG + hg) * 512 + ((ph * 4 + vq) * 16 + 4 * row) * 4 + qa;
+                    uint32_t *dst = ak + hg * 512 + ((ph * 4 + vq) * 16 + 4 * row) * 4 + qa;
                     dst[0] = Y0;
                     dst[4] = Y1;
                     dst[8] = Y2;
@@ -421,47 +424,44 @@ __global__ __launch_bounds__(64 * NW) void decode_split_mfma_kernel(DecodeArgs a
                     bacc = __builtin_amdgcn_fdot2(qh[hg][ph][0], as_h2(km[bi][ph].x), bacc, false);
                     bacc = __builtin_amdgcn_fdot2(qh[hg][ph][1], as_h2(km[bi][ph].y), bacc, false);
                 }
-                beta[hg][bi] = row_sum(bacc) * kScoreScale;
+                beta[hg] = row_sum(bacc) * kScoreScale;
             }
-        }
-        wave_lds_fence();
-
-        // ---- key matrix products -> scores
-        float s[NHG][4];
-#pragma unroll
-        for (int k = 0; k < 4; k++) {
-            const int bi = k / TPB;
+            wave_lds_fence();
             v4i a0[NHG], a1[NHG];
 #pragma unroll
             for (int hg = 0; hg < NHG; hg++) {
-                a0[hg] = *(const v4i *)(ak + (bi * NHG + hg) * 512 + ((0 * 4 + row) * 16 + n) * 4);
-                a1[hg] = *(const v4i *)(ak + (bi * NHG + hg) * 512 + ((1 * 4 + row) * 16 + n) * 4);
+                a0[hg] = *(const v4i *)(ak + hg * 512 + ((0 * 4 + row) * 16 + n) * 4);
+                a1[hg] = *(const v4i *)(ak + hg * 512 + ((1 * 4 + row) * 16 + n) * 4);
             }
-            v4i acc[NHG];
-            if (B == 4) {
-                const uint4 w = kc[k];
-                const v4i b0 = CodeOps<4>::line(w.x, w.y), b1 = CodeOps<4>::line(w.z, w.w);
+            wave_lds_fence(); // the operands are in registers: the scratch may be overwritten
 #pragma unroll
-                for (int hg = 0; hg < NHG; hg++) acc[hg] = mfma(a1[hg], b1, mfma(a0[hg], b0, v4i{0, 0, 0, 0}));
-            } else if (B == 2) {
-                const uint4 w = kc[k >> 1];
-                const v4i b0 = CodeOps<2>::line((k & 1) ? w.z : w.x), b1 = CodeOps<2>::line((k & 1) ? w.w : w.y);
+            for (int k = bi * TPB; k < (bi + 1) * TPB; k++) {
+                v4i acc[NHG];
+                if (B == 4) {
+                    const uint4 w = kc[k];
+                    const v4i b0 = CodeOps<4>::line(w.x, w.y), b1 = CodeOps<4>::line(w.z, w.w);
 #pragma unroll
-                for (int hg = 0; hg < NHG; hg++) acc[hg] = mfma(a1[hg], b1, mfma(a0[hg], b0, v4i{0, 0, 0, 0}));
-            } else {
-                const uint4 wa = kc[2 * k], wb = kc[2 * k + 1];
-                const v4i lo0 = CodeOps<8>::lo(wa), hi0 = CodeOps<8>::hi(wa);
-                const v4i lo1 = CodeOps<8>::lo(wb), hi1 = CodeOps<8>::hi(wb);
+                    for (int hg = 0; hg < NHG; hg++) acc[hg] = mfma(a1[hg], b1, mfma(a0[hg], b0, v4i{0, 0, 0, 0}));
+                } else if (B == 2) {
+                    const uint4 w = kc[k >> 1];
+                    const v4i b0 = CodeOps<2>::line((k & 1) ? w.z : w.x), b1 = CodeOps<2>::line((k & 1) ? w.w : w.y);
 #pragma unroll
-                for (int hg = 0; hg < NHG; hg++) {
-                    const v4i alo = mfma(a1[hg], lo1, mfma(a0[hg], lo0, v4i{0, 0, 0, 0}));
-                    const v4i ahi = mfma(a1[hg], hi1, mfma(a0[hg], hi0, v4i{0, 0, 0, 0}));
-                    acc[hg] = alo + ahi * 16;
+                    for (int hg = 0; hg < NHG; hg++) acc[hg] = mfma(a1[hg], b1, mfma(a0[hg], b0, v4i{0, 0, 0, 0}));
+                } else {
+                    const uint4 wa = kc[2 * k], wb = kc[2 * k + 1];
+                    const v4i lo0 = CodeOps<8>::lo(wa), hi0 = CodeOps<8>::hi(wa);
+                    const v4i lo1 = CodeOps<8>::lo(wb), hi1 = CodeOps<8>::hi(wb);
+#pragma unroll
+                    for (int hg = 0; hg < NHG; hg++) {
+                        const v4i alo = mfma(a1[hg], lo1, mfma(a0[hg], lo0, v4i{0, 0, 0, 0}));
+                        const v4i ahi = mfma(a1[hg], hi1, mfma(a0[hg], hi0, v4i{0, 0, 0, 0}));
+                        acc[hg] = alo + ahi * 16;
+                    }
                 }
-            }
 #pragma unroll
-            for (int hg = 0; hg < NHG; hg++)
-                s[hg][k] = blk_ok[bi] ? limbs_to_float(acc[hg]) * inv_kf[hg][bi] + beta[hg][bi] : -INFINITY;
+                for (int hg = 0; hg < NHG; hg++)
+                    s[hg][k] = blk_ok[bi] ? limbs_to_float(acc[hg]) * inv_kf[hg] + beta[hg] : -INFINITY;
+            }
         }
 
         // ---- largest value scale of the chunk (the same for every head)
@@ -476,77 +476,90 @@ __global__ __launch_bounds__(64 * NW) void decode_split_mfma_kernel(DecodeArgs a
         const float vmagic = 3.0f * sbv; // p <= 1, scale < sbv: same construction as on the key side
         const uint32_t vfix = 0x80808080u - __float_as_uint(vmagic);
 
-        // ---- softmax bookkeeping; value side: p*scale as limbs -> LDS; zero and mean terms
-        float alpha[NHG], o_scale[NHG], psum_b[NHG][NBC];
+        // ---- softmax bookkeeping; zero and mean terms of the value side
+        float p[NHG][4], alpha[NHG], o_scale[NHG], psum_b[NHG][NBC];
 #pragma unroll
         for (int hg = 0; hg < NHG; hg++) {
-            float p[4], wc;
-            softmax_chunk(s[hg], st[hg], p, alpha[hg], wc);
+            float wc;
+            softmax_chunk(s[hg], st[hg], p[hg], alpha[hg], wc);
             o_scale[hg] = wc * sbv * 0x1p-22f;
 #pragma unroll
             for (int gam = 0; gam < NG; gam++) {
                 float zsum = 0.0f;
 #pragma unroll
-                for (int k = 0; k < 4; k++) {
-                    zsum += p[k] * h_hi(vm[k][gam]);
-                    const uint32_t X = (__float_as_uint(__builtin_fmaf(p[k], h_lo(vm[k][gam]), vmagic)) + vfix) ^ 0x80808080u;
-                    // byte transpose across the quad: lane with quad position L ends up with limb L
-                    // of the quad's four consecutive tokens
-                    const uint32_t P = dpp_u<0xB1>(X);
-                    const uint32_t T = __builtin_amdgcn_perm(P, X, sel1);
-                    const uint32_t Q = dpp_u<0x4E>(T);
-                    const uint32_t Y = __builtin_amdgcn_perm(Q, T, sel2);
-                    av[(hg * NG + gam) * 256 + k * 64 + (4 * row + qa) * 4 + vq] = Y;
-                }
+                for (int k = 0; k < 4; k++) zsum += p[hg][k] * h_hi(vm[k][gam]);
                 st[hg].Zp[gam] = st[hg].Zp[gam] * alpha[hg] + wc * zsum;
             }
 #pragma unroll
             for (int bi = 0; bi < NBC; bi++) {
                 float t = 0.0f;
 #pragma unroll
-                for (int k = bi * TPB; k < (bi + 1) * TPB; k++) t += p[k];
+                for (int k = bi * TPB; k < (bi + 1) * TPB; k++) t += p[hg][k];
                 psum_b[hg][bi] = MEAN ? row_sum(t) * wc : 0.0f;
             }
         }
-        wave_lds_fence();
 
-        // ---- value matrix products -> output accumulators
-        v4i avr[NHG][NG];
+        // ---- value side in passes of NGP scale groups: p*scale as limbs -> LDS, matrix products
+        // -> output accumulators
 #pragma unroll
-        for (int hg = 0; hg < NHG; hg++)
+        for (int vp = 0; vp < NG / NGP; vp++) {
 #pragma unroll
-            for (int gam = 0; gam < NG; gam++)
-                avr[hg][gam] = *(const v4i *)(av + (hg * NG + gam) * 256 + (row * 16 + n) * 4);
+            for (int hg = 0; hg < NHG; hg++)
 #pragma unroll
-        for (int ct = 0; ct < 8; ct++) {
-            v4i acc[NHG];
-            if (B == 4) {
-                const uint4 w = vc[ct >> 1];
-                const v4i bo = CodeOps<4>::line((ct & 1) ? w.z : w.x, (ct & 1) ? w.w : w.y);
+                for (int gl = 0; gl < NGP; gl++) {
+                    const int gam = vp * NGP + gl;
 #pragma unroll
-                for (int hg = 0; hg < NHG; hg++) acc[hg] = mfma(avr[hg][ct / TPG], bo, v4i{0, 0, 0, 0});
-            } else if (B == 2) {
-                const uint4 w = vc[ct >> 2];
-                const uint32_t ww = (ct & 3) == 0 ? w.x : ((ct & 3) == 1 ? w.y : ((ct & 3) == 2 ? w.z : w.w));
-                const v4i bo = CodeOps<2>::line(ww);
+                    for (int k = 0; k < 4; k++) {
+                        const uint32_t X = (__float_as_uint(__builtin_fmaf(p[hg][k], h_lo(vm[k][gam]), vmagic)) + vfix) ^ 0x80808080u;
+                        // byte transpose across the quad: lane with quad position L ends up with limb L
+                        // of the quad's four consecutive tokens
+                        const uint32_t P = dpp_u<0xB1>(X);
+                        const uint32_t T = __builtin_amdgcn_perm(P, X, sel1);
+                        const uint32_t Q = dpp_u<0x4E>(T);
+                        const uint32_t Y = __builtin_amdgcn_perm(Q, T, sel2);
+                        av[(hg * NGP + gl) * 256 + k * 64 + (4 * row + qa) * 4 + vq] = Y;
+                    }
+                }
+            wave_lds_fence();
+            v4i avr[NHG][NGP];
 #pragma unroll
-                for (int hg = 0; hg < NHG; hg++) acc[hg] = mfma(avr[hg][ct / TPG], bo, v4i{0, 0, 0, 0});
-            } else {
-                const v4i lo = CodeOps<8>::lo(vc[ct]), hi = CodeOps<8>::hi(vc[ct]);
+            for (int hg = 0; hg < NHG; hg++)
+#pragma unroll
+                for (int gl = 0; gl < NGP; gl++)
+                    avr[hg][gl] = *(const v4i *)(av + (hg * NGP + gl) * 256 + (row * 16 + n) * 4);
+            wave_lds_fence(); // operands in registers: the next pass (or chunk) may overwrite the scratch
+#pragma unroll
+            for (int ct = vp * NGP * TPG; ct < (vp + 1) * NGP * TPG; ct++) {
+                const int gl = ct / TPG - vp * NGP;
+                v4i acc[NHG];
+                if (B == 4) {
+                    const uint4 w = vc[ct >> 1];
+                    const v4i bo = CodeOps<4>::line((ct & 1) ? w.z : w.x, (ct & 1) ? w.w : w.y);
+#pragma unroll
+                    for (int hg = 0; hg < NHG; hg++) acc[hg] = mfma(avr[hg][gl], bo, v4i{0, 0, 0, 0});
+                } else if (B == 2) {
+                    const uint4 w = vc[ct >> 2];
+                    const uint32_t ww = (ct & 3) == 0 ? w.x : ((ct & 3) == 1 ? w.y : ((ct & 3) == 2 ? w.z : w.w));
+                    const v4i bo = CodeOps<2>::line(ww);
+#pragma unroll
+                    for (int hg = 0; hg < NHG; hg++) acc[hg] = mfma(avr[hg][gl], bo, v4i{0, 0, 0, 0});
+                } else {
+                    const v4i lo = CodeOps<8>::lo(vc[ct]), hi = CodeOps<8>::hi(vc[ct]);
+#pragma unroll
+                    for (int hg = 0; hg < NHG; hg++) {
+                        const v4i alo = mfma(avr[hg][gl], lo, v4i{0, 0, 0, 0});
+                        const v4i ahi = mfma(avr[hg][gl], hi, v4i{0, 0, 0, 0});
+                        acc[hg] = alo + ahi * 16;
+                    }
+                }
 #pragma unroll
                 for (int hg = 0; hg < NHG; hg++) {
-                    const v4i alo = mfma(avr[hg][ct / TPG], lo, v4i{0, 0, 0, 0});
-                    const v4i ahi = mfma(avr[hg][ct / TPG], hi, v4i{0, 0, 0, 0});
-                    acc[hg] = alo + ahi * 16;
+                    float o = st[hg].O[ct] * alpha[hg] + limbs_to_float(acc[hg]) * o_scale[hg];
+#pragma unroll
+                    for (int bi = 0; bi < NBC; bi++)
+                        o += __half2float(__ushort_as_half(vmean[bi][ct])) * psum_b[hg][bi];
+                    st[hg].O[ct] = o;
                 }
-            }
-#pragma unroll
-            for (int hg = 0; hg < NHG; hg++) {
-                float o = st[hg].O[ct] * alpha[hg] + limbs_to_float(acc[hg]) * o_scale[hg];
-#pragma unroll
-                for (int bi = 0; bi < NBC; bi++)
-                    o += __half2float(__ushort_as_half(vmean[bi][ct])) * psum_b[hg][bi];
-                st[hg].O[ct] = o;
             }
         }
     }
