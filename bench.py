@@ -24,7 +24,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published
 # HBM bytes per launch of the decode split kernel divided by its algorithmic bytes, from the
-# FETCH_SIZE / WRITE_SIZE counter runs summarised in profiles/decode_split_mfma_hbm_traffic.txt
+# FETCH_SIZE / WRITE_SIZE counter runs summarised in profiles/hot_path_kernels_hbm_traffic.txt
 # (counters scaled by what they read for a plain copy of known size: x2.000 and x1.000)
 TRAFFIC_RATIO = {2: 1.003, 4: 1.001, 8: 1.000}
 
