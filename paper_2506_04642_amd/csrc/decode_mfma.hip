@@ -320,7 +320,19 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
     const uint32_t sel1 = (qa & 1) ? 0x03070105u : 0x06020400u;
     const uint32_t sel2 = (qa & 2) ? 0x03020706u : 0x05040100u;
 
-    for (int ci = wave; ci < n_chunks; ci += NW) {
+    // Issue priority falls as a wave advances (quarters of its chunks).  By default the oldest wave
+    // of a SIMD wins every arbitration, so the workgroups that arrived first on a compute unit run
+    // ahead and leave the last ones to finish alone, at low occupancy and far below the memory
+    // rate; with the laggards preferred, all waves end within about a quarter of each other.
+    const int my_iters = (n_chunks - wave + NW - 1) / NW;
+    for (int ci = wave, itn = 0; ci < n_chunks; ci += NW, itn++) {
+        if (B != 8) { // the 8-bit instance runs one wave per SIMD: nothing to arbitrate
+            const int quart = itn * 4 / my_iters;
+            if (quart == 0) __builtin_amdgcn_s_setprio(3);
+            else if (quart == 1) __builtin_amdgcn_s_setprio(2);
+            else if (quart == 2) __builtin_amdgcn_s_setprio(1);
+            else __builtin_amdgcn_s_setprio(0);
+        }
         const int blk0 = w0 + ci * cstride;
         bool blk_ok[NBC];
 #pragma unroll
@@ -563,6 +575,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
             }
         }
     }
+
+    if (B != 8) __builtin_amdgcn_s_setprio(0);
 
     // ---- raw residual tokens (Sec. 3.3): wave 0 of the split that is next in turn
     const bool has_resid = a.r > 0 && sp == chunks_total % ns;
