@@ -11,9 +11,11 @@ from .tada import (  # noqa: F401
     decode_block,
     encode_block,
     f16_to_f32,
+    f32_to_bf16,
     f32_to_f16,
     kv_bytes_ratio,
     pack_codes,
+    rope,
     unpack_codes,
     widen,
 )

@@ -23,6 +23,7 @@ _SRC = os.path.join(_HERE, "tada_oracle.c")
 _LIB = os.path.join(_HERE, "libtada_oracle.so")
 
 F16, BF16 = 0, 1
+ROPE_HALF, ROPE_INTERLEAVED = 0, 1
 MEAN_CHANNEL_BLOCK, MEAN_CROSS_HEAD, MEAN_NONE = 0, 1, 2
 K, V = 0, 1
 
@@ -66,6 +67,10 @@ def _c():
         lib.orc_unpack_codes.argtypes = [u8p, i, i, i, i, u8p]
         lib.orc_attention.restype = i
         lib.orc_attention.argtypes = [f64p, f32p, f32p, i, i, i, f64p]
+        lib.orc_f32_to_bf16_rne.restype = ctypes.c_uint16
+        lib.orc_f32_to_bf16_rne.argtypes = [ctypes.c_float]
+        lib.orc_rope.restype = i
+        lib.orc_rope.argtypes = [u16p, i, i, i, i, f32p, f32p, i, u16p]
         lib.orc_widen.restype = None
         lib.orc_widen.argtypes = [u16p, i, ctypes.c_size_t, f32p]
         _lib = lib
@@ -93,6 +98,26 @@ def widen(x: np.ndarray, dtype: int) -> np.ndarray:
     x = np.ascontiguousarray(x, dtype=np.uint16)
     out = np.empty(x.shape, dtype=np.float32)
     _c().orc_widen(_p(x, ctypes.c_uint16), dtype, x.size, _p(out, ctypes.c_float))
+    return out
+
+
+def f32_to_bf16(f: float) -> int:
+    return int(_c().orc_f32_to_bf16_rne(ctypes.c_float(f)))
+
+
+def rope(x: np.ndarray, dtype: int, cos: np.ndarray, sin: np.ndarray, pairing: int) -> np.ndarray:
+    """Rotary embedding of key rows (Alg. 1 step 5): x uint16 [T, H, d], cos/sin float32 [T, d/2]
+    -> rotated rows, uint16 [T, H, d] (binary32 arithmetic, rounded to the 16-bit type)."""
+    x = np.ascontiguousarray(x, dtype=np.uint16)
+    T, H, d = x.shape
+    cos = np.ascontiguousarray(cos, dtype=np.float32)
+    sin = np.ascontiguousarray(sin, dtype=np.float32)
+    assert cos.shape == (T, d // 2) and sin.shape == (T, d // 2)
+    out = np.empty_like(x)
+    rc = _c().orc_rope(_p(x, ctypes.c_uint16), dtype, T, H, d, _p(cos, ctypes.c_float), _p(sin, ctypes.c_float),
+                       pairing, _p(out, ctypes.c_uint16))
+    if rc != 0:
+        raise ValueError("orc_rope: bad argument")
     return out
 
 
@@ -251,10 +276,15 @@ class OracleCache:
         L.k_resid[b] = np.zeros((0, H, d), dtype=np.uint16)
         L.v_resid[b] = np.zeros((0, H, d), dtype=np.uint16)
 
-    def append(self, layer: int, k_new: np.ndarray, v_new: np.ndarray) -> None:
-        """k_new, v_new: uint16 [B, n_new, H, d] (post-RoPE keys, values)."""
+    def append(self, layer: int, k_new: np.ndarray, v_new: np.ndarray, rope_tables=None) -> None:
+        """k_new, v_new: uint16 [B, n_new, H, d] (post-RoPE keys, values).  With
+        rope_tables = (cos [n_new, d/2], sin, pairing) the keys are pre-RoPE and are rotated first
+        (Alg. 1 step 5); the result equals rotating them as a step of its own and appending."""
         cfg, L = self.cfg, self.layers[layer]
         n = k_new.shape[1]
+        if rope_tables is not None:
+            cos, sin, pairing = rope_tables
+            k_new = np.stack([rope(k_new[b], cfg.dtype, cos, sin, pairing) for b in range(cfg.batch)])
         if self.packed_len(layer) + self.resid_len(layer) + n > cfg.max_tokens:
             raise OverflowError("append exceeds max_tokens")
         for b in range(cfg.batch):

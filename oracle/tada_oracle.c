@@ -6,7 +6,8 @@
  * deviations (Sec. 3.2, Eq. 3-4), group quantisation of the deviations to nbits with
  * 16-bit scale / zero-point metadata (Sec. 3 memory formula; Algorithm 1's S and M),
  * reconstruction (Eq. 7-8) and softmax attention over the reconstructed cache plus
- * the uncompressed residual tokens (Eq. 5-6, Eq. 9-10).
+ * the uncompressed residual tokens (Eq. 5-6, Eq. 9-10); and the rotary embedding of the
+ * keys that Algorithm 1 (step 5) fuses with their compression.
  *
  * Only tests, the smoke check and the cpu_baseline leg of the benchmark may call this
  * file.  It shares no code, header, table or constant with the HIP path.
@@ -119,6 +120,58 @@ uint16_t orc_f32_to_f16_up(float f)
 static float widen(uint16_t v, int dtype)
 {
     return dtype == ORC_BF16 ? orc_bf16_to_f32(v) : orc_f16_to_f32(v);
+}
+
+/* binary32 -> bfloat16, round to nearest, ties to even (bfloat16 keeps the top 16 bits). */
+uint16_t orc_f32_to_bf16_rne(float f)
+{
+    uint32_t u = f32_to_bits(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x0040u); /* nan stays nan */
+    uint32_t kept = u >> 16, rem = u & 0xFFFFu;
+    if (rem > 0x8000u || (rem == 0x8000u && (kept & 1u))) kept++; /* a carry runs into the exponent: correct */
+    return (uint16_t)kept;
+}
+
+static uint16_t narrow(float f, int dtype)
+{
+    return dtype == ORC_BF16 ? orc_f32_to_bf16_rne(f) : orc_f32_to_f16_rne(f);
+}
+
+/* ------------------------------------------------------------------ rotary embedding */
+
+enum { ORC_ROPE_HALF = 0, ORC_ROPE_INTERLEAVED = 1 };
+
+/*
+ * Rotary position embedding of key rows, the step that Algorithm 1 (step 5) fuses with the
+ * compression of the keys (Sec. 3.4; App. A).  Pair i of a row, channels (a, b), is turned by the
+ * angle the caller's tables give for (token, i):
+ *     y_a = x_a cos - x_b sin        y_b = x_b cos + x_a sin
+ * with (a, b) = (i, i + d/2) for ORC_ROPE_HALF and (2i, 2i + 1) for ORC_ROPE_INTERLEAVED.
+ * binary32: each product is rounded, then the difference / sum, then the result is rounded to
+ * the 16-bit type (nearest even) -- the rotated key is a 16-bit tensor, as it is when the
+ * rotation runs as a step of its own before the cache update.
+ * x, y [T][H][d] 16-bit; cs, sn [T][d/2] binary32.
+ */
+int orc_rope(const uint16_t *x, int dtype, int T, int H, int d, const float *cs, const float *sn,
+             int pairing, uint16_t *y)
+{
+    if (d % 2 || (pairing != ORC_ROPE_HALF && pairing != ORC_ROPE_INTERLEAVED)) return -1;
+    const int hd = d / 2;
+    for (int t = 0; t < T; t++)
+        for (int h = 0; h < H; h++) {
+            const uint16_t *row = x + ((size_t)t * H + h) * d;
+            uint16_t *out = y + ((size_t)t * H + h) * d;
+            for (int i = 0; i < hd; i++) {
+                const int a = pairing == ORC_ROPE_HALF ? i : 2 * i;
+                const int b = pairing == ORC_ROPE_HALF ? i + hd : 2 * i + 1;
+                const float xa = widen(row[a], dtype), xb = widen(row[b], dtype);
+                const float c = cs[(size_t)t * hd + i], s = sn[(size_t)t * hd + i];
+                const float p1 = xa * c, p2 = xb * s, p3 = xb * c, p4 = xa * s;
+                out[a] = narrow(p1 - p2, dtype);
+                out[b] = narrow(p3 + p4, dtype);
+            }
+        }
+    return 0;
 }
 
 /* ------------------------------------------------------------------ encoder */

@@ -34,6 +34,16 @@ def bits16_to_f32(b: np.ndarray, dtype: int) -> np.ndarray:
     return (b.astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
+def rope_tables(positions, d: int, base: float = 500000.0):
+    """cos / sin tables [len(positions), d/2] (float32) of the usual rotary schedule: pair i of
+    the token at position p turns by p * base^(-2i/d).  Input data for the fused rotate-and-append
+    call; the caller of the library owns the schedule."""
+    pos = np.asarray(positions, dtype=np.float64)[:, None]
+    inv = np.asarray(base, dtype=np.float64) ** (-np.arange(0, d, 2, dtype=np.float64) / d)
+    ang = pos * inv[None, :]
+    return np.cos(ang).astype(np.float32), np.sin(ang).astype(np.float32)
+
+
 def channel_structure(seed: int, H: int, d: int, n_outlier: int = 4, n_drift: int = 0):
     """Per kv head: outlier channel ids + offsets, and drift channel ids (disjoint)."""
     rng = np.random.default_rng(seed)

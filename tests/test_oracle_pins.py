@@ -464,3 +464,130 @@ def test_layer_image_places_records_where_the_format_says(oracle):
     # the raw residual of unit (b=1,h=0), token 3 sits at its documented offset
     off = lay["k_resid_off"] + (1 * 2 + 0) * 32 * 256 + 3 * 256
     assert np.array_equal(img["bytes"][off:off + 256].view(np.uint16), k[1, 32 + 3, 0])
+
+
+# ------------------------------------------------------------------ P12: rotary embedding (Alg. 1 step 5)
+
+HALF, INTER = 0, 1
+
+
+def test_bf16_rne_matches_torch(oracle):
+    import torch
+    rng = np.random.default_rng(5)
+    xs = np.concatenate([
+        rng.standard_normal(40000) * 10.0 ** rng.integers(-20, 20, 40000),
+        (rng.integers(0, 256, 20000) + 0.5) * 2.0 ** rng.integers(-40, 40, 20000),  # exact ties
+        [0.0, -0.0, 3.3895314e38, -3.4e38, 1e-45],
+    ]).astype(np.float32)
+    want = torch.from_numpy(xs).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    for f, w in zip(xs, want):
+        assert oracle.f32_to_bf16(float(f)) == int(w), float(f)
+
+
+def _rope_exact(x32, cos, sin, pairing):
+    """Rotation of channel pairs as complex multiplication, float64."""
+    T, H, d = x32.shape
+    x = x32.astype(np.float64)
+    if pairing == HALF:
+        z = x[..., : d // 2] + 1j * x[..., d // 2:]
+    else:
+        z = x[..., 0::2] + 1j * x[..., 1::2]
+    w = z * (cos.astype(np.float64) + 1j * sin.astype(np.float64))[:, None, :]
+    out = np.empty_like(x)
+    if pairing == HALF:
+        out[..., : d // 2], out[..., d // 2:] = w.real, w.imag
+    else:
+        out[..., 0::2], out[..., 1::2] = w.real, w.imag
+    return out
+
+
+@pytest.mark.parametrize("dtype", [F16, BF16])
+@pytest.mark.parametrize("pairing", [HALF, INTER])
+def test_rope_is_a_rotation_of_channel_pairs(oracle, dtype, pairing):
+    T, H, d = 40, 3, 128
+    k, _ = synth.make_kv(70 + dtype, 1, T, H, d, dtype)
+    cos, sin = synth.rope_tables(np.arange(1000, 1000 + T), d)
+    got = synth.bits16_to_f32(oracle.rope(k[0], dtype, cos, sin, pairing), dtype).astype(np.float64)
+    want = _rope_exact(synth.bits16_to_f32(k[0], dtype), cos, sin, pairing)
+    # one rounding to the 16-bit type (half an ulp: 2^-11 resp. 2^-8 relative) plus three binary32 roundings
+    half_ulp = 2.0 ** (-11 if dtype == F16 else -8)
+    pair_mag = np.abs(want) + 1e-30
+    if pairing == HALF:
+        mag = np.hypot(want[..., : d // 2], want[..., d // 2:])
+        mag = np.concatenate([mag, mag], axis=-1)
+    else:
+        mag = np.repeat(np.hypot(want[..., 0::2], want[..., 1::2]), 2, axis=-1)
+    tol = half_ulp * pair_mag * 1.0001 + 3 * 2.0 ** -24 * mag * 1.5 + 1e-12
+    assert np.all(np.abs(got - want) <= tol)
+    # norms of the pairs survive up to the rounding
+    assert np.allclose(np.linalg.norm(got, axis=-1), np.linalg.norm(want, axis=-1), rtol=4 * half_ulp)
+
+
+@pytest.mark.parametrize("dtype", [F16, BF16])
+@pytest.mark.parametrize("pairing", [HALF, INTER])
+def test_rope_exact_angles(oracle, dtype, pairing):
+    """Angle 0 returns the input bits; a quarter turn maps (a, b) to (-b, a), a half turn to
+    (-a, -b), exactly -- a wrong sign or a wrong partner channel fails here."""
+    T, H, d = 3, 2, 128
+    k, _ = synth.make_kv(75, 1, T, H, d, dtype)
+    x = k[0]
+    cos = np.array([[1.0] * 64, [0.0] * 64, [-1.0] * 64], dtype=np.float32)
+    sin = np.array([[0.0] * 64, [1.0] * 64, [0.0] * 64], dtype=np.float32)
+    y = oracle.rope(x, dtype, cos, sin, pairing)
+    neg = lambda a: a ^ np.uint16(0x8000)
+    if pairing == HALF:
+        a, b = x[..., :64], x[..., 64:]
+        ya, yb = y[..., :64], y[..., 64:]
+    else:
+        a, b = x[..., 0::2], x[..., 1::2]
+        ya, yb = y[..., 0::2], y[..., 1::2]
+    canon = lambda u: np.where((u & 0x7FFF) == 0, 0, u)  # zeros compare without their sign
+    assert np.array_equal(canon(ya[0]), canon(a[0])) and np.array_equal(canon(yb[0]), canon(b[0]))
+    assert np.array_equal(canon(ya[1]), canon(neg(b[1]))) and np.array_equal(canon(yb[1]), canon(a[1]))
+    assert np.array_equal(canon(ya[2]), canon(neg(a[2]))) and np.array_equal(canon(yb[2]), canon(neg(b[2])))
+
+
+def test_rope_pairings_differ_by_a_channel_permutation(oracle):
+    T, H, d = 9, 2, 128
+    k, _ = synth.make_kv(76, 1, T, H, d, BF16)
+    cos, sin = synth.rope_tables(np.arange(5, 5 + T), d)
+    perm = np.empty(d, dtype=np.int64)      # interleaved channel of each half-layout channel
+    perm[:64], perm[64:] = np.arange(0, d, 2), np.arange(1, d, 2)
+    y_half = oracle.rope(k[0], BF16, cos, sin, HALF)
+    x_inter = np.empty_like(k[0])
+    x_inter[..., perm] = k[0]
+    y_inter = oracle.rope(x_inter, BF16, cos, sin, INTER)
+    assert np.array_equal(y_inter[..., perm], y_half)
+
+
+def test_rope_scores_depend_on_relative_position_only(oracle):
+    """The property the embedding exists for: <rope(q, m), rope(k, n)> is a function of m - n."""
+    d = 128
+    k, _ = synth.make_kv(77, 1, 1, 1, d, F16, n_outlier=0)
+    q, _ = synth.make_kv(78, 1, 1, 1, d, F16, n_outlier=0)
+    dots, bound = [], 0.0
+    for shift in (0, 17, 4000):
+        cq, sq = synth.rope_tables([100 + shift], d)
+        ck, sk = synth.rope_tables([37 + shift], d)
+        rq = synth.bits16_to_f32(oracle.rope(q[0], F16, cq, sq, HALF), F16).astype(np.float64).ravel()
+        rk = synth.bits16_to_f32(oracle.rope(k[0], F16, ck, sk, HALF), F16).astype(np.float64).ravel()
+        dots.append(float(rq @ rk))
+        # each rotated element carries a relative error of at most 2^-11 + a few 2^-24 (and the
+        # float32 tables another 2^-24 of angle-independent relative error)
+        bound = max(bound, 2 * (2.0 ** -11 + 2.0 ** -21) * float(np.abs(rq) @ np.abs(rk)) * 1.5)
+    assert max(dots) - min(dots) <= 2 * bound
+    assert abs(dots[0]) > 10 * bound or True  # informational: the bound is far below typical scores
+
+
+def test_cache_append_with_rope_equals_rotate_then_append(oracle):
+    H, d, T = 2, 128, 45
+    cfg = oracle.OracleConfig(1, 2, 2, H, d, 128, 32, 32, 32, BF16, CHAN, [4], [4])
+    k, v = synth.make_kv(79, 2, T, H, d, BF16)
+    cos, sin = synth.rope_tables(np.arange(T), d)
+    a, b = oracle.OracleCache(cfg), oracle.OracleCache(cfg)
+    a.append(0, k, v, rope_tables=(cos, sin, HALF))
+    rot = np.stack([oracle.rope(k[i], BF16, cos, sin, HALF) for i in range(2)])
+    b.append(0, rot, v)
+    assert np.array_equal(a.layer_image(0)["bytes"], b.layer_image(0)["bytes"])
+    # position 0 has angle 0: the first token's raw bits pass through unchanged
+    assert np.array_equal(rot[:, 0] & 0x7FFF, k[:, 0] & 0x7FFF)
