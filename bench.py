@@ -198,6 +198,38 @@ def main():
     torch.cuda.synchronize()
     app_s = time.perf_counter() - app_t0
 
+    # ---- rotation fused into the bulk append (Alg. 1 step 5), on a scratch cache of one layer per
+    # bit width: the same 4096-token chunks through kv_quant_append and through kv_rope_quant_append
+    rope_stats = {}
+    n_rope = 4096
+    sbits = sorted(set(bits))
+    scfg = kv.make_config(len(sbits), B, Hq, Hkv, d, 2 * n_rope, G, G, G, kv.KV_BF16, kv.KV_MEAN_CHANNEL_BLOCK, sbits, sbits)
+    scratch = kv.KVCache(scfg, device=dev, zero=False)
+    kr, vr = synth.make_kv_torch(4242, B, n_rope, Hkv, d, synth.BF16, dev)
+    cos_h, sin_h = synth.rope_tables(np.arange(n_rope), d)
+    cos_d, sin_d = torch.from_numpy(cos_h).to(dev), torch.from_numpy(sin_h).to(dev)
+    for fused in (False, True):
+        ts = []
+        for rep in range(4):
+            kv.kv_cache_reset(scratch.handle, -1)
+            torch.cuda.synchronize()
+            c0.record(stream)
+            for l in range(len(sbits)):
+                if fused:
+                    scratch.append_rope(l, kr, vr, cos_d, sin_d, kv.KV_ROPE_HALF)
+                else:
+                    scratch.append(l, kr, vr)
+            c1.record(stream)
+            c1.synchronize()
+            ts.append(c0.elapsed_time(c1))
+        ms = sorted(ts[1:])[len(ts[1:]) // 2]
+        tok = len(sbits) * B * n_rope
+        rope_stats["rope_fused" if fused else "plain"] = {
+            "tokens_per_s": round(tok / (ms / 1e3), 1),
+            "input_GBps": round(tok * Hkv * d * 2 * 2 / (ms / 1e3) / 1e9, 1)}
+    scratch.close()
+    del scratch, kr, vr
+
     result = {
         "metric": "decode_attn_effective_hbm_GBps",
         "value": round(total_bytes / wall / 1e9, 2),
@@ -222,6 +254,7 @@ def main():
             "bulk_input_GBps": round(bulk_tokens * Hkv * d * 2 * 2 / (fill_ms / 1e3) / 1e9, 1),
             "single_token_tokens_per_s": round(B * n_app / app_s, 1) if n_app else None,
             "single_token_us_per_layer_call": round(app_s / max(n_app * L, 1) * 1e6, 2) if n_app else None,
+            "bulk_4096_token_calls": rope_stats,
         },
         "roofline": {"bound": "hbm", "kernel": "decode split kernel (all layers, weighted by layer)",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",

@@ -141,6 +141,27 @@ kv_status kv_quant_append(kv_cache *cache, int32_t layer, const void *k_new, con
                           int32_t n_new, int64_t stride_b, int64_t stride_t, int64_t stride_h,
                           void *stream);
 
+/* kv_quant_append with the rotary position embedding of the keys fused in (Algorithm 1 step 5,
+ * "RoPECompress"; Sec. 3.4 and App. A: the rotation is the last computation before the cache
+ * update, so the two are one kernel and the rotated keys never make a round trip through memory).
+ *   k_pre    : device, keys BEFORE the rotation; shape, strides and alignment as k_new above
+ *   rope_cos, rope_sin : device, float32 [n_new, head_dim/2], contiguous: cosine and sine of the
+ *              angle of (token t of this call, channel pair i).  The caller owns the schedule
+ *              (positions, base, scaling); the tables may be reused once the stream has passed.
+ *   pairing  : which channels form pair i (kv_rope_pairing)
+ * Pair (a, b) becomes (x_a cos - x_b sin, x_b cos + x_a sin), evaluated in binary32 with one
+ * rounding per operation and then rounded (nearest even) to cfg.dtype; from there on the call is
+ * kv_quant_append of the rotated keys, bit for bit.  Values are not rotated.
+ * Errors as kv_quant_append; KV_E_NULL for a missing table, KV_E_BAD_CONFIG for a bad pairing. */
+typedef enum {
+    KV_ROPE_HALF = 0,        /* pair i = channels (i, i + head_dim/2)  */
+    KV_ROPE_INTERLEAVED = 1  /* pair i = channels (2i, 2i + 1)         */
+} kv_rope_pairing;
+kv_status kv_rope_quant_append(kv_cache *cache, int32_t layer, const void *k_pre, const void *v_new,
+                               int32_t n_new, int64_t stride_b, int64_t stride_t, int64_t stride_h,
+                               const float *rope_cos, const float *rope_sin, int32_t pairing,
+                               void *stream);
+
 /* One decode step of attention for `layer` over all tokens currently cached (packed + residual).
  *   q    : device, [batch, n_q_heads, head_dim], 16-bit cfg.dtype, contiguous, post-RoPE
  *   out  : device, [batch, n_q_heads, head_dim] float32, contiguous

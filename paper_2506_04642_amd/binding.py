@@ -29,7 +29,7 @@ KV_MEAN_CHANNEL_BLOCK, KV_MEAN_CROSS_HEAD, KV_MEAN_NONE = 0, 1, 2
 
 EXPORTS = [
     "kv_cache_bytes", "kv_workspace_bytes", "kv_cache_create", "kv_cache_destroy", "kv_cache_reset",
-    "kv_cache_len", "kv_cache_describe", "kv_quant_append", "kv_decode_attn", "kv_decode_attn_split",
+    "kv_cache_len", "kv_cache_describe", "kv_quant_append", "kv_rope_quant_append", "kv_decode_attn", "kv_decode_attn_split",
     "kv_decode_attn_merge", "kv_decode_splits", "kv_decode_bytes", "kv_set_decode_path", "kv_set_decode_splits", "kv_strerror", "kv_last_hip_error",
 ]
 
@@ -65,6 +65,7 @@ _lib.kv_cache_reset.argtypes = [_vp, _i32]
 _lib.kv_cache_len.argtypes = [_vp, _i32, ctypes.POINTER(_i32), ctypes.POINTER(_i32)]
 _lib.kv_cache_describe.argtypes = [_vp, _i32, ctypes.POINTER(kv_layer_layout)]
 _lib.kv_quant_append.argtypes = [_vp, _i32, _vp, _vp, _i32, _i64, _i64, _i64, _vp]
+_lib.kv_rope_quant_append.argtypes = [_vp, _i32, _vp, _vp, _i32, _i64, _i64, _i64, _vp, _vp, _i32, _vp]
 _lib.kv_decode_attn.argtypes = [_vp, _i32, _vp, _vp, _vp, ctypes.c_size_t, _vp]
 _lib.kv_decode_attn_split.argtypes = [_vp, _i32, _vp, _vp, ctypes.c_size_t, _vp]
 _lib.kv_decode_attn_merge.argtypes = [_vp, _i32, _vp, _vp, ctypes.c_size_t, _vp]
@@ -163,6 +164,16 @@ def kv_quant_append(cache: int, layer: int, k_ptr: int, v_ptr: int, n_new: int, 
            "kv_quant_append")
 
 
+KV_ROPE_HALF, KV_ROPE_INTERLEAVED = 0, 1
+
+
+def kv_rope_quant_append(cache: int, layer: int, k_ptr: int, v_ptr: int, n_new: int, stride_b: int,
+                         stride_t: int, stride_h: int, cos_ptr: int, sin_ptr: int, pairing: int,
+                         stream: int = 0) -> None:
+    _check(_lib.kv_rope_quant_append(cache, layer, k_ptr, v_ptr, n_new, stride_b, stride_t, stride_h,
+                                     cos_ptr, sin_ptr, pairing, stream), "kv_rope_quant_append")
+
+
 def kv_decode_attn(cache: int, layer: int, q_ptr: int, out_ptr: int, ws_ptr: int, ws_bytes: int,
                    stream: int = 0) -> None:
     _check(_lib.kv_decode_attn(cache, layer, q_ptr, out_ptr, ws_ptr, ws_bytes, stream), "kv_decode_attn")
@@ -236,6 +247,18 @@ class KVCache:
         assert k_new.stride(3) == 1 and k_new.element_size() == 2
         kv_quant_append(self.handle, layer, k_new.data_ptr(), v_new.data_ptr(), k_new.shape[1],
                         k_new.stride(0), k_new.stride(1), k_new.stride(2), self._stream())
+
+    def append_rope(self, layer: int, k_pre, v_new, cos, sin, pairing: int = KV_ROPE_HALF) -> None:
+        """As append, with pre-rotation keys and float32 device tables cos, sin [n_new, d/2]."""
+        torch = self.torch
+        assert k_pre.shape == v_new.shape and k_pre.stride() == v_new.stride()
+        assert k_pre.stride(3) == 1 and k_pre.element_size() == 2
+        assert cos.dtype == torch.float32 and sin.dtype == torch.float32
+        assert cos.is_contiguous() and sin.is_contiguous()
+        assert tuple(cos.shape) == (k_pre.shape[1], k_pre.shape[3] // 2) and cos.shape == sin.shape
+        kv_rope_quant_append(self.handle, layer, k_pre.data_ptr(), v_new.data_ptr(), k_pre.shape[1],
+                             k_pre.stride(0), k_pre.stride(1), k_pre.stride(2), cos.data_ptr(),
+                             sin.data_ptr(), pairing, self._stream())
 
     def attend(self, layer: int, q, out=None):
         """q: device [B, Hq, d] 16-bit contiguous -> float32 [B, Hq, d]."""

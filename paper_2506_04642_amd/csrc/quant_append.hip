@@ -15,8 +15,15 @@
 //   code  = clamp(rint((D - zero) / scale), 0, qmax)          0 when scale == 0
 //
 // resid_copy_kernel stores raw 16-bit tokens in the residual buffer (Sec. 3.3).
+//
+// With rotary tables (Algorithm 1 step 5: rotation fused with the key compression) every kernel
+// turns the new key rows on their way in, in binary32 with one rounding per operation,
+//   y_a = x_a cos - x_b sin     y_b = x_b cos + x_a sin
+// and rounds the result to the 16-bit type, so that the cache holds exactly what a separate
+// rotation step followed by a plain append would have stored.
 #include "tadakv_internal.h"
 #include <hip/hip_fp16.h>
+#include <type_traits>
 
 namespace tadakv {
 namespace {
@@ -32,6 +39,53 @@ __device__ __forceinline__ float widen16(uint16_t v, int dtype)
 
 __device__ __forceinline__ uint16_t f16_rne(float f) { return __half_as_ushort(__float2half_rn(f)); }
 __device__ __forceinline__ float f16_val(uint16_t h) { return __half2float(__ushort_as_half(h)); }
+
+// binary32 -> the cache's 16-bit type, round to nearest even
+__device__ __forceinline__ uint16_t narrow16(float f, int dtype)
+{
+    if (dtype == 1) {
+        const uint32_t u = __float_as_uint(f);
+        if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x0040u);
+        return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+    }
+    return f16_rne(f);
+}
+
+// f rounded to the 16-bit type (DT: 0 binary16, 1 bfloat16) and widened again, without branches
+template <int DT> __device__ __forceinline__ float round16(float f)
+{
+    if (DT == 1) {
+        const uint32_t u = __float_as_uint(f);
+        const uint32_t r = (u + 0x7FFFu + ((u >> 16) & 1u)) & 0xFFFF0000u;
+        const uint32_t nan = (u | 0x00400000u) & 0xFFFF0000u;
+        return __uint_as_float((u & 0x7FFFFFFFu) > 0x7F800000u ? nan : r);
+    }
+    return __half2float(__float2half_rn(f));
+}
+
+// One rotated pair: (a, b) -> (a cos - b sin, b cos + a sin), rounded to the 16-bit type and widened again.
+template <int DT>
+__device__ __forceinline__ void rope_pair_t(float xa, float xb, float c, float s, float &ya, float &yb)
+{
+    const float p1 = xa * c, p2 = xb * s, p3 = xb * c, p4 = xa * s;
+    ya = round16<DT>(p1 - p2);
+    yb = round16<DT>(p3 + p4);
+}
+__device__ __forceinline__ void rope_pair(float xa, float xb, float c, float s, int dtype, float &ya, float &yb)
+{
+    if (dtype == 1) rope_pair_t<1>(xa, xb, c, s, ya, yb);
+    else rope_pair_t<0>(xa, xb, c, s, ya, yb);
+}
+
+// Channel c of a new key row after the rotation (row: the 128 raw elements, cs / sn: the token's 64 angles).
+__device__ __forceinline__ float rope_elem(const uint16_t *row, int c, const float *cs, const float *sn, int mode, int dtype)
+{
+    const int i = mode == 1 ? (c & 63) : (c >> 1);
+    const int ia = mode == 1 ? i : 2 * i, ib = mode == 1 ? i + 64 : 2 * i + 1;
+    float ya, yb;
+    rope_pair(widen16(row[ia], dtype), widen16(row[ib], dtype), cs[i], sn[i], dtype, ya, yb);
+    return c == ia ? ya : yb;
+}
 
 // largest binary16 <= f
 __device__ __forceinline__ uint16_t f16_down(float f)
@@ -141,7 +195,7 @@ __device__ __forceinline__ void word_origin(int which, int bits, int G, int w, i
 // starts the arithmetic of the current one, so that HBM latency is covered by the quantiser.
 // All loops have compile-time trip counts: a thread pulls its 16..64 elements out of LDS in one
 // burst, works in registers, and writes back in one burst.
-template <int G, int GC>
+template <int G, int GC, bool ROPE>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu((G == 32 && GC == 32) ? 4 : 1, 8))) void flush_block_kernel(AppendArgs a, int n_items)
 {
     constexpr int NLD = G * 16 / kThreads;   // 16-byte pieces per thread and item
@@ -161,9 +215,18 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu((G == 
     const int U = a.batch * a.n_kv_heads;
     const bool centre = gm.mean_mode == 0; // per-channel block mean
 
+    // Item `it` is (block, unit) number it / 2, keys or values.  A workgroup's items are a whole
+    // number of grids apart; with an even grid a plain it & 1 would hand it keys only or values
+    // only, and the two cost differently, so the side flips from one round of the grid to the next.
+    auto side_of = [&](int it) {
+        const int round = (gridDim.x & 1) ? 0 : it / (int)gridDim.x;
+        return (it ^ round) & 1;
+    };
+    constexpr int NRP = ROPE ? G * 64 / kThreads : 1; // (token, pair) rotations per thread and key item
     uint4 pre[NLD];
+    float pcs[NRP], psn[NRP]; // the angles of the next key item travel with its rows
     auto fetch = [&](int it) {
-        const int which = it & 1, u = (it >> 1) % U, fb = (it >> 1) / U;
+        const int which = side_of(it), u = (it >> 1) % U, fb = (it >> 1) / U;
         const int b = u / a.n_kv_heads, h = u % a.n_kv_heads;
 #pragma unroll
         for (int k = 0; k < NLD; k++) {
@@ -171,16 +234,32 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu((G == 
             pre[k] = *(const uint4 *)(src_row(a, which, b, h, fb * G + t) + ch * 8);
         }
     };
+    // The angles of a key item are loaded when its arithmetic starts, ahead of the prefetch of the
+    // next item's rows (loads return in order: issued after it they would wait for HBM), and are
+    // dead again after the rotation, so they do not add to the register peak of the quantiser.
+    auto fetch_angles = [&](int it) {
+        const int which = side_of(it), fb = (it >> 1) / U;
+        if (ROPE && which == 0) {
+#pragma unroll
+            for (int k = 0; k < NRP; k++) {
+                const int i = tid + k * kThreads, t = i >> 6, pr = i & 63;
+                int tn = fb * G + t - a.r_old; // negative: a row from the residual buffer, not turned
+                tn = tn < 0 ? 0 : tn;
+                pcs[k] = a.rope_cos[(long long)tn * 64 + pr];
+                psn[k] = a.rope_sin[(long long)tn * 64 + pr];
+            }
+        }
+    };
     if ((int)blockIdx.x < n_items) fetch(blockIdx.x);
 
     for (int it = blockIdx.x; it < n_items; it += gridDim.x) {
-        const int which = it & 1, u = (it >> 1) % U, fb = (it >> 1) / U;
+        const int which = side_of(it), u = (it >> 1) % U, fb = (it >> 1) / U;
         const int b = u / a.n_kv_heads;
         const int bits = which == 0 ? gm.k_bits : gm.v_bits;
         unsigned char *rec = a.layer + ((long long)u * gm.NB + (a.first_block + fb)) * gm.rec_bytes;
         unsigned char *codes_out = rec + (which == 0 ? gm.k_codes : gm.v_codes);
 
-        if (bits == 16) {
+        if (bits == 16 && !(ROPE && which == 0)) {
             // stored raw: G rows of 256 bytes
 #pragma unroll
             for (int k = 0; k < NLD; k++) {
@@ -192,6 +271,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu((G == 
         }
 
         // 1. the block, widened to binary32, into LDS; then start loading the next item
+        fetch_angles(it);
 #pragma unroll
         for (int k = 0; k < NLD; k++) {
             const int i = tid + k * kThreads, t = i >> 4, ch = i & 15;
@@ -206,6 +286,42 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu((G == 
         }
         if (it + (int)gridDim.x < n_items) fetch(it + gridDim.x);
         __syncthreads();
+
+        if (ROPE && which == 0) {
+            // 1b. turn the key rows that come from this call's input (rows taken from the residual
+            // buffer were turned when they were stored); one thread per (token, pair)
+            const int pr = tid & 63;
+            const int ia = a.rope == 1 ? pr : 2 * pr, ib = a.rope == 1 ? pr + 64 : 2 * pr + 1;
+            auto turn = [&](auto dt) {
+#pragma unroll
+                for (int k = 0; k < NRP; k++) {
+                    const int t = (tid >> 6) + k * (kThreads / 64);
+                    float ya, yb;
+                    rope_pair_t<decltype(dt)::value>(x[t * kRowPad + ia], x[t * kRowPad + ib], pcs[k], psn[k], ya, yb);
+                    if (fb * G + t >= a.r_old) {
+                        x[t * kRowPad + ia] = ya;
+                        x[t * kRowPad + ib] = yb;
+                    }
+                }
+            };
+            if (gm.dtype == 1) turn(std::integral_constant<int, 1>{});
+            else turn(std::integral_constant<int, 0>{});
+            __syncthreads();
+            if (bits == 16) {
+                // stored raw: the rotated rows, narrowed again (exact)
+                for (int i = tid; i < G * 16; i += kThreads) {
+                    const int t = i >> 4, ch = i & 15;
+                    uint32_t w[4];
+#pragma unroll
+                    for (int e = 0; e < 4; e++)
+                        w[e] = (uint32_t)narrow16(x[t * kRowPad + ch * 8 + 2 * e], gm.dtype) |
+                               ((uint32_t)narrow16(x[t * kRowPad + ch * 8 + 2 * e + 1], gm.dtype) << 16);
+                    *(uint4 *)(codes_out + (long long)t * 256 + ch * 16) = uint4{w[0], w[1], w[2], w[3]};
+                }
+                __syncthreads();
+                continue;
+            }
+        }
 
         const int qmax = (1 << bits) - 1;
         const float qmaxf = (float)qmax;
@@ -360,10 +476,19 @@ __global__ __launch_bounds__(kThreads) void xhead_mean_kernel(AppendArgs a)
     for (int i = threadIdx.x; i < G * (kHeadDim / 2); i += kThreads) {
         const int t = i / (kHeadDim / 2), cp = i % (kHeadDim / 2);
         float acc0 = 0.0f, acc1 = 0.0f;
+        const int tn = fb * G + t - a.r_old;
+        const bool turn = a.rope != 0 && which == 0 && tn >= 0;
         for (int h = 0; h < H; h++) {
-            const uint32_t w = *(const uint32_t *)(src_row(a, which, b, h, fb * G + t) + 2 * cp);
-            acc0 = acc0 + widen16((uint16_t)(w & 0xFFFFu), gm.dtype);
-            acc1 = acc1 + widen16((uint16_t)(w >> 16), gm.dtype);
+            const uint16_t *row = src_row(a, which, b, h, fb * G + t);
+            if (turn) {
+                const float *cs = a.rope_cos + (long long)tn * 64, *sn = a.rope_sin + (long long)tn * 64;
+                acc0 = acc0 + rope_elem(row, 2 * cp, cs, sn, a.rope, gm.dtype);
+                acc1 = acc1 + rope_elem(row, 2 * cp + 1, cs, sn, a.rope, gm.dtype);
+            } else {
+                const uint32_t w = *(const uint32_t *)(row + 2 * cp);
+                acc0 = acc0 + widen16((uint16_t)(w & 0xFFFFu), gm.dtype);
+                acc1 = acc1 + widen16((uint16_t)(w >> 16), gm.dtype);
+            }
         }
         const uint32_t m0 = f16_rne(acc0 / (float)H), m1 = f16_rne(acc1 / (float)H);
         *(uint32_t *)(dst + t * kHeadDim + 2 * cp) = m0 | (m1 << 16);
@@ -383,12 +508,24 @@ __global__ __launch_bounds__(kThreads) void resid_copy_kernel(AppendArgs a)
                           (long long)h * a.stride_h + ch * 8;
     const long long off = (which == 0 ? a.geom.k_resid_off : a.geom.v_resid_off) +
                           ((long long)u * a.geom.R + a.copy_dst + i) * (kHeadDim * 2) + ch * 16;
+    if (a.rope != 0 && which == 0) {
+        const uint16_t *row = src - ch * 8;
+        const int tn = a.copy_src + i;
+        const float *cs = a.rope_cos + (long long)tn * 64, *sn = a.rope_sin + (long long)tn * 64;
+        uint32_t w[4];
+#pragma unroll
+        for (int e = 0; e < 4; e++)
+            w[e] = (uint32_t)narrow16(rope_elem(row, ch * 8 + 2 * e, cs, sn, a.rope, a.geom.dtype), a.geom.dtype) |
+                   ((uint32_t)narrow16(rope_elem(row, ch * 8 + 2 * e + 1, cs, sn, a.rope, a.geom.dtype), a.geom.dtype) << 16);
+        *(uint4 *)(a.layer + off) = uint4{w[0], w[1], w[2], w[3]};
+        return;
+    }
     *(uint4 *)(a.layer + off) = *(const uint4 *)src;
 }
 
 } // namespace
 
-template <int G, int GC> hipError_t launch_flush_g(const AppendArgs &a, hipStream_t s)
+template <int G, int GC, bool ROPE> hipError_t launch_flush_g(const AppendArgs &a, hipStream_t s)
 {
     const int U = a.batch * a.n_kv_heads;
     constexpr int v_items = G * (kHeadDim / GC) * 2;
@@ -400,10 +537,10 @@ template <int G, int GC> hipError_t launch_flush_g(const AppendArgs &a, hipStrea
     static const int slots = [] {
         int per_cu = 0, dev = 0, cus = 0;
         if (lds > 64 * 1024 &&
-            hipFuncSetAttribute((const void *)flush_block_kernel<G, GC>, hipFuncAttributeMaxDynamicSharedMemorySize,
+            hipFuncSetAttribute((const void *)flush_block_kernel<G, GC, ROPE>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)lds) != hipSuccess)
             return 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, flush_block_kernel<G, GC>, kThreads, lds) != hipSuccess ||
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, flush_block_kernel<G, GC, ROPE>, kThreads, lds) != hipSuccess ||
             hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
             return 0;
@@ -411,14 +548,19 @@ template <int G, int GC> hipError_t launch_flush_g(const AppendArgs &a, hipStrea
     }();
     if (slots < 1) return hipErrorInvalidValue;
     const int grid = items < slots ? (int)items : slots;
-    hipLaunchKernelGGL((flush_block_kernel<G, GC>), dim3(grid), dim3(kThreads), lds, s, a, (int)items);
+    hipLaunchKernelGGL((flush_block_kernel<G, GC, ROPE>), dim3(grid), dim3(kThreads), lds, s, a, (int)items);
     return note_launch(hipGetLastError());
 }
 template <int G> hipError_t launch_flush_gc(const AppendArgs &a, hipStream_t s)
 {
-    if (a.geom.Gc == 32) return launch_flush_g<G, 32>(a, s);
-    if (a.geom.Gc == 64) return launch_flush_g<G, 64>(a, s);
-    return launch_flush_g<G, 128>(a, s);
+    if (a.rope != 0) {
+        if (a.geom.Gc == 32) return launch_flush_g<G, 32, true>(a, s);
+        if (a.geom.Gc == 64) return launch_flush_g<G, 64, true>(a, s);
+        return launch_flush_g<G, 128, true>(a, s);
+    }
+    if (a.geom.Gc == 32) return launch_flush_g<G, 32, false>(a, s);
+    if (a.geom.Gc == 64) return launch_flush_g<G, 64, false>(a, s);
+    return launch_flush_g<G, 128, false>(a, s);
 }
 
 hipError_t launch_flush(const AppendArgs &a, hipStream_t s)

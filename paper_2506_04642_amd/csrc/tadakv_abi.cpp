@@ -306,9 +306,10 @@ kv_status kv_cache_describe(const kv_cache *cache, int32_t layer, kv_layer_layou
     return KV_OK;
 }
 
-kv_status kv_quant_append(kv_cache *cache, int32_t layer, const void *k_new, const void *v_new,
-                          int32_t n_new, int64_t stride_b, int64_t stride_t, int64_t stride_h,
-                          void *stream)
+// rope: 0 none, 1 pairs (i, i + d/2), 2 pairs (2i, 2i + 1)
+static kv_status append_impl(kv_cache *cache, int32_t layer, const void *k_new, const void *v_new,
+                             int32_t n_new, int64_t stride_b, int64_t stride_t, int64_t stride_h,
+                             int rope, const float *rope_cos, const float *rope_sin, void *stream)
 {
     kv_status st = layer_ok(cache, layer);
     if (st != KV_OK) return st;
@@ -319,6 +320,10 @@ kv_status kv_quant_append(kv_cache *cache, int32_t layer, const void *k_new, con
     if (((uintptr_t)k_new % 16) || ((uintptr_t)v_new % 16)) return KV_E_ALIGN;
     if (stride_b % 8 || stride_t % 8 || stride_h % 8) return KV_E_ALIGN;
     if (stride_h < c.head_dim || stride_t < 0 || stride_b < 0) return KV_E_BAD_CONFIG;
+    if (rope != 0) {
+        if (!rope_cos || !rope_sin) return KV_E_NULL;
+        if (((uintptr_t)rope_cos % 4) || ((uintptr_t)rope_sin % 4)) return KV_E_ALIGN;
+    }
     const long long have = (long long)cache->packed[layer] + cache->resid[layer];
     if (have + n_new > c.max_tokens) return KV_E_CAPACITY;
     const int G = c.group_tokens, R = c.resid_cap;
@@ -337,6 +342,9 @@ kv_status kv_quant_append(kv_cache *cache, int32_t layer, const void *k_new, con
     a.batch = c.batch;
     a.r_old = r_old;
     a.first_block = cache->packed[layer] / G;
+    a.rope = rope;
+    a.rope_cos = rope_cos;
+    a.rope_sin = rope_sin;
     a.n_flush_blocks = (int)(n_flush_tok / G);
     if (n_flush_tok > 0) {
         a.copy_src = (int)(n_flush_tok - r_old);
@@ -353,6 +361,22 @@ kv_status kv_quant_append(kv_cache *cache, int32_t layer, const void *k_new, con
     cache->packed[layer] += (int)n_flush_tok;
     cache->resid[layer] = (int)(total - n_flush_tok);
     return KV_OK;
+}
+
+kv_status kv_quant_append(kv_cache *cache, int32_t layer, const void *k_new, const void *v_new,
+                          int32_t n_new, int64_t stride_b, int64_t stride_t, int64_t stride_h,
+                          void *stream)
+{
+    return append_impl(cache, layer, k_new, v_new, n_new, stride_b, stride_t, stride_h, 0, nullptr, nullptr, stream);
+}
+
+kv_status kv_rope_quant_append(kv_cache *cache, int32_t layer, const void *k_pre, const void *v_new,
+                               int32_t n_new, int64_t stride_b, int64_t stride_t, int64_t stride_h,
+                               const float *rope_cos, const float *rope_sin, int32_t pairing, void *stream)
+{
+    if (pairing != KV_ROPE_HALF && pairing != KV_ROPE_INTERLEAVED) return KV_E_BAD_CONFIG;
+    return append_impl(cache, layer, k_pre, v_new, n_new, stride_b, stride_t, stride_h,
+                       pairing == KV_ROPE_HALF ? 1 : 2, rope_cos, rope_sin, stream);
 }
 
 kv_status kv_decode_splits(const kv_cache *cache, int32_t layer, int32_t *n_splits)

@@ -32,6 +32,10 @@ struct AppendArgs {
     int first_block;    // index of the first block this call writes
     int n_flush_blocks; // blocks to compress
     int copy_src, copy_dst, copy_n; // raw tail: input tokens [copy_src, copy_src+copy_n) -> residual[copy_dst..]
+    // rotary embedding applied to the new keys on their way in (0: none, 1: pairs (i, i + 64),
+    // 2: pairs (2i, 2i + 1)); tables [n_new][64] binary32, device
+    int rope;
+    const float *rope_cos, *rope_sin;
 };
 
 struct DecodeArgs {

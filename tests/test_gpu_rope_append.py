@@ -1,0 +1,128 @@
+"""GPU parity of the fused rotate-and-append call (Alg. 1 step 5) against the CPU oracle:
+cache bytes bit for bit, attention within 2e-3 max-abs."""
+import numpy as np
+import pytest
+
+from paper_2506_04642_amd import synth
+from parity_util import check_attention, check_bytes, make_pair, to_dev
+
+pytestmark = pytest.mark.gpu
+
+F16, BF16 = 0, 1
+CHAN, CROSS, NONE = 0, 1, 2
+HALF, INTER = 0, 1
+
+
+@pytest.fixture(scope="module")
+def kv():
+    import torch
+
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_2506_04642_amd import binding
+
+    return binding
+
+
+def rope_append_both(gpu, orc, layer, k, v, dtype, pairing, chunks, pos0=0, base=500000.0):
+    """Pre-rotation keys k, values v (uint16 [B, T, H, d]) appended in chunks; token t of the
+    sequence sits at position pos0 + t."""
+    import torch
+
+    kd, vd = to_dev(k, dtype), to_dev(v, dtype)
+    pos = 0
+    for n in chunks:
+        if n:
+            cos, sin = synth.rope_tables(np.arange(pos0 + pos, pos0 + pos + n), k.shape[3], base)
+            gpu.append_rope(layer, kd[:, pos:pos + n], vd[:, pos:pos + n],
+                            torch.from_numpy(cos).to("cuda:0"), torch.from_numpy(sin).to("cuda:0"), pairing)
+            orc.append(layer, k[:, pos:pos + n], v[:, pos:pos + n], rope_tables=(cos, sin, pairing))
+        pos += n
+    assert pos == k.shape[1]
+
+
+@pytest.mark.parametrize("pairing", [HALF, INTER])
+@pytest.mark.parametrize("dtype", [F16, BF16])
+@pytest.mark.parametrize("bits", [2, 4, 8, 16])
+def test_rope_append_formats(kv, oracle, bits, dtype, pairing):
+    print("case rope_formats bits=%d dtype=%d pairing=%d" % (bits, dtype, pairing), flush=True)
+    T = 32 * 5 + 9
+    gpu, orc = make_pair(kv, oracle, B=2, Hq=8, Hkv=2, T_max=256, dtype=dtype, k_bits=(bits,))
+    k, v = synth.make_kv(300 + bits, 2, T, 2, 128, dtype)
+    rope_append_both(gpu, orc, 0, k, v, dtype, pairing, [T - 1, 1], pos0=4000)
+    check_bytes(gpu, orc, 0)
+    check_attention(gpu, orc, 0, synth.make_q(300 + bits, 2, 8, 128, dtype), dtype)
+
+
+@pytest.mark.parametrize("G,Gc,R", [(32, 32, 64), (64, 64, 64), (128, 32, 128), (32, 128, 32)])
+def test_rope_append_chunkings_and_groups(kv, oracle, G, Gc, R):
+    """Single-token appends, uneven chunks and one bulk call store the same bytes; rows that wait
+    in the residual buffer are not rotated a second time when their block is compressed."""
+    print("case rope_chunkings G=%d Gc=%d R=%d" % (G, Gc, R), flush=True)
+    T = 2 * R + 37
+    k, v = synth.make_kv(310 + G, 1, T, 2, 128, BF16)
+    images = []
+    for chunks in ([T], [1] * T, [5, R - 6, 0, 3, T - R - 2]):
+        gpu, orc = make_pair(kv, oracle, B=1, Hq=2, Hkv=2, T_max=4 * R, G=G, Gc=Gc, R=R, dtype=BF16,
+                             k_bits=(4,), v_bits=(2,))
+        rope_append_both(gpu, orc, 0, k, v, BF16, HALF, chunks)
+        check_bytes(gpu, orc, 0)
+        images.append(orc.layer_image(0)["bytes"].copy())
+    assert np.array_equal(images[0], images[1]) and np.array_equal(images[0], images[2])
+
+
+@pytest.mark.parametrize("mode", [CHAN, NONE, CROSS])
+def test_rope_append_mean_modes(kv, oracle, mode):
+    print("case rope_mean_modes mode=%d" % mode, flush=True)
+    T = 32 * 3 + 5
+    gpu, orc = make_pair(kv, oracle, L=3, B=2, Hq=8, Hkv=4, T_max=128, dtype=BF16, mode=mode, k_bits=(2, 4, 8))
+    for layer in range(3):
+        k, v = synth.make_kv(320 + layer, 2, T, 4, 128, BF16)
+        rope_append_both(gpu, orc, layer, k, v, BF16, HALF, [40, T - 40], pos0=100)
+        check_bytes(gpu, orc, layer)
+        check_attention(gpu, orc, layer, synth.make_q(320 + layer, 2, 8, 128, BF16), BF16)
+
+
+def test_rope_append_equals_rotating_first(kv, oracle):
+    """The fused call stores what a separate rotation (here: the oracle's) followed by the plain
+    append stores; strided input views are accepted."""
+    import torch
+
+    print("case rope_equals_unfused", flush=True)
+    T, H = 70, 2
+    k, v = synth.make_kv(330, 2, T, H, 128, BF16)
+    cos, sin = synth.rope_tables(np.arange(T), 128)
+    fused, _ = make_pair(kv, oracle, B=2, Hq=4, Hkv=H, T_max=128, dtype=BF16, k_bits=(4,))
+    plain, orc = make_pair(kv, oracle, B=2, Hq=4, Hkv=H, T_max=128, dtype=BF16, k_bits=(4,))
+    big_k = torch.zeros((2, T, 3 * H, 128), dtype=torch.bfloat16, device="cuda:0")
+    big_v = torch.zeros_like(big_k)
+    big_k[:, :, H:2 * H] = to_dev(k, BF16)
+    big_v[:, :, H:2 * H] = to_dev(v, BF16)
+    fused.append_rope(0, big_k[:, :, H:2 * H], big_v[:, :, H:2 * H], torch.from_numpy(cos).to("cuda:0"),
+                      torch.from_numpy(sin).to("cuda:0"), HALF)
+    rot = np.stack([oracle.rope(k[b], BF16, cos, sin, HALF) for b in range(2)])
+    plain.append(0, to_dev(rot, BF16), to_dev(v, BF16))
+    orc.append(0, rot, v)
+    check_bytes(plain, orc, 0)
+    check_bytes(fused, orc, 0)
+
+
+def test_rope_append_argument_errors(kv, oracle):
+    import torch
+
+    print("case rope_errors", flush=True)
+    gpu, _ = make_pair(kv, oracle, B=1, Hq=1, Hkv=1, T_max=64, dtype=F16, k_bits=(4,))
+    k = torch.zeros((1, 4, 1, 128), dtype=torch.float16, device="cuda:0")
+    cs = torch.zeros((4, 64), dtype=torch.float32, device="cuda:0")
+    args = (gpu.handle, 0, k.data_ptr(), k.data_ptr(), 4, k.stride(0), k.stride(1), k.stride(2))
+    for bad, code in (((0, cs.data_ptr(), 0), kv.KV_E_NULL), ((cs.data_ptr(), 0, 0), kv.KV_E_NULL),
+                      ((cs.data_ptr(), cs.data_ptr(), 2), kv.KV_E_BAD_CONFIG),
+                      ((cs.data_ptr() + 2, cs.data_ptr(), 0), kv.KV_E_ALIGN)):
+        with pytest.raises(kv.KVError) as e:
+            kv.kv_rope_quant_append(*args, *bad, 0)
+        assert e.value.status == code
+    assert gpu.lengths(0) == (0, 0)
+    with pytest.raises(kv.KVError) as e:  # capacity is checked as in the plain call
+        big = torch.zeros((1, 65, 1, 128), dtype=torch.float16, device="cuda:0")
+        cs65 = torch.zeros((65, 64), dtype=torch.float32, device="cuda:0")
+        gpu.append_rope(0, big, big, cs65, cs65)
+    assert e.value.status == kv.KV_E_CAPACITY
