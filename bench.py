@@ -45,6 +45,8 @@ def parse():
     ap.add_argument("--seed", type=int, default=2000)
     ap.add_argument("--splits", type=int, default=0, help="force the sequence split count (0 = automatic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--separate-append", dest="fused_step", action="store_false",
+                    help="append and attend as two calls per layer instead of the one-call decode step")
     return ap.parse_args()
 
 
@@ -119,11 +121,19 @@ def main():
         nbytes = 0
         for l in range(L):
             kd, vd = k_dec[l]
-            cache.append(l, kd[:, s:s + 1], vd[:, s:s + 1])
+            fused = args.fused_step and cache.lengths(l)[1] + 1 < G  # the token completes no block (R = G)
+            if not fused:
+                cache.append(l, kd[:, s:s + 1], vd[:, s:s + 1])
             if events is not None:
                 e0, e1 = events[l]
                 e0.record(stream)
-            kv.kv_decode_attn_split(cache.handle, l, q_dec[l].data_ptr(), ws, wsb, sp)
+            if fused:
+                # the attention kernel takes the new token from the caller's rows and stores it
+                kn, vn = kd[:, s], vd[:, s]
+                kv.kv_append_decode_attn_split(cache.handle, l, kn.data_ptr(), vn.data_ptr(), kn.stride(0),
+                                               kn.stride(1), q_dec[l].data_ptr(), ws, wsb, sp)
+            else:
+                kv.kv_decode_attn_split(cache.handle, l, q_dec[l].data_ptr(), ws, wsb, sp)
             if events is not None:
                 e1.record(stream)
             kv.kv_decode_attn_merge(cache.handle, l, out.data_ptr(), ws, wsb, sp)

@@ -178,6 +178,22 @@ kv_status kv_decode_attn_split(const kv_cache *cache, int32_t layer, const void 
 kv_status kv_decode_attn_merge(const kv_cache *cache, int32_t layer, float *out,
                                const void *workspace, size_t workspace_bytes, void *stream);
 
+/* One step of the decode loop in a single call (Algorithm 1 steps 8-9, KVCache.update followed by
+ * TaDAFlashAttn): append ONE new token per sequence, then attend over the whole cache including it.
+ * Equals kv_quant_append(n_new = 1) followed by kv_decode_attn, bit for bit; where the layer is
+ * served by the matrix-core kernel and the token does not complete a block, the attention kernel
+ * itself reads the new rows and stores them in the residual buffer, which saves a launch.
+ *   k_new, v_new : device, element (b,h,c) at b*stride_b + h*stride_h + c (post-RoPE keys)
+ *   other arguments as kv_decode_attn.  Errors of both calls apply; on error nothing is enqueued
+ *   and the cache is unchanged.
+ * _split is the first half, to be followed by kv_decode_attn_merge (as kv_decode_attn_split). */
+kv_status kv_append_decode_attn(kv_cache *cache, int32_t layer, const void *k_new, const void *v_new,
+                                int64_t stride_b, int64_t stride_h, const void *q, float *out,
+                                void *workspace, size_t workspace_bytes, void *stream);
+kv_status kv_append_decode_attn_split(kv_cache *cache, int32_t layer, const void *k_new, const void *v_new,
+                                      int64_t stride_b, int64_t stride_h, const void *q,
+                                      void *workspace, size_t workspace_bytes, void *stream);
+
 /* Number of sequence splits kv_decode_attn uses for `layer` at its current length. */
 kv_status kv_decode_splits(const kv_cache *cache, int32_t layer, int32_t *n_splits);
 

@@ -29,7 +29,7 @@ KV_MEAN_CHANNEL_BLOCK, KV_MEAN_CROSS_HEAD, KV_MEAN_NONE = 0, 1, 2
 
 EXPORTS = [
     "kv_cache_bytes", "kv_workspace_bytes", "kv_cache_create", "kv_cache_destroy", "kv_cache_reset",
-    "kv_cache_len", "kv_cache_describe", "kv_quant_append", "kv_rope_quant_append", "kv_decode_attn", "kv_decode_attn_split",
+    "kv_cache_len", "kv_cache_describe", "kv_quant_append", "kv_rope_quant_append", "kv_append_decode_attn", "kv_append_decode_attn_split", "kv_decode_attn", "kv_decode_attn_split",
     "kv_decode_attn_merge", "kv_decode_splits", "kv_decode_bytes", "kv_set_decode_path", "kv_set_decode_splits", "kv_strerror", "kv_last_hip_error",
 ]
 
@@ -67,6 +67,8 @@ _lib.kv_cache_describe.argtypes = [_vp, _i32, ctypes.POINTER(kv_layer_layout)]
 _lib.kv_quant_append.argtypes = [_vp, _i32, _vp, _vp, _i32, _i64, _i64, _i64, _vp]
 _lib.kv_rope_quant_append.argtypes = [_vp, _i32, _vp, _vp, _i32, _i64, _i64, _i64, _vp, _vp, _i32, _vp]
 _lib.kv_decode_attn.argtypes = [_vp, _i32, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+_lib.kv_append_decode_attn.argtypes = [_vp, _i32, _vp, _vp, _i64, _i64, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+_lib.kv_append_decode_attn_split.argtypes = [_vp, _i32, _vp, _vp, _i64, _i64, _vp, _vp, ctypes.c_size_t, _vp]
 _lib.kv_decode_attn_split.argtypes = [_vp, _i32, _vp, _vp, ctypes.c_size_t, _vp]
 _lib.kv_decode_attn_merge.argtypes = [_vp, _i32, _vp, _vp, ctypes.c_size_t, _vp]
 _lib.kv_decode_splits.argtypes = [_vp, _i32, ctypes.POINTER(_i32)]
@@ -179,6 +181,18 @@ def kv_decode_attn(cache: int, layer: int, q_ptr: int, out_ptr: int, ws_ptr: int
     _check(_lib.kv_decode_attn(cache, layer, q_ptr, out_ptr, ws_ptr, ws_bytes, stream), "kv_decode_attn")
 
 
+def kv_append_decode_attn(cache: int, layer: int, k_ptr: int, v_ptr: int, stride_b: int, stride_h: int,
+                          q_ptr: int, out_ptr: int, ws_ptr: int, ws_bytes: int, stream: int = 0) -> None:
+    _check(_lib.kv_append_decode_attn(cache, layer, k_ptr, v_ptr, stride_b, stride_h, q_ptr, out_ptr, ws_ptr,
+                                      ws_bytes, stream), "kv_append_decode_attn")
+
+
+def kv_append_decode_attn_split(cache: int, layer: int, k_ptr: int, v_ptr: int, stride_b: int, stride_h: int,
+                                q_ptr: int, ws_ptr: int, ws_bytes: int, stream: int = 0) -> None:
+    _check(_lib.kv_append_decode_attn_split(cache, layer, k_ptr, v_ptr, stride_b, stride_h, q_ptr, ws_ptr,
+                                            ws_bytes, stream), "kv_append_decode_attn_split")
+
+
 def kv_decode_attn_split(cache: int, layer: int, q_ptr: int, ws_ptr: int, ws_bytes: int, stream: int = 0) -> None:
     _check(_lib.kv_decode_attn_split(cache, layer, q_ptr, ws_ptr, ws_bytes, stream), "kv_decode_attn_split")
 
@@ -268,6 +282,21 @@ class KVCache:
             out = torch.empty(q.shape, dtype=torch.float32, device=self.device)
         kv_decode_attn(self.handle, layer, q.data_ptr(), out.data_ptr(), self.workspace.data_ptr(),
                        self.ws_bytes, self._stream())
+        return out
+
+    def append_attend(self, layer: int, k_new, v_new, q, out=None):
+        """One decode step: k_new, v_new [B, 1, Hkv, d] (or [B, Hkv, d]), q [B, Hq, d] -> float32 [B, Hq, d]."""
+        torch = self.torch
+        if k_new.dim() == 4:
+            assert k_new.shape[1] == 1
+            k_new, v_new = k_new[:, 0], v_new[:, 0]
+        assert k_new.shape == v_new.shape and k_new.stride() == v_new.stride()
+        assert k_new.stride(2) == 1 and k_new.element_size() == 2 and q.is_contiguous()
+        if out is None:
+            out = torch.empty(q.shape, dtype=torch.float32, device=self.device)
+        kv_append_decode_attn(self.handle, layer, k_new.data_ptr(), v_new.data_ptr(), k_new.stride(0),
+                              k_new.stride(1), q.data_ptr(), out.data_ptr(), self.workspace.data_ptr(),
+                              self.ws_bytes, self._stream())
         return out
 
     def lengths(self, layer: int):

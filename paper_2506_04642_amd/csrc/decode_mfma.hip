@@ -600,13 +600,24 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
                         qs[(4 * hg + row) * 128 + 32 * vq + 16 * ph + 4 * qa + y] = qf[hg][ph][y];
             const unsigned char *kr = a.layer + gm.k_resid_off + (long long)u * gm.R * 256;
             const unsigned char *vr = a.layer + gm.v_resid_off + (long long)u * gm.R * 256;
+            // a token appended by this very call: read from the caller's rows and stored in the cache here
+            const long long fresh_off = (long long)b * a.fresh_stride_b + (long long)h * a.fresh_stride_h;
+            const int t_fresh = a.k_fresh ? a.r - 1 : -1;
             for (int t0 = 0; t0 < a.r; t0 += 32) {
                 const int nt = a.r - t0 < 32 ? a.r - t0 : 32;
                 wave_lds_fence();
                 for (int i = lane; i < nt * 16; i += 64) {
                     const int t = i >> 4, ch = i & 15;
-                    const uint4 kv_ = *(const uint4 *)(kr + (long long)(t0 + t) * 256 + ch * 16);
-                    const uint4 vv_ = *(const uint4 *)(vr + (long long)(t0 + t) * 256 + ch * 16);
+                    uint4 kv_, vv_;
+                    if (t0 + t == t_fresh) {
+                        kv_ = *(const uint4 *)(a.k_fresh + fresh_off + ch * 8);
+                        vv_ = *(const uint4 *)(a.v_fresh + fresh_off + ch * 8);
+                        *(uint4 *)const_cast<unsigned char *>(kr + (long long)t_fresh * 256 + ch * 16) = kv_;
+                        *(uint4 *)const_cast<unsigned char *>(vr + (long long)t_fresh * 256 + ch * 16) = vv_;
+                    } else {
+                        kv_ = *(const uint4 *)(kr + (long long)(t0 + t) * 256 + ch * 16);
+                        vv_ = *(const uint4 *)(vr + (long long)(t0 + t) * 256 + ch * 16);
+                    }
                     *(uint2 *)(kraw + t * RS + ch * 16) = uint2{kv_.x, kv_.y};
                     *(uint2 *)(kraw + t * RS + ch * 16 + 8) = uint2{kv_.z, kv_.w};
                     *(uint2 *)(vraw + t * RS + ch * 16) = uint2{vv_.x, vv_.y};

@@ -473,6 +473,67 @@ kv_status kv_decode_attn_merge(const kv_cache *cache, int32_t layer, float *out,
     return launch_decode_merge(a, (hipStream_t)stream) == hipSuccess ? KV_OK : KV_E_HIP;
 }
 
+kv_status kv_append_decode_attn_split(kv_cache *cache, int32_t layer, const void *k_new, const void *v_new,
+                                      int64_t stride_b, int64_t stride_h, const void *q,
+                                      void *workspace, size_t workspace_bytes, void *stream)
+{
+    kv_status st = layer_ok(cache, layer);
+    if (st != KV_OK) return st;
+    if (!k_new || !v_new || !q) return KV_E_NULL;
+    const kv_config &c = cache->cfg;
+    if (((uintptr_t)k_new % 16) || ((uintptr_t)v_new % 16) || ((uintptr_t)q % 16)) return KV_E_ALIGN;
+    if (stride_b % 8 || stride_h % 8) return KV_E_ALIGN;
+    if (stride_h < c.head_dim || stride_b < 0) return KV_E_BAD_CONFIG;
+    const int p_old = cache->packed[layer], r_old = cache->resid[layer];
+    if ((long long)p_old + r_old + 1 > c.max_tokens) return KV_E_CAPACITY;
+    const bool flush = r_old + 1 == c.resid_cap;
+
+    // the decode launch as it will look once the token is in, checked before anything is enqueued
+    DecodeArgs a{};
+    cache->packed[layer] = flush ? p_old + c.resid_cap : p_old;
+    cache->resid[layer] = flush ? 0 : r_old + 1;
+    st = fill_decode(cache, layer, &a);
+    const bool mfma = st == KV_OK && use_mfma(cache, a);
+    if (st == KV_OK && (!workspace || workspace_bytes < workspace_need(c, a.n_splits))) st = KV_E_WORKSPACE;
+    if (st == KV_OK && ((uintptr_t)workspace % 256)) st = KV_E_ALIGN;
+    if (st == KV_OK && c.mean_mode == KV_MEAN_CROSS_HEAD && a.geom.k_bits != 16 && a.geom.G > 64) st = KV_E_UNSUPPORTED;
+    if (st == KV_OK && cache->decode_path == 2 && !mfma) st = KV_E_UNSUPPORTED;
+    if (st != KV_OK || flush || !mfma) {
+        cache->packed[layer] = p_old;
+        cache->resid[layer] = r_old;
+        if (st != KV_OK) return st;
+        // a block is due for compression, or the layer is served by the vector-ALU kernels:
+        // the two steps run as launches of their own
+        st = kv_quant_append(cache, layer, k_new, v_new, 1, stride_b, 0, stride_h, stream);
+        if (st != KV_OK) return st;
+        return kv_decode_attn_split(cache, layer, q, workspace, workspace_bytes, stream);
+    }
+    a.q = (const uint16_t *)q;
+    a.ws = (float *)workspace;
+    a.out = nullptr;
+    a.k_fresh = (const uint16_t *)k_new;
+    a.v_fresh = (const uint16_t *)v_new;
+    a.fresh_stride_b = stride_b;
+    a.fresh_stride_h = stride_h;
+    if (launch_decode_split_mfma(a, (hipStream_t)stream) != hipSuccess) {
+        cache->resid[layer] = r_old;
+        return KV_E_HIP;
+    }
+    return KV_OK;
+}
+
+kv_status kv_append_decode_attn(kv_cache *cache, int32_t layer, const void *k_new, const void *v_new,
+                                int64_t stride_b, int64_t stride_h, const void *q, float *out,
+                                void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!out) return KV_E_NULL;
+    if ((uintptr_t)out % 16) return KV_E_ALIGN;
+    kv_status st = kv_append_decode_attn_split(cache, layer, k_new, v_new, stride_b, stride_h, q, workspace,
+                                               workspace_bytes, stream);
+    if (st != KV_OK) return st;
+    return kv_decode_attn_merge(cache, layer, out, workspace, workspace_bytes, stream);
+}
+
 kv_status kv_decode_attn(const kv_cache *cache, int32_t layer, const void *q, float *out,
                          void *workspace, size_t workspace_bytes, void *stream)
 {

@@ -49,6 +49,10 @@ struct DecodeArgs {
     int r;               // residual tokens
     int n_splits;
     int blocks_per_split;
+    // matrix-core kernel only: the newest residual token (index r - 1) is not in the cache yet;
+    // the kernel takes it from these rows and stores it (null: every token is in the cache)
+    const uint16_t *k_fresh, *v_fresh;
+    long long fresh_stride_b, fresh_stride_h; // elements
 };
 
 // records the outcome of a launch for kv_last_hip_error and passes it through
