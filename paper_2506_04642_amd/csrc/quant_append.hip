@@ -461,6 +461,302 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu((G == 
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// flush_wave_kernel: the same arithmetic for blocks of 32 tokens with one wavefront per item and
+// the block held in registers; no LDS, no workgroup barrier.  Lane l owns tokens 8 tg .. 8 tg + 7
+// (tg = l & 3) of channels 8 c8 .. 8 c8 + 7 (c8 = l >> 2): a wave's load instruction covers four
+// whole rows; the quad holds a channel's 32 tokens, so the token-order sum of the mean and the key
+// groups' extrema move by quad DPP; a value group (one token, Gc channels) is lanes 4 apart in a
+// row of 16; an 8-token run of one channel (a value word at 4 bits) and 8 channels of one token
+// (a key word at 4 bits) are both in one lane.
+template <int CTRL> __device__ __forceinline__ uint32_t dpp_u(uint32_t x)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xF, 0xF, true);
+}
+template <int CTRL> __device__ __forceinline__ float dpp_f(float x) { return __uint_as_float(dpp_u<CTRL>(__float_as_uint(x))); }
+// value of quad lane P in every lane of the quad
+template <int P> __device__ __forceinline__ uint32_t quad_bcast_u(uint32_t x) { return dpp_u<P * 0x55>(x); }
+template <int P> __device__ __forceinline__ float quad_bcast_f(float x) { return dpp_f<P * 0x55>(x); }
+// value of lane src (any lane), through the LDS crossbar
+__device__ __forceinline__ uint32_t from_lane_u(uint32_t x, int src) { return (uint32_t)__builtin_amdgcn_ds_bpermute(src << 2, (int)x); }
+__device__ __forceinline__ float from_lane_f(float x, int src) { return __uint_as_float(from_lane_u(__float_as_uint(x), src)); }
+// one of four by a lane-dependent index 0..3
+template <class T> __device__ __forceinline__ T pick4(int i, T a0, T a1, T a2, T a3)
+{
+    const T lo = i & 1 ? a1 : a0, hi = i & 1 ? a3 : a2;
+    return i & 2 ? hi : lo;
+}
+
+struct MetaOut {
+    uint32_t pk; // scale | zero << 16, binary16 patterns
+    float rs;    // correctly rounded 1 / scale, 0 for a constant group
+};
+__device__ __forceinline__ MetaOut meta_of(float mn, float mx, int qmax)
+{
+    uint16_t s16, z16;
+    float sc, z;
+    group_meta(mn, mx, qmax, s16, z16, sc, z);
+    MetaOut o;
+    o.pk = (uint32_t)s16 | ((uint32_t)z16 << 16);
+    o.rs = sc != 0.0f ? 1.0f / sc : 0.0f;
+    return o;
+}
+
+template <int GC, int BITS>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 8))) void flush_wave_kernel(AppendArgs a, int n_items)
+{
+    constexpr int G = 32;
+    constexpr int bits = BITS; // keys and values of the layer share the width in this instance
+    constexpr int NGV = kHeadDim / GC;
+    const LayerGeom &gm = a.geom;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int tg = lane & 3, c8 = lane >> 2;
+    const int U = a.batch * a.n_kv_heads;
+    const int workers = (int)gridDim.x * (kThreads / 64);
+
+    for (int it = (int)blockIdx.x * (kThreads / 64) + wave; it < n_items; it += workers) {
+        // keys and values cost differently: a worker alternates between them (workers is even)
+        const int which = (it ^ (it / workers)) & 1, u = (it >> 1) % U, fb = (it >> 1) / U;
+        const int b = u / a.n_kv_heads, h = u % a.n_kv_heads;
+        unsigned char *rec = a.layer + ((long long)u * gm.NB + (a.first_block + fb)) * gm.rec_bytes;
+        unsigned char *codes_out = rec + (which == 0 ? gm.k_codes : gm.v_codes);
+
+        uint4 pre[8];
+#pragma unroll
+        for (int j = 0; j < 8; j++) pre[j] = *(const uint4 *)(src_row(a, which, b, h, fb * G + 8 * tg + j) + c8 * 8);
+
+        float x[8][8]; // [token j][channel e]
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            const uint32_t wv[4] = {pre[j].x, pre[j].y, pre[j].z, pre[j].w};
+#pragma unroll
+            for (int k = 0; k < 4; k++) {
+                x[j][2 * k] = widen16((uint16_t)(wv[k] & 0xFFFFu), gm.dtype);
+                x[j][2 * k + 1] = widen16((uint16_t)(wv[k] >> 16), gm.dtype);
+            }
+        }
+
+        // ---- mean-centring
+        if (gm.mean_mode == 0) {
+            // per channel over the block: the sum runs over the tokens in order, so the four lanes of
+            // a quad add their eight tokens one after the other and hand the running sum on
+            float acc[8];
+#pragma unroll
+            for (int e = 0; e < 8; e++) acc[e] = 0.0f;
+#pragma unroll
+            for (int p = 0; p < 4; p++) {
+                float cin[8];
+#pragma unroll
+                for (int e = 0; e < 8; e++)
+                    cin[e] = p == 0 ? 0.0f : (p == 1 ? quad_bcast_f<0>(acc[e]) : (p == 2 ? quad_bcast_f<1>(acc[e]) : quad_bcast_f<2>(acc[e])));
+                if (tg == p) {
+#pragma unroll
+                    for (int e = 0; e < 8; e++) {
+                        float sacc = cin[e];
+#pragma unroll
+                        for (int j = 0; j < 8; j++) sacc = sacc + x[j][e];
+                        acc[e] = sacc;
+                    }
+                }
+            }
+            uint32_t mpk[4];
+            float m[8];
+#pragma unroll
+            for (int e = 0; e < 8; e++) {
+                const uint32_t m16 = quad_bcast_u<3>((uint32_t)f16_rne(acc[e] / (float)G));
+                m[e] = f16_val((uint16_t)m16);
+                if (e & 1) mpk[e >> 1] |= m16 << 16;
+                else mpk[e >> 1] = m16;
+            }
+            if (tg == 0)
+                *(uint4 *)(rec + (which == 0 ? gm.k_mean : gm.v_mean) + c8 * 16) = uint4{mpk[0], mpk[1], mpk[2], mpk[3]};
+#pragma unroll
+            for (int j = 0; j < 8; j++)
+#pragma unroll
+                for (int e = 0; e < 8; e++) x[j][e] = x[j][e] - m[e];
+        } else if (gm.mean_mode == 1) {
+            // mean over the kv heads per (token, channel), written by xhead_mean_kernel before this launch
+            const uint16_t *xm = (const uint16_t *)(a.layer + gm.xmean_off) +
+                                 (((long long)b * gm.NB + (a.first_block + fb)) * 2 + which) * G * kHeadDim;
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                const uint4 mv = *(const uint4 *)(xm + (8 * tg + j) * kHeadDim + c8 * 8);
+                const uint32_t wv[4] = {mv.x, mv.y, mv.z, mv.w};
+#pragma unroll
+                for (int k = 0; k < 4; k++) {
+                    x[j][2 * k] = x[j][2 * k] - f16_val((uint16_t)(wv[k] & 0xFFFFu));
+                    x[j][2 * k + 1] = x[j][2 * k + 1] - f16_val((uint16_t)(wv[k] >> 16));
+                }
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; j++)
+#pragma unroll
+                for (int e = 0; e < 8; e++) x[j][e] = x[j][e] - 0.0f;
+        }
+
+        constexpr int qmax = (1 << bits) - 1;
+        constexpr float qmaxf = (float)qmax;
+
+        if (which == 0) {
+            // ---- keys: one group per channel over the 32 tokens (eight in the lane, four lanes)
+            float mn[8], mx[8];
+#pragma unroll
+            for (int e = 0; e < 8; e++) {
+                float lo = x[0][e], hi = x[0][e];
+#pragma unroll
+                for (int j = 1; j < 8; j++) {
+                    lo = fminf(lo, x[j][e]);
+                    hi = fmaxf(hi, x[j][e]);
+                }
+                lo = fminf(lo, dpp_f<0xB1>(lo));
+                hi = fmaxf(hi, dpp_f<0xB1>(hi));
+                mn[e] = fminf(lo, dpp_f<0x4E>(lo));
+                mx[e] = fmaxf(hi, dpp_f<0x4E>(hi));
+            }
+            // quad lane tg works out the metadata of channels 2 tg and 2 tg + 1, then all share
+            const MetaOut ma = meta_of(pick4(tg, mn[0], mn[2], mn[4], mn[6]), pick4(tg, mx[0], mx[2], mx[4], mx[6]), qmax);
+            const MetaOut mb = meta_of(pick4(tg, mn[1], mn[3], mn[5], mn[7]), pick4(tg, mx[1], mx[3], mx[5], mx[7]), qmax);
+            uint32_t pk[8];
+            float rs[8];
+            pk[0] = quad_bcast_u<0>(ma.pk); rs[0] = quad_bcast_f<0>(ma.rs);
+            pk[1] = quad_bcast_u<0>(mb.pk); rs[1] = quad_bcast_f<0>(mb.rs);
+            pk[2] = quad_bcast_u<1>(ma.pk); rs[2] = quad_bcast_f<1>(ma.rs);
+            pk[3] = quad_bcast_u<1>(mb.pk); rs[3] = quad_bcast_f<1>(mb.rs);
+            pk[4] = quad_bcast_u<2>(ma.pk); rs[4] = quad_bcast_f<2>(ma.rs);
+            pk[5] = quad_bcast_u<2>(mb.pk); rs[5] = quad_bcast_f<2>(mb.rs);
+            pk[6] = quad_bcast_u<3>(ma.pk); rs[6] = quad_bcast_f<3>(ma.rs);
+            pk[7] = quad_bcast_u<3>(mb.pk); rs[7] = quad_bcast_f<3>(mb.rs);
+            if (tg == 0) {
+                uint32_t sw[4], zw[4];
+#pragma unroll
+                for (int k = 0; k < 4; k++) {
+                    sw[k] = (pk[2 * k] & 0xFFFFu) | (pk[2 * k + 1] << 16);
+                    zw[k] = (pk[2 * k] >> 16) | (pk[2 * k + 1] & 0xFFFF0000u);
+                }
+                *(uint4 *)(rec + gm.k_scale + c8 * 16) = uint4{sw[0], sw[1], sw[2], sw[3]};
+                *(uint4 *)(rec + gm.k_zero + c8 * 16) = uint4{zw[0], zw[1], zw[2], zw[3]};
+            }
+            float sc[8], z[8];
+#pragma unroll
+            for (int e = 0; e < 8; e++) {
+                sc[e] = f16_val((uint16_t)(pk[e] & 0xFFFFu));
+                z[e] = f16_val((uint16_t)(pk[e] >> 16));
+            }
+            // codes and words: a key word runs along channels
+            const int tt = tg >> 1, jj = c8 >> 2;
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                uint32_t cd[8];
+#pragma unroll
+                for (int e = 0; e < 8; e++) cd[e] = quant_code(x[j][e], sc[e], rs[e], z[e], qmaxf);
+                const int n = 8 * (tg & 1) + j;
+                if (bits == 4) {
+                    uint32_t w = 0;
+#pragma unroll
+                    for (int e = 0; e < 8; e++) w |= cd[e] << (8 * (e & 3) + 4 * (e >> 2));
+                    ((uint32_t *)codes_out)[((tt * 4 + jj) * 16 + n) * 4 + (c8 & 3)] = w;
+                } else if (bits == 8) {
+                    const uint32_t w0 = cd[0] | (cd[1] << 8) | (cd[2] << 16) | (cd[3] << 24);
+                    const uint32_t w1 = cd[4] | (cd[5] << 8) | (cd[6] << 16) | (cd[7] << 24);
+                    const int piece = ((tt * 2 + ((c8 >> 1) & 1)) * 4 + jj) * 16 + n;
+                    *(uint2 *)(codes_out + (piece * 4 + 2 * (c8 & 1)) * 4) = uint2{w0, w1};
+                } else {
+                    // 16 channels per word: this lane's half, shifted into place, joined with the
+                    // neighbouring channel octet's (lane ^ 4)
+                    uint32_t w = 0;
+#pragma unroll
+                    for (int e = 0; e < 8; e++) w |= cd[e] << (8 * (e & 3) + 2 * (e >> 2));
+                    w <<= 4 * (c8 & 1);
+                    w |= from_lane_u(w, lane ^ 4);
+                    if ((j >> 2) == (c8 & 1))
+                        ((uint32_t *)codes_out)[(jj * 16 + n) * 4 + ((tt << 1) | ((c8 >> 1) & 1))] = w;
+                }
+            }
+        } else {
+            // ---- values: one group per (token, Gc channels): eight in the lane, Gc / 8 lanes
+            float mn[8], mx[8];
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                float lo = x[j][0], hi = x[j][0];
+#pragma unroll
+                for (int e = 1; e < 8; e++) {
+                    lo = fminf(lo, x[j][e]);
+                    hi = fmaxf(hi, x[j][e]);
+                }
+                // lanes 4 and 8 apart in the row of 16 (rotations: the coset is covered either way)
+                lo = fminf(lo, dpp_f<0x124>(lo));
+                hi = fmaxf(hi, dpp_f<0x124>(hi));
+                lo = fminf(lo, dpp_f<0x128>(lo));
+                hi = fmaxf(hi, dpp_f<0x128>(hi));
+                if (GC >= 64) {
+                    lo = fminf(lo, from_lane_f(lo, lane ^ 16));
+                    hi = fmaxf(hi, from_lane_f(hi, lane ^ 16));
+                }
+                if (GC >= 128) {
+                    lo = fminf(lo, from_lane_f(lo, lane ^ 32));
+                    hi = fmaxf(hi, from_lane_f(hi, lane ^ 32));
+                }
+                mn[j] = lo;
+                mx[j] = hi;
+            }
+            // lane with q4 = c8 & 3 works out tokens 2 q4 and 2 q4 + 1 of its group, then the four share
+            const int q4 = c8 & 3;
+            const MetaOut ma = meta_of(pick4(q4, mn[0], mn[2], mn[4], mn[6]), pick4(q4, mx[0], mx[2], mx[4], mx[6]), qmax);
+            const MetaOut mb = meta_of(pick4(q4, mn[1], mn[3], mn[5], mn[7]), pick4(q4, mx[1], mx[3], mx[5], mx[7]), qmax);
+            if ((c8 & (GC / 8 - 1)) == q4) {
+                const int gam = c8 / (GC / 8), t = 8 * tg + 2 * q4;
+                *(uint32_t *)(rec + gm.v_meta + (t * NGV + gam) * 4) = ma.pk;
+                *(uint32_t *)(rec + gm.v_meta + ((t + 1) * NGV + gam) * 4) = mb.pk;
+            }
+            uint32_t pk[8];
+            float rs[8];
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                const int src = (lane & ~12) | ((j >> 1) << 2);
+                pk[j] = from_lane_u((j & 1) ? mb.pk : ma.pk, src);
+                rs[j] = from_lane_f((j & 1) ? mb.rs : ma.rs, src);
+            }
+            float sc[8], z[8];
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                sc[j] = f16_val((uint16_t)(pk[j] & 0xFFFFu));
+                z[j] = f16_val((uint16_t)(pk[j] >> 16));
+            }
+            // codes and words: a value word runs along tokens
+            const int tt = tg >> 1;
+#pragma unroll
+            for (int e = 0; e < 8; e++) {
+                uint32_t cd[8];
+#pragma unroll
+                for (int j = 0; j < 8; j++) cd[j] = quant_code(x[j][e], sc[j], rs[j], z[j], qmaxf);
+                const int n = 8 * (c8 & 1) + e;
+                if (bits == 4) {
+                    uint32_t w = 0;
+#pragma unroll
+                    for (int j = 0; j < 8; j++) w |= cd[j] << (8 * (j & 3) + 4 * (j >> 2));
+                    const int piece = ((c8 >> 2) * 2 + tt) * 16 + n;
+                    ((uint32_t *)codes_out)[piece * 4 + 2 * ((c8 >> 1) & 1) + (tg & 1)] = w;
+                } else if (bits == 8) {
+                    const uint32_t w0 = cd[0] | (cd[1] << 8) | (cd[2] << 16) | (cd[3] << 24);
+                    const uint32_t w1 = cd[4] | (cd[5] << 8) | (cd[6] << 16) | (cd[7] << 24);
+                    const int piece = ((c8 >> 1) * 2 + tt) * 16 + n;
+                    *(uint2 *)(codes_out + (piece * 4 + 2 * (tg & 1)) * 4) = uint2{w0, w1};
+                } else {
+                    uint32_t w = 0;
+#pragma unroll
+                    for (int j = 0; j < 8; j++) w |= cd[j] << (8 * (j & 3) + 2 * (j >> 2));
+                    w <<= 4 * (tg & 1);
+                    w |= dpp_u<0xB1>(w);
+                    const int piece = ((c8 >> 3) * 2 + tt) * 16 + n;
+                    if ((e >> 2) == (tg & 1)) ((uint32_t *)codes_out)[piece * 4 + ((c8 >> 1) & 3)] = w;
+                }
+            }
+        }
+    }
+}
+
 // Cross-head mean (Eq. 1-2): for every token of a block and every channel, the mean over the kv
 // heads, m = f16_rne((x_0 + x_1 + ... + x_{H-1}) / H) with the sum taken in head order.
 // grid (blocks to flush, batch, K|V); written to the layer's mean plane.
@@ -563,6 +859,26 @@ template <int G> hipError_t launch_flush_gc(const AppendArgs &a, hipStream_t s)
     return launch_flush_g<G, 128, false>(a, s);
 }
 
+template <int GC, int BITS> hipError_t launch_flush_wave(const AppendArgs &a, hipStream_t s)
+{
+    const int U = a.batch * a.n_kv_heads;
+    const long long items = (long long)a.n_flush_blocks * U * 2;
+    if (items > 0x7FFFFFFF) return hipErrorInvalidValue;
+    static const int slots = [] {
+        int per_cu = 0, dev = 0, cus = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, flush_wave_kernel<GC, BITS>, kThreads, 0) != hipSuccess ||
+            hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+            return 0;
+        return per_cu * cus;
+    }();
+    if (slots < 1) return hipErrorInvalidValue;
+    const long long want = (items + kThreads / 64 - 1) / (kThreads / 64);
+    const int grid = want < slots ? (int)want : slots;
+    hipLaunchKernelGGL((flush_wave_kernel<GC, BITS>), dim3(grid), dim3(kThreads), 0, s, a, (int)items);
+    return note_launch(hipGetLastError());
+}
+
 hipError_t launch_flush(const AppendArgs &a, hipStream_t s)
 {
     const int U = a.batch * a.n_kv_heads;
@@ -573,6 +889,14 @@ hipError_t launch_flush(const AppendArgs &a, hipStream_t s)
         hipLaunchKernelGGL(xhead_mean_kernel, dim3(a.n_flush_blocks, a.batch, 2), dim3(kThreads), 0, s, a);
         hipError_t e = note_launch(hipGetLastError());
         if (e != hipSuccess) return e;
+    }
+    const int kb = a.geom.k_bits;
+    if (a.geom.G == 32 && a.rope == 0 && kb == a.geom.v_bits && kb != 16) {
+        // blocks of 32 tokens, one width for keys and values, no rotation: one wavefront per
+        // item, registers only
+        if (a.geom.Gc == 32) return kb == 2 ? launch_flush_wave<32, 2>(a, s) : kb == 4 ? launch_flush_wave<32, 4>(a, s) : launch_flush_wave<32, 8>(a, s);
+        if (a.geom.Gc == 64) return kb == 2 ? launch_flush_wave<64, 2>(a, s) : kb == 4 ? launch_flush_wave<64, 4>(a, s) : launch_flush_wave<64, 8>(a, s);
+        return kb == 2 ? launch_flush_wave<128, 2>(a, s) : kb == 4 ? launch_flush_wave<128, 4>(a, s) : launch_flush_wave<128, 8>(a, s);
     }
     if (a.geom.G == 32) return launch_flush_gc<32>(a, s);
     if (a.geom.G == 64) return launch_flush_gc<64>(a, s);
