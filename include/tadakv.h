@@ -145,7 +145,7 @@ kv_status kv_quant_append(kv_cache *cache, int32_t layer, const void *k_new, con
  * "RoPECompress"; Sec. 3.4 and App. A: the rotation is the last computation before the cache
  * update, so the two are one kernel and the rotated keys never make a round trip through memory).
  *   k_pre    : device, keys BEFORE the rotation; shape, strides and alignment as k_new above
- *   rope_cos, rope_sin : device, float32 [n_new, head_dim/2], contiguous: cosine and sine of the
+ *   rope_cos, rope_sin : device, float32 [n_new, head_dim/2], contiguous, 16-byte aligned: cosine and sine of the
  *              angle of (token t of this call, channel pair i).  The caller owns the schedule
  *              (positions, base, scaling); the tables may be reused once the stream has passed.
  *   pairing  : which channels form pair i (kv_rope_pairing)

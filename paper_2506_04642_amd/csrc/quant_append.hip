@@ -502,8 +502,67 @@ __device__ __forceinline__ MetaOut meta_of(float mn, float mx, int qmax)
     return o;
 }
 
-template <int GC, int BITS>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 8))) void flush_wave_kernel(AppendArgs a, int n_items)
+// Rotation of this lane's 8 x 8 key values, token pair by token pair (Alg. 1 step 5).  With the
+// (i, i + 64) pairing the partner channel lives in lane l ^ 32 (same tokens); with (2i, 2i + 1)
+// it is the neighbouring register.  Rows that come from the residual buffer (tn < 0) were
+// rotated when they were stored.
+template <int DT>
+__device__ __forceinline__ void rope_in_lanes(float (&x)[8][8], const AppendArgs &a, int tn0, int lane)
+{
+    const int c8 = lane >> 2;
+    const bool half_mode = a.rope == 1;
+    // first of this lane's pair indices: 8 pairs (half) or 4 pairs (interleaved)
+    const int i0 = half_mode ? 8 * (c8 & 7) : 4 * c8;
+#pragma unroll
+    for (int jb = 0; jb < 8; jb += 2) {
+        float4 cs[2][2], sn[2][2];
+#pragma unroll
+        for (int d = 0; d < 2; d++) {
+            int tn = tn0 + jb + d;
+            tn = tn < 0 ? 0 : tn;
+            const float *pc = a.rope_cos + (long long)tn * 64 + i0, *ps = a.rope_sin + (long long)tn * 64 + i0;
+            cs[d][0] = *(const float4 *)pc;
+            sn[d][0] = *(const float4 *)ps;
+            if (half_mode) {
+                cs[d][1] = *(const float4 *)(pc + 4);
+                sn[d][1] = *(const float4 *)(ps + 4);
+            } else {
+                cs[d][1] = float4{0.0f, 0.0f, 0.0f, 0.0f};
+                sn[d][1] = float4{0.0f, 0.0f, 0.0f, 0.0f};
+            }
+        }
+#pragma unroll
+        for (int d = 0; d < 2; d++) {
+            const int j = jb + d;
+            const bool turn = tn0 + j >= 0;
+            const float cv[8] = {cs[d][0].x, cs[d][0].y, cs[d][0].z, cs[d][0].w, cs[d][1].x, cs[d][1].y, cs[d][1].z, cs[d][1].w};
+            const float sv[8] = {sn[d][0].x, sn[d][0].y, sn[d][0].z, sn[d][0].w, sn[d][1].x, sn[d][1].y, sn[d][1].z, sn[d][1].w};
+            if (half_mode) {
+                // lower channel of the pair: x cos - partner sin; upper: x cos + partner sin
+                const bool lower = c8 < 8;
+#pragma unroll
+                for (int e = 0; e < 8; e++) {
+                    const float xp = from_lane_f(x[j][e], lane ^ 32);
+                    const float p1 = x[j][e] * cv[e], p2 = xp * sv[e];
+                    const float y = round16<DT>(lower ? p1 - p2 : p1 + p2);
+                    x[j][e] = turn ? y : x[j][e];
+                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < 4; k++) {
+                    const float xa = x[j][2 * k], xb = x[j][2 * k + 1];
+                    float ya, yb;
+                    rope_pair_t<DT>(xa, xb, cv[k], sv[k], ya, yb);
+                    x[j][2 * k] = turn ? ya : xa;
+                    x[j][2 * k + 1] = turn ? yb : xb;
+                }
+            }
+        }
+    }
+}
+
+template <int GC, int BITS, bool ROPE>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ? 2 : 4, 8))) void flush_wave_kernel(AppendArgs a, int n_items)
 {
     constexpr int G = 32;
     constexpr int bits = BITS; // keys and values of the layer share the width in this instance
@@ -535,6 +594,12 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 8))
                 x[j][2 * k] = widen16((uint16_t)(wv[k] & 0xFFFFu), gm.dtype);
                 x[j][2 * k + 1] = widen16((uint16_t)(wv[k] >> 16), gm.dtype);
             }
+        }
+
+        if (ROPE && which == 0) {
+            const int tn0 = fb * G + 8 * tg - a.r_old; // index of this lane's first token in the call's input
+            if (gm.dtype == 1) rope_in_lanes<1>(x, a, tn0, lane);
+            else rope_in_lanes<0>(x, a, tn0, lane);
         }
 
         // ---- mean-centring
@@ -859,14 +924,14 @@ template <int G> hipError_t launch_flush_gc(const AppendArgs &a, hipStream_t s)
     return launch_flush_g<G, 128, false>(a, s);
 }
 
-template <int GC, int BITS> hipError_t launch_flush_wave(const AppendArgs &a, hipStream_t s)
+template <int GC, int BITS, bool ROPE> hipError_t launch_flush_wave(const AppendArgs &a, hipStream_t s)
 {
     const int U = a.batch * a.n_kv_heads;
     const long long items = (long long)a.n_flush_blocks * U * 2;
     if (items > 0x7FFFFFFF) return hipErrorInvalidValue;
     static const int slots = [] {
         int per_cu = 0, dev = 0, cus = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, flush_wave_kernel<GC, BITS>, kThreads, 0) != hipSuccess ||
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, flush_wave_kernel<GC, BITS, ROPE>, kThreads, 0) != hipSuccess ||
             hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
             return 0;
@@ -875,7 +940,7 @@ template <int GC, int BITS> hipError_t launch_flush_wave(const AppendArgs &a, hi
     if (slots < 1) return hipErrorInvalidValue;
     const long long want = (items + kThreads / 64 - 1) / (kThreads / 64);
     const int grid = want < slots ? (int)want : slots;
-    hipLaunchKernelGGL((flush_wave_kernel<GC, BITS>), dim3(grid), dim3(kThreads), 0, s, a, (int)items);
+    hipLaunchKernelGGL((flush_wave_kernel<GC, BITS, ROPE>), dim3(grid), dim3(kThreads), 0, s, a, (int)items);
     return note_launch(hipGetLastError());
 }
 
@@ -891,12 +956,15 @@ hipError_t launch_flush(const AppendArgs &a, hipStream_t s)
         if (e != hipSuccess) return e;
     }
     const int kb = a.geom.k_bits;
-    if (a.geom.G == 32 && a.rope == 0 && kb == a.geom.v_bits && kb != 16) {
-        // blocks of 32 tokens, one width for keys and values, no rotation: one wavefront per
-        // item, registers only
-        if (a.geom.Gc == 32) return kb == 2 ? launch_flush_wave<32, 2>(a, s) : kb == 4 ? launch_flush_wave<32, 4>(a, s) : launch_flush_wave<32, 8>(a, s);
-        if (a.geom.Gc == 64) return kb == 2 ? launch_flush_wave<64, 2>(a, s) : kb == 4 ? launch_flush_wave<64, 4>(a, s) : launch_flush_wave<64, 8>(a, s);
-        return kb == 2 ? launch_flush_wave<128, 2>(a, s) : kb == 4 ? launch_flush_wave<128, 4>(a, s) : launch_flush_wave<128, 8>(a, s);
+    if (a.geom.G == 32 && kb == a.geom.v_bits && kb != 16) {
+        // blocks of 32 tokens, one width for keys and values: one wavefront per item, registers only
+        const int gc = a.geom.Gc;
+#define TADAKV_WAVE(GCV, R)                                                                      \
+    (kb == 2 ? launch_flush_wave<GCV, 2, R>(a, s) : kb == 4 ? launch_flush_wave<GCV, 4, R>(a, s) \
+                                                           : launch_flush_wave<GCV, 8, R>(a, s))
+        if (a.rope != 0) return gc == 32 ? TADAKV_WAVE(32, true) : gc == 64 ? TADAKV_WAVE(64, true) : TADAKV_WAVE(128, true);
+        return gc == 32 ? TADAKV_WAVE(32, false) : gc == 64 ? TADAKV_WAVE(64, false) : TADAKV_WAVE(128, false);
+#undef TADAKV_WAVE
     }
     if (a.geom.G == 32) return launch_flush_gc<32>(a, s);
     if (a.geom.G == 64) return launch_flush_gc<64>(a, s);

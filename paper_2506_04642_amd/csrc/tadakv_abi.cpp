@@ -322,7 +322,7 @@ static kv_status append_impl(kv_cache *cache, int32_t layer, const void *k_new, 
     if (stride_h < c.head_dim || stride_t < 0 || stride_b < 0) return KV_E_BAD_CONFIG;
     if (rope != 0) {
         if (!rope_cos || !rope_sin) return KV_E_NULL;
-        if (((uintptr_t)rope_cos % 4) || ((uintptr_t)rope_sin % 4)) return KV_E_ALIGN;
+        if (((uintptr_t)rope_cos % 16) || ((uintptr_t)rope_sin % 16)) return KV_E_ALIGN;
     }
     const long long have = (long long)cache->packed[layer] + cache->resid[layer];
     if (have + n_new > c.max_tokens) return KV_E_CAPACITY;
