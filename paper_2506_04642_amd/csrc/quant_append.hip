@@ -573,13 +573,21 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ?
     const int tg = lane & 3, c8 = lane >> 2;
     const int U = a.batch * a.n_kv_heads;
     const int workers = (int)gridDim.x * (kThreads / 64);
+    // Each wave assembles its item's part of the record (codes, scale / zero, mean: contiguous in
+    // the record) in LDS at the final offsets and then writes it out as one linear run of 16-byte
+    // pieces; the words a lane produces are 4 to 16 bytes apart from its neighbours', and storing
+    // them directly left partly written cache lines to be completed from memory.
+    constexpr int IMG_BYTES = G * kHeadDim * BITS / 8 + 768;
+    __shared__ __attribute__((aligned(16))) unsigned char lds_img[kThreads / 64][IMG_BYTES];
+    unsigned char *img = lds_img[wave];
 
     for (int it = (int)blockIdx.x * (kThreads / 64) + wave; it < n_items; it += workers) {
         // keys and values cost differently: a worker alternates between them (workers is even)
         const int which = (it ^ (it / workers)) & 1, u = (it >> 1) % U, fb = (it >> 1) / U;
         const int b = u / a.n_kv_heads, h = u % a.n_kv_heads;
         unsigned char *rec = a.layer + ((long long)u * gm.NB + (a.first_block + fb)) * gm.rec_bytes;
-        unsigned char *codes_out = rec + (which == 0 ? gm.k_codes : gm.v_codes);
+        const int base_off = which == 0 ? gm.k_codes : gm.v_codes; // start of this item's part of the record
+        unsigned char *codes_out = img;
 
         uint4 pre[8];
 #pragma unroll
@@ -635,7 +643,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ?
                 else mpk[e >> 1] = m16;
             }
             if (tg == 0)
-                *(uint4 *)(rec + (which == 0 ? gm.k_mean : gm.v_mean) + c8 * 16) = uint4{mpk[0], mpk[1], mpk[2], mpk[3]};
+                *(uint4 *)(img + ((which == 0 ? gm.k_mean : gm.v_mean) - base_off) + c8 * 16) = uint4{mpk[0], mpk[1], mpk[2], mpk[3]};
 #pragma unroll
             for (int j = 0; j < 8; j++)
 #pragma unroll
@@ -700,8 +708,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ?
                     sw[k] = (pk[2 * k] & 0xFFFFu) | (pk[2 * k + 1] << 16);
                     zw[k] = (pk[2 * k] >> 16) | (pk[2 * k + 1] & 0xFFFF0000u);
                 }
-                *(uint4 *)(rec + gm.k_scale + c8 * 16) = uint4{sw[0], sw[1], sw[2], sw[3]};
-                *(uint4 *)(rec + gm.k_zero + c8 * 16) = uint4{zw[0], zw[1], zw[2], zw[3]};
+                *(uint4 *)(img + (gm.k_scale - base_off) + c8 * 16) = uint4{sw[0], sw[1], sw[2], sw[3]};
+                *(uint4 *)(img + (gm.k_zero - base_off) + c8 * 16) = uint4{zw[0], zw[1], zw[2], zw[3]};
             }
             float sc[8], z[8];
 #pragma unroll
@@ -772,8 +780,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ?
             const MetaOut mb = meta_of(pick4(q4, mn[1], mn[3], mn[5], mn[7]), pick4(q4, mx[1], mx[3], mx[5], mx[7]), qmax);
             if ((c8 & (GC / 8 - 1)) == q4) {
                 const int gam = c8 / (GC / 8), t = 8 * tg + 2 * q4;
-                *(uint32_t *)(rec + gm.v_meta + (t * NGV + gam) * 4) = ma.pk;
-                *(uint32_t *)(rec + gm.v_meta + ((t + 1) * NGV + gam) * 4) = mb.pk;
+                *(uint32_t *)(img + (gm.v_meta - base_off) + (t * NGV + gam) * 4) = ma.pk;
+                *(uint32_t *)(img + (gm.v_meta - base_off) + ((t + 1) * NGV + gam) * 4) = mb.pk;
             }
             uint32_t pk[8];
             float rs[8];
@@ -819,6 +827,14 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ?
                 }
             }
         }
+
+        // ---- the assembled part of the record -> memory, linear
+        int part_bytes;
+        if (which == 0) part_bytes = (gm.mean_mode == 0 ? gm.k_mean : gm.k_zero) + 256 - base_off;
+        else part_bytes = (gm.mean_mode == 0 ? gm.v_mean + 256 : gm.v_meta + G * NGV * 4) - base_off;
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // this wave's LDS writes have landed
+        for (int off = lane * 16; off < part_bytes; off += 64 * 16) *(uint4 *)(rec + base_off + off) = *(const uint4 *)(img + off);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // the image is in registers before the next item overwrites it
     }
 }
 
