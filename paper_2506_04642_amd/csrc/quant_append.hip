@@ -562,7 +562,7 @@ __device__ __forceinline__ void rope_in_lanes(float (&x)[8][8], const AppendArgs
 }
 
 template <int GC, int BITS, bool ROPE>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ? 2 : 4, 8))) void flush_wave_kernel(AppendArgs a, int n_items)
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ? 2 : 3, 8))) void flush_wave_kernel(AppendArgs a, int n_items)
 {
     constexpr int G = 32;
     constexpr int bits = BITS; // keys and values of the layer share the width in this instance
