@@ -134,11 +134,12 @@ __device__ __forceinline__ void softmax_chunk(const float (&s)[4], State &st, fl
     float mc = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
     mc = row_max(mc);
     const float m_new = fmaxf(st.M, mc);
-    alpha = exp2f(st.M - m_new);
-    wc = exp2f(mc - m_new);
+    // the bare instruction: arguments are <= 0 (or -inf), and a weight below 2^-126 may flush to zero
+    alpha = __builtin_amdgcn_exp2f(st.M - m_new);
+    wc = __builtin_amdgcn_exp2f(mc - m_new);
     st.M = m_new;
 #pragma unroll
-    for (int k = 0; k < 4; k++) p[k] = exp2f(s[k] - mc);
+    for (int k = 0; k < 4; k++) p[k] = __builtin_amdgcn_exp2f(s[k] - mc);
     st.l = st.l * alpha + wc * ((p[0] + p[1]) + (p[2] + p[3]));
 }
 
