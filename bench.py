@@ -44,6 +44,8 @@ def parse():
     ap.add_argument("--scheme", default="mixed248", help="layer bit map: mixed248 or mixed24_8ends")
     ap.add_argument("--seed", type=int, default=2000)
     ap.add_argument("--splits", type=int, default=0, help="force the sequence split count (0 = automatic)")
+    ap.add_argument("--mean-mode", default="channel", choices=["channel", "cross", "none"],
+                    help="channel: per-channel block mean (the workload); cross: mean over kv heads (Eq. 1-2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--separate-append", dest="fused_step", action="store_false",
                     help="append and attend as two calls per layer instead of the one-call decode step")
@@ -73,7 +75,8 @@ def main():
     n_dec = K + W
     max_tokens = (T0 + n_dec + 8 + G - 1) // G * G
     bits = synth.layer_bits(args.seed, L, args.scheme)
-    cfg = kv.make_config(L, B, Hq, Hkv, d, max_tokens, G, G, G, kv.KV_BF16, kv.KV_MEAN_CHANNEL_BLOCK, bits, bits)
+    mean_mode = {"channel": kv.KV_MEAN_CHANNEL_BLOCK, "cross": kv.KV_MEAN_CROSS_HEAD, "none": kv.KV_MEAN_NONE}[args.mean_mode]
+    cfg = kv.make_config(L, B, Hq, Hkv, d, max_tokens, G, G, G, kv.KV_BF16, mean_mode, bits, bits)
     cache = kv.KVCache(cfg, device=dev, zero=False)
     kv.kv_set_decode_path(cache.handle, args.path)
     if args.splits:
@@ -255,7 +258,9 @@ def main():
         "data": "synthetic",
         "config": {"workload": "llama-shaped full cache: %d layers, %dq/%dkv heads, head_dim 128, "
                                "batch %d, context %d, bf16, G=Gc=%d, %s layer bit map (seed %d), "
-                               "per-channel block mean" % (L, Hq, Hkv, B, T0, G, args.scheme, args.seed),
+                               "%s" % (L, Hq, Hkv, B, T0, G, args.scheme, args.seed,
+                                       {"channel": "per-channel block mean", "cross": "cross-head mean",
+                                        "none": "no mean"}[args.mean_mode]),
                    "layers": L, "batch": B, "context": T0, "bit_map": bits, "decode_path": args.path},
         "pct_of_hbm_peak": round(total_bytes / wall / 1e9 / HBM_PEAK_GBPS * 100, 2),
         "decode_tokens_per_s": round(B * K / wall, 1),
@@ -280,7 +285,7 @@ def main():
         ocfg_bits = [sample_layers[l] for l in sorted(sample_layers)]
         nl = len(ocfg_bits)
         ocfg = oracle.OracleConfig(nl, 1, Hq, Hkv, d, max_tokens, G, G, G, oracle.tada.BF16,
-                                   oracle.tada.MEAN_CHANNEL_BLOCK, ocfg_bits, ocfg_bits)
+                                   mean_mode, ocfg_bits, ocfg_bits)
         orc = oracle.OracleCache(ocfg)
         enc_s = att_s = 0.0
         att_bytes = 0

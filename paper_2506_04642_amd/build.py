@@ -19,6 +19,7 @@ UNITS = [
     ("decode_valu.hip", []),
     # matrix-instruction results go straight to ordinary vector registers
     ("decode_mfma.hip", ["-mllvm", "-amdgpu-mfma-vgpr-form"]),
+    ("xhead_dense.hip", []),
 ]
 
 

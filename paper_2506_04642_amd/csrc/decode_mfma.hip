@@ -129,9 +129,9 @@ struct State {
 // of token 16k + n or -inf.  Returns p[k] relative to the chunk's own max, and the factors
 // alpha (old state) and wc (this chunk) that bring both to the new running max.
 __device__ __forceinline__ void softmax_chunk(const float (&s)[4], State &st, float (&p)[4], float &alpha,
-                                              float &wc)
+                                              float &wc, float &mc)
 {
-    float mc = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
+    mc = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
     mc = row_max(mc);
     const float m_new = fmaxf(st.M, mc);
     // the bare instruction: arguments are <= 0 (or -inf), and a weight below 2^-126 may flush to zero
@@ -211,9 +211,13 @@ template <> struct CodeOps<8> { // four words = one tile line; split into nibble
     }
 };
 
-template <int B, int G, int GC, bool MEAN, int NW, int NHG>
-__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2 && NHG == 1) ? 4 : 1, 8))) void decode_split_mfma_kernel(DecodeArgs a)
+// XH: cross-head mean.  The records carry no mean (MEAN is false); the mean's share of every
+// score comes in through a.xs, and the softmax weights go out through a.xp / a.xmc for the kernel
+// that adds the value mean plane's share to the partial outputs.
+template <int B, int G, int GC, bool MEAN, int NW, int NHG, bool XH>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2 && NHG == 1 && !XH) ? 4 : 1, 8))) void decode_split_mfma_kernel(DecodeArgs a)
 {
+    static_assert(!(XH && MEAN), "cross-head layers store no per-record mean");
     typedef RecLayout<B, G, GC, MEAN> RL;
     constexpr int NBC = 64 / G;            // blocks per 64-token chunk
     constexpr int TPB = G / 16;            // 16-token tiles per block
@@ -321,6 +325,27 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
     const uint32_t sel1 = (qa & 1) ? 0x03070105u : 0x06020400u;
     const uint32_t sel2 = (qa & 2) ? 0x03020706u : 0x05040100u;
 
+    // cross-head mean: q . mean_K of this lane's tokens (16 k + n of a chunk), worked out by the
+    // kernel that ran before this one; loaded one chunk ahead
+    long long xq[NHG]; // query head index in the batch
+    float xsn[NHG][4];
+    auto load_xs = [&](int ci) {
+        const int blk = w0 + ci * cstride;
+#pragma unroll
+        for (int hg = 0; hg < NHG; hg++)
+#pragma unroll
+            for (int k = 0; k < 4; k++)
+                xsn[hg][k] = blk + k / TPB < b_end ? a.xs[xq[hg] * a.tcap + (long long)blk * G + 16 * k + n] : 0.0f;
+    };
+    if (XH) {
+#pragma unroll
+        for (int hg = 0; hg < NHG; hg++) {
+            const int head = 4 * hg + row;
+            xq[hg] = (long long)b * a.n_q_heads + h * g + (head < g ? head : 0);
+        }
+        if (wave < n_chunks) load_xs(wave);
+    }
+
     // Issue priority falls as a wave advances (quarters of its chunks).  By default the oldest wave
     // of a SIMD wins every arbitration, so the workgroups that arrived first on a compute unit run
     // ahead and leave the last ones to finish alone, at low occupancy and far below the memory
@@ -388,6 +413,18 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
         // every read of the staging buffer has returned: start fetching this wave's next chunk
         wave_lds_fence();
         if (ci + NW < n_chunks) issue(ci + NW);
+
+        float xsv[NHG][4];
+        long long xbase[NHG]; // this lane's first token of the chunk in xs / xp
+        if (XH) {
+#pragma unroll
+            for (int hg = 0; hg < NHG; hg++) {
+                xbase[hg] = xq[hg] * a.tcap + (long long)blk0 * G;
+#pragma unroll
+                for (int k = 0; k < 4; k++) xsv[hg][k] = xsn[hg][k];
+            }
+            if (ci + NW < n_chunks) load_xs(ci + NW);
+        }
 
         // ---- key side, one block at a time (the operand scratch holds one block's operands):
         // q*scale as limbs -> LDS, zero/mean term, then the block's matrix products -> scores
@@ -472,8 +509,11 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
                     }
                 }
 #pragma unroll
-                for (int hg = 0; hg < NHG; hg++)
-                    s[hg][k] = blk_ok[bi] ? limbs_to_float(acc[hg]) * inv_kf[hg] + beta[hg] : -INFINITY;
+                for (int hg = 0; hg < NHG; hg++) {
+                    float sc_ = limbs_to_float(acc[hg]) * inv_kf[hg] + beta[hg];
+                    if (XH) sc_ += xsv[hg][k] * kScoreScale;
+                    s[hg][k] = blk_ok[bi] ? sc_ : -INFINITY;
+                }
             }
         }
 
@@ -493,8 +533,15 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
         float p[NHG][4], alpha[NHG], o_scale[NHG], psum_b[NHG][NBC];
 #pragma unroll
         for (int hg = 0; hg < NHG; hg++) {
-            float wc;
-            softmax_chunk(s[hg], st[hg], p[hg], alpha[hg], wc);
+            float wc, mc;
+            softmax_chunk(s[hg], st[hg], p[hg], alpha[hg], wc, mc);
+            if (XH && 4 * hg + row < g) {
+                // the weights and the chunk's maximum, for the value mean plane's share
+#pragma unroll
+                for (int k = 0; k < 4; k++)
+                    if (blk_ok[k / TPB]) a.xp[xbase[hg] + 16 * k + n] = p[hg][k];
+                if (n == 0) a.xmc[xq[hg] * (a.tcap / 64 + 1) + blk0 / NBC] = mc;
+            }
             o_scale[hg] = wc * sbv * 0x1p-22f;
 #pragma unroll
             for (int gam = 0; gam < NG; gam++) {
@@ -655,7 +702,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
                                    ? (spart[head * 32 + t] + spart[(NH + head) * 32 + t]) * kScoreScale
                                    : -INFINITY;
                     }
-                    softmax_chunk(s, st[hg], p, al[hg], wcr[hg]);
+                    float mcr;
+                    softmax_chunk(s, st[hg], p, al[hg], wcr[hg], mcr);
                     pr[hg][0] = p[0];
                     pr[hg][1] = p[1];
                 }
@@ -739,11 +787,11 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
 }
 
 // Resident workgroups of one instantiation on the whole device (0 if the query fails).
-template <int B, int G, int GC, bool MEAN, int NW, int NHG> int resident_blocks()
+template <int B, int G, int GC, bool MEAN, int NW, int NHG, bool XH> int resident_blocks()
 {
     static const int n = [] {
         int per_cu = 0, dev = 0, cus = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_split_mfma_kernel<B, G, GC, MEAN, NW, NHG>,
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_split_mfma_kernel<B, G, GC, MEAN, NW, NHG, XH>,
                                                          64 * NW, 0) != hipSuccess)
             return 0;
         if (hipGetDevice(&dev) != hipSuccess) return 0;
@@ -753,22 +801,22 @@ template <int B, int G, int GC, bool MEAN, int NW, int NHG> int resident_blocks(
     return n;
 }
 
-template <int B, int G, int GC, bool MEAN, int NHG> hipError_t launch_inst(const DecodeArgs &a, hipStream_t s)
+template <int B, int G, int GC, bool MEAN, int NHG, bool XH> hipError_t launch_inst(const DecodeArgs &a, hipStream_t s)
 {
     constexpr int NW = kWavesPerBlock;
     if (!RecLayout<B, G, GC, MEAN>::matches(a.geom)) return hipErrorInvalidValue;
     dim3 grid(a.n_splits, a.batch * a.n_kv_heads);
     (void)hipGetLastError(); // drop any stale error left by earlier runtime calls of this thread
-    hipLaunchKernelGGL((decode_split_mfma_kernel<B, G, GC, MEAN, NW, NHG>), grid, dim3(64 * NW), 0, s, a);
+    hipLaunchKernelGGL((decode_split_mfma_kernel<B, G, GC, MEAN, NW, NHG, XH>), grid, dim3(64 * NW), 0, s, a);
     return note_launch(hipGetLastError());
 }
 
 // Split count that puts every workgroup of the launch on the device at once (one "round"):
 // the kernel is a bandwidth stream, and a second, partly filled round only adds a tail.
-template <int B, int G, int GC, bool MEAN, int NHG> int plan_inst(const DecodeArgs &a)
+template <int B, int G, int GC, bool MEAN, int NHG, bool XH> int plan_inst(const DecodeArgs &a)
 {
     constexpr int NW = kWavesPerBlock, NBC = 64 / G;
-    const int slots = resident_blocks<B, G, GC, MEAN, NW, NHG>();
+    const int slots = resident_blocks<B, G, GC, MEAN, NW, NHG, XH>();
     const int U = a.batch * a.n_kv_heads;
     const int chunks = (a.n_blocks + NBC - 1) / NBC;
     int ns = slots / U;
@@ -783,26 +831,28 @@ template <int B, int G, int GC, bool MEAN, int NHG> int plan_inst(const DecodeAr
 struct DoLaunch {
     hipStream_t s;
     hipError_t result = hipErrorInvalidValue;
-    template <int B, int G, int GC, bool MEAN, int NHG> void run(const DecodeArgs &a) { result = launch_inst<B, G, GC, MEAN, NHG>(a, s); }
+    template <int B, int G, int GC, bool MEAN, int NHG, bool XH> void run(const DecodeArgs &a) { result = launch_inst<B, G, GC, MEAN, NHG, XH>(a, s); }
 };
 struct DoPlan {
     int result = 1;
-    template <int B, int G, int GC, bool MEAN, int NHG> void run(const DecodeArgs &a) { result = plan_inst<B, G, GC, MEAN, NHG>(a); }
+    template <int B, int G, int GC, bool MEAN, int NHG, bool XH> void run(const DecodeArgs &a) { result = plan_inst<B, G, GC, MEAN, NHG, XH>(a); }
 };
 struct DoMatch {
     bool result = false;
-    template <int B, int G, int GC, bool MEAN, int NHG> void run(const DecodeArgs &a) { result = RecLayout<B, G, GC, MEAN>::matches(a.geom); }
+    template <int B, int G, int GC, bool MEAN, int NHG, bool XH> void run(const DecodeArgs &a) { result = RecLayout<B, G, GC, MEAN>::matches(a.geom); }
 };
 
 template <int B, int G, int GC, class F> void pick_mean_heads(const DecodeArgs &a, F &f)
 {
-    const bool mean = a.geom.mean_mode == 0;
+    const int mode = a.geom.mean_mode; // 0 per-channel block mean, 1 cross-head mean, 2 none
     if (a.g <= 4) {
-        if (mean) f.template run<B, G, GC, true, 1>(a);
-        else f.template run<B, G, GC, false, 1>(a);
+        if (mode == 0) f.template run<B, G, GC, true, 1, false>(a);
+        else if (mode == 1) f.template run<B, G, GC, false, 1, true>(a);
+        else f.template run<B, G, GC, false, 1, false>(a);
     } else {
-        if (mean) f.template run<B, G, GC, true, 2>(a);
-        else f.template run<B, G, GC, false, 2>(a);
+        if (mode == 0) f.template run<B, G, GC, true, 2, false>(a);
+        else if (mode == 1) f.template run<B, G, GC, false, 2, true>(a);
+        else f.template run<B, G, GC, false, 2, false>(a);
     }
 }
 template <class F> void pick(const DecodeArgs &a, F &f)
@@ -828,7 +878,7 @@ bool decode_mfma_supported(const DecodeArgs &a)
     if (!(g.k_bits == 2 || g.k_bits == 4 || g.k_bits == 8)) return false;
     if (!((g.G == 32 && g.Gc == 32) || (g.G == 64 && g.Gc == 64))) return false;
     if (a.g > 8) return false;
-    if (g.mean_mode == 1) return false; // cross-head mean: not on this path
+    if (g.mean_mode == 1 && a.n_q_heads > 64) return false; // the dense mean terms keep all query heads of a sequence in LDS
     if (a.batch * a.n_kv_heads > 65535) return false;
     // the kernels address record fields with compile-time offsets
     DoMatch m;
@@ -847,6 +897,11 @@ int decode_mfma_splits(const DecodeArgs &a)
 hipError_t launch_decode_split_mfma(const DecodeArgs &a, hipStream_t s)
 {
     if (!decode_mfma_supported(a)) return hipErrorInvalidValue;
+    if (a.geom.mean_mode == 1) {
+        if (!a.xs || !a.xp || !a.xmc) return hipErrorInvalidValue;
+        const hipError_t e = launch_xhead_scores(a, s);
+        if (e != hipSuccess) return e;
+    }
     DoLaunch l;
     l.s = s;
     pick(a, l);

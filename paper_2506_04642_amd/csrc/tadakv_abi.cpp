@@ -17,6 +17,7 @@ struct kv_cache {
     std::vector<int> packed, resid; // tokens
     int decode_path = 0;
     int forced_splits = 0;
+    size_t xhead_off = 0, xhead_bytes = 0; // cross-head mean: where its arrays start in the workspace, total size
 };
 
 namespace {
@@ -128,6 +129,30 @@ size_t workspace_need(const kv_config &c, int n_splits)
     return (size_t)c.batch * c.n_q_heads * n_splits * kPartialStride * sizeof(float);
 }
 
+// Largest split count any length of this configuration can ask for.
+int worst_splits(const kv_config &c)
+{
+    int worst = 1;
+    const int NB = c.max_tokens / c.group_tokens;
+    for (int nb = 0; nb <= NB; nb++) {
+        int ns, bps;
+        choose_splits(c, nb, 1, &ns, &bps);
+        if (ns > worst) worst = ns;
+    }
+    if (mfma_split_bound(c) > worst) worst = mfma_split_bound(c);
+    return worst;
+}
+
+// Cross-head mean on the matrix-core path: behind the partials (sized for the largest split count)
+// the workspace holds xs and xp, [batch][Hq][max_tokens] floats each, and xmc,
+// [batch][Hq][max_tokens / 64 + 1] floats.
+size_t xhead_offset(const kv_config &c) { return (size_t)align_up((long long)workspace_need(c, worst_splits(c)), 256); }
+size_t xhead_total(const kv_config &c)
+{
+    const size_t rows = (size_t)c.batch * c.n_q_heads;
+    return xhead_offset(c) + rows * ((size_t)2 * c.max_tokens + c.max_tokens / 64 + 1) * sizeof(float);
+}
+
 kv_status layer_ok(const kv_cache *k, int layer)
 {
     if (!k) return KV_E_NULL;
@@ -146,6 +171,7 @@ kv_status fill_decode(const kv_cache *k, int layer, DecodeArgs *a)
     a->g = c.n_q_heads / c.n_kv_heads;
     a->n_blocks = k->packed[layer] / c.group_tokens;
     a->r = k->resid[layer];
+    a->tcap = c.max_tokens;
     if (a->n_blocks == 0 && a->r == 0) return KV_E_EMPTY;
     choose_splits(c, a->n_blocks, a->r, &a->n_splits, &a->blocks_per_split);
     if (k->decode_path != 1 && decode_mfma_supported(*a)) {
@@ -168,6 +194,24 @@ bool use_mfma(const kv_cache *k, const DecodeArgs &a)
 {
     if (k->decode_path == 1) return false;
     return decode_mfma_supported(a);
+}
+
+// Workspace bytes this launch needs, and the cross-head arrays placed in it.
+kv_status bind_workspace(const kv_cache *k, DecodeArgs *a, void *workspace, size_t workspace_bytes)
+{
+    const kv_config &c = k->cfg;
+    const bool xhead = c.mean_mode == KV_MEAN_CROSS_HEAD && a->geom.k_bits != 16 && use_mfma(k, *a);
+    const size_t need = xhead ? k->xhead_bytes : workspace_need(c, a->n_splits);
+    if (!workspace || workspace_bytes < need) return KV_E_WORKSPACE;
+    if ((uintptr_t)workspace % 256) return KV_E_ALIGN;
+    a->ws = (float *)workspace;
+    if (xhead) {
+        const size_t rows = (size_t)c.batch * c.n_q_heads;
+        a->xs = (float *)((unsigned char *)workspace + k->xhead_off);
+        a->xp = a->xs + rows * c.max_tokens;
+        a->xmc = a->xp + rows * c.max_tokens;
+    }
+    return KV_OK;
 }
 
 } // namespace
@@ -218,16 +262,8 @@ kv_status kv_workspace_bytes(const kv_config *cfg, size_t *bytes)
     if (!bytes) return KV_E_NULL;
     kv_status st = check_config(cfg);
     if (st != KV_OK) return st;
-    // the split count grows with the length; take the largest over all reachable lengths
-    int worst = 1;
-    const int NB = cfg->max_tokens / cfg->group_tokens;
-    for (int nb = 0; nb <= NB; nb++) {
-        int ns, bps;
-        choose_splits(*cfg, nb, 1, &ns, &bps);
-        if (ns > worst) worst = ns;
-    }
-    if (mfma_split_bound(*cfg) > worst) worst = mfma_split_bound(*cfg);
-    *bytes = workspace_need(*cfg, worst);
+    // the split count grows with the length: sized for the largest over all reachable lengths
+    *bytes = cfg->mean_mode == KV_MEAN_CROSS_HEAD ? xhead_total(*cfg) : workspace_need(*cfg, worst_splits(*cfg));
     return KV_OK;
 }
 
@@ -253,6 +289,10 @@ kv_status kv_cache_create(const kv_config *cfg, void *const *layer_dev_ptrs, kv_
     }
     k->packed.assign(cfg->n_layers, 0);
     k->resid.assign(cfg->n_layers, 0);
+    if (cfg->mean_mode == KV_MEAN_CROSS_HEAD) {
+        k->xhead_off = xhead_offset(k->cfg);
+        k->xhead_bytes = xhead_total(k->cfg);
+    }
     *out = k;
     return KV_OK;
 }
@@ -442,12 +482,11 @@ kv_status kv_decode_attn_split(const kv_cache *cache, int32_t layer, const void 
     DecodeArgs a{};
     st = fill_decode(cache, layer, &a);
     if (st != KV_OK) return st;
-    if (!workspace || workspace_bytes < workspace_need(cache->cfg, a.n_splits)) return KV_E_WORKSPACE;
-    if ((uintptr_t)workspace % 256) return KV_E_ALIGN;
+    st = bind_workspace(cache, &a, workspace, workspace_bytes);
+    if (st != KV_OK) return st;
     if (cache->cfg.mean_mode == KV_MEAN_CROSS_HEAD && a.geom.k_bits != 16 && a.geom.G > 64)
         return KV_E_UNSUPPORTED; // the cross-head mean tiles of a 128-token block do not fit the kernel's LDS
     a.q = (const uint16_t *)q;
-    a.ws = (float *)workspace;
     a.out = nullptr;
     hipStream_t s = (hipStream_t)stream;
     if (cache->decode_path == 2 && !decode_mfma_supported(a)) return KV_E_UNSUPPORTED;
@@ -465,11 +504,12 @@ kv_status kv_decode_attn_merge(const kv_cache *cache, int32_t layer, float *out,
     DecodeArgs a{};
     st = fill_decode(cache, layer, &a);
     if (st != KV_OK) return st;
-    if (!workspace || workspace_bytes < workspace_need(cache->cfg, a.n_splits)) return KV_E_WORKSPACE;
-    if ((uintptr_t)workspace % 256) return KV_E_ALIGN;
+    st = bind_workspace(cache, &a, const_cast<void *>(workspace), workspace_bytes);
+    if (st != KV_OK) return st;
     a.q = nullptr;
-    a.ws = (float *)const_cast<void *>(workspace);
     a.out = out;
+    // cross-head mean on the matrix-core path: the value mean plane's share joins the partials first
+    if (a.xs && launch_xhead_values(a, (hipStream_t)stream) != hipSuccess) return KV_E_HIP;
     return launch_decode_merge(a, (hipStream_t)stream) == hipSuccess ? KV_OK : KV_E_HIP;
 }
 
@@ -494,8 +534,7 @@ kv_status kv_append_decode_attn_split(kv_cache *cache, int32_t layer, const void
     cache->resid[layer] = flush ? 0 : r_old + 1;
     st = fill_decode(cache, layer, &a);
     const bool mfma = st == KV_OK && use_mfma(cache, a);
-    if (st == KV_OK && (!workspace || workspace_bytes < workspace_need(c, a.n_splits))) st = KV_E_WORKSPACE;
-    if (st == KV_OK && ((uintptr_t)workspace % 256)) st = KV_E_ALIGN;
+    if (st == KV_OK) st = bind_workspace(cache, &a, workspace, workspace_bytes);
     if (st == KV_OK && c.mean_mode == KV_MEAN_CROSS_HEAD && a.geom.k_bits != 16 && a.geom.G > 64) st = KV_E_UNSUPPORTED;
     if (st == KV_OK && cache->decode_path == 2 && !mfma) st = KV_E_UNSUPPORTED;
     if (st != KV_OK || flush || !mfma) {
@@ -509,7 +548,6 @@ kv_status kv_append_decode_attn_split(kv_cache *cache, int32_t layer, const void
         return kv_decode_attn_split(cache, layer, q, workspace, workspace_bytes, stream);
     }
     a.q = (const uint16_t *)q;
-    a.ws = (float *)workspace;
     a.out = nullptr;
     a.k_fresh = (const uint16_t *)k_new;
     a.v_fresh = (const uint16_t *)v_new;

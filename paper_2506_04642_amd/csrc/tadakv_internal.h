@@ -53,6 +53,12 @@ struct DecodeArgs {
     // the kernel takes it from these rows and stores it (null: every token is in the cache)
     const uint16_t *k_fresh, *v_fresh;
     long long fresh_stride_b, fresh_stride_h; // elements
+    // cross-head mean on the matrix-core path: the dense mean terms go through three arrays in the
+    // workspace (null otherwise).  xs [batch][Hq][tcap]: q . mean_K of every packed token;
+    // xp [batch][Hq][tcap]: softmax weight of every packed token relative to its chunk's maximum;
+    // xmc [batch][Hq][tcap / 64]: that maximum (exp2 domain) per 64-token chunk.
+    float *xs, *xp, *xmc;
+    int tcap;
 };
 
 // records the outcome of a launch for kv_last_hip_error and passes it through
@@ -65,5 +71,9 @@ hipError_t launch_decode_split_mfma(const DecodeArgs &a, hipStream_t s);
 bool decode_mfma_supported(const DecodeArgs &a);
 int decode_mfma_splits(const DecodeArgs &a); // preferred split count of the matrix-core kernel
 hipError_t launch_decode_merge(const DecodeArgs &a, hipStream_t s);
+// cross-head mean, matrix-core path: scores of the queries against the key mean plane (before the
+// split kernel) and the value mean plane's contribution to the partial outputs (before the merge)
+hipError_t launch_xhead_scores(const DecodeArgs &a, hipStream_t s);
+hipError_t launch_xhead_values(const DecodeArgs &a, hipStream_t s);
 
 } // namespace tadakv

@@ -294,6 +294,27 @@ def test_cross_head_mean_mixed_layers_bf16(kv, oracle):
         check_attention(gpu, orc, l, synth.make_q(l, 1, 32, 128, BF16), BF16)
 
 
+@pytest.mark.parametrize("decode_path", [2], indirect=True, ids=["mfma"])
+@pytest.mark.parametrize("bits,G,g,T", [(4, 32, 3, 2000 + 13), (2, 32, 5, 1056), (8, 64, 4, 1600 + 40), (4, 64, 8, 704)])
+def test_cross_head_mean_on_the_matrix_cores(kv, oracle, decode_path, bits, G, g, T):
+    """Cross-head mean with the deviations on the matrix-core kernel and the two dense mean terms
+    in their own kernels; several splits, an odd block count, a raw tail."""
+    print("case cross_head_mfma bits=%d G=%d g=%d T=%d" % (bits, G, g, T), flush=True)
+    Hkv = 4
+    gpu, orc = make_pair(kv, oracle, B=2, Hq=Hkv * g, Hkv=Hkv, T_max=(T // G + 2) * G, G=G, Gc=G, dtype=BF16, mode=CROSS,
+                         k_bits=(bits,))
+    k, v = synth.make_kv(500 + bits + g, 2, T, Hkv, 128, BF16)
+    append_both(gpu, orc, 0, k, v, BF16, chunks=[T - 1, 1])
+    check_bytes(gpu, orc, 0)
+    q = synth.make_q(500 + bits, 2, Hkv * g, 128, BF16)
+    check_attention(gpu, orc, 0, q, BF16)
+    import torch
+    a = gpu.attend(0, to_dev(q, BF16))
+    b = gpu.attend(0, to_dev(q, BF16))
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+
+
 # ------------------------------------------------------------------ matrix-core kernels, forced
 
 
