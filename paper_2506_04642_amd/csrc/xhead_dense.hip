@@ -100,31 +100,41 @@ __global__ __launch_bounds__(kThreads) void xhead_scores_kernel(DecodeArgs a)
     }
 }
 
-// grid (n_splits, units).  The chunks of a split are the ones the split kernel gave it (chunk
-// sp + n_splits j of the unit).  Thread = (channel pair, quarter of the chunk's tokens); every
-// thread keeps sums for all query heads of the unit, the four quarters are added at the end.
-template <int NI> // query heads per kv head, rounded up to 1, 2, 4 or 8 (weights of the padding heads are zero)
+// One workgroup per (unit, split).  The chunks of a split are the ones the split kernel gave it
+// (chunk sp + n_splits j of the unit).  Per chunk the workgroup puts the 64 value-mean rows and
+// the weights of the unit's query heads (as a binary16 pair hi + lo, so that nothing is lost) in
+// LDS; wave v then owns channels 32 v .. 32 v + 31 and accumulates
+//   D[head][channel] += W[head][token] . M[token][channel]
+// with v_mfma_f32_16x16x32_f16 (A = weights: row = head, 8 consecutive tokens per lane; B = mean:
+// column = channel, the same 8 tokens gathered from 8 rows of the LDS tile).
+// (Tried: waves that stage their own 64 x 32 slab and never meet at a barrier -- a row per lane
+// makes every load instruction touch 64 cache lines, and the kernel ran at half the speed.)
+constexpr int kMvStride = 132; // halfs per LDS row of the mean tile: rows 8 apart start in different banks
+constexpr int kWStride = 72;   // halfs per LDS row of the weights
+
 __global__ __launch_bounds__(kThreads) void xhead_values_kernel(DecodeArgs a)
 {
-    __shared__ float w[kMaxGroupQ][64];
-    __shared__ float red[4][kMaxGroupQ][kHeadDim];
+    __shared__ __attribute__((aligned(16))) _Float16 mvs[64 * kMvStride];
+    __shared__ __attribute__((aligned(16))) _Float16 whi[16 * kWStride], wlo[16 * kWStride];
     const LayerGeom &gm = a.geom;
-    const int sp = blockIdx.x, u = blockIdx.y, ns = a.n_splits, g = a.g;
-    const int b = u / a.n_kv_heads, h = u % a.n_kv_heads;
+    // Workgroups are handed to the 8 XCDs in turn (index % 8), each XCD with an L2 of its own.  All
+    // kv heads of one (sequence, split) read the same rows of the value mean plane, so they are
+    // given indices 8 apart: same XCD, one fetch from memory, the other heads hit its L2.
+    const int ns = a.n_splits, g = a.g;
+    const int xr = blockIdx.x >> 3, h = xr % a.n_kv_heads;
+    const int pair = (xr / a.n_kv_heads) * 8 + (blockIdx.x & 7); // (sequence, split) number
+    if (pair >= a.batch * ns) return;
+    const int b = pair / ns, sp = pair - b * ns, u = b * a.n_kv_heads + h;
     const int nbc = 64 / gm.G > 0 ? 64 / gm.G : 1;
     const int chunks_total = (a.n_blocks + nbc - 1) / nbc;
     const int T = a.n_blocks * gm.G;
-    const int cp = threadIdx.x & 63, tq = threadIdx.x >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 15, kg = lane >> 4;
     const int ncap = a.tcap / 64 + 1;
-    float acc[NI][2];
-#pragma unroll
-    for (int i = 0; i < NI; i++) acc[i][0] = acc[i][1] = 0.0f;
-    for (int e = threadIdx.x; e < kMaxGroupQ * 64; e += kThreads) w[e >> 6][e & 63] = 0.0f;
-    // value plane of this sequence: token t sits (t + (t rounded down to its block)) rows of 128 in
-    const uint16_t *vplane = (const uint16_t *)(a.layer + gm.xmean_off) + ((long long)b * gm.NB * 2 + 1) * gm.G * kHeadDim + 2 * cp;
-    const int gmask = ~(gm.G - 1);
-    // weight staging: thread e handles (head e / 64, token e % 64) of the chunk, twice if g > 4
-    const int wi = threadIdx.x >> 6, wt_tok = threadIdx.x & 63;
+    for (int e = tid; e < 16 * kWStride; e += kThreads) whi[e] = wlo[e] = (_Float16)0.0f;
+
+    // weight staging: thread handles (head tid / 64 [+ 4], token tid % 64) of the chunk
+    const int wi = tid >> 6, wt_tok = tid & 63;
     float Msp[2];
     long long wq[2];
 #pragma unroll
@@ -133,67 +143,71 @@ __global__ __launch_bounds__(kThreads) void xhead_values_kernel(DecodeArgs a)
         Msp[r] = a.ws[((long long)(u * g + i) * ns + sp) * kPartialStride + kHeadDim];
         wq[r] = (long long)b * a.n_q_heads + h * g + i;
     }
-    // Two chunks ahead: the weights of this thread's (head, token) entries and its 16 mean words of
-    // a chunk are loaded into a register slot two iterations before they are used.
-    uint32_t mv[2][16];
-    float xpv[2][2], xmv[2][2];
-    auto fetch = [&](auto slot_c, int c) {
-        constexpr int slot = decltype(slot_c)::value;
+    // mean tile staging: thread moves the 16-byte pieces tid + 256 k (row = piece / 16).
+    // value plane of this sequence: token t sits (t + (t rounded down to its block)) rows of 128 in
+    const uint16_t *vplane = (const uint16_t *)(a.layer + gm.xmean_off) + ((long long)b * gm.NB * 2 + 1) * gm.G * kHeadDim;
+    const int gmask = ~(gm.G - 1);
+    uint4 mreg[4];
+    float xpv[2], xmv[2];
+    auto fetch = [&](int c) {
 #pragma unroll
         for (int r = 0; r < 2; r++) {
             const int t = c * 64 + wt_tok;
-            xpv[slot][r] = t < T ? a.xp[wq[r] * a.tcap + t] : 0.0f;
-            xmv[slot][r] = a.xmc[wq[r] * ncap + c];
+            xpv[r] = t < T ? a.xp[wq[r] * a.tcap + t] : 0.0f;
+            xmv[r] = a.xmc[wq[r] * ncap + c];
         }
 #pragma unroll
-        for (int k = 0; k < 16; k++) {
-            const int t = c * 64 + 4 * k + tq;
-            mv[slot][k] = t < T ? *(const uint32_t *)(vplane + (long long)(t + (t & gmask)) * kHeadDim) : 0u;
+        for (int k = 0; k < 4; k++) {
+            const int p = tid + kThreads * k, t = c * 64 + (p >> 4);
+            mreg[k] = t < T ? *(const uint4 *)(vplane + (long long)(t + (t & gmask)) * kHeadDim + (p & 15) * 8) : uint4{0u, 0u, 0u, 0u};
         }
     };
-    auto step = [&](auto slot_c, int c_next) {
-        constexpr int slot = decltype(slot_c)::value;
-        __syncthreads(); // the previous chunk's weights have been used
+    v4f acc[2] = {{0.0f, 0.0f, 0.0f, 0.0f}, {0.0f, 0.0f, 0.0f, 0.0f}};
+    if (sp < chunks_total) fetch(sp);
+    for (int c = sp; c < chunks_total; c += ns) {
+        __syncthreads(); // the previous chunk's tiles have been read
 #pragma unroll
         for (int r = 0; r < 2; r++) {
             const int i = wi + 4 * r;
-            if (i < g) w[i][wt_tok] = xpv[slot][r] * exp2f(xmv[slot][r] - Msp[r]);
-        }
-        uint32_t cur[16];
-#pragma unroll
-        for (int k = 0; k < 16; k++) cur[k] = mv[slot][k];
-        if (c_next < chunks_total) fetch(slot_c, c_next);
-        __syncthreads();
-#pragma unroll
-        for (int k = 0; k < 16; k++) {
-            const float m0 = f16_val((uint16_t)(cur[k] & 0xFFFFu)), m1 = f16_val((uint16_t)(cur[k] >> 16));
-#pragma unroll
-            for (int i = 0; i < NI; i++) {
-                const float wt = w[i][4 * k + tq];
-                acc[i][0] += wt * m0;
-                acc[i][1] += wt * m1;
+            if (i < g) {
+                const float wt = xpv[r] * exp2f(xmv[r] - Msp[r]);
+                const _Float16 hi = (_Float16)wt;
+                whi[i * kWStride + wt_tok] = hi;
+                wlo[i * kWStride + wt_tok] = (_Float16)(wt - (float)hi);
             }
         }
-    };
-    const std::integral_constant<int, 0> s0;
-    const std::integral_constant<int, 1> s1;
-    if (sp < chunks_total) fetch(s0, sp);
-    if (sp + ns < chunks_total) fetch(s1, sp + ns);
-    for (int c = sp; c < chunks_total; c += 2 * ns) {
-        step(s0, c + 2 * ns);
-        if (c + ns < chunks_total) step(s1, c + 3 * ns);
-    }
 #pragma unroll
-    for (int i = 0; i < NI; i++) {
-        red[tq][i][2 * cp] = acc[i][0];
-        red[tq][i][2 * cp + 1] = acc[i][1];
+        for (int k = 0; k < 4; k++) {
+            const int p = tid + kThreads * k;
+            uint2 *dst = (uint2 *)(mvs + (p >> 4) * kMvStride + (p & 15) * 8);
+            dst[0] = uint2{mreg[k].x, mreg[k].y};
+            dst[1] = uint2{mreg[k].z, mreg[k].w};
+        }
+        if (c + ns < chunks_total) fetch(c + ns);
+        __syncthreads();
+#pragma unroll
+        for (int ks = 0; ks < 2; ks++) {
+            const v8h ahi = *(const v8h *)(whi + n * kWStride + 32 * ks + 8 * kg);
+            const v8h alo = *(const v8h *)(wlo + n * kWStride + 32 * ks + 8 * kg);
+#pragma unroll
+            for (int cc = 0; cc < 2; cc++) {
+                v8h bm;
+                const _Float16 *col = mvs + (32 * ks + 8 * kg) * kMvStride + 32 * wave + 16 * cc + n;
+#pragma unroll
+                for (int j = 0; j < 8; j++) bm[j] = col[j * kMvStride];
+                acc[cc] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ahi, bm, acc[cc], 0, 0, 0);
+                acc[cc] = __builtin_amdgcn_mfma_f32_16x16x32_f16(alo, bm, acc[cc], 0, 0, 0);
+            }
+        }
     }
-    __syncthreads();
-    for (int e = threadIdx.x; e < g * kHeadDim; e += kThreads) {
-        const int i = e >> 7, ch = e & 127;
-        const float sum = (red[0][i][ch] + red[1][i][ch]) + (red[2][i][ch] + red[3][i][ch]);
-        a.ws[((long long)(u * g + i) * ns + sp) * kPartialStride + ch] += sum;
-    }
+    // D: lane holds heads 4 kg .. 4 kg + 3 of channel 32 wave + 16 cc + n
+#pragma unroll
+    for (int cc = 0; cc < 2; cc++)
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            const int i = 4 * kg + j;
+            if (i < g) a.ws[((long long)(u * g + i) * ns + sp) * kPartialStride + 32 * wave + 16 * cc + n] += acc[cc][j];
+        }
 }
 
 } // namespace
@@ -216,12 +230,11 @@ hipError_t launch_xhead_values(const DecodeArgs &a, hipStream_t s)
 {
     if (a.n_blocks == 0) return hipSuccess;
     if (a.batch * a.n_kv_heads > 65535) return hipErrorInvalidValue;
-    dim3 grid(a.n_splits, a.batch * a.n_kv_heads);
+    const long long pairs8 = ((long long)a.batch * a.n_splits + 7) / 8;
+    if (pairs8 * 8 * a.n_kv_heads > 0x7FFFFFFF) return hipErrorInvalidValue;
+    dim3 grid((unsigned)(pairs8 * 8 * a.n_kv_heads));
     (void)hipGetLastError(); // drop any stale error left by earlier runtime calls of this thread
-    if (a.g <= 1) hipLaunchKernelGGL(xhead_values_kernel<1>, grid, dim3(kThreads), 0, s, a);
-    else if (a.g <= 2) hipLaunchKernelGGL(xhead_values_kernel<2>, grid, dim3(kThreads), 0, s, a);
-    else if (a.g <= 4) hipLaunchKernelGGL(xhead_values_kernel<4>, grid, dim3(kThreads), 0, s, a);
-    else hipLaunchKernelGGL(xhead_values_kernel<8>, grid, dim3(kThreads), 0, s, a);
+    hipLaunchKernelGGL(xhead_values_kernel, grid, dim3(kThreads), 0, s, a);
     return note_launch(hipGetLastError());
 }
 
