@@ -264,6 +264,58 @@ def test_full_cache_shape_sampled_units(kv, oracle, decode_path):
         assert err <= 2e-3
 
 
+@pytest.mark.parametrize("decode_path", [0], indirect=True, ids=["auto"])
+def test_full_cache_shape_cross_head_sampled_units(kv, oracle, decode_path):
+    """The same launch configuration with the mean over the kv heads (Eq. 1-2): one 4-bit layer,
+    records, mean plane and attention of sampled sequences against the oracle."""
+    import torch
+
+    print("case full_cache_shape_cross_head", flush=True)
+    B, Hq, Hkv, d, G, T = 16, 32, 8, 128, 32, 32768 + 13
+    cfg = kv.make_config(1, B, Hq, Hkv, d, 32768 + 64, G, G, G, kv.KV_BF16, kv.KV_MEAN_CROSS_HEAD, [4], [4])
+    gpu = kv.KVCache(cfg, zero=False)
+    sample = (3, 15)
+    ocfg = oracle.OracleConfig(1, len(sample), Hq, Hkv, d, 32768 + 64, G, G, G, BF16, CROSS, [4], [4])
+    orc = oracle.OracleCache(ocfg)
+    host_k, host_v = [], []
+    for t0 in range(0, T, 8192):
+        n = min(8192, T - t0)
+        k, v = synth.make_kv_torch(950 + t0 // 8192, B, n, Hkv, d, BF16, "cuda:0")
+        gpu.append(0, k, v)
+        host_k.append(k[list(sample)].cpu())
+        host_v.append(v[list(sample)].cpu())
+    k16 = torch.cat(host_k, 1).view(torch.int16).numpy().view(np.uint16)
+    v16 = torch.cat(host_v, 1).view(torch.int16).numpy().view(np.uint16)
+    orc.append(0, k16, v16)
+    torch.cuda.synchronize()
+    assert gpu.lengths(0) == (orc.packed_len(0), orc.resid_len(0)) == (32768, 13)
+    lay = kv.kv_cache_describe(gpu.handle, 0)
+    img = orc.layer_image(0)
+    NB, n_rec = (32768 + 64) // G, 32768 // G
+    dev = gpu.layers[0]
+    olay = oracle.tada.record_layout(ocfg, 0)
+    plane = 2 * G * d * 2  # bytes of one block's K and V mean rows
+    for si, b in enumerate(sample):
+        for h in range(Hkv):
+            g0 = ((b * Hkv + h) * NB) * lay.rec_bytes
+            o0 = ((si * Hkv + h) * NB) * lay.rec_bytes
+            got = dev[g0:g0 + n_rec * lay.rec_bytes].cpu().numpy()
+            m = img["valid"][o0:o0 + n_rec * lay.rec_bytes]
+            assert np.array_equal(got[m], img["bytes"][o0:o0 + n_rec * lay.rec_bytes][m]), (b, h)
+        g0, o0 = lay.xmean_off + b * NB * plane, olay["xmean_off"] + si * NB * plane
+        got = dev[g0:g0 + n_rec * plane].cpu().numpy()
+        assert img["valid"][o0:o0 + n_rec * plane].all()
+        assert np.array_equal(got, img["bytes"][o0:o0 + n_rec * plane]), ("mean plane", b)
+    q = synth.make_q_torch(79, B, Hq, d, BF16, "cuda:0")
+    out = gpu.attend(0, q)
+    torch.cuda.synchronize()
+    q16 = q[list(sample)].cpu().view(torch.int16).numpy().view(np.uint16)
+    want = orc.attend(0, q16)
+    err = float(np.max(np.abs(out[list(sample)].cpu().numpy().astype(np.float64) - want)))
+    print("  splits=%d attention max-abs error %.3e" % (kv.kv_decode_splits(gpu.handle, 0), err), flush=True)
+    assert err <= 2e-3
+
+
 # ------------------------------------------------------------------ cross-head mean (Eq. 1-2 as printed)
 
 
