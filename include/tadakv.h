@@ -24,7 +24,11 @@
  *     NULL = the default stream) and ordered by it.
  *   - All arguments are validated on the host before anything is enqueued; on error nothing has
  *     been enqueued and the cache is unchanged.
- *   - Sequence lengths are tracked on the host and are uniform across the batch.
+ *   - Sequence lengths are tracked on the host, per sequence.  The batch-wide calls move all
+ *     sequences together; kv_quant_append_seq / kv_cache_reset_seq let one sequence join or leave
+ *     (a new request taking over a slot of the batch: Sec. 3.3's buffer and blocks are per sequence),
+ *     after which the lengths differ and the decode kernels take each sequence's own counts.
+ *     Caches of more than 64 sequences must keep their lengths equal.
  *   - One cache must be used by one thread at a time.
  *   - head_dim must be 128.
  */
@@ -126,8 +130,14 @@ kv_status kv_cache_destroy(kv_cache *cache);
 /* Forget the contents of one layer (layer < 0: all layers).  Host bookkeeping only. */
 kv_status kv_cache_reset(kv_cache *cache, int32_t layer);
 
-/* Current lengths of a layer: tokens in packed blocks, tokens in the raw residual. */
+/* Forget the contents of one sequence in one layer (layer < 0: all layers): its slot is free for
+ * a new request.  Host bookkeeping only.  KV_E_BAD_CONFIG for a sequence index out of range. */
+kv_status kv_cache_reset_seq(kv_cache *cache, int32_t layer, int32_t seq);
+
+/* Current lengths of a layer: tokens in packed blocks, tokens in the raw residual.
+ * kv_cache_len answers for the whole batch and returns KV_E_UNSUPPORTED while the sequences differ. */
 kv_status kv_cache_len(const kv_cache *cache, int32_t layer, int32_t *packed, int32_t *resid);
+kv_status kv_cache_len_seq(const kv_cache *cache, int32_t layer, int32_t seq, int32_t *packed, int32_t *resid);
 
 /* Offsets of a layer's buffer, so raw bytes can be compared with an independent packer. */
 kv_status kv_cache_describe(const kv_cache *cache, int32_t layer, kv_layer_layout *out);
@@ -143,6 +153,13 @@ kv_status kv_cache_describe(const kv_cache *cache, int32_t layer, kv_layer_layou
 kv_status kv_quant_append(kv_cache *cache, int32_t layer, const void *k_new, const void *v_new,
                           int32_t n_new, int64_t stride_b, int64_t stride_t, int64_t stride_h,
                           void *stream);
+
+/* kv_quant_append for ONE sequence of the batch (a request's prompt entering its slot; NEXT to the
+ * uniform-length workloads of the paper this is what serving needs).  k_new, v_new: rows of that
+ * sequence only, element (t,h,c) at t*stride_t + h*stride_h + c.  Same semantics and errors as
+ * kv_quant_append; KV_E_BAD_CONFIG for a sequence index out of range. */
+kv_status kv_quant_append_seq(kv_cache *cache, int32_t layer, int32_t seq, const void *k_new, const void *v_new,
+                              int32_t n_new, int64_t stride_t, int64_t stride_h, void *stream);
 
 /* kv_quant_append with the rotary position embedding of the keys fused in (Algorithm 1 step 5,
  * "RoPECompress"; Sec. 3.4 and App. A: the rotation is the last computation before the cache
@@ -169,7 +186,8 @@ kv_status kv_rope_quant_append(kv_cache *cache, int32_t layer, const void *k_pre
  *   q    : device, [batch, n_q_heads, head_dim], 16-bit cfg.dtype, contiguous, post-RoPE
  *   out  : device, [batch, n_q_heads, head_dim] float32, contiguous
  *   workspace : device, at least kv_workspace_bytes, 256-byte aligned; contents are scratch.
- * Scores are scaled by 1/sqrt(head_dim).  KV_E_EMPTY if the layer holds no token. */
+ * Scores are scaled by 1/sqrt(head_dim).  KV_E_EMPTY if the layer holds no token at all; a sequence
+ * without tokens next to others that have some gets zeros. */
 kv_status kv_decode_attn(const kv_cache *cache, int32_t layer, const void *q, float *out,
                          void *workspace, size_t workspace_bytes, void *stream);
 

@@ -250,11 +250,18 @@ class OracleCache:
             self.layers.append(L)
 
     # -- lengths
-    def packed_len(self, layer: int) -> int:
-        return len(self.layers[layer].k_blocks[0]) * self.cfg.group_tokens
+    def packed_len(self, layer: int, b: int = 0) -> int:
+        return len(self.layers[layer].k_blocks[b]) * self.cfg.group_tokens
 
-    def resid_len(self, layer: int) -> int:
-        return self.layers[layer].k_resid[0].shape[0]
+    def resid_len(self, layer: int, b: int = 0) -> int:
+        return self.layers[layer].k_resid[b].shape[0]
+
+    def reset_seq(self, layer: int, b: int) -> None:
+        """Sequence b leaves: its blocks and residual buffer (Sec. 3.3: both are per sequence) are dropped."""
+        cfg, L = self.cfg, self.layers[layer]
+        L.k_blocks[b], L.v_blocks[b] = [], []
+        L.k_resid[b] = np.zeros((0, cfg.n_kv_heads, cfg.head_dim), dtype=np.uint16)
+        L.v_resid[b] = np.zeros((0, cfg.n_kv_heads, cfg.head_dim), dtype=np.uint16)
 
     # -- append
     def _flush(self, layer: int, b: int) -> None:
@@ -285,17 +292,28 @@ class OracleCache:
         if rope_tables is not None:
             cos, sin, pairing = rope_tables
             k_new = np.stack([rope(k_new[b], cfg.dtype, cos, sin, pairing) for b in range(cfg.batch)])
-        if self.packed_len(layer) + self.resid_len(layer) + n > cfg.max_tokens:
+        if any(self.packed_len(layer, b) + self.resid_len(layer, b) + n > cfg.max_tokens for b in range(cfg.batch)):
             raise OverflowError("append exceeds max_tokens")
         for b in range(cfg.batch):
-            done = 0
-            while done < n:
-                take = min(cfg.resid_cap - L.k_resid[b].shape[0], n - done)
-                L.k_resid[b] = np.concatenate([L.k_resid[b], k_new[b, done:done + take]], axis=0)
-                L.v_resid[b] = np.concatenate([L.v_resid[b], v_new[b, done:done + take]], axis=0)
-                done += take
-                if L.k_resid[b].shape[0] == cfg.resid_cap:
-                    self._flush(layer, b)
+            self._append_one(layer, b, k_new[b], v_new[b])
+
+    def append_seq(self, layer: int, b: int, k_new: np.ndarray, v_new: np.ndarray) -> None:
+        """Tokens of one sequence only: k_new, v_new uint16 [n_new, H, d]."""
+        if self.packed_len(layer, b) + self.resid_len(layer, b) + k_new.shape[0] > self.cfg.max_tokens:
+            raise OverflowError("append exceeds max_tokens")
+        self._append_one(layer, b, k_new, v_new)
+
+    def _append_one(self, layer: int, b: int, k_new: np.ndarray, v_new: np.ndarray) -> None:
+        cfg, L = self.cfg, self.layers[layer]
+        n = k_new.shape[0]
+        done = 0
+        while done < n:
+            take = min(cfg.resid_cap - L.k_resid[b].shape[0], n - done)
+            L.k_resid[b] = np.concatenate([L.k_resid[b], k_new[done:done + take]], axis=0)
+            L.v_resid[b] = np.concatenate([L.v_resid[b], v_new[done:done + take]], axis=0)
+            done += take
+            if L.k_resid[b].shape[0] == cfg.resid_cap:
+                self._flush(layer, b)
 
     # -- reconstruction and attention
     def reconstruct(self, layer: int, b: int, which: int) -> np.ndarray:
@@ -330,7 +348,10 @@ class OracleCache:
             kh = self.reconstruct(layer, b, K)
             vh = self.reconstruct(layer, b, V)
             for h in heads:
-                out[b, h * g:(h + 1) * g] = attention(qf[b, h * g:(h + 1) * g], kh[h], vh[h])
+                if kh.shape[1] == 0:  # a sequence that holds no token: nothing to attend to, zeros
+                    out[b, h * g:(h + 1) * g] = 0.0
+                else:
+                    out[b, h * g:(h + 1) * g] = attention(qf[b, h * g:(h + 1) * g], kh[h], vh[h])
         return out
 
     # -- storage format

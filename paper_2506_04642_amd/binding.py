@@ -29,7 +29,7 @@ KV_MEAN_CHANNEL_BLOCK, KV_MEAN_CROSS_HEAD, KV_MEAN_NONE = 0, 1, 2
 
 EXPORTS = [
     "kv_cache_bytes", "kv_workspace_bytes", "kv_cache_create", "kv_cache_destroy", "kv_cache_reset",
-    "kv_cache_len", "kv_cache_describe", "kv_quant_append", "kv_rope_quant_append", "kv_append_decode_attn", "kv_append_decode_attn_split", "kv_decode_attn", "kv_decode_attn_split",
+    "kv_cache_len", "kv_cache_len_seq", "kv_cache_reset_seq", "kv_cache_describe", "kv_quant_append", "kv_quant_append_seq", "kv_rope_quant_append", "kv_append_decode_attn", "kv_append_decode_attn_split", "kv_decode_attn", "kv_decode_attn_split",
     "kv_decode_attn_merge", "kv_decode_splits", "kv_decode_bytes", "kv_set_decode_path", "kv_set_decode_splits", "kv_strerror", "kv_last_hip_error",
 ]
 
@@ -63,6 +63,9 @@ _lib.kv_cache_create.argtypes = [_cfgp, ctypes.POINTER(_vp), ctypes.POINTER(_vp)
 _lib.kv_cache_destroy.argtypes = [_vp]
 _lib.kv_cache_reset.argtypes = [_vp, _i32]
 _lib.kv_cache_len.argtypes = [_vp, _i32, ctypes.POINTER(_i32), ctypes.POINTER(_i32)]
+_lib.kv_cache_len_seq.argtypes = [_vp, _i32, _i32, ctypes.POINTER(_i32), ctypes.POINTER(_i32)]
+_lib.kv_cache_reset_seq.argtypes = [_vp, _i32, _i32]
+_lib.kv_quant_append_seq.argtypes = [_vp, _i32, _i32, _vp, _vp, _i32, _i64, _i64, _vp]
 _lib.kv_cache_describe.argtypes = [_vp, _i32, ctypes.POINTER(kv_layer_layout)]
 _lib.kv_quant_append.argtypes = [_vp, _i32, _vp, _vp, _i32, _i64, _i64, _i64, _vp]
 _lib.kv_rope_quant_append.argtypes = [_vp, _i32, _vp, _vp, _i32, _i64, _i64, _i64, _vp, _vp, _i32, _vp]
@@ -152,6 +155,22 @@ def kv_cache_len(cache: int, layer: int):
     p, r = _i32(), _i32()
     _check(_lib.kv_cache_len(cache, layer, ctypes.byref(p), ctypes.byref(r)), "kv_cache_len")
     return p.value, r.value
+
+
+def kv_cache_len_seq(cache: int, layer: int, seq: int):
+    p, r = _i32(), _i32()
+    _check(_lib.kv_cache_len_seq(cache, layer, seq, ctypes.byref(p), ctypes.byref(r)), "kv_cache_len_seq")
+    return p.value, r.value
+
+
+def kv_cache_reset_seq(cache: int, layer: int, seq: int) -> None:
+    _check(_lib.kv_cache_reset_seq(cache, layer, seq), "kv_cache_reset_seq")
+
+
+def kv_quant_append_seq(cache: int, layer: int, seq: int, k_ptr: int, v_ptr: int, n_new: int, stride_t: int,
+                        stride_h: int, stream: int = 0) -> None:
+    _check(_lib.kv_quant_append_seq(cache, layer, seq, k_ptr, v_ptr, n_new, stride_t, stride_h, stream),
+           "kv_quant_append_seq")
 
 
 def kv_cache_describe(cache: int, layer: int) -> kv_layer_layout:
@@ -262,6 +281,13 @@ class KVCache:
         kv_quant_append(self.handle, layer, k_new.data_ptr(), v_new.data_ptr(), k_new.shape[1],
                         k_new.stride(0), k_new.stride(1), k_new.stride(2), self._stream())
 
+    def append_seq(self, layer: int, seq: int, k_new, v_new) -> None:
+        """k_new, v_new: device tensors [n_new, Hkv, d] of one sequence of the batch."""
+        assert k_new.shape == v_new.shape and k_new.stride() == v_new.stride()
+        assert k_new.stride(2) == 1 and k_new.element_size() == 2
+        kv_quant_append_seq(self.handle, layer, seq, k_new.data_ptr(), v_new.data_ptr(), k_new.shape[0],
+                            k_new.stride(0), k_new.stride(1), self._stream())
+
     def append_rope(self, layer: int, k_pre, v_new, cos, sin, pairing: int = KV_ROPE_HALF) -> None:
         """As append, with pre-rotation keys and float32 device tables cos, sin [n_new, d/2]."""
         torch = self.torch
@@ -299,5 +325,5 @@ class KVCache:
                               self.ws_bytes, self._stream())
         return out
 
-    def lengths(self, layer: int):
-        return kv_cache_len(self.handle, layer)
+    def lengths(self, layer: int, seq: Optional[int] = None):
+        return kv_cache_len(self.handle, layer) if seq is None else kv_cache_len_seq(self.handle, layer, seq)

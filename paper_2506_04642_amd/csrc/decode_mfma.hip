@@ -257,8 +257,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
     // ---- chunks of this split: the splits of a unit interleave chunk by chunk (split sp, wave w
     // takes chunks sp + n_splits * (w + NW * k)), so that together they sweep the unit's records
     // front to back as one moving window instead of as n_splits far-apart streams
-    const int b_end = a.n_blocks;
-    const int chunks_total = (a.n_blocks + NBC - 1) / NBC;
+    const int b_end = seq_blocks(a, b), r_seq = seq_resid(a, b); // this sequence's packed blocks and raw tokens
+    const int chunks_total = (b_end + NBC - 1) / NBC;
     const int ns = a.n_splits;
     // local chunk j of this split is the unit's chunk sp + ns * j
     const int n_chunks = sp < chunks_total ? (chunks_total - sp + ns - 1) / ns : 0;
@@ -627,7 +627,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
     if (B != 8) __builtin_amdgcn_s_setprio(0);
 
     // ---- raw residual tokens (Sec. 3.3): wave 0 of the split that is next in turn
-    const bool has_resid = a.r > 0 && sp == chunks_total % ns;
+    const bool has_resid = r_seq > 0 && sp == chunks_total % ns;
     if (has_resid) {
         __syncthreads(); // every wave is out of its main loop; wave 0 may take all of LDS
         if (wave == 0) {
@@ -650,9 +650,9 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
             const unsigned char *vr = a.layer + gm.v_resid_off + (long long)u * gm.R * 256;
             // a token appended by this very call: read from the caller's rows and stored in the cache here
             const long long fresh_off = (long long)b * a.fresh_stride_b + (long long)h * a.fresh_stride_h;
-            const int t_fresh = a.k_fresh ? a.r - 1 : -1;
-            for (int t0 = 0; t0 < a.r; t0 += 32) {
-                const int nt = a.r - t0 < 32 ? a.r - t0 : 32;
+            const int t_fresh = a.k_fresh ? r_seq - 1 : -1;
+            for (int t0 = 0; t0 < r_seq; t0 += 32) {
+                const int nt = r_seq - t0 < 32 ? r_seq - t0 : 32;
                 wave_lds_fence();
                 for (int i = lane; i < nt * 16; i += 64) {
                     const int t = i >> 4, ch = i & 15;

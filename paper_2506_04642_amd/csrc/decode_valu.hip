@@ -291,11 +291,12 @@ template <int KB, int VB> __global__ __launch_bounds__(kThreads) void decode_spl
 #pragma unroll
     for (int k = 0; k < kMaxGroupQ / 2; k++) acc[k] = 0.0f;
 
-    const int work = a.n_blocks + (a.r > 0 ? 1 : 0);
+    const int nb_seq = seq_blocks(a, b), r_seq = seq_resid(a, b); // this sequence's packed blocks and raw tokens
+    const int work = nb_seq + (r_seq > 0 ? 1 : 0);
     const int w0 = sp * a.blocks_per_split;
     int w1 = w0 + a.blocks_per_split;
     if (w1 > work) w1 = work;
-    const int b_end = w1 < a.n_blocks ? w1 : a.n_blocks;
+    const int b_end = w1 < nb_seq ? w1 : nb_seq;
 
     for (int j = w0; j < b_end; j++) {
         const unsigned char *rec = a.layer + ((long long)u * gm.NB + j) * gm.rec_bytes;
@@ -313,11 +314,11 @@ template <int KB, int VB> __global__ __launch_bounds__(kThreads) void decode_spl
                                   xm ? xm + G * kHeadDim * 2 : nullptr, acc);
         }
     }
-    if (w1 > a.n_blocks && a.r > 0) {
+    if (w0 < w1 && w1 > nb_seq && r_seq > 0) {
         const unsigned char *kr = a.layer + gm.k_resid_off + (long long)u * gm.R * 256;
         const unsigned char *vr = a.layer + gm.v_resid_off + (long long)u * gm.R * 256;
-        for (int t0 = 0; t0 < a.r; t0 += 32) {
-            const int n = a.r - t0 < 32 ? a.r - t0 : 32;
+        for (int t0 = 0; t0 < r_seq; t0 += 32) {
+            const int n = r_seq - t0 < 32 ? r_seq - t0 : 32;
             process_block<16, 16>(a, sm, n, kr + t0 * 256, nullptr, nullptr, nullptr, vr + t0 * 256,
                                   nullptr, nullptr, nullptr, nullptr, acc);
         }
@@ -357,7 +358,7 @@ __global__ __launch_bounds__(256) void merge_kernel(DecodeArgs a)
 #pragma unroll 4
     for (int j = 0; j < ns; j++) {
         const float *pj = base + j * kPartialStride;
-        const float w = exp2f(pj[kHeadDim] - M);
+        const float w = pj[kHeadDim] == -INFINITY ? 0.0f : exp2f(pj[kHeadDim] - M);
         const float2 o = *(const float2 *)(pj + 2 * lane);
         n0 += o.x * w;
         n1 += o.y * w;
@@ -365,8 +366,9 @@ __global__ __launch_bounds__(256) void merge_kernel(DecodeArgs a)
     }
     const int b = u / a.n_kv_heads, h = u % a.n_kv_heads;
     float2 r;
-    r.x = n0 / den;
-    r.y = n1 / den;
+    // a sequence that holds no token (every split empty, M == -inf) gives zeros
+    r.x = M == -INFINITY ? 0.0f : n0 / den;
+    r.y = M == -INFINITY ? 0.0f : n1 / den;
     *(float2 *)(a.out + ((long long)b * a.n_q_heads + h * a.g + i) * kHeadDim + 2 * lane) = r;
 }
 

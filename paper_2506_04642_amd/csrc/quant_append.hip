@@ -143,7 +143,7 @@ __device__ __forceinline__ uint32_t quant_code(float dev, float s, float rs, flo
 // [old residual (r_old tokens) | new tokens] for unit (b, h).
 __device__ __forceinline__ const uint16_t *src_row(const AppendArgs &a, int which, int b, int h, int ci)
 {
-    const int u = b * a.n_kv_heads + h;
+    const int u = (a.b0 + b) * a.n_kv_heads + h; // unit in the cache
     if (ci < a.r_old) {
         const long long off = (which == 0 ? a.geom.k_resid_off : a.geom.v_resid_off) +
                               ((long long)u * a.geom.R + ci) * (kHeadDim * 2);
@@ -256,7 +256,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu((G == 
         const int which = side_of(it), u = (it >> 1) % U, fb = (it >> 1) / U;
         const int b = u / a.n_kv_heads;
         const int bits = which == 0 ? gm.k_bits : gm.v_bits;
-        unsigned char *rec = a.layer + ((long long)u * gm.NB + (a.first_block + fb)) * gm.rec_bytes;
+        unsigned char *rec = a.layer + ((long long)(a.b0 * a.n_kv_heads + u) * gm.NB + (a.first_block + fb)) * gm.rec_bytes;
         unsigned char *codes_out = rec + (which == 0 ? gm.k_codes : gm.v_codes);
 
         if (bits == 16 && !(ROPE && which == 0)) {
@@ -355,7 +355,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu((G == 
             // xhead_mean_kernel just before this launch
             const uint16_t *xm = gm.mean_mode == 1
                                      ? (const uint16_t *)(a.layer + gm.xmean_off) +
-                                           (((long long)b * gm.NB + (a.first_block + fb)) * 2 + which) * G * kHeadDim
+                                           (((long long)(a.b0 + b) * gm.NB + (a.first_block + fb)) * 2 + which) * G * kHeadDim
                                      : nullptr;
             float dv[HT];
 #pragma unroll
@@ -585,7 +585,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ?
         // keys and values cost differently: a worker alternates between them (workers is even)
         const int which = (it ^ (it / workers)) & 1, u = (it >> 1) % U, fb = (it >> 1) / U;
         const int b = u / a.n_kv_heads, h = u % a.n_kv_heads;
-        unsigned char *rec = a.layer + ((long long)u * gm.NB + (a.first_block + fb)) * gm.rec_bytes;
+        unsigned char *rec = a.layer + ((long long)(a.b0 * a.n_kv_heads + u) * gm.NB + (a.first_block + fb)) * gm.rec_bytes;
         const int base_off = which == 0 ? gm.k_codes : gm.v_codes; // start of this item's part of the record
         unsigned char *codes_out = img;
 
@@ -651,7 +651,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ?
         } else if (gm.mean_mode == 1) {
             // mean over the kv heads per (token, channel), written by xhead_mean_kernel before this launch
             const uint16_t *xm = (const uint16_t *)(a.layer + gm.xmean_off) +
-                                 (((long long)b * gm.NB + (a.first_block + fb)) * 2 + which) * G * kHeadDim;
+                                 (((long long)(a.b0 + b) * gm.NB + (a.first_block + fb)) * 2 + which) * G * kHeadDim;
 #pragma unroll
             for (int j = 0; j < 8; j++) {
                 const uint4 mv = *(const uint4 *)(xm + (8 * tg + j) * kHeadDim + c8 * 8);
@@ -849,7 +849,7 @@ __global__ __launch_bounds__(kThreads) void xhead_mean_kernel(AppendArgs a)
     const int bits = which == 0 ? gm.k_bits : gm.v_bits;
     if (bits == 16) return;
     uint16_t *dst = (uint16_t *)(a.layer + gm.xmean_off) +
-                    (((long long)b * gm.NB + (a.first_block + fb)) * 2 + which) * G * kHeadDim;
+                    (((long long)(a.b0 + b) * gm.NB + (a.first_block + fb)) * 2 + which) * G * kHeadDim;
     for (int i = threadIdx.x; i < G * (kHeadDim / 2); i += kThreads) {
         const int t = i / (kHeadDim / 2), cp = i % (kHeadDim / 2);
         float acc0 = 0.0f, acc1 = 0.0f;
@@ -884,7 +884,7 @@ __global__ __launch_bounds__(kThreads) void resid_copy_kernel(AppendArgs a)
     const uint16_t *src = base + (long long)b * a.stride_b + (long long)(a.copy_src + i) * a.stride_t +
                           (long long)h * a.stride_h + ch * 8;
     const long long off = (which == 0 ? a.geom.k_resid_off : a.geom.v_resid_off) +
-                          ((long long)u * a.geom.R + a.copy_dst + i) * (kHeadDim * 2) + ch * 16;
+                          ((long long)(a.b0 * a.n_kv_heads + u) * a.geom.R + a.copy_dst + i) * (kHeadDim * 2) + ch * 16;
     if (a.rope != 0 && which == 0) {
         const uint16_t *row = src - ch * 8;
         const int tn = a.copy_src + i;

@@ -14,7 +14,17 @@ struct kv_cache {
     std::vector<uint8_t> k_bits, v_bits;
     std::vector<unsigned char *> layers;
     std::vector<LayerGeom> geom;
-    std::vector<int> packed, resid; // tokens
+    std::vector<int> packed, resid; // tokens, [layer][sequence]
+    int &P(int layer, int b) { return packed[(size_t)layer * cfg.batch + b]; }
+    int &R(int layer, int b) { return resid[(size_t)layer * cfg.batch + b]; }
+    int P(int layer, int b) const { return packed[(size_t)layer * cfg.batch + b]; }
+    int R(int layer, int b) const { return resid[(size_t)layer * cfg.batch + b]; }
+    bool uniform(int layer) const
+    {
+        for (int b = 1; b < cfg.batch; b++)
+            if (P(layer, b) != P(layer, 0) || R(layer, b) != R(layer, 0)) return false;
+        return true;
+    }
     int decode_path = 0;
     int forced_splits = 0;
     size_t xhead_off = 0, xhead_bytes = 0; // cross-head mean: where its arrays start in the workspace, total size
@@ -169,9 +179,22 @@ kv_status fill_decode(const kv_cache *k, int layer, DecodeArgs *a)
     a->n_q_heads = c.n_q_heads;
     a->batch = c.batch;
     a->g = c.n_q_heads / c.n_kv_heads;
-    a->n_blocks = k->packed[layer] / c.group_tokens;
-    a->r = k->resid[layer];
     a->tcap = c.max_tokens;
+    // sequences may differ in length: the launch is planned for the longest, the kernels take
+    // each sequence's own counts from the table
+    a->ragged = k->uniform(layer) ? 0 : 1;
+    if (a->ragged && c.batch > kMaxRaggedBatch) return KV_E_UNSUPPORTED;
+    a->n_blocks = 0;
+    a->r = 0;
+    for (int b = 0; b < c.batch; b++) {
+        const int nb = k->P(layer, b) / c.group_tokens, r = k->R(layer, b);
+        if (nb > a->n_blocks) a->n_blocks = nb;
+        if (r > a->r) a->r = r;
+        if (a->ragged) {
+            a->nb_seq[b] = nb;
+            a->r_seq[b] = r;
+        }
+    }
     if (a->n_blocks == 0 && a->r == 0) return KV_E_EMPTY;
     choose_splits(c, a->n_blocks, a->r, &a->n_splits, &a->blocks_per_split);
     if (k->decode_path != 1 && decode_mfma_supported(*a)) {
@@ -287,8 +310,8 @@ kv_status kv_cache_create(const kv_config *cfg, void *const *layer_dev_ptrs, kv_
         k->layers.push_back((unsigned char *)layer_dev_ptrs[l]);
         k->geom.push_back(make_geom(k->cfg, l));
     }
-    k->packed.assign(cfg->n_layers, 0);
-    k->resid.assign(cfg->n_layers, 0);
+    k->packed.assign((size_t)cfg->n_layers * cfg->batch, 0);
+    k->resid.assign((size_t)cfg->n_layers * cfg->batch, 0);
     if (cfg->mean_mode == KV_MEAN_CROSS_HEAD) {
         k->xhead_off = xhead_offset(k->cfg);
         k->xhead_bytes = xhead_total(k->cfg);
@@ -309,7 +332,29 @@ kv_status kv_cache_reset(kv_cache *cache, int32_t layer)
     if (!cache) return KV_E_NULL;
     if (layer >= cache->cfg.n_layers) return KV_E_BAD_LAYER;
     for (int l = 0; l < cache->cfg.n_layers; l++)
-        if (layer < 0 || l == layer) cache->packed[l] = cache->resid[l] = 0;
+        if (layer < 0 || l == layer)
+            for (int b = 0; b < cache->cfg.batch; b++) cache->P(l, b) = cache->R(l, b) = 0;
+    return KV_OK;
+}
+
+kv_status kv_cache_reset_seq(kv_cache *cache, int32_t layer, int32_t seq)
+{
+    if (!cache) return KV_E_NULL;
+    if (layer >= cache->cfg.n_layers) return KV_E_BAD_LAYER;
+    if (seq < 0 || seq >= cache->cfg.batch) return KV_E_BAD_CONFIG;
+    for (int l = 0; l < cache->cfg.n_layers; l++)
+        if (layer < 0 || l == layer) cache->P(l, seq) = cache->R(l, seq) = 0;
+    return KV_OK;
+}
+
+kv_status kv_cache_len_seq(const kv_cache *cache, int32_t layer, int32_t seq, int32_t *packed, int32_t *resid)
+{
+    kv_status st = layer_ok(cache, layer);
+    if (st != KV_OK) return st;
+    if (!packed || !resid) return KV_E_NULL;
+    if (seq < 0 || seq >= cache->cfg.batch) return KV_E_BAD_CONFIG;
+    *packed = cache->P(layer, seq);
+    *resid = cache->R(layer, seq);
     return KV_OK;
 }
 
@@ -318,8 +363,9 @@ kv_status kv_cache_len(const kv_cache *cache, int32_t layer, int32_t *packed, in
     kv_status st = layer_ok(cache, layer);
     if (st != KV_OK) return st;
     if (!packed || !resid) return KV_E_NULL;
-    *packed = cache->packed[layer];
-    *resid = cache->resid[layer];
+    if (!cache->uniform(layer)) return KV_E_UNSUPPORTED; // the sequences differ: ask per sequence
+    *packed = cache->P(layer, 0);
+    *resid = cache->R(layer, 0);
     return KV_OK;
 }
 
@@ -347,7 +393,10 @@ kv_status kv_cache_describe(const kv_cache *cache, int32_t layer, kv_layer_layou
 }
 
 // rope: 0 none, 1 pairs (i, i + d/2), 2 pairs (2i, 2i + 1)
-static kv_status append_impl(kv_cache *cache, int32_t layer, const void *k_new, const void *v_new,
+// Sequences seq0 .. seq0 + n_seq - 1 of the cache each take n_new tokens; input row (b, t, h) of
+// the run is at b*stride_b + t*stride_t + h*stride_h from k_new / v_new.  Runs of sequences that
+// hold the same number of tokens go into one launch.
+static kv_status append_impl(kv_cache *cache, int32_t layer, int seq0, int n_seq, const void *k_new, const void *v_new,
                              int32_t n_new, int64_t stride_b, int64_t stride_t, int64_t stride_h,
                              int rope, const float *rope_cos, const float *rope_sin, void *stream)
 {
@@ -364,42 +413,50 @@ static kv_status append_impl(kv_cache *cache, int32_t layer, const void *k_new, 
         if (!rope_cos || !rope_sin) return KV_E_NULL;
         if (((uintptr_t)rope_cos % 16) || ((uintptr_t)rope_sin % 16)) return KV_E_ALIGN;
     }
-    const long long have = (long long)cache->packed[layer] + cache->resid[layer];
-    if (have + n_new > c.max_tokens) return KV_E_CAPACITY;
+    for (int b = seq0; b < seq0 + n_seq; b++)
+        if ((long long)cache->P(layer, b) + cache->R(layer, b) + n_new > c.max_tokens) return KV_E_CAPACITY;
     const int G = c.group_tokens, R = c.resid_cap;
-    const int r_old = cache->resid[layer];
-    const long long total = (long long)r_old + n_new;
-    const long long n_flush_tok = total / R * R;
-    AppendArgs a{};
-    a.geom = cache->geom[layer];
-    a.layer = cache->layers[layer];
-    a.k_new = (const uint16_t *)k_new;
-    a.v_new = (const uint16_t *)v_new;
-    a.stride_b = stride_b;
-    a.stride_t = stride_t;
-    a.stride_h = stride_h;
-    a.n_kv_heads = c.n_kv_heads;
-    a.batch = c.batch;
-    a.r_old = r_old;
-    a.first_block = cache->packed[layer] / G;
-    a.rope = rope;
-    a.rope_cos = rope_cos;
-    a.rope_sin = rope_sin;
-    a.n_flush_blocks = (int)(n_flush_tok / G);
-    if (n_flush_tok > 0) {
-        a.copy_src = (int)(n_flush_tok - r_old);
-        a.copy_dst = 0;
-        a.copy_n = (int)(total - n_flush_tok);
-    } else {
-        a.copy_src = 0;
-        a.copy_dst = r_old;
-        a.copy_n = n_new;
-    }
     hipStream_t s = (hipStream_t)stream;
-    if (a.n_flush_blocks > 0 && launch_flush(a, s) != hipSuccess) return KV_E_HIP;
-    if (a.copy_n > 0 && launch_resid_copy(a, s) != hipSuccess) return KV_E_HIP;
-    cache->packed[layer] += (int)n_flush_tok;
-    cache->resid[layer] = (int)(total - n_flush_tok);
+    for (int b0 = seq0; b0 < seq0 + n_seq;) {
+        int b1 = b0 + 1;
+        while (b1 < seq0 + n_seq && cache->P(layer, b1) == cache->P(layer, b0) && cache->R(layer, b1) == cache->R(layer, b0)) b1++;
+        const int r_old = cache->R(layer, b0);
+        const long long total = (long long)r_old + n_new;
+        const long long n_flush_tok = total / R * R;
+        AppendArgs a{};
+        a.geom = cache->geom[layer];
+        a.layer = cache->layers[layer];
+        a.k_new = (const uint16_t *)k_new + (long long)(b0 - seq0) * stride_b;
+        a.v_new = (const uint16_t *)v_new + (long long)(b0 - seq0) * stride_b;
+        a.stride_b = stride_b;
+        a.stride_t = stride_t;
+        a.stride_h = stride_h;
+        a.n_kv_heads = c.n_kv_heads;
+        a.batch = b1 - b0;
+        a.b0 = b0;
+        a.r_old = r_old;
+        a.first_block = cache->P(layer, b0) / G;
+        a.rope = rope;
+        a.rope_cos = rope_cos;
+        a.rope_sin = rope_sin;
+        a.n_flush_blocks = (int)(n_flush_tok / G);
+        if (n_flush_tok > 0) {
+            a.copy_src = (int)(n_flush_tok - r_old);
+            a.copy_dst = 0;
+            a.copy_n = (int)(total - n_flush_tok);
+        } else {
+            a.copy_src = 0;
+            a.copy_dst = r_old;
+            a.copy_n = n_new;
+        }
+        if (a.n_flush_blocks > 0 && launch_flush(a, s) != hipSuccess) return KV_E_HIP;
+        if (a.copy_n > 0 && launch_resid_copy(a, s) != hipSuccess) return KV_E_HIP;
+        for (int b = b0; b < b1; b++) {
+            cache->P(layer, b) += (int)n_flush_tok;
+            cache->R(layer, b) = (int)(total - n_flush_tok);
+        }
+        b0 = b1;
+    }
     return KV_OK;
 }
 
@@ -407,15 +464,26 @@ kv_status kv_quant_append(kv_cache *cache, int32_t layer, const void *k_new, con
                           int32_t n_new, int64_t stride_b, int64_t stride_t, int64_t stride_h,
                           void *stream)
 {
-    return append_impl(cache, layer, k_new, v_new, n_new, stride_b, stride_t, stride_h, 0, nullptr, nullptr, stream);
+    if (!cache) return KV_E_NULL;
+    return append_impl(cache, layer, 0, cache->cfg.batch, k_new, v_new, n_new, stride_b, stride_t, stride_h, 0, nullptr,
+                       nullptr, stream);
+}
+
+kv_status kv_quant_append_seq(kv_cache *cache, int32_t layer, int32_t seq, const void *k_new, const void *v_new,
+                              int32_t n_new, int64_t stride_t, int64_t stride_h, void *stream)
+{
+    if (!cache) return KV_E_NULL;
+    if (seq < 0 || seq >= cache->cfg.batch) return KV_E_BAD_CONFIG;
+    return append_impl(cache, layer, seq, 1, k_new, v_new, n_new, 0, stride_t, stride_h, 0, nullptr, nullptr, stream);
 }
 
 kv_status kv_rope_quant_append(kv_cache *cache, int32_t layer, const void *k_pre, const void *v_new,
                                int32_t n_new, int64_t stride_b, int64_t stride_t, int64_t stride_h,
                                const float *rope_cos, const float *rope_sin, int32_t pairing, void *stream)
 {
+    if (!cache) return KV_E_NULL;
     if (pairing != KV_ROPE_HALF && pairing != KV_ROPE_INTERLEAVED) return KV_E_BAD_CONFIG;
-    return append_impl(cache, layer, k_pre, v_new, n_new, stride_b, stride_t, stride_h,
+    return append_impl(cache, layer, 0, cache->cfg.batch, k_pre, v_new, n_new, stride_b, stride_t, stride_h,
                        pairing == KV_ROPE_HALF ? 1 : 2, rope_cos, rope_sin, stream);
 }
 
@@ -438,19 +506,23 @@ kv_status kv_decode_bytes(const kv_cache *cache, int32_t layer, size_t *bytes)
     if (!bytes) return KV_E_NULL;
     const kv_config &c = cache->cfg;
     const LayerGeom &g = cache->geom[layer];
-    const size_t U = (size_t)c.batch * c.n_kv_heads, d = c.head_dim;
-    const size_t nb = cache->packed[layer] / c.group_tokens;
+    const size_t H = c.n_kv_heads, d = c.head_dim;
+    size_t nb = 0, r_sum = 0; // blocks and raw tokens summed over the sequences
+    for (int b = 0; b < c.batch; b++) {
+        nb += cache->P(layer, b) / c.group_tokens;
+        r_sum += cache->R(layer, b);
+    }
     size_t rec = 0; // bytes of a record that carry information (no padding)
     rec += (size_t)g.G * d * g.k_bits / 8;
     if (g.k_bits != 16) rec += 2 * d * 2 + (g.k_mean >= 0 ? d * 2 : 0);
     rec += (size_t)g.G * d * g.v_bits / 8;
     if (g.v_bits != 16) rec += (size_t)g.G * (d / g.Gc) * 4 + (g.v_mean >= 0 ? d * 2 : 0);
-    size_t total = U * nb * rec;
+    size_t total = H * nb * rec;
     if (c.mean_mode == KV_MEAN_CROSS_HEAD) {
         size_t sides = (g.k_bits != 16) + (g.v_bits != 16);
-        total += (size_t)c.batch * nb * sides * g.G * d * 2;
+        total += nb * sides * g.G * d * 2;
     }
-    total += U * (size_t)cache->resid[layer] * d * 2 * 2;
+    total += H * r_sum * d * 2 * 2;
     total += (size_t)c.batch * c.n_q_heads * d * (2 + 4);
     *bytes = total;
     return KV_OK;
@@ -524,22 +596,34 @@ kv_status kv_append_decode_attn_split(kv_cache *cache, int32_t layer, const void
     if (((uintptr_t)k_new % 16) || ((uintptr_t)v_new % 16) || ((uintptr_t)q % 16)) return KV_E_ALIGN;
     if (stride_b % 8 || stride_h % 8) return KV_E_ALIGN;
     if (stride_h < c.head_dim || stride_b < 0) return KV_E_BAD_CONFIG;
-    const int p_old = cache->packed[layer], r_old = cache->resid[layer];
-    if ((long long)p_old + r_old + 1 > c.max_tokens) return KV_E_CAPACITY;
-    const bool flush = r_old + 1 == c.resid_cap;
+    bool flush = false; // does the token complete a block of some sequence
+    for (int b = 0; b < c.batch; b++) {
+        if ((long long)cache->P(layer, b) + cache->R(layer, b) + 1 > c.max_tokens) return KV_E_CAPACITY;
+        if (cache->R(layer, b) + 1 == c.resid_cap) flush = true;
+    }
 
     // the decode launch as it will look once the token is in, checked before anything is enqueued
+    const std::vector<int> p_old(cache->packed.begin() + (size_t)layer * c.batch, cache->packed.begin() + (size_t)(layer + 1) * c.batch);
+    const std::vector<int> r_old(cache->resid.begin() + (size_t)layer * c.batch, cache->resid.begin() + (size_t)(layer + 1) * c.batch);
+    auto restore = [&] {
+        for (int b = 0; b < c.batch; b++) {
+            cache->P(layer, b) = p_old[b];
+            cache->R(layer, b) = r_old[b];
+        }
+    };
+    for (int b = 0; b < c.batch; b++) {
+        const bool fl = r_old[b] + 1 == c.resid_cap;
+        cache->P(layer, b) = fl ? p_old[b] + c.resid_cap : p_old[b];
+        cache->R(layer, b) = fl ? 0 : r_old[b] + 1;
+    }
     DecodeArgs a{};
-    cache->packed[layer] = flush ? p_old + c.resid_cap : p_old;
-    cache->resid[layer] = flush ? 0 : r_old + 1;
     st = fill_decode(cache, layer, &a);
     const bool mfma = st == KV_OK && use_mfma(cache, a);
     if (st == KV_OK) st = bind_workspace(cache, &a, workspace, workspace_bytes);
     if (st == KV_OK && c.mean_mode == KV_MEAN_CROSS_HEAD && a.geom.k_bits != 16 && a.geom.G > 64) st = KV_E_UNSUPPORTED;
     if (st == KV_OK && cache->decode_path == 2 && !mfma) st = KV_E_UNSUPPORTED;
     if (st != KV_OK || flush || !mfma) {
-        cache->packed[layer] = p_old;
-        cache->resid[layer] = r_old;
+        restore();
         if (st != KV_OK) return st;
         // a block is due for compression, or the layer is served by the vector-ALU kernels:
         // the two steps run as launches of their own
@@ -554,7 +638,7 @@ kv_status kv_append_decode_attn_split(kv_cache *cache, int32_t layer, const void
     a.fresh_stride_b = stride_b;
     a.fresh_stride_h = stride_h;
     if (launch_decode_split_mfma(a, (hipStream_t)stream) != hipSuccess) {
-        cache->resid[layer] = r_old;
+        restore();
         return KV_E_HIP;
     }
     return KV_OK;

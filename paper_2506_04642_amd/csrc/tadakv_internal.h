@@ -9,6 +9,7 @@ constexpr int kHeadDim = 128;
 constexpr int kMaxGroupQ = 8;       // query heads per kv head the kernels are sized for
 constexpr int kPartialStride = 132; // floats per (unit, q head, split): O[128], max, sum, pad
 constexpr int kMaxSplits = 256;
+constexpr int kMaxRaggedBatch = 64; // sequences whose lengths may differ from one another
 
 // Geometry of one layer's buffer; byte offsets, -1 where a field is absent.
 struct LayerGeom {
@@ -27,7 +28,8 @@ struct AppendArgs {
     const uint16_t *k_new;  // device
     const uint16_t *v_new;
     long long stride_b, stride_t, stride_h; // elements
-    int n_kv_heads, batch;
+    int n_kv_heads, batch; // batch: sequences of this launch (a run b0 .. b0 + batch - 1 of the cache's)
+    int b0;             // first sequence of the run in the cache; the input pointers already point at it
     int r_old;          // residual tokens before the call
     int first_block;    // index of the first block this call writes
     int n_flush_blocks; // blocks to compress
@@ -59,7 +61,15 @@ struct DecodeArgs {
     // xmc [batch][Hq][tcap / 64]: that maximum (exp2 domain) per 64-token chunk.
     float *xs, *xp, *xmc;
     int tcap;
+    // sequences of different lengths: n_blocks and r above are the maxima, the kernels take each
+    // sequence's own counts from these (ragged == 0: every sequence has n_blocks and r)
+    int ragged;
+    int nb_seq[kMaxRaggedBatch], r_seq[kMaxRaggedBatch];
 };
+
+// packed blocks / raw tokens of sequence b
+__host__ __device__ inline int seq_blocks(const DecodeArgs &a, int b) { return a.ragged ? a.nb_seq[b] : a.n_blocks; }
+__host__ __device__ inline int seq_resid(const DecodeArgs &a, int b) { return a.ragged ? a.r_seq[b] : a.r; }
 
 // records the outcome of a launch for kv_last_hip_error and passes it through
 hipError_t note_launch(hipError_t e);

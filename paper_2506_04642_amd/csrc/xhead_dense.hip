@@ -50,7 +50,7 @@ template <int MT> // 16-head tiles: ceil(Hq / 16)
 __global__ __launch_bounds__(kThreads) void xhead_scores_kernel(DecodeArgs a)
 {
     const int Hq = a.n_q_heads, b = blockIdx.y;
-    const int T = a.n_blocks * a.geom.G;
+    const int T = seq_blocks(a, b) * a.geom.G;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 15, kg = lane >> 4;
     v8h qa[MT][4];
@@ -126,8 +126,8 @@ __global__ __launch_bounds__(kThreads) void xhead_values_kernel(DecodeArgs a)
     if (pair >= a.batch * ns) return;
     const int b = pair / ns, sp = pair - b * ns, u = b * a.n_kv_heads + h;
     const int nbc = 64 / gm.G > 0 ? 64 / gm.G : 1;
-    const int chunks_total = (a.n_blocks + nbc - 1) / nbc;
-    const int T = a.n_blocks * gm.G;
+    const int chunks_total = (seq_blocks(a, b) + nbc - 1) / nbc;
+    const int T = seq_blocks(a, b) * gm.G;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, kg = lane >> 4;
     const int ncap = a.tcap / 64 + 1;

@@ -591,3 +591,28 @@ def test_cache_append_with_rope_equals_rotate_then_append(oracle):
     assert np.array_equal(a.layer_image(0)["bytes"], b.layer_image(0)["bytes"])
     # position 0 has angle 0: the first token's raw bits pass through unchanged
     assert np.array_equal(rot[:, 0] & 0x7FFF, k[:, 0] & 0x7FFF)
+
+
+# ------------------------------------------------------------------ P13: sequences of different lengths
+
+
+def test_per_sequence_appends_equal_a_batch_of_one_each(oracle):
+    """A sequence's blocks and residual buffer are its own (Sec. 3.3): a slot of a batch filled by
+    per-sequence appends holds what a batch-of-one cache fed the same tokens holds, a reset slot
+    is empty, and an empty sequence attends to nothing (zeros)."""
+    H, d, G = 2, 128, 32
+    cfg = oracle.OracleConfig(1, 3, 4, H, d, 256, G, G, G, F16, CHAN, [4], [4])
+    one = oracle.OracleConfig(1, 1, 4, H, d, 256, G, G, G, F16, CHAN, [4], [4])
+    big = oracle.OracleCache(cfg)
+    q = synth.make_q(5, 3, 4, d, F16)
+    for b, n in ((0, 70), (2, 33)):
+        k, v = synth.make_kv(90 + b, 1, n, H, d, F16)
+        big.append_seq(0, b, k[0], v[0])
+        ref = oracle.OracleCache(one)
+        ref.append(0, k, v)
+        assert (big.packed_len(0, b), big.resid_len(0, b)) == (ref.packed_len(0), ref.resid_len(0))
+        assert np.array_equal(big.attend(0, q)[b], ref.attend(0, q[b:b + 1])[0])
+    assert np.array_equal(big.attend(0, q)[1], np.zeros((4, d)))
+    big.reset_seq(0, 0)
+    assert (big.packed_len(0, 0), big.resid_len(0, 0)) == (0, 0)
+    assert np.array_equal(big.attend(0, q)[0], np.zeros((4, d)))
