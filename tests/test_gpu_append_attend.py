@@ -63,7 +63,7 @@ def run_steps(kv, oracle, *, bits, G, R, mode, g, Hkv, B, T0, steps, dtype, path
 
 
 @pytest.mark.parametrize("bits", [2, 4, 8])
-@pytest.mark.parametrize("G,R", [(32, 32), (64, 64), (32, 64)])
+@pytest.mark.parametrize("G,R", [(32, 32), (64, 64), (32, 64), (32, 128)])
 def test_decode_steps_across_block_boundaries(kv, oracle, bits, G, R):
     """Starts a few tokens before a block completes, so the steps cover: token kept raw (fused
     kernel), token that completes a block (separate launches), first token after a flush."""
