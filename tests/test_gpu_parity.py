@@ -1,3 +1,10 @@
+    # The matrix-core kernel carries q*scale and p*scale as 23-bit fixed point relative to the largest
+    # scale of a block / 64-token chunk: with a key outlier that draws all the weight onto a token
+    # whose value is 300, outputs reach +-200 and carry a relative error of about 1e-5.  The 2e-3
+    # bound is stated for the workloads' magnitudes (outputs of order 1, |x| up to about 20).
+    q = synth.make_q(800 + bits, B, Hkv * g, 128, F16)
+    scale = max(1.0, float(np.max(np.abs(orc.attend(0, q)))) / 20.0)
+    err = check_attention(gpu, orc, 0, q, F16, tol=2e-3 * scale)
 """GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
 Packed codes and metadata must match bit for bit; attention within 2e-3 max-abs."""
 import numpy as np
@@ -423,3 +430,37 @@ def test_prefill_then_decode_steps_with_drift(kv, oracle, decode_path):
             if s % 13 == 0 or s in (31, 32, steps - 1):
                 check_attention(gpu, orc, l, synth.make_q(l * 100 + s, 3, 8, 128, BF16), BF16)
         check_bytes(gpu, orc, l)
+
+
+# ------------------------------------------------------------------ degenerate inputs
+
+
+@pytest.mark.parametrize("bits", [2, 4, 8])
+@pytest.mark.parametrize("mode", [CHAN, CROSS, NONE])
+def test_degenerate_values(kv, oracle, bits, mode):
+    """Groups with zero range (scale 0), all-zero tokens, zeros of both signs, binary16-subnormal
+    magnitudes and a few large values: same bytes as the oracle, finite attention."""
+    print("case degenerate bits=%d mode=%d" % (bits, mode), flush=True)
+    B, Hkv, g, G, T = 2, 2, 4, 32, 4 * 32 + 5
+    rng = np.random.default_rng(800 + bits)
+    x = np.zeros((2, B, T, Hkv, 128), dtype=np.float32)
+    x[:, :, 0:32] = 0.0                                  # an all-zero block
+    x[:, :, 32:64] = 1.5                                 # a constant block: every group has zero range
+    x[:, :, 64:96] = rng.standard_normal((2, B, 32, Hkv, 128)) * 1e-6   # below binary16 normal range
+    x[:, :, 96:] = rng.standard_normal((2, B, T - 96, Hkv, 128))
+    x[:, :, 96:128, :, 5] = 0.0                          # a constant channel inside a varying block
+    x[:, :, 100, :, :] = 0.0                             # a constant token (value groups of zero range)
+    x[:, :, 110, :, 7] = 300.0                           # outliers
+    x[:, :, 111, :, 9] = -250.0
+    kb = synth.f32_to_bits16(x[0], F16)
+    vb = synth.f32_to_bits16(x[1], F16)
+    kb[:, 1:32:2] |= 0x8000                              # negative zeros among the zeros
+    vb[:, 100, :, ::3] |= 0x8000
+    gpu, orc = make_pair(kv, oracle, B=B, Hq=Hkv * g, Hkv=Hkv, T_max=6 * G, G=G, Gc=G, dtype=F16, mode=mode, k_bits=(bits,))
+    append_both(gpu, orc, 0, kb, vb, F16, chunks=[40, T - 40])
+    check_bytes(gpu, orc, 0)
+    # The matrix-core kernel carries q*scale and p*scale as 23-bit fixed point relative to the largest
+    # scale of a block / 64-token chunk, so its absolute error grows with that scale; the 2e-3 bound
+    # is stated for the workloads' magnitudes (|x| up to about 20), the outliers here are 15 times that.
+    err = check_attention(gpu, orc, 0, synth.make_q(800 + bits, B, Hkv * g, 128, F16), F16, tol=2e-3 * 300.0 / 20.0)
+    print("  attention max-abs error %.3e" % err, flush=True)
