@@ -1,10 +1,3 @@
-    # The matrix-core kernel carries q*scale and p*scale as 23-bit fixed point relative to the largest
-    # scale of a block / 64-token chunk: with a key outlier that draws all the weight onto a token
-    # whose value is 300, outputs reach +-200 and carry a relative error of about 1e-5.  The 2e-3
-    # bound is stated for the workloads' magnitudes (outputs of order 1, |x| up to about 20).
-    q = synth.make_q(800 + bits, B, Hkv * g, 128, F16)
-    scale = max(1.0, float(np.max(np.abs(orc.attend(0, q)))) / 20.0)
-    err = check_attention(gpu, orc, 0, q, F16, tol=2e-3 * scale)
 """GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
 Packed codes and metadata must match bit for bit; attention within 2e-3 max-abs."""
 import numpy as np
@@ -460,7 +453,10 @@ def test_degenerate_values(kv, oracle, bits, mode):
     append_both(gpu, orc, 0, kb, vb, F16, chunks=[40, T - 40])
     check_bytes(gpu, orc, 0)
     # The matrix-core kernel carries q*scale and p*scale as 23-bit fixed point relative to the largest
-    # scale of a block / 64-token chunk, so its absolute error grows with that scale; the 2e-3 bound
-    # is stated for the workloads' magnitudes (|x| up to about 20), the outliers here are 15 times that.
-    err = check_attention(gpu, orc, 0, synth.make_q(800 + bits, B, Hkv * g, 128, F16), F16, tol=2e-3 * 300.0 / 20.0)
-    print("  attention max-abs error %.3e" % err, flush=True)
+    # scale of a block / 64-token chunk: with a key outlier that draws all the weight onto a token
+    # whose value is 300, outputs reach +-200 and carry a relative error of about 1e-5.  The 2e-3
+    # bound is stated for the workloads' magnitudes (outputs of order 1, |x| up to about 20).
+    q = synth.make_q(800 + bits, B, Hkv * g, 128, F16)
+    scale = max(1.0, float(np.max(np.abs(orc.attend(0, q)))) / 20.0)
+    err = check_attention(gpu, orc, 0, q, F16, tol=2e-3 * scale)
+    print("  attention max-abs error %.3e (bound %.1e)" % (err, 2e-3 * scale), flush=True)
