@@ -68,7 +68,7 @@ typedef enum { KV_MEAN_CHANNEL_BLOCK = 0, KV_MEAN_CROSS_HEAD = 1, KV_MEAN_NONE =
 
 typedef struct {
     int32_t n_layers;
-    int32_t batch;          /* sequences; all have the same length */
+    int32_t batch;          /* sequences (slots); their lengths are tracked one by one */
     int32_t n_q_heads;      /* multiple of n_kv_heads; query head i reads kv head i / (Hq/Hkv) */
     int32_t n_kv_heads;
     int32_t head_dim;       /* 128 */
