@@ -561,6 +561,167 @@ __device__ __forceinline__ void rope_in_lanes(float (&x)[8][8], const AppendArgs
     }
 }
 
+// Codes and packed words of 32 key tokens held as deviations x[token j][channel e] (lane = (tg, c8)),
+// given the per-channel metadata; `half` is the 32-token half of the block (0 for blocks of 32).
+// A key word runs along channels.
+template <int BITS>
+__device__ __forceinline__ void emit_key_words(const float (&x)[8][8], const float (&sc)[8], const float (&rs)[8],
+                                               const float (&z)[8], int half, int lane, unsigned char *codes_out)
+{
+    constexpr float qmaxf = (float)((1 << BITS) - 1);
+    const int tg = lane & 3, c8 = lane >> 2;
+    const int tt = 2 * half + (tg >> 1), jj = c8 >> 2; // 16-token tile of the block, channel-tile pair
+#pragma unroll
+    for (int j = 0; j < 8; j++) {
+        uint32_t cd[8];
+#pragma unroll
+        for (int e = 0; e < 8; e++) cd[e] = quant_code(x[j][e], sc[e], rs[e], z[e], qmaxf);
+        const int n = 8 * (tg & 1) + j;
+        if (BITS == 4) {
+            uint32_t w = 0;
+#pragma unroll
+            for (int e = 0; e < 8; e++) w |= cd[e] << (8 * (e & 3) + 4 * (e >> 2));
+            ((uint32_t *)codes_out)[((tt * 4 + jj) * 16 + n) * 4 + (c8 & 3)] = w;
+        } else if (BITS == 8) {
+            const uint32_t w0 = cd[0] | (cd[1] << 8) | (cd[2] << 16) | (cd[3] << 24);
+            const uint32_t w1 = cd[4] | (cd[5] << 8) | (cd[6] << 16) | (cd[7] << 24);
+            const int piece = ((tt * 2 + ((c8 >> 1) & 1)) * 4 + jj) * 16 + n;
+            *(uint2 *)(codes_out + (piece * 4 + 2 * (c8 & 1)) * 4) = uint2{w0, w1};
+        } else {
+            // 16 channels per word: this lane's half, shifted into place, joined with the
+            // neighbouring channel octet's (lane ^ 4); two token tiles share a piece
+            uint32_t w = 0;
+#pragma unroll
+            for (int e = 0; e < 8; e++) w |= cd[e] << (8 * (e & 3) + 2 * (e >> 2));
+            w <<= 4 * (c8 & 1);
+            w |= from_lane_u(w, lane ^ 4);
+            if ((j >> 2) == (c8 & 1))
+                ((uint32_t *)codes_out)[(((tt >> 1) * 4 + jj) * 16 + n) * 4 + (((tt & 1) << 1) | ((c8 >> 1) & 1))] = w;
+        }
+    }
+}
+
+// Metadata, codes and packed words of 32 value tokens held as deviations x[token j][channel e]:
+// one group per (token, GC channels) = eight channels in the lane times GC / 8 lanes.  NT is the
+// number of 16-token tiles of the block; meta_out points at the block's (scale, zero) array.
+template <int GC, int BITS, int NT>
+__device__ __forceinline__ void emit_value_half(const float (&x)[8][8], int half, int lane, unsigned char *codes_out,
+                                                unsigned char *meta_out)
+{
+    constexpr int NGV = kHeadDim / GC;
+    constexpr int qmax = (1 << BITS) - 1;
+    constexpr float qmaxf = (float)qmax;
+    const int tg = lane & 3, c8 = lane >> 2;
+    float mn[8], mx[8];
+#pragma unroll
+    for (int j = 0; j < 8; j++) {
+        float lo = x[j][0], hi = x[j][0];
+#pragma unroll
+        for (int e = 1; e < 8; e++) {
+            lo = fminf(lo, x[j][e]);
+            hi = fmaxf(hi, x[j][e]);
+        }
+        // lanes 4 and 8 apart in the row of 16 (rotations: the coset is covered either way)
+        lo = fminf(lo, dpp_f<0x124>(lo));
+        hi = fmaxf(hi, dpp_f<0x124>(hi));
+        lo = fminf(lo, dpp_f<0x128>(lo));
+        hi = fmaxf(hi, dpp_f<0x128>(hi));
+        if (GC >= 64) {
+            lo = fminf(lo, from_lane_f(lo, lane ^ 16));
+            hi = fmaxf(hi, from_lane_f(hi, lane ^ 16));
+        }
+        if (GC >= 128) {
+            lo = fminf(lo, from_lane_f(lo, lane ^ 32));
+            hi = fmaxf(hi, from_lane_f(hi, lane ^ 32));
+        }
+        mn[j] = lo;
+        mx[j] = hi;
+    }
+    // lane with q4 = c8 & 3 works out tokens 2 q4 and 2 q4 + 1 of its group, then the four share
+    const int q4 = c8 & 3;
+    const MetaOut ma = meta_of(pick4(q4, mn[0], mn[2], mn[4], mn[6]), pick4(q4, mx[0], mx[2], mx[4], mx[6]), qmax);
+    const MetaOut mb = meta_of(pick4(q4, mn[1], mn[3], mn[5], mn[7]), pick4(q4, mx[1], mx[3], mx[5], mx[7]), qmax);
+    if ((c8 & (GC / 8 - 1)) == q4) {
+        const int gam = c8 / (GC / 8), t = 32 * half + 8 * tg + 2 * q4;
+        *(uint32_t *)(meta_out + (t * NGV + gam) * 4) = ma.pk;
+        *(uint32_t *)(meta_out + ((t + 1) * NGV + gam) * 4) = mb.pk;
+    }
+    float sc[8], z[8], rs[8];
+#pragma unroll
+    for (int j = 0; j < 8; j++) {
+        const int src = (lane & ~12) | ((j >> 1) << 2);
+        const uint32_t pk = from_lane_u((j & 1) ? mb.pk : ma.pk, src);
+        rs[j] = from_lane_f((j & 1) ? mb.rs : ma.rs, src);
+        sc[j] = f16_val((uint16_t)(pk & 0xFFFFu));
+        z[j] = f16_val((uint16_t)(pk >> 16));
+    }
+    // codes and words: a value word runs along tokens
+    const int tt = 2 * half + (tg >> 1);
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+        uint32_t cd[8];
+#pragma unroll
+        for (int j = 0; j < 8; j++) cd[j] = quant_code(x[j][e], sc[j], rs[j], z[j], qmaxf);
+        const int n = 8 * (c8 & 1) + e;
+        if (BITS == 4) {
+            uint32_t w = 0;
+#pragma unroll
+            for (int j = 0; j < 8; j++) w |= cd[j] << (8 * (j & 3) + 4 * (j >> 2));
+            const int piece = ((c8 >> 2) * NT + tt) * 16 + n;
+            ((uint32_t *)codes_out)[piece * 4 + 2 * ((c8 >> 1) & 1) + (tg & 1)] = w;
+        } else if (BITS == 8) {
+            const uint32_t w0 = cd[0] | (cd[1] << 8) | (cd[2] << 16) | (cd[3] << 24);
+            const uint32_t w1 = cd[4] | (cd[5] << 8) | (cd[6] << 16) | (cd[7] << 24);
+            const int piece = ((c8 >> 1) * NT + tt) * 16 + n;
+            *(uint2 *)(codes_out + (piece * 4 + 2 * (tg & 1)) * 4) = uint2{w0, w1};
+        } else {
+            uint32_t w = 0;
+#pragma unroll
+            for (int j = 0; j < 8; j++) w |= cd[j] << (8 * (j & 3) + 2 * (j >> 2));
+            w <<= 4 * (tg & 1);
+            w |= dpp_u<0xB1>(w);
+            const int piece = ((c8 >> 3) * NT + tt) * 16 + n;
+            if ((e >> 2) == (tg & 1)) ((uint32_t *)codes_out)[piece * 4 + ((c8 >> 1) & 3)] = w;
+        }
+    }
+}
+
+// Key metadata of the eight channels of a lane from the groups' extrema (equal in the four lanes
+// of a quad): quad lane tg works out channels 2 tg and 2 tg + 1, then all share; lane tg == 0
+// stores the packed scale / zero rows.
+__device__ __forceinline__ void key_metadata(const float (&mn)[8], const float (&mx)[8], int qmax, int lane,
+                                             unsigned char *scale_out, unsigned char *zero_out, float (&sc)[8],
+                                             float (&rs)[8], float (&z)[8])
+{
+    const int tg = lane & 3, c8 = lane >> 2;
+    const MetaOut ma = meta_of(pick4(tg, mn[0], mn[2], mn[4], mn[6]), pick4(tg, mx[0], mx[2], mx[4], mx[6]), qmax);
+    const MetaOut mb = meta_of(pick4(tg, mn[1], mn[3], mn[5], mn[7]), pick4(tg, mx[1], mx[3], mx[5], mx[7]), qmax);
+    uint32_t pk[8];
+    pk[0] = quad_bcast_u<0>(ma.pk); rs[0] = quad_bcast_f<0>(ma.rs);
+    pk[1] = quad_bcast_u<0>(mb.pk); rs[1] = quad_bcast_f<0>(mb.rs);
+    pk[2] = quad_bcast_u<1>(ma.pk); rs[2] = quad_bcast_f<1>(ma.rs);
+    pk[3] = quad_bcast_u<1>(mb.pk); rs[3] = quad_bcast_f<1>(mb.rs);
+    pk[4] = quad_bcast_u<2>(ma.pk); rs[4] = quad_bcast_f<2>(ma.rs);
+    pk[5] = quad_bcast_u<2>(mb.pk); rs[5] = quad_bcast_f<2>(mb.rs);
+    pk[6] = quad_bcast_u<3>(ma.pk); rs[6] = quad_bcast_f<3>(ma.rs);
+    pk[7] = quad_bcast_u<3>(mb.pk); rs[7] = quad_bcast_f<3>(mb.rs);
+    if (tg == 0) {
+        uint32_t sw[4], zw[4];
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+            sw[k] = (pk[2 * k] & 0xFFFFu) | (pk[2 * k + 1] << 16);
+            zw[k] = (pk[2 * k] >> 16) | (pk[2 * k + 1] & 0xFFFF0000u);
+        }
+        *(uint4 *)(scale_out + c8 * 16) = uint4{sw[0], sw[1], sw[2], sw[3]};
+        *(uint4 *)(zero_out + c8 * 16) = uint4{zw[0], zw[1], zw[2], zw[3]};
+    }
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+        sc[e] = f16_val((uint16_t)(pk[e] & 0xFFFFu));
+        z[e] = f16_val((uint16_t)(pk[e] >> 16));
+    }
+}
+
 template <int GC, int BITS, bool ROPE>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ? 2 : 3, 8))) void flush_wave_kernel(AppendArgs a, int n_items)
 {
@@ -838,6 +999,174 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ?
     }
 }
 
+
+// The same for blocks of 64 tokens: a wave takes the block as two halves of 32 tokens, twice.
+// The first pass gathers what spans the block -- the per-channel sums in token order (the
+// running sum goes from quad lane 3 of the first half to quad lane 0 of the second) and, for
+// keys, the channels' extrema --, the second pass loads the rows again (they are in the cache),
+// forms the deviations and emits metadata, codes and words half by half.  With a per-channel
+// mean m the extrema of the deviations are those of the raw values moved by m: rounding is
+// monotone, so min_t fl(x_t - m) = fl(min_t x_t - m).
+template <int GC, int BITS>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 8))) void flush_wave64_kernel(AppendArgs a, int n_items)
+{
+    constexpr int G = 64;
+    constexpr int NGV = kHeadDim / GC;
+    constexpr int qmax = (1 << BITS) - 1;
+    const LayerGeom &gm = a.geom;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int tg = lane & 3, c8 = lane >> 2;
+    const int U = a.batch * a.n_kv_heads;
+    const int workers = (int)gridDim.x * (kThreads / 64);
+    constexpr int META_BYTES = G * NGV * 4 + 256 > 768 ? G * NGV * 4 + 256 : 768;
+    constexpr int IMG_BYTES = G * kHeadDim * BITS / 8 + META_BYTES;
+    __shared__ __attribute__((aligned(16))) unsigned char lds_img[kThreads / 64][IMG_BYTES];
+    unsigned char *img = lds_img[wave];
+
+    for (int it = (int)blockIdx.x * (kThreads / 64) + wave; it < n_items; it += workers) {
+        const int which = (it ^ (it / workers)) & 1, u = (it >> 1) % U, fb = (it >> 1) / U;
+        const int b = u / a.n_kv_heads, h = u % a.n_kv_heads;
+        unsigned char *rec = a.layer + ((long long)(a.b0 * a.n_kv_heads + u) * gm.NB + (a.first_block + fb)) * gm.rec_bytes;
+        const int base_off = which == 0 ? gm.k_codes : gm.v_codes;
+        const uint16_t *xm = (const uint16_t *)(a.layer + gm.xmean_off) +
+                             (((long long)(a.b0 + b) * gm.NB + (a.first_block + fb)) * 2 + which) * G * kHeadDim;
+        const int mode = gm.mean_mode;
+
+        // rows 32 half + 8 tg .. + 7 of the block, channels 8 c8 .. + 7, widened; in cross-head
+        // mode already as deviations from the (token, channel) mean
+        auto load_half = [&](int half, float (&x)[8][8]) {
+            uint4 pre[8];
+#pragma unroll
+            for (int j = 0; j < 8; j++) pre[j] = *(const uint4 *)(src_row(a, which, b, h, fb * G + 32 * half + 8 * tg + j) + c8 * 8);
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                const uint32_t wv[4] = {pre[j].x, pre[j].y, pre[j].z, pre[j].w};
+#pragma unroll
+                for (int k = 0; k < 4; k++) {
+                    x[j][2 * k] = widen16((uint16_t)(wv[k] & 0xFFFFu), gm.dtype);
+                    x[j][2 * k + 1] = widen16((uint16_t)(wv[k] >> 16), gm.dtype);
+                }
+            }
+            if (mode == 1) {
+#pragma unroll
+                for (int j = 0; j < 8; j++) {
+                    const uint4 mv = *(const uint4 *)(xm + (32 * half + 8 * tg + j) * kHeadDim + c8 * 8);
+                    const uint32_t wv[4] = {mv.x, mv.y, mv.z, mv.w};
+#pragma unroll
+                    for (int k = 0; k < 4; k++) {
+                        x[j][2 * k] = x[j][2 * k] - f16_val((uint16_t)(wv[k] & 0xFFFFu));
+                        x[j][2 * k + 1] = x[j][2 * k + 1] - f16_val((uint16_t)(wv[k] >> 16));
+                    }
+                }
+            }
+        };
+
+        // ---- first pass: channel sums in token order (per-channel mean mode), key extrema
+        float acc[8], mn[8], mx[8];
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+            acc[e] = 0.0f;
+            mn[e] = INFINITY;
+            mx[e] = -INFINITY;
+        }
+        if (mode == 0 || which == 0) {
+#pragma unroll
+            for (int half = 0; half < 2; half++) {
+                float x[8][8];
+                load_half(half, x);
+                if (mode == 0) {
+#pragma unroll
+                    for (int p = 0; p < 4; p++) {
+                        float cin[8];
+#pragma unroll
+                        for (int e = 0; e < 8; e++)
+                            cin[e] = p == 0 ? (half == 0 ? 0.0f : quad_bcast_f<3>(acc[e]))
+                                            : (p == 1 ? quad_bcast_f<0>(acc[e]) : (p == 2 ? quad_bcast_f<1>(acc[e]) : quad_bcast_f<2>(acc[e])));
+                        if (tg == p) {
+#pragma unroll
+                            for (int e = 0; e < 8; e++) {
+                                float sacc = cin[e];
+#pragma unroll
+                                for (int j = 0; j < 8; j++) sacc = sacc + x[j][e];
+                                acc[e] = sacc;
+                            }
+                        }
+                    }
+                }
+                if (which == 0) {
+#pragma unroll
+                    for (int e = 0; e < 8; e++)
+#pragma unroll
+                        for (int j = 0; j < 8; j++) {
+                            mn[e] = fminf(mn[e], x[j][e]);
+                            mx[e] = fmaxf(mx[e], x[j][e]);
+                        }
+                }
+            }
+        }
+        float m[8];
+#pragma unroll
+        for (int e = 0; e < 8; e++) m[e] = 0.0f;
+        if (mode == 0) {
+            uint32_t mpk[4];
+#pragma unroll
+            for (int e = 0; e < 8; e++) {
+                const uint32_t m16 = quad_bcast_u<3>((uint32_t)f16_rne(acc[e] / (float)G));
+                m[e] = f16_val((uint16_t)m16);
+                if (e & 1) mpk[e >> 1] |= m16 << 16;
+                else mpk[e >> 1] = m16;
+            }
+            if (tg == 0)
+                *(uint4 *)(img + ((which == 0 ? gm.k_mean : gm.v_mean) - base_off) + c8 * 16) = uint4{mpk[0], mpk[1], mpk[2], mpk[3]};
+        }
+
+        if (which == 0) {
+            // ---- keys: extrema over the quad, moved by the mean; metadata; then the codes
+#pragma unroll
+            for (int e = 0; e < 8; e++) {
+                float lo = mn[e], hi = mx[e];
+                lo = fminf(lo, dpp_f<0xB1>(lo));
+                hi = fmaxf(hi, dpp_f<0xB1>(hi));
+                lo = fminf(lo, dpp_f<0x4E>(lo));
+                hi = fmaxf(hi, dpp_f<0x4E>(hi));
+                mn[e] = lo - m[e];
+                mx[e] = hi - m[e];
+            }
+            float sc[8], rs[8], z[8];
+            key_metadata(mn, mx, qmax, lane, img + (gm.k_scale - base_off), img + (gm.k_zero - base_off), sc, rs, z);
+#pragma unroll
+            for (int half = 0; half < 2; half++) {
+                float x[8][8];
+                load_half(half, x);
+#pragma unroll
+                for (int j = 0; j < 8; j++)
+#pragma unroll
+                    for (int e = 0; e < 8; e++) x[j][e] = x[j][e] - m[e];
+                emit_key_words<BITS>(x, sc, rs, z, half, lane, img);
+            }
+        } else {
+#pragma unroll
+            for (int half = 0; half < 2; half++) {
+                float x[8][8];
+                load_half(half, x);
+#pragma unroll
+                for (int j = 0; j < 8; j++)
+#pragma unroll
+                    for (int e = 0; e < 8; e++) x[j][e] = x[j][e] - m[e];
+                emit_value_half<GC, BITS, G / 16>(x, half, lane, img, img + (gm.v_meta - base_off));
+            }
+        }
+
+        int part_bytes;
+        if (which == 0) part_bytes = (mode == 0 ? gm.k_mean : gm.k_zero) + 256 - base_off;
+        else part_bytes = (mode == 0 ? gm.v_mean + 256 : gm.v_meta + G * NGV * 4) - base_off;
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // this wave's LDS writes have landed
+        for (int off = lane * 16; off < part_bytes; off += 64 * 16) *(uint4 *)(rec + base_off + off) = *(const uint4 *)(img + off);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // the image is in registers before the next item overwrites it
+    }
+}
+
 // Cross-head mean (Eq. 1-2): for every token of a block and every channel, the mean over the kv
 // heads, m = f16_rne((x_0 + x_1 + ... + x_{H-1}) / H) with the sum taken in head order.
 // grid (blocks to flush, batch, K|V); written to the layer's mean plane.
@@ -960,6 +1289,26 @@ template <int GC, int BITS, bool ROPE> hipError_t launch_flush_wave(const Append
     return note_launch(hipGetLastError());
 }
 
+template <int GC, int BITS> hipError_t launch_flush_wave64(const AppendArgs &a, hipStream_t s)
+{
+    const int U = a.batch * a.n_kv_heads;
+    const long long items = (long long)a.n_flush_blocks * U * 2;
+    if (items > 0x7FFFFFFF) return hipErrorInvalidValue;
+    static const int slots = [] {
+        int per_cu = 0, dev = 0, cus = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, flush_wave64_kernel<GC, BITS>, kThreads, 0) != hipSuccess ||
+            hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+            return 0;
+        return per_cu * cus;
+    }();
+    if (slots < 1) return hipErrorInvalidValue;
+    const long long want = (items + kThreads / 64 - 1) / (kThreads / 64);
+    const int grid = want < slots ? (int)want : slots;
+    hipLaunchKernelGGL((flush_wave64_kernel<GC, BITS>), dim3(grid), dim3(kThreads), 0, s, a, (int)items);
+    return note_launch(hipGetLastError());
+}
+
 hipError_t launch_flush(const AppendArgs &a, hipStream_t s)
 {
     const int U = a.batch * a.n_kv_heads;
@@ -981,6 +1330,14 @@ hipError_t launch_flush(const AppendArgs &a, hipStream_t s)
         if (a.rope != 0) return gc == 32 ? TADAKV_WAVE(32, true) : gc == 64 ? TADAKV_WAVE(64, true) : TADAKV_WAVE(128, true);
         return gc == 32 ? TADAKV_WAVE(32, false) : gc == 64 ? TADAKV_WAVE(64, false) : TADAKV_WAVE(128, false);
 #undef TADAKV_WAVE
+    }
+    if (a.geom.G == 64 && kb == a.geom.v_bits && kb != 16 && a.rope == 0) {
+        // blocks of 64 tokens: the same wave kernel in two passes over two halves
+        const int gc = a.geom.Gc;
+#define TADAKV_WAVE64(GCV) \
+    (kb == 2 ? launch_flush_wave64<GCV, 2>(a, s) : kb == 4 ? launch_flush_wave64<GCV, 4>(a, s) : launch_flush_wave64<GCV, 8>(a, s))
+        return gc == 32 ? TADAKV_WAVE64(32) : gc == 64 ? TADAKV_WAVE64(64) : TADAKV_WAVE64(128);
+#undef TADAKV_WAVE64
     }
     if (a.geom.G == 32) return launch_flush_gc<32>(a, s);
     if (a.geom.G == 64) return launch_flush_gc<64>(a, s);
