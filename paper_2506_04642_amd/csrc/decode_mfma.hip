@@ -112,10 +112,27 @@ __device__ __forceinline__ v4i mfma(v4i a, v4i b, v4i c)
 {
     return __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, c, 0, 0, 0);
 }
-// three signed-byte limbs (weights 1, 256, 65536) -> float; every partial value is exact
+// three signed-byte limbs (weights 1, 256, 65536) -> float.  The two upper limbs are combined in
+// integer (no overflow: a limb sum is below 2^23), so the conversion rounds once, at 2^-24 relative.
 __device__ __forceinline__ float limbs_to_float(v4i acc)
 {
-    return (float)acc.x + 256.0f * (float)acc.y + 65536.0f * (float)acc.z;
+    return (float)acc.x + 256.0f * (float)(acc.y + (acc.z << 8));
+}
+// Hides a value's origin from the optimiser: without this a constant of the form (C - m) that is
+// added to many values is re-associated into two operations per value.
+__device__ __forceinline__ uint32_t opaque(uint32_t x)
+{
+    asm volatile("" : "+v"(x));
+    return x;
+}
+// power of two strictly above the larger of the two non-negative binary16 values in w (at least
+// 2^-14), and its reciprocal, straight from the exponent field
+__device__ __forceinline__ void pow2_above_h2(uint32_t w, bool both, float &p, float &inv)
+{
+    const uint32_t m = both ? max(w & 0xFFFFu, w >> 16) : (w & 0xFFFFu);
+    const uint32_t b = ((m & 0x7C00u) << 13) + (113u << 23); // value exponent (e5 - 15) + 1, biased by 127
+    p = __uint_as_float(b);
+    inv = __uint_as_float(0x7F000000u - b);
 }
 
 // running softmax state of one lane for one query head; O for channels 16*ct + n
@@ -435,9 +452,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
             // so the largest is found with packed 16-bit integer maxima on the raw words
             uint32_t smw = pk_max_u16(pk_max_u16(ks[bi][0].x, ks[bi][0].y), pk_max_u16(ks[bi][1].x, ks[bi][1].y));
             smw = row_pk_max_u16(smw);
-            const float smax = fmaxf(h_lo(smw), h_hi(smw));
             float sb, inv_sb;
-            pow2_above(smax, 0x1p-40f, sb, inv_sb);
+            pow2_above_h2(smw, true, sb, inv_sb);
             float inv_kf[NHG], beta[NHG];
 #pragma unroll
             for (int hg = 0; hg < NHG; hg++) {
@@ -446,7 +462,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
                 // the low mantissa bits of the sum, ulp = qb sb 2^-22: one fused multiply-add per
                 // element does the scaling, the rounding and the float -> integer conversion.
                 const float magic = three_qb[hg] * sb;
-                const uint32_t cfix = 0x80808080u - __float_as_uint(magic);
+                const uint32_t cfix = opaque(0x80808080u - __float_as_uint(magic));
                 float bacc = 0.0f;
 #pragma unroll
                 for (int ph = 0; ph < 2; ph++) {
@@ -455,7 +471,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
                     for (int y = 0; y < 4; y++) {
                         const uint32_t sw = (y & 2) ? ks[bi][ph].y : ks[bi][ph].x;
                         const float sv = (y & 1) ? h_hi(sw) : h_lo(sw);
-                        X[y] = (__float_as_uint(__builtin_fmaf(qf[hg][ph][y], sv, magic)) + cfix) ^ 0x80808080u;
+                        X[y] = __float_as_uint(__builtin_fmaf(qf[hg][ph][y], sv, magic)) + cfix;
                     }
                     // 4 x 4 byte transpose: limb L of the lane's four consecutive channels
                     const uint32_t U = __builtin_amdgcn_perm(X[1], X[0], 0x05010400u);
@@ -466,9 +482,10 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
                     const uint32_t Y1 = __builtin_amdgcn_perm(W, U, 0x07060302u);
                     const uint32_t Y2 = __builtin_amdgcn_perm(W2, U2, 0x05040100u);
                     uint32_t *dst = ak + hg * 512 + ((ph * 4 + vq) * 16 + 4 * row) * 4 + qa;
-                    dst[0] = Y0;
-                    dst[4] = Y1;
-                    dst[8] = Y2;
+                    // biased bytes -> signed bytes, after the transpose (three words instead of four)
+                    dst[0] = Y0 ^ 0x80808080u;
+                    dst[4] = Y1 ^ 0x80808080u;
+                    dst[8] = Y2 ^ 0x80808080u;
                     bacc = __builtin_amdgcn_fdot2(qh[hg][ph][0], as_h2(kz[bi][ph].x), bacc, false);
                     bacc = __builtin_amdgcn_fdot2(qh[hg][ph][1], as_h2(kz[bi][ph].y), bacc, false);
                     bacc = __builtin_amdgcn_fdot2(qh[hg][ph][0], as_h2(km[bi][ph].x), bacc, false);
@@ -525,9 +542,9 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
             for (int gam = 0; gam < NG; gam++) svw = pk_max_u16(svw, vm[k][gam]);
         svw = row_pk_max_u16(svw);
         float sbv, inv_sbv;
-        pow2_above(h_lo(svw), 0x1p-40f, sbv, inv_sbv);
+        pow2_above_h2(svw, false, sbv, inv_sbv);
         const float vmagic = 3.0f * sbv; // p <= 1, scale < sbv: same construction as on the key side
-        const uint32_t vfix = 0x80808080u - __float_as_uint(vmagic);
+        const uint32_t vfix = opaque(0x80808080u - __float_as_uint(vmagic));
 
         // ---- softmax bookkeeping; zero and mean terms of the value side
         float p[NHG][4], alpha[NHG], o_scale[NHG], psum_b[NHG][NBC];
@@ -571,13 +588,12 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
 #pragma unroll
                     for (int k = 0; k < 4; k++) {
                         const uint32_t X = (__float_as_uint(__builtin_fmaf(p[hg][k], h_lo(vm[k][gam]), vmagic)) + vfix) ^ 0x80808080u;
-                        // byte transpose across the quad: lane with quad position L ends up with limb L
-                        // of the quad's four consecutive tokens
-                        const uint32_t P = dpp_u<0xB1>(X);
-                        const uint32_t T = __builtin_amdgcn_perm(P, X, sel1);
-                        const uint32_t Q = dpp_u<0x4E>(T);
-                        const uint32_t Y = __builtin_amdgcn_perm(Q, T, sel2);
-                        av[(hg * NGP + gl) * 256 + k * 64 + (4 * row + qa) * 4 + vq] = Y;
+                        // limb L of token 4 vq + qa of tile k is byte qa of word (4 row + L) * 4 + vq:
+                        // three byte stores (the LDS port is idle, the vector ALU is not)
+                        unsigned char *o8 = (unsigned char *)(av + (hg * NGP + gl) * 256 + k * 64 + (4 * row) * 4 + vq) + qa;
+                        o8[0] = (unsigned char)X;
+                        o8[16] = (unsigned char)(X >> 8);
+                        o8[32] = (unsigned char)(X >> 16);
                     }
                 }
             wave_lds_fence();
