@@ -114,9 +114,10 @@ typedef struct kv_cache kv_cache; /* opaque host-side descriptor */
 kv_status kv_cache_bytes(const kv_config *cfg, int32_t layer, size_t *bytes);
 
 /* Size of the workspace kv_decode_attn needs for any length up to max_tokens: the per-split partial
- * results, and, with KV_MEAN_CROSS_HEAD, three float arrays of about 2 * batch * n_q_heads *
- * max_tokens elements through which the dense mean terms pass (the queries' products with the key
- * mean of every token, and the softmax weights for the value mean). */
+ * results, and, with KV_MEAN_CROSS_HEAD, float arrays of about 2 * batch * n_q_heads * max_tokens
+ * elements through which the dense mean terms pass (the queries' products with the key mean of
+ * every token, the softmax weights for the value mean) plus batch * n_q_heads * ranges * head_dim
+ * for the value mean's share of the output per token range (ranges <= 768 / batch, at most 256). */
 kv_status kv_workspace_bytes(const kv_config *cfg, size_t *bytes);
 
 /* Build the host descriptor.  layer_dev_ptrs: host array of n_layers device pointers, each at

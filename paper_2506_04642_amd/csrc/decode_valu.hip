@@ -341,22 +341,30 @@ template <int KB, int VB> __global__ __launch_bounds__(kThreads) void decode_spl
     }
 }
 
-// out[b, head] = sum_j o_j 2^(m_j - M) / sum_j l_j 2^(m_j - M),  M = max_j m_j.
-// One wave per (unit, query head); a lane owns two channels.  The order of the sums is fixed.
+// Cross-split merge (flash decoding, App. A):
+//   out[b, head] = sum_j o_j 2^(m_j - M) / sum_j l_j 2^(m_j - M),  M = max_j m_j.
+// One workgroup per query head, a lane owns two channels; wave w adds up the
+// splits w, w + 4, ... in rising order and the four sums are added in wave order, so the result
+// does not depend on timing.  A long-context launch has a hundred splits per head and few heads:
+// the loads of a wave are independent and issued several splits at a time.
 __global__ __launch_bounds__(256) void merge_kernel(DecodeArgs a)
 {
+    __shared__ float red[4][3][64];
+    __shared__ float mx[4];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int uq = blockIdx.x * 4 + wave; // (unit, head-in-group)
-    if (uq >= a.batch * a.n_q_heads) return;
+    const int uq = blockIdx.x; // (unit, head-in-group)
     const int u = uq / a.g, i = uq % a.g;
     const int ns = a.n_splits;
     const float *base = a.ws + (long long)uq * ns * kPartialStride;
     float M = -INFINITY;
-    for (int j = lane; j < ns; j += 64) M = fmaxf(M, base[j * kPartialStride + kHeadDim]);
+    for (int j = threadIdx.x; j < ns; j += 256) M = fmaxf(M, base[j * kPartialStride + kHeadDim]);
     M = wave_max(M);
+    if (lane == 0) mx[wave] = M;
+    __syncthreads();
+    M = fmaxf(fmaxf(mx[0], mx[1]), fmaxf(mx[2], mx[3]));
     float n0 = 0.0f, n1 = 0.0f, den = 0.0f;
-#pragma unroll 4
-    for (int j = 0; j < ns; j++) {
+#pragma unroll 8
+    for (int j = wave; j < ns; j += 4) {
         const float *pj = base + j * kPartialStride;
         const float w = pj[kHeadDim] == -INFINITY ? 0.0f : exp2f(pj[kHeadDim] - M);
         const float2 o = *(const float2 *)(pj + 2 * lane);
@@ -364,6 +372,24 @@ __global__ __launch_bounds__(256) void merge_kernel(DecodeArgs a)
         n1 += o.y * w;
         den += pj[kHeadDim + 1] * w;
     }
+    // cross-head mean: the value mean plane's share, already relative to M (one term per range)
+    if (a.xo && a.n_blocks > 0) {
+        const float *xb = a.xo + (long long)uq * a.n_xr * kHeadDim;
+#pragma unroll 8
+        for (int r = wave; r < a.n_xr; r += 4) {
+            const float2 o = *(const float2 *)(xb + r * kHeadDim + 2 * lane);
+            n0 += o.x;
+            n1 += o.y;
+        }
+    }
+    red[wave][0][lane] = n0;
+    red[wave][1][lane] = n1;
+    red[wave][2][lane] = den;
+    __syncthreads();
+    if (wave != 0) return;
+    n0 = ((red[0][0][lane] + red[1][0][lane]) + red[2][0][lane]) + red[3][0][lane];
+    n1 = ((red[0][1][lane] + red[1][1][lane]) + red[2][1][lane]) + red[3][1][lane];
+    den = ((red[0][2][lane] + red[1][2][lane]) + red[2][2][lane]) + red[3][2][lane];
     const int b = u / a.n_kv_heads, h = u % a.n_kv_heads;
     float2 r;
     // a sequence that holds no token (every split empty, M == -inf) gives zeros
@@ -411,7 +437,7 @@ hipError_t launch_decode_split_valu(const DecodeArgs &a, hipStream_t s)
 
 hipError_t launch_decode_merge(const DecodeArgs &a, hipStream_t s)
 {
-    dim3 grid((a.batch * a.n_q_heads + 3) / 4);
+    dim3 grid(a.batch * a.n_q_heads);
     (void)hipGetLastError(); // drop any stale error left by earlier runtime calls of this thread
     hipLaunchKernelGGL(merge_kernel, grid, dim3(256), 0, s, a);
     return note_launch(hipGetLastError());

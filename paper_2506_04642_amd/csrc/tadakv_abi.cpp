@@ -154,13 +154,32 @@ int worst_splits(const kv_config &c)
 }
 
 // Cross-head mean on the matrix-core path: behind the partials (sized for the largest split count)
-// the workspace holds xs and xp, [batch][Hq][max_tokens] floats each, and xmc,
-// [batch][Hq][max_tokens / 64 + 1] floats.
+// the workspace holds xs and xp, [batch][Hq][max_tokens] floats each, xmc,
+// [batch][Hq][max_tokens / 64 + 1] floats, and xo, [batch][Hq][ranges][128] floats.
+// Token ranges of the value-mean product: one resident round of workgroups per launch (three per
+// compute unit on 256 units), at least four chunks each.
+int xhead_range_cap(const kv_config &c)
+{
+    int r = 768 / c.batch;
+    return r < 1 ? 1 : (r > 256 ? 256 : r);
+}
+int xhead_ranges(const kv_config &c, int n_blocks)
+{
+    const int chunks = (int)(((long long)n_blocks * c.group_tokens + 63) / 64);
+    int r = chunks / 4;
+    if (r > xhead_range_cap(c)) r = xhead_range_cap(c);
+    return r < 1 ? 1 : r;
+}
 size_t xhead_offset(const kv_config &c) { return (size_t)align_up((long long)workspace_need(c, worst_splits(c)), 256); }
+size_t xhead_xo_offset(const kv_config &c)
+{
+    const size_t rows = (size_t)c.batch * c.n_q_heads;
+    return (size_t)align_up((long long)(xhead_offset(c) + rows * ((size_t)2 * c.max_tokens + c.max_tokens / 64 + 1) * sizeof(float)), 256);
+}
 size_t xhead_total(const kv_config &c)
 {
     const size_t rows = (size_t)c.batch * c.n_q_heads;
-    return xhead_offset(c) + rows * ((size_t)2 * c.max_tokens + c.max_tokens / 64 + 1) * sizeof(float);
+    return xhead_xo_offset(c) + rows * xhead_range_cap(c) * kHeadDim * sizeof(float);
 }
 
 kv_status layer_ok(const kv_cache *k, int layer)
@@ -233,6 +252,8 @@ kv_status bind_workspace(const kv_cache *k, DecodeArgs *a, void *workspace, size
         a->xs = (float *)((unsigned char *)workspace + k->xhead_off);
         a->xp = a->xs + rows * c.max_tokens;
         a->xmc = a->xp + rows * c.max_tokens;
+        a->xo = (float *)((unsigned char *)workspace + xhead_xo_offset(c));
+        a->n_xr = xhead_ranges(c, a->n_blocks);
     }
     return KV_OK;
 }

@@ -58,9 +58,13 @@ struct DecodeArgs {
     // cross-head mean on the matrix-core path: the dense mean terms go through three arrays in the
     // workspace (null otherwise).  xs [batch][Hq][tcap]: q . mean_K of every packed token;
     // xp [batch][Hq][tcap]: softmax weight of every packed token relative to its chunk's maximum;
-    // xmc [batch][Hq][tcap / 64]: that maximum (exp2 domain) per 64-token chunk.
+    // xmc [batch][Hq][tcap / 64 + 1]: that maximum (exp2 domain) per 64-token chunk.
     float *xs, *xp, *xmc;
     int tcap;
+    // xo [batch][Hq][n_xr][128]: the value mean plane's share of the output, per range of chunks,
+    // relative to the head's largest split maximum; the merge adds the ranges up
+    float *xo;
+    int n_xr;
     // sequences of different lengths: n_blocks and r above are the maxima, the kernels take each
     // sequence's own counts from these (ragged == 0: every sequence has n_blocks and r)
     int ragged;

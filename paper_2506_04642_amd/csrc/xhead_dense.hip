@@ -8,9 +8,9 @@
 // The deviation terms run on the matrix cores inside the split kernel; the two mean terms are
 // plain dense products against a 16-bit stream that every head of the sequence shares:
 //   xhead_scores_kernel : xs[b][i][t] = q_i . m_K[b,t,:]            for every packed token, before the split kernel
-//   xhead_values_kernel : partial O[u, i, split] += sum_t w_t m_V[b,t,:]   after it, before the merge
+//   xhead_values_kernel : xo[b][i][range] = sum_{t in range} w_t m_V[b,t,:]   after it, before the merge
 // where w_t = p_t 2^(mc - M): p_t is the weight the split kernel wrote relative to its chunk's
-// maximum mc, and M the split's final running maximum (both in the exp2 domain).
+// maximum mc, and M the largest of the head's split maxima (both in the exp2 domain).
 #include "tadakv_internal.h"
 #include <hip/hip_fp16.h>
 #include <type_traits>
@@ -100,58 +100,72 @@ __global__ __launch_bounds__(kThreads) void xhead_scores_kernel(DecodeArgs a)
     }
 }
 
-// One workgroup per (unit, split).  The chunks of a split are the ones the split kernel gave it
-// (chunk sp + n_splits j of the unit).  Per chunk the workgroup puts the 64 value-mean rows and
-// the weights of the unit's query heads (as a binary16 pair hi + lo, so that nothing is lost) in
-// LDS; wave v then owns channels 32 v .. 32 v + 31 and accumulates
+// One workgroup per (sequence, range of 64-token chunks), all query heads of the sequence at once:
+// the value mean plane is shared by the sequence's kv heads, so its rows are read once.  Per
+// chunk the workgroup puts the 64 value-mean rows and the weights of the query heads (as a
+// binary16 pair hi + lo, so that nothing is lost) in LDS; wave v then owns channels
+// 32 v .. 32 v + 31 and accumulates
 //   D[head][channel] += W[head][token] . M[token][channel]
 // with v_mfma_f32_16x16x32_f16 (A = weights: row = head, 8 consecutive tokens per lane; B = mean:
-// column = channel, the same 8 tokens gathered from 8 rows of the LDS tile).
+// column = channel, the same 8 tokens gathered from 8 rows of the LDS tile).  The weights are
+// brought to the head's largest split maximum M (the one the merge uses):
+//   w_t = p_t 2^(mc - M),  p_t relative to the chunk maximum mc as the split kernel wrote it,
+// so the result needs no further factor and the merge adds it to its numerator.
 // (Tried: waves that stage their own 64 x 32 slab and never meet at a barrier -- a row per lane
-// makes every load instruction touch 64 cache lines, and the kernel ran at half the speed.)
+// makes every load instruction touch 64 cache lines, and the kernel ran at half the speed.  One
+// workgroup per (kv head, split): the plane went through L2 once per kv head, 127 us per layer
+// on the full-cache workload.)
 constexpr int kMvStride = 132; // halfs per LDS row of the mean tile: rows 8 apart start in different banks
 constexpr int kWStride = 72;   // halfs per LDS row of the weights
 
+template <int MT> // 16-head tiles: ceil(Hq / 16)
 __global__ __launch_bounds__(kThreads) void xhead_values_kernel(DecodeArgs a)
 {
+    constexpr int NR = 4 * MT; // heads per thread in the weight staging
     __shared__ __attribute__((aligned(16))) _Float16 mvs[64 * kMvStride];
-    __shared__ __attribute__((aligned(16))) _Float16 whi[16 * kWStride], wlo[16 * kWStride];
+    __shared__ __attribute__((aligned(16))) _Float16 whi[16 * MT * kWStride], wlo[16 * MT * kWStride];
+    __shared__ float Mh[64];
     const LayerGeom &gm = a.geom;
-    // Workgroups are handed to the 8 XCDs in turn (index % 8), each XCD with an L2 of its own.  All
-    // kv heads of one (sequence, split) read the same rows of the value mean plane, so they are
-    // given indices 8 apart: same XCD, one fetch from memory, the other heads hit its L2.
-    const int ns = a.n_splits, g = a.g;
-    const int xr = blockIdx.x >> 3, h = xr % a.n_kv_heads;
-    const int pair = (xr / a.n_kv_heads) * 8 + (blockIdx.x & 7); // (sequence, split) number
-    if (pair >= a.batch * ns) return;
-    const int b = pair / ns, sp = pair - b * ns, u = b * a.n_kv_heads + h;
+    const int ns = a.n_splits, Hq = a.n_q_heads;
+    const int b = blockIdx.y, rg = blockIdx.x;
     const int nbc = 64 / gm.G > 0 ? 64 / gm.G : 1;
-    const int chunks_total = (seq_blocks(a, b) + nbc - 1) / nbc;
+    const int chunks_total = (seq_blocks(a, b) + nbc - 1) / nbc;   // of this sequence
+    const int chunks_max = (a.n_blocks + nbc - 1) / nbc;           // of the longest one: fixes the ranges
+    const int cpr = (chunks_max + a.n_xr - 1) / a.n_xr;
+    const int c0 = rg * cpr, c1 = c0 + cpr < chunks_total ? c0 + cpr : chunks_total;
     const int T = seq_blocks(a, b) * gm.G;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, kg = lane >> 4;
     const int ncap = a.tcap / 64 + 1;
-    for (int e = tid; e < 16 * kWStride; e += kThreads) whi[e] = wlo[e] = (_Float16)0.0f;
+    for (int e = tid; e < 16 * MT * kWStride; e += kThreads) whi[e] = wlo[e] = (_Float16)0.0f;
+    if (tid < 64) {
+        float M = -INFINITY;
+        if (tid < Hq)
+            for (int sp = 0; sp < ns; sp++)
+                M = fmaxf(M, a.ws[(((long long)b * Hq + tid) * ns + sp) * kPartialStride + kHeadDim]);
+        Mh[tid] = M;
+    }
+    __syncthreads();
 
-    // weight staging: thread handles (head tid / 64 [+ 4], token tid % 64) of the chunk
+    // weight staging: thread handles (head tid / 64 + 4 r, token tid % 64) of the chunk
     const int wi = tid >> 6, wt_tok = tid & 63;
-    float Msp[2];
-    long long wq[2];
+    float Mq[NR];
+    long long wq[NR];
 #pragma unroll
-    for (int r = 0; r < 2; r++) {
-        const int i = wi + 4 * r < g ? wi + 4 * r : 0;
-        Msp[r] = a.ws[((long long)(u * g + i) * ns + sp) * kPartialStride + kHeadDim];
-        wq[r] = (long long)b * a.n_q_heads + h * g + i;
+    for (int r = 0; r < NR; r++) {
+        const int i = wi + 4 * r < Hq ? wi + 4 * r : 0;
+        Mq[r] = Mh[i];
+        wq[r] = (long long)b * Hq + i;
     }
     // mean tile staging: thread moves the 16-byte pieces tid + 256 k (row = piece / 16).
     // value plane of this sequence: token t sits (t + (t rounded down to its block)) rows of 128 in
     const uint16_t *vplane = (const uint16_t *)(a.layer + gm.xmean_off) + ((long long)b * gm.NB * 2 + 1) * gm.G * kHeadDim;
     const int gmask = ~(gm.G - 1);
     uint4 mreg[4];
-    float xpv[2], xmv[2];
+    float xpv[NR], xmv[NR];
     auto fetch = [&](int c) {
 #pragma unroll
-        for (int r = 0; r < 2; r++) {
+        for (int r = 0; r < NR; r++) {
             const int t = c * 64 + wt_tok;
             xpv[r] = t < T ? a.xp[wq[r] * a.tcap + t] : 0.0f;
             xmv[r] = a.xmc[wq[r] * ncap + c];
@@ -162,15 +176,17 @@ __global__ __launch_bounds__(kThreads) void xhead_values_kernel(DecodeArgs a)
             mreg[k] = t < T ? *(const uint4 *)(vplane + (long long)(t + (t & gmask)) * kHeadDim + (p & 15) * 8) : uint4{0u, 0u, 0u, 0u};
         }
     };
-    v4f acc[2] = {{0.0f, 0.0f, 0.0f, 0.0f}, {0.0f, 0.0f, 0.0f, 0.0f}};
-    if (sp < chunks_total) fetch(sp);
-    for (int c = sp; c < chunks_total; c += ns) {
+    v4f acc[MT][2];
+#pragma unroll
+    for (int mt = 0; mt < MT; mt++) acc[mt][0] = acc[mt][1] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+    if (c0 < c1) fetch(c0);
+    for (int c = c0; c < c1; c++) {
         __syncthreads(); // the previous chunk's tiles have been read
 #pragma unroll
-        for (int r = 0; r < 2; r++) {
+        for (int r = 0; r < NR; r++) {
             const int i = wi + 4 * r;
-            if (i < g) {
-                const float wt = xpv[r] * exp2f(xmv[r] - Msp[r]);
+            if (i < Hq) {
+                const float wt = xpv[r] * exp2f(xmv[r] - Mq[r]);
                 const _Float16 hi = (_Float16)wt;
                 whi[i * kWStride + wt_tok] = hi;
                 wlo[i * kWStride + wt_tok] = (_Float16)(wt - (float)hi);
@@ -183,31 +199,39 @@ __global__ __launch_bounds__(kThreads) void xhead_values_kernel(DecodeArgs a)
             dst[0] = uint2{mreg[k].x, mreg[k].y};
             dst[1] = uint2{mreg[k].z, mreg[k].w};
         }
-        if (c + ns < chunks_total) fetch(c + ns);
+        if (c + 1 < c1) fetch(c + 1);
         __syncthreads();
 #pragma unroll
         for (int ks = 0; ks < 2; ks++) {
-            const v8h ahi = *(const v8h *)(whi + n * kWStride + 32 * ks + 8 * kg);
-            const v8h alo = *(const v8h *)(wlo + n * kWStride + 32 * ks + 8 * kg);
+            v8h bm[2];
 #pragma unroll
             for (int cc = 0; cc < 2; cc++) {
-                v8h bm;
                 const _Float16 *col = mvs + (32 * ks + 8 * kg) * kMvStride + 32 * wave + 16 * cc + n;
 #pragma unroll
-                for (int j = 0; j < 8; j++) bm[j] = col[j * kMvStride];
-                acc[cc] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ahi, bm, acc[cc], 0, 0, 0);
-                acc[cc] = __builtin_amdgcn_mfma_f32_16x16x32_f16(alo, bm, acc[cc], 0, 0, 0);
+                for (int j = 0; j < 8; j++) bm[cc][j] = col[j * kMvStride];
+            }
+#pragma unroll
+            for (int mt = 0; mt < MT; mt++) {
+                const v8h ahi = *(const v8h *)(whi + (16 * mt + n) * kWStride + 32 * ks + 8 * kg);
+                const v8h alo = *(const v8h *)(wlo + (16 * mt + n) * kWStride + 32 * ks + 8 * kg);
+#pragma unroll
+                for (int cc = 0; cc < 2; cc++) {
+                    acc[mt][cc] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ahi, bm[cc], acc[mt][cc], 0, 0, 0);
+                    acc[mt][cc] = __builtin_amdgcn_mfma_f32_16x16x32_f16(alo, bm[cc], acc[mt][cc], 0, 0, 0);
+                }
             }
         }
     }
-    // D: lane holds heads 4 kg .. 4 kg + 3 of channel 32 wave + 16 cc + n
+    // D: lane holds heads 16 mt + 4 kg .. + 3 of channel 32 wave + 16 cc + n; an empty range stores zeros
 #pragma unroll
-    for (int cc = 0; cc < 2; cc++)
+    for (int mt = 0; mt < MT; mt++)
 #pragma unroll
-        for (int j = 0; j < 4; j++) {
-            const int i = 4 * kg + j;
-            if (i < g) a.ws[((long long)(u * g + i) * ns + sp) * kPartialStride + 32 * wave + 16 * cc + n] += acc[cc][j];
-        }
+        for (int cc = 0; cc < 2; cc++)
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                const int i = 16 * mt + 4 * kg + j;
+                if (i < Hq) a.xo[(((long long)b * Hq + i) * a.n_xr + rg) * kHeadDim + 32 * wave + 16 * cc + n] = acc[mt][cc][j];
+            }
 }
 
 } // namespace
@@ -229,12 +253,13 @@ hipError_t launch_xhead_scores(const DecodeArgs &a, hipStream_t s)
 hipError_t launch_xhead_values(const DecodeArgs &a, hipStream_t s)
 {
     if (a.n_blocks == 0) return hipSuccess;
-    if (a.batch * a.n_kv_heads > 65535) return hipErrorInvalidValue;
-    const long long pairs8 = ((long long)a.batch * a.n_splits + 7) / 8;
-    if (pairs8 * 8 * a.n_kv_heads > 0x7FFFFFFF) return hipErrorInvalidValue;
-    dim3 grid((unsigned)(pairs8 * 8 * a.n_kv_heads));
+    if (a.batch > 65535 || a.n_q_heads > 64 || a.n_xr < 1 || !a.xo) return hipErrorInvalidValue;
+    dim3 grid(a.n_xr, a.batch);
+    const int mt = (a.n_q_heads + 15) / 16;
     (void)hipGetLastError(); // drop any stale error left by earlier runtime calls of this thread
-    hipLaunchKernelGGL(xhead_values_kernel, grid, dim3(kThreads), 0, s, a);
+    if (mt <= 1) hipLaunchKernelGGL(xhead_values_kernel<1>, grid, dim3(kThreads), 0, s, a);
+    else if (mt <= 2) hipLaunchKernelGGL(xhead_values_kernel<2>, grid, dim3(kThreads), 0, s, a);
+    else hipLaunchKernelGGL(xhead_values_kernel<4>, grid, dim3(kThreads), 0, s, a);
     return note_launch(hipGetLastError());
 }
 
