@@ -1007,8 +1007,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ?
 // forms the deviations and emits metadata, codes and words half by half.  With a per-channel
 // mean m the extrema of the deviations are those of the raw values moved by m: rounding is
 // monotone, so min_t fl(x_t - m) = fl(min_t x_t - m).
-template <int GC, int BITS>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 8))) void flush_wave64_kernel(AppendArgs a, int n_items)
+template <int GC, int BITS, bool ROPE>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ? 2 : 3, 8))) void flush_wave64_kernel(AppendArgs a, int n_items)
 {
     constexpr int G = 64;
     constexpr int NGV = kHeadDim / GC;
@@ -1047,6 +1047,12 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 8))
                     x[j][2 * k] = widen16((uint16_t)(wv[k] & 0xFFFFu), gm.dtype);
                     x[j][2 * k + 1] = widen16((uint16_t)(wv[k] >> 16), gm.dtype);
                 }
+            }
+            if (ROPE && which == 0) {
+                // both passes turn the rows the same way, so they see the same values
+                const int tn0 = fb * G + 32 * half + 8 * tg - a.r_old; // this lane's first token in the call's input
+                if (gm.dtype == 1) rope_in_lanes<1>(x, a, tn0, lane);
+                else rope_in_lanes<0>(x, a, tn0, lane);
             }
             if (mode == 1) {
 #pragma unroll
@@ -1289,14 +1295,14 @@ template <int GC, int BITS, bool ROPE> hipError_t launch_flush_wave(const Append
     return note_launch(hipGetLastError());
 }
 
-template <int GC, int BITS> hipError_t launch_flush_wave64(const AppendArgs &a, hipStream_t s)
+template <int GC, int BITS, bool ROPE> hipError_t launch_flush_wave64(const AppendArgs &a, hipStream_t s)
 {
     const int U = a.batch * a.n_kv_heads;
     const long long items = (long long)a.n_flush_blocks * U * 2;
     if (items > 0x7FFFFFFF) return hipErrorInvalidValue;
     static const int slots = [] {
         int per_cu = 0, dev = 0, cus = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, flush_wave64_kernel<GC, BITS>, kThreads, 0) != hipSuccess ||
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, flush_wave64_kernel<GC, BITS, ROPE>, kThreads, 0) != hipSuccess ||
             hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
             return 0;
@@ -1305,7 +1311,7 @@ template <int GC, int BITS> hipError_t launch_flush_wave64(const AppendArgs &a, 
     if (slots < 1) return hipErrorInvalidValue;
     const long long want = (items + kThreads / 64 - 1) / (kThreads / 64);
     const int grid = want < slots ? (int)want : slots;
-    hipLaunchKernelGGL((flush_wave64_kernel<GC, BITS>), dim3(grid), dim3(kThreads), 0, s, a, (int)items);
+    hipLaunchKernelGGL((flush_wave64_kernel<GC, BITS, ROPE>), dim3(grid), dim3(kThreads), 0, s, a, (int)items);
     return note_launch(hipGetLastError());
 }
 
@@ -1331,12 +1337,14 @@ hipError_t launch_flush(const AppendArgs &a, hipStream_t s)
         return gc == 32 ? TADAKV_WAVE(32, false) : gc == 64 ? TADAKV_WAVE(64, false) : TADAKV_WAVE(128, false);
 #undef TADAKV_WAVE
     }
-    if (a.geom.G == 64 && kb == a.geom.v_bits && kb != 16 && a.rope == 0) {
+    if (a.geom.G == 64 && kb == a.geom.v_bits && kb != 16) {
         // blocks of 64 tokens: the same wave kernel in two passes over two halves
         const int gc = a.geom.Gc;
-#define TADAKV_WAVE64(GCV) \
-    (kb == 2 ? launch_flush_wave64<GCV, 2>(a, s) : kb == 4 ? launch_flush_wave64<GCV, 4>(a, s) : launch_flush_wave64<GCV, 8>(a, s))
-        return gc == 32 ? TADAKV_WAVE64(32) : gc == 64 ? TADAKV_WAVE64(64) : TADAKV_WAVE64(128);
+#define TADAKV_WAVE64(GCV, R)                                                                        \
+    (kb == 2 ? launch_flush_wave64<GCV, 2, R>(a, s) : kb == 4 ? launch_flush_wave64<GCV, 4, R>(a, s) \
+                                                             : launch_flush_wave64<GCV, 8, R>(a, s))
+        if (a.rope != 0) return gc == 32 ? TADAKV_WAVE64(32, true) : gc == 64 ? TADAKV_WAVE64(64, true) : TADAKV_WAVE64(128, true);
+        return gc == 32 ? TADAKV_WAVE64(32, false) : gc == 64 ? TADAKV_WAVE64(64, false) : TADAKV_WAVE64(128, false);
 #undef TADAKV_WAVE64
     }
     if (a.geom.G == 32) return launch_flush_gc<32>(a, s);

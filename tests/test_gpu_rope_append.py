@@ -82,6 +82,22 @@ def test_rope_append_mean_modes(kv, oracle, mode):
         check_attention(gpu, orc, layer, synth.make_q(320 + layer, 2, 8, 128, BF16), BF16)
 
 
+@pytest.mark.parametrize("pairing", [HALF, INTER])
+@pytest.mark.parametrize("mode", [CHAN, CROSS])
+@pytest.mark.parametrize("bits", [2, 4, 8])
+def test_rope_append_blocks_of_64(kv, oracle, bits, mode, pairing):
+    """Blocks of 64 tokens with one width for keys and values (the two-pass wave quantiser):
+    chunks that leave rows waiting in the residual buffer, then whole blocks in one call."""
+    print("case rope_blocks64 bits=%d mode=%d pairing=%d" % (bits, mode, pairing), flush=True)
+    T = 64 * 4 + 21
+    gpu, orc = make_pair(kv, oracle, B=2, Hq=8, Hkv=2, T_max=384, G=64, Gc=64, R=64, dtype=BF16, mode=mode,
+                         k_bits=(bits,))
+    k, v = synth.make_kv(330 + bits, 2, T, 2, 128, BF16)
+    rope_append_both(gpu, orc, 0, k, v, BF16, pairing, [17, 50, 0, T - 67], pos0=777)
+    check_bytes(gpu, orc, 0)
+    check_attention(gpu, orc, 0, synth.make_q(330 + bits, 2, 8, 128, BF16), BF16)
+
+
 def test_rope_append_equals_rotating_first(kv, oracle):
     """The fused call stores what a separate rotation (here: the oracle's) followed by the plain
     append stores; strided input views are accepted."""
