@@ -23,17 +23,19 @@ import numpy as np
 WIDTHS = (2, 4, 8)
 
 
-def bytes_per_token(head_dim: int, group_tokens: int, group_channels: int, mean_mode: int = 0) -> Dict[int, float]:
+def bytes_per_token(head_dim: int, group_tokens: int, group_channels: int, mean_mode: int = 0,
+                    n_kv_heads: int = 8) -> Dict[int, float]:
     """Stored bytes per (kv head, token) at each width, metadata included (16 -> raw).  Mirrors the
     record of the storage format: codes for K and V, K scale/zero per channel and block, V scale/zero
-    per token and channel group, and (per-channel block mean mode) one binary16 mean per channel and
-    block for K and for V."""
+    per token and channel group, and the mean: one binary16 value per channel and block for K and
+    for V (per-channel block mean), or a kv head's share of the two binary16 mean vectors per
+    token (mean over the kv heads, Eq. 1-2)."""
     d, G, Gc = head_dim, group_tokens, group_channels
     out = {16: 2.0 * d * 2}
     for b in WIDTHS:
         codes = 2.0 * d * b / 8
         meta = 2 * 2.0 * d / G + 2 * 2.0 * d / Gc
-        mean = 2 * 2.0 * d / G if mean_mode == 0 else 0.0
+        mean = 2 * 2.0 * d / G if mean_mode == 0 else (2 * 2.0 * d / n_kv_heads if mean_mode == 1 else 0.0)
         out[b] = codes + meta + mean
     return out
 
@@ -49,7 +51,7 @@ def layer_recipe(seed: int, layer: int, n_layers: int) -> Tuple[int, float]:
 
 def measure_layer_errors(n_layers: int, *, seed: int = 0, batch: int = 2, n_q_heads: int = 8, n_kv_heads: int = 2,
                          context: int = 1024, group: int = 32, dtype: int = 1, mean_mode: int = 0,
-                         device: str = "cuda:0") -> np.ndarray:
+                         shared_sigma: float = 0.0, device: str = "cuda:0") -> np.ndarray:
     """err[l, i]: root-mean-square error of the decode-attention output of layer l stored at
     WIDTHS[i] against the same layer stored at 16 bits, relative to the rms of that output.
     Everything runs through the C ABI (quantise-append, decode attention)."""
@@ -66,7 +68,8 @@ def measure_layer_errors(n_layers: int, *, seed: int = 0, batch: int = 2, n_q_he
     err = np.zeros((n_layers, len(WIDTHS)))
     for l in range(n_layers):
         n_outlier, temperature = layer_recipe(seed, l, n_layers)
-        k, v = synth.make_kv_torch(seed * 1000 + l, batch, context, n_kv_heads, d, dtype, device, n_outlier=n_outlier)
+        k, v = synth.make_kv_torch(seed * 1000 + l, batch, context, n_kv_heads, d, dtype, device, n_outlier=n_outlier,
+                                   shared_sigma=shared_sigma)
         q = synth.make_q_torch(seed * 1000 + l, batch, n_q_heads, d, dtype, device)
         q = (q.float() * temperature).to(q.dtype)
         kv.kv_cache_reset(cache.handle, -1)
@@ -80,6 +83,25 @@ def measure_layer_errors(n_layers: int, *, seed: int = 0, batch: int = 2, n_q_he
             err[l, i] = float((outs[i] - ref).pow(2).mean().sqrt()) / scale
     cache.close()
     return err
+
+
+def mean_mode_table(n_layers: int = 4, *, seed: int = 0, shared_sigma: float = 2.0, **measure_kw) -> Dict[str, list]:
+    """Synthetic analogue of the paper's error comparison with and without mean-centring (Fig. 2):
+    the decode-attention error against the 16-bit cache, averaged over n_layers synthetic layers,
+    for no mean, the per-channel block mean and the mean over kv heads, at 2 / 4 / 8 bits.  The
+    inputs carry a component shared by all kv heads (shared_sigma), which is the structure the
+    paper attributes to real caches; with shared_sigma = 0 the mean over heads has nothing to
+    remove."""
+    out = {}
+    measure_kw.setdefault("n_kv_heads", 8)
+    measure_kw.setdefault("n_q_heads", 32)
+    group = measure_kw.get("group", 32)
+    for name, mode in (("none", 2), ("channel_block", 0), ("cross_head", 1)):
+        err = measure_layer_errors(n_layers, seed=seed, mean_mode=mode, shared_sigma=shared_sigma, **measure_kw)
+        per_token = bytes_per_token(128, group, group, mode, measure_kw["n_kv_heads"])
+        out[name] = {"rel_rms_error": [float(x) for x in err.mean(axis=0)],
+                     "bytes_vs_16bit": [per_token[b] / per_token[16] for b in WIDTHS]}
+    return out
 
 
 def map_cost(err: np.ndarray, bit_map: Sequence[int]) -> float:
@@ -172,7 +194,14 @@ if __name__ == "__main__":
     ap.add_argument("--budget", type=float, default=0.27, help="cache bytes as a fraction of the 16-bit cache")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--candidates", type=int, default=20000)
+    ap.add_argument("--mean-modes", action="store_true",
+                    help="print the error table over mean modes and widths instead of searching")
+    ap.add_argument("--shared-sigma", type=float, default=2.0, help="component common to all kv heads (--mean-modes)")
     a = ap.parse_args()
+    if a.mean_modes:
+        print(json.dumps({"widths": list(WIDTHS), "mean_modes": mean_mode_table(min(a.layers, 8), seed=a.seed,
+                                                                               shared_sigma=a.shared_sigma)}))
+        raise SystemExit(0)
     r = search(a.layers, a.budget, seed=a.seed, n_candidates=a.candidates)
     r["errors"] = np.round(r["errors"], 5).tolist()
     print(json.dumps(r))

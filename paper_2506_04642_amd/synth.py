@@ -98,9 +98,12 @@ def layer_bits(seed: int, n_layers: int, scheme: str = "mixed248"):
 
 
 def make_kv_torch(seed: int, B: int, T: int, H: int, d: int, dtype: int, device, n_outlier: int = 4,
-                  n_drift: int = 0, slope: float = 0.01, t0: int = 0):
+                  n_drift: int = 0, slope: float = 0.01, t0: int = 0, shared_sigma: float = 0.0):
     """Same recipe drawn on the device for shapes too large to ship from the host.
-    Returns torch tensors [B, T, H, d] of the 16-bit dtype."""
+    Returns torch tensors [B, T, H, d] of the 16-bit dtype.  shared_sigma > 0 adds to keys and to
+    values a component N(0, shared_sigma^2) per (sequence, token, channel) that all kv heads have in
+    common (the structure the mean over heads, Eq. 1-2, is meant to remove); 0 leaves the streams
+    of the other parameters untouched."""
     import torch
 
     gen = torch.Generator(device=device)
@@ -113,9 +116,18 @@ def make_kv_torch(seed: int, B: int, T: int, H: int, d: int, dtype: int, device,
     if n_drift:
         t = (torch.arange(T, device=device, dtype=torch.float32) + float(t0))[None, :, None, None]
         k += float(slope) * t * torch.from_numpy(drift).to(device)[None, None]
+    shared = None
+    if shared_sigma > 0.0:
+        gen2 = torch.Generator(device=device)
+        gen2.manual_seed(seed + 15485863)
+        shared = float(shared_sigma) * torch.randn((2, B, T, 1, d), generator=gen2, device=device, dtype=torch.float32)
+        k += shared[0]
     k16 = k.to(tdt)
     del k
-    v16 = torch.randn((B, T, H, d), generator=gen, device=device, dtype=torch.float32).to(tdt)
+    v = torch.randn((B, T, H, d), generator=gen, device=device, dtype=torch.float32)
+    if shared is not None:
+        v += shared[1]
+    v16 = v.to(tdt)
     return k16, v16
 
 

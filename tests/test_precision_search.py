@@ -27,6 +27,13 @@ def test_bytes_per_token_match_the_storage_format():
     assert abs(ratio - 0.3125) < 1e-12 and 0.25 < ratio < 0.35
 
 
+def test_bytes_per_token_cross_head_mean_matches_the_paper_formula():
+    """Sec. 3 memory formula: at 4 bits, 8 kv heads and groups of 32 the cache is
+    1/8 + 4/16 + 2/32 = 43.75 % of the 16-bit cache."""
+    pt = ps.bytes_per_token(128, 32, 32, 1, n_kv_heads=8)
+    assert pt[4] / pt[16] == 1 / 8 + 4 / 16 + 2 / 32
+
+
 @pytest.mark.parametrize("seed", [1, 2, 3])
 @pytest.mark.parametrize("budget", [0.23, 0.27, 0.4, 0.6])
 def test_exact_optimum_equals_brute_force(seed, budget):
@@ -84,3 +91,21 @@ def test_measured_proxy_matches_the_oracle(oracle):
         for i in range(3):
             want[l, i] = np.sqrt(np.mean((outs[i] - outs[3]) ** 2)) / scale
     assert np.allclose(got, want, rtol=1e-3, atol=1e-5), (got, want)
+
+
+@pytest.mark.gpu
+def test_mean_over_heads_removes_a_shared_component():
+    """Synthetic analogue of the paper's error comparison (Fig. 2): with a component common to
+    all kv heads the mean over heads cuts the attention error at every width; without one the
+    deviations only lose the 1/H of the variance that the mean carries."""
+    import torch
+
+    assert torch.cuda.is_available(), "needs the GPU"
+    print("case mean_mode_table", flush=True)
+    shared = ps.mean_mode_table(2, seed=3, shared_sigma=2.0, context=512)
+    plain = ps.mean_mode_table(2, seed=3, shared_sigma=0.0, context=512)
+    for i in range(3):
+        assert shared["cross_head"]["rel_rms_error"][i] < 0.6 * shared["none"]["rel_rms_error"][i]
+        r = plain["cross_head"]["rel_rms_error"][i] / plain["none"]["rel_rms_error"][i]
+        assert 0.75 < r < 1.05
+    assert shared["cross_head"]["bytes_vs_16bit"][1] == 0.4375
