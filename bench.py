@@ -41,6 +41,7 @@ def parse():
     ap.add_argument("--q-heads", type=int, default=32)
     ap.add_argument("--kv-heads", type=int, default=8)
     ap.add_argument("--group", type=int, default=32, help="group size G = Gc")
+    ap.add_argument("--resid", type=int, default=0, help="raw-token buffer length R, a multiple of G (0: R = G; the paper uses 128)")
     ap.add_argument("--scheme", default="mixed248", help="layer bit map: mixed248 or mixed24_8ends")
     ap.add_argument("--seed", type=int, default=2000)
     ap.add_argument("--splits", type=int, default=0, help="force the sequence split count (0 = automatic)")
@@ -76,7 +77,9 @@ def main():
     max_tokens = (T0 + n_dec + 8 + G - 1) // G * G
     bits = synth.layer_bits(args.seed, L, args.scheme)
     mean_mode = {"channel": kv.KV_MEAN_CHANNEL_BLOCK, "cross": kv.KV_MEAN_CROSS_HEAD, "none": kv.KV_MEAN_NONE}[args.mean_mode]
-    cfg = kv.make_config(L, B, Hq, Hkv, d, max_tokens, G, G, G, kv.KV_BF16, mean_mode, bits, bits)
+    R = args.resid if args.resid else G  # raw trailing tokens are compressed R at a time (Sec. 3.3)
+    max_tokens = (max_tokens + R - 1) // R * R
+    cfg = kv.make_config(L, B, Hq, Hkv, d, max_tokens, G, G, R, kv.KV_BF16, mean_mode, bits, bits)
     cache = kv.KVCache(cfg, device=dev, zero=False)
     kv.kv_set_decode_path(cache.handle, args.path)
     if args.splits:
@@ -125,7 +128,7 @@ def main():
         nbytes = 0
         for l in range(L):
             kd, vd = k_dec[l]
-            fused = args.fused_step and cache.lengths(l)[1] + 1 < G  # the token completes no block (R = G)
+            fused = args.fused_step and cache.lengths(l)[1] + 1 < R  # the token does not fill the raw buffer
             if not fused:
                 cache.append(l, kd[:, s:s + 1], vd[:, s:s + 1])
             if events is not None:

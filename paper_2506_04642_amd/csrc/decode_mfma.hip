@@ -642,8 +642,11 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
 
     if (B != 8) __builtin_amdgcn_s_setprio(0);
 
-    // ---- raw residual tokens (Sec. 3.3): wave 0 of the split that is next in turn
-    const bool has_resid = r_seq > 0 && sp == chunks_total % ns;
+    // ---- raw residual tokens (Sec. 3.3) in tiles of 32, dealt to the splits in turn after the
+    // unit's last chunk (wave 0 of a split takes its tiles): with the paper's buffer of 128 tokens
+    // one split alone would add 20 us to the launch
+    const int rt_first = (sp - chunks_total % ns + ns) % ns; // this split's first tile
+    const bool has_resid = rt_first * 32 < r_seq;
     if (has_resid) {
         __syncthreads(); // every wave is out of its main loop; wave 0 may take all of LDS
         if (wave == 0) {
@@ -667,7 +670,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
             // a token appended by this very call: read from the caller's rows and stored in the cache here
             const long long fresh_off = (long long)b * a.fresh_stride_b + (long long)h * a.fresh_stride_h;
             const int t_fresh = a.k_fresh ? r_seq - 1 : -1;
-            for (int t0 = 0; t0 < r_seq; t0 += 32) {
+            for (int t0 = rt_first * 32; t0 < r_seq; t0 += 32 * ns) {
                 const int nt = r_seq - t0 < 32 ? r_seq - t0 : 32;
                 wave_lds_fence();
                 for (int i = lane; i < nt * 16; i += 64) {
