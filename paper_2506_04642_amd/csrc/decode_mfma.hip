@@ -251,8 +251,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
     constexpr int AK_DW = NHG * 512, AV_DW = NHG * NGP * 256;
     constexpr int OPER_DW = AK_DW > AV_DW ? AK_DW : AV_DW;
     constexpr int WAVE_DW = STAGE_DW + OPER_DW;
-    constexpr int RESID_DW = 24576 / 4;    // the residual pass of wave 0 takes this much of the block's LDS
-    constexpr int LDS_DW = NW * WAVE_DW > RESID_DW ? NW * WAVE_DW : RESID_DW;
+    constexpr int LDS_DW = NW * WAVE_DW;
 
     __shared__ __attribute__((aligned(16))) uint32_t lds_all[LDS_DW];
 
@@ -643,114 +642,115 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
     if (B != 8) __builtin_amdgcn_s_setprio(0);
 
     // ---- raw residual tokens (Sec. 3.3) in tiles of 32, dealt to the splits in turn after the
-    // unit's last chunk (wave 0 of a split takes its tiles): with the paper's buffer of 128 tokens
-    // one split alone would add 20 us to the launch
+    // unit's last chunk; wave w of the split takes tokens 8 w .. 8 w + 7 of a tile into its own
+    // online-softmax state, with its own LDS region as scratch (no workgroup barrier)
     const int rt_first = (sp - chunks_total % ns + ns) % ns; // this split's first tile
-    const bool has_resid = rt_first * 32 < r_seq;
-    if (has_resid) {
-        __syncthreads(); // every wave is out of its main loop; wave 0 may take all of LDS
-        if (wave == 0) {
-            unsigned char *L = (unsigned char *)lds_all;
-            constexpr int RS = 264;  // bytes per staged row (33 * 8): rows start in different banks
-            constexpr int NH = 4 * NHG;
-            unsigned char *kraw = L, *vraw = L + 32 * RS;
-            float *qs = (float *)(L + 64 * RS);        // [NH][128]
-            float *spart = qs + NH * 128;               // [2][NH][32]
-            float *pl = spart + 2 * NH * 32;            // [NH][32]
-            static_assert(64 * RS + (NH * 128 + 2 * NH * 32 + NH * 32) * 4 <= RESID_DW * 4, "residual scratch");
+    if (rt_first * 32 + 8 * wave < r_seq) {
+        unsigned char *L = (unsigned char *)lds;
+        constexpr int RS = 264;  // bytes per staged row (33 * 8): rows start in different banks
+        constexpr int NH = 4 * NHG;
+        unsigned char *kraw = L, *vraw = L + 8 * RS;
+        uint16_t *qs = (uint16_t *)(L + 16 * RS);             // [NH][128], the queries as they came
+        float *spart = (float *)(L + 16 * RS + NH * 256);      // [8 channel slices][NH][8 tokens]
+        float *pl = spart + 8 * NH * 8;                        // [NH][8]
+        static_assert(16 * RS + NH * 256 + (8 * NH * 8 + NH * 8) * 4 <= WAVE_DW * 4, "residual scratch");
+        wave_lds_fence();
+#pragma unroll
+        for (int hg = 0; hg < NHG; hg++)
+#pragma unroll
+            for (int ph = 0; ph < 2; ph++)
+#pragma unroll
+                for (int y = 0; y < 4; y++) {
+                    // narrowing a widened 16-bit value is exact
+                    const float qv = qf[hg][ph][y];
+                    const uint16_t q16 = gm.dtype == 1 ? (uint16_t)(__float_as_uint(qv) >> 16)
+                                                       : __half_as_ushort(__float2half_rn(qv));
+                    qs[(4 * hg + row) * 128 + 32 * vq + 16 * ph + 4 * qa + y] = q16;
+                }
+        const unsigned char *kr = a.layer + gm.k_resid_off + (long long)u * gm.R * 256;
+        const unsigned char *vr = a.layer + gm.v_resid_off + (long long)u * gm.R * 256;
+        // a token appended by this very call: read from the caller's rows and stored in the cache here
+        const long long fresh_off = (long long)b * a.fresh_stride_b + (long long)h * a.fresh_stride_h;
+        const int t_fresh = a.k_fresh ? r_seq - 1 : -1;
+        for (int t0 = rt_first * 32 + 8 * wave; t0 < r_seq; t0 += 32 * ns) {
+            const int nt = r_seq - t0 < 8 ? r_seq - t0 : 8;
+            wave_lds_fence();
+            for (int i = lane; i < nt * 16; i += 64) {
+                const int t = i >> 4, ch = i & 15;
+                uint4 kv_, vv_;
+                if (t0 + t == t_fresh) {
+                    kv_ = *(const uint4 *)(a.k_fresh + fresh_off + ch * 8);
+                    vv_ = *(const uint4 *)(a.v_fresh + fresh_off + ch * 8);
+                    *(uint4 *)const_cast<unsigned char *>(kr + (long long)t_fresh * 256 + ch * 16) = kv_;
+                    *(uint4 *)const_cast<unsigned char *>(vr + (long long)t_fresh * 256 + ch * 16) = vv_;
+                } else {
+                    kv_ = *(const uint4 *)(kr + (long long)(t0 + t) * 256 + ch * 16);
+                    vv_ = *(const uint4 *)(vr + (long long)(t0 + t) * 256 + ch * 16);
+                }
+                *(uint2 *)(kraw + t * RS + ch * 16) = uint2{kv_.x, kv_.y};
+                *(uint2 *)(kraw + t * RS + ch * 16 + 8) = uint2{kv_.z, kv_.w};
+                *(uint2 *)(vraw + t * RS + ch * 16) = uint2{vv_.x, vv_.y};
+                *(uint2 *)(vraw + t * RS + ch * 16 + 8) = uint2{vv_.z, vv_.w};
+            }
+            wave_lds_fence();
+            {
+                // lane (token t, slice sl): q . k over channels 16 sl .. 16 sl + 15, every head
+                const int t = lane & 7, sl = lane >> 3;
+                float dn[NH];
+#pragma unroll
+                for (int i = 0; i < NH; i++) dn[i] = 0.0f;
+                if (t < nt) {
+#pragma unroll
+                    for (int c = 0; c < 16; c += 2) {
+                        const uint32_t w = *(const uint32_t *)(kraw + t * RS + (16 * sl + c) * 2);
+                        const float k0 = widen16((uint16_t)(w & 0xFFFFu), gm.dtype);
+                        const float k1 = widen16((uint16_t)(w >> 16), gm.dtype);
+#pragma unroll
+                        for (int i = 0; i < NH; i++) {
+                            const uint32_t qw = *(const uint32_t *)(qs + i * 128 + 16 * sl + c);
+                            dn[i] += widen16((uint16_t)(qw & 0xFFFFu), gm.dtype) * k0 + widen16((uint16_t)(qw >> 16), gm.dtype) * k1;
+                        }
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < NH; i++) spart[(sl * NH + i) * 8 + t] = dn[i];
+            }
+            wave_lds_fence();
+            float pr[NHG], al[NHG], wcr[NHG];
+#pragma unroll
+            for (int hg = 0; hg < NHG; hg++) {
+                const int head = 4 * hg + row;
+                float s[4], p[4];
+                float dot = 0.0f;
+#pragma unroll
+                for (int sl = 0; sl < 8; sl++) dot += spart[(sl * NH + head) * 8 + (n & 7)];
+                s[0] = n < nt ? dot * kScoreScale : -INFINITY;
+                s[1] = s[2] = s[3] = -INFINITY;
+                float mcr;
+                softmax_chunk(s, st[hg], p, al[hg], wcr[hg], mcr);
+                pr[hg] = p[0];
+            }
 #pragma unroll
             for (int hg = 0; hg < NHG; hg++)
+                if (n < nt) pl[(4 * hg + row) * 8 + n] = pr[hg];
+            wave_lds_fence();
 #pragma unroll
-                for (int ph = 0; ph < 2; ph++)
+            for (int hg = 0; hg < NHG; hg++) {
+                float add[8];
 #pragma unroll
-                    for (int y = 0; y < 4; y++)
-                        qs[(4 * hg + row) * 128 + 32 * vq + 16 * ph + 4 * qa + y] = qf[hg][ph][y];
-            const unsigned char *kr = a.layer + gm.k_resid_off + (long long)u * gm.R * 256;
-            const unsigned char *vr = a.layer + gm.v_resid_off + (long long)u * gm.R * 256;
-            // a token appended by this very call: read from the caller's rows and stored in the cache here
-            const long long fresh_off = (long long)b * a.fresh_stride_b + (long long)h * a.fresh_stride_h;
-            const int t_fresh = a.k_fresh ? r_seq - 1 : -1;
-            for (int t0 = rt_first * 32; t0 < r_seq; t0 += 32 * ns) {
-                const int nt = r_seq - t0 < 32 ? r_seq - t0 : 32;
-                wave_lds_fence();
-                for (int i = lane; i < nt * 16; i += 64) {
-                    const int t = i >> 4, ch = i & 15;
-                    uint4 kv_, vv_;
-                    if (t0 + t == t_fresh) {
-                        kv_ = *(const uint4 *)(a.k_fresh + fresh_off + ch * 8);
-                        vv_ = *(const uint4 *)(a.v_fresh + fresh_off + ch * 8);
-                        *(uint4 *)const_cast<unsigned char *>(kr + (long long)t_fresh * 256 + ch * 16) = kv_;
-                        *(uint4 *)const_cast<unsigned char *>(vr + (long long)t_fresh * 256 + ch * 16) = vv_;
-                    } else {
-                        kv_ = *(const uint4 *)(kr + (long long)(t0 + t) * 256 + ch * 16);
-                        vv_ = *(const uint4 *)(vr + (long long)(t0 + t) * 256 + ch * 16);
-                    }
-                    *(uint2 *)(kraw + t * RS + ch * 16) = uint2{kv_.x, kv_.y};
-                    *(uint2 *)(kraw + t * RS + ch * 16 + 8) = uint2{kv_.z, kv_.w};
-                    *(uint2 *)(vraw + t * RS + ch * 16) = uint2{vv_.x, vv_.y};
-                    *(uint2 *)(vraw + t * RS + ch * 16 + 8) = uint2{vv_.z, vv_.w};
-                }
-                wave_lds_fence();
-                {
-                    const int t = lane & 31, half = lane >> 5;
-                    float dn[NH];
+                for (int ct = 0; ct < 8; ct++) add[ct] = 0.0f;
+                for (int t = 0; t < nt; t++) {
+                    const float pv = pl[(4 * hg + row) * 8 + t];
 #pragma unroll
-                    for (int i = 0; i < NH; i++) dn[i] = 0.0f;
-                    if (t < nt) {
-                        for (int c = half * 64; c < half * 64 + 64; c += 2) {
-                            const uint32_t w = *(const uint32_t *)(kraw + t * RS + c * 2);
-                            const float k0 = widen16((uint16_t)(w & 0xFFFFu), gm.dtype);
-                            const float k1 = widen16((uint16_t)(w >> 16), gm.dtype);
-#pragma unroll
-                            for (int i = 0; i < NH; i++) dn[i] += qs[i * 128 + c] * k0 + qs[i * 128 + c + 1] * k1;
-                        }
-#pragma unroll
-                        for (int i = 0; i < NH; i++) spart[(half * NH + i) * 32 + t] = dn[i];
-                    }
-                }
-                wave_lds_fence();
-                float pr[NHG][2], al[NHG], wcr[NHG];
-#pragma unroll
-                for (int hg = 0; hg < NHG; hg++) {
-                    const int head = 4 * hg + row;
-                    float s[4], p[4];
-#pragma unroll
-                    for (int k = 0; k < 4; k++) {
-                        const int t = n + 16 * k;
-                        s[k] = (k < 2 && t < nt)
-                                   ? (spart[head * 32 + t] + spart[(NH + head) * 32 + t]) * kScoreScale
-                                   : -INFINITY;
-                    }
-                    float mcr;
-                    softmax_chunk(s, st[hg], p, al[hg], wcr[hg], mcr);
-                    pr[hg][0] = p[0];
-                    pr[hg][1] = p[1];
+                    for (int ct = 0; ct < 8; ct++)
+                        add[ct] += pv * widen16(*(const uint16_t *)(vraw + t * RS + (16 * ct + n) * 2), gm.dtype);
                 }
 #pragma unroll
-                for (int hg = 0; hg < NHG; hg++)
+                for (int ct = 0; ct < 8; ct++) st[hg].O[ct] = st[hg].O[ct] * al[hg] + wcr[hg] * add[ct];
 #pragma unroll
-                    for (int k = 0; k < 2; k++)
-                        if (n + 16 * k < nt) pl[(4 * hg + row) * 32 + n + 16 * k] = pr[hg][k];
-                wave_lds_fence();
-#pragma unroll
-                for (int hg = 0; hg < NHG; hg++) {
-                    float add[8];
-#pragma unroll
-                    for (int ct = 0; ct < 8; ct++) add[ct] = 0.0f;
-                    for (int t = 0; t < nt; t++) {
-                        const float pv = pl[(4 * hg + row) * 32 + t];
-#pragma unroll
-                        for (int ct = 0; ct < 8; ct++)
-                            add[ct] += pv * widen16(*(const uint16_t *)(vraw + t * RS + (16 * ct + n) * 2), gm.dtype);
-                    }
-#pragma unroll
-                    for (int ct = 0; ct < 8; ct++) st[hg].O[ct] = st[hg].O[ct] * al[hg] + wcr[hg] * add[ct];
-#pragma unroll
-                    for (int gam = 0; gam < 4; gam++) st[hg].Zp[gam] *= al[hg];
-                }
+                for (int gam = 0; gam < 4; gam++) st[hg].Zp[gam] *= al[hg];
             }
         }
-        __syncthreads();
     }
 
     // ---- finish the wave's state and merge the waves: [NHG][10][64] floats at the start of each wave's LDS
