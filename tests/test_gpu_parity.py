@@ -264,6 +264,86 @@ def test_full_cache_shape_sampled_units(kv, oracle, decode_path):
         assert err <= 2e-3
 
 
+def _full_size_sampled(kv, oracle, *, B, Hq, Hkv, G, T, bits, sample, seed, n_drift=0, decode_steps=0):
+    """Fills one layer per bit width at a workload's full size on the GPU, re-does the sampled
+    sequences with the oracle and compares their cache bytes and attention outputs; then
+    `decode_steps` one-call decode steps (append + attend) checked the same way at the end."""
+    import torch
+
+    d, L = 128, len(bits)
+    T_max = (T + decode_steps + G) // G * G + G
+    cfg = kv.make_config(L, B, Hq, Hkv, d, T_max, G, G, G, kv.KV_BF16, kv.KV_MEAN_CHANNEL_BLOCK, list(bits), list(bits))
+    gpu = kv.KVCache(cfg, zero=False)
+    ocfg = oracle.OracleConfig(L, len(sample), Hq, Hkv, d, T_max, G, G, G, BF16, CHAN, list(bits), list(bits))
+    orc = oracle.OracleCache(ocfg)
+    as_u16 = lambda t: t.contiguous().view(torch.int16).numpy().view(np.uint16)
+    for l in range(L):
+        host_k, host_v = [], []
+        for t0 in range(0, T, 8192):
+            n = min(8192, T - t0)
+            k, v = synth.make_kv_torch(seed + 10 * l + t0 // 8192, B, n, Hkv, d, BF16, "cuda:0", n_drift=n_drift, t0=t0)
+            gpu.append(l, k, v)
+            host_k.append(k[list(sample)].cpu())
+            host_v.append(v[list(sample)].cpu())
+        orc.append(l, as_u16(torch.cat(host_k, 1)), as_u16(torch.cat(host_v, 1)))
+    for s in range(decode_steps):
+        for l in range(L):
+            k, v = synth.make_kv_torch(seed + 5000 + 10 * l + s, B, 1, Hkv, d, BF16, "cuda:0", n_drift=n_drift, t0=T + s)
+            q = synth.make_q_torch(seed + 7000 + 10 * l + s, B, Hq, d, BF16, "cuda:0")
+            out = gpu.append_attend(l, k, v, q)
+            orc.append(l, as_u16(k[list(sample)].cpu()), as_u16(v[list(sample)].cpu()))
+            if s == decode_steps - 1:
+                torch.cuda.synchronize()
+                want = orc.attend(l, as_u16(q[list(sample)].cpu()))
+                err = float(np.max(np.abs(out[list(sample)].cpu().numpy().astype(np.float64) - want)))
+                print("  layer %d after %d steps: attention max-abs error %.3e" % (l, decode_steps, err), flush=True)
+                assert err <= 2e-3
+    torch.cuda.synchronize()
+    NB = T_max // G
+    for l in range(L):
+        print("  layer %d (%d-bit) splits=%d" % (l, bits[l], kv.kv_decode_splits(gpu.handle, l)), flush=True)
+        assert gpu.lengths(l) == (orc.packed_len(l), orc.resid_len(l))
+        lay = kv.kv_cache_describe(gpu.handle, l)
+        img = orc.layer_image(l)  # image of a cache that holds only the sampled sequences
+        dev = gpu.layers[l]
+        n_rec = orc.packed_len(l) // G
+        for si, b in enumerate(sample):
+            for h in range(Hkv):
+                g0 = ((b * Hkv + h) * NB) * lay.rec_bytes
+                o0 = ((si * Hkv + h) * NB) * lay.rec_bytes
+                got = dev[g0:g0 + n_rec * lay.rec_bytes].cpu().numpy()
+                want = img["bytes"][o0:o0 + n_rec * lay.rec_bytes]
+                m = img["valid"][o0:o0 + n_rec * lay.rec_bytes]
+                assert np.array_equal(got[m], want[m]), (l, b, h)
+        q = synth.make_q_torch(seed + 77 + l, B, Hq, d, BF16, "cuda:0")
+        out = gpu.attend(l, q)
+        torch.cuda.synchronize()
+        want = orc.attend(l, as_u16(q[list(sample)].cpu()))
+        err = float(np.max(np.abs(out[list(sample)].cpu().numpy().astype(np.float64) - want)))
+        print("  attention max-abs error %.3e" % err, flush=True)
+        assert err <= 2e-3
+    gpu.close()
+
+
+@pytest.mark.parametrize("decode_path", [0], indirect=True, ids=["auto"])
+def test_long_context_full_size(kv, oracle, decode_path):
+    """The 70B-shaped long-context workload at its full size (batch 1, 64 query / 8 kv heads, 131072
+    tokens plus a raw tail, groups of 64, one layer per bit width) in the launch configuration
+    the library picks for it."""
+    print("case long_context_full", flush=True)
+    _full_size_sampled(kv, oracle, B=1, Hq=64, Hkv=8, G=64, T=131072 + 29, bits=(2, 4, 8), sample=(0,), seed=1300)
+
+
+@pytest.mark.parametrize("decode_path", [0], indirect=True, ids=["auto"])
+def test_prefill_then_decode_full_size(kv, oracle, decode_path):
+    """The prefill-then-decode workload at its full batch (64 sequences, 16384-token bulk prefill,
+    drifting key channels, one layer per bit width), two sampled sequences, then 40 one-call decode
+    steps that cross a block boundary."""
+    print("case prefill_decode_full", flush=True)
+    _full_size_sampled(kv, oracle, B=64, Hq=32, Hkv=8, G=32, T=16384, bits=(2, 4, 8), sample=(3, 60), seed=1400,
+                       n_drift=8, decode_steps=40)
+
+
 @pytest.mark.parametrize("decode_path", [0], indirect=True, ids=["auto"])
 def test_full_cache_shape_cross_head_sampled_units(kv, oracle, decode_path):
     """The same launch configuration with the mean over the kv heads (Eq. 1-2): one 4-bit layer,
