@@ -200,6 +200,13 @@ kv_status kv_decode_attn_split(const kv_cache *cache, int32_t layer, const void 
 kv_status kv_decode_attn_merge(const kv_cache *cache, int32_t layer, float *out,
                                const void *workspace, size_t workspace_bytes, void *stream);
 
+/* As kv_decode_attn_merge, with the output narrowed (round to nearest even) to the cache's 16-bit
+ * input type, for callers whose next layer takes 16-bit activations (the attention output O of
+ * Algorithm 1 step 9 feeds a 16-bit projection): split (or the append-and-split call) first, then this.
+ *   out16 : device, [batch, n_q_heads, head_dim] of kv_config.dtype, contiguous, 16-byte aligned */
+kv_status kv_decode_attn_merge16(const kv_cache *cache, int32_t layer, void *out16,
+                                 const void *workspace, size_t workspace_bytes, void *stream);
+
 /* One step of the decode loop in a single call (Algorithm 1 steps 8-9, KVCache.update followed by
  * TaDAFlashAttn): append ONE new token per sequence, then attend over the whole cache including it.
  * Equals kv_quant_append(n_new = 1) followed by kv_decode_attn, bit for bit; where the layer is

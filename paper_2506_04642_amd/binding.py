@@ -30,7 +30,7 @@ KV_MEAN_CHANNEL_BLOCK, KV_MEAN_CROSS_HEAD, KV_MEAN_NONE = 0, 1, 2
 EXPORTS = [
     "kv_cache_bytes", "kv_workspace_bytes", "kv_cache_create", "kv_cache_destroy", "kv_cache_reset",
     "kv_cache_len", "kv_cache_len_seq", "kv_cache_reset_seq", "kv_cache_describe", "kv_quant_append", "kv_quant_append_seq", "kv_rope_quant_append", "kv_append_decode_attn", "kv_append_decode_attn_split", "kv_decode_attn", "kv_decode_attn_split",
-    "kv_decode_attn_merge", "kv_decode_splits", "kv_decode_bytes", "kv_set_decode_path", "kv_set_decode_splits", "kv_strerror", "kv_last_hip_error",
+    "kv_decode_attn_merge", "kv_decode_attn_merge16", "kv_decode_splits", "kv_decode_bytes", "kv_set_decode_path", "kv_set_decode_splits", "kv_strerror", "kv_last_hip_error",
 ]
 
 
@@ -74,6 +74,7 @@ _lib.kv_append_decode_attn.argtypes = [_vp, _i32, _vp, _vp, _i64, _i64, _vp, _vp
 _lib.kv_append_decode_attn_split.argtypes = [_vp, _i32, _vp, _vp, _i64, _i64, _vp, _vp, ctypes.c_size_t, _vp]
 _lib.kv_decode_attn_split.argtypes = [_vp, _i32, _vp, _vp, ctypes.c_size_t, _vp]
 _lib.kv_decode_attn_merge.argtypes = [_vp, _i32, _vp, _vp, ctypes.c_size_t, _vp]
+_lib.kv_decode_attn_merge16.argtypes = [_vp, _i32, _vp, _vp, ctypes.c_size_t, _vp]
 _lib.kv_decode_splits.argtypes = [_vp, _i32, ctypes.POINTER(_i32)]
 _lib.kv_decode_bytes.argtypes = [_vp, _i32, _szp]
 _lib.kv_set_decode_path.argtypes = [_vp, _i32]
@@ -220,6 +221,10 @@ def kv_decode_attn_merge(cache: int, layer: int, out_ptr: int, ws_ptr: int, ws_b
     _check(_lib.kv_decode_attn_merge(cache, layer, out_ptr, ws_ptr, ws_bytes, stream), "kv_decode_attn_merge")
 
 
+def kv_decode_attn_merge16(cache: int, layer: int, out16_ptr: int, ws_ptr: int, ws_bytes: int, stream: int = 0) -> None:
+    _check(_lib.kv_decode_attn_merge16(cache, layer, out16_ptr, ws_ptr, ws_bytes, stream), "kv_decode_attn_merge16")
+
+
 def kv_decode_splits(cache: int, layer: int) -> int:
     n = _i32()
     _check(_lib.kv_decode_splits(cache, layer, ctypes.byref(n)), "kv_decode_splits")
@@ -308,6 +313,15 @@ class KVCache:
             out = torch.empty(q.shape, dtype=torch.float32, device=self.device)
         kv_decode_attn(self.handle, layer, q.data_ptr(), out.data_ptr(), self.workspace.data_ptr(),
                        self.ws_bytes, self._stream())
+        return out
+
+    def attend16(self, layer: int, q):
+        """As attend, with the output in q's 16-bit type (split, then the narrowing merge)."""
+        torch = self.torch
+        assert q.is_contiguous()
+        out = torch.empty(q.shape, dtype=q.dtype, device=self.device)
+        kv_decode_attn_split(self.handle, layer, q.data_ptr(), self.workspace.data_ptr(), self.ws_bytes, self._stream())
+        kv_decode_attn_merge16(self.handle, layer, out.data_ptr(), self.workspace.data_ptr(), self.ws_bytes, self._stream())
         return out
 
     def append_attend(self, layer: int, k_new, v_new, q, out=None):

@@ -25,6 +25,15 @@ __device__ __forceinline__ float widen16(uint16_t v, int dtype)
     return __half2float(__ushort_as_half(v));
 }
 __device__ __forceinline__ float f16_val(uint16_t h) { return __half2float(__ushort_as_half(h)); }
+// binary32 -> the 16-bit type, round to nearest even (finite inputs)
+__device__ __forceinline__ uint16_t narrow16_rne(float f, int dtype)
+{
+    if (dtype == 1) {
+        const uint32_t u = __float_as_uint(f);
+        return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+    }
+    return __half_as_ushort(__float2half_rn(f));
+}
 
 __device__ __forceinline__ float wave_max(float v)
 {
@@ -395,7 +404,9 @@ __global__ __launch_bounds__(256) void merge_kernel(DecodeArgs a)
     // a sequence that holds no token (every split empty, M == -inf) gives zeros
     r.x = M == -INFINITY ? 0.0f : n0 / den;
     r.y = M == -INFINITY ? 0.0f : n1 / den;
-    *(float2 *)(a.out + ((long long)b * a.n_q_heads + h * a.g + i) * kHeadDim + 2 * lane) = r;
+    const long long o = ((long long)b * a.n_q_heads + h * a.g + i) * kHeadDim + 2 * lane;
+    if (a.out16) *(uint32_t *)(a.out16 + o) = (uint32_t)narrow16_rne(r.x, a.geom.dtype) | ((uint32_t)narrow16_rne(r.y, a.geom.dtype) << 16);
+    else *(float2 *)(a.out + o) = r;
 }
 
 template <int KB, int VB> hipError_t launch_one(const DecodeArgs &a, hipStream_t s)

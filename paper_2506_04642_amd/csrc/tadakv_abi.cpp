@@ -587,13 +587,13 @@ kv_status kv_decode_attn_split(const kv_cache *cache, int32_t layer, const void 
     return e == hipSuccess ? KV_OK : KV_E_HIP;
 }
 
-kv_status kv_decode_attn_merge(const kv_cache *cache, int32_t layer, float *out,
-                               const void *workspace, size_t workspace_bytes, void *stream)
+static kv_status merge_impl(const kv_cache *cache, int32_t layer, float *out, uint16_t *out16,
+                            const void *workspace, size_t workspace_bytes, void *stream)
 {
     kv_status st = layer_ok(cache, layer);
     if (st != KV_OK) return st;
-    if (!out) return KV_E_NULL;
-    if ((uintptr_t)out % 16) return KV_E_ALIGN;
+    if (!out && !out16) return KV_E_NULL;
+    if (((uintptr_t)out % 16) || ((uintptr_t)out16 % 16)) return KV_E_ALIGN;
     DecodeArgs a{};
     st = fill_decode(cache, layer, &a);
     if (st != KV_OK) return st;
@@ -601,9 +601,24 @@ kv_status kv_decode_attn_merge(const kv_cache *cache, int32_t layer, float *out,
     if (st != KV_OK) return st;
     a.q = nullptr;
     a.out = out;
+    a.out16 = out16;
     // cross-head mean on the matrix-core path: the value mean plane's share joins the partials first
     if (a.xs && launch_xhead_values(a, (hipStream_t)stream) != hipSuccess) return KV_E_HIP;
     return launch_decode_merge(a, (hipStream_t)stream) == hipSuccess ? KV_OK : KV_E_HIP;
+}
+
+kv_status kv_decode_attn_merge(const kv_cache *cache, int32_t layer, float *out,
+                               const void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!out) return KV_E_NULL;
+    return merge_impl(cache, layer, out, nullptr, workspace, workspace_bytes, stream);
+}
+
+kv_status kv_decode_attn_merge16(const kv_cache *cache, int32_t layer, void *out16,
+                                 const void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!out16) return KV_E_NULL;
+    return merge_impl(cache, layer, nullptr, (uint16_t *)out16, workspace, workspace_bytes, stream);
 }
 
 kv_status kv_append_decode_attn_split(kv_cache *cache, int32_t layer, const void *k_new, const void *v_new,

@@ -46,6 +46,7 @@ struct DecodeArgs {
     const uint16_t *q;   // [batch][Hq][128]
     float *ws;           // partials [U][g][n_splits][kPartialStride]
     float *out;          // [batch][Hq][128]
+    uint16_t *out16;     // the same in the cache's 16-bit type, if not null (then `out` is not written)
     int n_kv_heads, n_q_heads, batch, g;
     int n_blocks;        // packed blocks in the layer
     int r;               // residual tokens

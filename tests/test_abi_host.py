@@ -27,7 +27,7 @@ def _cfg(kv, **over):
 def test_every_declared_function_is_exported(kv):
     text = open(os.path.join(ROOT, "include", "tadakv.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    declared = set(re.findall(r"\b(kv_[a-z_]+)\s*\(", text))
+    declared = set(re.findall(r"\b(kv_[a-z0-9_]+)\s*\(", text))
     assert declared, "no declarations found"
     assert declared == set(kv.EXPORTS)
     lib = ctypes.CDLL(kv.LIB_PATH)
@@ -107,6 +107,10 @@ def test_call_errors_are_caught_before_any_launch(kv):
         assert lib.kv_decode_attn(h, 0, Q, O, W, 1 << 20, None) == kv.KV_E_EMPTY
         assert lib.kv_decode_attn(h, 0, Q, None, W, 1 << 20, None) == kv.KV_E_NULL
         assert lib.kv_decode_attn(h, 9, Q, O, W, 1 << 20, None) == kv.KV_E_BAD_LAYER
+        assert lib.kv_decode_attn_merge16(h, 0, None, W, 1 << 20, None) == kv.KV_E_NULL
+        assert lib.kv_decode_attn_merge16(h, 0, O + 2, W, 1 << 20, None) == kv.KV_E_ALIGN
+        assert lib.kv_decode_attn_merge16(h, 0, O, W, 1 << 20, None) == kv.KV_E_EMPTY
+        assert lib.kv_decode_attn_merge16(h, 9, O, W, 1 << 20, None) == kv.KV_E_BAD_LAYER
         assert lib.kv_set_decode_path(h, 7) == kv.KV_E_BAD_CONFIG
         assert lib.kv_set_decode_splits(h, 1000) == kv.KV_E_BAD_CONFIG
         assert lib.kv_set_decode_splits(h, 4) == kv.KV_OK

@@ -5,7 +5,7 @@ import pytest
 
 from paper_2506_04642_amd import synth
 import parity_util
-from parity_util import append_both, check_attention, check_bytes, make_pair, to_dev
+from parity_util import ATTN_TOL, append_both, check_attention, check_bytes, make_pair, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -503,6 +503,31 @@ def test_prefill_then_decode_steps_with_drift(kv, oracle, decode_path):
             if s % 13 == 0 or s in (31, 32, steps - 1):
                 check_attention(gpu, orc, l, synth.make_q(l * 100 + s, 3, 8, 128, BF16), BF16)
         check_bytes(gpu, orc, l)
+
+
+@pytest.mark.parametrize("dtype", [F16, BF16])
+@pytest.mark.parametrize("mode", [CHAN, CROSS])
+def test_output_in_the_16_bit_type(kv, oracle, dtype, mode):
+    """The narrowing merge: the 32-bit result rounded to nearest even in the cache's 16-bit type.
+    Bitwise against the 32-bit output of the same cache; against the oracle within 2e-3 plus half a
+    unit in the last place of the 16-bit type."""
+    import torch
+
+    print("case out16 dtype=%d mode=%d" % (dtype, mode), flush=True)
+    gpu, orc = make_pair(kv, oracle, B=2, Hq=8, Hkv=2, T_max=1024 + 64, dtype=dtype, mode=mode, k_bits=(4,))
+    k, v = synth.make_kv(810 + dtype, 2, 1024 + 9, 2, 128, dtype)
+    append_both(gpu, orc, 0, k, v, dtype)
+    q = synth.make_q(811, 2, 8, 128, dtype)
+    qd = to_dev(q, dtype)
+    out32 = gpu.attend(0, qd)
+    out16 = gpu.attend16(0, qd)
+    torch.cuda.synchronize()
+    assert out16.dtype == qd.dtype
+    assert torch.equal(out16, out32.to(out16.dtype)), "narrowing differs from round-to-nearest-even of the 32-bit output"
+    want = orc.attend(0, q)
+    half_ulp = 2.0 ** (-9 if dtype == BF16 else -12)
+    err = np.abs(out16.float().cpu().numpy().astype(np.float64) - want)
+    assert np.all(err <= ATTN_TOL + half_ulp * np.abs(want) + 1e-7)
 
 
 # ------------------------------------------------------------------ degenerate inputs
