@@ -28,7 +28,7 @@
  *     sequences together; kv_quant_append_seq / kv_cache_reset_seq let one sequence join or leave
  *     (a new request taking over a slot of the batch: Sec. 3.3's buffer and blocks are per sequence),
  *     after which the lengths differ and the decode kernels take each sequence's own counts.
- *     Caches of more than 64 sequences must keep their lengths equal.
+ *     Caches of more than 256 sequences must keep their lengths equal.
  *   - One cache must be used by one thread at a time.
  *   - head_dim must be 128.
  */

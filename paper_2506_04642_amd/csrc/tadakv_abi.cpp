@@ -210,8 +210,9 @@ kv_status fill_decode(const kv_cache *k, int layer, DecodeArgs *a)
         if (nb > a->n_blocks) a->n_blocks = nb;
         if (r > a->r) a->r = r;
         if (a->ragged) {
-            a->nb_seq[b] = nb;
-            a->r_seq[b] = r;
+            if (nb > 65535 || r > 65535) return KV_E_UNSUPPORTED; // the table holds 16-bit counts
+            a->nb_seq[b] = (uint16_t)nb;
+            a->r_seq[b] = (uint16_t)r;
         }
     }
     if (a->n_blocks == 0 && a->r == 0) return KV_E_EMPTY;

@@ -9,7 +9,7 @@ constexpr int kHeadDim = 128;
 constexpr int kMaxGroupQ = 8;       // query heads per kv head the kernels are sized for
 constexpr int kPartialStride = 132; // floats per (unit, q head, split): O[128], max, sum, pad
 constexpr int kMaxSplits = 256;
-constexpr int kMaxRaggedBatch = 64; // sequences whose lengths may differ from one another
+constexpr int kMaxRaggedBatch = 256; // sequences whose lengths may differ from one another
 
 // Geometry of one layer's buffer; byte offsets, -1 where a field is absent.
 struct LayerGeom {
@@ -69,7 +69,7 @@ struct DecodeArgs {
     // sequences of different lengths: n_blocks and r above are the maxima, the kernels take each
     // sequence's own counts from these (ragged == 0: every sequence has n_blocks and r)
     int ragged;
-    int nb_seq[kMaxRaggedBatch], r_seq[kMaxRaggedBatch];
+    uint16_t nb_seq[kMaxRaggedBatch], r_seq[kMaxRaggedBatch]; // 1 KiB of the kernel arguments
 };
 
 // packed blocks / raw tokens of sequence b

@@ -139,3 +139,35 @@ def test_bulk_append_with_unequal_lengths_and_errors(kv, oracle):
         with pytest.raises(kv.KVError) as e:
             gpu.lengths(0, bad_seq)
         assert e.value.status == kv.KV_E_BAD_CONFIG
+
+
+def test_many_sequences_of_different_lengths(kv, oracle):
+    """200 slots with prompts of 0 .. 3 blocks plus a tail: more sequences than the first version of
+    the length table held (64); batch-wide decode steps afterwards."""
+    import torch
+
+    print("case ragged 200 sequences", flush=True)
+    B, Hkv, g, G = 200, 1, 4, 32
+    gpu, orc = make_pair(kv, oracle, B=B, Hq=Hkv * g, Hkv=Hkv, T_max=6 * G, G=G, Gc=G, R=G, dtype=BF16, mode=CHAN,
+                         k_bits=(4,))
+    rng = np.random.default_rng(99)
+    for b in range(B):
+        n = int(rng.integers(0, 3 * G + 20))
+        if b % 17 == 5 or n == 0:
+            continue  # empty slots among the others
+        k, v = synth.make_kv(9000 + b, 1, n, Hkv, 128, BF16)
+        gpu.append_seq(0, b, to_dev(k[0], BF16), to_dev(v[0], BF16))
+        orc.append_seq(0, b, k[0], v[0])
+    check_lengths(gpu, orc, 0, B)
+    check_attend(gpu, orc, 0, synth.make_q(31, B, Hkv * g, 128, BF16), BF16)
+    ks, vs = synth.make_kv(9500, B, 3, Hkv, 128, BF16)
+    kd, vd = to_dev(ks, BF16), to_dev(vs, BF16)
+    for s in range(3):
+        q = synth.make_q(40 + s, B, Hkv * g, 128, BF16)
+        out = gpu.append_attend(0, kd[:, s:s + 1], vd[:, s:s + 1], to_dev(q, BF16))
+        orc.append(0, ks[:, s:s + 1], vs[:, s:s + 1])
+        torch.cuda.synchronize()
+        err = float(np.max(np.abs(out.cpu().numpy().astype(np.float64) - orc.attend(0, q))))
+        assert err <= ATTN_TOL, "step %d: %.3e" % (s, err)
+    check_lengths(gpu, orc, 0, B)
+    check_bytes_ragged(gpu, orc, 0)
