@@ -80,6 +80,9 @@ typedef struct {
     int32_t mean_mode;      /* kv_mean_mode */
     const uint8_t *k_bits;  /* host, [n_layers], each 2, 4, 8 or 16 */
     const uint8_t *v_bits;  /* host, [n_layers]; the paper uses the same width for both */
+    int32_t pool_blocks;    /* 0: dense placement, every sequence owns its max_tokens/G block slots.
+                               > 0: paged placement, a layer buffer holds pool_blocks block slots which
+                               the sequences share through a block table (kv_cache_set_block_table) */
 } kv_config;                /* copied by kv_cache_create; the caller keeps its arrays */
 
 /* Byte offsets inside one layer's device buffer (see kv_cache_describe).
@@ -87,6 +90,9 @@ typedef struct {
  *              | cross-head mean plane [batch][max_tokens/G][2 (K,V)][G][head_dim] binary16
  *                (KV_MEAN_CROSS_HEAD only)
  *              | raw key residual [batch*n_kv_heads][R][head_dim] | raw value residual, same shape.
+ * Paged placement (pool_blocks > 0): records [pool_blocks][n_kv_heads] of rec_bytes each (a block slot
+ * holds one block of G tokens of every kv head of one sequence) | cross-head mean plane
+ * [pool_blocks][2][G][head_dim] | the residual buffers as above.
  * Record (one sequence, one kv head, one block of G tokens), offsets relative to the record:
  *   k_codes | k_scale[head_dim] | k_zero[head_dim] | k_mean[head_dim]
  *   | v_codes | v_meta[G][head_dim/Gc]{scale,zero} | v_mean[head_dim]
@@ -119,6 +125,20 @@ kv_status kv_cache_bytes(const kv_config *cfg, int32_t layer, size_t *bytes);
  * every token, the softmax weights for the value mean) plus batch * n_q_heads * ranges * head_dim
  * for the value mean's share of the output per token range (ranges <= 768 / batch, at most 256). */
 kv_status kv_workspace_bytes(const kv_config *cfg, size_t *bytes);
+
+/* Paged placement (caches created with pool_blocks > 0): where the blocks of the sequences live.
+ *   table_dev : device, [batch][stride] int32; entry (b, j) is the block slot, 0 <= slot < pool_blocks,
+ *               of logical block j (tokens j*G .. j*G + G - 1) of sequence b, for every layer alike.
+ *               The caller owns the array and hands out the slots: a slot belongs to at most one live
+ *               block (entries outside the range are clamped into it, so a stale entry cannot make a
+ *               kernel leave the buffer).  The kernels read the entries when they run, in stream
+ *               order: the array may be updated between calls on the same stream, and must hold an
+ *               entry for every block a call touches (blocks below a sequence's length, and the
+ *               blocks an append is about to fill).
+ *   stride    : entries per sequence, at least max_tokens / G.
+ * Host call, nothing is enqueued.  Until a table is set, appends and decodes of a paged cache return
+ * KV_E_BAD_CONFIG.  KV_E_BAD_CONFIG also for a cache with dense placement. */
+kv_status kv_cache_set_block_table(kv_cache *cache, const int32_t *table_dev, int32_t stride);
 
 /* Build the host descriptor.  layer_dev_ptrs: host array of n_layers device pointers, each at
  * least kv_cache_bytes(layer) long and 256-byte aligned; the caller owns them and must keep them

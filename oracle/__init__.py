@@ -15,6 +15,7 @@ from .tada import (  # noqa: F401
     f32_to_f16,
     kv_bytes_ratio,
     pack_codes,
+    record_layout,
     rope,
     unpack_codes,
     widen,

@@ -28,7 +28,7 @@ KV_F16, KV_BF16 = 0, 1
 KV_MEAN_CHANNEL_BLOCK, KV_MEAN_CROSS_HEAD, KV_MEAN_NONE = 0, 1, 2
 
 EXPORTS = [
-    "kv_cache_bytes", "kv_workspace_bytes", "kv_cache_create", "kv_cache_destroy", "kv_cache_reset",
+    "kv_cache_bytes", "kv_workspace_bytes", "kv_cache_create", "kv_cache_destroy", "kv_cache_set_block_table", "kv_cache_reset",
     "kv_cache_len", "kv_cache_len_seq", "kv_cache_reset_seq", "kv_cache_describe", "kv_quant_append", "kv_quant_append_seq", "kv_rope_quant_append", "kv_append_decode_attn", "kv_append_decode_attn_split", "kv_decode_attn", "kv_decode_attn_split",
     "kv_decode_attn_merge", "kv_decode_attn_merge16", "kv_decode_splits", "kv_decode_bytes", "kv_set_decode_path", "kv_set_decode_splits", "kv_strerror", "kv_last_hip_error",
 ]
@@ -41,6 +41,7 @@ class kv_config(ctypes.Structure):
         ("group_tokens", ctypes.c_int32), ("group_channels", ctypes.c_int32), ("resid_cap", ctypes.c_int32),
         ("dtype", ctypes.c_int32), ("mean_mode", ctypes.c_int32),
         ("k_bits", ctypes.POINTER(ctypes.c_uint8)), ("v_bits", ctypes.POINTER(ctypes.c_uint8)),
+        ("pool_blocks", ctypes.c_int32),
     ]
 
 
@@ -61,6 +62,7 @@ _lib.kv_cache_bytes.argtypes = [_cfgp, _i32, _szp]
 _lib.kv_workspace_bytes.argtypes = [_cfgp, _szp]
 _lib.kv_cache_create.argtypes = [_cfgp, ctypes.POINTER(_vp), ctypes.POINTER(_vp)]
 _lib.kv_cache_destroy.argtypes = [_vp]
+_lib.kv_cache_set_block_table.argtypes = [_vp, _vp, _i32]
 _lib.kv_cache_reset.argtypes = [_vp, _i32]
 _lib.kv_cache_len.argtypes = [_vp, _i32, ctypes.POINTER(_i32), ctypes.POINTER(_i32)]
 _lib.kv_cache_len_seq.argtypes = [_vp, _i32, _i32, ctypes.POINTER(_i32), ctypes.POINTER(_i32)]
@@ -110,14 +112,15 @@ def _check(status: int, where: str) -> None:
 
 def make_config(n_layers, batch, n_q_heads, n_kv_heads, head_dim, max_tokens, group_tokens,
                 group_channels, resid_cap, dtype, mean_mode, k_bits: Sequence[int],
-                v_bits: Sequence[int]) -> kv_config:
-    """Fill a kv_config; the bit arrays are kept alive on the returned object."""
+                v_bits: Sequence[int], pool_blocks: int = 0) -> kv_config:
+    """Fill a kv_config; the bit arrays are kept alive on the returned object.  pool_blocks > 0
+    asks for paged placement (block slots shared through kv_cache_set_block_table)."""
     kb = (ctypes.c_uint8 * len(k_bits))(*k_bits)
     vb = (ctypes.c_uint8 * len(v_bits))(*v_bits)
     cfg = kv_config(n_layers, batch, n_q_heads, n_kv_heads, head_dim, max_tokens, group_tokens,
                     group_channels, resid_cap, dtype, mean_mode,
                     ctypes.cast(kb, ctypes.POINTER(ctypes.c_uint8)),
-                    ctypes.cast(vb, ctypes.POINTER(ctypes.c_uint8)))
+                    ctypes.cast(vb, ctypes.POINTER(ctypes.c_uint8)), pool_blocks)
     cfg._keep = (kb, vb)
     return cfg
 
@@ -129,6 +132,10 @@ def kv_cache_bytes(cfg: kv_config, layer: int) -> int:
     n = ctypes.c_size_t()
     _check(_lib.kv_cache_bytes(ctypes.byref(cfg), layer, ctypes.byref(n)), "kv_cache_bytes")
     return n.value
+
+
+def kv_cache_set_block_table(cache: int, table_ptr: int, stride: int) -> None:
+    _check(_lib.kv_cache_set_block_table(cache, table_ptr, stride), "kv_cache_set_block_table")
 
 
 def kv_workspace_bytes(cfg: kv_config) -> int:
@@ -264,6 +271,13 @@ class KVCache:
         self.ws_bytes = kv_workspace_bytes(cfg)
         self.workspace = torch.empty(self.ws_bytes, dtype=torch.uint8, device=self.device)
         self.handle: Optional[int] = kv_cache_create(cfg, [t.data_ptr() for t in self.layers])
+
+    def set_block_table(self, table) -> None:
+        """Paged placement: table is a device int32 tensor [batch, stride] of block slots; it is kept
+        alive here and read by the kernels when they run."""
+        assert table.dtype == self.torch.int32 and table.is_contiguous() and table.dim() == 2
+        self._table = table
+        kv_cache_set_block_table(self.handle, table.data_ptr(), table.shape[1])
 
     def close(self):
         if self.handle:

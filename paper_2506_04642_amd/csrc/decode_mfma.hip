@@ -284,6 +284,15 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
 
     auto issue = [&](int ci) {
         const int blk0 = w0 + ci * cstride;
+        if (gm.table) {
+            // paged placement: every block of the chunk has a place of its own
+#pragma unroll
+            for (int bi = 0; bi < NBC; bi++) {
+                const int blk = blk0 + bi < b_end ? blk0 + bi : blk0; // no second block: the first one twice
+                stage_issue<REC>(a.layer + record_offset(gm, a.n_kv_heads, b, h, blk), stage + bi * (REC / 4), lane);
+            }
+            return;
+        }
         const unsigned char *src = unit_base + (long long)blk0 * REC;
         if (NBC == 1 || blk0 + 1 < b_end) {
             stage_issue<CB>(src, stage, lane);

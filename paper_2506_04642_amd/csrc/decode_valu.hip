@@ -308,14 +308,14 @@ template <int KB, int VB> __global__ __launch_bounds__(kThreads) void decode_spl
     const int b_end = w1 < nb_seq ? w1 : nb_seq;
 
     for (int j = w0; j < b_end; j++) {
-        const unsigned char *rec = a.layer + ((long long)u * gm.NB + j) * gm.rec_bytes;
+        const unsigned char *rec = a.layer + record_offset(gm, a.n_kv_heads, b, u % a.n_kv_heads, j);
         if (KB == 16) {
             for (int t0 = 0; t0 < G; t0 += 32)
                 process_block<16, 16>(a, sm, 32, rec + gm.k_codes + t0 * 256, nullptr, nullptr, nullptr,
                                       rec + gm.v_codes + t0 * 256, nullptr, nullptr, nullptr, nullptr, acc);
         } else {
             const unsigned char *xm = gm.mean_mode == 1
-                                          ? a.layer + gm.xmean_off + ((long long)b * gm.NB + j) * 2 * G * kHeadDim * 2
+                                          ? a.layer + xmean_offset(gm, b, j, 0)
                                           : nullptr;
             process_block<KB, VB>(a, sm, G, rec + gm.k_codes, rec + gm.k_scale, rec + gm.k_zero,
                                   gm.k_mean >= 0 ? rec + gm.k_mean : nullptr, rec + gm.v_codes,

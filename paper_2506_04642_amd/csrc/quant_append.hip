@@ -254,9 +254,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu((G == 
 
     for (int it = blockIdx.x; it < n_items; it += gridDim.x) {
         const int which = side_of(it), u = (it >> 1) % U, fb = (it >> 1) / U;
-        const int b = u / a.n_kv_heads;
+        const int b = u / a.n_kv_heads, h = u % a.n_kv_heads;
         const int bits = which == 0 ? gm.k_bits : gm.v_bits;
-        unsigned char *rec = a.layer + ((long long)(a.b0 * a.n_kv_heads + u) * gm.NB + (a.first_block + fb)) * gm.rec_bytes;
+        unsigned char *rec = a.layer + record_offset(gm, a.n_kv_heads, a.b0 + b, h, a.first_block + fb);
         unsigned char *codes_out = rec + (which == 0 ? gm.k_codes : gm.v_codes);
 
         if (bits == 16 && !(ROPE && which == 0)) {
@@ -354,8 +354,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu((G == 
             // cross-head mode: the mean of (token, channel) over the kv heads, written by
             // xhead_mean_kernel just before this launch
             const uint16_t *xm = gm.mean_mode == 1
-                                     ? (const uint16_t *)(a.layer + gm.xmean_off) +
-                                           (((long long)(a.b0 + b) * gm.NB + (a.first_block + fb)) * 2 + which) * G * kHeadDim
+                                     ? (const uint16_t *)(a.layer + xmean_offset(gm, a.b0 + b, a.first_block + fb, which))
                                      : nullptr;
             float dv[HT];
 #pragma unroll
@@ -746,7 +745,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ?
         // keys and values cost differently: a worker alternates between them (workers is even)
         const int which = (it ^ (it / workers)) & 1, u = (it >> 1) % U, fb = (it >> 1) / U;
         const int b = u / a.n_kv_heads, h = u % a.n_kv_heads;
-        unsigned char *rec = a.layer + ((long long)(a.b0 * a.n_kv_heads + u) * gm.NB + (a.first_block + fb)) * gm.rec_bytes;
+        unsigned char *rec = a.layer + record_offset(gm, a.n_kv_heads, a.b0 + b, h, a.first_block + fb);
         const int base_off = which == 0 ? gm.k_codes : gm.v_codes; // start of this item's part of the record
         unsigned char *codes_out = img;
 
@@ -811,8 +810,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ?
                 for (int e = 0; e < 8; e++) x[j][e] = x[j][e] - m[e];
         } else if (gm.mean_mode == 1) {
             // mean over the kv heads per (token, channel), written by xhead_mean_kernel before this launch
-            const uint16_t *xm = (const uint16_t *)(a.layer + gm.xmean_off) +
-                                 (((long long)(a.b0 + b) * gm.NB + (a.first_block + fb)) * 2 + which) * G * kHeadDim;
+            const uint16_t *xm = (const uint16_t *)(a.layer + xmean_offset(gm, a.b0 + b, a.first_block + fb, which));
 #pragma unroll
             for (int j = 0; j < 8; j++) {
                 const uint4 mv = *(const uint4 *)(xm + (8 * tg + j) * kHeadDim + c8 * 8);
@@ -1027,11 +1025,10 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ?
     for (int it = (int)blockIdx.x * (kThreads / 64) + wave; it < n_items; it += workers) {
         const int which = (it ^ (it / workers)) & 1, u = (it >> 1) % U, fb = (it >> 1) / U;
         const int b = u / a.n_kv_heads, h = u % a.n_kv_heads;
-        unsigned char *rec = a.layer + ((long long)(a.b0 * a.n_kv_heads + u) * gm.NB + (a.first_block + fb)) * gm.rec_bytes;
+        unsigned char *rec = a.layer + record_offset(gm, a.n_kv_heads, a.b0 + b, h, a.first_block + fb);
         const int base_off = which == 0 ? gm.k_codes : gm.v_codes;
-        const uint16_t *xm = (const uint16_t *)(a.layer + gm.xmean_off) +
-                             (((long long)(a.b0 + b) * gm.NB + (a.first_block + fb)) * 2 + which) * G * kHeadDim;
         const int mode = gm.mean_mode;
+        const uint16_t *xm = mode == 1 ? (const uint16_t *)(a.layer + xmean_offset(gm, a.b0 + b, a.first_block + fb, which)) : nullptr;
 
         // rows 32 half + 8 tg .. + 7 of the block, channels 8 c8 .. + 7, widened; in cross-head
         // mode already as deviations from the (token, channel) mean
@@ -1183,8 +1180,7 @@ __global__ __launch_bounds__(kThreads) void xhead_mean_kernel(AppendArgs a)
     const int fb = blockIdx.x, b = blockIdx.y, which = blockIdx.z;
     const int bits = which == 0 ? gm.k_bits : gm.v_bits;
     if (bits == 16) return;
-    uint16_t *dst = (uint16_t *)(a.layer + gm.xmean_off) +
-                    (((long long)(a.b0 + b) * gm.NB + (a.first_block + fb)) * 2 + which) * G * kHeadDim;
+    uint16_t *dst = (uint16_t *)(a.layer + xmean_offset(gm, a.b0 + b, a.first_block + fb, which));
     for (int i = threadIdx.x; i < G * (kHeadDim / 2); i += kThreads) {
         const int t = i / (kHeadDim / 2), cp = i % (kHeadDim / 2);
         float acc0 = 0.0f, acc1 = 0.0f;

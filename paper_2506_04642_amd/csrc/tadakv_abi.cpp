@@ -25,6 +25,8 @@ struct kv_cache {
             if (P(layer, b) != P(layer, 0) || R(layer, b) != R(layer, 0)) return false;
         return true;
     }
+    const int32_t *table = nullptr; // paged placement: the caller's block table (device)
+    int table_stride = 0;
     int decode_path = 0;
     int forced_splits = 0;
     size_t xhead_off = 0, xhead_bytes = 0; // cross-head mean: where its arrays start in the workspace, total size
@@ -47,6 +49,7 @@ kv_status check_config(const kv_config *c)
     if (!(c->group_tokens == 32 || c->group_tokens == 64 || c->group_tokens == 128)) return KV_E_BAD_CONFIG;
     if (!(c->group_channels == 32 || c->group_channels == 64 || c->group_channels == 128)) return KV_E_BAD_CONFIG;
     if (c->max_tokens <= 0 || c->max_tokens % c->group_tokens) return KV_E_BAD_CONFIG;
+    if (c->pool_blocks < 0) return KV_E_BAD_CONFIG;
     if (c->resid_cap <= 0 || c->resid_cap % c->group_tokens || c->resid_cap > c->max_tokens) return KV_E_BAD_CONFIG;
     if (!(c->dtype == KV_F16 || c->dtype == KV_BF16)) return KV_E_BAD_CONFIG;
     if (!(c->mean_mode == KV_MEAN_CHANNEL_BLOCK || c->mean_mode == KV_MEAN_CROSS_HEAD ||
@@ -90,10 +93,13 @@ LayerGeom make_geom(const kv_config &c, int layer)
     }
     g.rec_bytes = align_up(off, 256);
     const long long U = (long long)c.batch * c.n_kv_heads;
-    long long total = align_up(U * g.NB * g.rec_bytes, 256);
+    // block slots: every sequence its own (dense), or a shared pool (paged)
+    const long long slots = c.pool_blocks > 0 ? c.pool_blocks : (long long)c.batch * g.NB;
+    g.pool = c.pool_blocks;
+    long long total = align_up(slots * c.n_kv_heads * g.rec_bytes, 256);
     g.xmean_off = total;
     if (c.mean_mode == KV_MEAN_CROSS_HEAD)
-        total = align_up(total + (long long)c.batch * g.NB * 2 * G * d * 2, 256);
+        total = align_up(total + slots * 2 * G * d * 2, 256);
     g.k_resid_off = total;
     total = align_up(total + U * c.resid_cap * d * 2, 256);
     g.v_resid_off = total;
@@ -193,6 +199,11 @@ kv_status fill_decode(const kv_cache *k, int layer, DecodeArgs *a)
 {
     const kv_config &c = k->cfg;
     a->geom = k->geom[layer];
+    if (c.pool_blocks > 0) {
+        if (!k->table) return KV_E_BAD_CONFIG; // paged placement without a block table
+        a->geom.table = k->table;
+        a->geom.table_stride = k->table_stride;
+    }
     a->layer = k->layers[layer];
     a->n_kv_heads = c.n_kv_heads;
     a->n_q_heads = c.n_q_heads;
@@ -342,6 +353,19 @@ kv_status kv_cache_create(const kv_config *cfg, void *const *layer_dev_ptrs, kv_
     return KV_OK;
 }
 
+kv_status kv_cache_set_block_table(kv_cache *cache, const int32_t *table_dev, int32_t stride)
+{
+    if (!cache) return KV_E_NULL;
+    const kv_config &c = cache->cfg;
+    if (c.pool_blocks <= 0) return KV_E_BAD_CONFIG;
+    if (!table_dev) return KV_E_NULL;
+    if ((uintptr_t)table_dev % 4) return KV_E_ALIGN;
+    if (stride < c.max_tokens / c.group_tokens) return KV_E_BAD_CONFIG;
+    cache->table = table_dev;
+    cache->table_stride = stride;
+    return KV_OK;
+}
+
 kv_status kv_cache_destroy(kv_cache *cache)
 {
     if (!cache) return KV_E_NULL;
@@ -435,6 +459,7 @@ static kv_status append_impl(kv_cache *cache, int32_t layer, int seq0, int n_seq
         if (!rope_cos || !rope_sin) return KV_E_NULL;
         if (((uintptr_t)rope_cos % 16) || ((uintptr_t)rope_sin % 16)) return KV_E_ALIGN;
     }
+    if (c.pool_blocks > 0 && !cache->table) return KV_E_BAD_CONFIG; // paged placement without a block table
     for (int b = seq0; b < seq0 + n_seq; b++)
         if ((long long)cache->P(layer, b) + cache->R(layer, b) + n_new > c.max_tokens) return KV_E_CAPACITY;
     const int G = c.group_tokens, R = c.resid_cap;
@@ -447,6 +472,8 @@ static kv_status append_impl(kv_cache *cache, int32_t layer, int seq0, int n_seq
         const long long n_flush_tok = total / R * R;
         AppendArgs a{};
         a.geom = cache->geom[layer];
+        a.geom.table = cache->table;
+        a.geom.table_stride = cache->table_stride;
         a.layer = cache->layers[layer];
         a.k_new = (const uint16_t *)k_new + (long long)(b0 - seq0) * stride_b;
         a.v_new = (const uint16_t *)v_new + (long long)(b0 - seq0) * stride_b;

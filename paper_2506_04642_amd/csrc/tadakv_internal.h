@@ -20,7 +20,30 @@ struct LayerGeom {
     int k_codes, k_scale, k_zero, k_mean;
     int v_codes, v_meta, v_mean;
     long long xmean_off, k_resid_off, v_resid_off, layer_bytes;
+    // paged placement: block slots shared through a device table [batch][table_stride] (null: dense)
+    const int32_t *table;
+    int table_stride, pool;
 };
+
+// Block slot of logical block blk of sequence b.  Entries outside the pool are clamped into it.
+__device__ __forceinline__ long long block_slot(const LayerGeom &g, int b, int blk)
+{
+    if (!g.table) return (long long)b * g.NB + blk;
+    int p = g.table[(long long)b * g.table_stride + blk];
+    p = p < 0 ? 0 : (p >= g.pool ? g.pool - 1 : p);
+    return p;
+}
+// Byte offset of the record of (sequence b, kv head h, block blk) in the layer buffer.
+__device__ __forceinline__ long long record_offset(const LayerGeom &g, int n_kv_heads, int b, int h, int blk)
+{
+    if (!g.table) return ((long long)(b * n_kv_heads + h) * g.NB + blk) * g.rec_bytes;
+    return (block_slot(g, b, blk) * n_kv_heads + h) * g.rec_bytes;
+}
+// Byte offset of the cross-head mean tile [G][128] binary16 of (sequence b, block blk, K | V).
+__device__ __forceinline__ long long xmean_offset(const LayerGeom &g, int b, int blk, int which)
+{
+    return g.xmean_off + ((block_slot(g, b, blk) * 2 + which) * g.G * kHeadDim) * 2;
+}
 
 struct AppendArgs {
     LayerGeom geom;

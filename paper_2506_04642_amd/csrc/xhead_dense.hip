@@ -33,8 +33,7 @@ __device__ __forceinline__ const uint16_t *mean_row(const DecodeArgs &a, int b, 
     const LayerGeom &gm = a.geom;
     const int lg = 31 - __builtin_clz(gm.G); // G is 32, 64 or 128
     const int blk = t >> lg, tin = t - (blk << lg);
-    return (const uint16_t *)(a.layer + gm.xmean_off) + (((long long)b * gm.NB + blk) * 2 + which) * gm.G * kHeadDim +
-           tin * kHeadDim;
+    return (const uint16_t *)(a.layer + xmean_offset(gm, b, blk, which)) + tin * kHeadDim;
 }
 
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
@@ -157,10 +156,8 @@ __global__ __launch_bounds__(kThreads) void xhead_values_kernel(DecodeArgs a)
         Mq[r] = Mh[i];
         wq[r] = (long long)b * Hq + i;
     }
-    // mean tile staging: thread moves the 16-byte pieces tid + 256 k (row = piece / 16).
-    // value plane of this sequence: token t sits (t + (t rounded down to its block)) rows of 128 in
-    const uint16_t *vplane = (const uint16_t *)(a.layer + gm.xmean_off) + ((long long)b * gm.NB * 2 + 1) * gm.G * kHeadDim;
-    const int gmask = ~(gm.G - 1);
+    // mean tile staging: thread moves the 16-byte pieces tid + 256 k (row = piece / 16) of the
+    // value mean rows of the chunk's tokens
     uint4 mreg[4];
     float xpv[NR], xmv[NR];
     auto fetch = [&](int c) {
@@ -173,7 +170,7 @@ __global__ __launch_bounds__(kThreads) void xhead_values_kernel(DecodeArgs a)
 #pragma unroll
         for (int k = 0; k < 4; k++) {
             const int p = tid + kThreads * k, t = c * 64 + (p >> 4);
-            mreg[k] = t < T ? *(const uint4 *)(vplane + (long long)(t + (t & gmask)) * kHeadDim + (p & 15) * 8) : uint4{0u, 0u, 0u, 0u};
+            mreg[k] = t < T ? *(const uint4 *)(mean_row(a, b, 1, t) + (p & 15) * 8) : uint4{0u, 0u, 0u, 0u};
         }
     };
     v4f acc[MT][2];

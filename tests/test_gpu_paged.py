@@ -1,0 +1,199 @@
+"""GPU parity of paged placement (block slots shared through a block table): the same contents as
+dense placement, found where the table says.  The oracle keeps its dense image; the test gathers the
+GPU's records through the table before comparing bytes."""
+import numpy as np
+import pytest
+
+from paper_2506_04642_amd import synth
+import parity_util
+from parity_util import ATTN_TOL, to_dev
+
+pytestmark = pytest.mark.gpu
+
+BF16 = 1
+CHAN, CROSS, NONE = 0, 1, 2
+
+
+@pytest.fixture(scope="module")
+def kv():
+    import torch
+
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_2506_04642_amd import binding
+
+    return binding
+
+
+def make_paged(kv, oracle, *, B, Hkv, g, T_max, G, R, mode, bits, pool, seed, path):
+    import torch
+
+    cfg = kv.make_config(1, B, Hkv * g, Hkv, 128, T_max, G, G, R, BF16, mode, [bits], [bits], pool_blocks=pool)
+    ocfg = oracle.OracleConfig(1, B, Hkv * g, Hkv, 128, T_max, G, G, R, BF16, mode, [bits], [bits])
+    gpu = kv.KVCache(cfg, zero=True)
+    kv.kv_set_decode_path(gpu.handle, path)
+    NB = T_max // G
+    # every slot is handed out once, in a seeded order; the rest of the table holds out-of-range
+    # entries, which no kernel may follow (and which are clamped if one did)
+    rng = np.random.default_rng(seed)
+    table = np.full((B, NB + 3), 10 ** 6, dtype=np.int32)
+    table[:, NB:] = -7
+    slots = rng.permutation(pool)
+    return gpu, oracle.OracleCache(ocfg), table, list(slots)
+
+
+def give_blocks(table, slots, b, upto_blocks):
+    """Sequence b gets slots for its logical blocks below upto_blocks."""
+    for j in range(upto_blocks):
+        if table[b, j] >= 10 ** 6:
+            table[b, j] = slots.pop()
+
+
+def push_table(gpu, table):
+    import torch
+
+    if not hasattr(gpu, "_table"):
+        gpu.set_block_table(torch.from_numpy(table.copy()).to("cuda:0"))
+    else:
+        gpu._table.copy_(torch.from_numpy(table))
+
+
+def check_bytes_paged(kv, oracle, gpu, orc, table):
+    import torch
+
+    torch.cuda.synchronize()
+    cfg = orc.cfg
+    H, G, d, B = cfg.n_kv_heads, cfg.group_tokens, cfg.head_dim, cfg.batch
+    NB = cfg.max_tokens // G
+    img = orc.layer_image(0)
+    lo = oracle.record_layout(cfg, 0)
+    lg = kv.kv_cache_describe(gpu.handle, 0)
+    got = gpu.layers[0].cpu().numpy()
+    REC = lg.rec_bytes
+    assert REC == lo["rec_bytes"]
+    for b in range(B):
+        assert gpu.lengths(0, b) == (orc.packed_len(0, b), orc.resid_len(0, b))
+        for j in range(orc.packed_len(0, b) // G):
+            p = int(table[b, j])
+            for h in range(H):
+                go, oo = (p * H + h) * REC, ((b * H + h) * NB + j) * REC
+                m = img["valid"][oo:oo + REC]
+                assert m.any()
+                assert np.array_equal(got[go:go + REC][m], img["bytes"][oo:oo + REC][m]), (b, j, h)
+            if cfg.mean_mode == CROSS:
+                sz = 2 * G * d * 2
+                go, oo = lg.xmean_off + p * sz, lo["xmean_off"] + (b * NB + j) * sz
+                m = img["valid"][oo:oo + sz]
+                assert np.array_equal(got[go:go + sz][m], img["bytes"][oo:oo + sz][m]), (b, j)
+    sz = B * H * cfg.resid_cap * d * 2
+    for name in ("k_resid_off", "v_resid_off"):
+        go, oo = getattr(lg, name), lo[name]
+        m = img["valid"][oo:oo + sz]
+        assert np.array_equal(got[go:go + sz][m], img["bytes"][oo:oo + sz][m]), name
+
+
+@pytest.mark.parametrize("path", [0, 1], ids=["auto", "valu"])
+@pytest.mark.parametrize("bits,G,R,mode,g", [(4, 32, 32, CHAN, 4), (2, 64, 64, CHAN, 8), (8, 32, 64, NONE, 2),
+                                             (4, 32, 32, CROSS, 4), (2, 64, 64, CROSS, 2)])
+def test_paged_prompts_then_decode_steps(kv, oracle, bits, G, R, mode, g, path):
+    """Prompts of different lengths enter their slots one by one (slots handed out as needed, in a
+    shuffled order, from a pool smaller than batch x capacity), then batch-wide one-call decode steps
+    run across block boundaries while new slots are handed out."""
+    import torch
+
+    print("case paged bits=%d G=%d R=%d mode=%d g=%d path=%d" % (bits, G, R, mode, g, path), flush=True)
+    B, Hkv = 4, 2
+    NB = 12
+    gpu, orc, table, slots = make_paged(kv, oracle, B=B, Hkv=Hkv, g=g, T_max=NB * G, G=G, R=R, mode=mode, bits=bits,
+                                        pool=26, seed=50 + bits + G, path=path)
+    prompts = {0: 5 * G + 3, 1: 17, 3: 7 * G + G - 2}  # slot 2 stays empty for now
+    steps = R + 5
+    for b, n in prompts.items():
+        give_blocks(table, slots, b, (n + steps) // G + 1)
+    give_blocks(table, slots, 2, steps // G + 1)
+    push_table(gpu, table)
+    seed = 700 + bits + G
+    for b, n in prompts.items():
+        k, v = synth.make_kv(seed + b, 1, n, Hkv, 128, BF16)
+        gpu.append_seq(0, b, to_dev(k[0], BF16), to_dev(v[0], BF16))
+        orc.append_seq(0, b, k[0], v[0])
+    check_bytes_paged(kv, oracle, gpu, orc, table)
+    q = synth.make_q(seed, B, Hkv * g, 128, BF16)
+    out = gpu.attend(0, to_dev(q, BF16))
+    torch.cuda.synchronize()
+    assert float(np.max(np.abs(out.cpu().numpy().astype(np.float64) - orc.attend(0, q)))) <= ATTN_TOL
+    ks, vs = synth.make_kv(seed + 50, B, steps, Hkv, 128, BF16)
+    kd, vd = to_dev(ks, BF16), to_dev(vs, BF16)
+    for s in range(steps):
+        q = synth.make_q(seed * 7 + s, B, Hkv * g, 128, BF16)
+        out = gpu.append_attend(0, kd[:, s:s + 1], vd[:, s:s + 1], to_dev(q, BF16))
+        orc.append(0, ks[:, s:s + 1], vs[:, s:s + 1])
+        torch.cuda.synchronize()
+        err = float(np.max(np.abs(out.cpu().numpy().astype(np.float64) - orc.attend(0, q))))
+        assert err <= ATTN_TOL, "step %d: %.3e" % (s, err)
+    check_bytes_paged(kv, oracle, gpu, orc, table)
+
+    # sequence 3 leaves; its slots go back to the pool and a new prompt takes them, in another order
+    kv.kv_cache_reset_seq(gpu.handle, 0, 3)
+    orc.reset_seq(0, 3)
+    freed = [int(x) for x in table[3, :NB] if x < 10 ** 6]
+    table[3, :NB] = 10 ** 6
+    slots.extend(freed[::-1])
+    n = 3 * G + 11
+    give_blocks(table, slots, 3, n // G + 1)
+    push_table(gpu, table)
+    k, v = synth.make_kv(seed + 99, 1, n, Hkv, 128, BF16)
+    gpu.append_seq(0, 3, to_dev(k[0], BF16), to_dev(v[0], BF16))
+    orc.append_seq(0, 3, k[0], v[0])
+    q = synth.make_q(seed + 5, B, Hkv * g, 128, BF16)
+    out = gpu.attend(0, to_dev(q, BF16))
+    torch.cuda.synchronize()
+    assert float(np.max(np.abs(out.cpu().numpy().astype(np.float64) - orc.attend(0, q)))) <= ATTN_TOL
+    check_bytes_paged(kv, oracle, gpu, orc, table)
+
+
+def test_paged_bulk_append_with_rotation(kv, oracle):
+    """Bulk rotate-and-append of a uniform batch into shuffled slots."""
+    import torch
+
+    print("case paged rope", flush=True)
+    B, Hkv, g, G = 2, 2, 4, 32
+    NB = 8
+    gpu, orc, table, slots = make_paged(kv, oracle, B=B, Hkv=Hkv, g=g, T_max=NB * G, G=G, R=G, mode=CHAN, bits=4, pool=12,
+                                        seed=3, path=0)
+    T = 5 * G + 9
+    for b in range(B):
+        give_blocks(table, slots, b, T // G + 1)
+    push_table(gpu, table)
+    k, v = synth.make_kv(880, B, T, Hkv, 128, BF16)
+    cos, sin = synth.rope_tables(np.arange(100, 100 + T), 128, 500000.0)
+    gpu.append_rope(0, to_dev(k, BF16), to_dev(v, BF16), torch.from_numpy(cos).to("cuda:0"),
+                    torch.from_numpy(sin).to("cuda:0"), 0)
+    orc.append(0, k, v, rope_tables=(cos, sin, 0))
+    check_bytes_paged(kv, oracle, gpu, orc, table)
+    q = synth.make_q(881, B, Hkv * g, 128, BF16)
+    out = gpu.attend(0, to_dev(q, BF16))
+    torch.cuda.synchronize()
+    assert float(np.max(np.abs(out.cpu().numpy().astype(np.float64) - orc.attend(0, q)))) <= ATTN_TOL
+
+
+def test_paged_cache_needs_a_table(kv, oracle):
+    import torch
+
+    print("case paged errors", flush=True)
+    cfg = kv.make_config(1, 1, 4, 1, 128, 128, 32, 32, 32, BF16, CHAN, [4], [4], pool_blocks=3)
+    gpu = kv.KVCache(cfg)
+    k = torch.zeros((1, 1, 1, 128), dtype=torch.bfloat16, device="cuda:0")
+    with pytest.raises(kv.KVError) as e:
+        gpu.append(0, k, k)
+    assert e.value.status == kv.KV_E_BAD_CONFIG
+    with pytest.raises(kv.KVError) as e:
+        kv.kv_cache_set_block_table(gpu.handle, 0, 4)
+    assert e.value.status == kv.KV_E_NULL
+    t = torch.zeros((1, 3), dtype=torch.int32, device="cuda:0")
+    with pytest.raises(kv.KVError) as e:
+        gpu.set_block_table(t)  # stride below max_tokens / G
+    assert e.value.status == kv.KV_E_BAD_CONFIG
+    dense = kv.KVCache(kv.make_config(1, 1, 4, 1, 128, 128, 32, 32, 32, BF16, CHAN, [4], [4]))
+    with pytest.raises(kv.KVError) as e:
+        dense.set_block_table(torch.zeros((1, 4), dtype=torch.int32, device="cuda:0"))
+    assert e.value.status == kv.KV_E_BAD_CONFIG
