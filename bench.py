@@ -41,6 +41,7 @@ def parse():
     ap.add_argument("--q-heads", type=int, default=32)
     ap.add_argument("--kv-heads", type=int, default=8)
     ap.add_argument("--group", type=int, default=32, help="group size G = Gc")
+    ap.add_argument("--paged", action="store_true", help="paged placement: block slots in a shuffled order through a block table")
     ap.add_argument("--resid", type=int, default=0, help="raw-token buffer length R, a multiple of G (0: R = G; the paper uses 128)")
     ap.add_argument("--scheme", default="mixed248", help="layer bit map: mixed248 or mixed24_8ends")
     ap.add_argument("--seed", type=int, default=2000)
@@ -79,8 +80,12 @@ def main():
     mean_mode = {"channel": kv.KV_MEAN_CHANNEL_BLOCK, "cross": kv.KV_MEAN_CROSS_HEAD, "none": kv.KV_MEAN_NONE}[args.mean_mode]
     R = args.resid if args.resid else G  # raw trailing tokens are compressed R at a time (Sec. 3.3)
     max_tokens = (max_tokens + R - 1) // R * R
-    cfg = kv.make_config(L, B, Hq, Hkv, d, max_tokens, G, G, R, kv.KV_BF16, mean_mode, bits, bits)
+    pool = B * (max_tokens // G) if args.paged else 0
+    cfg = kv.make_config(L, B, Hq, Hkv, d, max_tokens, G, G, R, kv.KV_BF16, mean_mode, bits, bits, pool_blocks=pool)
     cache = kv.KVCache(cfg, device=dev, zero=False)
+    if args.paged:
+        perm = np.random.default_rng(args.seed).permutation(pool).astype(np.int32).reshape(B, max_tokens // G)
+        cache.set_block_table(torch.from_numpy(perm).to(dev))
     kv.kv_set_decode_path(cache.handle, args.path)
     if args.splits:
         kv.kv_set_decode_splits(cache.handle, args.splits)

@@ -231,8 +231,9 @@ template <> struct CodeOps<8> { // four words = one tile line; split into nibble
 // XH: cross-head mean.  The records carry no mean (MEAN is false); the mean's share of every
 // score comes in through a.xs, and the softmax weights go out through a.xp / a.xmc for the kernel
 // that adds the value mean plane's share to the partial outputs.
-template <int B, int G, int GC, bool MEAN, int NW, int NHG, bool XH>
-__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2 && NHG == 1 && !XH) ? 4 : 1, 8))) void decode_split_mfma_kernel(DecodeArgs a)
+// PG: paged placement (block slots through a table); the dense instances carry none of its state.
+template <int B, int G, int GC, bool MEAN, int NW, int NHG, bool XH, bool PG>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2 && NHG == 1 && !XH) ? (PG ? 3 : 4) : 1, 8))) void decode_split_mfma_kernel(DecodeArgs a)
 {
     static_assert(!(XH && MEAN), "cross-head layers store no per-record mean");
     typedef RecLayout<B, G, GC, MEAN> RL;
@@ -282,14 +283,31 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
     const int cstride = ns * NBC;     // blocks between consecutive local chunks
     const unsigned char *unit_base = a.layer + (long long)u * gm.NB * REC;
 
+    // Paged placement: lane l keeps the slots of the blocks of this wave's chunk number slot_base + l
+    // (one table read per 64 chunks of the wave), so that the fetch of a chunk waits for no lookup.
+    int slotv[NBC], slot_base = 0;
+    auto load_slots = [&](int it0) {
+        slot_base = it0;
+        const int blk0 = w0 + (wave + NW * (it0 + lane)) * cstride;
+#pragma unroll
+        for (int bi = 0; bi < NBC; bi++) {
+            int blk = blk0 + bi < b_end ? blk0 + bi : blk0; // no second block: the first one again
+            blk = blk < b_end ? blk : b_end - 1;            // chunks past the end: any block the sequence has
+            slotv[bi] = blk >= 0 ? (int)block_slot(gm, b, blk) : 0;
+        }
+    };
+    if (PG) load_slots(0);
+
     auto issue = [&](int ci) {
         const int blk0 = w0 + ci * cstride;
-        if (gm.table) {
-            // paged placement: every block of the chunk has a place of its own
+        if (PG) {
+            // every block of the chunk has a place of its own
+            const int it = (ci - wave) / NW;
+            if (it - slot_base >= 64) load_slots(it);
 #pragma unroll
             for (int bi = 0; bi < NBC; bi++) {
-                const int blk = blk0 + bi < b_end ? blk0 + bi : blk0; // no second block: the first one twice
-                stage_issue<REC>(a.layer + record_offset(gm, a.n_kv_heads, b, h, blk), stage + bi * (REC / 4), lane);
+                const long long slot = __builtin_amdgcn_readlane(slotv[bi], it - slot_base);
+                stage_issue<REC>(a.layer + (slot * a.n_kv_heads + h) * REC, stage + bi * (REC / 4), lane);
             }
             return;
         }
@@ -815,11 +833,11 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
 }
 
 // Resident workgroups of one instantiation on the whole device (0 if the query fails).
-template <int B, int G, int GC, bool MEAN, int NW, int NHG, bool XH> int resident_blocks()
+template <int B, int G, int GC, bool MEAN, int NW, int NHG, bool XH, bool PG> int resident_blocks()
 {
     static const int n = [] {
         int per_cu = 0, dev = 0, cus = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_split_mfma_kernel<B, G, GC, MEAN, NW, NHG, XH>,
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_split_mfma_kernel<B, G, GC, MEAN, NW, NHG, XH, PG>,
                                                          64 * NW, 0) != hipSuccess)
             return 0;
         if (hipGetDevice(&dev) != hipSuccess) return 0;
@@ -829,22 +847,22 @@ template <int B, int G, int GC, bool MEAN, int NW, int NHG, bool XH> int residen
     return n;
 }
 
-template <int B, int G, int GC, bool MEAN, int NHG, bool XH> hipError_t launch_inst(const DecodeArgs &a, hipStream_t s)
+template <int B, int G, int GC, bool MEAN, int NHG, bool XH, bool PG> hipError_t launch_inst(const DecodeArgs &a, hipStream_t s)
 {
     constexpr int NW = kWavesPerBlock;
     if (!RecLayout<B, G, GC, MEAN>::matches(a.geom)) return hipErrorInvalidValue;
     dim3 grid(a.n_splits, a.batch * a.n_kv_heads);
     (void)hipGetLastError(); // drop any stale error left by earlier runtime calls of this thread
-    hipLaunchKernelGGL((decode_split_mfma_kernel<B, G, GC, MEAN, NW, NHG, XH>), grid, dim3(64 * NW), 0, s, a);
+    hipLaunchKernelGGL((decode_split_mfma_kernel<B, G, GC, MEAN, NW, NHG, XH, PG>), grid, dim3(64 * NW), 0, s, a);
     return note_launch(hipGetLastError());
 }
 
 // Split count that puts every workgroup of the launch on the device at once (one "round"):
 // the kernel is a bandwidth stream, and a second, partly filled round only adds a tail.
-template <int B, int G, int GC, bool MEAN, int NHG, bool XH> int plan_inst(const DecodeArgs &a)
+template <int B, int G, int GC, bool MEAN, int NHG, bool XH, bool PG> int plan_inst(const DecodeArgs &a)
 {
     constexpr int NW = kWavesPerBlock, NBC = 64 / G;
-    const int slots = resident_blocks<B, G, GC, MEAN, NW, NHG, XH>();
+    const int slots = resident_blocks<B, G, GC, MEAN, NW, NHG, XH, PG>();
     const int U = a.batch * a.n_kv_heads;
     const int chunks = (a.n_blocks + NBC - 1) / NBC;
     int ns = slots / U;
@@ -859,29 +877,34 @@ template <int B, int G, int GC, bool MEAN, int NHG, bool XH> int plan_inst(const
 struct DoLaunch {
     hipStream_t s;
     hipError_t result = hipErrorInvalidValue;
-    template <int B, int G, int GC, bool MEAN, int NHG, bool XH> void run(const DecodeArgs &a) { result = launch_inst<B, G, GC, MEAN, NHG, XH>(a, s); }
+    template <int B, int G, int GC, bool MEAN, int NHG, bool XH, bool PG> void run(const DecodeArgs &a) { result = launch_inst<B, G, GC, MEAN, NHG, XH, PG>(a, s); }
 };
 struct DoPlan {
     int result = 1;
-    template <int B, int G, int GC, bool MEAN, int NHG, bool XH> void run(const DecodeArgs &a) { result = plan_inst<B, G, GC, MEAN, NHG, XH>(a); }
+    template <int B, int G, int GC, bool MEAN, int NHG, bool XH, bool PG> void run(const DecodeArgs &a) { result = plan_inst<B, G, GC, MEAN, NHG, XH, PG>(a); }
 };
 struct DoMatch {
     bool result = false;
-    template <int B, int G, int GC, bool MEAN, int NHG, bool XH> void run(const DecodeArgs &a) { result = RecLayout<B, G, GC, MEAN>::matches(a.geom); }
+    template <int B, int G, int GC, bool MEAN, int NHG, bool XH, bool PG> void run(const DecodeArgs &a) { result = RecLayout<B, G, GC, MEAN>::matches(a.geom); }
 };
 
-template <int B, int G, int GC, class F> void pick_mean_heads(const DecodeArgs &a, F &f)
+template <int B, int G, int GC, bool PG, class F> void pick_mean_heads_pg(const DecodeArgs &a, F &f)
 {
     const int mode = a.geom.mean_mode; // 0 per-channel block mean, 1 cross-head mean, 2 none
     if (a.g <= 4) {
-        if (mode == 0) f.template run<B, G, GC, true, 1, false>(a);
-        else if (mode == 1) f.template run<B, G, GC, false, 1, true>(a);
-        else f.template run<B, G, GC, false, 1, false>(a);
+        if (mode == 0) f.template run<B, G, GC, true, 1, false, PG>(a);
+        else if (mode == 1) f.template run<B, G, GC, false, 1, true, PG>(a);
+        else f.template run<B, G, GC, false, 1, false, PG>(a);
     } else {
-        if (mode == 0) f.template run<B, G, GC, true, 2, false>(a);
-        else if (mode == 1) f.template run<B, G, GC, false, 2, true>(a);
-        else f.template run<B, G, GC, false, 2, false>(a);
+        if (mode == 0) f.template run<B, G, GC, true, 2, false, PG>(a);
+        else if (mode == 1) f.template run<B, G, GC, false, 2, true, PG>(a);
+        else f.template run<B, G, GC, false, 2, false, PG>(a);
     }
+}
+template <int B, int G, int GC, class F> void pick_mean_heads(const DecodeArgs &a, F &f)
+{
+    if (a.geom.table) pick_mean_heads_pg<B, G, GC, true>(a, f);
+    else pick_mean_heads_pg<B, G, GC, false>(a, f);
 }
 template <class F> void pick(const DecodeArgs &a, F &f)
 {
