@@ -866,7 +866,11 @@ template <int B, int G, int GC, bool MEAN, int NHG, bool XH, bool PG> int plan_i
     const int U = a.batch * a.n_kv_heads;
     const int chunks = (a.n_blocks + NBC - 1) / NBC;
     int ns = slots / U;
-    const int cap = chunks / (NW * 4); // at least four chunks per wave, or the prologue dominates
+    // at least four chunks per wave, or the prologue dominates -- unless the launch is so small that
+    // the device cannot be filled even then: such a launch is bound by latency, and the widest
+    // spread (one chunk per wave) is the shortest
+    const bool small = (long long)U * chunks < (long long)slots * NW * 4;
+    const int cap = small ? (chunks + NW - 1) / NW : chunks / (NW * 4);
     if (ns > cap) ns = cap;
     if (ns > kMaxSplits) ns = kMaxSplits;
     if (ns < 1) ns = 1;
