@@ -126,6 +126,16 @@ kv_status kv_cache_bytes(const kv_config *cfg, int32_t layer, size_t *bytes);
  * for the value mean's share of the output per token range (ranges <= 768 / batch, at most 256). */
 kv_status kv_workspace_bytes(const kv_config *cfg, size_t *bytes);
 
+/* Which sequences the batch-wide calls act on (a serving loop whose slots are not all busy).
+ *   active : host, [n] bytes, n == batch; non-zero = active.  NULL: all sequences (the initial state).
+ * Until changed again: kv_quant_append, kv_rope_quant_append and kv_append_decode_attn(_split) give
+ * tokens only to the active sequences (the input rows of the others are not read), and the decode
+ * calls treat the others as empty for the call: their output rows are zeros and their part of the
+ * cache is not read.  Lengths and contents of the sequences that are not active stay as they are;
+ * the per-sequence calls (kv_quant_append_seq, kv_cache_reset_seq, kv_cache_len_seq) ignore the
+ * setting.  Host call, copied, nothing is enqueued.  Limits as for sequences of different lengths. */
+kv_status kv_cache_set_active(kv_cache *cache, const uint8_t *active, int32_t n);
+
 /* Paged placement (caches created with pool_blocks > 0): where the blocks of the sequences live.
  *   table_dev : device, [batch][stride] int32; entry (b, j) is the block slot, 0 <= slot < pool_blocks,
  *               of logical block j (tokens j*G .. j*G + G - 1) of sequence b, for every layer alike.

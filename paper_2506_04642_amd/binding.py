@@ -28,7 +28,7 @@ KV_F16, KV_BF16 = 0, 1
 KV_MEAN_CHANNEL_BLOCK, KV_MEAN_CROSS_HEAD, KV_MEAN_NONE = 0, 1, 2
 
 EXPORTS = [
-    "kv_cache_bytes", "kv_workspace_bytes", "kv_cache_create", "kv_cache_destroy", "kv_cache_set_block_table", "kv_cache_reset",
+    "kv_cache_bytes", "kv_workspace_bytes", "kv_cache_create", "kv_cache_destroy", "kv_cache_set_block_table", "kv_cache_set_active", "kv_cache_reset",
     "kv_cache_len", "kv_cache_len_seq", "kv_cache_reset_seq", "kv_cache_describe", "kv_quant_append", "kv_quant_append_seq", "kv_rope_quant_append", "kv_append_decode_attn", "kv_append_decode_attn_split", "kv_decode_attn", "kv_decode_attn_split",
     "kv_decode_attn_merge", "kv_decode_attn_merge16", "kv_decode_splits", "kv_decode_bytes", "kv_set_decode_path", "kv_set_decode_splits", "kv_strerror", "kv_last_hip_error",
 ]
@@ -63,6 +63,7 @@ _lib.kv_workspace_bytes.argtypes = [_cfgp, _szp]
 _lib.kv_cache_create.argtypes = [_cfgp, ctypes.POINTER(_vp), ctypes.POINTER(_vp)]
 _lib.kv_cache_destroy.argtypes = [_vp]
 _lib.kv_cache_set_block_table.argtypes = [_vp, _vp, _i32]
+_lib.kv_cache_set_active.argtypes = [_vp, ctypes.POINTER(ctypes.c_uint8), _i32]
 _lib.kv_cache_reset.argtypes = [_vp, _i32]
 _lib.kv_cache_len.argtypes = [_vp, _i32, ctypes.POINTER(_i32), ctypes.POINTER(_i32)]
 _lib.kv_cache_len_seq.argtypes = [_vp, _i32, _i32, ctypes.POINTER(_i32), ctypes.POINTER(_i32)]
@@ -132,6 +133,15 @@ def kv_cache_bytes(cfg: kv_config, layer: int) -> int:
     n = ctypes.c_size_t()
     _check(_lib.kv_cache_bytes(ctypes.byref(cfg), layer, ctypes.byref(n)), "kv_cache_bytes")
     return n.value
+
+
+def kv_cache_set_active(cache: int, active: Optional[Sequence[int]]) -> None:
+    """active: one flag per sequence, or None for all."""
+    if active is None:
+        _check(_lib.kv_cache_set_active(cache, None, 0), "kv_cache_set_active")
+        return
+    arr = (ctypes.c_uint8 * len(active))(*[1 if x else 0 for x in active])
+    _check(_lib.kv_cache_set_active(cache, arr, len(active)), "kv_cache_set_active")
 
 
 def kv_cache_set_block_table(cache: int, table_ptr: int, stride: int) -> None:

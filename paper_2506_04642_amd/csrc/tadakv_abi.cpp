@@ -25,6 +25,8 @@ struct kv_cache {
             if (P(layer, b) != P(layer, 0) || R(layer, b) != R(layer, 0)) return false;
         return true;
     }
+    std::vector<uint8_t> active;    // batch-wide calls act on these sequences only (empty: on all)
+    bool on(int b) const { return active.empty() || active[b] != 0; }
     const int32_t *table = nullptr; // paged placement: the caller's block table (device)
     int table_stride = 0;
     int decode_path = 0;
@@ -212,12 +214,17 @@ kv_status fill_decode(const kv_cache *k, int layer, DecodeArgs *a)
     a->tcap = c.max_tokens;
     // sequences may differ in length: the launch is planned for the longest, the kernels take
     // each sequence's own counts from the table
-    a->ragged = k->uniform(layer) ? 0 : 1;
+    // a sequence that is not active counts as empty for this launch (its output rows are zeros)
+    a->ragged = 0;
+    for (int b = 0; b < c.batch; b++) {
+        if (!k->on(b) && (k->P(layer, b) || k->R(layer, b))) a->ragged = 1;
+        if (k->on(b) != k->on(0) || k->P(layer, b) != k->P(layer, 0) || k->R(layer, b) != k->R(layer, 0)) a->ragged = 1;
+    }
     if (a->ragged && c.batch > kMaxRaggedBatch) return KV_E_UNSUPPORTED;
     a->n_blocks = 0;
     a->r = 0;
     for (int b = 0; b < c.batch; b++) {
-        const int nb = k->P(layer, b) / c.group_tokens, r = k->R(layer, b);
+        const int nb = k->on(b) ? k->P(layer, b) / c.group_tokens : 0, r = k->on(b) ? k->R(layer, b) : 0;
         if (nb > a->n_blocks) a->n_blocks = nb;
         if (r > a->r) a->r = r;
         if (a->ragged) {
@@ -353,6 +360,18 @@ kv_status kv_cache_create(const kv_config *cfg, void *const *layer_dev_ptrs, kv_
     return KV_OK;
 }
 
+kv_status kv_cache_set_active(kv_cache *cache, const uint8_t *active, int32_t n)
+{
+    if (!cache) return KV_E_NULL;
+    if (!active) {
+        cache->active.clear();
+        return KV_OK;
+    }
+    if (n != cache->cfg.batch) return KV_E_BAD_CONFIG;
+    cache->active.assign(active, active + n);
+    return KV_OK;
+}
+
 kv_status kv_cache_set_block_table(kv_cache *cache, const int32_t *table_dev, int32_t stride)
 {
     if (!cache) return KV_E_NULL;
@@ -442,7 +461,8 @@ kv_status kv_cache_describe(const kv_cache *cache, int32_t layer, kv_layer_layou
 // Sequences seq0 .. seq0 + n_seq - 1 of the cache each take n_new tokens; input row (b, t, h) of
 // the run is at b*stride_b + t*stride_t + h*stride_h from k_new / v_new.  Runs of sequences that
 // hold the same number of tokens go into one launch.
-static kv_status append_impl(kv_cache *cache, int32_t layer, int seq0, int n_seq, const void *k_new, const void *v_new,
+// masked: a batch-wide call, which leaves out the sequences that are not active
+static kv_status append_impl(kv_cache *cache, int32_t layer, int seq0, int n_seq, bool masked, const void *k_new, const void *v_new,
                              int32_t n_new, int64_t stride_b, int64_t stride_t, int64_t stride_h,
                              int rope, const float *rope_cos, const float *rope_sin, void *stream)
 {
@@ -460,13 +480,18 @@ static kv_status append_impl(kv_cache *cache, int32_t layer, int seq0, int n_seq
         if (((uintptr_t)rope_cos % 16) || ((uintptr_t)rope_sin % 16)) return KV_E_ALIGN;
     }
     if (c.pool_blocks > 0 && !cache->table) return KV_E_BAD_CONFIG; // paged placement without a block table
+    auto takes = [&](int b) { return !masked || cache->on(b); };
     for (int b = seq0; b < seq0 + n_seq; b++)
-        if ((long long)cache->P(layer, b) + cache->R(layer, b) + n_new > c.max_tokens) return KV_E_CAPACITY;
+        if (takes(b) && (long long)cache->P(layer, b) + cache->R(layer, b) + n_new > c.max_tokens) return KV_E_CAPACITY;
     const int G = c.group_tokens, R = c.resid_cap;
     hipStream_t s = (hipStream_t)stream;
     for (int b0 = seq0; b0 < seq0 + n_seq;) {
+        if (!takes(b0)) {
+            b0++;
+            continue;
+        }
         int b1 = b0 + 1;
-        while (b1 < seq0 + n_seq && cache->P(layer, b1) == cache->P(layer, b0) && cache->R(layer, b1) == cache->R(layer, b0)) b1++;
+        while (b1 < seq0 + n_seq && takes(b1) && cache->P(layer, b1) == cache->P(layer, b0) && cache->R(layer, b1) == cache->R(layer, b0)) b1++;
         const int r_old = cache->R(layer, b0);
         const long long total = (long long)r_old + n_new;
         const long long n_flush_tok = total / R * R;
@@ -514,7 +539,7 @@ kv_status kv_quant_append(kv_cache *cache, int32_t layer, const void *k_new, con
                           void *stream)
 {
     if (!cache) return KV_E_NULL;
-    return append_impl(cache, layer, 0, cache->cfg.batch, k_new, v_new, n_new, stride_b, stride_t, stride_h, 0, nullptr,
+    return append_impl(cache, layer, 0, cache->cfg.batch, true, k_new, v_new, n_new, stride_b, stride_t, stride_h, 0, nullptr,
                        nullptr, stream);
 }
 
@@ -523,7 +548,7 @@ kv_status kv_quant_append_seq(kv_cache *cache, int32_t layer, int32_t seq, const
 {
     if (!cache) return KV_E_NULL;
     if (seq < 0 || seq >= cache->cfg.batch) return KV_E_BAD_CONFIG;
-    return append_impl(cache, layer, seq, 1, k_new, v_new, n_new, 0, stride_t, stride_h, 0, nullptr, nullptr, stream);
+    return append_impl(cache, layer, seq, 1, false, k_new, v_new, n_new, 0, stride_t, stride_h, 0, nullptr, nullptr, stream);
 }
 
 kv_status kv_rope_quant_append(kv_cache *cache, int32_t layer, const void *k_pre, const void *v_new,
@@ -532,7 +557,7 @@ kv_status kv_rope_quant_append(kv_cache *cache, int32_t layer, const void *k_pre
 {
     if (!cache) return KV_E_NULL;
     if (pairing != KV_ROPE_HALF && pairing != KV_ROPE_INTERLEAVED) return KV_E_BAD_CONFIG;
-    return append_impl(cache, layer, 0, cache->cfg.batch, k_pre, v_new, n_new, stride_b, stride_t, stride_h,
+    return append_impl(cache, layer, 0, cache->cfg.batch, true, k_pre, v_new, n_new, stride_b, stride_t, stride_h,
                        pairing == KV_ROPE_HALF ? 1 : 2, rope_cos, rope_sin, stream);
 }
 
@@ -558,6 +583,7 @@ kv_status kv_decode_bytes(const kv_cache *cache, int32_t layer, size_t *bytes)
     const size_t H = c.n_kv_heads, d = c.head_dim;
     size_t nb = 0, r_sum = 0; // blocks and raw tokens summed over the sequences
     for (int b = 0; b < c.batch; b++) {
+        if (!cache->on(b)) continue; // a decode launch does not read the sequences that are not active
         nb += cache->P(layer, b) / c.group_tokens;
         r_sum += cache->R(layer, b);
     }
@@ -662,6 +688,7 @@ kv_status kv_append_decode_attn_split(kv_cache *cache, int32_t layer, const void
     if (stride_h < c.head_dim || stride_b < 0) return KV_E_BAD_CONFIG;
     bool flush = false; // does the token complete a block of some sequence
     for (int b = 0; b < c.batch; b++) {
+        if (!cache->on(b)) continue;
         if ((long long)cache->P(layer, b) + cache->R(layer, b) + 1 > c.max_tokens) return KV_E_CAPACITY;
         if (cache->R(layer, b) + 1 == c.resid_cap) flush = true;
     }
@@ -676,6 +703,7 @@ kv_status kv_append_decode_attn_split(kv_cache *cache, int32_t layer, const void
         }
     };
     for (int b = 0; b < c.batch; b++) {
+        if (!cache->on(b)) continue;
         const bool fl = r_old[b] + 1 == c.resid_cap;
         cache->P(layer, b) = fl ? p_old[b] + c.resid_cap : p_old[b];
         cache->R(layer, b) = fl ? 0 : r_old[b] + 1;

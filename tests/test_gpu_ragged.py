@@ -171,3 +171,52 @@ def test_many_sequences_of_different_lengths(kv, oracle):
         assert err <= ATTN_TOL, "step %d: %.3e" % (s, err)
     check_lengths(gpu, orc, 0, B)
     check_bytes_ragged(gpu, orc, 0)
+
+
+@pytest.mark.parametrize("path", [0, 1], ids=["auto", "valu"])
+@pytest.mark.parametrize("mode", [CHAN, CROSS])
+def test_active_set(kv, oracle, mode, path):
+    """Batch-wide calls with some slots switched off: only the active sequences take tokens, the
+    others keep their contents and get zeros from the decode calls while they are off."""
+    import torch
+
+    print("case active set mode=%d path=%d" % (mode, path), flush=True)
+    parity_util.DECODE_PATH = path
+    try:
+        B, Hkv, g, G = 6, 2, 4, 32
+        gpu, orc = make_pair(kv, oracle, B=B, Hq=Hkv * g, Hkv=Hkv, T_max=8 * G, G=G, Gc=G, R=G, dtype=BF16, mode=mode,
+                             k_bits=(4,))
+        k, v = synth.make_kv(1200, B, 2 * G + 20, Hkv, 128, BF16)
+        gpu.append(0, to_dev(k, BF16), to_dev(v, BF16))  # everyone active at first
+        orc.append(0, k, v)
+        active = [1, 0, 1, 1, 0, 1]
+        kv.kv_cache_set_active(gpu.handle, active)
+        steps = G  # crosses a block boundary of the active sequences
+        ks, vs = synth.make_kv(1201, B, steps + 3, Hkv, 128, BF16)
+        kd, vd = to_dev(ks, BF16), to_dev(vs, BF16)
+        on = [b for b in range(B) if active[b]]
+        off = [b for b in range(B) if not active[b]]
+        for s in range(steps):
+            q = synth.make_q(1300 + s, B, Hkv * g, 128, BF16)
+            out = gpu.append_attend(0, kd[:, s:s + 1], vd[:, s:s + 1], to_dev(q, BF16))
+            for b in on:
+                orc.append_seq(0, b, ks[b, s:s + 1], vs[b, s:s + 1])
+            torch.cuda.synchronize()
+            got = out.cpu().numpy().astype(np.float64)
+            want = orc.attend(0, q)
+            assert float(np.max(np.abs(got[on] - want[on]))) <= ATTN_TOL, s
+            assert not got[off].any(), "a sequence that is off must get zeros"
+        check_lengths(gpu, orc, 0, B)
+        # a bulk append under the mask, then everyone on again: the sequences that were off are intact
+        gpu.append(0, kd[:, steps:steps + 3], vd[:, steps:steps + 3])
+        for b in on:
+            orc.append_seq(0, b, ks[b, steps:steps + 3], vs[b, steps:steps + 3])
+        kv.kv_cache_set_active(gpu.handle, None)
+        check_lengths(gpu, orc, 0, B)
+        check_bytes_ragged(gpu, orc, 0)
+        check_attend(gpu, orc, 0, synth.make_q(1400, B, Hkv * g, 128, BF16), BF16)
+        with pytest.raises(kv.KVError) as e:
+            kv.kv_cache_set_active(gpu.handle, [1, 0])
+        assert e.value.status == kv.KV_E_BAD_CONFIG
+    finally:
+        parity_util.DECODE_PATH = 0
