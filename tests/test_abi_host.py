@@ -58,6 +58,7 @@ def test_sizes_follow_the_record_format(kv):
     (dict(dtype=5), "KV_E_BAD_CONFIG"),
     (dict(mean_mode=9), "KV_E_BAD_CONFIG"),
     (dict(batch=0), "KV_E_BAD_CONFIG"),
+    (dict(pool_blocks=-1), "KV_E_BAD_CONFIG"),
     (dict(k_bits=[4, 3]), "KV_E_BAD_BITS"),
     (dict(v_bits=[1, 2]), "KV_E_BAD_BITS"),
     (dict(k_bits=[16, 2]), "KV_E_UNSUPPORTED"),
@@ -130,3 +131,31 @@ def test_strerror_names_every_status(kv):
         seen.add(msg)
     assert len(seen) == 11
     assert kv.kv_strerror(-99) == "unknown status"
+
+
+def test_paged_placement_and_active_set_host_checks(kv):
+    """Sizes of a paged cache follow the pool; table and active-set arguments are checked on the host."""
+    paged = _cfg(kv, pool_blocks=5, mean_mode=kv.KV_MEAN_CROSS_HEAD)
+    # 5 slots x 2 kv heads x 4-bit records without mean fields (160 B per token), the slots' two mean
+    # tiles, the raw buffers of the 4 units
+    assert kv.kv_cache_bytes(paged, 0) == 5 * 2 * 5120 + 5 * 2 * 32 * 256 + 2 * 4 * 32 * 256
+    h = kv.kv_cache_create(paged, [0x100000, 0x200000])
+    d = kv.kv_cache_create(_cfg(kv), [0x100000, 0x200000])
+    try:
+        lib = kv._lib
+        K, V, T = 0x300000, 0x400000, 0x500000
+        assert lib.kv_quant_append(h, 0, K, V, 1, 1024, 256, 128, None) == kv.KV_E_BAD_CONFIG  # no table yet
+        assert lib.kv_cache_set_block_table(h, None, 8) == kv.KV_E_NULL
+        assert lib.kv_cache_set_block_table(h, T + 2, 8) == kv.KV_E_ALIGN
+        assert lib.kv_cache_set_block_table(h, T, 7) == kv.KV_E_BAD_CONFIG  # fewer entries than blocks per sequence
+        assert lib.kv_cache_set_block_table(h, T, 8) == kv.KV_OK
+        assert lib.kv_cache_set_block_table(d, T, 8) == kv.KV_E_BAD_CONFIG  # dense placement
+        assert lib.kv_cache_set_block_table(None, T, 8) == kv.KV_E_NULL
+        flags = (ctypes.c_uint8 * 2)(1, 0)
+        assert lib.kv_cache_set_active(d, flags, 3) == kv.KV_E_BAD_CONFIG
+        assert lib.kv_cache_set_active(d, flags, 2) == kv.KV_OK
+        assert lib.kv_cache_set_active(d, None, 0) == kv.KV_OK
+        assert lib.kv_cache_set_active(None, flags, 2) == kv.KV_E_NULL
+    finally:
+        kv.kv_cache_destroy(h)
+        kv.kv_cache_destroy(d)
