@@ -1,0 +1,180 @@
+"""Seeded random walk over configurations and call sequences: every case draws a format (widths,
+group sizes, mean mode, heads, raw-buffer length, dtype, dense or paged placement), fills the
+sequences with prompts of different lengths, then mixes batch-wide appends, one-call decode steps,
+per-sequence appends, resets and activity masks, checking attention after every step and the cache
+bytes at the end against the CPU oracle."""
+import numpy as np
+import pytest
+
+from paper_2506_04642_amd import synth
+import parity_util
+from parity_util import ATTN_TOL, to_dev
+
+pytestmark = pytest.mark.gpu
+
+CHAN, CROSS, NONE = 0, 1, 2
+
+
+@pytest.fixture(scope="module")
+def kv():
+    import torch
+
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_2506_04642_amd import binding
+
+    return binding
+
+
+def gather_check(kv, oracle, gpu, orc, table):
+    """Cache bytes against the oracle's dense image, through the block table if there is one."""
+    import torch
+
+    torch.cuda.synchronize()
+    cfg = orc.cfg
+    H, G, d, B = cfg.n_kv_heads, cfg.group_tokens, cfg.head_dim, cfg.batch
+    NB = cfg.max_tokens // G
+    img = orc.layer_image(0)
+    lo = oracle.record_layout(cfg, 0)
+    lg = kv.kv_cache_describe(gpu.handle, 0)
+    got = gpu.layers[0].cpu().numpy()
+    REC = lg.rec_bytes
+    for b in range(B):
+        assert gpu.lengths(0, b) == (orc.packed_len(0, b), orc.resid_len(0, b)), b
+        for j in range(orc.packed_len(0, b) // G):
+            slot = int(table[b, j]) if table is not None else b * NB + j
+            for h in range(H):
+                go = (slot * H + h) * REC if table is not None else ((b * H + h) * NB + j) * REC
+                oo = ((b * H + h) * NB + j) * REC
+                m = img["valid"][oo:oo + REC]
+                assert np.array_equal(got[go:go + REC][m], img["bytes"][oo:oo + REC][m]), (b, j, h)
+            if cfg.mean_mode == CROSS and cfg.k_bits[0] != 16:
+                sz = 2 * G * d * 2
+                go, oo = lg.xmean_off + slot * sz, lo["xmean_off"] + (b * NB + j) * sz
+                m = img["valid"][oo:oo + sz]
+                assert np.array_equal(got[go:go + sz][m], img["bytes"][oo:oo + sz][m]), (b, j)
+    sz = B * H * cfg.resid_cap * d * 2
+    for name in ("k_resid_off", "v_resid_off"):
+        go, oo = getattr(lg, name), lo[name]
+        m = img["valid"][oo:oo + sz]
+        assert np.array_equal(got[go:go + sz][m], img["bytes"][oo:oo + sz][m]), name
+
+
+@pytest.mark.parametrize("case", range(48))
+def test_random_configuration_and_call_sequence(kv, oracle, case):
+    import torch
+
+    rng = np.random.default_rng(4000 + case)
+    G = int(rng.choice([32, 32, 32, 64, 64, 128]))
+    Gc = G if G <= 64 and rng.random() < 0.7 else int(rng.choice([32, 64, 128]))
+    bits = int(rng.choice([2, 4, 8, 8 if G == 128 else 16]))
+    vbits = bits if (bits == 16 or rng.random() < 0.7) else int(rng.choice([2, 4, 8]))
+    mode = int(rng.choice([CHAN, CHAN, CROSS, CROSS, NONE]))
+    if mode == CROSS and G == 128:
+        mode = CHAN  # the cross-head decode path has no instance for blocks of 128 tokens
+    Hkv = int(rng.choice([1, 2, 4]))
+    g = int(rng.choice([1, 2, 3, 4, 5, 8]))
+    B = int(rng.integers(1, 6))
+    R = G * int(rng.choice([1, 1, 2]))
+    dtype = int(rng.integers(0, 2))
+    paged = bool(rng.random() < 0.4)
+    path = int(rng.choice([0, 0, 1]))
+    NB = 6 * (R // G)
+    T_max = NB * G
+    pool = B * NB - int(rng.integers(0, NB)) if paged else 0
+    print("case %d: G=%d Gc=%d bits=%d/%d mode=%d Hkv=%d g=%d B=%d R=%d dtype=%d paged=%s path=%d" % (
+        case, G, Gc, bits, vbits, mode, Hkv, g, B, R, dtype, paged, path), flush=True)
+
+    cfg = kv.make_config(1, B, Hkv * g, Hkv, 128, T_max, G, Gc, R, dtype, mode, [bits], [vbits], pool_blocks=pool)
+    ocfg = oracle.OracleConfig(1, B, Hkv * g, Hkv, 128, T_max, G, Gc, R, dtype, mode, [bits], [vbits])
+    gpu = kv.KVCache(cfg, zero=True)
+    orc = oracle.OracleCache(ocfg)
+    kv.kv_set_decode_path(gpu.handle, path)
+    table = None
+    if paged:
+        # a shuffled assignment for every logical block that fits the pool; the budget below keeps the
+        # sequences within their assigned blocks
+        perm = list(rng.permutation(pool))
+        table = np.full((B, NB), 10 ** 6, dtype=np.int32)
+        order = [(b, j) for j in range(NB) for b in range(B)]
+        for (b, j) in order:
+            if perm:
+                table[b, j] = perm.pop()
+        gpu.set_block_table(torch.from_numpy(table).to("cuda:0"))
+    cap = [T_max if table is None else int((table[b] < 10 ** 6).sum()) * G for b in range(B)]
+    length = [0] * B
+    seed = 5000 + 17 * case
+
+    def attend_check(active=None):
+        if not any(length[b] for b in range(B) if active is None or active[b]):
+            return
+        q = synth.make_q(seed + sum(length), B, Hkv * g, 128, dtype)
+        out = gpu.attend(0, to_dev(q, dtype))
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().astype(np.float64)
+        want = orc.attend(0, q)
+        for b in range(B):
+            if active is not None and not active[b]:
+                assert not got[b].any()
+            elif length[b] == 0:
+                assert not got[b].any()
+            else:
+                err = float(np.max(np.abs(got[b] - want[b])))
+                assert err <= ATTN_TOL, (b, err)
+
+    for step in range(14):
+        op = rng.choice(["seq", "batch", "step", "step", "reset", "mask"])
+        if op == "seq":
+            b = int(rng.integers(0, B))
+            n = int(rng.integers(1, 2 * G))
+            if length[b] + n > cap[b]:
+                continue
+            k, v = synth.make_kv(seed + 100 * step + b, 1, n, Hkv, 128, dtype)
+            gpu.append_seq(0, b, to_dev(k[0], dtype), to_dev(v[0], dtype))
+            orc.append_seq(0, b, k[0], v[0])
+            length[b] += n
+            attend_check()
+        elif op == "batch":
+            n = int(rng.integers(1, G + 5))
+            if any(length[b] + n > cap[b] for b in range(B)):
+                continue
+            k, v = synth.make_kv(seed + 100 * step + 50, B, n, Hkv, 128, dtype)
+            gpu.append(0, to_dev(k, dtype), to_dev(v, dtype))
+            for b in range(B):
+                orc.append_seq(0, b, k[b], v[b])
+                length[b] += n
+            attend_check()
+        elif op == "step":
+            if any(length[b] + 1 > cap[b] for b in range(B)):
+                continue
+            k, v = synth.make_kv(seed + 100 * step + 60, B, 1, Hkv, 128, dtype)
+            q = synth.make_q(seed + 100 * step + 61, B, Hkv * g, 128, dtype)
+            out = gpu.append_attend(0, to_dev(k, dtype), to_dev(v, dtype), to_dev(q, dtype))
+            for b in range(B):
+                orc.append_seq(0, b, k[b], v[b])
+                length[b] += 1
+            torch.cuda.synchronize()
+            err = float(np.max(np.abs(out.cpu().numpy().astype(np.float64) - orc.attend(0, q))))
+            assert err <= ATTN_TOL, (step, err)
+        elif op == "reset":
+            b = int(rng.integers(0, B))
+            kv.kv_cache_reset_seq(gpu.handle, 0, b)
+            orc.reset_seq(0, b)
+            length[b] = 0
+            attend_check()
+        else:
+            active = [int(rng.random() < 0.6) for _ in range(B)]
+            if not any(active):
+                active[0] = 1
+            kv.kv_cache_set_active(gpu.handle, active)
+            n = int(rng.integers(1, 4))
+            if not any(length[b] + n > cap[b] for b in range(B) if active[b]):
+                k, v = synth.make_kv(seed + 100 * step + 70, B, n, Hkv, 128, dtype)
+                gpu.append(0, to_dev(k, dtype), to_dev(v, dtype))
+                for b in range(B):
+                    if active[b]:
+                        orc.append_seq(0, b, k[b], v[b])
+                        length[b] += n
+                attend_check(active)
+            kv.kv_cache_set_active(gpu.handle, None)
+    gather_check(kv, oracle, gpu, orc, table)
+    gpu.close()
