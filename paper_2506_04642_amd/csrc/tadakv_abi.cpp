@@ -273,6 +273,9 @@ kv_status bind_workspace(const kv_cache *k, DecodeArgs *a, void *workspace, size
         a->xmc = a->xp + rows * c.max_tokens;
         a->xo = (float *)((unsigned char *)workspace + xhead_xo_offset(c));
         a->n_xr = xhead_ranges(c, a->n_blocks);
+        // one resident round of workgroups, whatever the compiler made of the kernel's registers
+        const int fit = xhead_values_resident(c.n_q_heads) / c.batch;
+        if (fit >= 1 && a->n_xr > fit) a->n_xr = fit;
     }
     return KV_OK;
 }

@@ -113,5 +113,6 @@ hipError_t launch_decode_merge(const DecodeArgs &a, hipStream_t s);
 // split kernel) and the value mean plane's contribution to the partial outputs (before the merge)
 hipError_t launch_xhead_scores(const DecodeArgs &a, hipStream_t s);
 hipError_t launch_xhead_values(const DecodeArgs &a, hipStream_t s);
+int xhead_values_resident(int n_q_heads); // workgroups of the value-mean kernel the device holds at once
 
 } // namespace tadakv

@@ -118,7 +118,7 @@ constexpr int kMvStride = 132; // halfs per LDS row of the mean tile: rows 8 apa
 constexpr int kWStride = 72;   // halfs per LDS row of the weights
 
 template <int MT> // 16-head tiles: ceil(Hq / 16)
-__global__ __launch_bounds__(kThreads) void xhead_values_kernel(DecodeArgs a)
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(MT <= 2 ? 3 : 1, 8))) void xhead_values_kernel(DecodeArgs a)
 {
     constexpr int NR = 4 * MT; // heads per thread in the weight staging
     __shared__ __attribute__((aligned(16))) _Float16 mvs[64 * kMvStride];
@@ -157,7 +157,10 @@ __global__ __launch_bounds__(kThreads) void xhead_values_kernel(DecodeArgs a)
         wq[r] = (long long)b * Hq + i;
     }
     // mean tile staging: thread moves the 16-byte pieces tid + 256 k (row = piece / 16) of the
-    // value mean rows of the chunk's tokens
+    // value mean rows of the chunk's tokens; a chunk lies in one or two blocks, whose tiles are
+    // looked up once per chunk (the cross-head decode path serves G = 32 and 64)
+    const int G = gm.G;
+    const int thr_off = (tid >> 4) * (kHeadDim * 2) + (tid & 15) * 16;
     uint4 mreg[4];
     float xpv[NR], xmv[NR];
     auto fetch = [&](int c) {
@@ -167,10 +170,16 @@ __global__ __launch_bounds__(kThreads) void xhead_values_kernel(DecodeArgs a)
             xpv[r] = t < T ? a.xp[wq[r] * a.tcap + t] : 0.0f;
             xmv[r] = a.xmc[wq[r] * ncap + c];
         }
+        const int blk0 = c * (64 / G); // c < chunks_total: the chunk's first block exists
+        const unsigned char *tile0 = a.layer + xmean_offset(gm, b, blk0, 1);
+        const unsigned char *tile1 = (G < 64 && (blk0 + 1) * G < T) ? a.layer + xmean_offset(gm, b, blk0 + 1, 1) : tile0;
+        // piece tid + 256 k is row (tid >> 4) + 16 k: a wave-uniform base per k plus the thread's own offset
 #pragma unroll
         for (int k = 0; k < 4; k++) {
-            const int p = tid + kThreads * k, t = c * 64 + (p >> 4);
-            mreg[k] = t < T ? *(const uint4 *)(mean_row(a, b, 1, t) + (p & 15) * 8) : uint4{0u, 0u, 0u, 0u};
+            const bool second = 16 * k >= G; // rows 16 k .. 16 k + 15 lie in the chunk's second block
+            const unsigned char *base = (second ? tile1 : tile0) + (16 * k - (second ? G : 0)) * (kHeadDim * 2);
+            const int t = c * 64 + 16 * k + (tid >> 4);
+            mreg[k] = t < T ? *(const uint4 *)(base + thr_off) : uint4{0u, 0u, 0u, 0u};
         }
     };
     v4f acc[MT][2];
@@ -245,6 +254,25 @@ hipError_t launch_xhead_scores(const DecodeArgs &a, hipStream_t s)
     else if (mt <= 2) hipLaunchKernelGGL(xhead_scores_kernel<2>, grid, dim3(kThreads), 0, s, a);
     else hipLaunchKernelGGL(xhead_scores_kernel<4>, grid, dim3(kThreads), 0, s, a);
     return note_launch(hipGetLastError());
+}
+
+// Workgroups of the value-mean kernel that the device holds at once (0 if the query fails).
+template <int MT> static int values_resident()
+{
+    static const int n = [] {
+        int per_cu = 0, dev = 0, cus = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, xhead_values_kernel<MT>, kThreads, 0) != hipSuccess) return 0;
+        if (hipGetDevice(&dev) != hipSuccess) return 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+        return per_cu * cus;
+    }();
+    return n;
+}
+
+int xhead_values_resident(int n_q_heads)
+{
+    const int mt = (n_q_heads + 15) / 16;
+    return mt <= 1 ? values_resident<1>() : mt <= 2 ? values_resident<2>() : values_resident<4>();
 }
 
 hipError_t launch_xhead_values(const DecodeArgs &a, hipStream_t s)
