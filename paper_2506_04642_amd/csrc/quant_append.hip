@@ -1181,6 +1181,31 @@ __global__ __launch_bounds__(kThreads) void xhead_mean_kernel(AppendArgs a)
     const int bits = which == 0 ? gm.k_bits : gm.v_bits;
     if (bits == 16) return;
     uint16_t *dst = (uint16_t *)(a.layer + xmean_offset(gm, a.b0 + b, a.first_block + fb, which));
+    if (!(a.rope != 0 && which == 0)) {
+        // no rotation on this side: a thread takes eight channels of a token as 16-byte pieces
+        for (int i = threadIdx.x; i < G * (kHeadDim / 8); i += kThreads) {
+            const int t = i / (kHeadDim / 8), c8 = i % (kHeadDim / 8);
+            float acc[8];
+#pragma unroll
+            for (int e = 0; e < 8; e++) acc[e] = 0.0f;
+#pragma unroll 4
+            for (int h = 0; h < H; h++) {
+                const uint4 w = *(const uint4 *)(src_row(a, which, b, h, fb * G + t) + c8 * 8);
+                const uint32_t wv[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+                for (int k = 0; k < 4; k++) {
+                    acc[2 * k] = acc[2 * k] + widen16((uint16_t)(wv[k] & 0xFFFFu), gm.dtype);
+                    acc[2 * k + 1] = acc[2 * k + 1] + widen16((uint16_t)(wv[k] >> 16), gm.dtype);
+                }
+            }
+            uint32_t mw[4];
+#pragma unroll
+            for (int k = 0; k < 4; k++)
+                mw[k] = (uint32_t)f16_rne(acc[2 * k] / (float)H) | ((uint32_t)f16_rne(acc[2 * k + 1] / (float)H) << 16);
+            *(uint4 *)(dst + t * kHeadDim + c8 * 8) = uint4{mw[0], mw[1], mw[2], mw[3]};
+        }
+        return;
+    }
     for (int i = threadIdx.x; i < G * (kHeadDim / 2); i += kThreads) {
         const int t = i / (kHeadDim / 2), cp = i % (kHeadDim / 2);
         float acc0 = 0.0f, acc1 = 0.0f;
