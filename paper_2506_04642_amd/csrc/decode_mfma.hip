@@ -96,12 +96,10 @@ __device__ __forceinline__ float h_lo(uint32_t w) { return __half2float(__ushort
 __device__ __forceinline__ float h_hi(uint32_t w) { return __half2float(__ushort_as_half((uint16_t)(w >> 16))); }
 __device__ __forceinline__ half2_t as_h2(uint32_t w) { return __builtin_bit_cast(half2_t, w); }
 
-// power of two strictly above x (x >= 0) but at least 2 * floor_v; and its reciprocal
-__device__ __forceinline__ void pow2_above(float x, float floor_v, float &p, float &inv)
+// power of two strictly above x (x >= 0) but at least 2 * floor_v
+__device__ __forceinline__ float pow2_above(float x, float floor_v)
 {
-    const uint32_t b = (__float_as_uint(fmaxf(x, floor_v)) & 0x7F800000u) + 0x00800000u;
-    p = __uint_as_float(b);
-    inv = __uint_as_float(0x7F000000u - b);
+    return __uint_as_float((__float_as_uint(fmaxf(x, floor_v)) & 0x7F800000u) + 0x00800000u);
 }
 
 // waits for this wave's outstanding LDS traffic and keeps the compiler from moving LDS accesses
@@ -126,13 +124,11 @@ __device__ __forceinline__ uint32_t opaque(uint32_t x)
     return x;
 }
 // power of two strictly above the larger of the two non-negative binary16 values in w (at least
-// 2^-14), and its reciprocal, straight from the exponent field
-__device__ __forceinline__ void pow2_above_h2(uint32_t w, bool both, float &p, float &inv)
+// 2^-14), straight from the exponent field
+__device__ __forceinline__ float pow2_above_h2(uint32_t w, bool both)
 {
     const uint32_t m = both ? max(w & 0xFFFFu, w >> 16) : (w & 0xFFFFu);
-    const uint32_t b = ((m & 0x7C00u) << 13) + (113u << 23); // value exponent (e5 - 15) + 1, biased by 127
-    p = __uint_as_float(b);
-    inv = __uint_as_float(0x7F000000u - b);
+    return __uint_as_float(((m & 0x7C00u) << 13) + (113u << 23)); // value exponent (e5 - 15) + 1, biased by 127
 }
 
 // running softmax state of one lane for one query head; O for channels 16*ct + n
@@ -342,8 +338,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
                 qmax = fmaxf(qmax, fabsf(qf[hg][ph][y]));
             }
         qmax = row_max(qmax);
-        float qb, inv_qb;
-        pow2_above(qmax, 0x1p-60f, qb, inv_qb);
+        const float qb = pow2_above(qmax, 0x1p-60f);
         three_qb[hg] = 3.0f * qb;
         inv_kf_base[hg] = qb * 0x1p-22f * kScoreScale;
 #pragma unroll
@@ -364,9 +359,6 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
         for (int k = 0; k < 4; k++) st[hg].Zp[k] = 0.0f;
     }
     wave_lds_fence();
-
-    const uint32_t sel1 = (qa & 1) ? 0x03070105u : 0x06020400u;
-    const uint32_t sel2 = (qa & 2) ? 0x03020706u : 0x05040100u;
 
     // cross-head mean: q . mean_K of this lane's tokens (16 k + n of a chunk), worked out by the
     // kernel that ran before this one; loaded one chunk ahead
@@ -478,8 +470,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
             // so the largest is found with packed 16-bit integer maxima on the raw words
             uint32_t smw = pk_max_u16(pk_max_u16(ks[bi][0].x, ks[bi][0].y), pk_max_u16(ks[bi][1].x, ks[bi][1].y));
             smw = row_pk_max_u16(smw);
-            float sb, inv_sb;
-            pow2_above_h2(smw, true, sb, inv_sb);
+            const float sb = pow2_above_h2(smw, true);
             float inv_kf[NHG], beta[NHG];
 #pragma unroll
             for (int hg = 0; hg < NHG; hg++) {
@@ -567,8 +558,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
 #pragma unroll
             for (int gam = 0; gam < NG; gam++) svw = pk_max_u16(svw, vm[k][gam]);
         svw = row_pk_max_u16(svw);
-        float sbv, inv_sbv;
-        pow2_above_h2(svw, false, sbv, inv_sbv);
+        const float sbv = pow2_above_h2(svw, false);
         const float vmagic = 3.0f * sbv; // p <= 1, scale < sbv: same construction as on the key side
         const uint32_t vfix = opaque(0x80808080u - __float_as_uint(vmagic));
 

@@ -25,7 +25,6 @@ __device__ __forceinline__ float widen16(uint16_t v, int dtype)
     if (dtype == 1) return __uint_as_float((uint32_t)v << 16);
     return __half2float(__ushort_as_half(v));
 }
-__device__ __forceinline__ float f16_val(uint16_t h) { return __half2float(__ushort_as_half(h)); }
 
 // mean plane row of (batch b, side which, token t): 128 binary16 values
 __device__ __forceinline__ const uint16_t *mean_row(const DecodeArgs &a, int b, int which, int t)
