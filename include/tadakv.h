@@ -237,6 +237,17 @@ kv_status kv_decode_attn_merge(const kv_cache *cache, int32_t layer, float *out,
 kv_status kv_decode_attn_merge16(const kv_cache *cache, int32_t layer, void *out16,
                                  const void *workspace, size_t workspace_bytes, void *stream);
 
+/* Reconstruction of a layer's contents (Eq. 7-8): x^ = mean + (zero + scale * code), evaluated in
+ * binary32 in that order with one rounding per operation; tokens that are still raw (the residual
+ * buffer, 16-bit layers) are widened.  Not on the decode path, which never forms x^; for callers
+ * that need the tensors (a prefill kernel of their own, error measurements).
+ *   k_out, v_out : device, [batch, t_cap, n_kv_heads, head_dim] binary32, 16-byte aligned; either may
+ *                  be NULL.  Token t of sequence b is written for t < its length, the rest is left alone.
+ *   t_cap        : tokens per sequence in the outputs; KV_E_CAPACITY if a sequence is longer.
+ * KV_E_EMPTY if the layer holds no token.  Sequences that are not active (kv_cache_set_active) are
+ * skipped. */
+kv_status kv_dequant(const kv_cache *cache, int32_t layer, float *k_out, float *v_out, int32_t t_cap, void *stream);
+
 /* One step of the decode loop in a single call (Algorithm 1 steps 8-9, KVCache.update followed by
  * TaDAFlashAttn): append ONE new token per sequence, then attend over the whole cache including it.
  * Equals kv_quant_append(n_new = 1) followed by kv_decode_attn, bit for bit; where the layer is

@@ -30,7 +30,7 @@ KV_MEAN_CHANNEL_BLOCK, KV_MEAN_CROSS_HEAD, KV_MEAN_NONE = 0, 1, 2
 EXPORTS = [
     "kv_cache_bytes", "kv_workspace_bytes", "kv_cache_create", "kv_cache_destroy", "kv_cache_set_block_table", "kv_cache_set_active", "kv_cache_reset",
     "kv_cache_len", "kv_cache_len_seq", "kv_cache_reset_seq", "kv_cache_describe", "kv_quant_append", "kv_quant_append_seq", "kv_rope_quant_append", "kv_append_decode_attn", "kv_append_decode_attn_split", "kv_decode_attn", "kv_decode_attn_split",
-    "kv_decode_attn_merge", "kv_decode_attn_merge16", "kv_decode_splits", "kv_decode_bytes", "kv_set_decode_path", "kv_set_decode_splits", "kv_strerror", "kv_last_hip_error",
+    "kv_decode_attn_merge", "kv_decode_attn_merge16", "kv_dequant", "kv_decode_splits", "kv_decode_bytes", "kv_set_decode_path", "kv_set_decode_splits", "kv_strerror", "kv_last_hip_error",
 ]
 
 
@@ -78,6 +78,7 @@ _lib.kv_append_decode_attn_split.argtypes = [_vp, _i32, _vp, _vp, _i64, _i64, _v
 _lib.kv_decode_attn_split.argtypes = [_vp, _i32, _vp, _vp, ctypes.c_size_t, _vp]
 _lib.kv_decode_attn_merge.argtypes = [_vp, _i32, _vp, _vp, ctypes.c_size_t, _vp]
 _lib.kv_decode_attn_merge16.argtypes = [_vp, _i32, _vp, _vp, ctypes.c_size_t, _vp]
+_lib.kv_dequant.argtypes = [_vp, _i32, _vp, _vp, _i32, _vp]
 _lib.kv_decode_splits.argtypes = [_vp, _i32, ctypes.POINTER(_i32)]
 _lib.kv_decode_bytes.argtypes = [_vp, _i32, _szp]
 _lib.kv_set_decode_path.argtypes = [_vp, _i32]
@@ -238,6 +239,10 @@ def kv_decode_attn_merge(cache: int, layer: int, out_ptr: int, ws_ptr: int, ws_b
     _check(_lib.kv_decode_attn_merge(cache, layer, out_ptr, ws_ptr, ws_bytes, stream), "kv_decode_attn_merge")
 
 
+def kv_dequant(cache: int, layer: int, k_out_ptr: int, v_out_ptr: int, t_cap: int, stream: int = 0) -> None:
+    _check(_lib.kv_dequant(cache, layer, k_out_ptr, v_out_ptr, t_cap, stream), "kv_dequant")
+
+
 def kv_decode_attn_merge16(cache: int, layer: int, out16_ptr: int, ws_ptr: int, ws_bytes: int, stream: int = 0) -> None:
     _check(_lib.kv_decode_attn_merge16(cache, layer, out16_ptr, ws_ptr, ws_bytes, stream), "kv_decode_attn_merge16")
 
@@ -338,6 +343,16 @@ class KVCache:
         kv_decode_attn(self.handle, layer, q.data_ptr(), out.data_ptr(), self.workspace.data_ptr(),
                        self.ws_bytes, self._stream())
         return out
+
+    def dequant(self, layer: int, t_cap: int):
+        """The layer's reconstructed keys and values, float32 [B, t_cap, Hkv, d] each (zeros past a
+        sequence's length)."""
+        torch = self.torch
+        shape = (self.cfg.batch, t_cap, self.cfg.n_kv_heads, self.cfg.head_dim)
+        k = torch.zeros(shape, dtype=torch.float32, device=self.device)
+        v = torch.zeros(shape, dtype=torch.float32, device=self.device)
+        kv_dequant(self.handle, layer, k.data_ptr(), v.data_ptr(), t_cap, self._stream())
+        return k, v
 
     def attend16(self, layer: int, q):
         """As attend, with the output in q's 16-bit type (split, then the narrowing merge)."""

@@ -409,6 +409,79 @@ __global__ __launch_bounds__(256) void merge_kernel(DecodeArgs a)
     else *(float2 *)(a.out + o) = r;
 }
 
+// code (token t, channel c) of a block's key (which = 0) or value side, from the packed words
+template <int B> __device__ __forceinline__ uint32_t code_of(const unsigned char *codes, int which, int G, int t, int c)
+{
+    constexpr int PW = 32 / B; // codes per word
+    const uint32_t *w = (const uint32_t *)codes;
+    int j; // number of the code inside its word: code 4 f + y is field f of byte y
+    uint32_t word;
+    if (which == 0) {
+        word = w[k_word<B>(t, c - c % PW)];
+        j = c % PW;
+    } else {
+        word = w[v_word<B>(t - t % PW, c, G / 16)];
+        j = t % PW;
+    }
+    return (word >> (B * (j >> 2) + 8 * (j & 3))) & ((1u << B) - 1u);
+}
+
+// Reconstruction (Eq. 7-8): x^ = mean + (zero + scale * code) in binary32, one rounding per
+// operation, in that order; raw rows (16-bit layers, the residual buffer) are widened.
+// grid (blocks of the longest sequence + 1, units, K | V): workgroup (j, u, which) writes block j of
+// unit u, the last index of x the unit's raw tail.  out [batch][t_cap][n_kv_heads][128] binary32.
+__global__ __launch_bounds__(kThreads) void dequant_kernel(DequantArgs q)
+{
+    const DecodeArgs &a = q.d;
+    const LayerGeom &gm = a.geom;
+    const int G = gm.G, u = blockIdx.y, which = blockIdx.z;
+    const int b = u / a.n_kv_heads, h = u % a.n_kv_heads;
+    float *out = which == 0 ? q.k_out : q.v_out;
+    if (!out) return;
+    const int nb = seq_blocks(a, b), r = seq_resid(a, b);
+    const int bits = which == 0 ? gm.k_bits : gm.v_bits;
+    float *dst_u = out + ((long long)b * q.t_cap * a.n_kv_heads + h) * kHeadDim; // token stride: n_kv_heads * 128
+    const long long tstride = (long long)a.n_kv_heads * kHeadDim;
+    if ((int)blockIdx.x == a.n_blocks) {
+        const unsigned char *raw = a.layer + (which == 0 ? gm.k_resid_off : gm.v_resid_off) + (long long)u * gm.R * 256;
+        for (int e = threadIdx.x; e < r * kHeadDim; e += kThreads) {
+            const int t = e / kHeadDim, c = e % kHeadDim;
+            dst_u[(long long)(nb * G + t) * tstride + c] = widen16(*(const uint16_t *)(raw + t * 256 + c * 2), gm.dtype);
+        }
+        return;
+    }
+    const int j = blockIdx.x;
+    if (j >= nb) return;
+    const unsigned char *rec = a.layer + record_offset(gm, a.n_kv_heads, b, h, j);
+    const unsigned char *codes = rec + (which == 0 ? gm.k_codes : gm.v_codes);
+    const uint16_t *xm = gm.mean_mode == 1 && bits != 16 ? (const uint16_t *)(a.layer + xmean_offset(gm, b, j, which)) : nullptr;
+    const int ng = kHeadDim / gm.Gc;
+    for (int e = threadIdx.x; e < G * kHeadDim; e += kThreads) {
+        const int t = e / kHeadDim, c = e % kHeadDim;
+        float x;
+        if (bits == 16) {
+            x = widen16(*(const uint16_t *)(codes + (t * kHeadDim + c) * 2), gm.dtype);
+        } else {
+            const uint32_t code = bits == 2 ? code_of<2>(codes, which, G, t, c)
+                                            : bits == 4 ? code_of<4>(codes, which, G, t, c) : code_of<8>(codes, which, G, t, c);
+            float sc, z, m = 0.0f;
+            if (which == 0) {
+                sc = f16_val(*(const uint16_t *)(rec + gm.k_scale + c * 2));
+                z = f16_val(*(const uint16_t *)(rec + gm.k_zero + c * 2));
+                if (gm.k_mean >= 0) m = f16_val(*(const uint16_t *)(rec + gm.k_mean + c * 2));
+            } else {
+                const uint32_t sz = *(const uint32_t *)(rec + gm.v_meta + (t * ng + c / gm.Gc) * 4);
+                sc = f16_val((uint16_t)(sz & 0xFFFFu));
+                z = f16_val((uint16_t)(sz >> 16));
+                if (gm.v_mean >= 0) m = f16_val(*(const uint16_t *)(rec + gm.v_mean + c * 2));
+            }
+            if (xm) m = f16_val(xm[t * kHeadDim + c]);
+            x = __fadd_rn(m, __fadd_rn(z, __fmul_rn(sc, (float)code)));
+        }
+        dst_u[(long long)(j * G + t) * tstride + c] = x;
+    }
+}
+
 template <int KB, int VB> hipError_t launch_one(const DecodeArgs &a, hipStream_t s)
 {
     const int g = a.g, G = a.geom.G;
@@ -444,6 +517,16 @@ hipError_t launch_decode_split_valu(const DecodeArgs &a, hipStream_t s)
     TADAKV_CASE(8, 2) TADAKV_CASE(8, 4) TADAKV_CASE(8, 8)
 #undef TADAKV_CASE
     return hipErrorInvalidValue;
+}
+
+hipError_t launch_dequant(const DequantArgs &q, hipStream_t s)
+{
+    const DecodeArgs &a = q.d;
+    const int U = a.batch * a.n_kv_heads;
+    if (U > 65535) return hipErrorInvalidValue;
+    (void)hipGetLastError(); // drop any stale error left by earlier runtime calls of this thread
+    hipLaunchKernelGGL(dequant_kernel, dim3(a.n_blocks + 1, U, 2), dim3(kThreads), 0, s, q);
+    return note_launch(hipGetLastError());
 }
 
 hipError_t launch_decode_merge(const DecodeArgs &a, hipStream_t s)

@@ -678,6 +678,24 @@ kv_status kv_decode_attn_merge16(const kv_cache *cache, int32_t layer, void *out
     return merge_impl(cache, layer, nullptr, (uint16_t *)out16, workspace, workspace_bytes, stream);
 }
 
+kv_status kv_dequant(const kv_cache *cache, int32_t layer, float *k_out, float *v_out, int32_t t_cap, void *stream)
+{
+    kv_status st = layer_ok(cache, layer);
+    if (st != KV_OK) return st;
+    if (!k_out && !v_out) return KV_E_NULL;
+    if (((uintptr_t)k_out % 16) || ((uintptr_t)v_out % 16)) return KV_E_ALIGN;
+    const kv_config &c = cache->cfg;
+    for (int b = 0; b < c.batch; b++)
+        if (cache->on(b) && cache->P(layer, b) + cache->R(layer, b) > t_cap) return KV_E_CAPACITY;
+    DequantArgs q{};
+    st = fill_decode(cache, layer, &q.d);
+    if (st != KV_OK) return st;
+    q.k_out = k_out;
+    q.v_out = v_out;
+    q.t_cap = t_cap;
+    return launch_dequant(q, (hipStream_t)stream) == hipSuccess ? KV_OK : KV_E_HIP;
+}
+
 kv_status kv_append_decode_attn_split(kv_cache *cache, int32_t layer, const void *k_new, const void *v_new,
                                       int64_t stride_b, int64_t stride_h, const void *q,
                                       void *workspace, size_t workspace_bytes, void *stream)

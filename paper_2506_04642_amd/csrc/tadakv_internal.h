@@ -99,6 +99,13 @@ struct DecodeArgs {
 __host__ __device__ inline int seq_blocks(const DecodeArgs &a, int b) { return a.ragged ? a.nb_seq[b] : a.n_blocks; }
 __host__ __device__ inline int seq_resid(const DecodeArgs &a, int b) { return a.ragged ? a.r_seq[b] : a.r; }
 
+// reconstruction of a layer's contents: lengths and geometry as for a decode launch
+struct DequantArgs {
+    DecodeArgs d;
+    float *k_out, *v_out; // [batch][t_cap][n_kv_heads][128] binary32, either may be null
+    int t_cap;
+};
+
 // records the outcome of a launch for kv_last_hip_error and passes it through
 hipError_t note_launch(hipError_t e);
 
@@ -109,6 +116,7 @@ hipError_t launch_decode_split_mfma(const DecodeArgs &a, hipStream_t s);
 bool decode_mfma_supported(const DecodeArgs &a);
 int decode_mfma_splits(const DecodeArgs &a); // preferred split count of the matrix-core kernel
 hipError_t launch_decode_merge(const DecodeArgs &a, hipStream_t s);
+hipError_t launch_dequant(const DequantArgs &q, hipStream_t s);
 // cross-head mean, matrix-core path: scores of the queries against the key mean plane (before the
 // split kernel) and the value mean plane's contribution to the partial outputs (before the merge)
 hipError_t launch_xhead_scores(const DecodeArgs &a, hipStream_t s);

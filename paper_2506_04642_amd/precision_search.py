@@ -85,9 +85,42 @@ def measure_layer_errors(n_layers: int, *, seed: int = 0, batch: int = 2, n_q_he
     return err
 
 
+def measure_reconstruction_errors(n_layers: int, *, seed: int = 0, batch: int = 2, n_q_heads: int = 8, n_kv_heads: int = 2,
+                                  context: int = 1024, group: int = 32, dtype: int = 1, mean_mode: int = 0,
+                                  shared_sigma: float = 0.0, device: str = "cuda:0") -> np.ndarray:
+    """err[l, i, side]: Frobenius norm of (x - x^) over that of x for the keys (side 0) and values
+    (side 1) of synthetic layer l stored at WIDTHS[i]; x^ is the cache's reconstruction (Eq. 7-8)
+    through the C ABI."""
+    import torch
+
+    from . import binding as kv
+    from . import synth
+
+    d = 128
+    bits = list(WIDTHS)
+    cfg = kv.make_config(len(bits), batch, n_q_heads, n_kv_heads, d, context + group, group, group, group, dtype,
+                         mean_mode, bits, bits)
+    cache = kv.KVCache(cfg, device=device, zero=False)
+    err = np.zeros((n_layers, len(WIDTHS), 2))
+    for l in range(n_layers):
+        n_outlier, _ = layer_recipe(seed, l, n_layers)
+        k, v = synth.make_kv_torch(seed * 1000 + l, batch, context, n_kv_heads, d, dtype, device, n_outlier=n_outlier,
+                                   shared_sigma=shared_sigma)
+        kv.kv_cache_reset(cache.handle, -1)
+        for i in range(len(bits)):
+            cache.append(i, k, v)
+            kh, vh = cache.dequant(i, context)
+            for side, (x, xh) in enumerate(((k, kh), (v, vh))):
+                x = x.double()
+                err[l, i, side] = float((x - xh.double()).pow(2).sum().sqrt() / x.pow(2).sum().sqrt())
+    cache.close()
+    return err
+
+
 def mean_mode_table(n_layers: int = 4, *, seed: int = 0, shared_sigma: float = 2.0, **measure_kw) -> Dict[str, list]:
     """Synthetic analogue of the paper's error comparison with and without mean-centring (Fig. 2):
-    the decode-attention error against the 16-bit cache, averaged over n_layers synthetic layers,
+    the relative Frobenius error of the reconstructed keys and values and the decode-attention
+    error against the 16-bit cache, averaged over n_layers synthetic layers,
     for no mean, the per-channel block mean and the mean over kv heads, at 2 / 4 / 8 bits.  The
     inputs carry a component shared by all kv heads (shared_sigma), which is the structure the
     paper attributes to real caches; with shared_sigma = 0 the mean over heads has nothing to
@@ -99,7 +132,10 @@ def mean_mode_table(n_layers: int = 4, *, seed: int = 0, shared_sigma: float = 2
     for name, mode in (("none", 2), ("channel_block", 0), ("cross_head", 1)):
         err = measure_layer_errors(n_layers, seed=seed, mean_mode=mode, shared_sigma=shared_sigma, **measure_kw)
         per_token = bytes_per_token(128, group, group, mode, measure_kw["n_kv_heads"])
+        rec = measure_reconstruction_errors(n_layers, seed=seed, mean_mode=mode, shared_sigma=shared_sigma, **measure_kw)
         out[name] = {"rel_rms_error": [float(x) for x in err.mean(axis=0)],
+                     "k_rel_frobenius": [float(x) for x in rec[:, :, 0].mean(axis=0)],
+                     "v_rel_frobenius": [float(x) for x in rec[:, :, 1].mean(axis=0)],
                      "bytes_vs_16bit": [per_token[b] / per_token[16] for b in WIDTHS]}
     return out
 
