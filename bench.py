@@ -177,7 +177,8 @@ def main():
         idx = [l for l in range(L) if bits[l] == b_]
         ms = float(split_ms[:, idx].mean())
         byts = float(np.mean([layer_bytes[l] for l in idx]))
-        per_bits[str(b_)] = {"layers": len(idx), "avg_ms": round(ms, 5), "bytes": int(byts),
+        per_bits[str(b_)] = {"layers": len(idx), "splits": kv.kv_decode_splits(cache.handle, idx[0]),
+                             "avg_ms": round(ms, 5), "bytes": int(byts),
                              "GBps": round(byts / ms / 1e6, 1), "frac": round(byts / ms / 1e6 / HBM_PEAK_GBPS, 4),
                              "traffic": int(byts * TRAFFIC_RATIO[b_]) if b_ in TRAFFIC_RATIO and args.path != 1 else None}
     achieved = float(sum(layer_bytes)) / float(split_ms.mean(axis=0).sum()) / 1e6

@@ -55,3 +55,29 @@ def test_decode_call_replayed_from_a_graph(kv, oracle, mode, bits):
         assert torch.equal(out_static, eager), "replay %d differs from the eager call" % rep
         err = float(np.max(np.abs(out_static.cpu().numpy().astype(np.float64) - orc.attend(0, q))))
         assert err <= ATTN_TOL, (rep, err)
+
+
+def test_calls_on_a_stream_of_their_own(kv, oracle):
+    """The library enqueues on the stream it is given: the same calls on a side stream give the
+    same cache bytes and outputs as on the default stream."""
+    import torch
+
+    from parity_util import check_bytes
+
+    print("case side stream", flush=True)
+    B, Hq, Hkv, T = 2, 8, 2, 700
+    gpu, orc = make_pair(kv, oracle, B=B, Hq=Hq, Hkv=Hkv, T_max=1024, dtype=BF16, mode=CHAN, k_bits=(4,))
+    k, v = synth.make_kv(1700, B, T, Hkv, 128, BF16)
+    kd, vd = to_dev(k, BF16), to_dev(v, BF16)
+    q = synth.make_q(1701, B, Hq, 128, BF16)
+    qd = to_dev(q, BF16)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        gpu.append(0, kd[:, :T - 1], vd[:, :T - 1])
+        out = gpu.append_attend(0, kd[:, T - 1:], vd[:, T - 1:], qd)
+    side.synchronize()
+    orc.append(0, k, v)
+    check_bytes(gpu, orc, 0)
+    err = float(np.max(np.abs(out.cpu().numpy().astype(np.float64) - orc.attend(0, q))))
+    assert err <= ATTN_TOL
