@@ -15,6 +15,10 @@
  *   per-layer bits  : one bit width in {2,4,8} (or 16 = stored raw) per layer for keys and for
  *                     values (Sec. 3.3 "Searching for quantization precision", App. B); the map is
  *                     an input here, the search that produces it is not part of this library.
+ *   around these    : kv_rope_quant_append (Algorithm 1 step 5: the rotary embedding fused into the
+ *                     key append), kv_append_decode_attn (steps 8-9 in one call), kv_dequant (Eq. 7-8
+ *                     as tensors), sequences of different lengths, paged placement of the blocks
+ *                     (kv_cache_set_block_table), idle slots (kv_cache_set_active).
  *
  * Conventions
  *   - Every function returns KV_OK (0) or a negative kv_status.  Nothing throws or aborts.
