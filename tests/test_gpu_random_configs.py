@@ -3,6 +3,8 @@ group sizes, mean mode, heads, raw-buffer length, dtype, dense or paged placemen
 sequences with prompts of different lengths, then mixes batch-wide appends, one-call decode steps,
 per-sequence appends, resets and activity masks, checking attention after every step and the cache
 bytes at the end against the CPU oracle."""
+import os
+
 import numpy as np
 import pytest
 
@@ -59,7 +61,8 @@ def gather_check(kv, oracle, gpu, orc, table):
         assert np.array_equal(got[go:go + sz][m], img["bytes"][oo:oo + sz][m]), name
 
 
-@pytest.mark.parametrize("case", range(48))
+# more cases on request: TADAKV_RANDOM_CASES=1000 python -m pytest tests/test_gpu_random_configs.py
+@pytest.mark.parametrize("case", range(int(os.environ.get("TADAKV_RANDOM_CASES", "48"))))
 def test_random_configuration_and_call_sequence(kv, oracle, case):
     import torch
 
@@ -78,7 +81,8 @@ def test_random_configuration_and_call_sequence(kv, oracle, case):
     dtype = int(rng.integers(0, 2))
     paged = bool(rng.random() < 0.4)
     path = int(rng.choice([0, 0, 1]))
-    NB = 6 * (R // G)
+    long_case = bool(rng.random() < 0.25)  # a quarter of the cases start from prompts of many blocks
+    NB = (40 if long_case else 6) * (R // G)
     T_max = NB * G
     pool = B * NB - int(rng.integers(0, NB)) if paged else 0
     print("case %d: G=%d Gc=%d bits=%d/%d mode=%d Hkv=%d g=%d B=%d R=%d dtype=%d paged=%s path=%d" % (
@@ -121,6 +125,15 @@ def test_random_configuration_and_call_sequence(kv, oracle, case):
                 err = float(np.max(np.abs(got[b] - want[b])))
                 assert err <= ATTN_TOL, (b, err)
 
+    if long_case:
+        for b in range(B):
+            n = int(rng.integers(0, min(cap[b], 30 * G)))
+            if n:
+                k, v = synth.make_kv(seed + 7000 + b, 1, n, Hkv, 128, dtype)
+                gpu.append_seq(0, b, to_dev(k[0], dtype), to_dev(v[0], dtype))
+                orc.append_seq(0, b, k[0], v[0])
+                length[b] += n
+        attend_check()
     for step in range(14):
         op = rng.choice(["seq", "batch", "step", "step", "reset", "mask"])
         if op == "seq":
