@@ -317,6 +317,16 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
             stage_issue<REC>(src, stage + (NBC - 1) * (REC / 4), lane);
         }
     };
+    // the query words are requested ahead of the first chunk: loads return in order, and the
+    // query is worked on while the chunk is still on its way
+    uint2 qraw[NHG][2];
+#pragma unroll
+    for (int hg = 0; hg < NHG; hg++) {
+        const int head = 4 * hg + row;
+        const uint16_t *qp = a.q + ((long long)b * a.n_q_heads + h * g + (head < g ? head : 0)) * kHeadDim;
+#pragma unroll
+        for (int ph = 0; ph < 2; ph++) qraw[hg][ph] = *(const uint2 *)(qp + 32 * vq + 16 * ph + 4 * qa);
+    }
     if (wave < n_chunks) issue(wave);
 
     // ---- query of heads 4*hg + row: this lane's eight channels, widened and as binary16 pairs
@@ -327,14 +337,14 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
 #pragma unroll
     for (int hg = 0; hg < NHG; hg++) {
         const int head = 4 * hg + row;
-        const uint16_t *qp = a.q + ((long long)b * a.n_q_heads + h * g + (head < g ? head : 0)) * kHeadDim;
         float qmax = 0.0f;
 #pragma unroll
         for (int ph = 0; ph < 2; ph++)
 #pragma unroll
             for (int y = 0; y < 4; y++) {
-                const int c = 32 * vq + 16 * ph + 4 * qa + y;
-                qf[hg][ph][y] = head < g ? widen16(qp[c], gm.dtype) : 0.0f;
+                const uint32_t w = (y & 2) ? qraw[hg][ph].y : qraw[hg][ph].x;
+                const uint16_t q16 = (uint16_t)((y & 1) ? (w >> 16) : (w & 0xFFFFu));
+                qf[hg][ph][y] = head < g ? widen16(q16, gm.dtype) : 0.0f;
                 qmax = fmaxf(qmax, fabsf(qf[hg][ph][y]));
             }
         qmax = row_max(qmax);
