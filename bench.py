@@ -178,7 +178,9 @@ def main():
         ms = float(split_ms[:, idx].mean())
         byts = float(np.mean([layer_bytes[l] for l in idx]))
         per_bits[str(b_)] = {"layers": len(idx), "splits": kv.kv_decode_splits(cache.handle, idx[0]),
-                             "avg_ms": round(ms, 5), "bytes": int(byts),
+                             "avg_ms": round(ms, 5), "median_ms": round(float(np.median(split_ms[:, idx])), 5),
+                             "p10_ms": round(float(np.percentile(split_ms[:, idx], 10)), 5),
+                             "p90_ms": round(float(np.percentile(split_ms[:, idx], 90)), 5), "bytes": int(byts),
                              "GBps": round(byts / ms / 1e6, 1), "frac": round(byts / ms / 1e6 / HBM_PEAK_GBPS, 4),
                              "traffic": int(byts * TRAFFIC_RATIO[b_]) if b_ in TRAFFIC_RATIO and args.path != 1 else None}
     achieved = float(sum(layer_bytes)) / float(split_ms.mean(axis=0).sum()) / 1e6
