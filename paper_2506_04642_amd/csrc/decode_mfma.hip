@@ -199,6 +199,28 @@ __device__ __forceinline__ void stage_issue(const unsigned char *src, uint32_t *
 }
 __device__ __forceinline__ void stage_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
+// Blocks of 128 tokens are read as two halves of 64: the pieces of half hf of the record at src
+// (its key codes, the block's key metadata, its runs of value codes -- 1 KiB per group of channel
+// tiles --, its value metadata, the block's value mean) are placed so that the staging buffer
+// holds the image of a 64-token record, which is what the arithmetic below works on.  A wave
+// takes the two halves of a block one after the other; the pieces they share are fetched with the
+// first (shared) and stay in the buffer for the second.
+template <int B, int GC, bool MEAN>
+__device__ __forceinline__ void stage_issue_half(const unsigned char *src, int hf, bool shared, uint32_t *dst, int lane)
+{
+    typedef RecLayout<B, 64, GC, MEAN> RL;   // the image
+    typedef RecLayout<B, 128, GC, MEAN> RS;  // the record
+    constexpr int NG = kHeadDim / GC;
+    static_assert(RS::KC == 2 * RL::KC && RL::KC % 1024 == 0, "code halves");
+    stage_issue<RL::KC>(src + RS::K_CODES + hf * RL::KC, dst + RL::K_CODES / 4, lane);
+    if (shared) stage_issue<512 + (MEAN ? 256 : 0)>(src + RS::K_SCALE, dst + RL::K_SCALE / 4, lane);
+#pragma unroll
+    for (int r = 0; r < RL::KC / 1024; r++)
+        stage_issue<1024>(src + RS::V_CODES + (2 * r + hf) * 1024, dst + (RL::V_CODES + r * 1024) / 4, lane);
+    stage_issue<64 * NG * 4>(src + RS::V_META + hf * 64 * NG * 4, dst + RL::V_META / 4, lane);
+    if (MEAN && shared) stage_issue<256>(src + RS::V_MEAN, dst + RL::V_MEAN / 4, lane);
+}
+
 // int8 operand of the matrix instruction for the codes held in a lane
 template <int B> struct CodeOps;
 template <> struct CodeOps<4> { // two words = one tile line of 16 codes
@@ -228,11 +250,17 @@ template <> struct CodeOps<8> { // four words = one tile line; split into nibble
 // score comes in through a.xs, and the softmax weights go out through a.xp / a.xmc for the kernel
 // that adds the value mean plane's share to the partial outputs.
 // PG: paged placement (block slots through a table); the dense instances carry none of its state.
-template <int B, int G, int GC, bool MEAN, int NW, int NHG, bool XH, bool PG>
+// GS: tokens per block of the cache (32, 64, or 128 read as two halves of 64).
+template <int B, int GS, int GC, bool MEAN, int NW, int NHG, bool XH, bool PG>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2 && NHG == 1 && !XH) ? (PG ? 3 : 4) : 1, 8))) void decode_split_mfma_kernel(DecodeArgs a)
 {
     static_assert(!(XH && MEAN), "cross-head layers store no per-record mean");
-    typedef RecLayout<B, G, GC, MEAN> RL;
+    constexpr bool H2 = GS == 128;         // a block is worked on as two halves
+    static_assert(!(H2 && XH), "the dense mean kernels take blocks of at most 64 tokens");
+    constexpr int G = H2 ? 64 : GS;        // tokens per block as the arithmetic sees it
+    constexpr int HB = GS / G;             // such blocks per block of the cache
+    typedef RecLayout<B, G, GC, MEAN> RL;  // the staged image
+    constexpr int SREC = RecLayout<B, GS, GC, MEAN>::REC; // bytes of a record in the cache
     constexpr int NBC = 64 / G;            // blocks per 64-token chunk
     constexpr int TPB = G / 16;            // 16-token tiles per block
     constexpr int NG = kHeadDim / GC;      // value scale groups
@@ -270,32 +298,42 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
     // ---- chunks of this split: the splits of a unit interleave chunk by chunk (split sp, wave w
     // takes chunks sp + n_splits * (w + NW * k)), so that together they sweep the unit's records
     // front to back as one moving window instead of as n_splits far-apart streams
-    const int b_end = seq_blocks(a, b), r_seq = seq_resid(a, b); // this sequence's packed blocks and raw tokens
+    const int b_end = seq_blocks(a, b) * HB, r_seq = seq_resid(a, b); // this sequence's packed blocks and raw tokens
     const int chunks_total = (b_end + NBC - 1) / NBC;
     const int ns = a.n_splits;
     // local chunk j of this split is the unit's chunk sp + ns * j
-    const int n_chunks = sp < chunks_total ? (chunks_total - sp + ns - 1) / ns : 0;
     const int w0 = sp * NBC;          // first block of local chunk 0
     const int cstride = ns * NBC;     // blocks between consecutive local chunks
-    const unsigned char *unit_base = a.layer + (long long)u * gm.NB * REC;
+    // H2: the splits interleave block by block, and a wave's chunks 2 k and 2 k + 1 are the two
+    // halves of its k-th block; n_chunks is then the wave's own bound (wave + NW * its chunks)
+    const int blocks_sp = sp * HB < chunks_total ? (chunks_total / HB - sp + ns - 1) / ns : 0; // H2 only
+    const int n_chunks = H2 ? wave + NW * 2 * ((blocks_sp - wave + NW - 1) / NW)
+                            : (sp < chunks_total ? (chunks_total - sp + ns - 1) / ns : 0);
+    // first block (as the arithmetic counts them) of this wave's local chunk ci = wave + NW * k
+    auto blk_of = [&](int ci) {
+        if (!H2) return w0 + ci * cstride;
+        const int k = (ci - wave) / NW;
+        return 2 * (sp + ns * (wave + NW * (k >> 1))) + (k & 1);
+    };
+    const unsigned char *unit_base = a.layer + (long long)u * gm.NB * SREC;
 
     // Paged placement: lane l keeps the slots of the blocks of this wave's chunk number slot_base + l
     // (one table read per 64 chunks of the wave), so that the fetch of a chunk waits for no lookup.
     int slotv[NBC], slot_base = 0;
     auto load_slots = [&](int it0) {
         slot_base = it0;
-        const int blk0 = w0 + (wave + NW * (it0 + lane)) * cstride;
+        const int blk0 = blk_of(wave + NW * (it0 + lane));
 #pragma unroll
         for (int bi = 0; bi < NBC; bi++) {
             int blk = blk0 + bi < b_end ? blk0 + bi : blk0; // no second block: the first one again
             blk = blk < b_end ? blk : b_end - 1;            // chunks past the end: any block the sequence has
-            slotv[bi] = blk >= 0 ? (int)block_slot(gm, b, blk) : 0;
+            slotv[bi] = blk >= 0 ? (int)block_slot(gm, b, blk / HB) : 0;
         }
     };
     if (PG) load_slots(0);
 
     auto issue = [&](int ci) {
-        const int blk0 = w0 + ci * cstride;
+        const int blk0 = blk_of(ci);
         if (PG) {
             // every block of the chunk has a place of its own
             const int it = (ci - wave) / NW;
@@ -303,12 +341,16 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
 #pragma unroll
             for (int bi = 0; bi < NBC; bi++) {
                 const long long slot = __builtin_amdgcn_readlane(slotv[bi], it - slot_base);
-                stage_issue<REC>(a.layer + (slot * a.n_kv_heads + h) * REC, stage + bi * (REC / 4), lane);
+                const unsigned char *rec = a.layer + (slot * a.n_kv_heads + h) * SREC;
+                if (H2) stage_issue_half<B, GC, MEAN>(rec, blk0 & 1, !(blk0 & 1), stage, lane);
+                else stage_issue<REC>(rec, stage + bi * (REC / 4), lane);
             }
             return;
         }
-        const unsigned char *src = unit_base + (long long)blk0 * REC;
-        if (NBC == 1 || blk0 + 1 < b_end) {
+        const unsigned char *src = unit_base + (long long)(blk0 / HB) * SREC;
+        if (H2) {
+            stage_issue_half<B, GC, MEAN>(src, blk0 & 1, !(blk0 & 1), stage, lane);
+        } else if (NBC == 1 || blk0 + 1 < b_end) {
             stage_issue<CB>(src, stage, lane);
         } else {
             // the chunk's second block does not exist: stage the first one twice so that the
@@ -375,7 +417,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
     long long xq[NHG]; // query head index in the batch
     float xsn[NHG][4];
     auto load_xs = [&](int ci) {
-        const int blk = w0 + ci * cstride;
+        const int blk = blk_of(ci);
 #pragma unroll
         for (int hg = 0; hg < NHG; hg++)
 #pragma unroll
@@ -404,7 +446,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
             else if (quart == 2) __builtin_amdgcn_s_setprio(1);
             else __builtin_amdgcn_s_setprio(0);
         }
-        const int blk0 = w0 + ci * cstride;
+        const int blk0 = blk_of(ci);
         bool blk_ok[NBC];
 #pragma unroll
         for (int bi = 0; bi < NBC; bi++) blk_ok[bi] = blk0 + bi < b_end;
@@ -434,6 +476,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
             if (NG == 4) {
                 const uint4 t = *(const uint4 *)p;
                 vm[k][0] = t.x; vm[k][1 % NG] = t.y; vm[k][2 % NG] = t.z; vm[k][3 % NG] = t.w;
+            } else if (NG == 1) {
+                vm[k][0] = *(const uint32_t *)p;
             } else {
                 const uint2 t = *(const uint2 *)p;
                 vm[k][0] = t.x; vm[k][1 % NG] = t.y;
@@ -861,10 +905,10 @@ template <int B, int G, int GC, bool MEAN, int NHG, bool XH, bool PG> hipError_t
 // the kernel is a bandwidth stream, and a second, partly filled round only adds a tail.
 template <int B, int G, int GC, bool MEAN, int NHG, bool XH, bool PG> int plan_inst(const DecodeArgs &a)
 {
-    constexpr int NW = kWavesPerBlock, NBC = 64 / G;
+    constexpr int NW = kWavesPerBlock;
     const int slots = resident_blocks<B, G, GC, MEAN, NW, NHG, XH, PG>();
     const int U = a.batch * a.n_kv_heads;
-    const int chunks = (a.n_blocks + NBC - 1) / NBC;
+    const int chunks = (a.n_blocks * G + 63) / 64; // chunks of 64 tokens
     int ns = slots / U;
     // at least four chunks per wave, or the prologue dominates -- unless the launch is so small that
     // the device cannot be filled even then: such a launch is bound by latency, and the widest
@@ -910,6 +954,23 @@ template <int B, int G, int GC, class F> void pick_mean_heads(const DecodeArgs &
     if (a.geom.table) pick_mean_heads_pg<B, G, GC, true>(a, f);
     else pick_mean_heads_pg<B, G, GC, false>(a, f);
 }
+// blocks of 128 tokens: no instance for the mean over the heads
+template <int B, bool PG, class F> void pick_heads_128_pg(const DecodeArgs &a, F &f)
+{
+    const bool mean = a.geom.mean_mode == 0;
+    if (a.g <= 4) {
+        if (mean) f.template run<B, 128, 128, true, 1, false, PG>(a);
+        else f.template run<B, 128, 128, false, 1, false, PG>(a);
+    } else {
+        if (mean) f.template run<B, 128, 128, true, 2, false, PG>(a);
+        else f.template run<B, 128, 128, false, 2, false, PG>(a);
+    }
+}
+template <int B, class F> void pick_heads_128(const DecodeArgs &a, F &f)
+{
+    if (a.geom.table) pick_heads_128_pg<B, true>(a, f);
+    else pick_heads_128_pg<B, false>(a, f);
+}
 template <class F> void pick(const DecodeArgs &a, F &f)
 {
     const int bits = a.geom.k_bits;
@@ -917,10 +978,14 @@ template <class F> void pick(const DecodeArgs &a, F &f)
         if (bits == 2) pick_mean_heads<2, 32, 32>(a, f);
         else if (bits == 4) pick_mean_heads<4, 32, 32>(a, f);
         else pick_mean_heads<8, 32, 32>(a, f);
-    } else {
+    } else if (a.geom.G == 64) {
         if (bits == 2) pick_mean_heads<2, 64, 64>(a, f);
         else if (bits == 4) pick_mean_heads<4, 64, 64>(a, f);
         else pick_mean_heads<8, 64, 64>(a, f);
+    } else {
+        if (bits == 2) pick_heads_128<2>(a, f);
+        else if (bits == 4) pick_heads_128<4>(a, f);
+        else pick_heads_128<8>(a, f);
     }
 }
 
@@ -931,7 +996,8 @@ bool decode_mfma_supported(const DecodeArgs &a)
     const LayerGeom &g = a.geom;
     if (g.k_bits != g.v_bits) return false;
     if (!(g.k_bits == 2 || g.k_bits == 4 || g.k_bits == 8)) return false;
-    if (!((g.G == 32 && g.Gc == 32) || (g.G == 64 && g.Gc == 64))) return false;
+    if (!((g.G == 32 && g.Gc == 32) || (g.G == 64 && g.Gc == 64) || (g.G == 128 && g.Gc == 128 && g.mean_mode != 1)))
+        return false;
     if (a.g > 8) return false;
     if (g.mean_mode == 1 && a.n_q_heads > 64) return false; // the dense mean terms keep all query heads of a sequence in LDS
     if (a.batch * a.n_kv_heads > 65535) return false;

@@ -998,17 +998,22 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ?
 }
 
 
-// The same for blocks of 64 tokens: a wave takes the block as two halves of 32 tokens, twice.
+// The same for blocks of 64 or 128 tokens: a wave takes the block in parts of 32 tokens, twice.
 // The first pass gathers what spans the block -- the per-channel sums in token order (the
-// running sum goes from quad lane 3 of the first half to quad lane 0 of the second) and, for
+// running sum goes from quad lane 3 of one part to quad lane 0 of the next) and, for
 // keys, the channels' extrema --, the second pass loads the rows again (they are in the cache),
-// forms the deviations and emits metadata, codes and words half by half.  With a per-channel
+// forms the deviations and emits metadata, codes and words part by part.  With a per-channel
 // mean m the extrema of the deviations are those of the raw values moved by m: rounding is
 // monotone, so min_t fl(x_t - m) = fl(min_t x_t - m).
-template <int GC, int BITS, bool ROPE>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ? 2 : 3, 8))) void flush_wave64_kernel(AppendArgs a, int n_items)
+template <int G, int GC, int BITS, bool ROPE> struct WaveImage {
+    static constexpr int NGV = kHeadDim / GC;
+    static constexpr int META_BYTES = G * NGV * 4 + 256 > 768 ? G * NGV * 4 + 256 : 768;
+    static constexpr int BYTES = G * kHeadDim * BITS / 8 + META_BYTES; // the larger of a record's key and value part
+};
+template <int G, int GC, int BITS, bool ROPE>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ? 2 : 3, 8))) void flush_wave_parts_kernel(AppendArgs a, int n_items)
 {
-    constexpr int G = 64;
+    constexpr int NP = G / 32; // parts of 32 tokens
     constexpr int NGV = kHeadDim / GC;
     constexpr int qmax = (1 << BITS) - 1;
     const LayerGeom &gm = a.geom;
@@ -1017,10 +1022,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ?
     const int tg = lane & 3, c8 = lane >> 2;
     const int U = a.batch * a.n_kv_heads;
     const int workers = (int)gridDim.x * (kThreads / 64);
-    constexpr int META_BYTES = G * NGV * 4 + 256 > 768 ? G * NGV * 4 + 256 : 768;
-    constexpr int IMG_BYTES = G * kHeadDim * BITS / 8 + META_BYTES;
-    __shared__ __attribute__((aligned(16))) unsigned char lds_img[kThreads / 64][IMG_BYTES];
-    unsigned char *img = lds_img[wave];
+    constexpr int IMG_BYTES = WaveImage<G, GC, BITS, ROPE>::BYTES;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_img[]; // [waves][IMG_BYTES], sized at launch
+    unsigned char *img = lds_img + wave * IMG_BYTES;
 
     for (int it = (int)blockIdx.x * (kThreads / 64) + wave; it < n_items; it += workers) {
         const int which = (it ^ (it / workers)) & 1, u = (it >> 1) % U, fb = (it >> 1) / U;
@@ -1075,7 +1079,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ?
         }
         if (mode == 0 || which == 0) {
 #pragma unroll
-            for (int half = 0; half < 2; half++) {
+            for (int half = 0; half < NP; half++) {
                 float x[8][8];
                 load_half(half, x);
                 if (mode == 0) {
@@ -1139,7 +1143,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ?
             float sc[8], rs[8], z[8];
             key_metadata(mn, mx, qmax, lane, img + (gm.k_scale - base_off), img + (gm.k_zero - base_off), sc, rs, z);
 #pragma unroll
-            for (int half = 0; half < 2; half++) {
+            for (int half = 0; half < NP; half++) {
                 float x[8][8];
                 load_half(half, x);
 #pragma unroll
@@ -1150,7 +1154,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ?
             }
         } else {
 #pragma unroll
-            for (int half = 0; half < 2; half++) {
+            for (int half = 0; half < NP; half++) {
                 float x[8][8];
                 load_half(half, x);
 #pragma unroll
@@ -1316,14 +1320,19 @@ template <int GC, int BITS, bool ROPE> hipError_t launch_flush_wave(const Append
     return note_launch(hipGetLastError());
 }
 
-template <int GC, int BITS, bool ROPE> hipError_t launch_flush_wave64(const AppendArgs &a, hipStream_t s)
+template <int G, int GC, int BITS, bool ROPE> hipError_t launch_flush_wave_parts(const AppendArgs &a, hipStream_t s)
 {
     const int U = a.batch * a.n_kv_heads;
     const long long items = (long long)a.n_flush_blocks * U * 2;
     if (items > 0x7FFFFFFF) return hipErrorInvalidValue;
+    constexpr size_t lds = (size_t)(kThreads / 64) * WaveImage<G, GC, BITS, ROPE>::BYTES;
     static const int slots = [] {
         int per_cu = 0, dev = 0, cus = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, flush_wave64_kernel<GC, BITS, ROPE>, kThreads, 0) != hipSuccess ||
+        if (lds > 64 * 1024 &&
+            hipFuncSetAttribute((const void *)flush_wave_parts_kernel<G, GC, BITS, ROPE>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+            return 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, flush_wave_parts_kernel<G, GC, BITS, ROPE>, kThreads, lds) != hipSuccess ||
             hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
             return 0;
@@ -1332,7 +1341,7 @@ template <int GC, int BITS, bool ROPE> hipError_t launch_flush_wave64(const Appe
     if (slots < 1) return hipErrorInvalidValue;
     const long long want = (items + kThreads / 64 - 1) / (kThreads / 64);
     const int grid = want < slots ? (int)want : slots;
-    hipLaunchKernelGGL((flush_wave64_kernel<GC, BITS, ROPE>), dim3(grid), dim3(kThreads), 0, s, a, (int)items);
+    hipLaunchKernelGGL((flush_wave_parts_kernel<G, GC, BITS, ROPE>), dim3(grid), dim3(kThreads), lds, s, a, (int)items);
     return note_launch(hipGetLastError());
 }
 
@@ -1359,14 +1368,18 @@ hipError_t launch_flush(const AppendArgs &a, hipStream_t s)
 #undef TADAKV_WAVE
     }
     if (a.geom.G == 64 && kb == a.geom.v_bits && kb != 16) {
-        // blocks of 64 tokens: the same wave kernel in two passes over two halves
+        // blocks of 64 tokens: the same arithmetic in two passes over two parts of 32 tokens
         const int gc = a.geom.Gc;
-#define TADAKV_WAVE64(GCV, R)                                                                        \
-    (kb == 2 ? launch_flush_wave64<GCV, 2, R>(a, s) : kb == 4 ? launch_flush_wave64<GCV, 4, R>(a, s) \
-                                                             : launch_flush_wave64<GCV, 8, R>(a, s))
-        if (a.rope != 0) return gc == 32 ? TADAKV_WAVE64(32, true) : gc == 64 ? TADAKV_WAVE64(64, true) : TADAKV_WAVE64(128, true);
-        return gc == 32 ? TADAKV_WAVE64(32, false) : gc == 64 ? TADAKV_WAVE64(64, false) : TADAKV_WAVE64(128, false);
-#undef TADAKV_WAVE64
+#define TADAKV_PARTS(GV, GCV, R)                                                \
+    (kb == 2 ? launch_flush_wave_parts<GV, GCV, 2, R>(a, s)                     \
+             : kb == 4 ? launch_flush_wave_parts<GV, GCV, 4, R>(a, s) : launch_flush_wave_parts<GV, GCV, 8, R>(a, s))
+        if (a.rope != 0) return gc == 32 ? TADAKV_PARTS(64, 32, true) : gc == 64 ? TADAKV_PARTS(64, 64, true) : TADAKV_PARTS(64, 128, true);
+        return gc == 32 ? TADAKV_PARTS(64, 32, false) : gc == 64 ? TADAKV_PARTS(64, 64, false) : TADAKV_PARTS(64, 128, false);
+    }
+    if (a.geom.G == 128 && a.geom.Gc == 128 && kb == a.geom.v_bits && kb != 16) {
+        // blocks of 128 tokens with one value group per token: four parts
+        return a.rope != 0 ? TADAKV_PARTS(128, 128, true) : TADAKV_PARTS(128, 128, false);
+#undef TADAKV_PARTS
     }
     if (a.geom.G == 32) return launch_flush_gc<32>(a, s);
     if (a.geom.G == 64) return launch_flush_gc<64>(a, s);

@@ -93,7 +93,8 @@ def check_bytes_paged(kv, oracle, gpu, orc, table):
 
 @pytest.mark.parametrize("path", [0, 1], ids=["auto", "valu"])
 @pytest.mark.parametrize("bits,G,R,mode,g", [(4, 32, 32, CHAN, 4), (2, 64, 64, CHAN, 8), (8, 32, 64, NONE, 2),
-                                             (4, 32, 32, CROSS, 4), (2, 64, 64, CROSS, 2)])
+                                             (4, 32, 32, CROSS, 4), (2, 64, 64, CROSS, 2), (8, 128, 128, CHAN, 8),
+                                             (2, 128, 128, NONE, 3)])
 def test_paged_prompts_then_decode_steps(kv, oracle, bits, G, R, mode, g, path):
     """Prompts of different lengths enter their slots one by one (slots handed out as needed, in a
     shuffled order, from a pool smaller than batch x capacity), then batch-wide one-call decode steps

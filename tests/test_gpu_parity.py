@@ -64,7 +64,7 @@ def test_llama8b_layer_bf16_4bit(kv, oracle, T):
 
 @pytest.mark.parametrize("bits", [2, 4, 8, 16])
 @pytest.mark.parametrize("dtype", [F16, BF16])
-@pytest.mark.parametrize("G,Gc", [(32, 32), (64, 64), (128, 32), (32, 128)])
+@pytest.mark.parametrize("G,Gc", [(32, 32), (64, 64), (128, 32), (32, 128), (128, 128)])
 def test_bit_widths_and_groups(kv, oracle, bits, dtype, G, Gc):
     print("case widths bits=%d dtype=%d G=%d Gc=%d" % (bits, dtype, G, Gc), flush=True)
     T = 3 * G + 5
@@ -332,6 +332,16 @@ def test_long_context_full_size(kv, oracle, decode_path):
     the library picks for it."""
     print("case long_context_full", flush=True)
     _full_size_sampled(kv, oracle, B=1, Hq=64, Hkv=8, G=64, T=131072 + 29, bits=(2, 4, 8), sample=(0,), seed=1300)
+
+
+@pytest.mark.parametrize("decode_path", [0], indirect=True, ids=["auto"])
+def test_long_context_blocks_of_128(kv, oracle, decode_path):
+    """Blocks and value groups of 128 (the group size of the paper's storage example, Sec. 3): a long
+    sequence with 64 query / 8 kv heads and one with 32 / 8, one layer per bit width, a raw tail."""
+    print("case long_context_g128", flush=True)
+    _full_size_sampled(kv, oracle, B=1, Hq=64, Hkv=8, G=128, T=32768 + 128 + 77, bits=(2, 4, 8), sample=(0,), seed=1500)
+    _full_size_sampled(kv, oracle, B=4, Hq=32, Hkv=8, G=128, T=8192 + 5, bits=(2, 4, 8), sample=(1, 3), seed=1510,
+                       decode_steps=8)
 
 
 @pytest.mark.parametrize("decode_path", [0], indirect=True, ids=["auto"])

@@ -41,7 +41,8 @@ def check_attend(gpu, orc, layer, q, dtype):
 
 
 @pytest.mark.parametrize("path", [0, 1, 2], ids=["auto", "valu", "mfma"])
-@pytest.mark.parametrize("bits,G,mode", [(4, 32, CHAN), (2, 64, CHAN), (8, 32, NONE), (4, 32, CROSS)])
+@pytest.mark.parametrize("bits,G,mode", [(4, 32, CHAN), (2, 64, CHAN), (8, 32, NONE), (4, 32, CROSS), (4, 128, CHAN),
+                                          (2, 128, NONE)])
 def test_requests_join_step_and_leave(kv, oracle, path, bits, G, mode):
     """Four slots: prompts of different lengths enter one by one (one slot stays empty at first),
     everybody decodes for a while through the one-call step, one request leaves and a new one
