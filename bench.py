@@ -173,6 +173,8 @@ def main():
 
     split_ms = np.array([[evs[s][l][0].elapsed_time(evs[s][l][1]) for l in range(L)] for s in range(K)])
     per_bits = {}
+    # the counter runs were made on the matrix-core kernels of the default format
+    traffic_known = args.path != 1 and args.group == 32 and args.mean_mode == "channel" and not args.paged
     for b_ in sorted(set(bits)):
         idx = [l for l in range(L) if bits[l] == b_]
         ms = float(split_ms[:, idx].mean())
@@ -182,10 +184,10 @@ def main():
                              "p10_ms": round(float(np.percentile(split_ms[:, idx], 10)), 5),
                              "p90_ms": round(float(np.percentile(split_ms[:, idx], 90)), 5), "bytes": int(byts),
                              "GBps": round(byts / ms / 1e6, 1), "frac": round(byts / ms / 1e6 / HBM_PEAK_GBPS, 4),
-                             "traffic": int(byts * TRAFFIC_RATIO[b_]) if b_ in TRAFFIC_RATIO and args.path != 1 else None}
+                             "traffic": int(byts * TRAFFIC_RATIO[b_]) if b_ in TRAFFIC_RATIO and traffic_known else None}
     achieved = float(sum(layer_bytes)) / float(split_ms.mean(axis=0).sum()) / 1e6
     traffic = None
-    if args.path != 1 and all(b_ in TRAFFIC_RATIO for b_ in bits):
+    if traffic_known and all(b_ in TRAFFIC_RATIO for b_ in bits):
         traffic = int(sum(layer_bytes[l] * TRAFFIC_RATIO[bits[l]] for l in range(L)) / L)
 
     # ---- what a plain streaming read of the same size reaches on this machine (context for `frac`):
