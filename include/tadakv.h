@@ -279,8 +279,8 @@ kv_status kv_decode_bytes(const kv_cache *cache, int32_t layer, size_t *bytes);
  * 1 = portable vector-ALU kernels, 2 = matrix-core (MFMA) kernels where supported.
  * The matrix-core kernels serve layers with k_bits == v_bits in {2, 4, 8}, group_tokens ==
  * group_channels in {32, 64, 128} and up to 8 query heads per kv head (with KV_MEAN_CROSS_HEAD:
- * group sizes 32 and 64, at most 64 query heads); with path 2 a decode of any other layer returns
- * KV_E_UNSUPPORTED.  Returns KV_E_BAD_CONFIG for other values.  Affects later calls on this cache only. */
+ * at most 64 query heads); with path 2 a decode of any other layer returns KV_E_UNSUPPORTED.  The
+ * vector-ALU kernels serve every format except KV_MEAN_CROSS_HEAD with group_tokens == 128.  Returns KV_E_BAD_CONFIG for other values.  Affects later calls on this cache only. */
 kv_status kv_set_decode_path(kv_cache *cache, int32_t path);
 
 /* Force the number of sequence splits of later decode calls on this cache (clamped to the number

@@ -256,7 +256,6 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
 {
     static_assert(!(XH && MEAN), "cross-head layers store no per-record mean");
     constexpr bool H2 = GS == 128;         // a block is worked on as two halves
-    static_assert(!(H2 && XH), "the dense mean kernels take blocks of at most 64 tokens");
     constexpr int G = H2 ? 64 : GS;        // tokens per block as the arithmetic sees it
     constexpr int HB = GS / G;             // such blocks per block of the cache
     typedef RecLayout<B, G, GC, MEAN> RL;  // the staged image
@@ -954,23 +953,7 @@ template <int B, int G, int GC, class F> void pick_mean_heads(const DecodeArgs &
     if (a.geom.table) pick_mean_heads_pg<B, G, GC, true>(a, f);
     else pick_mean_heads_pg<B, G, GC, false>(a, f);
 }
-// blocks of 128 tokens: no instance for the mean over the heads
-template <int B, bool PG, class F> void pick_heads_128_pg(const DecodeArgs &a, F &f)
-{
-    const bool mean = a.geom.mean_mode == 0;
-    if (a.g <= 4) {
-        if (mean) f.template run<B, 128, 128, true, 1, false, PG>(a);
-        else f.template run<B, 128, 128, false, 1, false, PG>(a);
-    } else {
-        if (mean) f.template run<B, 128, 128, true, 2, false, PG>(a);
-        else f.template run<B, 128, 128, false, 2, false, PG>(a);
-    }
-}
-template <int B, class F> void pick_heads_128(const DecodeArgs &a, F &f)
-{
-    if (a.geom.table) pick_heads_128_pg<B, true>(a, f);
-    else pick_heads_128_pg<B, false>(a, f);
-}
+
 template <class F> void pick(const DecodeArgs &a, F &f)
 {
     const int bits = a.geom.k_bits;
@@ -983,9 +966,9 @@ template <class F> void pick(const DecodeArgs &a, F &f)
         else if (bits == 4) pick_mean_heads<4, 64, 64>(a, f);
         else pick_mean_heads<8, 64, 64>(a, f);
     } else {
-        if (bits == 2) pick_heads_128<2>(a, f);
-        else if (bits == 4) pick_heads_128<4>(a, f);
-        else pick_heads_128<8>(a, f);
+        if (bits == 2) pick_mean_heads<2, 128, 128>(a, f);
+        else if (bits == 4) pick_mean_heads<4, 128, 128>(a, f);
+        else pick_mean_heads<8, 128, 128>(a, f);
     }
 }
 
@@ -996,7 +979,7 @@ bool decode_mfma_supported(const DecodeArgs &a)
     const LayerGeom &g = a.geom;
     if (g.k_bits != g.v_bits) return false;
     if (!(g.k_bits == 2 || g.k_bits == 4 || g.k_bits == 8)) return false;
-    if (!((g.G == 32 && g.Gc == 32) || (g.G == 64 && g.Gc == 64) || (g.G == 128 && g.Gc == 128 && g.mean_mode != 1)))
+    if (!((g.G == 32 && g.Gc == 32) || (g.G == 64 && g.Gc == 64) || (g.G == 128 && g.Gc == 128)))
         return false;
     if (a.g > 8) return false;
     if (g.mean_mode == 1 && a.n_q_heads > 64) return false; // the dense mean terms keep all query heads of a sequence in LDS

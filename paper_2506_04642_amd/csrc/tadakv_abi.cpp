@@ -634,8 +634,8 @@ kv_status kv_decode_attn_split(const kv_cache *cache, int32_t layer, const void 
     if (st != KV_OK) return st;
     st = bind_workspace(cache, &a, workspace, workspace_bytes);
     if (st != KV_OK) return st;
-    if (cache->cfg.mean_mode == KV_MEAN_CROSS_HEAD && a.geom.k_bits != 16 && a.geom.G > 64)
-        return KV_E_UNSUPPORTED; // the cross-head mean tiles of a 128-token block do not fit the kernel's LDS
+    if (cache->cfg.mean_mode == KV_MEAN_CROSS_HEAD && a.geom.k_bits != 16 && a.geom.G > 64 && !use_mfma(cache, a))
+        return KV_E_UNSUPPORTED; // the cross-head mean tiles of a 128-token block do not fit the vector-ALU kernel's LDS
     a.q = (const uint16_t *)q;
     a.out = nullptr;
     hipStream_t s = (hipStream_t)stream;
@@ -733,7 +733,7 @@ kv_status kv_append_decode_attn_split(kv_cache *cache, int32_t layer, const void
     st = fill_decode(cache, layer, &a);
     const bool mfma = st == KV_OK && use_mfma(cache, a);
     if (st == KV_OK) st = bind_workspace(cache, &a, workspace, workspace_bytes);
-    if (st == KV_OK && c.mean_mode == KV_MEAN_CROSS_HEAD && a.geom.k_bits != 16 && a.geom.G > 64) st = KV_E_UNSUPPORTED;
+    if (st == KV_OK && c.mean_mode == KV_MEAN_CROSS_HEAD && a.geom.k_bits != 16 && a.geom.G > 64 && !mfma) st = KV_E_UNSUPPORTED;
     if (st == KV_OK && cache->decode_path == 2 && !mfma) st = KV_E_UNSUPPORTED;
     if (st != KV_OK || flush || !mfma) {
         restore();

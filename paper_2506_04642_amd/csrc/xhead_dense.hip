@@ -126,9 +126,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(MT <= 
     const LayerGeom &gm = a.geom;
     const int ns = a.n_splits, Hq = a.n_q_heads;
     const int b = blockIdx.y, rg = blockIdx.x;
-    const int nbc = 64 / gm.G > 0 ? 64 / gm.G : 1;
-    const int chunks_total = (seq_blocks(a, b) + nbc - 1) / nbc;   // of this sequence
-    const int chunks_max = (a.n_blocks + nbc - 1) / nbc;           // of the longest one: fixes the ranges
+    const int chunks_total = (seq_blocks(a, b) * gm.G + 63) / 64;  // 64-token chunks of this sequence
+    const int chunks_max = (a.n_blocks * gm.G + 63) / 64;          // of the longest one: fixes the ranges
     const int cpr = (chunks_max + a.n_xr - 1) / a.n_xr;
     const int c0 = rg * cpr, c1 = c0 + cpr < chunks_total ? c0 + cpr : chunks_total;
     const int T = seq_blocks(a, b) * gm.G;
@@ -156,9 +155,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(MT <= 
         wq[r] = (long long)b * Hq + i;
     }
     // mean tile staging: thread moves the 16-byte pieces tid + 256 k (row = piece / 16) of the
-    // value mean rows of the chunk's tokens; a chunk lies in one or two blocks, whose tiles are
-    // looked up once per chunk (the cross-head decode path serves G = 32 and 64)
-    const int G = gm.G;
+    // value mean rows of the chunk's tokens; a chunk lies in one or two blocks (or is half of one),
+    // whose tiles are looked up once per chunk
+    const int G = gm.G, lgG = 31 - __builtin_clz(G); // G is 32, 64 or 128
     const int thr_off = (tid >> 4) * (kHeadDim * 2) + (tid & 15) * 16;
     uint4 mreg[4];
     float xpv[NR], xmv[NR];
@@ -169,8 +168,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(MT <= 
             xpv[r] = t < T ? a.xp[wq[r] * a.tcap + t] : 0.0f;
             xmv[r] = a.xmc[wq[r] * ncap + c];
         }
-        const int blk0 = c * (64 / G); // c < chunks_total: the chunk's first block exists
-        const unsigned char *tile0 = a.layer + xmean_offset(gm, b, blk0, 1);
+        const int blk0 = (c * 64) >> lgG; // c < chunks_total: the chunk's first block exists
+        const unsigned char *tile0 = a.layer + xmean_offset(gm, b, blk0, 1) + (c * 64 - blk0 * G) * (kHeadDim * 2);
         const unsigned char *tile1 = (G < 64 && (blk0 + 1) * G < T) ? a.layer + xmean_offset(gm, b, blk0 + 1, 1) : tile0;
         // piece tid + 256 k is row (tid >> 4) + 16 k: a wave-uniform base per k plus the thread's own offset
 #pragma unroll

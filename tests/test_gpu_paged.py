@@ -94,13 +94,15 @@ def check_bytes_paged(kv, oracle, gpu, orc, table):
 @pytest.mark.parametrize("path", [0, 1], ids=["auto", "valu"])
 @pytest.mark.parametrize("bits,G,R,mode,g", [(4, 32, 32, CHAN, 4), (2, 64, 64, CHAN, 8), (8, 32, 64, NONE, 2),
                                              (4, 32, 32, CROSS, 4), (2, 64, 64, CROSS, 2), (8, 128, 128, CHAN, 8),
-                                             (2, 128, 128, NONE, 3)])
+                                             (2, 128, 128, NONE, 3), (4, 128, 128, CROSS, 4)])
 def test_paged_prompts_then_decode_steps(kv, oracle, bits, G, R, mode, g, path):
     """Prompts of different lengths enter their slots one by one (slots handed out as needed, in a
     shuffled order, from a pool smaller than batch x capacity), then batch-wide one-call decode steps
     run across block boundaries while new slots are handed out."""
     import torch
 
+    if path == 1 and mode == CROSS and G == 128:
+        pytest.skip("the vector-ALU kernels do not take the mean over the heads with blocks of 128 tokens")
     print("case paged bits=%d G=%d R=%d mode=%d g=%d path=%d" % (bits, G, R, mode, g, path), flush=True)
     B, Hkv = 4, 2
     NB = 12

@@ -42,13 +42,15 @@ def check_attend(gpu, orc, layer, q, dtype):
 
 @pytest.mark.parametrize("path", [0, 1, 2], ids=["auto", "valu", "mfma"])
 @pytest.mark.parametrize("bits,G,mode", [(4, 32, CHAN), (2, 64, CHAN), (8, 32, NONE), (4, 32, CROSS), (4, 128, CHAN),
-                                          (2, 128, NONE)])
+                                          (2, 128, NONE), (8, 128, CROSS)])
 def test_requests_join_step_and_leave(kv, oracle, path, bits, G, mode):
     """Four slots: prompts of different lengths enter one by one (one slot stays empty at first),
     everybody decodes for a while through the one-call step, one request leaves and a new one
     takes its slot, decoding goes on."""
     import torch
 
+    if path == 1 and mode == CROSS and G == 128:
+        pytest.skip("the vector-ALU kernels do not take the mean over the heads with blocks of 128 tokens")
     print("case ragged path=%d bits=%d G=%d mode=%d" % (path, bits, G, mode), flush=True)
     parity_util.DECODE_PATH = path
     try:
