@@ -53,7 +53,7 @@ def test_rope_append_formats(kv, oracle, bits, dtype, pairing):
     check_attention(gpu, orc, 0, synth.make_q(300 + bits, 2, 8, 128, dtype), dtype)
 
 
-@pytest.mark.parametrize("G,Gc,R", [(32, 32, 64), (64, 64, 64), (128, 32, 128), (32, 128, 32)])
+@pytest.mark.parametrize("G,Gc,R", [(32, 32, 64), (64, 64, 64), (128, 32, 128), (32, 128, 32), (128, 128, 128), (128, 128, 256)])
 def test_rope_append_chunkings_and_groups(kv, oracle, G, Gc, R):
     """Single-token appends, uneven chunks and one bulk call store the same bytes; rows that wait
     in the residual buffer are not rotated a second time when their block is compressed."""
@@ -96,6 +96,22 @@ def test_rope_append_blocks_of_64(kv, oracle, bits, mode, pairing):
     rope_append_both(gpu, orc, 0, k, v, BF16, pairing, [17, 50, 0, T - 67], pos0=777)
     check_bytes(gpu, orc, 0)
     check_attention(gpu, orc, 0, synth.make_q(330 + bits, 2, 8, 128, BF16), BF16)
+
+
+@pytest.mark.parametrize("pairing", [HALF, INTER])
+@pytest.mark.parametrize("mode", [CHAN, CROSS])
+@pytest.mark.parametrize("bits", [2, 4, 8])
+def test_rope_append_blocks_of_128(kv, oracle, bits, mode, pairing):
+    """Blocks and value groups of 128 with one width for keys and values (the wave quantiser in
+    four parts): rows that wait in the residual buffer, then whole blocks in one call."""
+    print("case rope_blocks128 bits=%d mode=%d pairing=%d" % (bits, mode, pairing), flush=True)
+    T = 128 * 3 + 45
+    gpu, orc = make_pair(kv, oracle, B=2, Hq=8, Hkv=2, T_max=640, G=128, Gc=128, R=128, dtype=BF16, mode=mode,
+                         k_bits=(bits,))
+    k, v = synth.make_kv(340 + bits, 2, T, 2, 128, BF16)
+    rope_append_both(gpu, orc, 0, k, v, BF16, pairing, [17, 100, 0, 30, T - 147], pos0=555)
+    check_bytes(gpu, orc, 0)
+    check_attention(gpu, orc, 0, synth.make_q(340 + bits, 2, 8, 128, BF16), BF16)
 
 
 def test_rope_append_equals_rotating_first(kv, oracle):
