@@ -33,6 +33,10 @@
  *     (a new request taking over a slot of the batch: Sec. 3.3's buffer and blocks are per sequence),
  *     after which the lengths differ and the decode kernels take each sequence's own counts.
  *     Caches of more than 256 sequences must keep their lengths equal.
+ *   - The calls enqueue kernels only, so they may be recorded into a HIP graph for a fixed cache
+ *     state.  The first use of a kernel variant in a process asks the runtime for its occupancy
+ *     (and, for two quantiser variants, raises its LDS limit): make one ordinary call of each kind
+ *     before recording.
  *   - One cache must be used by one thread at a time.
  *   - head_dim must be 128.
  */
