@@ -233,10 +233,12 @@ if __name__ == "__main__":
     ap.add_argument("--mean-modes", action="store_true",
                     help="print the error table over mean modes and widths instead of searching")
     ap.add_argument("--shared-sigma", type=float, default=2.0, help="component common to all kv heads (--mean-modes)")
+    ap.add_argument("--group", type=int, default=32, choices=[32, 64, 128], help="group size G = Gc (--mean-modes)")
     a = ap.parse_args()
     if a.mean_modes:
-        print(json.dumps({"widths": list(WIDTHS), "mean_modes": mean_mode_table(min(a.layers, 8), seed=a.seed,
-                                                                               shared_sigma=a.shared_sigma)}))
+        print(json.dumps({"widths": list(WIDTHS), "group": a.group,
+                          "mean_modes": mean_mode_table(min(a.layers, 8), seed=a.seed, shared_sigma=a.shared_sigma,
+                                                        group=a.group)}))
         raise SystemExit(0)
     r = search(a.layers, a.budget, seed=a.seed, n_candidates=a.candidates)
     r["errors"] = np.round(r["errors"], 5).tolist()
