@@ -498,10 +498,10 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
 #pragma unroll
             for (int ct = 0; ct < 8; ct++)
                 vmean[bi][ct] = MEAN ? *(const uint16_t *)(sb8 + bi * REC + RL::V_MEAN + (16 * ct + n) * 2) : (uint16_t)0;
-        // every read of the staging buffer has returned: start fetching this wave's next chunk
-        wave_lds_fence();
-        if (ci + NW < n_chunks) issue(ci + NW);
-
+        // The mean's scores of this chunk are taken over, and those of the next chunk requested,
+        // before the next chunk's fetch is issued: loads return in order, and the compiler, which
+        // cannot see the wait above, would otherwise wait for everything outstanding -- the fetch
+        // just issued included -- before it lets the registers of the previous request be reused.
         float xsv[NHG][4];
         long long xbase[NHG]; // this lane's first token of the chunk in xs / xp
         if (XH) {
@@ -513,6 +513,9 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
             }
             if (ci + NW < n_chunks) load_xs(ci + NW);
         }
+        // every read of the staging buffer has returned: start fetching this wave's next chunk
+        wave_lds_fence();
+        if (ci + NW < n_chunks) issue(ci + NW);
 
         // ---- key side, one block at a time (the operand scratch holds one block's operands):
         // q*scale as limbs -> LDS, zero/mean term, then the block's matrix products -> scores
