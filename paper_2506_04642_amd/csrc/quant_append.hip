@@ -130,13 +130,15 @@ __device__ __forceinline__ void group_meta(float mn, float mx, int qmax, uint16_
 __device__ __forceinline__ uint32_t quant_code(float dev, float s, float rs, float z, float qmaxf)
 {
     // A constant group has s == 0 and is given rs == 0: then dev == z, every term below is zero
-    // and the code is 0 without a special case.  The clamp never binds (0 <= dev - z and
-    // (dev - z)/s < qmax + 1/2 by construction of z and s); it is kept as one median instruction.
+    // and the code is 0 without a special case.  0 <= u < qmax + 1/2 by construction of z and s
+    // (z <= dev; scale rounded up), so the clamp never binds.  Rounding to the nearest integer,
+    // ties to even, is the addition of 2^23 (the sum's unit in the last place is 1); the integer is
+    // then the sum's significand field, of which the code's bits are kept.
     const float xv = dev - z;
     const float q = xv * rs;
     const float e = __builtin_fmaf(-q, s, xv);
     const float u = __builtin_fmaf(e, rs, q);
-    return (uint32_t)__builtin_amdgcn_fmed3f(rintf(u), 0.0f, qmaxf);
+    return __float_as_uint(u + 0x1p23f) & (uint32_t)qmaxf;
 }
 
 // Row of 128 16-bit elements that holds token `ci` of the concatenation
