@@ -562,6 +562,33 @@ __device__ __forceinline__ void rope_in_lanes(float (&x)[8][8], const AppendArgs
     }
 }
 
+// The eight 16-byte pieces a lane loaded (eight 16-bit values each), widened to binary32; the
+// branch on the input type is taken once for all 64 values instead of as a select per value.
+__device__ __forceinline__ void widen_pieces(const uint4 (&pre)[8], int dtype, float (&x)[8][8])
+{
+    if (dtype == 1) {
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            const uint32_t wv[4] = {pre[j].x, pre[j].y, pre[j].z, pre[j].w};
+#pragma unroll
+            for (int k = 0; k < 4; k++) {
+                x[j][2 * k] = __uint_as_float(wv[k] << 16);
+                x[j][2 * k + 1] = __uint_as_float(wv[k] & 0xFFFF0000u);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            const uint32_t wv[4] = {pre[j].x, pre[j].y, pre[j].z, pre[j].w};
+#pragma unroll
+            for (int k = 0; k < 4; k++) {
+                x[j][2 * k] = f16_val((uint16_t)(wv[k] & 0xFFFFu));
+                x[j][2 * k + 1] = f16_val((uint16_t)(wv[k] >> 16));
+            }
+        }
+    }
+}
+
 // Codes and packed words of 32 key tokens held as deviations x[token j][channel e] (lane = (tg, c8)),
 // given the per-channel metadata; `half` is the 32-token half of the block (0 for blocks of 32).
 // A key word runs along channels.
@@ -756,15 +783,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ?
         for (int j = 0; j < 8; j++) pre[j] = *(const uint4 *)(src_row(a, which, b, h, fb * G + 8 * tg + j) + c8 * 8);
 
         float x[8][8]; // [token j][channel e]
-#pragma unroll
-        for (int j = 0; j < 8; j++) {
-            const uint32_t wv[4] = {pre[j].x, pre[j].y, pre[j].z, pre[j].w};
-#pragma unroll
-            for (int k = 0; k < 4; k++) {
-                x[j][2 * k] = widen16((uint16_t)(wv[k] & 0xFFFFu), gm.dtype);
-                x[j][2 * k + 1] = widen16((uint16_t)(wv[k] >> 16), gm.dtype);
-            }
-        }
+        widen_pieces(pre, gm.dtype, x);
 
         if (ROPE && which == 0) {
             const int tn0 = fb * G + 8 * tg - a.r_old; // index of this lane's first token in the call's input
@@ -1042,15 +1061,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ?
             uint4 pre[8];
 #pragma unroll
             for (int j = 0; j < 8; j++) pre[j] = *(const uint4 *)(src_row(a, which, b, h, fb * G + 32 * half + 8 * tg + j) + c8 * 8);
-#pragma unroll
-            for (int j = 0; j < 8; j++) {
-                const uint32_t wv[4] = {pre[j].x, pre[j].y, pre[j].z, pre[j].w};
-#pragma unroll
-                for (int k = 0; k < 4; k++) {
-                    x[j][2 * k] = widen16((uint16_t)(wv[k] & 0xFFFFu), gm.dtype);
-                    x[j][2 * k + 1] = widen16((uint16_t)(wv[k] >> 16), gm.dtype);
-                }
-            }
+            widen_pieces(pre, gm.dtype, x);
             if (ROPE && which == 0) {
                 // both passes turn the rows the same way, so they see the same values
                 const int tn0 = fb * G + 32 * half + 8 * tg - a.r_old; // this lane's first token in the call's input
