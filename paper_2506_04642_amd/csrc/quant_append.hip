@@ -562,6 +562,15 @@ __device__ __forceinline__ void rope_in_lanes(float (&x)[8][8], const AppendArgs
     }
 }
 
+// Minimum / maximum as the bare instructions.  fminf / fmaxf make the compiler put a quieting
+// instruction in front of every operand it cannot prove to be free of signalling NaNs (every value
+// that came through a lane exchange, for one), which doubled the cost of the extrema below; the
+// instructions themselves return the other operand when one is a NaN, like fminf / fmaxf.
+__device__ __forceinline__ float vmin(float a, float b) { float r; asm("v_min_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b)); return r; }
+__device__ __forceinline__ float vmax(float a, float b) { float r; asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b)); return r; }
+__device__ __forceinline__ float vmin3(float a, float b, float c) { float r; asm("v_min3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c)); return r; }
+__device__ __forceinline__ float vmax3(float a, float b, float c) { float r; asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c)); return r; }
+
 // The eight 16-byte pieces a lane loaded (eight 16-bit values each), widened to binary32; the
 // branch on the input type is taken once for all 64 values instead of as a select per value.
 __device__ __forceinline__ void widen_pieces(const uint4 (&pre)[8], int dtype, float (&x)[8][8])
@@ -643,24 +652,20 @@ __device__ __forceinline__ void emit_value_half(const float (&x)[8][8], int half
     float mn[8], mx[8];
 #pragma unroll
     for (int j = 0; j < 8; j++) {
-        float lo = x[j][0], hi = x[j][0];
-#pragma unroll
-        for (int e = 1; e < 8; e++) {
-            lo = fminf(lo, x[j][e]);
-            hi = fmaxf(hi, x[j][e]);
-        }
+        float lo = vmin(vmin3(x[j][0], x[j][1], x[j][2]), vmin3(x[j][3], x[j][4], vmin3(x[j][5], x[j][6], x[j][7])));
+        float hi = vmax(vmax3(x[j][0], x[j][1], x[j][2]), vmax3(x[j][3], x[j][4], vmax3(x[j][5], x[j][6], x[j][7])));
         // lanes 4 and 8 apart in the row of 16 (rotations: the coset is covered either way)
-        lo = fminf(lo, dpp_f<0x124>(lo));
-        hi = fmaxf(hi, dpp_f<0x124>(hi));
-        lo = fminf(lo, dpp_f<0x128>(lo));
-        hi = fmaxf(hi, dpp_f<0x128>(hi));
+        lo = vmin(lo, dpp_f<0x124>(lo));
+        hi = vmax(hi, dpp_f<0x124>(hi));
+        lo = vmin(lo, dpp_f<0x128>(lo));
+        hi = vmax(hi, dpp_f<0x128>(hi));
         if (GC >= 64) {
-            lo = fminf(lo, from_lane_f(lo, lane ^ 16));
-            hi = fmaxf(hi, from_lane_f(hi, lane ^ 16));
+            lo = vmin(lo, from_lane_f(lo, lane ^ 16));
+            hi = vmax(hi, from_lane_f(hi, lane ^ 16));
         }
         if (GC >= 128) {
-            lo = fminf(lo, from_lane_f(lo, lane ^ 32));
-            hi = fmaxf(hi, from_lane_f(hi, lane ^ 32));
+            lo = vmin(lo, from_lane_f(lo, lane ^ 32));
+            hi = vmax(hi, from_lane_f(hi, lane ^ 32));
         }
         mn[j] = lo;
         mx[j] = hi;
@@ -857,16 +862,12 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ?
             float mn[8], mx[8];
 #pragma unroll
             for (int e = 0; e < 8; e++) {
-                float lo = x[0][e], hi = x[0][e];
-#pragma unroll
-                for (int j = 1; j < 8; j++) {
-                    lo = fminf(lo, x[j][e]);
-                    hi = fmaxf(hi, x[j][e]);
-                }
-                lo = fminf(lo, dpp_f<0xB1>(lo));
-                hi = fmaxf(hi, dpp_f<0xB1>(hi));
-                mn[e] = fminf(lo, dpp_f<0x4E>(lo));
-                mx[e] = fmaxf(hi, dpp_f<0x4E>(hi));
+                float lo = vmin(vmin3(x[0][e], x[1][e], x[2][e]), vmin3(x[3][e], x[4][e], vmin3(x[5][e], x[6][e], x[7][e])));
+                float hi = vmax(vmax3(x[0][e], x[1][e], x[2][e]), vmax3(x[3][e], x[4][e], vmax3(x[5][e], x[6][e], x[7][e])));
+                lo = vmin(lo, dpp_f<0xB1>(lo));
+                hi = vmax(hi, dpp_f<0xB1>(hi));
+                mn[e] = vmin(lo, dpp_f<0x4E>(lo));
+                mx[e] = vmax(hi, dpp_f<0x4E>(hi));
             }
             // quad lane tg works out the metadata of channels 2 tg and 2 tg + 1, then all share
             const MetaOut ma = meta_of(pick4(tg, mn[0], mn[2], mn[4], mn[6]), pick4(tg, mx[0], mx[2], mx[4], mx[6]), qmax);
@@ -932,24 +933,20 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ?
             float mn[8], mx[8];
 #pragma unroll
             for (int j = 0; j < 8; j++) {
-                float lo = x[j][0], hi = x[j][0];
-#pragma unroll
-                for (int e = 1; e < 8; e++) {
-                    lo = fminf(lo, x[j][e]);
-                    hi = fmaxf(hi, x[j][e]);
-                }
+                float lo = vmin(vmin3(x[j][0], x[j][1], x[j][2]), vmin3(x[j][3], x[j][4], vmin3(x[j][5], x[j][6], x[j][7])));
+                float hi = vmax(vmax3(x[j][0], x[j][1], x[j][2]), vmax3(x[j][3], x[j][4], vmax3(x[j][5], x[j][6], x[j][7])));
                 // lanes 4 and 8 apart in the row of 16 (rotations: the coset is covered either way)
-                lo = fminf(lo, dpp_f<0x124>(lo));
-                hi = fmaxf(hi, dpp_f<0x124>(hi));
-                lo = fminf(lo, dpp_f<0x128>(lo));
-                hi = fmaxf(hi, dpp_f<0x128>(hi));
+                lo = vmin(lo, dpp_f<0x124>(lo));
+                hi = vmax(hi, dpp_f<0x124>(hi));
+                lo = vmin(lo, dpp_f<0x128>(lo));
+                hi = vmax(hi, dpp_f<0x128>(hi));
                 if (GC >= 64) {
-                    lo = fminf(lo, from_lane_f(lo, lane ^ 16));
-                    hi = fmaxf(hi, from_lane_f(hi, lane ^ 16));
+                    lo = vmin(lo, from_lane_f(lo, lane ^ 16));
+                    hi = vmax(hi, from_lane_f(hi, lane ^ 16));
                 }
                 if (GC >= 128) {
-                    lo = fminf(lo, from_lane_f(lo, lane ^ 32));
-                    hi = fmaxf(hi, from_lane_f(hi, lane ^ 32));
+                    lo = vmin(lo, from_lane_f(lo, lane ^ 32));
+                    hi = vmax(hi, from_lane_f(hi, lane ^ 32));
                 }
                 mn[j] = lo;
                 mx[j] = hi;
@@ -1116,12 +1113,10 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ?
                 }
                 if (which == 0) {
 #pragma unroll
-                    for (int e = 0; e < 8; e++)
-#pragma unroll
-                        for (int j = 0; j < 8; j++) {
-                            mn[e] = fminf(mn[e], x[j][e]);
-                            mx[e] = fmaxf(mx[e], x[j][e]);
-                        }
+                    for (int e = 0; e < 8; e++) {
+                        mn[e] = vmin3(vmin3(mn[e], x[0][e], x[1][e]), vmin3(x[2][e], x[3][e], x[4][e]), vmin3(x[5][e], x[6][e], x[7][e]));
+                        mx[e] = vmax3(vmax3(mx[e], x[0][e], x[1][e]), vmax3(x[2][e], x[3][e], x[4][e]), vmax3(x[5][e], x[6][e], x[7][e]));
+                    }
                 }
             }
         }
@@ -1146,10 +1141,10 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ?
 #pragma unroll
             for (int e = 0; e < 8; e++) {
                 float lo = mn[e], hi = mx[e];
-                lo = fminf(lo, dpp_f<0xB1>(lo));
-                hi = fmaxf(hi, dpp_f<0xB1>(hi));
-                lo = fminf(lo, dpp_f<0x4E>(lo));
-                hi = fmaxf(hi, dpp_f<0x4E>(hi));
+                lo = vmin(lo, dpp_f<0xB1>(lo));
+                hi = vmax(hi, dpp_f<0xB1>(hi));
+                lo = vmin(lo, dpp_f<0x4E>(lo));
+                hi = vmax(hi, dpp_f<0x4E>(hi));
                 mn[e] = lo - m[e];
                 mx[e] = hi - m[e];
             }
