@@ -784,8 +784,16 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ?
         unsigned char *codes_out = img;
 
         uint4 pre[8];
+        if (fb * G >= a.r_old) {
+            // the whole block comes from the call's input (every block but a call's first): one
+            // address, the lane's other rows a token stride apart
+            const uint16_t *row0 = src_row(a, which, b, h, fb * G + 8 * tg) + c8 * 8;
 #pragma unroll
-        for (int j = 0; j < 8; j++) pre[j] = *(const uint4 *)(src_row(a, which, b, h, fb * G + 8 * tg + j) + c8 * 8);
+            for (int j = 0; j < 8; j++) pre[j] = *(const uint4 *)(row0 + (long long)j * a.stride_t);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; j++) pre[j] = *(const uint4 *)(src_row(a, which, b, h, fb * G + 8 * tg + j) + c8 * 8);
+        }
 
         float x[8][8]; // [token j][channel e]
         widen_pieces(pre, gm.dtype, x);
