@@ -141,6 +141,24 @@ __device__ __forceinline__ uint32_t quant_code(float dev, float s, float rs, flo
     return __float_as_uint(u + 0x1p23f) & (uint32_t)qmaxf;
 }
 
+// The quotient alone (see quant_code), and four of them rounded to the nearest integer (ties to
+// even), clamped to 0 .. 255 and packed as the bytes of a word by the conversion instruction that
+// does all three at once.
+__device__ __forceinline__ float quant_quotient(float dev, float s, float rs, float z)
+{
+    const float xv = dev - z;
+    const float q = xv * rs;
+    const float e = __builtin_fmaf(-q, s, xv);
+    return __builtin_fmaf(e, rs, q);
+}
+__device__ __forceinline__ uint32_t pack4_u8(float u0, float u1, float u2, float u3)
+{
+    uint32_t w = __builtin_amdgcn_cvt_pk_u8_f32(u0, 0, 0);
+    w = __builtin_amdgcn_cvt_pk_u8_f32(u1, 1, w);
+    w = __builtin_amdgcn_cvt_pk_u8_f32(u2, 2, w);
+    return __builtin_amdgcn_cvt_pk_u8_f32(u3, 3, w);
+}
+
 // Row of 128 16-bit elements that holds token `ci` of the concatenation
 // [old residual (r_old tokens) | new tokens] for unit (b, h).
 __device__ __forceinline__ const uint16_t *src_row(const AppendArgs &a, int which, int b, int h, int ci)
@@ -610,20 +628,25 @@ __device__ __forceinline__ void emit_key_words(const float (&x)[8][8], const flo
     const int tt = 2 * half + (tg >> 1), jj = c8 >> 2; // 16-token tile of the block, channel-tile pair
 #pragma unroll
     for (int j = 0; j < 8; j++) {
+        const int n = 8 * (tg & 1) + j;
+        if (BITS == 8) {
+            float uq[8];
+#pragma unroll
+            for (int e = 0; e < 8; e++) uq[e] = quant_quotient(x[j][e], sc[e], rs[e], z[e]);
+            const uint32_t w0 = pack4_u8(uq[0], uq[1], uq[2], uq[3]);
+            const uint32_t w1 = pack4_u8(uq[4], uq[5], uq[6], uq[7]);
+            const int piece = ((tt * 2 + ((c8 >> 1) & 1)) * 4 + jj) * 16 + n;
+            *(uint2 *)(codes_out + (piece * 4 + 2 * (c8 & 1)) * 4) = uint2{w0, w1};
+            continue;
+        }
         uint32_t cd[8];
 #pragma unroll
         for (int e = 0; e < 8; e++) cd[e] = quant_code(x[j][e], sc[e], rs[e], z[e], qmaxf);
-        const int n = 8 * (tg & 1) + j;
         if (BITS == 4) {
             uint32_t w = 0;
 #pragma unroll
             for (int e = 0; e < 8; e++) w |= cd[e] << (8 * (e & 3) + 4 * (e >> 2));
             ((uint32_t *)codes_out)[((tt * 4 + jj) * 16 + n) * 4 + (c8 & 3)] = w;
-        } else if (BITS == 8) {
-            const uint32_t w0 = cd[0] | (cd[1] << 8) | (cd[2] << 16) | (cd[3] << 24);
-            const uint32_t w1 = cd[4] | (cd[5] << 8) | (cd[6] << 16) | (cd[7] << 24);
-            const int piece = ((tt * 2 + ((c8 >> 1) & 1)) * 4 + jj) * 16 + n;
-            *(uint2 *)(codes_out + (piece * 4 + 2 * (c8 & 1)) * 4) = uint2{w0, w1};
         } else {
             // 16 channels per word: this lane's half, shifted into place, joined with the
             // neighbouring channel octet's (lane ^ 4); two token tiles share a piece
@@ -692,21 +715,26 @@ __device__ __forceinline__ void emit_value_half(const float (&x)[8][8], int half
     const int tt = 2 * half + (tg >> 1);
 #pragma unroll
     for (int e = 0; e < 8; e++) {
+        const int n = 8 * (c8 & 1) + e;
+        if (BITS == 8) {
+            float uq[8];
+#pragma unroll
+            for (int j = 0; j < 8; j++) uq[j] = quant_quotient(x[j][e], sc[j], rs[j], z[j]);
+            const uint32_t w0 = pack4_u8(uq[0], uq[1], uq[2], uq[3]);
+            const uint32_t w1 = pack4_u8(uq[4], uq[5], uq[6], uq[7]);
+            const int piece = ((c8 >> 1) * NT + tt) * 16 + n;
+            *(uint2 *)(codes_out + (piece * 4 + 2 * (tg & 1)) * 4) = uint2{w0, w1};
+            continue;
+        }
         uint32_t cd[8];
 #pragma unroll
         for (int j = 0; j < 8; j++) cd[j] = quant_code(x[j][e], sc[j], rs[j], z[j], qmaxf);
-        const int n = 8 * (c8 & 1) + e;
         if (BITS == 4) {
             uint32_t w = 0;
 #pragma unroll
             for (int j = 0; j < 8; j++) w |= cd[j] << (8 * (j & 3) + 4 * (j >> 2));
             const int piece = ((c8 >> 2) * NT + tt) * 16 + n;
             ((uint32_t *)codes_out)[piece * 4 + 2 * ((c8 >> 1) & 1) + (tg & 1)] = w;
-        } else if (BITS == 8) {
-            const uint32_t w0 = cd[0] | (cd[1] << 8) | (cd[2] << 16) | (cd[3] << 24);
-            const uint32_t w1 = cd[4] | (cd[5] << 8) | (cd[6] << 16) | (cd[7] << 24);
-            const int piece = ((c8 >> 1) * NT + tt) * 16 + n;
-            *(uint2 *)(codes_out + (piece * 4 + 2 * (tg & 1)) * 4) = uint2{w0, w1};
         } else {
             uint32_t w = 0;
 #pragma unroll
@@ -910,20 +938,25 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ?
             const int tt = tg >> 1, jj = c8 >> 2;
 #pragma unroll
             for (int j = 0; j < 8; j++) {
+                const int n = 8 * (tg & 1) + j;
+                if (bits == 8) {
+                    float uq[8];
+#pragma unroll
+                    for (int e = 0; e < 8; e++) uq[e] = quant_quotient(x[j][e], sc[e], rs[e], z[e]);
+                    const uint32_t w0 = pack4_u8(uq[0], uq[1], uq[2], uq[3]);
+                    const uint32_t w1 = pack4_u8(uq[4], uq[5], uq[6], uq[7]);
+                    const int piece = ((tt * 2 + ((c8 >> 1) & 1)) * 4 + jj) * 16 + n;
+                    *(uint2 *)(codes_out + (piece * 4 + 2 * (c8 & 1)) * 4) = uint2{w0, w1};
+                    continue;
+                }
                 uint32_t cd[8];
 #pragma unroll
                 for (int e = 0; e < 8; e++) cd[e] = quant_code(x[j][e], sc[e], rs[e], z[e], qmaxf);
-                const int n = 8 * (tg & 1) + j;
                 if (bits == 4) {
                     uint32_t w = 0;
 #pragma unroll
                     for (int e = 0; e < 8; e++) w |= cd[e] << (8 * (e & 3) + 4 * (e >> 2));
                     ((uint32_t *)codes_out)[((tt * 4 + jj) * 16 + n) * 4 + (c8 & 3)] = w;
-                } else if (bits == 8) {
-                    const uint32_t w0 = cd[0] | (cd[1] << 8) | (cd[2] << 16) | (cd[3] << 24);
-                    const uint32_t w1 = cd[4] | (cd[5] << 8) | (cd[6] << 16) | (cd[7] << 24);
-                    const int piece = ((tt * 2 + ((c8 >> 1) & 1)) * 4 + jj) * 16 + n;
-                    *(uint2 *)(codes_out + (piece * 4 + 2 * (c8 & 1)) * 4) = uint2{w0, w1};
                 } else {
                     // 16 channels per word: this lane's half, shifted into place, joined with the
                     // neighbouring channel octet's (lane ^ 4)
@@ -986,21 +1019,26 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ?
             const int tt = tg >> 1;
 #pragma unroll
             for (int e = 0; e < 8; e++) {
+                const int n = 8 * (c8 & 1) + e;
+                if (bits == 8) {
+                    float uq[8];
+#pragma unroll
+                    for (int j = 0; j < 8; j++) uq[j] = quant_quotient(x[j][e], sc[j], rs[j], z[j]);
+                    const uint32_t w0 = pack4_u8(uq[0], uq[1], uq[2], uq[3]);
+                    const uint32_t w1 = pack4_u8(uq[4], uq[5], uq[6], uq[7]);
+                    const int piece = ((c8 >> 1) * 2 + tt) * 16 + n;
+                    *(uint2 *)(codes_out + (piece * 4 + 2 * (tg & 1)) * 4) = uint2{w0, w1};
+                    continue;
+                }
                 uint32_t cd[8];
 #pragma unroll
                 for (int j = 0; j < 8; j++) cd[j] = quant_code(x[j][e], sc[j], rs[j], z[j], qmaxf);
-                const int n = 8 * (c8 & 1) + e;
                 if (bits == 4) {
                     uint32_t w = 0;
 #pragma unroll
                     for (int j = 0; j < 8; j++) w |= cd[j] << (8 * (j & 3) + 4 * (j >> 2));
                     const int piece = ((c8 >> 2) * 2 + tt) * 16 + n;
                     ((uint32_t *)codes_out)[piece * 4 + 2 * ((c8 >> 1) & 1) + (tg & 1)] = w;
-                } else if (bits == 8) {
-                    const uint32_t w0 = cd[0] | (cd[1] << 8) | (cd[2] << 16) | (cd[3] << 24);
-                    const uint32_t w1 = cd[4] | (cd[5] << 8) | (cd[6] << 16) | (cd[7] << 24);
-                    const int piece = ((c8 >> 1) * 2 + tt) * 16 + n;
-                    *(uint2 *)(codes_out + (piece * 4 + 2 * (tg & 1)) * 4) = uint2{w0, w1};
                 } else {
                     uint32_t w = 0;
 #pragma unroll

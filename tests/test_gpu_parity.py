@@ -75,6 +75,38 @@ def test_bit_widths_and_groups(kv, oracle, bits, dtype, G, Gc):
     check_attention(gpu, orc, 0, synth.make_q(bits + G, 2, 8, 128, dtype), dtype)
 
 
+@pytest.mark.parametrize("G", [32, 64, 128])
+@pytest.mark.parametrize("bits", [2, 4, 8])
+def test_exact_ties_round_to_the_even_code(kv, oracle, bits, G):
+    """Groups built so that zero = 0 and scale = 1 exactly (minimum 0, maximum 2^bits - 1) and the
+    other members sit at k + 1/2: every one of them is a tie, which must go to the even code
+    (binary16 inputs, no centring, so that nothing else rounds on the way)."""
+    print("case ties bits=%d G=%d" % (bits, G), flush=True)
+    qmax = (1 << bits) - 1
+    B, H, T = 2, 2, 2 * G
+    halves = np.array([(k % qmax) + 0.5 for k in range(128)], dtype=np.float32)
+    k = np.zeros((B, T, H, 128), dtype=np.float32)
+    v = np.zeros((B, T, H, 128), dtype=np.float32)
+    # keys: a group is one channel over the G tokens of a block
+    for t in range(T):
+        tin = t % G
+        k[:, t] = 0.0 if tin == 0 else (qmax if tin == 1 else halves[(tin + np.arange(128)) % 128])
+    # values: a group is G (= Gc) channels of one token
+    for c in range(128):
+        cin = c % G
+        v[:, :, :, c] = 0.0 if cin == 0 else (qmax if cin == 1 else halves[(cin + np.arange(T)) % 128][None, :, None])
+    kb = k.astype(np.float16).view(np.uint16)
+    vb = v.astype(np.float16).view(np.uint16)
+    assert np.array_equal(kb.view(np.float16).astype(np.float32), k)  # all values are exact in binary16
+    gpu, orc = make_pair(kv, oracle, B=B, Hq=H, Hkv=H, T_max=T, G=G, Gc=G, dtype=F16, mode=NONE, k_bits=(bits,))
+    append_both(gpu, orc, 0, kb, vb, F16)
+    check_bytes(gpu, orc, 0)
+    # the oracle's own codes: ties went to even (pins the expectation, not only the agreement)
+    kr = orc.reconstruct(0, 0, 0)  # keys of sequence 0, [H, T, d]; zero = 0 and scale = 1: the codes themselves
+    for blk in range(T // G):
+        assert np.all(kr[:, blk * G + 2:(blk + 1) * G] % 2 == 0)
+
+
 @pytest.mark.parametrize("kb,vb", [(2, 4), (4, 2), (8, 2), (4, 8)])
 def test_different_widths_for_keys_and_values(kv, oracle, kb, vb):
     print("case kv_widths kb=%d vb=%d" % (kb, vb), flush=True)
