@@ -629,30 +629,20 @@ __device__ __forceinline__ void emit_key_words(const float (&x)[8][8], const flo
 #pragma unroll
     for (int j = 0; j < 8; j++) {
         const int n = 8 * (tg & 1) + j;
+        float uq[8];
+#pragma unroll
+        for (int e = 0; e < 8; e++) uq[e] = quant_quotient(x[j][e], sc[e], rs[e], z[e]);
+        const uint32_t clo = pack4_u8(uq[0], uq[1], uq[2], uq[3]), chi = pack4_u8(uq[4], uq[5], uq[6], uq[7]);
         if (BITS == 8) {
-            float uq[8];
-#pragma unroll
-            for (int e = 0; e < 8; e++) uq[e] = quant_quotient(x[j][e], sc[e], rs[e], z[e]);
-            const uint32_t w0 = pack4_u8(uq[0], uq[1], uq[2], uq[3]);
-            const uint32_t w1 = pack4_u8(uq[4], uq[5], uq[6], uq[7]);
             const int piece = ((tt * 2 + ((c8 >> 1) & 1)) * 4 + jj) * 16 + n;
-            *(uint2 *)(codes_out + (piece * 4 + 2 * (c8 & 1)) * 4) = uint2{w0, w1};
-            continue;
-        }
-        uint32_t cd[8];
-#pragma unroll
-        for (int e = 0; e < 8; e++) cd[e] = quant_code(x[j][e], sc[e], rs[e], z[e], qmaxf);
-        if (BITS == 4) {
-            uint32_t w = 0;
-#pragma unroll
-            for (int e = 0; e < 8; e++) w |= cd[e] << (8 * (e & 3) + 4 * (e >> 2));
+            *(uint2 *)(codes_out + (piece * 4 + 2 * (c8 & 1)) * 4) = uint2{clo, chi};
+        } else if (BITS == 4) {
+            const uint32_t w = clo | (chi << 4); // byte y: codes y and y + 4
             ((uint32_t *)codes_out)[((tt * 4 + jj) * 16 + n) * 4 + (c8 & 3)] = w;
         } else {
             // 16 channels per word: this lane's half, shifted into place, joined with the
             // neighbouring channel octet's (lane ^ 4); two token tiles share a piece
-            uint32_t w = 0;
-#pragma unroll
-            for (int e = 0; e < 8; e++) w |= cd[e] << (8 * (e & 3) + 2 * (e >> 2));
+            uint32_t w = clo | (chi << 2); // byte y: codes y and y + 4 in its low four bits
             w <<= 4 * (c8 & 1);
             w |= from_lane_u(w, lane ^ 4);
             if ((j >> 2) == (c8 & 1))
@@ -716,29 +706,19 @@ __device__ __forceinline__ void emit_value_half(const float (&x)[8][8], int half
 #pragma unroll
     for (int e = 0; e < 8; e++) {
         const int n = 8 * (c8 & 1) + e;
+        float uq[8];
+#pragma unroll
+        for (int j = 0; j < 8; j++) uq[j] = quant_quotient(x[j][e], sc[j], rs[j], z[j]);
+        const uint32_t clo = pack4_u8(uq[0], uq[1], uq[2], uq[3]), chi = pack4_u8(uq[4], uq[5], uq[6], uq[7]);
         if (BITS == 8) {
-            float uq[8];
-#pragma unroll
-            for (int j = 0; j < 8; j++) uq[j] = quant_quotient(x[j][e], sc[j], rs[j], z[j]);
-            const uint32_t w0 = pack4_u8(uq[0], uq[1], uq[2], uq[3]);
-            const uint32_t w1 = pack4_u8(uq[4], uq[5], uq[6], uq[7]);
             const int piece = ((c8 >> 1) * NT + tt) * 16 + n;
-            *(uint2 *)(codes_out + (piece * 4 + 2 * (tg & 1)) * 4) = uint2{w0, w1};
-            continue;
-        }
-        uint32_t cd[8];
-#pragma unroll
-        for (int j = 0; j < 8; j++) cd[j] = quant_code(x[j][e], sc[j], rs[j], z[j], qmaxf);
-        if (BITS == 4) {
-            uint32_t w = 0;
-#pragma unroll
-            for (int j = 0; j < 8; j++) w |= cd[j] << (8 * (j & 3) + 4 * (j >> 2));
+            *(uint2 *)(codes_out + (piece * 4 + 2 * (tg & 1)) * 4) = uint2{clo, chi};
+        } else if (BITS == 4) {
+            const uint32_t w = clo | (chi << 4); // byte y: codes y and y + 4
             const int piece = ((c8 >> 2) * NT + tt) * 16 + n;
             ((uint32_t *)codes_out)[piece * 4 + 2 * ((c8 >> 1) & 1) + (tg & 1)] = w;
         } else {
-            uint32_t w = 0;
-#pragma unroll
-            for (int j = 0; j < 8; j++) w |= cd[j] << (8 * (j & 3) + 2 * (j >> 2));
+            uint32_t w = clo | (chi << 2); // byte y: codes y and y + 4 in its low four bits
             w <<= 4 * (tg & 1);
             w |= dpp_u<0xB1>(w);
             const int piece = ((c8 >> 3) * NT + tt) * 16 + n;
@@ -939,30 +919,20 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ?
 #pragma unroll
             for (int j = 0; j < 8; j++) {
                 const int n = 8 * (tg & 1) + j;
+                float uq[8];
+#pragma unroll
+                for (int e = 0; e < 8; e++) uq[e] = quant_quotient(x[j][e], sc[e], rs[e], z[e]);
+                const uint32_t clo = pack4_u8(uq[0], uq[1], uq[2], uq[3]), chi = pack4_u8(uq[4], uq[5], uq[6], uq[7]);
                 if (bits == 8) {
-                    float uq[8];
-#pragma unroll
-                    for (int e = 0; e < 8; e++) uq[e] = quant_quotient(x[j][e], sc[e], rs[e], z[e]);
-                    const uint32_t w0 = pack4_u8(uq[0], uq[1], uq[2], uq[3]);
-                    const uint32_t w1 = pack4_u8(uq[4], uq[5], uq[6], uq[7]);
                     const int piece = ((tt * 2 + ((c8 >> 1) & 1)) * 4 + jj) * 16 + n;
-                    *(uint2 *)(codes_out + (piece * 4 + 2 * (c8 & 1)) * 4) = uint2{w0, w1};
-                    continue;
-                }
-                uint32_t cd[8];
-#pragma unroll
-                for (int e = 0; e < 8; e++) cd[e] = quant_code(x[j][e], sc[e], rs[e], z[e], qmaxf);
-                if (bits == 4) {
-                    uint32_t w = 0;
-#pragma unroll
-                    for (int e = 0; e < 8; e++) w |= cd[e] << (8 * (e & 3) + 4 * (e >> 2));
+                    *(uint2 *)(codes_out + (piece * 4 + 2 * (c8 & 1)) * 4) = uint2{clo, chi};
+                } else if (bits == 4) {
+                    const uint32_t w = clo | (chi << 4); // byte y: codes y and y + 4
                     ((uint32_t *)codes_out)[((tt * 4 + jj) * 16 + n) * 4 + (c8 & 3)] = w;
                 } else {
                     // 16 channels per word: this lane's half, shifted into place, joined with the
                     // neighbouring channel octet's (lane ^ 4)
-                    uint32_t w = 0;
-#pragma unroll
-                    for (int e = 0; e < 8; e++) w |= cd[e] << (8 * (e & 3) + 2 * (e >> 2));
+                    uint32_t w = clo | (chi << 2); // byte y: codes y and y + 4 in its low four bits
                     w <<= 4 * (c8 & 1);
                     w |= from_lane_u(w, lane ^ 4);
                     if ((j >> 2) == (c8 & 1))
@@ -1020,29 +990,19 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ?
 #pragma unroll
             for (int e = 0; e < 8; e++) {
                 const int n = 8 * (c8 & 1) + e;
+                float uq[8];
+#pragma unroll
+                for (int j = 0; j < 8; j++) uq[j] = quant_quotient(x[j][e], sc[j], rs[j], z[j]);
+                const uint32_t clo = pack4_u8(uq[0], uq[1], uq[2], uq[3]), chi = pack4_u8(uq[4], uq[5], uq[6], uq[7]);
                 if (bits == 8) {
-                    float uq[8];
-#pragma unroll
-                    for (int j = 0; j < 8; j++) uq[j] = quant_quotient(x[j][e], sc[j], rs[j], z[j]);
-                    const uint32_t w0 = pack4_u8(uq[0], uq[1], uq[2], uq[3]);
-                    const uint32_t w1 = pack4_u8(uq[4], uq[5], uq[6], uq[7]);
                     const int piece = ((c8 >> 1) * 2 + tt) * 16 + n;
-                    *(uint2 *)(codes_out + (piece * 4 + 2 * (tg & 1)) * 4) = uint2{w0, w1};
-                    continue;
-                }
-                uint32_t cd[8];
-#pragma unroll
-                for (int j = 0; j < 8; j++) cd[j] = quant_code(x[j][e], sc[j], rs[j], z[j], qmaxf);
-                if (bits == 4) {
-                    uint32_t w = 0;
-#pragma unroll
-                    for (int j = 0; j < 8; j++) w |= cd[j] << (8 * (j & 3) + 4 * (j >> 2));
+                    *(uint2 *)(codes_out + (piece * 4 + 2 * (tg & 1)) * 4) = uint2{clo, chi};
+                } else if (bits == 4) {
+                    const uint32_t w = clo | (chi << 4); // byte y: codes y and y + 4
                     const int piece = ((c8 >> 2) * 2 + tt) * 16 + n;
                     ((uint32_t *)codes_out)[piece * 4 + 2 * ((c8 >> 1) & 1) + (tg & 1)] = w;
                 } else {
-                    uint32_t w = 0;
-#pragma unroll
-                    for (int j = 0; j < 8; j++) w |= cd[j] << (8 * (j & 3) + 2 * (j >> 2));
+                    uint32_t w = clo | (chi << 2); // byte y: codes y and y + 4 in its low four bits
                     w <<= 4 * (tg & 1);
                     w |= dpp_u<0xB1>(w);
                     const int piece = ((c8 >> 3) * 2 + tt) * 16 + n;
