@@ -54,12 +54,7 @@ __device__ __forceinline__ uint16_t narrow16(float f, int dtype)
 // f rounded to the 16-bit type (DT: 0 binary16, 1 bfloat16) and widened again, without branches
 template <int DT> __device__ __forceinline__ float round16(float f)
 {
-    if (DT == 1) {
-        const uint32_t u = __float_as_uint(f);
-        const uint32_t r = (u + 0x7FFFu + ((u >> 16) & 1u)) & 0xFFFF0000u;
-        const uint32_t nan = (u | 0x00400000u) & 0xFFFF0000u;
-        return __uint_as_float((u & 0x7FFFFFFFu) > 0x7F800000u ? nan : r);
-    }
+    if (DT == 1) return (float)(__bf16)f; // the conversion instruction of this chip: round to nearest, ties to even
     return __half2float(__float2half_rn(f));
 }
 
@@ -623,7 +618,6 @@ template <int BITS>
 __device__ __forceinline__ void emit_key_words(const float (&x)[8][8], const float (&sc)[8], const float (&rs)[8],
                                                const float (&z)[8], int half, int lane, unsigned char *codes_out)
 {
-    constexpr float qmaxf = (float)((1 << BITS) - 1);
     const int tg = lane & 3, c8 = lane >> 2;
     const int tt = 2 * half + (tg >> 1), jj = c8 >> 2; // 16-token tile of the block, channel-tile pair
 #pragma unroll
@@ -660,7 +654,6 @@ __device__ __forceinline__ void emit_value_half(const float (&x)[8][8], int half
 {
     constexpr int NGV = kHeadDim / GC;
     constexpr int qmax = (1 << BITS) - 1;
-    constexpr float qmaxf = (float)qmax;
     const int tg = lane & 3, c8 = lane >> 2;
     float mn[8], mx[8];
 #pragma unroll
@@ -764,7 +757,7 @@ __device__ __forceinline__ void key_metadata(const float (&mn)[8], const float (
 }
 
 template <int GC, int BITS, bool ROPE>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ? 2 : 3, 8))) void flush_wave_kernel(AppendArgs a, int n_items)
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 8))) void flush_wave_kernel(AppendArgs a, int n_items)
 {
     constexpr int G = 32;
     constexpr int bits = BITS; // keys and values of the layer share the width in this instance
@@ -871,7 +864,6 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ?
         }
 
         constexpr int qmax = (1 << bits) - 1;
-        constexpr float qmaxf = (float)qmax;
 
         if (which == 0) {
             // ---- keys: one group per channel over the 32 tokens (eight in the lane, four lanes)
