@@ -216,6 +216,30 @@ def test_result_does_not_depend_on_the_split_count(kv, oracle):
         assert np.max(np.abs(o - outs[0])) < 1e-5
 
 
+@pytest.mark.parametrize("g", [4, 8])
+def test_split_count_with_blocks_of_128(kv, oracle, g):
+    """Blocks of 128 tokens are dealt to the splits whole (their two halves stay in one wave): any
+    split count, also more splits than blocks and counts that do not divide them, gives the same
+    attention."""
+    import torch
+
+    print("case split_independence_g128 g=%d" % g, flush=True)
+    gpu, orc = make_pair(kv, oracle, B=2, Hq=2 * g, Hkv=2, T_max=24 * 128, G=128, Gc=128, dtype=BF16, k_bits=(4,))
+    k, v = synth.make_kv(35, 2, 21 * 128 + 77, 2, 128, BF16)
+    append_both(gpu, orc, 0, k, v, BF16)
+    q = synth.make_q(35, 2, 2 * g, 128, BF16)
+    gpu.workspace = torch.empty(2 * 2 * g * 64 * 132 * 4 * 2, dtype=torch.uint8, device="cuda:0")
+    gpu.ws_bytes = gpu.workspace.numel()
+    outs = []
+    for ns in (1, 2, 5, 7, 21, 64):
+        kv.kv_set_decode_splits(gpu.handle, ns)
+        assert kv.kv_decode_splits(gpu.handle, 0) <= ns
+        check_attention(gpu, orc, 0, q, BF16)
+        outs.append(gpu.attend(0, to_dev(q, BF16)).cpu().numpy())
+    for o in outs[1:]:
+        assert np.max(np.abs(o - outs[0])) < 1e-5
+
+
 def test_repeat_calls_are_bitwise_reproducible(kv, oracle):
     print("case reproducible", flush=True)
     gpu, orc = make_pair(kv, oracle, B=2, Hq=8, Hkv=2, T_max=1024, dtype=BF16, k_bits=(2,))
