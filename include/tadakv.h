@@ -289,9 +289,15 @@ kv_status kv_set_decode_path(kv_cache *cache, int32_t path);
 
 /* Force the number of sequence splits of later decode calls on this cache (clamped to the number
  * of blocks); 0 restores the automatic choice.  The workspace must then hold
- * batch * n_q_heads * n_splits * 132 floats, which may exceed kv_workspace_bytes.
+ * batch * n_q_heads * n_splits * 132 floats (with KV_MEAN_CROSS_HEAD on the matrix-core kernels: the
+ * dense mean arrays behind them as well), which may exceed kv_workspace_bytes: ask
+ * kv_decode_workspace_need; a decode call with less returns KV_E_WORKSPACE.
  * KV_E_BAD_CONFIG if n_splits < 0 or > 256. */
 kv_status kv_set_decode_splits(kv_cache *cache, int32_t n_splits);
+
+/* Workspace bytes a decode call of `layer` needs in the cache's present state (lengths, kernel
+ * family, forced split count); never more than kv_workspace_bytes unless a split count is forced. */
+kv_status kv_decode_workspace_need(const kv_cache *cache, int32_t layer, size_t *bytes);
 
 const char *kv_strerror(kv_status s);
 

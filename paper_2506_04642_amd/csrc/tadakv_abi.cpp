@@ -32,6 +32,7 @@ struct kv_cache {
     int decode_path = 0;
     int forced_splits = 0;
     size_t xhead_off = 0, xhead_bytes = 0; // cross-head mean: where its arrays start in the workspace, total size
+    size_t xhead_xo_rel = 0;               // start of the value-mean output slots relative to xhead_off
 };
 
 namespace {
@@ -257,21 +258,37 @@ bool use_mfma(const kv_cache *k, const DecodeArgs &a)
     return decode_mfma_supported(a);
 }
 
-// Workspace bytes this launch needs, and the cross-head arrays placed in it.
+// Start of the cross-head arrays in the workspace: behind the partials of the largest automatic
+// split count, or of this launch's own count where a forced count exceeds that.
+size_t xhead_start(const kv_cache *k, const DecodeArgs &a)
+{
+    const size_t own = (size_t)align_up((long long)workspace_need(k->cfg, a.n_splits), 256);
+    return own > k->xhead_off ? own : k->xhead_off;
+}
+
+// Workspace bytes this launch needs (the cross-head arrays included where the launch uses them).
+size_t launch_workspace_need(const kv_cache *k, const DecodeArgs &a)
+{
+    const kv_config &c = k->cfg;
+    const bool xhead = c.mean_mode == KV_MEAN_CROSS_HEAD && a.geom.k_bits != 16 && use_mfma(k, a);
+    return xhead ? xhead_start(k, a) + (k->xhead_bytes - k->xhead_off) : workspace_need(c, a.n_splits);
+}
+
+// Checks the workspace against this launch's need and places the cross-head arrays in it.
 kv_status bind_workspace(const kv_cache *k, DecodeArgs *a, void *workspace, size_t workspace_bytes)
 {
     const kv_config &c = k->cfg;
     const bool xhead = c.mean_mode == KV_MEAN_CROSS_HEAD && a->geom.k_bits != 16 && use_mfma(k, *a);
-    const size_t need = xhead ? k->xhead_bytes : workspace_need(c, a->n_splits);
-    if (!workspace || workspace_bytes < need) return KV_E_WORKSPACE;
+    if (!workspace || workspace_bytes < launch_workspace_need(k, *a)) return KV_E_WORKSPACE;
     if ((uintptr_t)workspace % 256) return KV_E_ALIGN;
     a->ws = (float *)workspace;
     if (xhead) {
         const size_t rows = (size_t)c.batch * c.n_q_heads;
-        a->xs = (float *)((unsigned char *)workspace + k->xhead_off);
+        const size_t start = xhead_start(k, *a);
+        a->xs = (float *)((unsigned char *)workspace + start);
         a->xp = a->xs + rows * c.max_tokens;
         a->xmc = a->xp + rows * c.max_tokens;
-        a->xo = (float *)((unsigned char *)workspace + xhead_xo_offset(c));
+        a->xo = (float *)((unsigned char *)workspace + start + k->xhead_xo_rel);
         a->n_xr = xhead_ranges(c, a->n_blocks);
         // one resident round of workgroups, whatever the compiler made of the kernel's registers
         const int fit = xhead_values_resident(c.n_q_heads) / c.batch;
@@ -358,6 +375,7 @@ kv_status kv_cache_create(const kv_config *cfg, void *const *layer_dev_ptrs, kv_
     if (cfg->mean_mode == KV_MEAN_CROSS_HEAD) {
         k->xhead_off = xhead_offset(k->cfg);
         k->xhead_bytes = xhead_total(k->cfg);
+        k->xhead_xo_rel = xhead_xo_offset(k->cfg) - k->xhead_off;
     }
     *out = k;
     return KV_OK;
@@ -777,6 +795,18 @@ kv_status kv_decode_attn(const kv_cache *cache, int32_t layer, const void *q, fl
     kv_status st = kv_decode_attn_split(cache, layer, q, workspace, workspace_bytes, stream);
     if (st != KV_OK) return st;
     return kv_decode_attn_merge(cache, layer, out, workspace, workspace_bytes, stream);
+}
+
+kv_status kv_decode_workspace_need(const kv_cache *cache, int32_t layer, size_t *bytes)
+{
+    kv_status st = layer_ok(cache, layer);
+    if (st != KV_OK) return st;
+    if (!bytes) return KV_E_NULL;
+    DecodeArgs a{};
+    st = fill_decode(cache, layer, &a);
+    if (st != KV_OK) return st;
+    *bytes = launch_workspace_need(cache, a);
+    return KV_OK;
 }
 
 } // extern "C"

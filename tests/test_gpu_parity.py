@@ -516,6 +516,34 @@ def test_cross_head_mean_on_the_matrix_cores(kv, oracle, decode_path, bits, G, g
     assert torch.equal(a, b)
 
 
+@pytest.mark.parametrize("decode_path", [2], indirect=True, ids=["mfma"])
+def test_cross_head_mean_with_a_forced_split_count(kv, oracle, decode_path):
+    """A forced split count above the automatic one moves the dense mean arrays further back in the
+    workspace: the stock workspace is refused, one of kv_decode_workspace_need's size gives the
+    oracle's attention (the partials of 64 splits would otherwise run into those arrays)."""
+    import torch
+
+    print("case cross_head_forced_splits", flush=True)
+    B, Hkv, g, T = 16, 8, 4, 128 * 32 + 5
+    gpu, orc = make_pair(kv, oracle, B=B, Hq=Hkv * g, Hkv=Hkv, T_max=130 * 32, dtype=BF16, mode=CROSS, k_bits=(4,))
+    k, v = synth.make_kv(611, B, T, Hkv, 128, BF16)
+    append_both(gpu, orc, 0, k, v, BF16)
+    q = synth.make_q(611, B, Hkv * g, 128, BF16)
+    auto = kv.kv_decode_splits(gpu.handle, 0)
+    stock = gpu.ws_bytes
+    assert kv.kv_decode_workspace_need(gpu.handle, 0) <= stock
+    kv.kv_set_decode_splits(gpu.handle, 64)
+    assert auto < kv.kv_decode_splits(gpu.handle, 0) <= 64
+    need = kv.kv_decode_workspace_need(gpu.handle, 0)
+    assert need > stock
+    with pytest.raises(kv.KVError) as e:
+        gpu.attend(0, to_dev(q, BF16))
+    assert e.value.status == kv.KV_E_WORKSPACE
+    gpu.workspace = torch.empty(need, dtype=torch.uint8, device="cuda:0")
+    gpu.ws_bytes = need
+    check_attention(gpu, orc, 0, q, BF16, units=[(0, 0), (7, 3), (15, 7)])
+
+
 # ------------------------------------------------------------------ matrix-core kernels, forced
 
 
