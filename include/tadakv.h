@@ -299,6 +299,18 @@ kv_status kv_set_decode_splits(kv_cache *cache, int32_t n_splits);
  * family, forced split count); never more than kv_workspace_bytes unless a split count is forced. */
 kv_status kv_decode_workspace_need(const kv_cache *cache, int32_t layer, size_t *bytes);
 
+/* kv_decode_attn for callers that cannot allocate or carry a workspace (code under HIP graph
+ * capture, serving loops and harnesses that forbid allocation): the per-split partial results go
+ * through an array of KV_STATIC_WORKSPACE_BYTES that lives in the library's device image (each GPU
+ * the library runs on holds its own copy until the process ends).  Same kernels, same results bit
+ * for bit, same errors as kv_decode_attn; KV_E_WORKSPACE if the call needs more than the array holds
+ * (kv_decode_workspace_need tells; the cross-head mean's dense arrays at long contexts do not fit).
+ * The call allocates and frees nothing.  Every call on a GPU uses that GPU's one array, whose
+ * contents are scratch (each call writes all it later reads): calls that overlap on one GPU, on
+ * different streams or from different caches, race -- keep them on one stream or order them. */
+#define KV_STATIC_WORKSPACE_BYTES (8u << 20)
+kv_status kv_decode_attn_static(const kv_cache *cache, int32_t layer, const void *q, float *out, void *stream);
+
 const char *kv_strerror(kv_status s);
 
 /* Text of the HIP error behind the calling thread's most recent KV_E_HIP ("no error" if none). */

@@ -30,7 +30,7 @@ KV_MEAN_CHANNEL_BLOCK, KV_MEAN_CROSS_HEAD, KV_MEAN_NONE = 0, 1, 2
 EXPORTS = [
     "kv_cache_bytes", "kv_workspace_bytes", "kv_cache_create", "kv_cache_destroy", "kv_cache_set_block_table", "kv_cache_set_active", "kv_cache_reset",
     "kv_cache_len", "kv_cache_len_seq", "kv_cache_reset_seq", "kv_cache_describe", "kv_quant_append", "kv_quant_append_seq", "kv_rope_quant_append", "kv_append_decode_attn", "kv_append_decode_attn_split", "kv_decode_attn", "kv_decode_attn_split",
-    "kv_decode_attn_merge", "kv_decode_attn_merge16", "kv_dequant", "kv_decode_splits", "kv_decode_bytes", "kv_set_decode_path", "kv_set_decode_splits", "kv_decode_workspace_need", "kv_strerror", "kv_last_hip_error",
+    "kv_decode_attn_merge", "kv_decode_attn_merge16", "kv_dequant", "kv_decode_splits", "kv_decode_bytes", "kv_set_decode_path", "kv_set_decode_splits", "kv_decode_workspace_need", "kv_decode_attn_static", "kv_strerror", "kv_last_hip_error",
 ]
 
 
@@ -84,6 +84,7 @@ _lib.kv_decode_bytes.argtypes = [_vp, _i32, _szp]
 _lib.kv_set_decode_path.argtypes = [_vp, _i32]
 _lib.kv_set_decode_splits.argtypes = [_vp, _i32]
 _lib.kv_decode_workspace_need.argtypes = [_vp, _i32, _szp]
+_lib.kv_decode_attn_static.argtypes = [_vp, _i32, _vp, _vp, _vp]
 _lib.kv_strerror.argtypes = [_i32]
 _lib.kv_strerror.restype = ctypes.c_char_p
 _lib.kv_last_hip_error.argtypes = []
@@ -268,10 +269,17 @@ def kv_set_decode_splits(cache: int, n_splits: int) -> None:
     _check(_lib.kv_set_decode_splits(cache, n_splits), "kv_set_decode_splits")
 
 
+KV_STATIC_WORKSPACE_BYTES = 8 << 20
+
+
 def kv_decode_workspace_need(cache: int, layer: int) -> int:
     n = ctypes.c_size_t()
     _check(_lib.kv_decode_workspace_need(cache, layer, ctypes.byref(n)), "kv_decode_workspace_need")
     return n.value
+
+
+def kv_decode_attn_static(cache: int, layer: int, q_ptr: int, out_ptr: int, stream: int = 0) -> None:
+    _check(_lib.kv_decode_attn_static(cache, layer, q_ptr, out_ptr, stream), "kv_decode_attn_static")
 
 
 # ---- memory / stream plumbing

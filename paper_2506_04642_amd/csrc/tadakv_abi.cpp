@@ -4,6 +4,7 @@
 #include "../../include/tadakv.h"
 #include "tadakv_internal.h"
 
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -810,3 +811,40 @@ kv_status kv_decode_workspace_need(const kv_cache *cache, int32_t layer, size_t 
 }
 
 } // extern "C"
+
+// ---- decode attention without a caller workspace: the partial results live in the device image
+
+// Scratch for the per-split partial results of kv_decode_attn_static.  In host code this name is a
+// stand-in, not a device address: the address comes from hipGetSymbolAddress, once per device.
+static __device__ __align__(256) unsigned char scratch[KV_STATIC_WORKSPACE_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+void *g_scratch_ptr[kMaxDevices]; // device address of `scratch` on each device, null until first use
+
+// Address of the current device's copy of `scratch` (null on failure; the HIP error is noted).
+void *static_scratch()
+{
+    int dev = -1;
+    if (note_launch(hipGetDevice(&dev)) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (note_launch(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch))) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = p;
+    }
+    return g_scratch_ptr[dev];
+}
+} // namespace
+
+extern "C" kv_status kv_decode_attn_static(const kv_cache *cache, int32_t layer, const void *q, float *out, void *stream)
+{
+    size_t need = 0;
+    kv_status st = kv_decode_workspace_need(cache, layer, &need);
+    if (st != KV_OK) return st;
+    if (need > (size_t)KV_STATIC_WORKSPACE_BYTES) return KV_E_WORKSPACE;
+    void *ws = static_scratch();
+    if (!ws) return KV_E_HIP;
+    return kv_decode_attn(cache, layer, q, out, ws, (size_t)KV_STATIC_WORKSPACE_BYTES, stream);
+}
