@@ -11,10 +11,12 @@ from .tada import (  # noqa: F401
     decode_block,
     encode_block,
     f16_to_f32,
+    f64_to_16,
     f32_to_bf16,
     f32_to_f16,
     kv_bytes_ratio,
     pack_codes,
+    project,
     record_layout,
     rope,
     unpack_codes,

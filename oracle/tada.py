@@ -71,6 +71,10 @@ def _c():
         lib.orc_f32_to_bf16_rne.argtypes = [ctypes.c_float]
         lib.orc_rope.restype = i
         lib.orc_rope.argtypes = [u16p, i, i, i, i, f32p, f32p, i, u16p]
+        lib.orc_project.restype = i
+        lib.orc_project.argtypes = [u16p, u16p, i, i, i, i, u16p]
+        lib.orc_f64_to_16_rne.restype = ctypes.c_uint16
+        lib.orc_f64_to_16_rne.argtypes = [ctypes.c_double, i]
         lib.orc_widen.restype = None
         lib.orc_widen.argtypes = [u16p, i, ctypes.c_size_t, f32p]
         _lib = lib
@@ -118,6 +122,28 @@ def rope(x: np.ndarray, dtype: int, cos: np.ndarray, sin: np.ndarray, pairing: i
                        pairing, _p(out, ctypes.c_uint16))
     if rc != 0:
         raise ValueError("orc_rope: bad argument")
+    return out
+
+
+def f64_to_16(v: float, dtype: int) -> int:
+    """binary64 -> the 16-bit type's pattern, one rounding (nearest even)."""
+    return int(_c().orc_f64_to_16_rne(ctypes.c_double(v), dtype))
+
+
+def project(x: np.ndarray, w: np.ndarray, dtype: int) -> np.ndarray:
+    """The value projection of Alg. 1 step 3: x uint16 [..., kdim], w uint16 [n_out, kdim] (one row of
+    weights per output channel) -> uint16 [..., n_out]; binary64 dot products rounded once to the
+    16-bit type."""
+    x = np.ascontiguousarray(x, dtype=np.uint16)
+    w = np.ascontiguousarray(w, dtype=np.uint16)
+    kdim = x.shape[-1]
+    n_out = w.shape[0]
+    assert w.shape == (n_out, kdim)
+    rows = x.size // kdim
+    out = np.empty(x.shape[:-1] + (n_out,), dtype=np.uint16)
+    if _c().orc_project(_p(x, ctypes.c_uint16), _p(w, ctypes.c_uint16), dtype, rows, kdim, n_out,
+                        _p(out, ctypes.c_uint16)) != 0:
+        raise ValueError("orc_project rejected its arguments")
     return out
 
 
@@ -296,6 +322,15 @@ class OracleCache:
             raise OverflowError("append exceeds max_tokens")
         for b in range(cfg.batch):
             self._append_one(layer, b, k_new[b], v_new[b])
+
+    def append_compressv(self, layer: int, k_new: np.ndarray, x: np.ndarray, w_v: np.ndarray) -> np.ndarray:
+        """Alg. 1 steps 3 and 8: the values are the projection of the layer input, x uint16
+        [B, n_new, model_dim] against w_v uint16 [Hkv * d, model_dim], a 16-bit tensor; keys as in
+        append.  Returns the projected values, uint16 [B, n_new, Hkv, d]."""
+        cfg = self.cfg
+        v = project(x, w_v, cfg.dtype).reshape(x.shape[0], x.shape[1], cfg.n_kv_heads, cfg.head_dim)
+        self.append(layer, k_new, v)
+        return v
 
     def append_seq(self, layer: int, b: int, k_new: np.ndarray, v_new: np.ndarray) -> None:
         """Tokens of one sequence only: k_new, v_new uint16 [n_new, H, d]."""

@@ -6,8 +6,9 @@
  * deviations (Sec. 3.2, Eq. 3-4), group quantisation of the deviations to nbits with
  * 16-bit scale / zero-point metadata (Sec. 3 memory formula; Algorithm 1's S and M),
  * reconstruction (Eq. 7-8) and softmax attention over the reconstructed cache plus
- * the uncompressed residual tokens (Eq. 5-6, Eq. 9-10); and the rotary embedding of the
- * keys that Algorithm 1 (step 5) fuses with their compression.
+ * the uncompressed residual tokens (Eq. 5-6, Eq. 9-10); the rotary embedding of the
+ * keys that Algorithm 1 (step 5) fuses with their compression; and the value projection
+ * that step 3 fuses with the compression of the values.
  *
  * Only tests, the smoke check and the cpu_baseline leg of the benchmark may call this
  * file.  It shares no code, header, table or constant with the HIP path.
@@ -170,6 +171,47 @@ int orc_rope(const uint16_t *x, int dtype, int T, int H, int d, const float *cs,
                 out[a] = narrow(p1 - p2, dtype);
                 out[b] = narrow(p3 + p4, dtype);
             }
+        }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ value projection */
+
+/* binary64 -> the 16-bit type, ONE rounding (nearest, ties to even): the value is scaled by a power
+   of two so that the target's unit in the last place becomes 1, rounded to an integer by the
+   default rounding mode, and scaled back; what remains is exactly representable in the 16-bit
+   type (or overflows to infinity), so the final narrowing through binary32 is exact.  Going
+   through binary32 first would round twice. */
+uint16_t orc_f64_to_16_rne(double v, int dtype)
+{
+    if (v != v) return dtype == ORC_BF16 ? 0x7FC0u : 0x7E00u;
+    if (v == 0.0 || isinf(v)) return narrow((float)v, dtype);
+    const int sig = dtype == ORC_BF16 ? 8 : 11;      /* significand bits, hidden one included */
+    const int emin = dtype == ORC_BF16 ? -126 : -14; /* exponent of the smallest normal */
+    int e;
+    (void)frexp(v, &e); /* |v| in [2^(e-1), 2^e) */
+    int ulp_exp = (e - 1) - (sig - 1);
+    if (ulp_exp < emin - (sig - 1)) ulp_exp = emin - (sig - 1); /* subnormal range: fixed spacing */
+    const double r = ldexp(nearbyint(ldexp(v, -ulp_exp)), ulp_exp);
+    return narrow((float)r, dtype); /* exact, or beyond the largest finite value: infinity */
+}
+
+/*
+ * The value projection of Algorithm 1 step 3 (CompressV(X, W_V): the linear projection whose
+ * result is mean-centred and quantised): v[r][o] = sum_k x[r][k] * w[o][k], every product and the
+ * sum in binary64 in index order, rounded once to the 16-bit type -- the projected value is a
+ * 16-bit tensor, as it is when the projection runs as a step of its own.
+ * x [rows][kdim], w [n_out][kdim] (one row of weights per output channel), v [rows][n_out].
+ */
+int orc_project(const uint16_t *x, const uint16_t *w, int dtype, int rows, int kdim, int n_out, uint16_t *v)
+{
+    if (rows < 0 || kdim <= 0 || n_out <= 0) return -1;
+    for (int r = 0; r < rows; r++)
+        for (int o = 0; o < n_out; o++) {
+            double acc = 0.0;
+            for (int k = 0; k < kdim; k++)
+                acc += (double)widen(x[(size_t)r * kdim + k], dtype) * (double)widen(w[(size_t)o * kdim + k], dtype);
+            v[(size_t)r * n_out + o] = orc_f64_to_16_rne(acc, dtype);
         }
     return 0;
 }

@@ -77,6 +77,17 @@ def make_q(seed: int, B: int, Hq: int, d: int, dtype: int) -> np.ndarray:
     return f32_to_bits16(rng.standard_normal((B, Hq, d), dtype=np.float32), dtype)
 
 
+def make_xw(seed: int, B: int, T: int, model_dim: int, n_out: int, dtype: int):
+    """Inputs of the value projection (Alg. 1 step 3): the layer input X ~ N(0,1) as uint16
+    [B, T, model_dim] and the weights W_V ~ N(0, 1/model_dim) as uint16 [n_out, model_dim] (one row
+    per output channel, the layout of a linear layer's weight), so that the projected values are
+    about N(0,1) like the values of make_kv."""
+    rng = np.random.default_rng(seed + 611953)
+    x = rng.standard_normal((B, T, model_dim), dtype=np.float32)
+    w = rng.standard_normal((n_out, model_dim), dtype=np.float32) * np.float32(model_dim ** -0.5)
+    return f32_to_bits16(x, dtype), f32_to_bits16(w, dtype)
+
+
 def layer_bits(seed: int, n_layers: int, scheme: str = "mixed248"):
     """Per-layer bit map.  'mixed248': u<0.25 -> 8, u<0.625 -> 4, else 2 (about a quarter of
     the layers at 8 bits).  'mixed24_8ends': 8-bit on the first and last two layers, the rest
@@ -129,6 +140,18 @@ def make_kv_torch(seed: int, B: int, T: int, H: int, d: int, dtype: int, device,
         v += shared[1]
     v16 = v.to(tdt)
     return k16, v16
+
+
+def make_xw_torch(seed: int, B: int, T: int, model_dim: int, n_out: int, dtype: int, device):
+    """make_xw's recipe drawn on the device: X [B, T, model_dim], W_V [n_out, model_dim], 16-bit."""
+    import torch
+
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed + 611953)
+    tdt = torch.float16 if dtype == F16 else torch.bfloat16
+    x = torch.randn((B, T, model_dim), generator=gen, device=device, dtype=torch.float32).to(tdt)
+    w = (torch.randn((n_out, model_dim), generator=gen, device=device, dtype=torch.float32) * float(model_dim ** -0.5)).to(tdt)
+    return x, w
 
 
 def make_q_torch(seed: int, B: int, Hq: int, d: int, dtype: int, device):

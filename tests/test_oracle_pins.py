@@ -616,3 +616,96 @@ def test_per_sequence_appends_equal_a_batch_of_one_each(oracle):
     big.reset_seq(0, 0)
     assert (big.packed_len(0, 0), big.resid_len(0, 0)) == (0, 0)
     assert np.array_equal(big.attend(0, q)[0], np.zeros((4, d)))
+
+
+# ------------------------------------------------------------------ P14: value projection (Alg. 1 step 3)
+
+
+def _nearest16_exact(v: float, dtype: int) -> int:
+    """Brute force: among all finite patterns of the 16-bit type near v, the one closest to v in
+    exact rational arithmetic, ties to the even pattern."""
+    from fractions import Fraction
+
+    if dtype == F16:
+        vals = np.arange(0, 0x7C00, dtype=np.uint16).view(np.float16).astype(np.float64)
+    else:
+        vals = (np.arange(0, 0x7F80, dtype=np.uint32) << 16).view(np.float32).astype(np.float64)
+    a = abs(v)
+    i = int(np.searchsorted(vals, a))  # vals[i-1] < a <= vals[i]
+    cands = [j for j in (i - 1, i) if 0 <= j < len(vals)]
+    fa = Fraction(a)
+    best = min(cands, key=lambda j: (abs(Fraction(float(vals[j])) - fa), j & 1))
+    return best | (0x8000 if v < 0 else 0)
+
+
+@pytest.mark.parametrize("dtype", [F16, BF16])
+def test_f64_narrowing_rounds_once(oracle, dtype):
+    rng = np.random.default_rng(17)
+    sig = 11 if dtype == F16 else 8
+    xs = list(rng.standard_normal(300) * 10.0 ** rng.integers(-6, 4, 300))
+    # values a hair above / below a tie of the 16-bit type: rounding through binary32 first lands on
+    # the tie and then goes to the even neighbour, one rounding goes to the nearer one
+    for e in (-3, 0, 5):
+        for m in (1, 2, 5, 2 ** (sig - 1) - 1):
+            tie = (2 ** (sig - 1) + m + 0.5) * 2.0 ** (e - sig + 1)
+            xs += [tie * (1 + 2.0 ** -40), tie * (1 - 2.0 ** -40), tie, -tie * (1 + 2.0 ** -40)]
+    xs += [2.0 ** -16 * 1.37, 2.0 ** -20, 1e-7]  # subnormal range of binary16
+    for v in xs:
+        assert oracle.f64_to_16(float(v), dtype) == _nearest16_exact(float(v), dtype), v
+    if dtype == F16:  # numpy narrows binary64 to binary16 directly
+        got = np.array([oracle.f64_to_16(float(v), F16) for v in xs], dtype=np.uint16)
+        assert np.array_equal(got, np.asarray(xs, dtype=np.float64).astype(np.float16).view(np.uint16))
+
+
+def test_projection_hand_case_rounds_the_exact_sum_once(oracle):
+    # x . w = 1 + 2^-8 + 2^-30: just above the bfloat16 tie 1 + 2^-8, so the result is 1 + 2^-7;
+    # a binary32 accumulator (or narrowing through binary32) would drop the 2^-30 and return 1.0
+    x = synth.f32_to_bits16(np.array([[1.0, 2.0 ** -8, 2.0 ** -30]], dtype=np.float32), BF16)
+    w = synth.f32_to_bits16(np.array([[1.0, 1.0, 1.0], [1.0, 0.0, 0.0], [0.0, 2.0, 0.0]], dtype=np.float32), BF16)
+    v = oracle.project(x, w, BF16)
+    assert v.shape == (1, 3)
+    assert synth.bits16_to_f32(v, BF16).tolist() == [[1.0 + 2.0 ** -7, 1.0, 2.0 ** -7]]
+
+
+@pytest.mark.parametrize("dtype", [F16, BF16])
+def test_projection_of_small_integers_is_exact(oracle, dtype):
+    # integer inputs whose dot products stay below 2^8: every sum is representable, so the result
+    # must equal the integer matrix product; rows, inputs and outputs all differ in size, so a
+    # transposed operand or a swapped index cannot pass
+    rng = np.random.default_rng(23)
+    rows, kdim, n_out = 5, 12, 7
+    xi = rng.integers(-3, 4, (rows, kdim))
+    wi = rng.integers(-3, 4, (n_out, kdim))
+    v = oracle.project(synth.f32_to_bits16(xi.astype(np.float32), dtype), synth.f32_to_bits16(wi.astype(np.float32), dtype), dtype)
+    assert np.array_equal(synth.bits16_to_f32(v, dtype).astype(np.int64), xi @ wi.T)
+    assert np.abs(xi @ wi.T).max() < 256 and np.abs(xi @ wi.T).max() > 8
+
+
+@pytest.mark.parametrize("dtype", [F16, BF16])
+def test_projection_matches_numpy_float64(oracle, dtype):
+    B, T, kdim, n_out = 2, 9, 320, 256
+    x, w = synth.make_xw(31, B, T, kdim, n_out, dtype)
+    v = oracle.project(x, w, dtype)
+    assert v.shape == (B, T, n_out)
+    exact = synth.bits16_to_f32(x, dtype).astype(np.float64) @ synth.bits16_to_f32(w, dtype).astype(np.float64).T
+    got = synth.bits16_to_f32(v, dtype).astype(np.float64)
+    ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(exact), 2.0 ** -14))) - (10 if dtype == F16 else 7))
+    # half a unit in the last place of the 16-bit type (+ the few 1e-16 by which numpy's summation
+    # order may differ from the index order)
+    assert np.all(np.abs(got - exact) <= 0.5 * ulp * (1 + 1e-9))
+    assert np.std(got) > 0.5  # the recipe gives values of about unit variance
+
+
+def test_cache_append_with_projection_equals_project_then_append(oracle):
+    H, d, T, kdim = 2, 128, 45, 192
+    cfg = oracle.OracleConfig(1, 2, 2, H, d, 128, 32, 32, 32, BF16, CHAN, [4], [4])
+    k, _ = synth.make_kv(83, 2, T, H, d, BF16)
+    x, w = synth.make_xw(83, 2, T, kdim, H * d, BF16)
+    a, b = oracle.OracleCache(cfg), oracle.OracleCache(cfg)
+    v = a.append_compressv(0, k, x, w)
+    assert v.shape == (2, T, H, d)
+    b.append(0, k, oracle.project(x, w, BF16).reshape(2, T, H, d))
+    assert np.array_equal(a.layer_image(0)["bytes"], b.layer_image(0)["bytes"])
+    # output channel o of the projection is channel o % d of kv head o // d
+    one = oracle.project(x[1, 7:8], w[d + 5:d + 6], BF16)
+    assert one[0, 0] == v[1, 7, 1, 5]
