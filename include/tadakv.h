@@ -221,6 +221,41 @@ kv_status kv_rope_quant_append(kv_cache *cache, int32_t layer, const void *k_pre
                                const float *rope_cos, const float *rope_sin, int32_t pairing,
                                void *stream);
 
+/* Algorithm 1 steps 3 and 8 in one call ("CompressV(X, W_V)"; Sec. 3.4 and App. A "Compressing value
+ * activations": the values' linear projection is fused with their mean-centring and quantisation, so
+ * the projected values never make a round trip through memory), with the keys appended as by
+ * kv_quant_append (or, with tables, as by kv_rope_quant_append: step 5).
+ *   k_new   : device, keys [batch, n_new, n_kv_heads, head_dim], element (b,t,h,c) at
+ *             b*k_stride_b + t*k_stride_t + h*k_stride_h + c (elements; rows 16-byte aligned);
+ *             post-RoPE if rope_cos == rope_sin == NULL, else pre-RoPE
+ *   x       : device, the layer input [batch, n_new, model_dim], 16-bit cfg.dtype, element (b,t,k) at
+ *             b*x_stride_b + t*x_stride_t + k (rows contiguous and 16-byte aligned)
+ *   w_v     : device, value projection weights [n_kv_heads * head_dim, model_dim], cfg.dtype, contiguous:
+ *             one row per output channel (a linear layer's weight); channel o of the projection is
+ *             channel o % head_dim of kv head o / head_dim
+ *   model_dim : positive multiple of 64
+ *   rope_cos, rope_sin, pairing : as kv_rope_quant_append, or both NULL
+ *   v_proj  : device or NULL.  If given, [batch, n_new, n_kv_heads, head_dim] cfg.dtype, contiguous,
+ *             16-byte aligned: receives the projected values as the kernels rounded them (for
+ *             inspection and tests; production callers pass NULL and the tensor never exists)
+ * The projected value V[b,t,o] = sum_k x[b,t,k] * w_v[o,k] is accumulated in binary32 on the matrix
+ * cores (ascending k in steps of 32, the same chain for every token whichever kernel serves it, so the
+ * result does not depend on how a sequence is cut into calls) and rounded to nearest even to
+ * cfg.dtype: a 16-bit tensor, as it is when the projection is a step of its own.  It differs from the
+ * exactly rounded dot product by at most one unit in the last place of cfg.dtype in all but
+ * cancelling sums (error <= 2^-24 * sum_k |x w| + half a unit).  From there on the call is
+ * kv_quant_append of (k_new, V), bit for bit.
+ * Whole blocks made of this call's tokens are compressed in the projection kernel's epilogue; tokens
+ * that stay in the raw residual buffer (and the ones that complete a block begun by an earlier call)
+ * are stored there as rounded rows.  Served formats: group_tokens == 32, k_bits == v_bits in
+ * {2, 4, 8}, KV_MEAN_CHANNEL_BLOCK or KV_MEAN_NONE; others return KV_E_UNSUPPORTED (project, then
+ * kv_quant_append).  Other errors as kv_quant_append.  Sequences that are not active are skipped. */
+kv_status kv_compressv_append(kv_cache *cache, int32_t layer, const void *k_new, int64_t k_stride_b,
+                              int64_t k_stride_t, int64_t k_stride_h, const void *x, int64_t x_stride_b,
+                              int64_t x_stride_t, const void *w_v, int32_t model_dim, int32_t n_new,
+                              const float *rope_cos, const float *rope_sin, int32_t pairing, void *v_proj,
+                              void *stream);
+
 /* One decode step of attention for `layer` over all tokens currently cached (packed + residual).
  *   q    : device, [batch, n_q_heads, head_dim], 16-bit cfg.dtype, contiguous, post-RoPE
  *   out  : device, [batch, n_q_heads, head_dim] float32, contiguous

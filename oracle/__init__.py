@@ -17,6 +17,7 @@ from .tada import (  # noqa: F401
     kv_bytes_ratio,
     pack_codes,
     project,
+    project_f64,
     record_layout,
     rope,
     unpack_codes,

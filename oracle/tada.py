@@ -73,6 +73,8 @@ def _c():
         lib.orc_rope.argtypes = [u16p, i, i, i, i, f32p, f32p, i, u16p]
         lib.orc_project.restype = i
         lib.orc_project.argtypes = [u16p, u16p, i, i, i, i, u16p]
+        lib.orc_project_f64.restype = i
+        lib.orc_project_f64.argtypes = [u16p, u16p, i, i, i, i, f64p, f64p]
         lib.orc_f64_to_16_rne.restype = ctypes.c_uint16
         lib.orc_f64_to_16_rne.argtypes = [ctypes.c_double, i]
         lib.orc_widen.restype = None
@@ -145,6 +147,22 @@ def project(x: np.ndarray, w: np.ndarray, dtype: int) -> np.ndarray:
                         _p(out, ctypes.c_uint16)) != 0:
         raise ValueError("orc_project rejected its arguments")
     return out
+
+
+def project_f64(x: np.ndarray, w: np.ndarray, dtype: int):
+    """The dot products of ``project`` before their rounding, and the sums of the products' magnitudes:
+    two float64 arrays [..., n_out]."""
+    x = np.ascontiguousarray(x, dtype=np.uint16)
+    w = np.ascontiguousarray(w, dtype=np.uint16)
+    kdim, n_out = x.shape[-1], w.shape[0]
+    assert w.shape == (n_out, kdim)
+    rows = x.size // kdim
+    acc = np.empty(x.shape[:-1] + (n_out,), dtype=np.float64)
+    mag = np.empty_like(acc)
+    if _c().orc_project_f64(_p(x, ctypes.c_uint16), _p(w, ctypes.c_uint16), dtype, rows, kdim, n_out,
+                            _p(acc, ctypes.c_double), _p(mag, ctypes.c_double)) != 0:
+        raise ValueError("orc_project_f64 rejected its arguments")
+    return acc, mag
 
 
 # ----------------------------------------------------------------------------- block functions

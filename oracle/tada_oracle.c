@@ -216,6 +216,26 @@ int orc_project(const uint16_t *x, const uint16_t *w, int dtype, int rows, int k
     return 0;
 }
 
+/* The same dot products before the rounding, and the sums of the products' magnitudes (what a
+   test needs to bound the error of an implementation that accumulates in a narrower type). */
+int orc_project_f64(const uint16_t *x, const uint16_t *w, int dtype, int rows, int kdim, int n_out,
+                    double *sum, double *abs_sum)
+{
+    if (rows < 0 || kdim <= 0 || n_out <= 0) return -1;
+    for (int r = 0; r < rows; r++)
+        for (int o = 0; o < n_out; o++) {
+            double acc = 0.0, mag = 0.0;
+            for (int k = 0; k < kdim; k++) {
+                const double pr = (double)widen(x[(size_t)r * kdim + k], dtype) * (double)widen(w[(size_t)o * kdim + k], dtype);
+                acc += pr;
+                mag += fabs(pr);
+            }
+            sum[(size_t)r * n_out + o] = acc;
+            abs_sum[(size_t)r * n_out + o] = mag;
+        }
+    return 0;
+}
+
 /* ------------------------------------------------------------------ encoder */
 
 /* scale / zero of one group of deviations (asymmetric min/max), and its codes.

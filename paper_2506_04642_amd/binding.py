@@ -29,7 +29,7 @@ KV_MEAN_CHANNEL_BLOCK, KV_MEAN_CROSS_HEAD, KV_MEAN_NONE = 0, 1, 2
 
 EXPORTS = [
     "kv_cache_bytes", "kv_workspace_bytes", "kv_cache_create", "kv_cache_destroy", "kv_cache_set_block_table", "kv_cache_set_active", "kv_cache_reset",
-    "kv_cache_len", "kv_cache_len_seq", "kv_cache_reset_seq", "kv_cache_describe", "kv_quant_append", "kv_quant_append_seq", "kv_rope_quant_append", "kv_append_decode_attn", "kv_append_decode_attn_split", "kv_decode_attn", "kv_decode_attn_split",
+    "kv_cache_len", "kv_cache_len_seq", "kv_cache_reset_seq", "kv_cache_describe", "kv_quant_append", "kv_quant_append_seq", "kv_rope_quant_append", "kv_compressv_append", "kv_append_decode_attn", "kv_append_decode_attn_split", "kv_decode_attn", "kv_decode_attn_split",
     "kv_decode_attn_merge", "kv_decode_attn_merge16", "kv_dequant", "kv_decode_splits", "kv_decode_bytes", "kv_set_decode_path", "kv_set_decode_splits", "kv_decode_workspace_need", "kv_decode_attn_static", "kv_strerror", "kv_last_hip_error",
 ]
 
@@ -72,6 +72,7 @@ _lib.kv_quant_append_seq.argtypes = [_vp, _i32, _i32, _vp, _vp, _i32, _i64, _i64
 _lib.kv_cache_describe.argtypes = [_vp, _i32, ctypes.POINTER(kv_layer_layout)]
 _lib.kv_quant_append.argtypes = [_vp, _i32, _vp, _vp, _i32, _i64, _i64, _i64, _vp]
 _lib.kv_rope_quant_append.argtypes = [_vp, _i32, _vp, _vp, _i32, _i64, _i64, _i64, _vp, _vp, _i32, _vp]
+_lib.kv_compressv_append.argtypes = [_vp, _i32, _vp, _i64, _i64, _i64, _vp, _i64, _i64, _vp, _i32, _i32, _vp, _vp, _i32, _vp, _vp]
 _lib.kv_decode_attn.argtypes = [_vp, _i32, _vp, _vp, _vp, ctypes.c_size_t, _vp]
 _lib.kv_append_decode_attn.argtypes = [_vp, _i32, _vp, _vp, _i64, _i64, _vp, _vp, _vp, ctypes.c_size_t, _vp]
 _lib.kv_append_decode_attn_split.argtypes = [_vp, _i32, _vp, _vp, _i64, _i64, _vp, _vp, ctypes.c_size_t, _vp]
@@ -216,6 +217,14 @@ def kv_rope_quant_append(cache: int, layer: int, k_ptr: int, v_ptr: int, n_new: 
                                      cos_ptr, sin_ptr, pairing, stream), "kv_rope_quant_append")
 
 
+def kv_compressv_append(cache: int, layer: int, k_ptr: int, k_stride_b: int, k_stride_t: int, k_stride_h: int,
+                        x_ptr: int, x_stride_b: int, x_stride_t: int, w_ptr: int, model_dim: int, n_new: int,
+                        cos_ptr: int = 0, sin_ptr: int = 0, pairing: int = 0, v_proj_ptr: int = 0, stream: int = 0) -> None:
+    _check(_lib.kv_compressv_append(cache, layer, k_ptr, k_stride_b, k_stride_t, k_stride_h, x_ptr, x_stride_b,
+                                    x_stride_t, w_ptr, model_dim, n_new, cos_ptr or None, sin_ptr or None, pairing,
+                                    v_proj_ptr or None, stream), "kv_compressv_append")
+
+
 def kv_decode_attn(cache: int, layer: int, q_ptr: int, out_ptr: int, ws_ptr: int, ws_bytes: int,
                    stream: int = 0) -> None:
     _check(_lib.kv_decode_attn(cache, layer, q_ptr, out_ptr, ws_ptr, ws_bytes, stream), "kv_decode_attn")
@@ -348,6 +357,18 @@ class KVCache:
         kv_rope_quant_append(self.handle, layer, k_pre.data_ptr(), v_new.data_ptr(), k_pre.shape[1],
                              k_pre.stride(0), k_pre.stride(1), k_pre.stride(2), cos.data_ptr(),
                              sin.data_ptr(), pairing, self._stream())
+
+    def append_compressv(self, layer: int, k_new, x, w_v, cos=None, sin=None, pairing: int = KV_ROPE_HALF, v_proj=None) -> None:
+        """Alg. 1 steps 3 and 8: k_new [B, n_new, Hkv, d], x [B, n_new, model_dim], w_v [Hkv * d, model_dim]
+        (all 16-bit device tensors); optional rotary tables for the keys; v_proj, if given, a contiguous
+        [B, n_new, Hkv, d] tensor that receives the projected values."""
+        assert k_new.stride(3) == 1 and x.stride(2) == 1 and w_v.is_contiguous()
+        assert x.shape[0] == k_new.shape[0] and x.shape[1] == k_new.shape[1] and w_v.shape[1] == x.shape[2]
+        assert v_proj is None or (v_proj.is_contiguous() and tuple(v_proj.shape) == tuple(k_new.shape))
+        kv_compressv_append(self.handle, layer, k_new.data_ptr(), k_new.stride(0), k_new.stride(1), k_new.stride(2),
+                            x.data_ptr(), x.stride(0), x.stride(1), w_v.data_ptr(), x.shape[2], k_new.shape[1],
+                            cos.data_ptr() if cos is not None else 0, sin.data_ptr() if sin is not None else 0, pairing,
+                            v_proj.data_ptr() if v_proj is not None else 0, self._stream())
 
     def attend(self, layer: int, q, out=None):
         """q: device [B, Hq, d] 16-bit contiguous -> float32 [B, Hq, d]."""

@@ -16,6 +16,7 @@ COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
 UNITS = [
     ("tadakv_abi.cpp", ["-x", "hip"]),
     ("quant_append.hip", ["-ffp-contract=off"]),
+    ("compressv.hip", ["-ffp-contract=off"]),
     ("decode_valu.hip", []),
     # matrix-instruction results go straight to ordinary vector registers
     ("decode_mfma.hip", ["-mllvm", "-amdgpu-mfma-vgpr-form"]),
@@ -26,6 +27,7 @@ UNITS = [
 def sources():
     return [os.path.join(CSRC, s) for s, _ in UNITS] + [
         os.path.join(CSRC, "tadakv_internal.h"),
+        os.path.join(CSRC, "quant_wave.h"),
         os.path.join(os.path.dirname(HERE), "include", "tadakv.h"),
     ]
 

@@ -583,6 +583,139 @@ kv_status kv_rope_quant_append(kv_cache *cache, int32_t layer, const void *k_pre
                        pairing == KV_ROPE_HALF ? 1 : 2, rope_cos, rope_sin, stream);
 }
 
+kv_status kv_compressv_append(kv_cache *cache, int32_t layer, const void *k_new, int64_t k_stride_b, int64_t k_stride_t,
+                              int64_t k_stride_h, const void *x, int64_t x_stride_b, int64_t x_stride_t, const void *w_v,
+                              int32_t model_dim, int32_t n_new, const float *rope_cos, const float *rope_sin,
+                              int32_t pairing, void *v_proj, void *stream)
+{
+    kv_status st = layer_ok(cache, layer);
+    if (st != KV_OK) return st;
+    if (n_new < 0) return KV_E_BAD_CONFIG;
+    if (n_new == 0) return KV_OK;
+    if (!k_new || !x || !w_v) return KV_E_NULL;
+    const kv_config &c = cache->cfg;
+    if (((uintptr_t)k_new % 16) || ((uintptr_t)x % 16) || ((uintptr_t)w_v % 16) || ((uintptr_t)v_proj % 16)) return KV_E_ALIGN;
+    if (k_stride_b % 8 || k_stride_t % 8 || k_stride_h % 8 || x_stride_b % 8 || x_stride_t % 8) return KV_E_ALIGN;
+    if (k_stride_h < c.head_dim || k_stride_t < 0 || k_stride_b < 0) return KV_E_BAD_CONFIG;
+    if (model_dim <= 0 || model_dim % 64 || x_stride_t < model_dim || x_stride_b < 0) return KV_E_BAD_CONFIG;
+    int rope = 0;
+    if (rope_cos || rope_sin) {
+        if (!rope_cos || !rope_sin) return KV_E_NULL;
+        if (((uintptr_t)rope_cos % 16) || ((uintptr_t)rope_sin % 16)) return KV_E_ALIGN;
+        if (pairing != KV_ROPE_HALF && pairing != KV_ROPE_INTERLEAVED) return KV_E_BAD_CONFIG;
+        rope = pairing == KV_ROPE_HALF ? 1 : 2;
+    }
+    if (!compressv_supported(cache->geom[layer])) return KV_E_UNSUPPORTED;
+    if (c.pool_blocks > 0 && !cache->table) return KV_E_BAD_CONFIG; // paged placement without a block table
+    if ((long long)c.batch * c.n_kv_heads > 65535) return KV_E_UNSUPPORTED;
+    for (int b = 0; b < c.batch; b++)
+        if (cache->on(b) && (long long)cache->P(layer, b) + cache->R(layer, b) + n_new > c.max_tokens) return KV_E_CAPACITY;
+    const int G = c.group_tokens, R = c.resid_cap;
+    hipStream_t s = (hipStream_t)stream;
+    for (int b0 = 0; b0 < c.batch;) {
+        if (!cache->on(b0)) {
+            b0++;
+            continue;
+        }
+        int b1 = b0 + 1;
+        while (b1 < c.batch && cache->on(b1) && cache->P(layer, b1) == cache->P(layer, b0) && cache->R(layer, b1) == cache->R(layer, b0)) b1++;
+        const int r_old = cache->R(layer, b0);
+        const long long total = (long long)r_old + n_new;
+        const long long n_flush_tok = total / R * R;
+        // ---- keys: the ordinary append, keys' side only
+        AppendArgs a{};
+        a.geom = cache->geom[layer];
+        a.geom.table = cache->table;
+        a.geom.table_stride = cache->table_stride;
+        a.layer = cache->layers[layer];
+        a.k_new = (const uint16_t *)k_new + (long long)b0 * k_stride_b;
+        a.v_new = nullptr;
+        a.stride_b = k_stride_b;
+        a.stride_t = k_stride_t;
+        a.stride_h = k_stride_h;
+        a.n_kv_heads = c.n_kv_heads;
+        a.batch = b1 - b0;
+        a.b0 = b0;
+        a.r_old = r_old;
+        a.first_block = cache->P(layer, b0) / G;
+        a.rope = rope;
+        a.rope_cos = rope_cos;
+        a.rope_sin = rope_sin;
+        a.sides = 1;
+        a.n_flush_blocks = (int)(n_flush_tok / G);
+        if (n_flush_tok > 0) {
+            a.copy_src = (int)(n_flush_tok - r_old);
+            a.copy_dst = 0;
+            a.copy_n = (int)(total - n_flush_tok);
+        } else {
+            a.copy_src = 0;
+            a.copy_dst = r_old;
+            a.copy_n = n_new;
+        }
+        if (a.n_flush_blocks > 0 && launch_flush(a, s) != hipSuccess) return KV_E_HIP;
+        if (a.copy_n > 0 && launch_resid_copy(a, s) != hipSuccess) return KV_E_HIP;
+        // ---- values: projected by the kernels that also compress them (whole blocks of this call's
+        // tokens) or store them as raw rows (tokens that complete a block begun earlier, and the tail)
+        ProjectArgs p{};
+        p.geom = a.geom;
+        p.layer = a.layer;
+        p.x = (const uint16_t *)x + (long long)b0 * x_stride_b;
+        p.x_stride_b = x_stride_b;
+        p.x_stride_t = x_stride_t;
+        p.w = (const uint16_t *)w_v;
+        p.model_dim = model_dim;
+        p.n_kv_heads = c.n_kv_heads;
+        p.batch = b1 - b0;
+        p.b0 = b0;
+        p.vo_stride_h = c.head_dim;
+        p.vo_stride_t = (long long)c.n_kv_heads * c.head_dim;
+        p.vo_stride_b = (long long)n_new * p.vo_stride_t;
+        p.v_out = v_proj ? (uint16_t *)v_proj + (long long)b0 * p.vo_stride_b : nullptr;
+        auto raw_rows = [&](int t0, int n, int dst) {
+            ProjectArgs q = p;
+            q.mode = 1;
+            q.t0 = t0;
+            q.n_tok = n;
+            q.n_groups = (n + 31) / 32;
+            q.dst_row = dst;
+            return launch_compressv(q, s) == hipSuccess;
+        };
+        if (n_flush_tok == 0) {
+            if (!raw_rows(0, n_new, r_old)) return KV_E_HIP;
+        } else {
+            const int n_pre = (G - r_old % G) % G; // tokens that complete the block begun by earlier calls
+            if (n_pre > 0 && !raw_rows(0, n_pre, r_old)) return KV_E_HIP;
+            const int n_old_blocks = (r_old + n_pre) / G; // blocks whose rows all wait in the residual buffer now
+            if (n_old_blocks > 0) {
+                AppendArgs av = a;
+                av.sides = 2;
+                av.rope = 0;
+                av.r_old = r_old + n_pre;
+                av.n_flush_blocks = n_old_blocks;
+                if (launch_flush(av, s) != hipSuccess) return KV_E_HIP;
+            }
+            const int n_new_blocks = (int)(n_flush_tok / G) - n_old_blocks;
+            if (n_new_blocks > 0) {
+                ProjectArgs q = p;
+                q.mode = 0;
+                q.t0 = n_pre;
+                q.n_groups = n_new_blocks;
+                q.n_tok = 32 * n_new_blocks;
+                q.first_block = a.first_block + n_old_blocks;
+                if (launch_compressv(q, s) != hipSuccess) return KV_E_HIP;
+            }
+            const int tail = (int)(total - n_flush_tok);
+            if (tail > 0 && !raw_rows((int)(n_flush_tok - r_old), tail, 0)) return KV_E_HIP;
+        }
+        for (int b = b0; b < b1; b++) {
+            cache->P(layer, b) += (int)n_flush_tok;
+            cache->R(layer, b) = (int)(total - n_flush_tok);
+        }
+        b0 = b1;
+    }
+    return KV_OK;
+}
+
 kv_status kv_decode_splits(const kv_cache *cache, int32_t layer, int32_t *n_splits)
 {
     kv_status st = layer_ok(cache, layer);

@@ -61,6 +61,29 @@ struct AppendArgs {
     // 2: pairs (2i, 2i + 1)); tables [n_new][64] binary32, device
     int rope;
     const float *rope_cos, *rope_sin;
+    // 0: keys and values; 1: keys only; 2: values only (the other side of the call is handled by
+    // another kernel: the value projection fused with the compression, Alg. 1 step 3).  Only the
+    // one-wavefront-per-item quantiser (blocks of 32 tokens, one width) and the raw copy take 1 or 2.
+    int sides;
+};
+
+// Value projection fused with the compression (Alg. 1 step 3): one launch covers, for each sequence
+// of a run, n_groups groups of up to 32 consecutive tokens of the call's input.
+struct ProjectArgs {
+    LayerGeom geom;
+    unsigned char *layer;    // device base of the layer buffer
+    const uint16_t *x;       // layer input rows, [sequence of the run][token of the call][model_dim]
+    long long x_stride_b, x_stride_t; // elements
+    const uint16_t *w;       // value projection weights [n_kv_heads * 128][model_dim], one row per output channel
+    int model_dim;
+    int n_kv_heads, batch, b0; // sequences of this launch and the first one's index in the cache
+    int t0;                  // token of the call's input that group 0 starts at
+    int n_groups, n_tok;     // groups per sequence; tokens per sequence they cover (the last group may be short)
+    int mode;                // 0: group gi is compressed into block first_block + gi; 1: raw rows into the
+                             // residual buffer, token i of the launch at row dst_row + i
+    int first_block, dst_row;
+    uint16_t *v_out;         // if not null: the projected values as a tensor [sequence][token][kv head][128]
+    long long vo_stride_b, vo_stride_t, vo_stride_h;
 };
 
 struct DecodeArgs {
@@ -111,6 +134,8 @@ hipError_t note_launch(hipError_t e);
 
 hipError_t launch_flush(const AppendArgs &a, hipStream_t s);
 hipError_t launch_resid_copy(const AppendArgs &a, hipStream_t s);
+bool compressv_supported(const LayerGeom &g); // formats the fused value projection serves
+hipError_t launch_compressv(const ProjectArgs &p, hipStream_t s);
 hipError_t launch_decode_split_valu(const DecodeArgs &a, hipStream_t s);
 hipError_t launch_decode_split_mfma(const DecodeArgs &a, hipStream_t s);
 bool decode_mfma_supported(const DecodeArgs &a);

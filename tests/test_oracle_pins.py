@@ -696,6 +696,15 @@ def test_projection_matches_numpy_float64(oracle, dtype):
     assert np.std(got) > 0.5  # the recipe gives values of about unit variance
 
 
+def test_unrounded_projection_is_what_the_rounded_one_rounds(oracle):
+    x, w = synth.make_xw(37, 1, 6, 96, 40, BF16)
+    acc, mag = oracle.project_f64(x, w, BF16)
+    xf, wf = synth.bits16_to_f32(x, BF16).astype(np.float64), synth.bits16_to_f32(w, BF16).astype(np.float64)
+    assert np.allclose(acc, xf @ wf.T, rtol=0, atol=1e-12) and np.allclose(mag, np.abs(xf) @ np.abs(wf).T, rtol=1e-13)
+    v = oracle.project(x, w, BF16)
+    assert all(oracle.f64_to_16(float(a), BF16) == int(b) for a, b in zip(acc.ravel(), v.ravel()))
+
+
 def test_cache_append_with_projection_equals_project_then_append(oracle):
     H, d, T, kdim = 2, 128, 45, 192
     cfg = oracle.OracleConfig(1, 2, 2, H, d, 128, 32, 32, 32, BF16, CHAN, [4], [4])
