@@ -13,15 +13,16 @@
 //
 // compressv_gemm_kernel: a workgroup owns 256 tokens (eight groups of 32) x NH kv heads (128
 // channels each); wave (wm, wn) owns tokens 64 wm .. + 63 of head wn: 4 x 8 tiles of
-// v_mfma_f32_16x16x32 accumulators, i.e. two quantiser items.  X and W_V tiles of 64 k-values are
-// fetched straight into LDS (global_load_lds_dwordx4), two stages deep, 16-byte pieces of a row
-// XOR-swizzled by the row so that the operand reads (16 rows x one piece) hit distinct banks.
+// v_mfma_f32_16x16x32 accumulators, i.e. two quantiser items, two waves per SIMD.  X and W_V tiles
+// of 64 k-values (rows of 128 bytes, whole cache lines) are fetched straight into LDS
+// (global_load_lds_dwordx4) a stage ahead, 16-byte pieces of a row XOR-swizzled by the row so that
+// the operand reads (16 rows x one piece) hit distinct banks.
 // Every output element is one chain of model_dim / 32 matrix instructions in ascending k, the same
 // chain in project_rows_kernel below, so a token's projected value does not depend on which of
 // the two kernels, or which tile, produced it.
 //
 // project_rows_kernel: the decode step's shape (a handful of rows against the whole of W_V): one
-// wave per 16 output channels streams its rows of W_V once; bound by reading W_V.
+// wave per 16 output channels and 16 rows, its operands streamed with sixteen steps in flight.
 #include "quant_wave.h"
 
 namespace tadakv {
@@ -30,18 +31,38 @@ namespace {
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4))); // one matrix operand: eight 16-bit values
 typedef const __attribute__((address_space(1))) void *gptr_t;
 typedef __attribute__((address_space(3))) void *lptr_t;
 
 constexpr int kTileTokens = 256; // tokens per workgroup
-constexpr int kStepK = 64;       // k-values per stage: rows of 128 bytes
+constexpr int kStepK = 64;       // k-values per stage: rows of 128 bytes, whole cache lines
 constexpr int kEpiBytes = 16384; // per wave after the main loop: transposed 16-bit tile + record image
 constexpr int kTTStride = 80;    // bytes per channel column of the transposed tile (32 tokens + pad)
 
+template <int DT> __device__ __forceinline__ v4f mfma16(const u32x4 &a, const u32x4 &b, v4f c)
+{
+    if (DT == 1) return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b), c, 0, 0, 0);
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c, 0, 0, 0);
+}
 template <int DT> __device__ __forceinline__ v4f mfma16(const uint4 &a, const uint4 &b, v4f c)
 {
-    if (DT == 1) return __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(const v8bf *)&a, *(const v8bf *)&b, c, 0, 0, 0);
-    return __builtin_amdgcn_mfma_f32_16x16x32_f16(*(const v8h *)&a, *(const v8h *)&b, c, 0, 0, 0);
+    return mfma16<DT>(u32x4{a.x, a.y, a.z, a.w}, u32x4{b.x, b.y, b.z, b.w}, c);
+}
+
+// LDS operand read issued by hand.  The compiler makes every LDS read it knows of wait for all
+// outstanding direct-to-LDS fetches (it cannot tell which buffer they fill), which would undo the
+// fetch-ahead of the main loop; these reads are invisible to that rule.  The result must not be used
+// before lds_reads_done has been given the same registers.
+template <int OFF> __device__ __forceinline__ void lds_read16(u32x4 &dst, uint32_t addr)
+{
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF));
+}
+__device__ __forceinline__ void lds_reads_done(u32x4 (&a)[4], u32x4 (&b)[8])
+{
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]),
+                   "+v"(b[4]), "+v"(b[5]), "+v"(b[6]), "+v"(b[7]));
 }
 
 // two binary32 values rounded (nearest even) to the 16-bit type, packed low | high << 16
@@ -160,11 +181,16 @@ __device__ __forceinline__ void tile_out(const ProjectArgs &p, float (&x)[8][8],
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // the image is in registers before the next group overwrites it
 }
 
+template <int N> __device__ __forceinline__ void wait_vm()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
 template <int DT, int NH, int GC, int BITS>
 __global__ __launch_bounds__(256 * NH) void compressv_gemm_kernel(ProjectArgs p)
 {
     constexpr int NW = 4 * NH;                      // waves: 4 token quarters x NH heads
-    constexpr int A_BYTES = kTileTokens * 128;      // X tile of a stage
+    constexpr int A_BYTES = kTileTokens * 128;      // X tile of a stage: 64 k-values, rows of 128 bytes
     constexpr int B_BYTES = NH * kHeadDim * 128;    // W_V tile of a stage
     constexpr int STAGE = A_BYTES + B_BYTES;
     constexpr int PER = STAGE / 1024 / NW;          // fetch instructions (1 KiB each) per wave and stage
@@ -185,7 +211,7 @@ __global__ __launch_bounds__(256 * NH) void compressv_gemm_kernel(ProjectArgs p)
     if (tile * 8 >= n_f) return; // (the grid is padded to whole rounds of eight tiles)
 
     // ---- where this lane's pieces of a stage come from: instruction q of the stage fills rows
-    // 8 q .. 8 q + 7 (128 bytes each), lane l the piece (l & 7) ^ (row & 7) of row 8 q + (l >> 3)
+    // 8 q .. 8 q + 7 (128 bytes each: whole cache lines), lane l the piece (l & 7) ^ (row & 7) of row 8 q + (l >> 3)
     const uint16_t *src[PER];
     {
         const int r8 = lane >> 3, pc = (lane & 7) ^ r8;
@@ -206,11 +232,13 @@ __global__ __launch_bounds__(256 * NH) void compressv_gemm_kernel(ProjectArgs p)
             }
         }
     }
-    auto issue = [&](int stage, int kstep) {
+    const int stages = p.model_dim / kStepK;
+    auto issue = [&](int sg) { // stage sg (k-values 64 sg .. + 63; the last stage again beyond it) into buffer sg % 2
+        const int sk = sg < stages ? sg : stages - 1;
 #pragma unroll
         for (int i = 0; i < PER; i++) {
             const int q = wave * PER + i;
-            __builtin_amdgcn_global_load_lds((gptr_t)(src[i] + (long long)kstep * kStepK), (lptr_t)(lds + stage * STAGE + q * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr_t)(src[i] + (long long)sk * kStepK), (lptr_t)(lds + (sg & 1) * STAGE + q * 1024), 16, 0, 0);
         }
     };
 
@@ -221,33 +249,62 @@ __global__ __launch_bounds__(256 * NH) void compressv_gemm_kernel(ProjectArgs p)
         for (int nt = 0; nt < 8; nt++) acc[mt][nt] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
 
     const int n = lane & 15, kg = lane >> 4;
-    int off_ks[2]; // byte offset of this lane's operand piece inside a 16-row tile, per 32-k half of the stage
+    // this lane's operand piece inside a 16-row tile (2 KiB) for the low and the high 32 k-values of
+    // a stage: row n, piece 4 half + kg, swizzled by the row
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)lds;
+    const uint32_t a_base = lds0 + wm * (64 * 128) + n * 128, b_base = lds0 + A_BYTES + wn * (kHeadDim * 128) + n * 128;
+    const uint32_t sw_lo = (uint32_t)((kg ^ (n & 7)) << 4), sw_hi = (uint32_t)(((4 + kg) ^ (n & 7)) << 4);
+    u32x4 fa[2][4], fb[2][8]; // operands of the current half step and of the next one
+    auto read_frags = [&](int sg, uint32_t sw, u32x4(&a)[4], u32x4(&b)[8]) {
+        const uint32_t so = (uint32_t)((sg & 1) * STAGE) + sw;
+        lds_read16<0>(a[0], a_base + so);
+        lds_read16<2048>(a[1], a_base + so);
+        lds_read16<4096>(a[2], a_base + so);
+        lds_read16<6144>(a[3], a_base + so);
+        lds_read16<0>(b[0], b_base + so);
+        lds_read16<2048>(b[1], b_base + so);
+        lds_read16<4096>(b[2], b_base + so);
+        lds_read16<6144>(b[3], b_base + so);
+        lds_read16<8192>(b[4], b_base + so);
+        lds_read16<10240>(b[5], b_base + so);
+        lds_read16<12288>(b[6], b_base + so);
+        lds_read16<14336>(b[7], b_base + so);
+    };
+    auto mfmas = [&](u32x4(&a)[4], u32x4(&b)[8]) {
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int ks = 0; ks < 2; ks++) off_ks[ks] = n * 128 + (((4 * ks + kg) ^ (n & 7)) << 4);
+        for (int mt = 0; mt < 4; mt++)
+#pragma unroll
+            for (int nt = 0; nt < 8; nt++) acc[mt][nt] = mfma16<DT>(a[mt], b[nt], acc[mt][nt]);
+        __builtin_amdgcn_sched_barrier(0);
+    };
 
-    const int steps = p.model_dim / kStepK;
-    issue(0, 0);
-    for (int st = 0; st < steps; st++) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); // this wave's pieces of stage st are in LDS
-        __syncthreads();                                  // everybody's are, and stage st - 1 has been read by all
-        if (st + 1 < steps) issue((st + 1) & 1, st + 1);
-        const unsigned char *sa = lds + (st & 1) * STAGE + wm * (64 * 128);
-        const unsigned char *sb = lds + (st & 1) * STAGE + A_BYTES + wn * (kHeadDim * 128);
-#pragma unroll
-        for (int ks = 0; ks < 2; ks++) {
-            uint4 a[4], b[8];
-#pragma unroll
-            for (int mt = 0; mt < 4; mt++) a[mt] = *(const uint4 *)(sa + mt * 2048 + off_ks[ks]);
-#pragma unroll
-            for (int nt = 0; nt < 8; nt++) b[nt] = *(const uint4 *)(sb + nt * 2048 + off_ks[ks]);
-#pragma unroll
-            for (int mt = 0; mt < 4; mt++)
-#pragma unroll
-                for (int nt = 0; nt < 8; nt++) acc[mt][nt] = mfma16<DT>(a[mt], b[nt], acc[mt][nt]);
-        }
+    // A stage is consumed in two half steps of 32 k-values (32 matrix instructions per wave each);
+    // the operands of a half step are read from LDS while the matrix instructions of the half step
+    // before it run.  Once a wave holds the high half's operands it is done with the stage's buffer;
+    // at the one barrier of a stage everybody is, and everybody's part of the next stage (fetched one
+    // stage earlier) has landed; then the stage after the next is fetched into the freed buffer and
+    // the next stage's low operands are read.  Past the last stage the fetch repeats the last one into
+    // a buffer nobody reads any more and the operand read returns unused data, so that every stage is
+    // the same straight line of code.
+    issue(0);
+    issue(1);
+    wait_vm<PER>(); // stage 0 has landed
+    __builtin_amdgcn_s_barrier();
+    read_frags(0, sw_lo, fa[0], fb[0]);
+    for (int sg = 0; sg < stages; sg++) {
+        lds_reads_done(fa[0], fb[0]);
+        read_frags(sg, sw_hi, fa[1], fb[1]);
+        mfmas(fa[0], fb[0]);
+        lds_reads_done(fa[1], fb[1]);
+        wait_vm<0>();
+        __builtin_amdgcn_s_barrier();
+        issue(sg + 2);
+        read_frags(sg + 1, sw_lo, fa[0], fb[0]);
+        mfmas(fa[1], fb[1]);
     }
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     __syncthreads(); // the staging buffers are free: each wave takes 16 KiB of them for its epilogue
-
     unsigned char *tt = lds + wave * kEpiBytes;  // [128 channels][32 tokens] 16-bit, kTTStride bytes per channel
     unsigned char *img = tt + kHeadDim * kTTStride; // the values' part of a record
     const int tg = lane & 3, c8 = lane >> 2;
@@ -284,61 +341,54 @@ __global__ __launch_bounds__(256 * NH) void compressv_gemm_kernel(ProjectArgs p)
     }
 }
 
-// A few rows (a decode step: one token per sequence) against all of W_V.  One wave per 16 output
-// channels: B operand = its 16 rows of W_V, read once, 16 bytes per lane and matrix instruction
-// (k-values 32 s + 8 (l >> 4) .. + 7 of channel l & 15), several steps in flight; A operand = the
-// rows of X (16 per tile, MT tiles), from the cache.  Same accumulation chain as the tiled kernel.
+// A few rows (a decode step: one token per sequence) against all of W_V.  One wave per (16 output
+// channels, 16 rows): B operand = its 16 rows of W_V, 16 bytes per lane and matrix instruction
+// (k-values 32 s + 8 (l >> 4) .. + 7 of channel l & 15); A operand = its rows of X.  Sixteen steps
+// of loads are in flight per lane: each step's registers are loaded again as soon as its matrix
+// instruction has consumed them.  Same accumulation chain as the tiled kernel.
 // Row r of the launch is token t0 + r % n_tok of sequence r / n_tok (of the run).
-template <int DT, int MT>
+template <int DT>
 __global__ __launch_bounds__(64) void project_rows_kernel(ProjectArgs p)
 {
     const int lane = threadIdx.x, n = lane & 15, kg = lane >> 4;
-    const int o0 = blockIdx.x * 16; // first output channel of the wave
+    const int o0 = blockIdx.x * 16, r0 = blockIdx.y * 16; // first output channel, first row of the wave
     const int rows = p.batch * p.n_tok;
     const uint16_t *wrow = p.w + (long long)(o0 + n) * p.model_dim + 8 * kg;
-    const uint16_t *xrow[MT];
-#pragma unroll
-    for (int mt = 0; mt < MT; mt++) {
-        int r = 16 * mt + n;
-        r = r < rows ? r : rows - 1;
-        xrow[mt] = p.x + (long long)(r / p.n_tok) * p.x_stride_b + (long long)(p.t0 + r % p.n_tok) * p.x_stride_t + 8 * kg;
-    }
-    v4f acc[MT];
-#pragma unroll
-    for (int mt = 0; mt < MT; mt++) acc[mt] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
-    constexpr int UN = 8; // matrix-instruction steps per batch of loads
+    int ra = r0 + n;
+    ra = ra < rows ? ra : rows - 1;
+    const uint16_t *xrow = p.x + (long long)(ra / p.n_tok) * p.x_stride_b + (long long)(p.t0 + ra % p.n_tok) * p.x_stride_t + 8 * kg;
+    v4f acc = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+    constexpr int D = 16; // steps in flight
     const int steps = p.model_dim / 32;
-    for (int s0 = 0; s0 < steps; s0 += UN) {
-        uint4 b[UN], a[MT][UN];
+    uint4 a[D], b[D];
 #pragma unroll
-        for (int i = 0; i < UN; i++) {
-            const int s = s0 + i < steps ? s0 + i : steps - 1;
-            b[i] = *(const uint4 *)(wrow + 32 * s);
-#pragma unroll
-            for (int mt = 0; mt < MT; mt++) a[mt][i] = *(const uint4 *)(xrow[mt] + 32 * s);
-        }
-#pragma unroll
-        for (int i = 0; i < UN; i++)
-            if (s0 + i < steps) {
-#pragma unroll
-                for (int mt = 0; mt < MT; mt++) acc[mt] = mfma16<DT>(a[mt][i], b[i], acc[mt]);
-            }
+    for (int i = 0; i < D; i++) {
+        const int s = i < steps ? i : steps - 1;
+        b[i] = *(const uint4 *)(wrow + 32 * s);
+        a[i] = *(const uint4 *)(xrow + 32 * s);
     }
-    // lane: rows 16 mt + 4 kg .. + 3 of channel o0 + n
+    for (int s0 = 0; s0 < steps; s0 += D) {
+#pragma unroll
+        for (int i = 0; i < D; i++) {
+            if (s0 + i < steps) acc = mfma16<DT>(a[i], b[i], acc);
+            const int s = s0 + i + D < steps ? s0 + i + D : steps - 1;
+            b[i] = *(const uint4 *)(wrow + 32 * s);
+            a[i] = *(const uint4 *)(xrow + 32 * s);
+        }
+    }
+    // lane: rows r0 + 4 kg .. + 3 of channel o0 + n
     const int o = o0 + n, h = o / kHeadDim, c = o % kHeadDim;
 #pragma unroll
-    for (int mt = 0; mt < MT; mt++)
-#pragma unroll
-        for (int j = 0; j < 4; j++) {
-            const int r = 16 * mt + 4 * kg + j;
-            if (r >= rows) continue;
-            const int b = r / p.n_tok, t = r % p.n_tok;
-            const uint16_t v = (uint16_t)(narrow2<DT>(acc[mt][j], 0.0f) & 0xFFFFu);
-            if (p.v_out)
-                p.v_out[(long long)b * p.vo_stride_b + (long long)(p.t0 + t) * p.vo_stride_t + (long long)h * p.vo_stride_h + c] = v;
-            const long long u = (long long)(p.b0 + b) * p.n_kv_heads + h;
-            *(uint16_t *)(p.layer + p.geom.v_resid_off + (u * p.geom.R + p.dst_row + t) * (kHeadDim * 2) + c * 2) = v;
-        }
+    for (int j = 0; j < 4; j++) {
+        const int r = r0 + 4 * kg + j;
+        if (r >= rows) continue;
+        const int bb = r / p.n_tok, t = r % p.n_tok;
+        const uint16_t v = (uint16_t)(narrow2<DT>(acc[j], 0.0f) & 0xFFFFu);
+        if (p.v_out)
+            p.v_out[(long long)bb * p.vo_stride_b + (long long)(p.t0 + t) * p.vo_stride_t + (long long)h * p.vo_stride_h + c] = v;
+        const long long u = (long long)(p.b0 + bb) * p.n_kv_heads + h;
+        *(uint16_t *)(p.layer + p.geom.v_resid_off + (u * p.geom.R + p.dst_row + t) * (kHeadDim * 2) + c * 2) = v;
+    }
 }
 
 template <int DT, int NH, int GC, int BITS> hipError_t launch_gemm(const ProjectArgs &p, hipStream_t s)
@@ -364,11 +414,9 @@ template <int DT, int NH> hipError_t launch_gemm_fmt(const ProjectArgs &p, hipSt
 
 template <int DT> hipError_t launch_rows(const ProjectArgs &p, hipStream_t s)
 {
-    const int rows = p.batch * p.n_tok, mt = (rows + 15) / 16;
-    const dim3 grid(p.n_kv_heads * kHeadDim / 16), block(64);
-    if (mt == 1) hipLaunchKernelGGL((project_rows_kernel<DT, 1>), grid, block, 0, s, p);
-    else if (mt == 2) hipLaunchKernelGGL((project_rows_kernel<DT, 2>), grid, block, 0, s, p);
-    else hipLaunchKernelGGL((project_rows_kernel<DT, 4>), grid, block, 0, s, p);
+    const int rows = p.batch * p.n_tok;
+    const dim3 grid(p.n_kv_heads * kHeadDim / 16, (rows + 15) / 16), block(64);
+    hipLaunchKernelGGL((project_rows_kernel<DT>), grid, block, 0, s, p);
     return note_launch(hipGetLastError());
 }
 
@@ -385,7 +433,7 @@ hipError_t launch_compressv(const ProjectArgs &p, hipStream_t s)
         return note_launch(hipErrorInvalidValue);
     (void)hipGetLastError(); // drop any stale error left by earlier runtime calls of this thread
     // raw rows of a decode step: the streaming kernel
-    if (p.mode == 1 && (long long)p.batch * p.n_tok <= 64)
+    if (p.mode == 1 && (long long)p.batch * p.n_tok <= 256)
         return p.geom.dtype == 1 ? launch_rows<1>(p, s) : launch_rows<0>(p, s);
     if (p.n_kv_heads % 2 == 0) return p.geom.dtype == 1 ? launch_gemm_fmt<1, 2>(p, s) : launch_gemm_fmt<0, 2>(p, s);
     return p.geom.dtype == 1 ? launch_gemm_fmt<1, 1>(p, s) : launch_gemm_fmt<0, 1>(p, s);

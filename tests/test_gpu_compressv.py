@@ -145,10 +145,10 @@ def test_chunked_calls_equal_the_bulk_call(kv, oracle, R, bits):
     check_attention(gpu, orc, 0, synth.make_q(720, B, 4 * H, 128, BF16), BF16)
 
 
-@pytest.mark.parametrize("B", [1, 20, 40, 70])
+@pytest.mark.parametrize("B", [1, 20, 70, 300])
 def test_decode_steps(kv, oracle, B):
     """One token per sequence and call across two block boundaries: up to 64 rows go through the
-    streaming kernel (one, two or four row tiles), more through the tiled one."""
+    streaming kernel (one wave per 16 rows and 16 channels), more than 256 through the tiled one."""
     print("case compressv decode B=%d" % B, flush=True)
     H, kdim, T = 2, 256, 70
     gpu, orc = make_pair(kv, oracle, B=B, Hq=H, Hkv=H, T_max=96, dtype=BF16, k_bits=(4,))
