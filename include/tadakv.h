@@ -346,6 +346,15 @@ kv_status kv_decode_workspace_need(const kv_cache *cache, int32_t layer, size_t 
 #define KV_STATIC_WORKSPACE_BYTES (8u << 20)
 kv_status kv_decode_attn_static(const kv_cache *cache, int32_t layer, const void *q, float *out, void *stream);
 
+/* Measurement aid, not part of the method: one read-only pass over `bytes` bytes at `buf` (device,
+ * 16-byte aligned; whole 16-byte pieces are read) with 16-byte loads, one workgroup per contiguous
+ * 64 KiB -- the rate the memory system delivers to a kernel that does nothing else,
+ * which the benchmark reports beside the published HBM peak as the measured ceiling of the decode
+ * kernels (they are bound by reading the packed cache, App. A).  sink8: device, 8 bytes, or NULL
+ * (written only if the data folds to one particular value; its content is meaningless).
+ * KV_E_BAD_CONFIG for fewer than 16 bytes. */
+kv_status kv_stream_read_probe(const void *buf, size_t bytes, void *sink8, void *stream);
+
 const char *kv_strerror(kv_status s);
 
 /* Text of the HIP error behind the calling thread's most recent KV_E_HIP ("no error" if none). */

@@ -30,7 +30,7 @@ KV_MEAN_CHANNEL_BLOCK, KV_MEAN_CROSS_HEAD, KV_MEAN_NONE = 0, 1, 2
 EXPORTS = [
     "kv_cache_bytes", "kv_workspace_bytes", "kv_cache_create", "kv_cache_destroy", "kv_cache_set_block_table", "kv_cache_set_active", "kv_cache_reset",
     "kv_cache_len", "kv_cache_len_seq", "kv_cache_reset_seq", "kv_cache_describe", "kv_quant_append", "kv_quant_append_seq", "kv_rope_quant_append", "kv_compressv_append", "kv_append_decode_attn", "kv_append_decode_attn_split", "kv_decode_attn", "kv_decode_attn_split",
-    "kv_decode_attn_merge", "kv_decode_attn_merge16", "kv_dequant", "kv_decode_splits", "kv_decode_bytes", "kv_set_decode_path", "kv_set_decode_splits", "kv_decode_workspace_need", "kv_decode_attn_static", "kv_strerror", "kv_last_hip_error",
+    "kv_decode_attn_merge", "kv_decode_attn_merge16", "kv_dequant", "kv_decode_splits", "kv_decode_bytes", "kv_set_decode_path", "kv_set_decode_splits", "kv_decode_workspace_need", "kv_decode_attn_static", "kv_stream_read_probe", "kv_strerror", "kv_last_hip_error",
 ]
 
 
@@ -86,6 +86,7 @@ _lib.kv_set_decode_path.argtypes = [_vp, _i32]
 _lib.kv_set_decode_splits.argtypes = [_vp, _i32]
 _lib.kv_decode_workspace_need.argtypes = [_vp, _i32, _szp]
 _lib.kv_decode_attn_static.argtypes = [_vp, _i32, _vp, _vp, _vp]
+_lib.kv_stream_read_probe.argtypes = [_vp, ctypes.c_size_t, _vp, _vp]
 _lib.kv_strerror.argtypes = [_i32]
 _lib.kv_strerror.restype = ctypes.c_char_p
 _lib.kv_last_hip_error.argtypes = []
@@ -289,6 +290,10 @@ def kv_decode_workspace_need(cache: int, layer: int) -> int:
 
 def kv_decode_attn_static(cache: int, layer: int, q_ptr: int, out_ptr: int, stream: int = 0) -> None:
     _check(_lib.kv_decode_attn_static(cache, layer, q_ptr, out_ptr, stream), "kv_decode_attn_static")
+
+
+def kv_stream_read_probe(buf_ptr: int, nbytes: int, sink_ptr: int = 0, stream: int = 0) -> None:
+    _check(_lib.kv_stream_read_probe(buf_ptr, nbytes, sink_ptr or None, stream), "kv_stream_read_probe")
 
 
 # ---- memory / stream plumbing

@@ -21,6 +21,7 @@ UNITS = [
     # matrix-instruction results go straight to ordinary vector registers
     ("decode_mfma.hip", ["-mllvm", "-amdgpu-mfma-vgpr-form"]),
     ("xhead_dense.hip", []),
+    ("stream_probe.hip", []),
 ]
 
 

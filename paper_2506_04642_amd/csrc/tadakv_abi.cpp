@@ -931,6 +931,14 @@ kv_status kv_decode_attn(const kv_cache *cache, int32_t layer, const void *q, fl
     return kv_decode_attn_merge(cache, layer, out, workspace, workspace_bytes, stream);
 }
 
+kv_status kv_stream_read_probe(const void *buf, size_t bytes, void *sink8, void *stream)
+{
+    if (!buf) return KV_E_NULL;
+    if (((uintptr_t)buf % 16) || ((uintptr_t)sink8 % 8)) return KV_E_ALIGN;
+    if (bytes < 16) return KV_E_BAD_CONFIG;
+    return launch_stream_read(buf, bytes, (unsigned long long *)sink8, (hipStream_t)stream) == hipSuccess ? KV_OK : KV_E_HIP;
+}
+
 kv_status kv_decode_workspace_need(const kv_cache *cache, int32_t layer, size_t *bytes)
 {
     kv_status st = layer_ok(cache, layer);

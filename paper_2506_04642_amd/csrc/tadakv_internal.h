@@ -146,6 +146,8 @@ hipError_t launch_dequant(const DequantArgs &q, hipStream_t s);
 // split kernel) and the value mean plane's contribution to the partial outputs (before the merge)
 hipError_t launch_xhead_scores(const DecodeArgs &a, hipStream_t s);
 hipError_t launch_xhead_values(const DecodeArgs &a, hipStream_t s);
-int xhead_values_resident(int n_q_heads); // workgroups of the value-mean kernel the device holds at once
+int xhead_values_resident(int n_q_heads);
+// read-only streaming pass over a buffer (the benchmark's measured bandwidth ceiling)
+hipError_t launch_stream_read(const void *buf, size_t bytes, unsigned long long *sink, hipStream_t s); // workgroups of the value-mean kernel the device holds at once
 
 } // namespace tadakv
