@@ -39,6 +39,28 @@
  *     before recording.
  *   - One cache must be used by one thread at a time.
  *   - head_dim must be 128.
+ *
+ * Preconditions on the data (device memory cannot be validated by the host; outside them the
+ * results are unspecified, never an out-of-range access): every input element is finite, and every
+ * mean, group minimum and group range / (2^bits - 1) has magnitude below 65504 -- scale, zero and
+ * mean are stored as binary16 (for binary16 inputs this always holds; bfloat16 inputs must stay
+ * within about +-3e4).  Queries above 65504 in magnitude lose the cross-head mean's term.
+ *
+ * Error model
+ *   - Cache contents (codes, scale, zero, mean, raw rows): a function of the inputs alone, the same
+ *     bits on every run and for every way of cutting a sequence into append calls; |x - x^| <=
+ *     scale / 2 per element (+ binary32 rounding), x^ = mean + (zero + scale * code) (Eq. 7-8).
+ *   - Attention output against exact arithmetic on x^ (Eq. 5-6): the vector-ALU kernels accumulate
+ *     in binary32 throughout: error <= 2e-3 absolute for any input within the preconditions whose
+ *     outputs stay below about 1e3 in magnitude (relative 1e-6).  The matrix-core kernels form the
+ *     products of codes exactly (int8 x int8 -> int32) and carry the small operands, q * key scale
+ *     per block and softmax weight * value scale per 64-token chunk, as 23-bit fixed point relative
+ *     to the largest of them in the block / chunk: error <= 1.6e-5 * R absolute, R = the largest
+ *     range (max - min of the deviations) of a quantisation group in the layer, plus the binary32
+ *     level of the other path; i.e. <= 2e-3 up to R = 128 (activations of the kind the paper
+ *     quantises have R < 30: measured <= 1e-6), and 4.9e-3 on outputs of +-300 when a planted value
+ *     of 300 sets R.
+ *   - Repeated calls on the same state return the same bits (no atomics, fixed summation orders).
  */
 #ifndef TADAKV_H
 #define TADAKV_H
@@ -319,8 +341,17 @@ kv_status kv_decode_bytes(const kv_cache *cache, int32_t layer, size_t *bytes);
  * The matrix-core kernels serve layers with k_bits == v_bits in {2, 4, 8}, group_tokens ==
  * group_channels in {32, 64, 128} and up to 8 query heads per kv head (with KV_MEAN_CROSS_HEAD:
  * at most 64 query heads); with path 2 a decode of any other layer returns KV_E_UNSUPPORTED.  The
- * vector-ALU kernels serve every format except KV_MEAN_CROSS_HEAD with group_tokens == 128.  Returns KV_E_BAD_CONFIG for other values.  Affects later calls on this cache only. */
+ * vector-ALU kernels serve every format (about twenty times slower: use kv_decode_path_used to see
+ * which family a layer gets).  Returns KV_E_BAD_CONFIG for other values.  Affects later calls on
+ * this cache only. */
 kv_status kv_set_decode_path(kv_cache *cache, int32_t path);
+
+/* Which kernel family a decode call of `layer` would run on in the cache's present state:
+ * *path = 1 (vector-ALU kernels) or 2 (matrix-core kernels).  A layer whose format the matrix-core
+ * kernels do not take (different widths for keys and values, group_tokens != group_channels, a
+ * 16-bit layer) is served by the vector-ALU kernels under the automatic choice, at a small fraction
+ * of the rate: this call makes that visible.  Errors as kv_decode_splits. */
+kv_status kv_decode_path_used(const kv_cache *cache, int32_t layer, int32_t *path);
 
 /* Force the number of sequence splits of later decode calls on this cache (clamped to the number
  * of blocks); 0 restores the automatic choice.  The workspace must then hold

@@ -30,7 +30,7 @@ KV_MEAN_CHANNEL_BLOCK, KV_MEAN_CROSS_HEAD, KV_MEAN_NONE = 0, 1, 2
 EXPORTS = [
     "kv_cache_bytes", "kv_workspace_bytes", "kv_cache_create", "kv_cache_destroy", "kv_cache_set_block_table", "kv_cache_set_active", "kv_cache_reset",
     "kv_cache_len", "kv_cache_len_seq", "kv_cache_reset_seq", "kv_cache_describe", "kv_quant_append", "kv_quant_append_seq", "kv_rope_quant_append", "kv_compressv_append", "kv_append_decode_attn", "kv_append_decode_attn_split", "kv_decode_attn", "kv_decode_attn_split",
-    "kv_decode_attn_merge", "kv_decode_attn_merge16", "kv_dequant", "kv_decode_splits", "kv_decode_bytes", "kv_set_decode_path", "kv_set_decode_splits", "kv_decode_workspace_need", "kv_decode_attn_static", "kv_stream_read_probe", "kv_strerror", "kv_last_hip_error",
+    "kv_decode_attn_merge", "kv_decode_attn_merge16", "kv_dequant", "kv_decode_splits", "kv_decode_bytes", "kv_set_decode_path", "kv_decode_path_used", "kv_set_decode_splits", "kv_decode_workspace_need", "kv_decode_attn_static", "kv_stream_read_probe", "kv_strerror", "kv_last_hip_error",
 ]
 
 
@@ -84,6 +84,7 @@ _lib.kv_decode_splits.argtypes = [_vp, _i32, ctypes.POINTER(_i32)]
 _lib.kv_decode_bytes.argtypes = [_vp, _i32, _szp]
 _lib.kv_set_decode_path.argtypes = [_vp, _i32]
 _lib.kv_set_decode_splits.argtypes = [_vp, _i32]
+_lib.kv_decode_path_used.argtypes = [_vp, _i32, ctypes.POINTER(_i32)]
 _lib.kv_decode_workspace_need.argtypes = [_vp, _i32, _szp]
 _lib.kv_decode_attn_static.argtypes = [_vp, _i32, _vp, _vp, _vp]
 _lib.kv_stream_read_probe.argtypes = [_vp, ctypes.c_size_t, _vp, _vp]
@@ -273,6 +274,12 @@ def kv_decode_bytes(cache: int, layer: int) -> int:
 
 def kv_set_decode_path(cache: int, path: int) -> None:
     _check(_lib.kv_set_decode_path(cache, path), "kv_set_decode_path")
+
+
+def kv_decode_path_used(cache: int, layer: int) -> int:
+    n = _i32()
+    _check(_lib.kv_decode_path_used(cache, layer, ctypes.byref(n)), "kv_decode_path_used")
+    return n.value
 
 
 def kv_set_decode_splits(cache: int, n_splits: int) -> None:

@@ -766,6 +766,19 @@ kv_status kv_set_decode_path(kv_cache *cache, int32_t path)
     return KV_OK;
 }
 
+kv_status kv_decode_path_used(const kv_cache *cache, int32_t layer, int32_t *path)
+{
+    kv_status st = layer_ok(cache, layer);
+    if (st != KV_OK) return st;
+    if (!path) return KV_E_NULL;
+    DecodeArgs a{};
+    st = fill_decode(cache, layer, &a);
+    if (st != KV_OK) return st;
+    if (cache->decode_path == 2 && !decode_mfma_supported(a)) return KV_E_UNSUPPORTED;
+    *path = use_mfma(cache, a) ? 2 : 1;
+    return KV_OK;
+}
+
 kv_status kv_set_decode_splits(kv_cache *cache, int32_t n_splits)
 {
     if (!cache) return KV_E_NULL;
@@ -786,8 +799,6 @@ kv_status kv_decode_attn_split(const kv_cache *cache, int32_t layer, const void 
     if (st != KV_OK) return st;
     st = bind_workspace(cache, &a, workspace, workspace_bytes);
     if (st != KV_OK) return st;
-    if (cache->cfg.mean_mode == KV_MEAN_CROSS_HEAD && a.geom.k_bits != 16 && a.geom.G > 64 && !use_mfma(cache, a))
-        return KV_E_UNSUPPORTED; // the cross-head mean tiles of a 128-token block do not fit the vector-ALU kernel's LDS
     a.q = (const uint16_t *)q;
     a.out = nullptr;
     hipStream_t s = (hipStream_t)stream;
@@ -885,7 +896,6 @@ kv_status kv_append_decode_attn_split(kv_cache *cache, int32_t layer, const void
     st = fill_decode(cache, layer, &a);
     const bool mfma = st == KV_OK && use_mfma(cache, a);
     if (st == KV_OK) st = bind_workspace(cache, &a, workspace, workspace_bytes);
-    if (st == KV_OK && c.mean_mode == KV_MEAN_CROSS_HEAD && a.geom.k_bits != 16 && a.geom.G > 64 && !mfma) st = KV_E_UNSUPPORTED;
     if (st == KV_OK && cache->decode_path == 2 && !mfma) st = KV_E_UNSUPPORTED;
     if (st != KV_OK || flush || !mfma) {
         restore();

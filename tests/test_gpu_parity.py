@@ -129,6 +129,23 @@ def test_mean_modes_and_query_groups(kv, oracle, mode, g):
     check_attention(gpu, orc, 0, synth.make_q(g, 2, Hkv * g, 128, BF16), BF16)
 
 
+def test_decode_path_used_reports_the_kernel_family(kv, oracle):
+    """Under the automatic choice a layer whose format the matrix-core kernels do not take runs on the
+    vector-ALU kernels; kv_decode_path_used says so, and forcing the matrix cores refuses such a layer."""
+    print("case path_used", flush=True)
+    gpu, orc = make_pair(kv, oracle, L=3, B=1, Hq=4, Hkv=1, T_max=128, dtype=BF16, k_bits=(4, 4, 16), v_bits=(4, 2, 16))
+    k, v = synth.make_kv(91, 1, 40, 1, 128, BF16)
+    for l in range(3):
+        append_both(gpu, orc, l, k, v, BF16)
+    want = (1, 1, 1) if parity_util.DECODE_PATH == 1 else (2, 1, 1)
+    assert tuple(kv.kv_decode_path_used(gpu.handle, l) for l in range(3)) == want
+    kv.kv_set_decode_path(gpu.handle, 2)
+    assert kv.kv_decode_path_used(gpu.handle, 0) == 2
+    with pytest.raises(kv.KVError) as e:
+        kv.kv_decode_path_used(gpu.handle, 1)
+    assert e.value.status == kv.KV_E_UNSUPPORTED
+
+
 def test_mixed_layer_map(kv, oracle):
     print("case mixed_layer_map", flush=True)
     bits = (8, 4, 2, 16, 2, 4)
@@ -471,8 +488,6 @@ def test_full_cache_shape_cross_head_sampled_units(kv, oracle, decode_path):
 def test_cross_head_mean(kv, oracle, bits, Hkv, g, G):
     """The paper's own centring: the mean over the kv heads, one binary16 row per token shared by
     all heads.  With a single kv head the deviation is zero and the cache recovers fp16 inputs."""
-    if G == 128 and parity_util.DECODE_PATH == 1:
-        pytest.skip("the vector-ALU kernels do not take the mean over the heads with blocks of 128 tokens")
     print("case cross_head bits=%d Hkv=%d g=%d G=%d" % (bits, Hkv, g, G), flush=True)
     T = 3 * G + 7
     gpu, orc = make_pair(kv, oracle, B=2, Hq=Hkv * g, Hkv=Hkv, T_max=4 * G, G=G, Gc=G, dtype=F16, mode=CROSS,
@@ -654,11 +669,15 @@ def test_degenerate_values(kv, oracle, bits, mode):
     gpu, orc = make_pair(kv, oracle, B=B, Hq=Hkv * g, Hkv=Hkv, T_max=6 * G, G=G, Gc=G, dtype=F16, mode=mode, k_bits=(bits,))
     append_both(gpu, orc, 0, kb, vb, F16, chunks=[40, T - 40])
     check_bytes(gpu, orc, 0)
-    # The matrix-core kernel carries q*scale and p*scale as 23-bit fixed point relative to the largest
-    # scale of a block / 64-token chunk: with a key outlier that draws all the weight onto a token
-    # whose value is 300, outputs reach +-200 and carry a relative error of about 1e-5.  The 2e-3
-    # bound is stated for the workloads' magnitudes (outputs of order 1, |x| up to about 20).
+    # Two bounds, one per kernel family (the error model of include/tadakv.h).  The vector-ALU kernels
+    # accumulate in binary32 throughout and stay within the stated 2e-3 on these inputs too (outputs reach
+    # +-300: that is 7e-6 relative).  The matrix-core kernels carry q*scale and p*scale as 23-bit fixed
+    # point relative to the largest such weight of a block / 64-token chunk, which costs up to
+    # 1.6e-5 x the largest range of a quantisation group: 2e-3 holds up to ranges of 128 (the workloads'
+    # are below 30), and the planted values of 300 make the bound 4.9e-3 here.
     q = synth.make_q(800 + bits, B, Hkv * g, 128, F16)
-    scale = max(1.0, float(np.max(np.abs(orc.attend(0, q)))) / 20.0)
-    err = check_attention(gpu, orc, 0, q, F16, tol=2e-3 * scale)
-    print("  attention max-abs error %.3e (bound %.1e)" % (err, 2e-3 * scale), flush=True)
+    assert kv.kv_decode_path_used(gpu.handle, 0) == (1 if parity_util.DECODE_PATH == 1 else 2)
+    group_range = 300.0 + 2 * 4.5  # the outlier against a group of N(0,1) values
+    bound = 2e-3 if parity_util.DECODE_PATH == 1 else max(2e-3, 1.6e-5 * group_range)
+    err = check_attention(gpu, orc, 0, q, F16, tol=bound)
+    print("  attention max-abs error %.3e (bound %.1e)" % (err, bound), flush=True)

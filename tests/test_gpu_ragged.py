@@ -49,8 +49,6 @@ def test_requests_join_step_and_leave(kv, oracle, path, bits, G, mode):
     takes its slot, decoding goes on."""
     import torch
 
-    if path == 1 and mode == CROSS and G == 128:
-        pytest.skip("the vector-ALU kernels do not take the mean over the heads with blocks of 128 tokens")
     print("case ragged path=%d bits=%d G=%d mode=%d" % (path, bits, G, mode), flush=True)
     parity_util.DECODE_PATH = path
     try:
