@@ -26,8 +26,10 @@
  *     GPU that is current when the call is made.  The library never allocates or frees device
  *     memory and never synchronises: work is enqueued on the given hipStream_t (passed as void*,
  *     NULL = the default stream) and ordered by it.
- *   - All arguments are validated on the host before anything is enqueued; on error nothing has
- *     been enqueued and the cache is unchanged.
+ *   - All arguments are validated on the host before anything is enqueued; on an argument error
+ *     nothing has been enqueued and the cache is unchanged.  KV_E_HIP (the runtime refused a launch:
+ *     kv_last_hip_error tells why) can come after earlier launches of the same call were enqueued:
+ *     the layer's contents are then undefined and the layer should be reset.
  *   - Sequence lengths are tracked on the host, per sequence.  The batch-wide calls move all
  *     sequences together; kv_quant_append_seq / kv_cache_reset_seq let one sequence join or leave
  *     (a new request taking over a slot of the batch: Sec. 3.3's buffer and blocks are per sequence),

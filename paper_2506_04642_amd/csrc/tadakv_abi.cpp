@@ -63,6 +63,7 @@ kv_status check_config(const kv_config *c)
         if (!bits_ok(c->k_bits[l]) || !bits_ok(c->v_bits[l])) return KV_E_BAD_BITS;
     for (int l = 0; l < c->n_layers; l++) // one raw side next to one packed side: no kernel yet
         if ((c->k_bits[l] == 16) != (c->v_bits[l] == 16)) return KV_E_UNSUPPORTED;
+    if ((long long)c->batch * c->n_kv_heads > 65535) return KV_E_UNSUPPORTED; // units index a launch grid's second dimension
     return KV_OK;
 }
 
@@ -506,6 +507,9 @@ static kv_status append_impl(kv_cache *cache, int32_t layer, int seq0, int n_seq
     for (int b = seq0; b < seq0 + n_seq; b++)
         if (takes(b) && (long long)cache->P(layer, b) + cache->R(layer, b) + n_new > c.max_tokens) return KV_E_CAPACITY;
     const int G = c.group_tokens, R = c.resid_cap;
+    // every limit of the launches below is checked here, before the first of them: an error leaves
+    // nothing enqueued (the kernels number their work items, two per block and unit, with an int)
+    if (((long long)R + n_new) / G * n_seq * c.n_kv_heads * 2 > 0x7FFFFFFFLL) return KV_E_UNSUPPORTED;
     hipStream_t s = (hipStream_t)stream;
     for (int b0 = seq0; b0 < seq0 + n_seq;) {
         if (!takes(b0)) {

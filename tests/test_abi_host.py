@@ -62,6 +62,7 @@ def test_sizes_follow_the_record_format(kv):
     (dict(k_bits=[4, 3]), "KV_E_BAD_BITS"),
     (dict(v_bits=[1, 2]), "KV_E_BAD_BITS"),
     (dict(k_bits=[16, 2]), "KV_E_UNSUPPORTED"),
+    (dict(batch=8192, n_kv_heads=8, n_q_heads=8), "KV_E_UNSUPPORTED"),  # more than 65535 (sequence, kv head) units
 ])
 def test_bad_configs_are_refused(kv, over, status):
     with pytest.raises(kv.KVError) as e:
