@@ -40,6 +40,8 @@ namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef float v4f __attribute__((ext_vector_type(4)));
 
 constexpr int kWavesPerBlock = 4;
 constexpr float kScoreScale = 0.08838834764831845f * 1.4426950408889634f; // log2(e) / sqrt(128)
@@ -198,6 +200,50 @@ __device__ __forceinline__ void stage_issue(const unsigned char *src, uint32_t *
     }
 }
 __device__ __forceinline__ void stage_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// waits until at most N of this wave's fetches (the youngest N) are outstanding
+// (the instruction through its builtin, not as inline assembly: the compiler then knows that only
+// the youngest N fetches can still be outstanding and does not add a full wait of its own in front
+// of the next LDS read that might touch a fetched buffer)
+template <int N> __device__ __forceinline__ void stage_wait_but()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a six-bit counter");
+    __builtin_amdgcn_s_waitcnt((N & 15) | 0x0070 | 0x0F00 | ((N >> 4) << 14)); // vmcnt(N), nothing else waited for
+    asm volatile("" ::: "memory");
+}
+// dense binary16 product on the matrix cores (v_mfma_f32_16x16x32_f16), operands as 16 raw bytes
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ v4f mfma_h(const uint4 &a, const u32x4 &b, v4f c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c, 0, 0, 0);
+}
+__device__ __forceinline__ v4f mfma_h(const u32x4 &a, const u32x4 &b, v4f c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c, 0, 0, 0);
+}
+// LDS reads issued by hand, for the buffers that direct-to-LDS fetches of other waves fill: the
+// compiler makes every LDS read that may touch such a buffer wait for ALL of the wave's outstanding
+// fetches (its own next chunk included), because it cannot see the barriers that order the two.
+// A result must not be used before lds_got has been given the same registers.
+template <int OFF> __device__ __forceinline__ void lds_get16(u32x4 &dst, uint32_t addr)
+{
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF));
+}
+template <int OFF> __device__ __forceinline__ void lds_get4(uint32_t &dst, uint32_t addr)
+{
+    asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF));
+}
+__device__ __forceinline__ void lds_got(u32x4 (&r)[8])
+{
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]), "+v"(r[5]), "+v"(r[6]), "+v"(r[7]));
+}
+__device__ __forceinline__ void lds_got(uint32_t (&r)[8])
+{
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]), "+v"(r[5]), "+v"(r[6]), "+v"(r[7]));
+}
+__device__ __forceinline__ uint32_t lds_addr(const void *p)
+{
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)p;
+}
 
 // Blocks of 128 tokens are read as two halves of 64: the pieces of half hf of the record at src
 // (its key codes, the block's key metadata, its runs of value codes -- 1 KiB per group of channel
@@ -246,15 +292,27 @@ template <> struct CodeOps<8> { // four words = one tile line; split into nibble
     }
 };
 
-// XH: cross-head mean.  The records carry no mean (MEAN is false); the mean's share of every
-// score comes in through a.xs, and the softmax weights go out through a.xp / a.xmc for the kernel
-// that adds the value mean plane's share to the partial outputs.
+// XH: cross-head mean.  The records carry no mean (MEAN is false).
+//   XH == 1: the mean's share of every score comes in through a.xs, and the softmax weights go out
+//            through a.xp / a.xmc for the kernel that adds the value mean plane's share to the
+//            partial outputs (two more kernels and a round trip of scores and weights).
+//   XH == 2: both mean terms inside this kernel.  A workgroup is one (sequence, split) with one wave
+//            per kv head (NW = n_kv_heads): every wave takes the same chunks, each of its own head's
+//            records, and the chunk's key-mean and value-mean tiles (64 tokens x 128 channels of
+//            binary16, shared by all kv heads: Eq. 1-2) are fetched once per workgroup into LDS.
+//            q . mean_K and sum_t p_t mean_V[t] are dense binary16 products on the matrix cores
+//            (queries narrowed to binary16: exact in its normal range; weights as a binary16 pair
+//            hi + lo; binary32 accumulation), the value tile transposed in LDS first so that the
+//            token index is the contraction index of the operand.
 // PG: paged placement (block slots through a table); the dense instances carry none of its state.
 // GS: tokens per block of the cache (32, 64, or 128 read as two halves of 64).
-template <int B, int GS, int GC, bool MEAN, int NW, int NHG, bool XH, bool PG>
+template <int B, int GS, int GC, bool MEAN, int NW, int NHG, int XH, bool PG>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2 && NHG == 1 && !XH) ? (PG ? 3 : 4) : 1, 8))) void decode_split_mfma_kernel(DecodeArgs a)
 {
     static_assert(!(XH && MEAN), "cross-head layers store no per-record mean");
+    constexpr bool XF = XH == 2; // both mean terms in this kernel, a wave per kv head
+    static_assert(!XF || (!PG && GS <= 64), "the fused cross-head form takes dense placement and blocks of 32 or 64 tokens");
+    constexpr int CW = XF ? 1 : NW;          // waves that share a unit's chunks
     constexpr bool H2 = GS == 128;         // a block is worked on as two halves
     constexpr int G = H2 ? 64 : GS;        // tokens per block as the arithmetic sees it
     constexpr int HB = GS / G;             // such blocks per block of the cache
@@ -274,10 +332,19 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
     constexpr int NGP = NG > 2 ? 2 : NG;
     constexpr int AK_DW = NHG * 512, AV_DW = NHG * NGP * 256;
     constexpr int OPER_DW = AK_DW > AV_DW ? AK_DW : AV_DW;
-    constexpr int WAVE_DW = STAGE_DW + OPER_DW;
+    constexpr int PT_DW = XF ? NHG * 256 : 0; // softmax weights of a chunk as binary16 hi / lo: [2][NHG][4 heads][64 tokens]
+    constexpr int WAVE_DW = STAGE_DW + OPER_DW + PT_DW;
+    // fused cross-head form, shared by the waves: key-mean tile [64 tokens][128] binary16 (16-byte pieces
+    // of a row swizzled by the row), value-mean tile as fetched, and transposed [128 channels][64 + 8 tokens]
+    constexpr int XK_DW = XF ? 4096 : 0, XV_DW = XF ? 4096 : 0, XT_DW = XF ? 128 * 72 / 2 : 0;
+    constexpr int XT_ROW = 144; // bytes per channel row of the transposed tile
     constexpr int LDS_DW = NW * WAVE_DW;
 
     __shared__ __attribute__((aligned(16))) uint32_t lds_all[LDS_DW];
+    // The shared tiles are objects of their own: the compiler makes an LDS access wait for every
+    // outstanding direct-to-LDS fetch that it cannot prove to go elsewhere, and fetches into another
+    // object are provably elsewhere (a wave's next chunk must stay in flight across these accesses).
+    __shared__ __attribute__((aligned(16))) uint32_t lds_xk[XF ? XK_DW : 1], lds_xv[XF ? XV_DW : 1], lds_xt[XF ? XT_DW : 1];
 
     const LayerGeom &gm = a.geom;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -287,9 +354,12 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
     uint32_t *stage = lds;                 // the chunk as it lies in the cache
     uint32_t *ak = lds + STAGE_DW, *av = ak;
 
-    const int sp = blockIdx.x, u = blockIdx.y;
+    const int sp = blockIdx.x;
+    const int u = XF ? (int)blockIdx.y * a.n_kv_heads + wave : (int)blockIdx.y;
     const int b = u / a.n_kv_heads, h = u % a.n_kv_heads;
     const int g = a.g;
+    const int cw0 = XF ? 0 : wave; // this wave's first local chunk
+    unsigned char *xk8 = (unsigned char *)lds_xk, *xv8 = (unsigned char *)lds_xv, *xt8 = (unsigned char *)lds_xt;
 
     // rows 4i+3 of the operands (the unused fourth limb) must read as zero
     for (int i = lane; i < OPER_DW; i += 64) ak[i] = 0u;
@@ -368,7 +438,41 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
 #pragma unroll
         for (int ph = 0; ph < 2; ph++) qraw[hg][ph] = *(const uint2 *)(qp + 32 * vq + 16 * ph + 4 * qa);
     }
-    if (wave < n_chunks) issue(wave);
+    if (cw0 < n_chunks) issue(cw0);
+    // fused cross-head form: a wave's share of the mean tiles of a chunk, 16 / NW fetches of 1 KiB
+    // (four rows of a tile) each.  The second block of a chunk that does not exist is read as the first.
+    auto mean_row_src = [&](int which, int blk0, int r) {
+        int blk = blk0 + r / G;
+        blk = blk < b_end ? blk : blk0;
+        // (dense placement: block slot = sequence * blocks per sequence + block)
+        return a.layer + gm.xmean_off + ((((long long)b * gm.NB + blk) * 2 + which) * G + r % G) * (kHeadDim * 2);
+    };
+    auto issue_kmean = [&](int ci) {
+        typedef const __attribute__((address_space(1))) void *gptr_t;
+        typedef __attribute__((address_space(3))) void *lptr_t;
+        const int blk0 = blk_of(ci);
+#pragma unroll
+        for (int jj = 0; jj < 16 / NW; jj++) {
+            const int j = wave + NW * jj, r = 4 * j + (lane >> 4);
+            const unsigned char *src = mean_row_src(0, blk0, r) + (((lane & 15) ^ (r & 7)) << 4);
+            __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(xk8 + j * 1024), 16, 0, 0);
+        }
+    };
+    auto issue_vmean = [&](int ci) {
+        typedef const __attribute__((address_space(1))) void *gptr_t;
+        typedef __attribute__((address_space(3))) void *lptr_t;
+        const int blk0 = blk_of(ci);
+#pragma unroll
+        for (int jj = 0; jj < 16 / NW; jj++) {
+            const int j = wave + NW * jj, r = 4 * j + (lane >> 4);
+            const unsigned char *src = mean_row_src(1, blk0, r) + ((lane & 15) << 4);
+            __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(xv8 + j * 1024), 16, 0, 0);
+        }
+    };
+    if (XF && cw0 < n_chunks) {
+        issue_kmean(cw0);
+        issue_vmean(cw0);
+    }
 
     // ---- query of heads 4*hg + row: this lane's eight channels, widened and as binary16 pairs
     float qf[NHG][2][4];      // q, widened (exact)
@@ -411,6 +515,29 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
     }
     wave_lds_fence();
 
+    // fused cross-head form: the queries as the A operand of the dense products -- operand row 4 r is
+    // head r of the head group (the other rows are zero), so that the lane that holds head r's scores
+    // of the quantised part (lane row r) finds the mean's share in the first result register
+    uint4 qop[NHG][4];
+    if (XF) {
+        _Float16 *qs16 = (_Float16 *)ak; // [4 NHG heads][128], through the operand scratch
+#pragma unroll
+        for (int hg = 0; hg < NHG; hg++)
+#pragma unroll
+            for (int ph = 0; ph < 2; ph++)
+#pragma unroll
+                for (int y = 0; y < 4; y++) qs16[(4 * hg + row) * 128 + 32 * vq + 16 * ph + 4 * qa + y] = (_Float16)qf[hg][ph][y];
+        wave_lds_fence();
+#pragma unroll
+        for (int hg = 0; hg < NHG; hg++)
+#pragma unroll
+            for (int ks = 0; ks < 4; ks++)
+                qop[hg][ks] = (n & 3) == 0 ? *(const uint4 *)(qs16 + (4 * hg + (n >> 2)) * 128 + 32 * ks + 8 * row) : uint4{0u, 0u, 0u, 0u};
+        wave_lds_fence();
+        for (int i = lane; i < NHG * 256; i += 64) ak[i] = 0u; // the scratch reads as zero again
+        wave_lds_fence();
+    }
+
     // cross-head mean: q . mean_K of this lane's tokens (16 k + n of a chunk), worked out by the
     // kernel that ran before this one; loaded one chunk ahead
     long long xq[NHG]; // query head index in the batch
@@ -429,15 +556,15 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
             const int head = 4 * hg + row;
             xq[hg] = (long long)b * a.n_q_heads + h * g + (head < g ? head : 0);
         }
-        if (wave < n_chunks) load_xs(wave);
+        if (XH == 1 && wave < n_chunks) load_xs(wave);
     }
 
     // Issue priority falls as a wave advances (quarters of its chunks).  By default the oldest wave
     // of a SIMD wins every arbitration, so the workgroups that arrived first on a compute unit run
     // ahead and leave the last ones to finish alone, at low occupancy and far below the memory
     // rate; with the laggards preferred, all waves end within about a quarter of each other.
-    const int my_iters = (n_chunks - wave + NW - 1) / NW;
-    for (int ci = wave, itn = 0; ci < n_chunks; ci += NW, itn++) {
+    const int my_iters = (n_chunks - cw0 + CW - 1) / CW;
+    for (int ci = cw0, itn = 0; ci < n_chunks; ci += CW, itn++) {
         if (B != 8) { // the 8-bit instance runs one wave per SIMD: nothing to arbitrate
             const int quart = itn * 4 / my_iters;
             if (quart == 0) __builtin_amdgcn_s_setprio(3);
@@ -455,7 +582,14 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
         const int tt_row = row % TPB;
 
         // ---- staged chunk -> registers
-        stage_wait();
+        if (XF) {
+            // this wave's chunk and its share of the key-mean tile have landed (the value-mean share,
+            // requested last, may still be on its way); then everybody's share has
+            stage_wait_but<16 / NW>();
+            __builtin_amdgcn_s_barrier();
+        } else {
+            stage_wait();
+        }
         uint4 kc[NKL], vc[NVL];
 #pragma unroll
         for (int i = 0; i < NKL; i++) {
@@ -504,7 +638,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
         // just issued included -- before it lets the registers of the previous request be reused.
         float xsv[NHG][4];
         long long xbase[NHG]; // this lane's first token of the chunk in xs / xp
-        if (XH) {
+        if (XH == 1) {
 #pragma unroll
             for (int hg = 0; hg < NHG; hg++) {
                 xbase[hg] = xq[hg] * a.tcap + (long long)blk0 * G;
@@ -515,7 +649,41 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
         }
         // every read of the staging buffer has returned: start fetching this wave's next chunk
         wave_lds_fence();
-        if (ci + NW < n_chunks) issue(ci + NW);
+        const bool more = ci + CW < n_chunks;
+        if (more) issue(ci + CW);
+        if (XF) {
+            // q . mean_K of token 16 k + n for head `row` of each head group: B operand = the token's
+            // row of the key-mean tile (16 bytes per 32-channel step)
+            uint32_t xka[4]; // this lane's piece of row n for each 32-channel step (16 k + n has n's low bits)
+#pragma unroll
+            for (int ks = 0; ks < 4; ks++) xka[ks] = lds_addr(xk8) + n * 256 + (((4 * ks + row) ^ (n & 7)) << 4);
+#pragma unroll
+            for (int kp = 0; kp < 2; kp++) { // token tiles 2 kp, 2 kp + 1
+                u32x4 bop[8];
+#pragma unroll
+                for (int ks = 0; ks < 4; ks++) {
+                    if (kp == 0) { lds_get16<0>(bop[ks], xka[ks]); lds_get16<4096>(bop[4 + ks], xka[ks]); }
+                    else { lds_get16<8192>(bop[ks], xka[ks]); lds_get16<12288>(bop[4 + ks], xka[ks]); }
+                }
+                lds_got(bop);
+#pragma unroll
+                for (int kk = 0; kk < 2; kk++) {
+                    v4f accm[NHG];
+#pragma unroll
+                    for (int hg = 0; hg < NHG; hg++) accm[hg] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                    for (int ks = 0; ks < 4; ks++)
+#pragma unroll
+                        for (int hg = 0; hg < NHG; hg++) accm[hg] = mfma_h(qop[hg][ks], bop[4 * kk + ks], accm[hg]);
+#pragma unroll
+                    for (int hg = 0; hg < NHG; hg++) xsv[hg][2 * kp + kk] = accm[hg][0];
+                }
+            }
+            // everybody is done with the key-mean tile: fetch the next chunk's
+            wave_lds_fence();
+            __builtin_amdgcn_s_barrier();
+            if (more) issue_kmean(ci + CW);
+        }
 
         // ---- key side, one block at a time (the operand scratch holds one block's operands):
         // q*scale as limbs -> LDS, zero/mean term, then the block's matrix products -> scores
@@ -619,12 +787,13 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
         const uint32_t vfix = opaque(0x80808080u - __float_as_uint(vmagic));
 
         // ---- softmax bookkeeping; zero and mean terms of the value side
-        float p[NHG][4], alpha[NHG], o_scale[NHG], psum_b[NHG][NBC];
+        float p[NHG][4], alpha[NHG], o_scale[NHG], psum_b[NHG][NBC], wcs[NHG];
 #pragma unroll
         for (int hg = 0; hg < NHG; hg++) {
             float wc, mc;
             softmax_chunk(s[hg], st[hg], p[hg], alpha[hg], wc, mc);
-            if (XH && 4 * hg + row < g) {
+            wcs[hg] = wc;
+            if (XH == 1 && 4 * hg + row < g) {
                 // the weights and the chunk's maximum, for the value mean plane's share
 #pragma unroll
                 for (int k = 0; k < 4; k++)
@@ -645,6 +814,98 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
 #pragma unroll
                 for (int k = bi * TPB; k < (bi + 1) * TPB; k++) t += p[hg][k];
                 psum_b[hg][bi] = MEAN ? row_sum(t) * wc : 0.0f;
+            }
+        }
+
+        // ---- fused cross-head form: sum_t p_t mean_V[t] for head `row` of each head group, channels
+        // 16 ct + n, relative to the chunk's maximum like p
+        float omean[NHG][8];
+        if (XF) {
+            // the weights as the A operand (row 4 r = head r, as with the queries), binary16 hi + lo
+            _Float16 *pt = (_Float16 *)(lds + STAGE_DW + OPER_DW);
+#pragma unroll
+            for (int hg = 0; hg < NHG; hg++)
+#pragma unroll
+                for (int k = 0; k < 4; k++) {
+                    const _Float16 hi = (_Float16)p[hg][k];
+                    pt[(hg * 4 + row) * 64 + 16 * k + n] = hi;
+                    pt[((NHG + hg) * 4 + row) * 64 + 16 * k + n] = (_Float16)(p[hg][k] - (float)hi);
+                }
+            wave_lds_fence();
+            // (read by hand like the shared tiles: the wave's next chunk is on its way into the same LDS object)
+            u32x4 pop[NHG][2][2];
+            {
+                const uint32_t pa = lds_addr(pt) + ((n >> 2) * 64 + 8 * row) * 2;
+                u32x4 raw[8];
+#pragma unroll
+                for (int i = 0; i < 8; i++) raw[i] = u32x4{0u, 0u, 0u, 0u};
+                lds_get16<0>(raw[0], pa); lds_get16<64>(raw[1], pa);                       // hi, head group 0
+                if (NHG == 2) { lds_get16<512>(raw[2], pa); lds_get16<576>(raw[3], pa); }  // hi, head group 1
+                lds_get16<NHG * 512>(raw[4], pa); lds_get16<NHG * 512 + 64>(raw[5], pa);   // lo, head group 0
+                if (NHG == 2) { lds_get16<1536>(raw[6], pa); lds_get16<1600>(raw[7], pa); }
+                lds_got(raw);
+                const bool on = (n & 3) == 0;
+#pragma unroll
+                for (int hg = 0; hg < NHG; hg++)
+#pragma unroll
+                    for (int hl = 0; hl < 2; hl++)
+#pragma unroll
+                        for (int ks = 0; ks < 2; ks++) pop[hg][hl][ks] = on ? raw[4 * hl + 2 * hg + ks] : u32x4{0u, 0u, 0u, 0u};
+            }
+            // this wave's share of the value-mean tile has landed (younger requests: the next chunk and
+            // the next key-mean share, if there is a next chunk), then everybody's; the tile is
+            // transposed by all waves together, and once that is done its buffer takes the next chunk's
+            if (more) stage_wait_but<(NBC == 1 ? (CB + 1023) / 1024 : ((CB + 1023) / 1024 < 2 * ((REC + 1023) / 1024) ? (CB + 1023) / 1024 : 2 * ((REC + 1023) / 1024))) + 16 / NW>();
+            else stage_wait_but<0>();
+            __builtin_amdgcn_s_barrier();
+            {
+                for (int i = tid; i < 512; i += 64 * NW) {
+                    const int cp = i & 63, t8 = i >> 6; // channels 2 cp, 2 cp + 1; tokens 8 t8 .. 8 t8 + 7
+                    uint32_t w[8];
+                    const uint32_t xva = lds_addr(xv8) + (8 * t8 * 64 + cp) * 4;
+                    lds_get4<0>(w[0], xva); lds_get4<256>(w[1], xva); lds_get4<512>(w[2], xva); lds_get4<768>(w[3], xva);
+                    lds_get4<1024>(w[4], xva); lds_get4<1280>(w[5], xva); lds_get4<1536>(w[6], xva); lds_get4<1792>(w[7], xva);
+                    lds_got(w);
+                    uint4 lo, hi;
+                    lo.x = (w[0] & 0xFFFFu) | (w[1] << 16); hi.x = (w[0] >> 16) | (w[1] & 0xFFFF0000u);
+                    lo.y = (w[2] & 0xFFFFu) | (w[3] << 16); hi.y = (w[2] >> 16) | (w[3] & 0xFFFF0000u);
+                    lo.z = (w[4] & 0xFFFFu) | (w[5] << 16); hi.z = (w[4] >> 16) | (w[5] & 0xFFFF0000u);
+                    lo.w = (w[6] & 0xFFFFu) | (w[7] << 16); hi.w = (w[6] >> 16) | (w[7] & 0xFFFF0000u);
+                    *(uint4 *)(xt8 + (2 * cp) * XT_ROW + t8 * 16) = lo;
+                    *(uint4 *)(xt8 + (2 * cp + 1) * XT_ROW + t8 * 16) = hi;
+                }
+            }
+            wave_lds_fence();
+            __builtin_amdgcn_s_barrier();
+            if (more) issue_vmean(ci + CW);
+            const uint32_t xta = lds_addr(xt8) + n * XT_ROW + 16 * row; // channel n of a tile, tokens 8 row .. + 7
+#pragma unroll
+            for (int cq = 0; cq < 2; cq++) { // channel tiles 4 cq .. 4 cq + 3
+                u32x4 bop[8]; // [tile][32-token step]
+                if (cq == 0) {
+                    lds_get16<0 * 16 * XT_ROW>(bop[0], xta); lds_get16<0 * 16 * XT_ROW + 64>(bop[1], xta);
+                    lds_get16<1 * 16 * XT_ROW>(bop[2], xta); lds_get16<1 * 16 * XT_ROW + 64>(bop[3], xta);
+                    lds_get16<2 * 16 * XT_ROW>(bop[4], xta); lds_get16<2 * 16 * XT_ROW + 64>(bop[5], xta);
+                    lds_get16<3 * 16 * XT_ROW>(bop[6], xta); lds_get16<3 * 16 * XT_ROW + 64>(bop[7], xta);
+                } else {
+                    lds_get16<4 * 16 * XT_ROW>(bop[0], xta); lds_get16<4 * 16 * XT_ROW + 64>(bop[1], xta);
+                    lds_get16<5 * 16 * XT_ROW>(bop[2], xta); lds_get16<5 * 16 * XT_ROW + 64>(bop[3], xta);
+                    lds_get16<6 * 16 * XT_ROW>(bop[4], xta); lds_get16<6 * 16 * XT_ROW + 64>(bop[5], xta);
+                    lds_get16<7 * 16 * XT_ROW>(bop[6], xta); lds_get16<7 * 16 * XT_ROW + 64>(bop[7], xta);
+                }
+                lds_got(bop);
+#pragma unroll
+                for (int c4 = 0; c4 < 4; c4++) {
+                    v4f om[NHG];
+#pragma unroll
+                    for (int hg = 0; hg < NHG; hg++) om[hg] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                    for (int ks = 0; ks < 2; ks++)
+#pragma unroll
+                        for (int hg = 0; hg < NHG; hg++) om[hg] = mfma_h(pop[hg][1][ks], bop[2 * c4 + ks], mfma_h(pop[hg][0][ks], bop[2 * c4 + ks], om[hg]));
+#pragma unroll
+                    for (int hg = 0; hg < NHG; hg++) omean[hg][4 * cq + c4] = om[hg][0] * wcs[hg];
+                }
             }
         }
 
@@ -703,6 +964,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
 #pragma unroll
                 for (int hg = 0; hg < NHG; hg++) {
                     float o = st[hg].O[ct] * alpha[hg] + limbs_to_float(acc[hg]) * o_scale[hg];
+                    if (XF) o += omean[hg][ct];
 #pragma unroll
                     for (int bi = 0; bi < NBC; bi++)
                         o += __half2float(__ushort_as_half(vmean[bi][ct])) * psum_b[hg][bi];
@@ -718,7 +980,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
     // unit's last chunk; wave w of the split takes tokens 8 w .. 8 w + 7 of a tile into its own
     // online-softmax state, with its own LDS region as scratch (no workgroup barrier)
     const int rt_first = (sp - chunks_total % ns + ns) % ns; // this split's first tile
-    if (rt_first * 32 + 8 * wave < r_seq) {
+    if (rt_first * 32 + 8 * cw0 < r_seq) {
         unsigned char *L = (unsigned char *)lds;
         constexpr int RS = 264;  // bytes per staged row (33 * 8): rows start in different banks
         constexpr int NH = 4 * NHG;
@@ -745,7 +1007,11 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
         // a token appended by this very call: read from the caller's rows and stored in the cache here
         const long long fresh_off = (long long)b * a.fresh_stride_b + (long long)h * a.fresh_stride_h;
         const int t_fresh = a.k_fresh ? r_seq - 1 : -1;
-        for (int t0 = rt_first * 32 + 8 * wave; t0 < r_seq; t0 += 32 * ns) {
+        // (fused cross-head form: the wave has the unit to itself and takes all four groups of a tile)
+        for (int tg8 = XF ? 0 : wave;; tg8 += XF ? 1 : 4) {
+            const int t0 = (rt_first + ns * (tg8 >> 2)) * 32 + 8 * (tg8 & 3);
+            if ((rt_first + ns * (tg8 >> 2)) * 32 >= r_seq) break;
+            if (t0 >= r_seq) continue;
             const int nt = r_seq - t0 < 8 ? r_seq - t0 : 8;
             wave_lds_fence();
             for (int i = lane; i < nt * 16; i += 64) {
@@ -845,15 +1111,16 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
         for (int ct = 0; ct < 8; ct++) mine[(hg * 10 + 2 + ct) * 64 + lane] = st[hg].O[ct];
     }
     __syncthreads();
-    if (wave == 0) {
-        const float *all = (const float *)lds_all;
+    if (XF || wave == 0) {
+        constexpr int MW = XF ? 1 : NW; // waves whose states make up the partial result
+        const float *all = (const float *)lds_all + (XF ? wave * WAVE_DW : 0);
 #pragma unroll
         for (int hg = 0; hg < NHG; hg++) {
             const int head = 4 * hg + row;
             if (head >= g) continue;
-            float Mw[NW], M = -INFINITY;
+            float Mw[MW], M = -INFINITY;
 #pragma unroll
-            for (int w = 0; w < NW; w++) {
+            for (int w = 0; w < MW; w++) {
                 Mw[w] = all[w * WAVE_DW + (hg * 10 + 0) * 64 + lane];
                 M = fmaxf(M, Mw[w]);
             }
@@ -861,7 +1128,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
 #pragma unroll
             for (int ct = 0; ct < 8; ct++) o[ct] = 0.0f;
 #pragma unroll
-            for (int w = 0; w < NW; w++) {
+            for (int w = 0; w < MW; w++) {
                 const float wt = Mw[w] == -INFINITY ? 0.0f : exp2f(Mw[w] - M); // a wave that saw no token
                 lsum += all[w * WAVE_DW + (hg * 10 + 1) * 64 + lane] * wt;
 #pragma unroll
@@ -879,7 +1146,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
 }
 
 // Resident workgroups of one instantiation on the whole device (0 if the query fails).
-template <int B, int G, int GC, bool MEAN, int NW, int NHG, bool XH, bool PG> int resident_blocks()
+template <int B, int G, int GC, bool MEAN, int NW, int NHG, int XH, bool PG> int resident_blocks()
 {
     static const int n = [] {
         int per_cu = 0, dev = 0, cus = 0;
@@ -893,11 +1160,12 @@ template <int B, int G, int GC, bool MEAN, int NW, int NHG, bool XH, bool PG> in
     return n;
 }
 
-template <int B, int G, int GC, bool MEAN, int NHG, bool XH, bool PG> hipError_t launch_inst(const DecodeArgs &a, hipStream_t s)
+// XH == 2 (both cross-head mean terms inside the kernel): one workgroup per (sequence, split), NW = kv heads.
+template <int B, int G, int GC, bool MEAN, int NW, int NHG, int XH, bool PG> hipError_t launch_inst(const DecodeArgs &a, hipStream_t s)
 {
-    constexpr int NW = kWavesPerBlock;
     if (!RecLayout<B, G, GC, MEAN>::matches(a.geom)) return hipErrorInvalidValue;
-    dim3 grid(a.n_splits, a.batch * a.n_kv_heads);
+    if (XH == 2 && a.n_kv_heads != NW) return hipErrorInvalidValue;
+    dim3 grid(a.n_splits, XH == 2 ? a.batch : a.batch * a.n_kv_heads);
     (void)hipGetLastError(); // drop any stale error left by earlier runtime calls of this thread
     hipLaunchKernelGGL((decode_split_mfma_kernel<B, G, GC, MEAN, NW, NHG, XH, PG>), grid, dim3(64 * NW), 0, s, a);
     return note_launch(hipGetLastError());
@@ -905,18 +1173,18 @@ template <int B, int G, int GC, bool MEAN, int NHG, bool XH, bool PG> hipError_t
 
 // Split count that puts every workgroup of the launch on the device at once (one "round"):
 // the kernel is a bandwidth stream, and a second, partly filled round only adds a tail.
-template <int B, int G, int GC, bool MEAN, int NHG, bool XH, bool PG> int plan_inst(const DecodeArgs &a)
+template <int B, int G, int GC, bool MEAN, int NW, int NHG, int XH, bool PG> int plan_inst(const DecodeArgs &a)
 {
-    constexpr int NW = kWavesPerBlock;
     const int slots = resident_blocks<B, G, GC, MEAN, NW, NHG, XH, PG>();
-    const int U = a.batch * a.n_kv_heads;
+    const int U = XH == 2 ? a.batch : a.batch * a.n_kv_heads; // workgroups per split
+    constexpr int CW = XH == 2 ? 1 : NW;                      // waves that share a unit's chunks
     const int chunks = (a.n_blocks * G + 63) / 64; // chunks of 64 tokens
     int ns = slots / U;
     // at least four chunks per wave, or the prologue dominates -- unless the launch is so small that
     // the device cannot be filled even then: such a launch is bound by latency, and the widest
     // spread (one chunk per wave) is the shortest
-    const bool small = (long long)U * chunks < (long long)slots * NW * 4;
-    const int cap = small ? (chunks + NW - 1) / NW : chunks / (NW * 4);
+    const bool small = (long long)U * chunks < (long long)slots * CW * 4;
+    const int cap = small ? (chunks + CW - 1) / CW : chunks / (CW * 4);
     if (ns > cap) ns = cap;
     if (ns > kMaxSplits) ns = kMaxSplits;
     if (ns < 1) ns = 1;
@@ -927,28 +1195,51 @@ template <int B, int G, int GC, bool MEAN, int NHG, bool XH, bool PG> int plan_i
 struct DoLaunch {
     hipStream_t s;
     hipError_t result = hipErrorInvalidValue;
-    template <int B, int G, int GC, bool MEAN, int NHG, bool XH, bool PG> void run(const DecodeArgs &a) { result = launch_inst<B, G, GC, MEAN, NHG, XH, PG>(a, s); }
+    template <int B, int G, int GC, bool MEAN, int NW, int NHG, int XH, bool PG> void run(const DecodeArgs &a) { result = launch_inst<B, G, GC, MEAN, NW, NHG, XH, PG>(a, s); }
 };
 struct DoPlan {
     int result = 1;
-    template <int B, int G, int GC, bool MEAN, int NHG, bool XH, bool PG> void run(const DecodeArgs &a) { result = plan_inst<B, G, GC, MEAN, NHG, XH, PG>(a); }
+    template <int B, int G, int GC, bool MEAN, int NW, int NHG, int XH, bool PG> void run(const DecodeArgs &a) { result = plan_inst<B, G, GC, MEAN, NW, NHG, XH, PG>(a); }
 };
 struct DoMatch {
     bool result = false;
-    template <int B, int G, int GC, bool MEAN, int NHG, bool XH, bool PG> void run(const DecodeArgs &a) { result = RecLayout<B, G, GC, MEAN>::matches(a.geom); }
+    template <int B, int G, int GC, bool MEAN, int NW, int NHG, int XH, bool PG> void run(const DecodeArgs &a) { result = RecLayout<B, G, GC, MEAN>::matches(a.geom); }
 };
+
+// Does the layer get the fused cross-head form (both mean terms inside the split kernel)?  It takes a
+// wave per kv head (4 or 8 of them), dense placement, blocks of 32 or 64 tokens, and 2- or 4-bit
+// codes (eight 8-bit chunk buffers and the mean tiles do not fit the LDS of a compute unit).
+bool xhead_fused_fmt(const DecodeArgs &a)
+{
+    const LayerGeom &g = a.geom;
+    if (g.k_bits == 4 && a.n_kv_heads == 8 && a.g > 4) return false; // two head groups' operand scratch on top: over the LDS limit
+    return g.mean_mode == 1 && !g.table && (g.G == 32 || g.G == 64) && (g.k_bits == 2 || g.k_bits == 4) &&
+           (a.n_kv_heads == 4 || a.n_kv_heads == 8);
+}
 
 template <int B, int G, int GC, bool PG, class F> void pick_mean_heads_pg(const DecodeArgs &a, F &f)
 {
+    constexpr int NW = kWavesPerBlock;
     const int mode = a.geom.mean_mode; // 0 per-channel block mean, 1 cross-head mean, 2 none
     if (a.g <= 4) {
-        if (mode == 0) f.template run<B, G, GC, true, 1, false, PG>(a);
-        else if (mode == 1) f.template run<B, G, GC, false, 1, true, PG>(a);
-        else f.template run<B, G, GC, false, 1, false, PG>(a);
+        if (mode == 0) f.template run<B, G, GC, true, NW, 1, 0, PG>(a);
+        else if (mode == 1) f.template run<B, G, GC, false, NW, 1, 1, PG>(a);
+        else f.template run<B, G, GC, false, NW, 1, 0, PG>(a);
     } else {
-        if (mode == 0) f.template run<B, G, GC, true, 2, false, PG>(a);
-        else if (mode == 1) f.template run<B, G, GC, false, 2, true, PG>(a);
-        else f.template run<B, G, GC, false, 2, false, PG>(a);
+        if (mode == 0) f.template run<B, G, GC, true, NW, 2, 0, PG>(a);
+        else if (mode == 1) f.template run<B, G, GC, false, NW, 2, 1, PG>(a);
+        else f.template run<B, G, GC, false, NW, 2, 0, PG>(a);
+    }
+}
+// the fused cross-head instances: a wave per kv head
+template <int B, int G, int GC, class F> void pick_fused(const DecodeArgs &a, F &f)
+{
+    if (a.n_kv_heads == 8) {
+        if (a.g <= 4) f.template run<B, G, GC, false, 8, 1, 2, false>(a);
+        else if constexpr (B == 2) f.template run<B, G, GC, false, 8, 2, 2, false>(a); // (4-bit: does not fit, see xhead_fused_fmt)
+    } else {
+        if (a.g <= 4) f.template run<B, G, GC, false, 4, 1, 2, false>(a);
+        else f.template run<B, G, GC, false, 4, 2, 2, false>(a);
     }
 }
 template <int B, int G, int GC, class F> void pick_mean_heads(const DecodeArgs &a, F &f)
@@ -960,6 +1251,16 @@ template <int B, int G, int GC, class F> void pick_mean_heads(const DecodeArgs &
 template <class F> void pick(const DecodeArgs &a, F &f)
 {
     const int bits = a.geom.k_bits;
+    if (xhead_fused_fmt(a)) {
+        if (a.geom.G == 32) {
+            if (bits == 2) pick_fused<2, 32, 32>(a, f);
+            else pick_fused<4, 32, 32>(a, f);
+        } else {
+            if (bits == 2) pick_fused<2, 64, 64>(a, f);
+            else pick_fused<4, 64, 64>(a, f);
+        }
+        return;
+    }
     if (a.geom.G == 32) {
         if (bits == 2) pick_mean_heads<2, 32, 32>(a, f);
         else if (bits == 4) pick_mean_heads<4, 32, 32>(a, f);
@@ -976,6 +1277,8 @@ template <class F> void pick(const DecodeArgs &a, F &f)
 }
 
 } // namespace
+
+bool xhead_fused(const DecodeArgs &a) { return decode_mfma_supported(a) && xhead_fused_fmt(a); }
 
 bool decode_mfma_supported(const DecodeArgs &a)
 {
@@ -1004,7 +1307,7 @@ int decode_mfma_splits(const DecodeArgs &a)
 hipError_t launch_decode_split_mfma(const DecodeArgs &a, hipStream_t s)
 {
     if (!decode_mfma_supported(a)) return hipErrorInvalidValue;
-    if (a.geom.mean_mode == 1) {
+    if (a.geom.mean_mode == 1 && !xhead_fused_fmt(a)) {
         if (!a.xs || !a.xp || !a.xmc) return hipErrorInvalidValue;
         const hipError_t e = launch_xhead_scores(a, s);
         if (e != hipSuccess) return e;

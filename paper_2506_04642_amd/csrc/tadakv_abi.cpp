@@ -272,7 +272,7 @@ size_t xhead_start(const kv_cache *k, const DecodeArgs &a)
 size_t launch_workspace_need(const kv_cache *k, const DecodeArgs &a)
 {
     const kv_config &c = k->cfg;
-    const bool xhead = c.mean_mode == KV_MEAN_CROSS_HEAD && a.geom.k_bits != 16 && use_mfma(k, a);
+    const bool xhead = c.mean_mode == KV_MEAN_CROSS_HEAD && a.geom.k_bits != 16 && use_mfma(k, a) && !xhead_fused(a);
     return xhead ? xhead_start(k, a) + (k->xhead_bytes - k->xhead_off) : workspace_need(c, a.n_splits);
 }
 
@@ -280,7 +280,9 @@ size_t launch_workspace_need(const kv_cache *k, const DecodeArgs &a)
 kv_status bind_workspace(const kv_cache *k, DecodeArgs *a, void *workspace, size_t workspace_bytes)
 {
     const kv_config &c = k->cfg;
-    const bool xhead = c.mean_mode == KV_MEAN_CROSS_HEAD && a->geom.k_bits != 16 && use_mfma(k, *a);
+    // cross-head mean on the matrix-core path: the dense mean terms go through the workspace unless the
+    // layer's format has the form of the split kernel that takes them in
+    const bool xhead = c.mean_mode == KV_MEAN_CROSS_HEAD && a->geom.k_bits != 16 && use_mfma(k, *a) && !xhead_fused(*a);
     if (!workspace || workspace_bytes < launch_workspace_need(k, *a)) return KV_E_WORKSPACE;
     if ((uintptr_t)workspace % 256) return KV_E_ALIGN;
     a->ws = (float *)workspace;

@@ -139,6 +139,7 @@ hipError_t launch_compressv(const ProjectArgs &p, hipStream_t s);
 hipError_t launch_decode_split_valu(const DecodeArgs &a, hipStream_t s);
 hipError_t launch_decode_split_mfma(const DecodeArgs &a, hipStream_t s);
 bool decode_mfma_supported(const DecodeArgs &a);
+bool xhead_fused(const DecodeArgs &a); // cross-head mean: both mean terms inside the matrix-core split kernel
 int decode_mfma_splits(const DecodeArgs &a); // preferred split count of the matrix-core kernel
 hipError_t launch_decode_merge(const DecodeArgs &a, hipStream_t s);
 hipError_t launch_dequant(const DequantArgs &q, hipStream_t s);

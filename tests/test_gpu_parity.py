@@ -540,7 +540,8 @@ def test_cross_head_mean_with_a_forced_split_count(kv, oracle, decode_path):
 
     print("case cross_head_forced_splits", flush=True)
     B, Hkv, g, T = 16, 8, 4, 128 * 32 + 5
-    gpu, orc = make_pair(kv, oracle, B=B, Hq=Hkv * g, Hkv=Hkv, T_max=130 * 32, dtype=BF16, mode=CROSS, k_bits=(4,))
+    # (8-bit: the widths whose dense mean terms run as kernels of their own and pass through the workspace)
+    gpu, orc = make_pair(kv, oracle, B=B, Hq=Hkv * g, Hkv=Hkv, T_max=130 * 32, dtype=BF16, mode=CROSS, k_bits=(8,))
     k, v = synth.make_kv(611, B, T, Hkv, 128, BF16)
     append_both(gpu, orc, 0, k, v, BF16)
     q = synth.make_q(611, B, Hkv * g, 128, BF16)
