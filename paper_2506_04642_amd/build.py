@@ -18,8 +18,9 @@ UNITS = [
     ("quant_append.hip", ["-ffp-contract=off"]),
     ("compressv.hip", ["-ffp-contract=off"]),
     ("decode_valu.hip", []),
-    # matrix-instruction results go straight to ordinary vector registers
-    ("decode_mfma.hip", ["-mllvm", "-amdgpu-mfma-vgpr-form"]),
+    # matrix-instruction results go straight to ordinary vector registers; the direct-to-LDS fetches
+    # are issued by hand and name M0 as clobbered, which the compiler remarks on at every use
+    ("decode_mfma.hip", ["-mllvm", "-amdgpu-mfma-vgpr-form", "-Wno-inline-asm"]),
     ("xhead_dense.hip", []),
     ("stream_probe.hip", []),
 ]

@@ -179,72 +179,73 @@ template <int B, int G, int GC, bool MEAN> struct RecLayout {
 
 // Fetch NBYTES (multiple of 16) from src to the LDS address dst; both wave-uniform.  Lane l moves
 // the 16-byte pieces l, l + 64, ...; completion is tracked by the vector-memory counter.
+// The fetches are issued by hand (direct-to-LDS loads: lane l's 16 bytes land at M0 + offset + 16 l,
+// the offset applies to the global and to the LDS address alike).  The compiler does not see them:
+// through the builtin it makes every LDS access that it cannot tell apart from a fetch's destination
+// wait for ALL outstanding fetches, the wave's next chunk included, which is exactly the overlap
+// this kernel lives on.  Every read of a staged buffer therefore follows a wait written here
+// (stage_wait, stage_wait_but).
+template <int OFF> __device__ __forceinline__ void stage_fetch16(const unsigned char *gp, uint32_t lds)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off offset:%2"
+                 : : "s"(lds), "v"(gp), "n"(OFF) : "memory", "m0");
+}
 template <int NBYTES>
 __device__ __forceinline__ void stage_issue(const unsigned char *src, uint32_t *dst, int lane)
 {
-    typedef const __attribute__((address_space(1))) void *gptr_t;
-    typedef __attribute__((address_space(3))) void *lptr_t;
 #pragma unroll
     for (int base = 0; base < NBYTES; base += 4096) {
-        gptr_t gp = (gptr_t)(src + base + lane * 16);
-        lptr_t lp = (lptr_t)(dst + base / 4);
-        // the immediate offset applies to the global and to the LDS address alike
-        if (base + 0 * 1024 + 1024 <= NBYTES) __builtin_amdgcn_global_load_lds(gp, lp, 16, 0, 0);
-        else if (base + 0 * 1024 < NBYTES && base + lane * 16 < NBYTES) __builtin_amdgcn_global_load_lds(gp, lp, 16, 0, 0);
-        if (base + 1 * 1024 + 1024 <= NBYTES) __builtin_amdgcn_global_load_lds(gp, lp, 16, 1024, 0);
-        else if (base + 1 * 1024 < NBYTES && base + 1024 + lane * 16 < NBYTES) __builtin_amdgcn_global_load_lds(gp, lp, 16, 1024, 0);
-        if (base + 2 * 1024 + 1024 <= NBYTES) __builtin_amdgcn_global_load_lds(gp, lp, 16, 2048, 0);
-        else if (base + 2 * 1024 < NBYTES && base + 2048 + lane * 16 < NBYTES) __builtin_amdgcn_global_load_lds(gp, lp, 16, 2048, 0);
-        if (base + 3 * 1024 + 1024 <= NBYTES) __builtin_amdgcn_global_load_lds(gp, lp, 16, 3072, 0);
-        else if (base + 3 * 1024 < NBYTES && base + 3072 + lane * 16 < NBYTES) __builtin_amdgcn_global_load_lds(gp, lp, 16, 3072, 0);
+        const unsigned char *gp = src + base + lane * 16;
+        const uint32_t lp = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)(dst + base / 4));
+        if (base + 0 * 1024 + 1024 <= NBYTES) stage_fetch16<0>(gp, lp);
+        else if (base + 0 * 1024 < NBYTES && base + lane * 16 < NBYTES) stage_fetch16<0>(gp, lp);
+        if (base + 1 * 1024 + 1024 <= NBYTES) stage_fetch16<1024>(gp, lp);
+        else if (base + 1 * 1024 < NBYTES && base + 1024 + lane * 16 < NBYTES) stage_fetch16<1024>(gp, lp);
+        if (base + 2 * 1024 + 1024 <= NBYTES) stage_fetch16<2048>(gp, lp);
+        else if (base + 2 * 1024 < NBYTES && base + 2048 + lane * 16 < NBYTES) stage_fetch16<2048>(gp, lp);
+        if (base + 3 * 1024 + 1024 <= NBYTES) stage_fetch16<3072>(gp, lp);
+        else if (base + 3 * 1024 < NBYTES && base + 3072 + lane * 16 < NBYTES) stage_fetch16<3072>(gp, lp);
     }
 }
 __device__ __forceinline__ void stage_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
-// waits until at most N of this wave's fetches (the youngest N) are outstanding
-// (the instruction through its builtin, not as inline assembly: the compiler then knows that only
-// the youngest N fetches can still be outstanding and does not add a full wait of its own in front
-// of the next LDS read that might touch a fetched buffer)
-template <int N> __device__ __forceinline__ void stage_wait_but()
-{
-    static_assert(N >= 0 && N < 64, "vmcnt is a six-bit counter");
-    __builtin_amdgcn_s_waitcnt((N & 15) | 0x0070 | 0x0F00 | ((N >> 4) << 14)); // vmcnt(N), nothing else waited for
-    asm volatile("" ::: "memory");
-}
 // dense binary16 product on the matrix cores (v_mfma_f32_16x16x32_f16), operands as 16 raw bytes
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ v4f mfma_h(const uint4 &a, const u32x4 &b, v4f c)
-{
-    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c, 0, 0, 0);
-}
 __device__ __forceinline__ v4f mfma_h(const u32x4 &a, const u32x4 &b, v4f c)
 {
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c, 0, 0, 0);
 }
-// LDS reads issued by hand, for the buffers that direct-to-LDS fetches of other waves fill: the
-// compiler makes every LDS read that may touch such a buffer wait for ALL of the wave's outstanding
-// fetches (its own next chunk included), because it cannot see the barriers that order the two.
-// A result must not be used before lds_got has been given the same registers.
+// LDS reads issued by hand, for data read while a direct-to-LDS fetch is outstanding: the compiler
+// makes an LDS read that it cannot tell apart from the fetch's destination wait for ALL of the wave's
+// outstanding fetches (its next chunk included).  A result must not be used before lds_wait and then
+// lds_got of the register.
 template <int OFF> __device__ __forceinline__ void lds_get16(u32x4 &dst, uint32_t addr)
 {
     asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF));
 }
-template <int OFF> __device__ __forceinline__ void lds_get4(uint32_t &dst, uint32_t addr)
-{
-    asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF));
-}
-__device__ __forceinline__ void lds_got(u32x4 (&r)[8])
-{
-    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]), "+v"(r[5]), "+v"(r[6]), "+v"(r[7]));
-}
-__device__ __forceinline__ void lds_got(uint32_t (&r)[8])
-{
-    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]), "+v"(r[5]), "+v"(r[6]), "+v"(r[7]));
-}
+__device__ __forceinline__ void lds_wait() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+__device__ __forceinline__ void lds_got(u32x4 &r) { asm volatile("" : "+v"(r)); }
 __device__ __forceinline__ uint32_t lds_addr(const void *p)
 {
     return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)p;
 }
-
+// Global loads issued by hand, for data wanted long after younger fetches have been issued under a
+// condition: the compiler, which has to assume either outcome of the condition, would wait for
+// every outstanding fetch before the first use.  A result must not be used before glb_wait_but
+// (N = the number of fetches issued since, which may stay outstanding) and then glb_got of every
+// register.
+__device__ __forceinline__ void glb_get16(u32x4 &dst, const void *p)
+{
+    asm volatile("global_load_dwordx4 %0, %1, off ; by hand" : "=v"(dst) : "v"(p));
+}
+// (the wait and the hand-over of the registers are separate so that a wait chosen by a condition
+// is followed by ONE hand-over per register: registers handed over on either side of a branch would
+// be copied into common ones ahead of the branch, that is, before the data is there)
+template <int N> __device__ __forceinline__ void glb_wait_but()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a six-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+__device__ __forceinline__ void glb_got(u32x4 &r) { asm volatile("; by hand %0" : "+v"(r) : : "memory"); }
 // Blocks of 128 tokens are read as two halves of 64: the pieces of half hf of the record at src
 // (its key codes, the block's key metadata, its runs of value codes -- 1 KiB per group of channel
 // tiles --, its value metadata, the block's value mean) are placed so that the staging buffer
@@ -275,6 +276,22 @@ template <> struct CodeOps<4> { // two words = one tile line of 16 codes
         return v4i{(int)(w0 & kM4), (int)((w0 >> 4) & kM4), (int)(w1 & kM4), (int)((w1 >> 4) & kM4)};
     }
 };
+// Phase clocks (a build with -DTADA_PHASE_CLOCK only; the library proper carries none of it): every
+// wave sums the cycles between the marks of the main loop; kv_debug_phase_clocks hands the sums out.
+#ifdef TADA_PHASE_CLOCK
+__device__ unsigned long long tada_phase_clk[16];
+#define PHASE_INIT unsigned long long pclk_[14] = {}; unsigned long long plast_ = __builtin_readcyclecounter(); int piter_ = 0;
+#define PHASE(i) { const unsigned long long t_ = __builtin_readcyclecounter(); pclk_[i] += t_ - plast_; plast_ = t_; }
+#define PHASE_ITER piter_++;
+#define PHASE_DONE if (lane == 0) { for (int i_ = 0; i_ < 14; i_++) atomicAdd(&tada_phase_clk[i_], pclk_[i_]); \
+                                    atomicAdd(&tada_phase_clk[14], (unsigned long long)piter_); atomicAdd(&tada_phase_clk[15], 1ull); }
+#else
+#define PHASE_INIT
+#define PHASE(i)
+#define PHASE_ITER
+#define PHASE_DONE
+#endif
+
 template <> struct CodeOps<2> { // one word = one tile line
     static __device__ __forceinline__ v4i line(uint32_t w)
     {
@@ -302,8 +319,8 @@ template <> struct CodeOps<8> { // four words = one tile line; split into nibble
 //            binary16, shared by all kv heads: Eq. 1-2) are fetched once per workgroup into LDS.
 //            q . mean_K and sum_t p_t mean_V[t] are dense binary16 products on the matrix cores
 //            (queries narrowed to binary16: exact in its normal range; weights as a binary16 pair
-//            hi + lo; binary32 accumulation), the value tile transposed in LDS first so that the
-//            token index is the contraction index of the operand.
+//            hi + lo; binary32 accumulation); the value tile goes through registers and is written
+//            into LDS transposed, so that the token index is the contraction index of the operand.
 // PG: paged placement (block slots through a table); the dense instances carry none of its state.
 // GS: tokens per block of the cache (32, 64, or 128 read as two halves of 64).
 template <int B, int GS, int GC, bool MEAN, int NW, int NHG, int XH, bool PG>
@@ -332,19 +349,23 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
     constexpr int NGP = NG > 2 ? 2 : NG;
     constexpr int AK_DW = NHG * 512, AV_DW = NHG * NGP * 256;
     constexpr int OPER_DW = AK_DW > AV_DW ? AK_DW : AV_DW;
-    constexpr int PT_DW = XF ? NHG * 256 : 0; // softmax weights of a chunk as binary16 hi / lo: [2][NHG][4 heads][64 tokens]
-    constexpr int WAVE_DW = STAGE_DW + OPER_DW + PT_DW;
-    // fused cross-head form, shared by the waves: key-mean tile [64 tokens][128] binary16 (16-byte pieces
-    // of a row swizzled by the row), value-mean tile as fetched, and transposed [128 channels][64 + 8 tokens]
-    constexpr int XK_DW = XF ? 4096 : 0, XV_DW = XF ? 4096 : 0, XT_DW = XF ? 128 * 72 / 2 : 0;
-    constexpr int XT_ROW = 144; // bytes per channel row of the transposed tile
+    constexpr int WAVE_DW = STAGE_DW + OPER_DW;
+    // fused cross-head form: the workgroup's query heads, 4 NHG per kv head (wave), as 16-head blocks
+    constexpr int HP = 4 * NHG, HQP = NW * HP, NRB = XF ? HQP / 16 : 1;
+    constexpr int NCT = XF ? 8 / NW : 1;    // channel tiles of the value-mean product per wave
+    constexpr int PB_ROW = 144;             // bytes of a row of 64 binary16 (+ 8 of padding)
+    // shared by the waves, all [parity of the chunk]...: scores q . mean_K [head][64 tokens] binary32
+    // (the 16-token groups of a row rotated by the head so that writers and readers spread over the
+    // banks), softmax weights [hi | lo][head][64 + 8] binary16, rescale factors [head]; per wave: its
+    // strip of the value-mean tile, transposed, [NCT][16 channels][64 + 8 tokens] binary16
+    constexpr int XS_DW = XF ? 2 * HQP * 64 : 0, PB_DW = XF ? 2 * 2 * HQP * PB_ROW / 4 : 0, AL_DW = XF ? 2 * HQP : 0;
+    constexpr int VT_DW = XF ? NCT * 16 * PB_ROW / 4 : 0;
     constexpr int LDS_DW = NW * WAVE_DW;
 
     __shared__ __attribute__((aligned(16))) uint32_t lds_all[LDS_DW];
-    // The shared tiles are objects of their own: the compiler makes an LDS access wait for every
-    // outstanding direct-to-LDS fetch that it cannot prove to go elsewhere, and fetches into another
-    // object are provably elsewhere (a wave's next chunk must stay in flight across these accesses).
-    __shared__ __attribute__((aligned(16))) uint32_t lds_xk[XF ? XK_DW : 1], lds_xv[XF ? XV_DW : 1], lds_xt[XF ? XT_DW : 1];
+    // the exchange buffers of the fused cross-head form
+    __shared__ __attribute__((aligned(16))) uint32_t lds_xs[XF ? XS_DW : 1], lds_pb[XF ? PB_DW : 1], lds_al[XF ? AL_DW : 1],
+        lds_vt[XF ? NW * VT_DW : 1];
 
     const LayerGeom &gm = a.geom;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -359,7 +380,6 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
     const int b = u / a.n_kv_heads, h = u % a.n_kv_heads;
     const int g = a.g;
     const int cw0 = XF ? 0 : wave; // this wave's first local chunk
-    unsigned char *xk8 = (unsigned char *)lds_xk, *xv8 = (unsigned char *)lds_xv, *xt8 = (unsigned char *)lds_xt;
 
     // rows 4i+3 of the operands (the unused fourth limb) must read as zero
     for (int i = lane; i < OPER_DW; i += 64) ak[i] = 0u;
@@ -439,40 +459,14 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
         for (int ph = 0; ph < 2; ph++) qraw[hg][ph] = *(const uint2 *)(qp + 32 * vq + 16 * ph + 4 * qa);
     }
     if (cw0 < n_chunks) issue(cw0);
-    // fused cross-head form: a wave's share of the mean tiles of a chunk, 16 / NW fetches of 1 KiB
-    // (four rows of a tile) each.  The second block of a chunk that does not exist is read as the first.
+    // fused cross-head form: row r (token of the chunk that starts with block blk0) of the key (which
+    // = 0) or value (1) mean plane.  The second block of a chunk that does not exist is read as the first.
     auto mean_row_src = [&](int which, int blk0, int r) {
         int blk = blk0 + r / G;
         blk = blk < b_end ? blk : blk0;
         // (dense placement: block slot = sequence * blocks per sequence + block)
         return a.layer + gm.xmean_off + ((((long long)b * gm.NB + blk) * 2 + which) * G + r % G) * (kHeadDim * 2);
     };
-    auto issue_kmean = [&](int ci) {
-        typedef const __attribute__((address_space(1))) void *gptr_t;
-        typedef __attribute__((address_space(3))) void *lptr_t;
-        const int blk0 = blk_of(ci);
-#pragma unroll
-        for (int jj = 0; jj < 16 / NW; jj++) {
-            const int j = wave + NW * jj, r = 4 * j + (lane >> 4);
-            const unsigned char *src = mean_row_src(0, blk0, r) + (((lane & 15) ^ (r & 7)) << 4);
-            __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(xk8 + j * 1024), 16, 0, 0);
-        }
-    };
-    auto issue_vmean = [&](int ci) {
-        typedef const __attribute__((address_space(1))) void *gptr_t;
-        typedef __attribute__((address_space(3))) void *lptr_t;
-        const int blk0 = blk_of(ci);
-#pragma unroll
-        for (int jj = 0; jj < 16 / NW; jj++) {
-            const int j = wave + NW * jj, r = 4 * j + (lane >> 4);
-            const unsigned char *src = mean_row_src(1, blk0, r) + ((lane & 15) << 4);
-            __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(xv8 + j * 1024), 16, 0, 0);
-        }
-    };
-    if (XF && cw0 < n_chunks) {
-        issue_kmean(cw0);
-        issue_vmean(cw0);
-    }
 
     // ---- query of heads 4*hg + row: this lane's eight channels, widened and as binary16 pairs
     float qf[NHG][2][4];      // q, widened (exact)
@@ -515,27 +509,79 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
     }
     wave_lds_fence();
 
-    // fused cross-head form: the queries as the A operand of the dense products -- operand row 4 r is
-    // head r of the head group (the other rows are zero), so that the lane that holds head r's scores
-    // of the quantised part (lane row r) finds the mean's share in the first result register
-    uint4 qop[NHG][4];
+    // ---- fused cross-head form.  The mean terms are dense products that the whole workgroup shares:
+    // q . mean_K for all its query heads, 16 heads x 16 tokens per matrix product, dealt to the waves by
+    // (head block, token tile) -- wave w takes the pairs w NHG + e --, and sum_t p_t mean_V[t] by
+    // channel tile, every wave for all heads.  The waves exchange the small operands and results
+    // (scores, weights, rescale factors) through LDS, with one barrier per chunk: the scores of
+    // chunk i + 1 are worked out during chunk i, and every exchange buffer exists once per parity.
+    u32x4 qA[NHG][4];  // A operands of the score products: row = head of the block, binary16
+    int xs_w[NHG], xs_t0[NHG], xs_r[NHG], xs_rot[NHG]; // where this lane's scores are written and read (float index)
+    int km_row[NHG];   // this lane's row (token of the chunk) of the key-mean tile as B operand
+    v4f accv[NRB][NCT]; // sum_t p_t mean_V[t] (times 2^8) of heads 16 rb + 4 row + j, channel 16 (w NCT + c) + n
+    auto kmean_fetch = [&](u32x4 (&kb)[NHG][4], int blk0) {
+#pragma unroll
+        for (int e = 0; e < NHG; e++)
+#pragma unroll
+            for (int ks = 0; ks < 4; ks++) glb_get16(kb[e][ks], mean_row_src(0, blk0, km_row[e]) + 64 * ks + 16 * row);
+    };
+    auto kmean_scores = [&](const u32x4 (&kb)[NHG][4], int par) {
+        float *xs = (float *)lds_xs + par * (HQP * 64);
+#pragma unroll
+        for (int e = 0; e < NHG; e++) {
+            v4f acc = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int ks = 0; ks < 4; ks++) acc = mfma_h(qA[e][ks], kb[e][ks], acc);
+#pragma unroll
+            for (int j = 0; j < 4; j++) xs[xs_w[e] + j * 64 + (((xs_t0[e] + j) & 3) << 4)] = acc[j];
+        }
+    };
     if (XF) {
-        _Float16 *qs16 = (_Float16 *)ak; // [4 NHG heads][128], through the operand scratch
 #pragma unroll
-        for (int hg = 0; hg < NHG; hg++)
+        for (int e = 0; e < NHG; e++) {
+            const int pj = wave * NHG + e, rb = pj >> 2, tt = pj & 3; // head block, token tile
+            const int hp = 16 * rb + n, hk = hp / HP, local = hp % HP; // A row n: kv head, head of its group
+            const uint16_t *qp = a.q + ((long long)b * a.n_q_heads + hk * g + (local < g ? local : 0)) * kHeadDim + 8 * row;
 #pragma unroll
-            for (int ph = 0; ph < 2; ph++)
+            for (int ks = 0; ks < 4; ks++) {
+                const uint4 w = *(const uint4 *)(qp + 32 * ks);
+                const uint32_t wv[4] = {w.x, w.y, w.z, w.w};
+                uint32_t o[4];
 #pragma unroll
-                for (int y = 0; y < 4; y++) qs16[(4 * hg + row) * 128 + 32 * vq + 16 * ph + 4 * qa + y] = (_Float16)qf[hg][ph][y];
+                for (int k = 0; k < 4; k++) {
+                    const _Float16 lo = (_Float16)widen16((uint16_t)(wv[k] & 0xFFFFu), gm.dtype);
+                    const _Float16 hi = (_Float16)widen16((uint16_t)(wv[k] >> 16), gm.dtype);
+                    o[k] = local < g ? (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16) : 0u;
+                }
+                qA[e][ks] = u32x4{o[0], o[1], o[2], o[3]};
+            }
+            km_row[e] = 16 * tt + n;
+            // result register j: head 16 rb + 4 row + j, token 16 tt + n; the 16-token groups of head
+            // hp's row are rotated by (hp % 4 + hp / 4) % 4
+            xs_w[e] = (16 * rb + 4 * row) * 64 + n;
+            xs_t0[e] = (tt + row) & 3;
+        }
+#pragma unroll
+        for (int hg = 0; hg < NHG; hg++) {
+            xs_r[hg] = (wave * HP + 4 * hg + row) * 64 + n;
+            xs_rot[hg] = (row + wave * NHG + hg) & 3;
+        }
+#pragma unroll
+        for (int rb = 0; rb < NRB; rb++)
+#pragma unroll
+            for (int c = 0; c < NCT; c++) accv[rb][c] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+        if (n_chunks > 0) { // the scores of the first chunk
+            u32x4 kb[NHG][4];
+            kmean_fetch(kb, blk_of(0));
+            glb_wait_but<0>();
+#pragma unroll
+            for (int e = 0; e < NHG; e++)
+#pragma unroll
+                for (int ks = 0; ks < 4; ks++) glb_got(kb[e][ks]);
+            kmean_scores(kb, 0);
+        }
         wave_lds_fence();
-#pragma unroll
-        for (int hg = 0; hg < NHG; hg++)
-#pragma unroll
-            for (int ks = 0; ks < 4; ks++)
-                qop[hg][ks] = (n & 3) == 0 ? *(const uint4 *)(qs16 + (4 * hg + (n >> 2)) * 128 + 32 * ks + 8 * row) : uint4{0u, 0u, 0u, 0u};
-        wave_lds_fence();
-        for (int i = lane; i < NHG * 256; i += 64) ak[i] = 0u; // the scratch reads as zero again
-        wave_lds_fence();
+        __builtin_amdgcn_s_barrier();
     }
 
     // cross-head mean: q . mean_K of this lane's tokens (16 k + n of a chunk), worked out by the
@@ -564,7 +610,9 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
     // ahead and leave the last ones to finish alone, at low occupancy and far below the memory
     // rate; with the laggards preferred, all waves end within about a quarter of each other.
     const int my_iters = (n_chunks - cw0 + CW - 1) / CW;
+    PHASE_INIT
     for (int ci = cw0, itn = 0; ci < n_chunks; ci += CW, itn++) {
+        PHASE_ITER
         if (B != 8) { // the 8-bit instance runs one wave per SIMD: nothing to arbitrate
             const int quart = itn * 4 / my_iters;
             if (quart == 0) __builtin_amdgcn_s_setprio(3);
@@ -582,14 +630,25 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
         const int tt_row = row % TPB;
 
         // ---- staged chunk -> registers
+        PHASE(0)
+        const bool more = ci + CW < n_chunks;
+        const int par = itn & 1;
+        u32x4 kmB[NHG][4], vmp[NCT][2]; // fused cross-head form: operands fetched by hand
+        stage_wait(); // this wave's chunk has landed
         if (XF) {
-            // this wave's chunk and its share of the key-mean tile have landed (the value-mean share,
-            // requested last, may still be on its way); then everybody's share has
-            stage_wait_but<16 / NW>();
-            __builtin_amdgcn_s_barrier();
-        } else {
-            stage_wait();
+            // Requested here, ahead of the next chunk's fetch (loads return in order: the wait for
+            // these then leaves that fetch alone), and used after the key side, whose arithmetic
+            // covers the latency: the key-mean rows of the NEXT chunk (of this one again if it is
+            // the last: the scores are then worked out for nobody), and this wave's strip of this
+            // chunk's value-mean tile, lane = token, 32 bytes per channel tile.
+            kmean_fetch(kmB, more ? blk_of(ci + CW) : blk0);
+#pragma unroll
+            for (int c = 0; c < NCT; c++)
+#pragma unroll
+                for (int hf = 0; hf < 2; hf++)
+                    glb_get16(vmp[c][hf], mean_row_src(1, blk0, lane) + 32 * (wave * NCT + c) + 16 * hf);
         }
+        PHASE(1)
         uint4 kc[NKL], vc[NVL];
 #pragma unroll
         for (int i = 0; i < NKL; i++) {
@@ -649,40 +708,16 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
         }
         // every read of the staging buffer has returned: start fetching this wave's next chunk
         wave_lds_fence();
-        const bool more = ci + CW < n_chunks;
         if (more) issue(ci + CW);
+        PHASE(2)
         if (XF) {
-            // q . mean_K of token 16 k + n for head `row` of each head group: B operand = the token's
-            // row of the key-mean tile (16 bytes per 32-channel step)
-            uint32_t xka[4]; // this lane's piece of row n for each 32-channel step (16 k + n has n's low bits)
+            // q . mean_K of token 16 k + n for head `row` of each head group, worked out by the waves
+            // together during the previous chunk
+            const float *xs = (const float *)lds_xs + par * (HQP * 64);
 #pragma unroll
-            for (int ks = 0; ks < 4; ks++) xka[ks] = lds_addr(xk8) + n * 256 + (((4 * ks + row) ^ (n & 7)) << 4);
+            for (int hg = 0; hg < NHG; hg++)
 #pragma unroll
-            for (int kp = 0; kp < 2; kp++) { // token tiles 2 kp, 2 kp + 1
-                u32x4 bop[8];
-#pragma unroll
-                for (int ks = 0; ks < 4; ks++) {
-                    if (kp == 0) { lds_get16<0>(bop[ks], xka[ks]); lds_get16<4096>(bop[4 + ks], xka[ks]); }
-                    else { lds_get16<8192>(bop[ks], xka[ks]); lds_get16<12288>(bop[4 + ks], xka[ks]); }
-                }
-                lds_got(bop);
-#pragma unroll
-                for (int kk = 0; kk < 2; kk++) {
-                    v4f accm[NHG];
-#pragma unroll
-                    for (int hg = 0; hg < NHG; hg++) accm[hg] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-                    for (int ks = 0; ks < 4; ks++)
-#pragma unroll
-                        for (int hg = 0; hg < NHG; hg++) accm[hg] = mfma_h(qop[hg][ks], bop[4 * kk + ks], accm[hg]);
-#pragma unroll
-                    for (int hg = 0; hg < NHG; hg++) xsv[hg][2 * kp + kk] = accm[hg][0];
-                }
-            }
-            // everybody is done with the key-mean tile: fetch the next chunk's
-            wave_lds_fence();
-            __builtin_amdgcn_s_barrier();
-            if (more) issue_kmean(ci + CW);
+                for (int k = 0; k < 4; k++) xsv[hg][k] = xs[xs_r[hg] + (((k + xs_rot[hg]) & 3) << 4)];
         }
 
         // ---- key side, one block at a time (the operand scratch holds one block's operands):
@@ -775,6 +810,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
             }
         }
 
+        PHASE(5)
         // ---- largest value scale of the chunk (the same for every head)
         uint32_t svw = 0u; // low halves: scales (high halves, the zeros, are ignored)
 #pragma unroll
@@ -817,96 +853,98 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
             }
         }
 
-        // ---- fused cross-head form: sum_t p_t mean_V[t] for head `row` of each head group, channels
-        // 16 ct + n, relative to the chunk's maximum like p
-        float omean[NHG][8];
+        // ---- fused cross-head form: the value mean's share, sum_t p_t mean_V[t], for all heads of the
+        // workgroup and this wave's channel tile(s), kept relative to each head's running maximum
+        PHASE(6)
         if (XF) {
-            // the weights as the A operand (row 4 r = head r, as with the queries), binary16 hi + lo
-            _Float16 *pt = (_Float16 *)(lds + STAGE_DW + OPER_DW);
+            // this wave's weights, relative to the new running maximum and times 2^8 (so that the low
+            // part of a small weight is still a normal binary16 number), as binary16 hi + lo; and the
+            // factor that brings the old sums to the new maximum
+            _Float16 *pb = (_Float16 *)lds_pb + par * (2 * HQP * (PB_ROW / 2));
+            float *al = (float *)lds_al + par * HQP;
 #pragma unroll
-            for (int hg = 0; hg < NHG; hg++)
+            for (int hg = 0; hg < NHG; hg++) {
+                const int hp = wave * HP + 4 * hg + row;
 #pragma unroll
                 for (int k = 0; k < 4; k++) {
-                    const _Float16 hi = (_Float16)p[hg][k];
-                    pt[(hg * 4 + row) * 64 + 16 * k + n] = hi;
-                    pt[((NHG + hg) * 4 + row) * 64 + 16 * k + n] = (_Float16)(p[hg][k] - (float)hi);
+                    const float pv = p[hg][k] * (wcs[hg] * 256.0f);
+                    const _Float16 hi = (_Float16)pv;
+                    pb[hp * (PB_ROW / 2) + 16 * k + n] = hi;
+                    pb[(HQP + hp) * (PB_ROW / 2) + 16 * k + n] = (_Float16)(pv - (float)hi);
                 }
+                if (n == 0) al[hp] = alpha[hg];
+            }
+            PHASE(7)
+            // the operands fetched by hand are there (fetches issued since: the next chunk, if any)
+            constexpr int nCmin = NBC == 1 ? (CB + 1023) / 1024
+                                           : ((CB + 1023) / 1024 < 2 * ((REC + 1023) / 1024) ? (CB + 1023) / 1024 : 2 * ((REC + 1023) / 1024));
+            if (more) glb_wait_but<nCmin>();
+            else glb_wait_but<0>();
+#pragma unroll
+            for (int e = 0; e < NHG; e++)
+#pragma unroll
+                for (int ks = 0; ks < 4; ks++) glb_got(kmB[e][ks]);
+#pragma unroll
+            for (int c = 0; c < NCT; c++)
+#pragma unroll
+                for (int hf = 0; hf < 2; hf++) glb_got(vmp[c][hf]);
+            kmean_scores(kmB, par ^ 1); // the next chunk's scores
+            // the strip of the value-mean tile, transposed: [channel][token], so that the token index
+            // is the contraction index of the B operand
+            uint16_t *vt = (uint16_t *)lds_vt + wave * (NCT * 16 * (PB_ROW / 2));
+#pragma unroll
+            for (int c = 0; c < NCT; c++)
+#pragma unroll
+                for (int hf = 0; hf < 2; hf++)
+#pragma unroll
+                    for (int k = 0; k < 4; k++) {
+                        const uint32_t w = vmp[c][hf][k];
+                        vt[(c * 16 + 8 * hf + 2 * k) * (PB_ROW / 2) + lane] = (uint16_t)(w & 0xFFFFu);
+                        vt[(c * 16 + 8 * hf + 2 * k + 1) * (PB_ROW / 2) + lane] = (uint16_t)(w >> 16);
+                    }
             wave_lds_fence();
-            // (read by hand like the shared tiles: the wave's next chunk is on its way into the same LDS object)
-            u32x4 pop[NHG][2][2];
-            {
-                const uint32_t pa = lds_addr(pt) + ((n >> 2) * 64 + 8 * row) * 2;
-                u32x4 raw[8];
-#pragma unroll
-                for (int i = 0; i < 8; i++) raw[i] = u32x4{0u, 0u, 0u, 0u};
-                lds_get16<0>(raw[0], pa); lds_get16<64>(raw[1], pa);                       // hi, head group 0
-                if (NHG == 2) { lds_get16<512>(raw[2], pa); lds_get16<576>(raw[3], pa); }  // hi, head group 1
-                lds_get16<NHG * 512>(raw[4], pa); lds_get16<NHG * 512 + 64>(raw[5], pa);   // lo, head group 0
-                if (NHG == 2) { lds_get16<1536>(raw[6], pa); lds_get16<1600>(raw[7], pa); }
-                lds_got(raw);
-                const bool on = (n & 3) == 0;
-#pragma unroll
-                for (int hg = 0; hg < NHG; hg++)
-#pragma unroll
-                    for (int hl = 0; hl < 2; hl++)
-#pragma unroll
-                        for (int ks = 0; ks < 2; ks++) pop[hg][hl][ks] = on ? raw[4 * hl + 2 * hg + ks] : u32x4{0u, 0u, 0u, 0u};
+            PHASE(8)
+            __builtin_amdgcn_s_barrier(); // everybody's weights, factors and scores are in place
+            PHASE(9)
+            // (the reads by hand: the wave's next chunk is on its way into LDS)
+            const uint32_t vta = lds_addr(vt) + n * PB_ROW + 16 * row; // channel n of a tile, tokens 8 row .. + 7
+            const uint32_t pba = lds_addr(pb) + n * PB_ROW + 16 * row; // A operand: row n = head n of a block, tokens 8 row .. + 7
+            const uint32_t ala = lds_addr(al) + 16 * row;              // factors of heads 4 row .. + 3 of a block
+            u32x4 vb[NCT][2], ph[NRB][2], pl[NRB][2], al4[NRB];
+            lds_get16<0>(vb[0][0], vta);
+            lds_get16<64>(vb[0][1], vta);
+            if (NCT == 2) {
+                lds_get16<16 * PB_ROW>(vb[NCT - 1][0], vta);
+                lds_get16<16 * PB_ROW + 64>(vb[NCT - 1][1], vta);
             }
-            // this wave's share of the value-mean tile has landed (younger requests: the next chunk and
-            // the next key-mean share, if there is a next chunk), then everybody's; the tile is
-            // transposed by all waves together, and once that is done its buffer takes the next chunk's
-            if (more) stage_wait_but<(NBC == 1 ? (CB + 1023) / 1024 : ((CB + 1023) / 1024 < 2 * ((REC + 1023) / 1024) ? (CB + 1023) / 1024 : 2 * ((REC + 1023) / 1024))) + 16 / NW>();
-            else stage_wait_but<0>();
-            __builtin_amdgcn_s_barrier();
-            {
-                for (int i = tid; i < 512; i += 64 * NW) {
-                    const int cp = i & 63, t8 = i >> 6; // channels 2 cp, 2 cp + 1; tokens 8 t8 .. 8 t8 + 7
-                    uint32_t w[8];
-                    const uint32_t xva = lds_addr(xv8) + (8 * t8 * 64 + cp) * 4;
-                    lds_get4<0>(w[0], xva); lds_get4<256>(w[1], xva); lds_get4<512>(w[2], xva); lds_get4<768>(w[3], xva);
-                    lds_get4<1024>(w[4], xva); lds_get4<1280>(w[5], xva); lds_get4<1536>(w[6], xva); lds_get4<1792>(w[7], xva);
-                    lds_got(w);
-                    uint4 lo, hi;
-                    lo.x = (w[0] & 0xFFFFu) | (w[1] << 16); hi.x = (w[0] >> 16) | (w[1] & 0xFFFF0000u);
-                    lo.y = (w[2] & 0xFFFFu) | (w[3] << 16); hi.y = (w[2] >> 16) | (w[3] & 0xFFFF0000u);
-                    lo.z = (w[4] & 0xFFFFu) | (w[5] << 16); hi.z = (w[4] >> 16) | (w[5] & 0xFFFF0000u);
-                    lo.w = (w[6] & 0xFFFFu) | (w[7] << 16); hi.w = (w[6] >> 16) | (w[7] & 0xFFFF0000u);
-                    *(uint4 *)(xt8 + (2 * cp) * XT_ROW + t8 * 16) = lo;
-                    *(uint4 *)(xt8 + (2 * cp + 1) * XT_ROW + t8 * 16) = hi;
-                }
+            static_assert(NCT <= 2 && NRB <= 2, "operand reads of the value-mean product are written out for these");
+            lds_get16<0>(ph[0][0], pba);
+            lds_get16<64>(ph[0][1], pba);
+            lds_get16<HQP * PB_ROW>(pl[0][0], pba);
+            lds_get16<HQP * PB_ROW + 64>(pl[0][1], pba);
+            lds_get16<0>(al4[0], ala);
+            if (NRB == 2) {
+                lds_get16<16 * PB_ROW>(ph[NRB - 1][0], pba);
+                lds_get16<16 * PB_ROW + 64>(ph[NRB - 1][1], pba);
+                lds_get16<(HQP + 16) * PB_ROW>(pl[NRB - 1][0], pba);
+                lds_get16<(HQP + 16) * PB_ROW + 64>(pl[NRB - 1][1], pba);
+                lds_get16<64>(al4[NRB - 1], ala);
             }
-            wave_lds_fence();
-            __builtin_amdgcn_s_barrier();
-            if (more) issue_vmean(ci + CW);
-            const uint32_t xta = lds_addr(xt8) + n * XT_ROW + 16 * row; // channel n of a tile, tokens 8 row .. + 7
+            lds_wait();
 #pragma unroll
-            for (int cq = 0; cq < 2; cq++) { // channel tiles 4 cq .. 4 cq + 3
-                u32x4 bop[8]; // [tile][32-token step]
-                if (cq == 0) {
-                    lds_get16<0 * 16 * XT_ROW>(bop[0], xta); lds_get16<0 * 16 * XT_ROW + 64>(bop[1], xta);
-                    lds_get16<1 * 16 * XT_ROW>(bop[2], xta); lds_get16<1 * 16 * XT_ROW + 64>(bop[3], xta);
-                    lds_get16<2 * 16 * XT_ROW>(bop[4], xta); lds_get16<2 * 16 * XT_ROW + 64>(bop[5], xta);
-                    lds_get16<3 * 16 * XT_ROW>(bop[6], xta); lds_get16<3 * 16 * XT_ROW + 64>(bop[7], xta);
-                } else {
-                    lds_get16<4 * 16 * XT_ROW>(bop[0], xta); lds_get16<4 * 16 * XT_ROW + 64>(bop[1], xta);
-                    lds_get16<5 * 16 * XT_ROW>(bop[2], xta); lds_get16<5 * 16 * XT_ROW + 64>(bop[3], xta);
-                    lds_get16<6 * 16 * XT_ROW>(bop[4], xta); lds_get16<6 * 16 * XT_ROW + 64>(bop[5], xta);
-                    lds_get16<7 * 16 * XT_ROW>(bop[6], xta); lds_get16<7 * 16 * XT_ROW + 64>(bop[7], xta);
+            for (int c = 0; c < NCT; c++) { lds_got(vb[c][0]); lds_got(vb[c][1]); }
+#pragma unroll
+            for (int rb = 0; rb < NRB; rb++) { lds_got(ph[rb][0]); lds_got(ph[rb][1]); lds_got(pl[rb][0]); lds_got(pl[rb][1]); lds_got(al4[rb]); }
+#pragma unroll
+            for (int rb = 0; rb < NRB; rb++)
+#pragma unroll
+                for (int c = 0; c < NCT; c++) {
+                    v4f acc = accv[rb][c] * __builtin_bit_cast(v4f, al4[rb]);
+#pragma unroll
+                    for (int ks = 0; ks < 2; ks++) acc = mfma_h(pl[rb][ks], vb[c][ks], mfma_h(ph[rb][ks], vb[c][ks], acc));
+                    accv[rb][c] = acc;
                 }
-                lds_got(bop);
-#pragma unroll
-                for (int c4 = 0; c4 < 4; c4++) {
-                    v4f om[NHG];
-#pragma unroll
-                    for (int hg = 0; hg < NHG; hg++) om[hg] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-                    for (int ks = 0; ks < 2; ks++)
-#pragma unroll
-                        for (int hg = 0; hg < NHG; hg++) om[hg] = mfma_h(pop[hg][1][ks], bop[2 * c4 + ks], mfma_h(pop[hg][0][ks], bop[2 * c4 + ks], om[hg]));
-#pragma unroll
-                    for (int hg = 0; hg < NHG; hg++) omean[hg][4 * cq + c4] = om[hg][0] * wcs[hg];
-                }
-            }
+                        PHASE(10)
         }
 
         // ---- value side in passes of NGP scale groups: p*scale as limbs -> LDS, matrix products
@@ -964,7 +1002,6 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
 #pragma unroll
                 for (int hg = 0; hg < NHG; hg++) {
                     float o = st[hg].O[ct] * alpha[hg] + limbs_to_float(acc[hg]) * o_scale[hg];
-                    if (XF) o += omean[hg][ct];
 #pragma unroll
                     for (int bi = 0; bi < NBC; bi++)
                         o += __half2float(__ushort_as_half(vmean[bi][ct])) * psum_b[hg][bi];
@@ -972,9 +1009,29 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
                 }
             }
         }
+        PHASE(11)
     }
+    PHASE(12)
 
     if (B != 8) __builtin_amdgcn_s_setprio(0);
+
+    // fused cross-head form: the value mean's share goes from the waves that summed it (all heads, a
+    // channel tile) to the waves that own the heads, through the buffer the scores went through
+    if (XF) {
+        float *om = (float *)lds_xs; // [head][128]
+#pragma unroll
+        for (int rb = 0; rb < NRB; rb++)
+#pragma unroll
+            for (int c = 0; c < NCT; c++)
+#pragma unroll
+                for (int j = 0; j < 4; j++)
+                    om[(16 * rb + 4 * row + j) * kHeadDim + 16 * (wave * NCT + c) + n] = accv[rb][c][j] * 0x1p-8f;
+        __syncthreads();
+#pragma unroll
+        for (int hg = 0; hg < NHG; hg++)
+#pragma unroll
+            for (int ct = 0; ct < 8; ct++) st[hg].O[ct] += om[(wave * HP + 4 * hg + row) * kHeadDim + 16 * ct + n];
+    }
 
     // ---- raw residual tokens (Sec. 3.3) in tiles of 32, dealt to the splits in turn after the
     // unit's last chunk; wave w of the split takes tokens 8 w .. 8 w + 7 of a tile into its own
@@ -1110,6 +1167,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
 #pragma unroll
         for (int ct = 0; ct < 8; ct++) mine[(hg * 10 + 2 + ct) * 64 + lane] = st[hg].O[ct];
     }
+    PHASE(13)
+    PHASE_DONE
     __syncthreads();
     if (XF || wave == 0) {
         constexpr int MW = XF ? 1 : NW; // waves whose states make up the partial result
@@ -1212,7 +1271,7 @@ struct DoMatch {
 bool xhead_fused_fmt(const DecodeArgs &a)
 {
     const LayerGeom &g = a.geom;
-    if (g.k_bits == 4 && a.n_kv_heads == 8 && a.g > 4) return false; // two head groups' operand scratch on top: over the LDS limit
+    if (a.n_kv_heads == 8 && a.g > 4) return false; // 64 query heads' exchange buffers on top of eight chunk buffers: over the LDS limit
     return g.mean_mode == 1 && !g.table && (g.G == 32 || g.G == 64) && (g.k_bits == 2 || g.k_bits == 4) &&
            (a.n_kv_heads == 4 || a.n_kv_heads == 8);
 }
@@ -1235,8 +1294,7 @@ template <int B, int G, int GC, bool PG, class F> void pick_mean_heads_pg(const 
 template <int B, int G, int GC, class F> void pick_fused(const DecodeArgs &a, F &f)
 {
     if (a.n_kv_heads == 8) {
-        if (a.g <= 4) f.template run<B, G, GC, false, 8, 1, 2, false>(a);
-        else if constexpr (B == 2) f.template run<B, G, GC, false, 8, 2, 2, false>(a); // (4-bit: does not fit, see xhead_fused_fmt)
+        if (a.g <= 4) f.template run<B, G, GC, false, 8, 1, 2, false>(a); // (more heads do not fit, see xhead_fused_fmt)
     } else {
         if (a.g <= 4) f.template run<B, G, GC, false, 4, 1, 2, false>(a);
         else f.template run<B, G, GC, false, 4, 2, 2, false>(a);
@@ -1319,3 +1377,18 @@ hipError_t launch_decode_split_mfma(const DecodeArgs &a, hipStream_t s)
 }
 
 } // namespace tadakv
+
+#ifdef TADA_PHASE_CLOCK
+// out[0..13]: cycles summed over all waves per phase; out[14]: loop iterations; out[15]: waves.
+// reset != 0 clears the sums afterwards.
+extern "C" int kv_debug_phase_clocks(unsigned long long *out, int reset)
+{
+    if (hipDeviceSynchronize() != hipSuccess) return -1;
+    if (hipMemcpyFromSymbol(out, HIP_SYMBOL(tadakv::tada_phase_clk), 16 * sizeof(unsigned long long)) != hipSuccess) return -1;
+    if (reset) {
+        unsigned long long z[16] = {};
+        if (hipMemcpyToSymbol(HIP_SYMBOL(tadakv::tada_phase_clk), z, sizeof(z)) != hipSuccess) return -1;
+    }
+    return 0;
+}
+#endif
