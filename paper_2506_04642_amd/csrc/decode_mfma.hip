@@ -313,14 +313,16 @@ template <> struct CodeOps<8> { // four words = one tile line; split into nibble
 //   XH == 1: the mean's share of every score comes in through a.xs, and the softmax weights go out
 //            through a.xp / a.xmc for the kernel that adds the value mean plane's share to the
 //            partial outputs (two more kernels and a round trip of scores and weights).
-//   XH == 2: both mean terms inside this kernel.  A workgroup is one (sequence, split) with one wave
-//            per kv head (NW = n_kv_heads): every wave takes the same chunks, each of its own head's
-//            records, and the chunk's key-mean and value-mean tiles (64 tokens x 128 channels of
-//            binary16, shared by all kv heads: Eq. 1-2) are fetched once per workgroup into LDS.
-//            q . mean_K and sum_t p_t mean_V[t] are dense binary16 products on the matrix cores
-//            (queries narrowed to binary16: exact in its normal range; weights as a binary16 pair
-//            hi + lo; binary32 accumulation); the value tile goes through registers and is written
-//            into LDS transposed, so that the token index is the contraction index of the operand.
+//   XH == 2: both mean terms inside this kernel.  A workgroup is one (sequence, split) and NW kv
+//            heads (all of them, or half: then two workgroups share the split), a wave per kv head:
+//            every wave takes the same chunks, each of its own head's records.  The mean rows of a
+//            chunk (64 tokens x 128 channels of binary16 for keys and for values, shared by all kv
+//            heads: Eq. 1-2) go from global memory straight into matrix-core operands: q . mean_K and
+//            sum_t p_t mean_V[t] are dense binary16 products (queries narrowed to binary16: exact in
+//            its normal range; weights as a binary16 pair hi + lo; binary32 accumulation) that the
+//            waves share out among themselves -- the scores by (16 query heads, 16 tokens), the
+//            value share by 16-channel tile for all heads -- and whose small operands and results
+//            (scores, weights, rescale factors) they exchange through LDS, one barrier per chunk.
 // PG: paged placement (block slots through a table); the dense instances carry none of its state.
 // GS: tokens per block of the cache (32, 64, or 128 read as two halves of 64).
 template <int B, int GS, int GC, bool MEAN, int NW, int NHG, int XH, bool PG>
@@ -375,8 +377,21 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
     uint32_t *stage = lds;                 // the chunk as it lies in the cache
     uint32_t *ak = lds + STAGE_DW, *av = ak;
 
-    const int sp = blockIdx.x;
-    const int u = XF ? (int)blockIdx.y * a.n_kv_heads + wave : (int)blockIdx.y;
+    // fused cross-head form: a workgroup takes NW kv heads of a sequence; with twice as many heads two
+    // workgroups share a (sequence, split) and read the same mean rows -- they sit 8 apart in the
+    // launch order when the split count allows (same XCD and so the same L2, resident together)
+    const int halves = XF ? a.n_kv_heads / NW : 1;
+    int sp = blockIdx.x, half = 0;
+    if (XF && halves == 2) {
+        if (a.n_splits % 8 == 0) {
+            half = (sp >> 3) & 1;
+            sp = (sp & 7) | ((sp >> 4) << 3);
+        } else {
+            half = sp & 1;
+            sp >>= 1;
+        }
+    }
+    const int u = XF ? (int)blockIdx.y * a.n_kv_heads + half * NW + wave : (int)blockIdx.y;
     const int b = u / a.n_kv_heads, h = u % a.n_kv_heads;
     const int g = a.g;
     const int cw0 = XF ? 0 : wave; // this wave's first local chunk
@@ -540,7 +555,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
 #pragma unroll
         for (int e = 0; e < NHG; e++) {
             const int pj = wave * NHG + e, rb = pj >> 2, tt = pj & 3; // head block, token tile
-            const int hp = 16 * rb + n, hk = hp / HP, local = hp % HP; // A row n: kv head, head of its group
+            const int hp = 16 * rb + n, hk = half * NW + hp / HP, local = hp % HP; // A row n: kv head, head of its group
             const uint16_t *qp = a.q + ((long long)b * a.n_q_heads + hk * g + (local < g ? local : 0)) * kHeadDim + 8 * row;
 #pragma unroll
             for (int ks = 0; ks < 4; ks++) {
@@ -1219,12 +1234,12 @@ template <int B, int G, int GC, bool MEAN, int NW, int NHG, int XH, bool PG> int
     return n;
 }
 
-// XH == 2 (both cross-head mean terms inside the kernel): one workgroup per (sequence, split), NW = kv heads.
+// XH == 2 (both cross-head mean terms inside the kernel): a workgroup per (sequence, split) and NW kv heads.
 template <int B, int G, int GC, bool MEAN, int NW, int NHG, int XH, bool PG> hipError_t launch_inst(const DecodeArgs &a, hipStream_t s)
 {
     if (!RecLayout<B, G, GC, MEAN>::matches(a.geom)) return hipErrorInvalidValue;
-    if (XH == 2 && a.n_kv_heads != NW) return hipErrorInvalidValue;
-    dim3 grid(a.n_splits, XH == 2 ? a.batch : a.batch * a.n_kv_heads);
+    if (XH == 2 && a.n_kv_heads != NW && a.n_kv_heads != 2 * NW) return hipErrorInvalidValue;
+    dim3 grid(XH == 2 ? a.n_splits * (a.n_kv_heads / NW) : a.n_splits, XH == 2 ? a.batch : a.batch * a.n_kv_heads);
     (void)hipGetLastError(); // drop any stale error left by earlier runtime calls of this thread
     hipLaunchKernelGGL((decode_split_mfma_kernel<B, G, GC, MEAN, NW, NHG, XH, PG>), grid, dim3(64 * NW), 0, s, a);
     return note_launch(hipGetLastError());
@@ -1235,7 +1250,7 @@ template <int B, int G, int GC, bool MEAN, int NW, int NHG, int XH, bool PG> hip
 template <int B, int G, int GC, bool MEAN, int NW, int NHG, int XH, bool PG> int plan_inst(const DecodeArgs &a)
 {
     const int slots = resident_blocks<B, G, GC, MEAN, NW, NHG, XH, PG>();
-    const int U = XH == 2 ? a.batch : a.batch * a.n_kv_heads; // workgroups per split
+    const int U = XH == 2 ? a.batch * (a.n_kv_heads / NW) : a.batch * a.n_kv_heads; // workgroups per split
     constexpr int CW = XH == 2 ? 1 : NW;                      // waves that share a unit's chunks
     const int chunks = (a.n_blocks * G + 63) / 64; // chunks of 64 tokens
     int ns = slots / U;
@@ -1266,14 +1281,11 @@ struct DoMatch {
 };
 
 // Does the layer get the fused cross-head form (both mean terms inside the split kernel)?  It takes a
-// wave per kv head (4 or 8 of them), dense placement, blocks of 32 or 64 tokens, and 2- or 4-bit
-// codes (eight 8-bit chunk buffers and the mean tiles do not fit the LDS of a compute unit).
+// wave per kv head, 4 or 8 kv heads, dense placement and blocks of 32 or 64 tokens.
 bool xhead_fused_fmt(const DecodeArgs &a)
 {
     const LayerGeom &g = a.geom;
-    if (a.n_kv_heads == 8 && a.g > 4) return false; // 64 query heads' exchange buffers on top of eight chunk buffers: over the LDS limit
-    return g.mean_mode == 1 && !g.table && (g.G == 32 || g.G == 64) && (g.k_bits == 2 || g.k_bits == 4) &&
-           (a.n_kv_heads == 4 || a.n_kv_heads == 8);
+    return g.mean_mode == 1 && !g.table && (g.G == 32 || g.G == 64) && (a.n_kv_heads == 4 || a.n_kv_heads == 8);
 }
 
 template <int B, int G, int GC, bool PG, class F> void pick_mean_heads_pg(const DecodeArgs &a, F &f)
@@ -1290,15 +1302,21 @@ template <int B, int G, int GC, bool PG, class F> void pick_mean_heads_pg(const 
         else f.template run<B, G, GC, false, NW, 2, 0, PG>(a);
     }
 }
-// the fused cross-head instances: a wave per kv head
+// the fused cross-head instances: a wave per kv head.  Eight kv heads go to two workgroups of four
+// waves, except at 4 bits with up to four query heads per kv head, where one workgroup of eight is
+// faster (its four-wave twin needs more than 256 registers: one wave per SIMD; the 2-bit four-wave
+// instance fits a compute unit twice and beats its eight-wave twin, 159 against 168 us per layer
+// on 16 sequences of 32768 tokens; eight 8-bit chunk buffers do not fit the LDS).
 template <int B, int G, int GC, class F> void pick_fused(const DecodeArgs &a, F &f)
 {
-    if (a.n_kv_heads == 8) {
-        if (a.g <= 4) f.template run<B, G, GC, false, 8, 1, 2, false>(a); // (more heads do not fit, see xhead_fused_fmt)
-    } else {
-        if (a.g <= 4) f.template run<B, G, GC, false, 4, 1, 2, false>(a);
-        else f.template run<B, G, GC, false, 4, 2, 2, false>(a);
+    if constexpr (B == 4) {
+        if (a.n_kv_heads == 8 && a.g <= 4) {
+            f.template run<B, G, GC, false, 8, 1, 2, false>(a);
+            return;
+        }
     }
+    if (a.g <= 4) f.template run<B, G, GC, false, 4, 1, 2, false>(a);
+    else f.template run<B, G, GC, false, 4, 2, 2, false>(a);
 }
 template <int B, int G, int GC, class F> void pick_mean_heads(const DecodeArgs &a, F &f)
 {
@@ -1312,10 +1330,12 @@ template <class F> void pick(const DecodeArgs &a, F &f)
     if (xhead_fused_fmt(a)) {
         if (a.geom.G == 32) {
             if (bits == 2) pick_fused<2, 32, 32>(a, f);
-            else pick_fused<4, 32, 32>(a, f);
+            else if (bits == 4) pick_fused<4, 32, 32>(a, f);
+            else pick_fused<8, 32, 32>(a, f);
         } else {
             if (bits == 2) pick_fused<2, 64, 64>(a, f);
-            else pick_fused<4, 64, 64>(a, f);
+            else if (bits == 4) pick_fused<4, 64, 64>(a, f);
+            else pick_fused<8, 64, 64>(a, f);
         }
         return;
     }

@@ -510,13 +510,17 @@ def test_cross_head_mean_mixed_layers_bf16(kv, oracle):
 
 
 @pytest.mark.parametrize("decode_path", [2], indirect=True, ids=["mfma"])
-@pytest.mark.parametrize("bits,G,g,T", [(4, 32, 3, 2000 + 13), (2, 32, 5, 1056), (8, 64, 4, 1600 + 40), (4, 64, 8, 704),
-                                        (4, 128, 4, 2048 + 128 + 50), (2, 128, 8, 1280), (8, 128, 3, 1664 + 7)])
-def test_cross_head_mean_on_the_matrix_cores(kv, oracle, decode_path, bits, G, g, T):
-    """Cross-head mean with the deviations on the matrix-core kernel and the two dense mean terms
-    in their own kernels; several splits, an odd block count, a raw tail."""
-    print("case cross_head_mfma bits=%d G=%d g=%d T=%d" % (bits, G, g, T), flush=True)
-    Hkv = 4
+@pytest.mark.parametrize("bits,G,g,T,Hkv", [(4, 32, 3, 2000 + 13, 4), (2, 32, 5, 1056, 4), (8, 64, 4, 1600 + 40, 4),
+                                            (4, 64, 8, 704, 4), (4, 128, 4, 2048 + 128 + 50, 4), (2, 128, 8, 1280, 4),
+                                            (8, 128, 3, 1664 + 7, 4), (8, 32, 4, 1500 + 9, 8), (2, 32, 8, 1056 + 32, 8),
+                                            (4, 64, 5, 1344 + 3, 8), (8, 64, 8, 960, 8), (2, 64, 2, 2048 + 70, 8),
+                                            (4, 32, 4, 1120 + 31, 8), (4, 32, 2, 700, 2)])
+def test_cross_head_mean_on_the_matrix_cores(kv, oracle, decode_path, bits, G, g, T, Hkv):
+    """Cross-head mean with the deviations on the matrix-core kernel; the two dense mean terms inside
+    that kernel (4 or 8 kv heads, blocks of 32 or 64 tokens: a workgroup of 8 waves, of 4 waves, or two
+    workgroups of 4 that share a sequence's split) or in kernels of their own (the other formats);
+    several splits, an odd block count, a raw tail."""
+    print("case cross_head_mfma bits=%d G=%d g=%d T=%d Hkv=%d" % (bits, G, g, T, Hkv), flush=True)
     gpu, orc = make_pair(kv, oracle, B=2, Hq=Hkv * g, Hkv=Hkv, T_max=(T // G + 2) * G, G=G, Gc=G, dtype=BF16, mode=CROSS,
                          k_bits=(bits,))
     k, v = synth.make_kv(500 + bits + g, 2, T, Hkv, 128, BF16)
@@ -540,8 +544,9 @@ def test_cross_head_mean_with_a_forced_split_count(kv, oracle, decode_path):
 
     print("case cross_head_forced_splits", flush=True)
     B, Hkv, g, T = 16, 8, 4, 128 * 32 + 5
-    # (8-bit: the widths whose dense mean terms run as kernels of their own and pass through the workspace)
-    gpu, orc = make_pair(kv, oracle, B=B, Hq=Hkv * g, Hkv=Hkv, T_max=130 * 32, dtype=BF16, mode=CROSS, k_bits=(8,))
+    # (blocks of 128 tokens: a format whose dense mean terms run as kernels of their own and pass through the workspace)
+    gpu, orc = make_pair(kv, oracle, B=B, Hq=Hkv * g, Hkv=Hkv, T_max=33 * 128, G=128, Gc=128, dtype=BF16, mode=CROSS,
+                         k_bits=(4,))
     k, v = synth.make_kv(611, B, T, Hkv, 128, BF16)
     append_both(gpu, orc, 0, k, v, BF16)
     q = synth.make_q(611, B, Hkv * g, 128, BF16)
