@@ -474,6 +474,31 @@ def main():
         rope_stats["rope_fused" if fused else "plain"] = {
             "tokens_per_s": round(tok / (ms / 1e3), 1),
             "input_GBps": round(tok * Hkv * d * 2 * 2 / (ms / 1e3) / 1e9, 1)}
+    # ---- single-token append: what a call costs the host, split into the binding's Python (tensor
+    # slicing, checks, pointer extraction) and the library call itself, and what it costs the GPU
+    n1 = 48
+    host_split = {}
+    for how in ("binding", "library"):
+        kv.kv_cache_reset(scratch.handle, -1)
+        torch.cuda.synchronize()
+        c0.record(stream)
+        t0 = time.perf_counter()
+        if how == "binding":
+            for i in range(n1):
+                scratch.append(0, kr[:, i:i + 1], vr[:, i:i + 1])
+        else:
+            kp, vp, esz = kr.data_ptr(), vr.data_ptr(), kr.element_size()
+            s0, s1, s2, sp_ = kr.stride(0), kr.stride(1), kr.stride(2), stream.cuda_stream
+            for i in range(n1):
+                kv.kv_quant_append(scratch.handle, 0, kp + i * s1 * esz, vp + i * s1 * esz, 1, s0, s1, s2, sp_)
+        t_host = time.perf_counter() - t0  # the calls have returned; the GPU may still be busy
+        c1.record(stream)
+        c1.synchronize()
+        host_split[how + "_host_us_per_call"] = round(t_host / n1 * 1e6, 2)
+        host_split[how + "_gpu_us_per_call"] = round(c0.elapsed_time(c1) / n1 * 1e3, 2)
+    host_split["python_marshalling_us_per_call"] = round(host_split["binding_host_us_per_call"] - host_split["library_host_us_per_call"], 2)
+    host_split["note"] = ("one layer, batch %d, one token per sequence and call; host = wall time until the calls have returned "
+                          "(enqueue only), gpu = event time over the same calls" % B)
     scratch.close()
     del scratch, kr, vr
 
@@ -503,6 +528,7 @@ def main():
             "bulk_input_GBps": fig["bulk_append_input_GBps"],
             "single_token_tokens_per_s": round(B * n_app / app_s, 1) if n_app else None,
             "single_token_us_per_layer_call": round(app_s / max(n_app * L, 1) * 1e6, 2) if n_app else None,
+            "single_token_call_cost": host_split,
             "bulk_4096_token_calls": rope_stats,
         },
         "roofline": {"bound": "hbm", "kernel": "decode split kernel (all layers, weighted by layer)",
