@@ -41,18 +41,20 @@ def check_attend(gpu, orc, layer, q, dtype):
 
 
 @pytest.mark.parametrize("path", [0, 1, 2], ids=["auto", "valu", "mfma"])
-@pytest.mark.parametrize("bits,G,mode", [(4, 32, CHAN), (2, 64, CHAN), (8, 32, NONE), (4, 32, CROSS), (4, 128, CHAN),
-                                          (2, 128, NONE), (8, 128, CROSS)])
-def test_requests_join_step_and_leave(kv, oracle, path, bits, G, mode):
+@pytest.mark.parametrize("bits,G,mode,Hkv", [(4, 32, CHAN, 2), (2, 64, CHAN, 2), (8, 32, NONE, 2), (4, 32, CROSS, 2),
+                                              (4, 128, CHAN, 2), (2, 128, NONE, 2), (8, 128, CROSS, 2),
+                                              # 4 or 8 kv heads: the cross-head mean's terms inside the matrix-core kernel
+                                              (2, 32, CROSS, 8), (4, 64, CROSS, 8), (8, 64, CROSS, 4)])
+def test_requests_join_step_and_leave(kv, oracle, path, bits, G, mode, Hkv):
     """Four slots: prompts of different lengths enter one by one (one slot stays empty at first),
     everybody decodes for a while through the one-call step, one request leaves and a new one
     takes its slot, decoding goes on."""
     import torch
 
-    print("case ragged path=%d bits=%d G=%d mode=%d" % (path, bits, G, mode), flush=True)
+    print("case ragged path=%d bits=%d G=%d mode=%d Hkv=%d" % (path, bits, G, mode, Hkv), flush=True)
     parity_util.DECODE_PATH = path
     try:
-        B, Hkv, g, R = 4, 2, 4, G
+        B, g, R = 4, 4, G
         T_max = 12 * G
         gpu, orc = make_pair(kv, oracle, B=B, Hq=Hkv * g, Hkv=Hkv, T_max=T_max, G=G, Gc=G, R=R, dtype=BF16, mode=mode,
                              k_bits=(bits,))
