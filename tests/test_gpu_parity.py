@@ -428,17 +428,20 @@ def test_prefill_then_decode_full_size(kv, oracle, decode_path):
 
 
 @pytest.mark.parametrize("decode_path", [0], indirect=True, ids=["auto"])
-def test_full_cache_shape_cross_head_sampled_units(kv, oracle, decode_path):
-    """The same launch configuration with the mean over the kv heads (Eq. 1-2): one 4-bit layer,
-    records, mean plane and attention of sampled sequences against the oracle."""
+@pytest.mark.parametrize("bits", [4, 2, 8])
+def test_full_cache_shape_cross_head_sampled_units(kv, oracle, decode_path, bits):
+    """The same launch configuration with the mean over the kv heads (Eq. 1-2): one layer of each
+    width (4 bits: a workgroup of eight waves per sequence and split; 2 and 8 bits: two workgroups of
+    four that share the split's mean rows), records, mean plane and attention of sampled sequences
+    against the oracle."""
     import torch
 
-    print("case full_cache_shape_cross_head", flush=True)
+    print("case full_cache_shape_cross_head bits=%d" % bits, flush=True)
     B, Hq, Hkv, d, G, T = 16, 32, 8, 128, 32, 32768 + 13
-    cfg = kv.make_config(1, B, Hq, Hkv, d, 32768 + 64, G, G, G, kv.KV_BF16, kv.KV_MEAN_CROSS_HEAD, [4], [4])
+    cfg = kv.make_config(1, B, Hq, Hkv, d, 32768 + 64, G, G, G, kv.KV_BF16, kv.KV_MEAN_CROSS_HEAD, [bits], [bits])
     gpu = kv.KVCache(cfg, zero=False)
     sample = (3, 15)
-    ocfg = oracle.OracleConfig(1, len(sample), Hq, Hkv, d, 32768 + 64, G, G, G, BF16, CROSS, [4], [4])
+    ocfg = oracle.OracleConfig(1, len(sample), Hq, Hkv, d, 32768 + 64, G, G, G, BF16, CROSS, [bits], [bits])
     orc = oracle.OracleCache(ocfg)
     host_k, host_v = [], []
     for t0 in range(0, T, 8192):
