@@ -379,6 +379,38 @@ kv_status kv_decode_workspace_need(const kv_cache *cache, int32_t layer, size_t 
 #define KV_STATIC_WORKSPACE_BYTES (8u << 20)
 kv_status kv_decode_attn_static(const kv_cache *cache, int32_t layer, const void *q, float *out, void *stream);
 
+/* ---- Decode steps on device-resident lengths (Algorithm 1 steps 8-9 for serving loops that replay a
+ * recorded step).  The entry points above take the lengths of the sequences from the host-side
+ * descriptor and put them into their kernels' arguments, so a call recorded into a HIP graph is
+ * right for one state of the cache only.  Here the kernels take them from device memory and advance
+ * them themselves: one recorded call (per layer) replays step after step while the cache grows,
+ * compressing a sequence's raw tokens whenever the step's token fills its buffer (Sec. 3.3).
+ *   kv_dev_lengths_bytes       : size of the lengths array for a configuration (cfg, bytes: host).
+ *   kv_cache_lengths_to_device : dev_lengths (device, that many bytes, 16-byte aligned, owned by the
+ *       caller, kept by the cache until the next such call) receives the lengths the descriptor holds
+ *       now, by an asynchronous copy on `stream` from memory the cache keeps alive -- call it
+ *       outside graph capture, after the prompts have been appended, and again after any other call
+ *       that changes lengths (appends, resets).
+ *   kv_decode_step_dev : as kv_append_decode_attn -- one token per sequence appended, then attention
+ *       over everything cached -- with the same results bit for bit; enqueues four kernels (store the
+ *       token and write the lengths after the step; compress the raw buffers that it filled, none on
+ *       most steps; attention; merge, which also makes the new lengths current) and does NOT change
+ *       the descriptor's lengths.  A sequence that has no room for the token keeps its state and
+ *       attends over what it has.  The launch shapes (split count) are planned from the
+ *       descriptor's lengths: re-record after a few hundred steps to keep them near the best.
+ *   kv_cache_advance : the descriptor catches up with n_steps such steps of `layer` (-1: every
+ *       layer), so that the other entry points see the cache as it is; host only.
+ * Served: group_tokens == 32, k_bits == v_bits in {2, 4, 8}, KV_MEAN_CHANNEL_BLOCK or KV_MEAN_NONE,
+ * dense placement, all sequences active, layers on the matrix-core kernels; otherwise
+ * KV_E_UNSUPPORTED.  KV_E_BAD_CONFIG before kv_cache_lengths_to_device.  Other errors as
+ * kv_append_decode_attn. */
+kv_status kv_dev_lengths_bytes(const kv_config *cfg, size_t *bytes);
+kv_status kv_cache_lengths_to_device(kv_cache *cache, void *dev_lengths, void *stream);
+kv_status kv_decode_step_dev(const kv_cache *cache, int32_t layer, const void *k_new, const void *v_new,
+                             int64_t stride_b, int64_t stride_h, const void *q, float *out,
+                             void *workspace, size_t workspace_bytes, void *stream);
+kv_status kv_cache_advance(kv_cache *cache, int32_t layer, int32_t n_steps);
+
 /* Measurement aid, not part of the method: one read-only pass over `bytes` bytes at `buf` (device,
  * 16-byte aligned; whole 16-byte pieces are read) with 16-byte loads, one workgroup per contiguous
  * 64 KiB -- the rate the memory system delivers to a kernel that does nothing else,

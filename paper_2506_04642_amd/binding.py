@@ -30,7 +30,7 @@ KV_MEAN_CHANNEL_BLOCK, KV_MEAN_CROSS_HEAD, KV_MEAN_NONE = 0, 1, 2
 EXPORTS = [
     "kv_cache_bytes", "kv_workspace_bytes", "kv_cache_create", "kv_cache_destroy", "kv_cache_set_block_table", "kv_cache_set_active", "kv_cache_reset",
     "kv_cache_len", "kv_cache_len_seq", "kv_cache_reset_seq", "kv_cache_describe", "kv_quant_append", "kv_quant_append_seq", "kv_rope_quant_append", "kv_compressv_append", "kv_append_decode_attn", "kv_append_decode_attn_split", "kv_decode_attn", "kv_decode_attn_split",
-    "kv_decode_attn_merge", "kv_decode_attn_merge16", "kv_dequant", "kv_decode_splits", "kv_decode_bytes", "kv_set_decode_path", "kv_decode_path_used", "kv_set_decode_splits", "kv_decode_workspace_need", "kv_decode_attn_static", "kv_stream_read_probe", "kv_strerror", "kv_last_hip_error",
+    "kv_decode_attn_merge", "kv_decode_attn_merge16", "kv_dequant", "kv_decode_splits", "kv_decode_bytes", "kv_set_decode_path", "kv_decode_path_used", "kv_set_decode_splits", "kv_decode_workspace_need", "kv_decode_attn_static", "kv_dev_lengths_bytes", "kv_cache_lengths_to_device", "kv_decode_step_dev", "kv_cache_advance", "kv_stream_read_probe", "kv_strerror", "kv_last_hip_error",
 ]
 
 
@@ -87,6 +87,10 @@ _lib.kv_set_decode_splits.argtypes = [_vp, _i32]
 _lib.kv_decode_path_used.argtypes = [_vp, _i32, ctypes.POINTER(_i32)]
 _lib.kv_decode_workspace_need.argtypes = [_vp, _i32, _szp]
 _lib.kv_decode_attn_static.argtypes = [_vp, _i32, _vp, _vp, _vp]
+_lib.kv_dev_lengths_bytes.argtypes = [_cfgp, _szp]
+_lib.kv_cache_lengths_to_device.argtypes = [_vp, _vp, _vp]
+_lib.kv_decode_step_dev.argtypes = [_vp, _i32, _vp, _vp, _i64, _i64, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+_lib.kv_cache_advance.argtypes = [_vp, _i32, _i32]
 _lib.kv_stream_read_probe.argtypes = [_vp, ctypes.c_size_t, _vp, _vp]
 _lib.kv_strerror.argtypes = [_i32]
 _lib.kv_strerror.restype = ctypes.c_char_p
@@ -299,6 +303,26 @@ def kv_decode_attn_static(cache: int, layer: int, q_ptr: int, out_ptr: int, stre
     _check(_lib.kv_decode_attn_static(cache, layer, q_ptr, out_ptr, stream), "kv_decode_attn_static")
 
 
+def kv_dev_lengths_bytes(cfg: kv_config) -> int:
+    n = ctypes.c_size_t()
+    _check(_lib.kv_dev_lengths_bytes(ctypes.byref(cfg), ctypes.byref(n)), "kv_dev_lengths_bytes")
+    return n.value
+
+
+def kv_cache_lengths_to_device(cache: int, dev_ptr: int, stream: int = 0) -> None:
+    _check(_lib.kv_cache_lengths_to_device(cache, dev_ptr, stream), "kv_cache_lengths_to_device")
+
+
+def kv_decode_step_dev(cache: int, layer: int, k_ptr: int, v_ptr: int, stride_b: int, stride_h: int, q_ptr: int,
+                       out_ptr: int, ws_ptr: int, ws_bytes: int, stream: int = 0) -> None:
+    _check(_lib.kv_decode_step_dev(cache, layer, k_ptr, v_ptr, stride_b, stride_h, q_ptr, out_ptr, ws_ptr, ws_bytes,
+                                   stream), "kv_decode_step_dev")
+
+
+def kv_cache_advance(cache: int, layer: int, n_steps: int) -> None:
+    _check(_lib.kv_cache_advance(cache, layer, n_steps), "kv_cache_advance")
+
+
 def kv_stream_read_probe(buf_ptr: int, nbytes: int, sink_ptr: int = 0, stream: int = 0) -> None:
     _check(_lib.kv_stream_read_probe(buf_ptr, nbytes, sink_ptr or None, stream), "kv_stream_read_probe")
 
@@ -425,6 +449,25 @@ class KVCache:
                               k_new.stride(1), q.data_ptr(), out.data_ptr(), self.workspace.data_ptr(),
                               self.ws_bytes, self._stream())
         return out
+
+    def lengths_to_device(self):
+        """Device-resident lengths for decode steps that are replayed from a HIP graph: the lengths the
+        cache holds now go to a device array (allocated here on first use)."""
+        torch = self.torch
+        if getattr(self, "dev_lengths", None) is None:
+            self.dev_lengths = torch.zeros(kv_dev_lengths_bytes(self.cfg) // 4, dtype=torch.int32, device=self.device)
+        kv_cache_lengths_to_device(self.handle, self.dev_lengths.data_ptr(), self._stream())
+
+    def step_dev(self, layer: int, k_new, v_new, q, out) -> None:
+        """One decode step on the device-resident lengths: k_new, v_new [B, Hkv, d], q [B, Hq, d] 16-bit,
+        out [B, Hq, d] float32.  The cache's own lengths stay as they are (advance())."""
+        assert k_new.shape == v_new.shape and k_new.stride() == v_new.stride()
+        assert k_new.stride(2) == 1 and k_new.element_size() == 2 and q.is_contiguous() and out.is_contiguous()
+        kv_decode_step_dev(self.handle, layer, k_new.data_ptr(), v_new.data_ptr(), k_new.stride(0), k_new.stride(1),
+                           q.data_ptr(), out.data_ptr(), self.workspace.data_ptr(), self.ws_bytes, self._stream())
+
+    def advance(self, n_steps: int, layer: int = -1) -> None:
+        kv_cache_advance(self.handle, layer, n_steps)
 
     def lengths(self, layer: int, seq: Optional[int] = None):
         return kv_cache_len(self.handle, layer) if seq is None else kv_cache_len_seq(self.handle, layer, seq)

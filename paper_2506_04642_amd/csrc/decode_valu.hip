@@ -407,6 +407,9 @@ __global__ __launch_bounds__(256) void merge_kernel(DecodeArgs a)
     const long long o = ((long long)b * a.n_q_heads + h * a.g + i) * kHeadDim + 2 * lane;
     if (a.out16) *(uint32_t *)(a.out16 + o) = (uint32_t)narrow16_rne(r.x, a.geom.dtype) | ((uint32_t)narrow16_rne(r.y, a.geom.dtype) << 16);
     else *(float2 *)(a.out + o) = r;
+    // a decode step on device-resident lengths ends here: the state after the step becomes the current
+    // one (no workgroup of this kernel reads the lengths)
+    if (a.len_dev && blockIdx.x == 0 && lane == 0) a.len_dev[4 * a.batch] = (a.len_dev[4 * a.batch] & 1) ^ 1;
 }
 
 // code (token t, channel c) of a block's key (which = 0) or value side, from the packed words

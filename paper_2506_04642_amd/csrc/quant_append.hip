@@ -384,7 +384,16 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 8))
         const int which = a.sides ? a.sides - 1 : (it ^ (it / workers)) & 1, iu = a.sides ? it : it >> 1;
         const int u = iu % U, fb = iu / U;
         const int b = u / a.n_kv_heads, h = u % a.n_kv_heads;
-        unsigned char *rec = a.layer + record_offset(gm, a.n_kv_heads, a.b0 + b, h, a.first_block + fb);
+        int first_block = a.first_block;
+        if (a.len_dev) {
+            // a decode step on device-resident lengths: the sequence's raw buffer is compressed only if
+            // the step's token has filled it (the state before the step says so), as its next blocks
+            int nb, r;
+            dev_len(a.len_dev, a.batch, b, 0, gm.NB, gm.R, nb, r);
+            if (r + 1 != gm.R || nb * G + r + 1 > gm.NB * G) continue;
+            first_block = nb;
+        }
+        unsigned char *rec = a.layer + record_offset(gm, a.n_kv_heads, a.b0 + b, h, first_block + fb);
         const int base_off = which == 0 ? gm.k_codes : gm.v_codes; // start of this item's part of the record
         unsigned char *codes_out = img;
 
@@ -871,6 +880,35 @@ __global__ __launch_bounds__(kThreads) void resid_copy_kernel(AppendArgs a)
     *(uint4 *)(a.layer + off) = *(const uint4 *)src;
 }
 
+// A decode step's token, one per sequence, into the raw buffers, with the lengths on the device
+// (dev_len): unit u's rows go to position "raw tokens" of its sequence's current state, and the
+// state after the step goes to the other slot -- the token counted in, or, if it fills the raw
+// buffer, the buffer's tokens counted as packed blocks (the quantiser, launched next, compresses
+// them).  A sequence that has no room left keeps its state and takes no token.
+__global__ __launch_bounds__(kThreads) void step_store_kernel(AppendArgs a)
+{
+    const int u = blockIdx.x * 8 + (threadIdx.x >> 5);
+    if (u >= a.batch * a.n_kv_heads) return;
+    const int b = u / a.n_kv_heads, h = u % a.n_kv_heads;
+    const int lane = threadIdx.x & 31, which = lane >> 4, ch = lane & 15;
+    const LayerGeom &gm = a.geom;
+    int nb, r;
+    dev_len(a.len_dev, a.batch, b, 0, gm.NB, gm.R, nb, r);
+    const bool ok = r < gm.R && nb * gm.G + r + 1 <= gm.NB * gm.G;
+    const bool full = r + 1 == gm.R;
+    if (ok) {
+        const uint16_t *base = which == 0 ? a.k_new : a.v_new;
+        const uint16_t *src = base + (long long)b * a.stride_b + (long long)h * a.stride_h + ch * 8;
+        const long long off = (which == 0 ? gm.k_resid_off : gm.v_resid_off) + ((long long)u * gm.R + r) * (kHeadDim * 2) + ch * 16;
+        *(uint4 *)(a.layer + off) = *(const uint4 *)src;
+    }
+    if (h == 0 && lane == 0) {
+        int *after = a.len_dev + ((a.len_dev[4 * a.batch] & 1) ^ 1) * 2 * a.batch + 2 * b;
+        after[0] = ok && full ? nb + gm.R / gm.G : nb;
+        after[1] = ok ? (full ? 0 : r + 1) : r;
+    }
+}
+
 } // namespace
 
 template <int G, int GC, bool ROPE> hipError_t launch_flush_g(const AppendArgs &a, hipStream_t s)
@@ -997,6 +1035,21 @@ hipError_t launch_flush(const AppendArgs &a, hipStream_t s)
     if (a.geom.G == 32) return launch_flush_gc<32>(a, s);
     if (a.geom.G == 64) return launch_flush_gc<64>(a, s);
     return launch_flush_gc<128>(a, s);
+}
+
+bool step_store_supported(const LayerGeom &g)
+{
+    // the formats of the one-wavefront-per-item quantiser, dense placement, no mean over the heads
+    return g.G == 32 && g.k_bits == g.v_bits && g.k_bits != 16 && g.mean_mode != 1 && !g.table;
+}
+
+hipError_t launch_step_store(const AppendArgs &a, hipStream_t s)
+{
+    const int U = a.batch * a.n_kv_heads;
+    if (!a.len_dev || !step_store_supported(a.geom)) return hipErrorInvalidValue;
+    (void)hipGetLastError(); // drop any stale error left by earlier runtime calls of this thread
+    hipLaunchKernelGGL(step_store_kernel, dim3((U + 7) / 8), dim3(kThreads), 0, s, a);
+    return note_launch(hipGetLastError());
 }
 
 hipError_t launch_resid_copy(const AppendArgs &a, hipStream_t s)

@@ -34,6 +34,8 @@ struct kv_cache {
     int forced_splits = 0;
     size_t xhead_off = 0, xhead_bytes = 0; // cross-head mean: where its arrays start in the workspace, total size
     size_t xhead_xo_rel = 0;               // start of the value-mean output slots relative to xhead_off
+    int *len_dev = nullptr;                // device-resident lengths (kv_cache_lengths_to_device), [layer][dev_len_ints]
+    std::vector<int> len_image;            // what was last sent there (the copy's source stays alive)
 };
 
 namespace {
@@ -945,6 +947,114 @@ kv_status kv_decode_attn(const kv_cache *cache, int32_t layer, const void *q, fl
     kv_status st = kv_decode_attn_split(cache, layer, q, workspace, workspace_bytes, stream);
     if (st != KV_OK) return st;
     return kv_decode_attn_merge(cache, layer, out, workspace, workspace_bytes, stream);
+}
+
+kv_status kv_dev_lengths_bytes(const kv_config *cfg, size_t *bytes)
+{
+    if (!bytes) return KV_E_NULL;
+    kv_status st = check_config(cfg);
+    if (st != KV_OK) return st;
+    *bytes = (size_t)cfg->n_layers * dev_len_ints(cfg->batch) * sizeof(int);
+    return KV_OK;
+}
+
+kv_status kv_cache_lengths_to_device(kv_cache *cache, void *dev_lengths, void *stream)
+{
+    if (!cache || !dev_lengths) return KV_E_NULL;
+    if ((uintptr_t)dev_lengths % 16) return KV_E_ALIGN;
+    const kv_config &c = cache->cfg;
+    const int n = dev_len_ints(c.batch);
+    cache->len_image.assign((size_t)c.n_layers * n, 0);
+    for (int l = 0; l < c.n_layers; l++)
+        for (int p = 0; p < 2; p++)
+            for (int b = 0; b < c.batch; b++) {
+                cache->len_image[(size_t)l * n + p * 2 * c.batch + 2 * b] = cache->P(l, b) / c.group_tokens;
+                cache->len_image[(size_t)l * n + p * 2 * c.batch + 2 * b + 1] = cache->R(l, b);
+            }
+    if (note_launch(hipMemcpyAsync(dev_lengths, cache->len_image.data(), cache->len_image.size() * sizeof(int),
+                                   hipMemcpyHostToDevice, (hipStream_t)stream)) != hipSuccess)
+        return KV_E_HIP;
+    cache->len_dev = (int *)dev_lengths;
+    return KV_OK;
+}
+
+// what one decode step does to a sequence's lengths (tokens), or nothing if the sequence is full
+static void step_lengths(const kv_config &c, int *packed, int *resid)
+{
+    const int cap = c.max_tokens / c.group_tokens * c.group_tokens;
+    if (*resid >= c.resid_cap || *packed + *resid + 1 > cap) return;
+    if (*resid + 1 == c.resid_cap) {
+        *packed += c.resid_cap;
+        *resid = 0;
+    } else {
+        *resid += 1;
+    }
+}
+
+kv_status kv_cache_advance(kv_cache *cache, int32_t layer, int32_t n_steps)
+{
+    if (!cache) return KV_E_NULL;
+    if (n_steps < 0) return KV_E_BAD_CONFIG;
+    const kv_config &c = cache->cfg;
+    if (layer < -1 || layer >= c.n_layers) return KV_E_BAD_LAYER;
+    for (int l = layer < 0 ? 0 : layer; l < (layer < 0 ? c.n_layers : layer + 1); l++)
+        for (int b = 0; b < c.batch; b++)
+            for (int i = 0; i < n_steps; i++) step_lengths(c, &cache->P(l, b), &cache->R(l, b));
+    return KV_OK;
+}
+
+kv_status kv_decode_step_dev(const kv_cache *cache, int32_t layer, const void *k_new, const void *v_new,
+                             int64_t stride_b, int64_t stride_h, const void *q, float *out,
+                             void *workspace, size_t workspace_bytes, void *stream)
+{
+    kv_status st = layer_ok(cache, layer);
+    if (st != KV_OK) return st;
+    if (!k_new || !v_new || !q || !out) return KV_E_NULL;
+    if (!cache->len_dev) return KV_E_BAD_CONFIG; // kv_cache_lengths_to_device has not been called
+    const kv_config &c = cache->cfg;
+    if (((uintptr_t)k_new % 16) || ((uintptr_t)v_new % 16) || ((uintptr_t)q % 16) || ((uintptr_t)out % 16)) return KV_E_ALIGN;
+    if (stride_b % 8 || stride_h % 8) return KV_E_ALIGN;
+    if (stride_h < c.head_dim || stride_b < 0) return KV_E_BAD_CONFIG;
+    if (!cache->active.empty() || c.pool_blocks > 0) return KV_E_UNSUPPORTED;
+    if (!step_store_supported(cache->geom[layer]) || cache->decode_path == 1) return KV_E_UNSUPPORTED;
+
+    // the launches are sized for the lengths the host knows, one step on (a recorded call is replayed
+    // while the cache grows: the kernels take the true lengths from the device)
+    DecodeArgs a{};
+    {
+        kv_cache planned = *cache; // (host state only: vectors of lengths)
+        for (int b = 0; b < c.batch; b++) step_lengths(c, &planned.P(layer, b), &planned.R(layer, b));
+        st = fill_decode(&planned, layer, &a);
+        if (st != KV_OK) return st;
+    }
+    if (!use_mfma(cache, a)) return KV_E_UNSUPPORTED;
+    st = bind_workspace(cache, &a, workspace, workspace_bytes);
+    if (st != KV_OK) return st;
+    a.ragged = 0;
+    a.len_dev = cache->len_dev + (size_t)layer * dev_len_ints(c.batch);
+    a.q = (const uint16_t *)q;
+    a.out = out;
+
+    AppendArgs ap{};
+    ap.geom = cache->geom[layer];
+    ap.layer = cache->layers[layer];
+    ap.k_new = (const uint16_t *)k_new;
+    ap.v_new = (const uint16_t *)v_new;
+    ap.stride_b = stride_b;
+    ap.stride_t = 0;
+    ap.stride_h = stride_h;
+    ap.n_kv_heads = c.n_kv_heads;
+    ap.batch = c.batch;
+    ap.b0 = 0;
+    ap.r_old = c.resid_cap; // the quantiser takes every row of a block from the raw buffer
+    ap.first_block = 0;
+    ap.n_flush_blocks = c.resid_cap / c.group_tokens;
+    ap.len_dev = a.len_dev;
+    hipStream_t s = (hipStream_t)stream;
+    if (launch_step_store(ap, s) != hipSuccess) return KV_E_HIP;
+    if (launch_flush(ap, s) != hipSuccess) return KV_E_HIP;
+    if (launch_decode_split_mfma(a, s) != hipSuccess) return KV_E_HIP;
+    return launch_decode_merge(a, s) == hipSuccess ? KV_OK : KV_E_HIP;
 }
 
 kv_status kv_stream_read_probe(const void *buf, size_t bytes, void *sink8, void *stream)

@@ -45,6 +45,23 @@ __device__ __forceinline__ long long xmean_offset(const LayerGeom &g, int b, int
     return g.xmean_off + ((block_slot(g, b, blk) * 2 + which) * g.G * kHeadDim) * 2;
 }
 
+// Device-resident lengths of one layer (for decode steps replayed from a HIP graph, whose kernel
+// arguments cannot follow a growing cache): ints st[p * 2B + 2b] = packed blocks and st[p * 2B + 2b + 1]
+// = raw tokens of sequence b in state p (0 or 1), st[4B] = which state is the current one; B = batch.
+// A step's first kernel writes the state after the step into the other slot, its last one makes that
+// slot the current one.  Counts are clamped to the layer's capacity, so stale or foreign contents
+// cannot take an access out of the layer's buffers.
+constexpr int kDevLenPad = 4;
+__host__ __device__ inline int dev_len_ints(int batch) { return 4 * batch + kDevLenPad; }
+__device__ __forceinline__ void dev_len(const int *st, int batch, int b, int after, int nb_cap, int r_cap, int &nb, int &r)
+{
+    const int p = (st[4 * batch] & 1) ^ after;
+    nb = st[p * 2 * batch + 2 * b];
+    r = st[p * 2 * batch + 2 * b + 1];
+    nb = nb < 0 ? 0 : (nb > nb_cap ? nb_cap : nb);
+    r = r < 0 ? 0 : (r > r_cap ? r_cap : r);
+}
+
 struct AppendArgs {
     LayerGeom geom;
     unsigned char *layer;   // device base of the layer buffer
@@ -65,6 +82,11 @@ struct AppendArgs {
     // another kernel: the value projection fused with the compression, Alg. 1 step 3).  Only the
     // one-wavefront-per-item quantiser (blocks of 32 tokens, one width) and the raw copy take 1 or 2.
     int sides;
+    // not null: a decode step on device-resident lengths (dev_len).  The raw-row kernel stores one
+    // token per sequence at the sequence's own position and writes the state after the step; the
+    // quantiser compresses a sequence's raw buffer only if that token fills it, as block number
+    // "packed blocks" of the state before the step.
+    int *len_dev;
 };
 
 // Value projection fused with the compression (Alg. 1 step 3): one launch covers, for each sequence
@@ -115,12 +137,36 @@ struct DecodeArgs {
     // sequences of different lengths: n_blocks and r above are the maxima, the kernels take each
     // sequence's own counts from these (ragged == 0: every sequence has n_blocks and r)
     int ragged;
+    // not null: the kernels take every sequence's counts from these device-resident lengths (the state
+    // after the step's append, dev_len) instead; n_blocks and r only size the launch.  The merge makes
+    // that state the current one.
+    int *len_dev;
     uint16_t nb_seq[kMaxRaggedBatch], r_seq[kMaxRaggedBatch]; // 1 KiB of the kernel arguments
 };
 
 // packed blocks / raw tokens of sequence b
-__host__ __device__ inline int seq_blocks(const DecodeArgs &a, int b) { return a.ragged ? a.nb_seq[b] : a.n_blocks; }
-__host__ __device__ inline int seq_resid(const DecodeArgs &a, int b) { return a.ragged ? a.r_seq[b] : a.r; }
+__host__ __device__ inline int seq_blocks(const DecodeArgs &a, int b)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    if (a.len_dev) {
+        int nb, r;
+        dev_len(a.len_dev, a.batch, b, 1, a.geom.NB, a.geom.R, nb, r);
+        return nb;
+    }
+#endif
+    return a.ragged ? a.nb_seq[b] : a.n_blocks;
+}
+__host__ __device__ inline int seq_resid(const DecodeArgs &a, int b)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    if (a.len_dev) {
+        int nb, r;
+        dev_len(a.len_dev, a.batch, b, 1, a.geom.NB, a.geom.R, nb, r);
+        return r;
+    }
+#endif
+    return a.ragged ? a.r_seq[b] : a.r;
+}
 
 // reconstruction of a layer's contents: lengths and geometry as for a decode launch
 struct DequantArgs {
@@ -134,6 +180,8 @@ hipError_t note_launch(hipError_t e);
 
 hipError_t launch_flush(const AppendArgs &a, hipStream_t s);
 hipError_t launch_resid_copy(const AppendArgs &a, hipStream_t s);
+bool step_store_supported(const LayerGeom &g);                   // formats the device-length decode step serves
+hipError_t launch_step_store(const AppendArgs &a, hipStream_t s); // one token per sequence, lengths on the device
 bool compressv_supported(const LayerGeom &g); // formats the fused value projection serves
 hipError_t launch_compressv(const ProjectArgs &p, hipStream_t s);
 hipError_t launch_decode_split_valu(const DecodeArgs &a, hipStream_t s);

@@ -160,3 +160,29 @@ def test_paged_placement_and_active_set_host_checks(kv):
     finally:
         kv.kv_cache_destroy(h)
         kv.kv_cache_destroy(d)
+
+
+def test_device_length_steps_host_side(kv):
+    """Sizes, refusals and the descriptor's catching up (kv_cache_advance) -- no launch involved."""
+    cfg = _cfg(kv)
+    assert kv.kv_dev_lengths_bytes(cfg) == 2 * (4 * 2 + 4) * 4
+    h = kv.kv_cache_create(cfg, [0x100000, 0x200000])
+    try:
+        lib = kv._lib
+        K, V, Q, O, W = 0x300000, 0x400000, 0x500000, 0x600000, 0x700000
+        # before kv_cache_lengths_to_device there is nothing to step on
+        assert lib.kv_decode_step_dev(h, 0, K, V, 256, 128, Q, O, W, 1 << 20, None) == kv.KV_E_BAD_CONFIG
+        assert lib.kv_decode_step_dev(h, 0, None, V, 256, 128, Q, O, W, 1 << 20, None) == kv.KV_E_NULL
+        assert lib.kv_decode_step_dev(h, 7, K, V, 256, 128, Q, O, W, 1 << 20, None) == kv.KV_E_BAD_LAYER
+        assert lib.kv_cache_lengths_to_device(h, None, None) == kv.KV_E_NULL
+        assert lib.kv_cache_lengths_to_device(h, 0x800004, None) == kv.KV_E_ALIGN
+        assert lib.kv_cache_advance(h, 5, 1) == kv.KV_E_BAD_LAYER
+        assert lib.kv_cache_advance(h, 0, -1) == kv.KV_E_BAD_CONFIG
+        # 40 steps from empty: one block of 32 packed, 8 raw; the other layer untouched
+        kv.kv_cache_advance(h, 0, 40)
+        assert kv.kv_cache_len(h, 0) == (32, 8) and kv.kv_cache_len(h, 1) == (0, 0)
+        # every layer; a full sequence (capacity 256) stops growing
+        kv.kv_cache_advance(h, -1, 300)
+        assert kv.kv_cache_len(h, 0) == (256, 0) and kv.kv_cache_len(h, 1) == (256, 0)
+    finally:
+        kv.kv_cache_destroy(h)

@@ -1,7 +1,8 @@
 """The decode call (split + merge launches) recorded into a HIP graph and replayed: the library
 enqueues kernels only (no allocation, no synchronisation, no memset), so for a fixed cache state a
 serving loop can replay the call with new queries.  Every replay is checked against the eager call
-and the oracle, with eager work and synchronisations between the replays."""
+and the oracle, with eager work and synchronisations between the replays.  With the lengths on the
+device (kv_decode_step_dev) one recording replays whole decode steps while the cache grows."""
 import numpy as np
 import pytest
 
@@ -81,3 +82,81 @@ def test_calls_on_a_stream_of_their_own(kv, oracle):
     check_bytes(gpu, orc, 0)
     err = float(np.max(np.abs(out.cpu().numpy().astype(np.float64) - orc.attend(0, q))))
     assert err <= ATTN_TOL
+
+
+@pytest.mark.parametrize("mode", [CHAN, 2], ids=["channel_mean", "no_mean"])
+def test_growing_decode_loop_replayed_from_one_graph(kv, oracle, mode):
+    """Two layers (4- and 2-bit), three sequences of different lengths: one recording of
+    kv_decode_step_dev per layer is replayed for 40 steps, across at least one block flush of every
+    sequence; every step's output equals that of the eager one-call step on a twin cache, bit for
+    bit, and the oracle's within the tolerance; at the end the descriptor catches up and the cache's
+    bytes are the oracle's."""
+    import torch
+
+    print("case graph_steps mode=%d" % mode, flush=True)
+    B, Hq, Hkv, G, steps = 3, 8, 2, 32, 40
+    bits = (4, 2)
+    prompts = [5 * G + 30, 17, 2 * G + 3]  # sequence 0 fills its raw buffer on the second step
+    mk = lambda: make_pair(kv, oracle, L=2, B=B, Hq=Hq, Hkv=Hkv, T_max=12 * G, dtype=BF16, mode=mode, k_bits=bits)
+    gpu, orc = mk()
+    twin, _ = mk()
+    warm, _ = mk()
+    for c in (gpu, twin, warm):
+        kv.kv_set_decode_path(c.handle, 2)
+    for l in range(2):
+        for b, n in enumerate(prompts):
+            k, v = synth.make_kv(2000 + 10 * l + b, 1, n, Hkv, 128, BF16)
+            for c in (gpu, twin, warm):
+                c.append_seq(l, b, to_dev(k[0], BF16), to_dev(v[0], BF16))
+            orc.append_seq(l, b, k[0], v[0])
+    ks, vs = synth.make_kv(2100, B, steps, Hkv, 128, BF16)
+    kd, vd = to_dev(ks, BF16), to_dev(vs, BF16)
+    k_st = [torch.zeros((B, Hkv, 128), dtype=torch.bfloat16, device="cuda:0") for _ in range(2)]
+    v_st = [torch.zeros_like(k_st[0]) for _ in range(2)]
+    q_st = [torch.zeros((B, Hq, 128), dtype=torch.bfloat16, device="cuda:0") for _ in range(2)]
+    o_st = [torch.zeros((B, Hq, 128), dtype=torch.float32, device="cuda:0") for _ in range(2)]
+    # one-time queries (occupancy, attributes) happen outside the capture: a step on a throwaway cache
+    warm.lengths_to_device()
+    for l in range(2):
+        warm.step_dev(l, k_st[l], v_st[l], q_st[l], o_st[l])
+    torch.cuda.synchronize()
+    gpu.lengths_to_device()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(graph, stream=side):
+        for l in range(2):
+            gpu.step_dev(l, k_st[l], v_st[l], q_st[l], o_st[l])
+    torch.cuda.synchronize()
+    assert gpu.lengths(0, 0) == (5 * G, 30)  # the recording enqueued nothing yet and the descriptor stays behind
+    for s in range(steps):
+        qs = [synth.make_q(2200 + 2 * s + l, B, Hq, 128, BF16) for l in range(2)]
+        for l in range(2):
+            k_st[l].copy_(kd[:, s])
+            v_st[l].copy_(vd[:, s])
+            q_st[l].copy_(to_dev(qs[l], BF16))
+            o_st[l].zero_()
+        graph.replay()
+        eager = [twin.append_attend(l, kd[:, s:s + 1], vd[:, s:s + 1], to_dev(qs[l], BF16)) for l in range(2)]  # eager work between the replays
+        torch.cuda.synchronize()
+        for l in range(2):
+            assert torch.equal(o_st[l], eager[l]), "step %d layer %d differs from the eager step" % (s, l)
+            orc.append(l, ks[:, s:s + 1], vs[:, s:s + 1])
+            if s % 7 == 0 or s == steps - 1:
+                err = float(np.max(np.abs(o_st[l].cpu().numpy().astype(np.float64) - orc.attend(l, qs[l]))))
+                assert err <= ATTN_TOL, (s, l, err)
+    gpu.advance(steps)
+    for l in range(2):
+        for b in range(B):
+            assert gpu.lengths(l, b) == twin.lengths(l, b) == (orc.packed_len(l, b), orc.resid_len(l, b))
+    # the cache holds the oracle's bytes, and the descriptor is good for the ordinary calls again
+    for l in range(2):
+        img = orc.layer_image(l)
+        m = img["valid"]
+        for c in (gpu, twin):
+            got = c.layers[l].cpu().numpy()
+            bad = np.flatnonzero(got[m] != img["bytes"][m])
+            assert bad.size == 0, "layer %d: first differing valid byte at offset %d (%d differ)" % (l, np.flatnonzero(m)[bad[0]], bad.size)
+        q = to_dev(synth.make_q(2300 + l, B, Hq, 128, BF16), BF16)
+        assert torch.equal(gpu.attend(l, q), twin.attend(l, q))
