@@ -59,7 +59,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--separate-append", dest="fused_step", action="store_false",
                     help="append and attend as two calls per layer instead of the one-call decode step")
-    ap.add_argument("--legs", default="c0,c1,c3,c4,cross,compressv",
+    ap.add_argument("--legs", default="c0,c1,c3,c4,cross,compressv,graph",
                     help="other configurations measured after the headline one (comma list, or 'none')")
     ap.add_argument("--leg-steps", type=int, default=8, help="timed decode steps of each other configuration")
     return ap.parse_args()
@@ -314,6 +314,47 @@ def latency_leg(env, name, *, Hq, Hkv, T, dtype_name, reps=60):
            "note": "latency-bound: the packed cache fits the on-chip caches, GB/s is not an HBM rate"}
     cache.close()
     return res
+
+
+def graph_leg(env, fig, state, *, reps=4):
+    """Decode steps replayed from one HIP graph (kv_decode_step_dev: the kernels take the lengths from
+    device memory and advance them) on the cache of a finished decode workload, against that
+    workload's eager steps."""
+    torch, kv, stream = env.torch, env.kv, env.stream
+    cache, k_dec, q_dec = state["cache"], state["k_dec"], state["q_dec"]
+    L = len(state["bits"])
+    B, Hq, d = q_dec[0].shape
+    outs = [torch.empty((B, Hq, d), dtype=torch.float32, device=env.dev) for _ in range(L)]
+    ks = [k_dec[l][0][:, 0].contiguous() for l in range(L)]
+    vs = [k_dec[l][1][:, 0].contiguous() for l in range(L)]
+
+    def steps_all():
+        for l in range(L):
+            cache.step_dev(l, ks[l], vs[l], q_dec[l], outs[l])
+
+    cache.lengths_to_device()
+    steps_all()  # one eager step: one-time queries happen outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(graph, stream=side):
+        steps_all()
+    torch.cuda.synchronize()
+    graph.replay()  # warm
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        graph.replay()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    cache.advance(reps + 2)
+    nbytes = sum(kv.kv_decode_bytes(cache.handle, l) for l in range(L))
+    return {"workload": "the decode steps of the leg before, every layer's step recorded once (kv_decode_step_dev: store and "
+                        "quantise if the raw buffer fills, attention, merge) and replayed from one HIP graph",
+            "layers": L, "launches_per_step": 3 * L, "ms_per_step_graph": round(wall / reps * 1e3, 4),
+            "ms_per_step_eager": fig["ms_per_step"], "value_GBps_graph": round(nbytes * reps / wall / 1e9, 2),
+            "value_GBps_eager": fig["value_GBps"]}
 
 
 def compressv_leg(env, *, B, n, model_dim=4096, Hkv=8, bits=4, reps=6):
@@ -576,6 +617,12 @@ def main():
                 fx["workload"] = "headline shape with the mean over the kv heads (Eq. 1-2): first 8 layers of the bit map, batch 16, context 32768"
                 other["cross_head_mean"] = fx
                 release(env, sx)
+            elif leg == "graph":
+                # the headline shape's first 8 layers and the batch-1 long context, eager and replayed
+                fg, sg = run_decode_workload(env, L=8, B=16, Hq=32, Hkv=8, G=32, T0=32768, steps=ks, warmup=kw,
+                                             scheme="mixed248", seed=2000, shared_inputs=True)
+                other["graph_replay_headline_shape"] = graph_leg(env, fg, sg)
+                release(env, sg)
             elif leg == "compressv":
                 other["compressv_config2_shape"] = compressv_leg(env, B=16, n=4096)
                 other["compressv_config4_shape"] = compressv_leg(env, B=64, n=1024)

@@ -392,9 +392,9 @@ kv_status kv_decode_attn_static(const kv_cache *cache, int32_t layer, const void
  *       outside graph capture, after the prompts have been appended, and again after any other call
  *       that changes lengths (appends, resets).
  *   kv_decode_step_dev : as kv_append_decode_attn -- one token per sequence appended, then attention
- *       over everything cached -- with the same results bit for bit; enqueues four kernels (store the
- *       token and write the lengths after the step; compress the raw buffers that it filled, none on
- *       most steps; attention; merge, which also makes the new lengths current) and does NOT change
+ *       over everything cached -- with the same results bit for bit; enqueues three kernels (store the
+ *       token, write the lengths after the step and compress the raw buffers that the token filled,
+ *       none on most steps; attention; merge, which also makes the new lengths current) and does NOT change
  *       the descriptor's lengths.  A sequence that has no room for the token keeps its state and
  *       attends over what it has.  The launch shapes (split count) are planned from the
  *       descriptor's lengths: re-record after a few hundred steps to keep them near the best.

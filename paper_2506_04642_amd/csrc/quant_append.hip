@@ -43,6 +43,33 @@ __device__ __forceinline__ const uint16_t *src_row(const AppendArgs &a, int whic
     return base + (long long)b * a.stride_b + (long long)(ci - a.r_old) * a.stride_t + (long long)h * a.stride_h;
 }
 
+// A decode step's token, one per sequence, into the raw buffers, with the lengths on the device
+// (dev_len): unit u's rows go to position "raw tokens" of its sequence's current state, and the
+// state after the step goes to the other slot -- the token counted in, or, if it fills the raw
+// buffer, the buffer's tokens counted as packed blocks (the quantiser, launched next, compresses
+// them, in the same launch: flush_wave_kernel).  A sequence that has no room left keeps its state
+// and takes no token.  A group of 32 threads serves a unit.
+__device__ __forceinline__ void step_store_unit(const AppendArgs &a, int u)
+{
+    const int b = u / a.n_kv_heads, h = u % a.n_kv_heads;
+    const int lane = threadIdx.x & 31, which = lane >> 4, ch = lane & 15;
+    const LayerGeom &gm = a.geom;
+    int nb, r;
+    dev_len(a.len_dev, a.batch, b, 0, gm.NB, gm.R, nb, r);
+    const bool ok = r < gm.R && nb * gm.G + r + 1 <= gm.NB * gm.G;
+    const bool full = r + 1 == gm.R;
+    if (ok) {
+        const uint16_t *base = which == 0 ? a.k_new : a.v_new;
+        const uint16_t *src = base + (long long)b * a.stride_b + (long long)h * a.stride_h + ch * 8;
+        const long long off = (which == 0 ? gm.k_resid_off : gm.v_resid_off) + ((long long)u * gm.R + r) * (kHeadDim * 2) + ch * 16;
+        *(uint4 *)(a.layer + off) = *(const uint4 *)src;
+    }
+    if (h == 0 && lane == 0) {
+        int *after = a.len_dev + ((a.len_dev[4 * a.batch] & 1) ^ 1) * 2 * a.batch + 2 * b;
+        after[0] = ok && full ? nb + gm.R / gm.G : nb;
+        after[1] = ok ? (full ? 0 : r + 1) : r;
+    }
+}
 // (token, channel) of the first code of packed word w and whether the word runs along
 // channels (keys) or tokens (values); a word holds 32/bits codes.
 __device__ __forceinline__ void word_origin(int which, int bits, int G, int w, int &t0, int &c0)
@@ -377,6 +404,12 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 8))
     constexpr int IMG_BYTES = G * kHeadDim * BITS / 8 + 768;
     __shared__ __attribute__((aligned(16))) unsigned char lds_img[kThreads / 64][IMG_BYTES];
     unsigned char *img = lds_img[wave];
+
+    // a decode step on device-resident lengths: first the step's token goes into the raw buffers and
+    // the lengths after the step are written (nothing below reads what this writes: a buffer that the
+    // token fills is compressed from its first rows and the caller's row)
+    if (a.len_dev)
+        for (int su = (int)blockIdx.x * 8 + (int)(threadIdx.x >> 5); su < U; su += (int)gridDim.x * 8) step_store_unit(a, su);
 
     for (int it = (int)blockIdx.x * (kThreads / 64) + wave; it < n_items; it += workers) {
         // keys and values cost differently: a worker alternates between them (workers is even)
@@ -880,35 +913,6 @@ __global__ __launch_bounds__(kThreads) void resid_copy_kernel(AppendArgs a)
     *(uint4 *)(a.layer + off) = *(const uint4 *)src;
 }
 
-// A decode step's token, one per sequence, into the raw buffers, with the lengths on the device
-// (dev_len): unit u's rows go to position "raw tokens" of its sequence's current state, and the
-// state after the step goes to the other slot -- the token counted in, or, if it fills the raw
-// buffer, the buffer's tokens counted as packed blocks (the quantiser, launched next, compresses
-// them).  A sequence that has no room left keeps its state and takes no token.
-__global__ __launch_bounds__(kThreads) void step_store_kernel(AppendArgs a)
-{
-    const int u = blockIdx.x * 8 + (threadIdx.x >> 5);
-    if (u >= a.batch * a.n_kv_heads) return;
-    const int b = u / a.n_kv_heads, h = u % a.n_kv_heads;
-    const int lane = threadIdx.x & 31, which = lane >> 4, ch = lane & 15;
-    const LayerGeom &gm = a.geom;
-    int nb, r;
-    dev_len(a.len_dev, a.batch, b, 0, gm.NB, gm.R, nb, r);
-    const bool ok = r < gm.R && nb * gm.G + r + 1 <= gm.NB * gm.G;
-    const bool full = r + 1 == gm.R;
-    if (ok) {
-        const uint16_t *base = which == 0 ? a.k_new : a.v_new;
-        const uint16_t *src = base + (long long)b * a.stride_b + (long long)h * a.stride_h + ch * 8;
-        const long long off = (which == 0 ? gm.k_resid_off : gm.v_resid_off) + ((long long)u * gm.R + r) * (kHeadDim * 2) + ch * 16;
-        *(uint4 *)(a.layer + off) = *(const uint4 *)src;
-    }
-    if (h == 0 && lane == 0) {
-        int *after = a.len_dev + ((a.len_dev[4 * a.batch] & 1) ^ 1) * 2 * a.batch + 2 * b;
-        after[0] = ok && full ? nb + gm.R / gm.G : nb;
-        after[1] = ok ? (full ? 0 : r + 1) : r;
-    }
-}
-
 } // namespace
 
 template <int G, int GC, bool ROPE> hipError_t launch_flush_g(const AppendArgs &a, hipStream_t s)
@@ -1041,15 +1045,6 @@ bool step_store_supported(const LayerGeom &g)
 {
     // the formats of the one-wavefront-per-item quantiser, dense placement, no mean over the heads
     return g.G == 32 && g.k_bits == g.v_bits && g.k_bits != 16 && g.mean_mode != 1 && !g.table;
-}
-
-hipError_t launch_step_store(const AppendArgs &a, hipStream_t s)
-{
-    const int U = a.batch * a.n_kv_heads;
-    if (!a.len_dev || !step_store_supported(a.geom)) return hipErrorInvalidValue;
-    (void)hipGetLastError(); // drop any stale error left by earlier runtime calls of this thread
-    hipLaunchKernelGGL(step_store_kernel, dim3((U + 7) / 8), dim3(kThreads), 0, s, a);
-    return note_launch(hipGetLastError());
 }
 
 hipError_t launch_resid_copy(const AppendArgs &a, hipStream_t s)

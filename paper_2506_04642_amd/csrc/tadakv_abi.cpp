@@ -1046,13 +1046,12 @@ kv_status kv_decode_step_dev(const kv_cache *cache, int32_t layer, const void *k
     ap.n_kv_heads = c.n_kv_heads;
     ap.batch = c.batch;
     ap.b0 = 0;
-    ap.r_old = c.resid_cap; // the quantiser takes every row of a block from the raw buffer
+    ap.r_old = c.resid_cap - 1; // a buffer that the token fills: its rows, then the caller's row
     ap.first_block = 0;
     ap.n_flush_blocks = c.resid_cap / c.group_tokens;
     ap.len_dev = a.len_dev;
     hipStream_t s = (hipStream_t)stream;
-    if (launch_step_store(ap, s) != hipSuccess) return KV_E_HIP;
-    if (launch_flush(ap, s) != hipSuccess) return KV_E_HIP;
+    if (launch_flush(ap, s) != hipSuccess) return KV_E_HIP; // (stores the token, too)
     if (launch_decode_split_mfma(a, s) != hipSuccess) return KV_E_HIP;
     return launch_decode_merge(a, s) == hipSuccess ? KV_OK : KV_E_HIP;
 }

@@ -82,10 +82,10 @@ struct AppendArgs {
     // another kernel: the value projection fused with the compression, Alg. 1 step 3).  Only the
     // one-wavefront-per-item quantiser (blocks of 32 tokens, one width) and the raw copy take 1 or 2.
     int sides;
-    // not null: a decode step on device-resident lengths (dev_len).  The raw-row kernel stores one
-    // token per sequence at the sequence's own position and writes the state after the step; the
-    // quantiser compresses a sequence's raw buffer only if that token fills it, as block number
-    // "packed blocks" of the state before the step.
+    // not null: a decode step on device-resident lengths (dev_len).  The quantiser's launch first
+    // stores one token per sequence at the sequence's own position in the raw buffer and writes the
+    // state after the step; then it compresses a sequence's raw buffer only if that token fills it
+    // (r_old = R - 1: the last row from the caller), as block number "packed blocks" of the state before.
     int *len_dev;
 };
 
@@ -180,8 +180,7 @@ hipError_t note_launch(hipError_t e);
 
 hipError_t launch_flush(const AppendArgs &a, hipStream_t s);
 hipError_t launch_resid_copy(const AppendArgs &a, hipStream_t s);
-bool step_store_supported(const LayerGeom &g);                   // formats the device-length decode step serves
-hipError_t launch_step_store(const AppendArgs &a, hipStream_t s); // one token per sequence, lengths on the device
+bool step_store_supported(const LayerGeom &g); // formats the device-length decode step serves (launch_flush with len_dev)
 bool compressv_supported(const LayerGeom &g); // formats the fused value projection serves
 hipError_t launch_compressv(const ProjectArgs &p, hipStream_t s);
 hipError_t launch_decode_split_valu(const DecodeArgs &a, hipStream_t s);
