@@ -160,3 +160,38 @@ def test_growing_decode_loop_replayed_from_one_graph(kv, oracle, mode):
             assert bad.size == 0, "layer %d: first differing valid byte at offset %d (%d differ)" % (l, np.flatnonzero(m)[bad[0]], bad.size)
         q = to_dev(synth.make_q(2300 + l, B, Hq, 128, BF16), BF16)
         assert torch.equal(gpu.attend(l, q), twin.attend(l, q))
+
+
+def test_device_length_steps_stop_at_capacity(kv, oracle):
+    """A sequence that has no room for another token keeps its state: the step attends over what is
+    cached (the eager call would refuse the whole step with KV_E_CAPACITY), and kv_cache_advance
+    follows the same rule."""
+    import torch
+
+    print("case graph_steps_capacity", flush=True)
+    B, Hq, Hkv, G = 2, 8, 2, 32
+    gpu, orc = make_pair(kv, oracle, B=B, Hq=Hq, Hkv=Hkv, T_max=2 * G, dtype=BF16, mode=CHAN, k_bits=(4,))
+    kv.kv_set_decode_path(gpu.handle, 2)
+    k, v = synth.make_kv(2500, B, 2 * G + 4, Hkv, 128, BF16)
+    kd, vd = to_dev(k, BF16), to_dev(v, BF16)
+    for b, n in enumerate((G + 28, 9)):  # sequence 0 is four tokens short of its capacity
+        gpu.append_seq(0, b, kd[b, :n], vd[b, :n])
+        orc.append_seq(0, b, k[b, :n], v[b, :n])
+    gpu.lengths_to_device()
+    out = torch.zeros((B, Hq, 128), dtype=torch.float32, device="cuda:0")
+    for s in range(7):
+        q = synth.make_q(2600 + s, B, Hq, 128, BF16)
+        gpu.step_dev(0, kd[:, G + 28 + s], vd[:, G + 28 + s], to_dev(q, BF16), out)
+        torch.cuda.synchronize()
+        for b, n0 in enumerate((G + 28, 9)):
+            if n0 + s + 1 <= 2 * G:
+                t = G + 28 + s
+                orc.append_seq(0, b, k[b, t:t + 1], v[b, t:t + 1])
+        err = float(np.max(np.abs(out.cpu().numpy().astype(np.float64) - orc.attend(0, q))))
+        assert err <= ATTN_TOL, (s, err)
+    gpu.advance(7)
+    assert gpu.lengths(0, 0) == (2 * G, 0) == (orc.packed_len(0, 0), orc.resid_len(0, 0))
+    assert gpu.lengths(0, 1) == (0, 16) == (orc.packed_len(0, 1), orc.resid_len(0, 1))
+    with pytest.raises(kv.KVError) as e:
+        gpu.append(0, kd[:, :1], vd[:, :1])
+    assert e.value.status == kv.KV_E_CAPACITY
