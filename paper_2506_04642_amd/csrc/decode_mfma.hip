@@ -330,7 +330,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
 {
     static_assert(!(XH && MEAN), "cross-head layers store no per-record mean");
     constexpr bool XF = XH == 2; // both mean terms in this kernel, a wave per kv head
-    static_assert(!XF || (!PG && GS <= 64), "the fused cross-head form takes dense placement and blocks of 32 or 64 tokens");
+    static_assert(!XF || !PG, "the fused cross-head form takes dense placement");
     constexpr int CW = XF ? 1 : NW;          // waves that share a unit's chunks
     constexpr bool H2 = GS == 128;         // a block is worked on as two halves
     constexpr int G = H2 ? 64 : GS;        // tokens per block as the arithmetic sees it
@@ -409,15 +409,17 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
     const int w0 = sp * NBC;          // first block of local chunk 0
     const int cstride = ns * NBC;     // blocks between consecutive local chunks
     // H2: the splits interleave block by block, and a wave's chunks 2 k and 2 k + 1 are the two
-    // halves of its k-th block; n_chunks is then the wave's own bound (wave + NW * its chunks)
+    // halves of its k-th block; n_chunks is then the wave's own bound (cw0 + CW * its chunks; the
+    // CW waves that share a unit's chunks: all of the workgroup's, or, in the fused cross-head form,
+    // this one alone)
     const int blocks_sp = sp * HB < chunks_total ? (chunks_total / HB - sp + ns - 1) / ns : 0; // H2 only
-    const int n_chunks = H2 ? wave + NW * 2 * ((blocks_sp - wave + NW - 1) / NW)
+    const int n_chunks = H2 ? cw0 + CW * 2 * ((blocks_sp - cw0 + CW - 1) / CW)
                             : (sp < chunks_total ? (chunks_total - sp + ns - 1) / ns : 0);
-    // first block (as the arithmetic counts them) of this wave's local chunk ci = wave + NW * k
+    // first block (as the arithmetic counts them) of this wave's local chunk ci = cw0 + CW * k
     auto blk_of = [&](int ci) {
         if (!H2) return w0 + ci * cstride;
-        const int k = (ci - wave) / NW;
-        return 2 * (sp + ns * (wave + NW * (k >> 1))) + (k & 1);
+        const int k = (ci - cw0) / CW;
+        return 2 * (sp + ns * (cw0 + CW * (k >> 1))) + (k & 1);
     };
     const unsigned char *unit_base = a.layer + (long long)u * gm.NB * SREC;
 
@@ -479,8 +481,10 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
     auto mean_row_src = [&](int which, int blk0, int r) {
         int blk = blk0 + r / G;
         blk = blk < b_end ? blk : blk0;
-        // (dense placement: block slot = sequence * blocks per sequence + block)
-        return a.layer + gm.xmean_off + ((((long long)b * gm.NB + blk) * 2 + which) * G + r % G) * (kHeadDim * 2);
+        // (dense placement: block slot = sequence * blocks per sequence + block; with blocks of 128
+        // tokens blk counts their halves)
+        return a.layer + gm.xmean_off +
+               ((((long long)b * gm.NB + blk / HB) * 2 + which) * GS + (blk % HB) * G + r % G) * (kHeadDim * 2);
     };
 
     // ---- query of heads 4*hg + row: this lane's eight channels, widened and as binary16 pairs
@@ -1281,11 +1285,11 @@ struct DoMatch {
 };
 
 // Does the layer get the fused cross-head form (both mean terms inside the split kernel)?  It takes a
-// wave per kv head, 4 or 8 kv heads, dense placement and blocks of 32 or 64 tokens.
+// wave per kv head, 4 or 8 kv heads and dense placement.
 bool xhead_fused_fmt(const DecodeArgs &a)
 {
     const LayerGeom &g = a.geom;
-    return g.mean_mode == 1 && !g.table && (g.G == 32 || g.G == 64) && (a.n_kv_heads == 4 || a.n_kv_heads == 8);
+    return g.mean_mode == 1 && !g.table && (a.n_kv_heads == 4 || a.n_kv_heads == 8);
 }
 
 template <int B, int G, int GC, bool PG, class F> void pick_mean_heads_pg(const DecodeArgs &a, F &f)
@@ -1332,10 +1336,14 @@ template <class F> void pick(const DecodeArgs &a, F &f)
             if (bits == 2) pick_fused<2, 32, 32>(a, f);
             else if (bits == 4) pick_fused<4, 32, 32>(a, f);
             else pick_fused<8, 32, 32>(a, f);
-        } else {
+        } else if (a.geom.G == 64) {
             if (bits == 2) pick_fused<2, 64, 64>(a, f);
             else if (bits == 4) pick_fused<4, 64, 64>(a, f);
             else pick_fused<8, 64, 64>(a, f);
+        } else {
+            if (bits == 2) pick_fused<2, 128, 128>(a, f);
+            else if (bits == 4) pick_fused<4, 128, 128>(a, f);
+            else pick_fused<8, 128, 128>(a, f);
         }
         return;
     }

@@ -515,13 +515,13 @@ def test_cross_head_mean_mixed_layers_bf16(kv, oracle):
 @pytest.mark.parametrize("decode_path", [2], indirect=True, ids=["mfma"])
 @pytest.mark.parametrize("bits,G,g,T,Hkv", [(4, 32, 3, 2000 + 13, 4), (2, 32, 5, 1056, 4), (8, 64, 4, 1600 + 40, 4),
                                             (4, 64, 8, 704, 4), (4, 128, 4, 2048 + 128 + 50, 4), (2, 128, 8, 1280, 4),
-                                            (8, 128, 3, 1664 + 7, 4), (8, 32, 4, 1500 + 9, 8), (2, 32, 8, 1056 + 32, 8),
+                                            (8, 128, 3, 1664 + 7, 4), (4, 128, 6, 1536 + 128 + 9, 8), (2, 128, 2, 2304 + 1, 8), (8, 32, 4, 1500 + 9, 8), (2, 32, 8, 1056 + 32, 8),
                                             (4, 64, 5, 1344 + 3, 8), (8, 64, 8, 960, 8), (2, 64, 2, 2048 + 70, 8),
                                             (4, 32, 4, 1120 + 31, 8), (4, 32, 2, 700, 2)])
 def test_cross_head_mean_on_the_matrix_cores(kv, oracle, decode_path, bits, G, g, T, Hkv):
     """Cross-head mean with the deviations on the matrix-core kernel; the two dense mean terms inside
-    that kernel (4 or 8 kv heads, blocks of 32 or 64 tokens: a workgroup of 8 waves, of 4 waves, or two
-    workgroups of 4 that share a sequence's split) or in kernels of their own (the other formats);
+    that kernel (4 or 8 kv heads: a workgroup of 8 waves, of 4 waves, or two workgroups of 4 that share
+    a sequence's split; blocks of 128 tokens as two halves) or in kernels of their own (other head counts);
     several splits, an odd block count, a raw tail."""
     print("case cross_head_mfma bits=%d G=%d g=%d T=%d Hkv=%d" % (bits, G, g, T, Hkv), flush=True)
     gpu, orc = make_pair(kv, oracle, B=2, Hq=Hkv * g, Hkv=Hkv, T_max=(T // G + 2) * G, G=G, Gc=G, dtype=BF16, mode=CROSS,
@@ -546,8 +546,8 @@ def test_cross_head_mean_with_a_forced_split_count(kv, oracle, decode_path):
     import torch
 
     print("case cross_head_forced_splits", flush=True)
-    B, Hkv, g, T = 16, 8, 4, 128 * 32 + 5
-    # (blocks of 128 tokens: a format whose dense mean terms run as kernels of their own and pass through the workspace)
+    B, Hkv, g, T = 16, 16, 2, 128 * 32 + 5
+    # (16 kv heads: a format whose dense mean terms run as kernels of their own and pass through the workspace)
     gpu, orc = make_pair(kv, oracle, B=B, Hq=Hkv * g, Hkv=Hkv, T_max=33 * 128, G=128, Gc=128, dtype=BF16, mode=CROSS,
                          k_bits=(4,))
     k, v = synth.make_kv(611, B, T, Hkv, 128, BF16)
@@ -565,7 +565,7 @@ def test_cross_head_mean_with_a_forced_split_count(kv, oracle, decode_path):
     assert e.value.status == kv.KV_E_WORKSPACE
     gpu.workspace = torch.empty(need, dtype=torch.uint8, device="cuda:0")
     gpu.ws_bytes = need
-    check_attention(gpu, orc, 0, q, BF16, units=[(0, 0), (7, 3), (15, 7)])
+    check_attention(gpu, orc, 0, q, BF16, units=[(0, 0), (7, 3), (15, 13)])
 
 
 # ------------------------------------------------------------------ matrix-core kernels, forced
