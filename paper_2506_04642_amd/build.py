@@ -20,7 +20,8 @@ UNITS = [
     ("decode_valu.hip", []),
     # matrix-instruction results go straight to ordinary vector registers; the direct-to-LDS fetches
     # are issued by hand and name M0 as clobbered, which the compiler remarks on at every use
-    ("decode_mfma.hip", ["-mllvm", "-amdgpu-mfma-vgpr-form", "-Wno-inline-asm"]),
+    # (the assembly text is kept next to the object and read by verify_hand_loads after the compile)
+    ("decode_mfma.hip", ["-mllvm", "-amdgpu-mfma-vgpr-form", "-Wno-inline-asm", "-save-temps=obj"]),
     ("xhead_dense.hip", []),
     ("stream_probe.hip", []),
 ]
@@ -57,6 +58,20 @@ def build_library(force: bool = True, verbose: bool = False) -> str:
             raise RuntimeError("hipcc failed: %s\n%s" % (" ".join(cmd), out))
         if verbose and out.strip():
             print(out)
+    # the kernels that issue loads by hand: the compiler must have left the destinations alone
+    import importlib.util
+
+    spec = importlib.util.spec_from_file_location("verify_hand_loads", os.path.join(HERE, "verify_hand_loads.py"))
+    _v = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(_v)  # (by path: this file also runs as a script)
+
+    asm = os.path.join(objdir, "decode_mfma-hip-amdgcn-amd-amdhsa-gfx950.s")
+    checked = _v.verify(asm)
+    if verbose:
+        print("verify_hand_loads: %d kernels, %d global requests, %d LDS reads" % checked)
+    for f in os.listdir(objdir):
+        if f.startswith("decode_mfma-") or f.startswith("decode_mfma.hip-"):
+            os.remove(os.path.join(objdir, f))
     cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
     subprocess.run(cmd, check=True)
     return LIB

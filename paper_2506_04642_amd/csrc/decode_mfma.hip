@@ -228,14 +228,44 @@ __device__ __forceinline__ uint32_t lds_addr(const void *p)
 {
     return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)p;
 }
+// Progress counters in LDS, one per wave of a workgroup, for exchanges that are not fenced by a
+// barrier: a wave publishes how far it has come (after its own LDS traffic has completed), and a
+// wave that needs the others' data polls until every counter has reached what it needs.  All waves
+// of a workgroup are resident together and the wave that is furthest behind never waits (it needs
+// nothing that a wave ahead of it has yet to produce), so every wait ends; the spin limit is a
+// second line of defence only.
+__device__ __forceinline__ void progress_publish(uint32_t addr, uint32_t val, int lane)
+{
+    wave_lds_fence();
+    if (lane == 0) asm volatile("ds_write_b32 %0, %1" : : "v"(addr), "v"(val) : "memory");
+}
+template <int NW> __device__ __forceinline__ void progress_wait_all(uint32_t base, uint32_t need, int lane)
+{
+    const uint32_t ea = base + 4 * (lane & (NW - 1));
+    for (int spin = 0; spin < (1 << 20); spin++) {
+        uint32_t v;
+        asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(ea) : "memory");
+        if (__builtin_amdgcn_ballot_w64(v < need) == 0) break;
+        __builtin_amdgcn_s_sleep(1);
+    }
+}
 // Global loads issued by hand, for data wanted long after younger fetches have been issued under a
 // condition: the compiler, which has to assume either outcome of the condition, would wait for
 // every outstanding fetch before the first use.  A result must not be used before glb_wait_but
 // (N = the number of fetches issued since, which may stay outstanding) and then glb_got of every
 // register.
-__device__ __forceinline__ void glb_get16(u32x4 &dst, const void *p)
+// Between the request and the hand-over the compiler takes the destination for a value that exists:
+// under register pressure it may move it (into another register, into the accumulation file), and
+// then the data arrives in a register that has been given to something else -- an address, say.
+// Where the destinations stay awaited across much of an iteration (ACC) they are therefore
+// accumulation registers, of which these kernels use few: nothing competes for them, they take no
+// part in the pressure on the ordinary file, and what needs the data in an ordinary register copies
+// it after the hand-over.  In every case the build reads the generated code and refuses it if any
+// instruction between a request and its hand-over names a destination.
+template <bool ACC> __device__ __forceinline__ void glb_get16(u32x4 &dst, const void *p)
 {
-    asm volatile("global_load_dwordx4 %0, %1, off ; by hand" : "=v"(dst) : "v"(p));
+    if constexpr (ACC) asm volatile("global_load_dwordx4 %0, %1, off ; by hand" : "=a"(dst) : "v"(p));
+    else asm volatile("global_load_dwordx4 %0, %1, off ; by hand" : "=v"(dst) : "v"(p));
 }
 // (the wait and the hand-over of the registers are separate so that a wait chosen by a condition
 // is followed by ONE hand-over per register: registers handed over on either side of a branch would
@@ -245,7 +275,11 @@ template <int N> __device__ __forceinline__ void glb_wait_but()
     static_assert(N >= 0 && N < 64, "vmcnt is a six-bit counter");
     asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
 }
-__device__ __forceinline__ void glb_got(u32x4 &r) { asm volatile("; by hand %0" : "+v"(r) : : "memory"); }
+template <bool ACC> __device__ __forceinline__ void glb_got(u32x4 &r)
+{
+    if constexpr (ACC) asm volatile("; by hand %0" : "+a"(r) : : "memory");
+    else asm volatile("; by hand %0" : "+v"(r) : : "memory");
+}
 // Blocks of 128 tokens are read as two halves of 64: the pieces of half hf of the record at src
 // (its key codes, the block's key metadata, its runs of value codes -- 1 KiB per group of channel
 // tiles --, its value metadata, the block's value mean) are placed so that the staging buffer
@@ -332,6 +366,13 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
     constexpr bool XF = XH == 2; // both mean terms in this kernel, a wave per kv head
     static_assert(!XF || !PG, "the fused cross-head form takes dense placement");
     constexpr int CW = XF ? 1 : NW;          // waves that share a unit's chunks
+    // fused cross-head form in workgroups of four waves: the waves exchange through counters instead of
+    // a barrier per chunk and may drift apart by one chunk.  These instances run one wave per SIMD (all
+    // but the 2-bit one with up to four query heads per kv head, which fits a compute unit twice, loses
+    // 6 of 160 us per layer to the barrier and gains nothing measurable from the counters): a wave that
+    // waits at a barrier for the slowest chunk of the round leaves its SIMD idle
+    constexpr bool DR = XF && NW == 4 && !(B == 2 && NHG == 1);
+    constexpr int XSL = DR ? 3 : 2;          // copies of every exchange buffer
     constexpr bool H2 = GS == 128;         // a block is worked on as two halves
     constexpr int G = H2 ? 64 : GS;        // tokens per block as the arithmetic sees it
     constexpr int HB = GS / G;             // such blocks per block of the cache
@@ -356,18 +397,18 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
     constexpr int HP = 4 * NHG, HQP = NW * HP, NRB = XF ? HQP / 16 : 1;
     constexpr int NCT = XF ? 8 / NW : 1;    // channel tiles of the value-mean product per wave
     constexpr int PB_ROW = 144;             // bytes of a row of 64 binary16 (+ 8 of padding)
-    // shared by the waves, all [parity of the chunk]...: scores q . mean_K [head][64 tokens] binary32
+    // shared by the waves, all [parity of the chunk (chunk mod 3 with counters)]...: scores q . mean_K [head][64 tokens] binary32
     // (the 16-token groups of a row rotated by the head so that writers and readers spread over the
     // banks), softmax weights [hi | lo][head][64 + 8] binary16, rescale factors [head]; per wave: its
     // strip of the value-mean tile, transposed, [NCT][16 channels][64 + 8 tokens] binary16
-    constexpr int XS_DW = XF ? 2 * HQP * 64 : 0, PB_DW = XF ? 2 * 2 * HQP * PB_ROW / 4 : 0, AL_DW = XF ? 2 * HQP : 0;
+    constexpr int XS_DW = XF ? XSL * HQP * 64 : 0, PB_DW = XF ? XSL * 2 * HQP * PB_ROW / 4 : 0, AL_DW = XF ? XSL * HQP : 0;
     constexpr int VT_DW = XF ? NCT * 16 * PB_ROW / 4 : 0;
     constexpr int LDS_DW = NW * WAVE_DW;
 
     __shared__ __attribute__((aligned(16))) uint32_t lds_all[LDS_DW];
     // the exchange buffers of the fused cross-head form
     __shared__ __attribute__((aligned(16))) uint32_t lds_xs[XF ? XS_DW : 1], lds_pb[XF ? PB_DW : 1], lds_al[XF ? AL_DW : 1],
-        lds_vt[XF ? NW * VT_DW : 1];
+        lds_vt[XF ? NW * VT_DW : 1], lds_ev[XF ? 16 : 1];
 
     const LayerGeom &gm = a.geom;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -542,7 +583,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
 #pragma unroll
         for (int e = 0; e < NHG; e++)
 #pragma unroll
-            for (int ks = 0; ks < 4; ks++) glb_get16(kb[e][ks], mean_row_src(0, blk0, km_row[e]) + 64 * ks + 16 * row);
+            for (int ks = 0; ks < 4; ks++) glb_get16<DR>(kb[e][ks], mean_row_src(0, blk0, km_row[e]) + 64 * ks + 16 * row);
     };
     auto kmean_scores = [&](const u32x4 (&kb)[NHG][4], int par) {
         float *xs = (float *)lds_xs + par * (HQP * 64);
@@ -589,19 +630,90 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
         for (int rb = 0; rb < NRB; rb++)
 #pragma unroll
             for (int c = 0; c < NCT; c++) accv[rb][c] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
-        if (n_chunks > 0) { // the scores of the first chunk
-            u32x4 kb[NHG][4];
-            kmean_fetch(kb, blk_of(0));
-            glb_wait_but<0>();
+        // the scores of the first chunk (of the first two when the waves drift: there the scores
+        // are worked out two chunks ahead)
 #pragma unroll
-            for (int e = 0; e < NHG; e++)
+        for (int c0 = 0; c0 < (DR ? 2 : 1); c0++)
+            if (c0 < n_chunks) {
+                u32x4 kb[NHG][4];
+                kmean_fetch(kb, blk_of(c0));
+                glb_wait_but<0>();
 #pragma unroll
-                for (int ks = 0; ks < 4; ks++) glb_got(kb[e][ks]);
-            kmean_scores(kb, 0);
-        }
+                for (int e = 0; e < NHG; e++)
+#pragma unroll
+                    for (int ks = 0; ks < 4; ks++) glb_got<DR>(kb[e][ks]);
+                kmean_scores(kb, c0);
+            }
+        if (DR && lane < 16) lds_ev[lane] = 0u;
         wave_lds_fence();
         __builtin_amdgcn_s_barrier();
     }
+    // the value-mean product of one chunk: this wave's strip of the tile (as it came from memory, lane =
+    // token) goes through the wave's own LDS transposed, [channel][token], so that the token index is the
+    // contraction index of the B operand ...
+    auto vt_store = [&](const u32x4 (&vm_)[NCT][2]) {
+        uint16_t *vt = (uint16_t *)lds_vt + wave * (NCT * 16 * (PB_ROW / 2));
+#pragma unroll
+        for (int c = 0; c < NCT; c++)
+#pragma unroll
+            for (int hf = 0; hf < 2; hf++)
+#pragma unroll
+                for (int k = 0; k < 4; k++) {
+                    const uint32_t w = vm_[c][hf][k];
+                    vt[(c * 16 + 8 * hf + 2 * k) * (PB_ROW / 2) + lane] = (uint16_t)(w & 0xFFFFu);
+                    vt[(c * 16 + 8 * hf + 2 * k + 1) * (PB_ROW / 2) + lane] = (uint16_t)(w >> 16);
+                }
+        wave_lds_fence();
+    };
+    // ... and meets everybody's weights and rescale factors of that chunk (exchange buffers, copy sl)
+    auto vmean_add = [&](int sl) {
+        const uint16_t *vt = (const uint16_t *)lds_vt + wave * (NCT * 16 * (PB_ROW / 2));
+        const _Float16 *pb = (const _Float16 *)lds_pb + sl * (2 * HQP * (PB_ROW / 2));
+        const float *al = (const float *)lds_al + sl * HQP;
+        // (the reads by hand: the wave's next chunk is on its way into LDS)
+        const uint32_t vta = lds_addr(vt) + n * PB_ROW + 16 * row; // channel n of a tile, tokens 8 row .. + 7
+        const uint32_t pba = lds_addr(pb) + n * PB_ROW + 16 * row; // A operand: row n = head n of a block, tokens 8 row .. + 7
+        const uint32_t ala = lds_addr(al) + 16 * row;              // factors of heads 4 row .. + 3 of a block
+        u32x4 vb[NCT][2], ph[NRB][2], pl[NRB][2], al4[NRB];
+        lds_get16<0>(vb[0][0], vta);
+        lds_get16<64>(vb[0][1], vta);
+        if (NCT == 2) {
+            lds_get16<16 * PB_ROW>(vb[NCT - 1][0], vta);
+            lds_get16<16 * PB_ROW + 64>(vb[NCT - 1][1], vta);
+        }
+        static_assert(NCT <= 2 && NRB <= 2, "operand reads of the value-mean product are written out for these");
+        lds_get16<0>(ph[0][0], pba);
+        lds_get16<64>(ph[0][1], pba);
+        lds_get16<HQP * PB_ROW>(pl[0][0], pba);
+        lds_get16<HQP * PB_ROW + 64>(pl[0][1], pba);
+        lds_get16<0>(al4[0], ala);
+        if (NRB == 2) {
+            lds_get16<16 * PB_ROW>(ph[NRB - 1][0], pba);
+            lds_get16<16 * PB_ROW + 64>(ph[NRB - 1][1], pba);
+            lds_get16<(HQP + 16) * PB_ROW>(pl[NRB - 1][0], pba);
+            lds_get16<(HQP + 16) * PB_ROW + 64>(pl[NRB - 1][1], pba);
+            lds_get16<64>(al4[NRB - 1], ala);
+        }
+        lds_wait();
+#pragma unroll
+        for (int c = 0; c < NCT; c++) { lds_got(vb[c][0]); lds_got(vb[c][1]); }
+#pragma unroll
+        for (int rb = 0; rb < NRB; rb++) { lds_got(ph[rb][0]); lds_got(ph[rb][1]); lds_got(pl[rb][0]); lds_got(pl[rb][1]); lds_got(al4[rb]); }
+#pragma unroll
+        for (int rb = 0; rb < NRB; rb++)
+#pragma unroll
+            for (int c = 0; c < NCT; c++) {
+                v4f acc = accv[rb][c] * __builtin_bit_cast(v4f, al4[rb]);
+#pragma unroll
+                for (int ks = 0; ks < 2; ks++) acc = mfma_h(pl[rb][ks], vb[c][ks], mfma_h(ph[rb][ks], vb[c][ks], acc));
+                accv[rb][c] = acc;
+            }
+    };
+    // with counters: the strip of the previous chunk (its product runs one chunk late), and the copy of
+    // the exchange buffers that belongs to the chunk at hand (chunk mod 3)
+    u32x4 vmq[NCT][2];
+    int xsl = 0;
+    const uint32_t eva = lds_addr(lds_ev);
 
     // cross-head mean: q . mean_K of this lane's tokens (16 k + n of a chunk), worked out by the
     // kernel that ran before this one; loaded one chunk ahead
@@ -660,12 +772,13 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
             // covers the latency: the key-mean rows of the NEXT chunk (of this one again if it is
             // the last: the scores are then worked out for nobody), and this wave's strip of this
             // chunk's value-mean tile, lane = token, 32 bytes per channel tile.
-            kmean_fetch(kmB, more ? blk_of(ci + CW) : blk0);
+            // (with counters: of the chunk after the next)
+            kmean_fetch(kmB, DR ? (ci + 2 * CW < n_chunks ? blk_of(ci + 2 * CW) : blk0) : (more ? blk_of(ci + CW) : blk0));
 #pragma unroll
             for (int c = 0; c < NCT; c++)
 #pragma unroll
                 for (int hf = 0; hf < 2; hf++)
-                    glb_get16(vmp[c][hf], mean_row_src(1, blk0, lane) + 32 * (wave * NCT + c) + 16 * hf);
+                    glb_get16<DR>(vmp[c][hf], mean_row_src(1, blk0, lane) + 32 * (wave * NCT + c) + 16 * hf);
         }
         PHASE(1)
         uint4 kc[NKL], vc[NVL];
@@ -732,7 +845,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
         if (XF) {
             // q . mean_K of token 16 k + n for head `row` of each head group, worked out by the waves
             // together during the previous chunk
-            const float *xs = (const float *)lds_xs + par * (HQP * 64);
+            const float *xs = (const float *)lds_xs + (DR ? xsl : par) * (HQP * 64);
 #pragma unroll
             for (int hg = 0; hg < NHG; hg++)
 #pragma unroll
@@ -879,8 +992,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
             // this wave's weights, relative to the new running maximum and times 2^8 (so that the low
             // part of a small weight is still a normal binary16 number), as binary16 hi + lo; and the
             // factor that brings the old sums to the new maximum
-            _Float16 *pb = (_Float16 *)lds_pb + par * (2 * HQP * (PB_ROW / 2));
-            float *al = (float *)lds_al + par * HQP;
+            _Float16 *pb = (_Float16 *)lds_pb + (DR ? xsl : par) * (2 * HQP * (PB_ROW / 2));
+            float *al = (float *)lds_al + (DR ? xsl : par) * HQP;
 #pragma unroll
             for (int hg = 0; hg < NHG; hg++) {
                 const int hp = wave * HP + 4 * hg + row;
@@ -902,68 +1015,20 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
 #pragma unroll
             for (int e = 0; e < NHG; e++)
 #pragma unroll
-                for (int ks = 0; ks < 4; ks++) glb_got(kmB[e][ks]);
+                for (int ks = 0; ks < 4; ks++) glb_got<DR>(kmB[e][ks]);
 #pragma unroll
             for (int c = 0; c < NCT; c++)
 #pragma unroll
-                for (int hf = 0; hf < 2; hf++) glb_got(vmp[c][hf]);
-            kmean_scores(kmB, par ^ 1); // the next chunk's scores
-            // the strip of the value-mean tile, transposed: [channel][token], so that the token index
-            // is the contraction index of the B operand
-            uint16_t *vt = (uint16_t *)lds_vt + wave * (NCT * 16 * (PB_ROW / 2));
-#pragma unroll
-            for (int c = 0; c < NCT; c++)
-#pragma unroll
-                for (int hf = 0; hf < 2; hf++)
-#pragma unroll
-                    for (int k = 0; k < 4; k++) {
-                        const uint32_t w = vmp[c][hf][k];
-                        vt[(c * 16 + 8 * hf + 2 * k) * (PB_ROW / 2) + lane] = (uint16_t)(w & 0xFFFFu);
-                        vt[(c * 16 + 8 * hf + 2 * k + 1) * (PB_ROW / 2) + lane] = (uint16_t)(w >> 16);
-                    }
-            wave_lds_fence();
-            PHASE(8)
-            __builtin_amdgcn_s_barrier(); // everybody's weights, factors and scores are in place
-            PHASE(9)
-            // (the reads by hand: the wave's next chunk is on its way into LDS)
-            const uint32_t vta = lds_addr(vt) + n * PB_ROW + 16 * row; // channel n of a tile, tokens 8 row .. + 7
-            const uint32_t pba = lds_addr(pb) + n * PB_ROW + 16 * row; // A operand: row n = head n of a block, tokens 8 row .. + 7
-            const uint32_t ala = lds_addr(al) + 16 * row;              // factors of heads 4 row .. + 3 of a block
-            u32x4 vb[NCT][2], ph[NRB][2], pl[NRB][2], al4[NRB];
-            lds_get16<0>(vb[0][0], vta);
-            lds_get16<64>(vb[0][1], vta);
-            if (NCT == 2) {
-                lds_get16<16 * PB_ROW>(vb[NCT - 1][0], vta);
-                lds_get16<16 * PB_ROW + 64>(vb[NCT - 1][1], vta);
+                for (int hf = 0; hf < 2; hf++) glb_got<DR>(vmp[c][hf]);
+            if (!DR) {
+                kmean_scores(kmB, par ^ 1); // the next chunk's scores
+                vt_store(vmp);
+                PHASE(8)
+                __builtin_amdgcn_s_barrier(); // everybody's weights, factors and scores are in place
+                PHASE(9)
+                vmean_add(par);
+                PHASE(10)
             }
-            static_assert(NCT <= 2 && NRB <= 2, "operand reads of the value-mean product are written out for these");
-            lds_get16<0>(ph[0][0], pba);
-            lds_get16<64>(ph[0][1], pba);
-            lds_get16<HQP * PB_ROW>(pl[0][0], pba);
-            lds_get16<HQP * PB_ROW + 64>(pl[0][1], pba);
-            lds_get16<0>(al4[0], ala);
-            if (NRB == 2) {
-                lds_get16<16 * PB_ROW>(ph[NRB - 1][0], pba);
-                lds_get16<16 * PB_ROW + 64>(ph[NRB - 1][1], pba);
-                lds_get16<(HQP + 16) * PB_ROW>(pl[NRB - 1][0], pba);
-                lds_get16<(HQP + 16) * PB_ROW + 64>(pl[NRB - 1][1], pba);
-                lds_get16<64>(al4[NRB - 1], ala);
-            }
-            lds_wait();
-#pragma unroll
-            for (int c = 0; c < NCT; c++) { lds_got(vb[c][0]); lds_got(vb[c][1]); }
-#pragma unroll
-            for (int rb = 0; rb < NRB; rb++) { lds_got(ph[rb][0]); lds_got(ph[rb][1]); lds_got(pl[rb][0]); lds_got(pl[rb][1]); lds_got(al4[rb]); }
-#pragma unroll
-            for (int rb = 0; rb < NRB; rb++)
-#pragma unroll
-                for (int c = 0; c < NCT; c++) {
-                    v4f acc = accv[rb][c] * __builtin_bit_cast(v4f, al4[rb]);
-#pragma unroll
-                    for (int ks = 0; ks < 2; ks++) acc = mfma_h(pl[rb][ks], vb[c][ks], mfma_h(ph[rb][ks], vb[c][ks], acc));
-                    accv[rb][c] = acc;
-                }
-                        PHASE(10)
         }
 
         // ---- value side in passes of NGP scale groups: p*scale as limbs -> LDS, matrix products
@@ -1028,6 +1093,23 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
                 }
             }
         }
+        if (DR) {
+            // With counters (a wave's counter = the chunks it has finished): the product of the PREVIOUS
+            // chunk, once every wave has finished that chunk -- its weights and factors, written half a
+            // chunk ago at the latest, are then in place --, and the scores of the chunk after the next
+            // into the copy whose scores (of the previous chunk) everybody has then read.  A copy is
+            // written again three chunks later, and no wave gets more than one chunk ahead of another.
+            if (itn > 0) {
+                progress_wait_all<NW>(eva, (uint32_t)itn, lane);
+                vt_store(vmq);
+                vmean_add(xsl == 0 ? 2 : xsl - 1);
+            }
+            kmean_scores(kmB, xsl == 0 ? 2 : xsl - 1);
+#pragma unroll
+            for (int c = 0; c < NCT; c++) { vmq[c][0] = vmp[c][0]; vmq[c][1] = vmp[c][1]; }
+            progress_publish(eva + 4 * wave, (uint32_t)itn + 1u, lane);
+            xsl = xsl == 2 ? 0 : xsl + 1;
+        }
         PHASE(11)
     }
     PHASE(12)
@@ -1037,6 +1119,13 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
     // fused cross-head form: the value mean's share goes from the waves that summed it (all heads, a
     // channel tile) to the waves that own the heads, through the buffer the scores went through
     if (XF) {
+        if (DR) {
+            __builtin_amdgcn_s_barrier(); // (everybody has left the loop: a barrier serves)
+            if (n_chunks > 0) { // the last chunk's product
+                vt_store(vmq);
+                vmean_add(xsl == 0 ? 2 : xsl - 1);
+            }
+        }
         float *om = (float *)lds_xs; // [head][128]
 #pragma unroll
         for (int rb = 0; rb < NRB; rb++)

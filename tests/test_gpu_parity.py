@@ -517,7 +517,11 @@ def test_cross_head_mean_mixed_layers_bf16(kv, oracle):
                                             (4, 64, 8, 704, 4), (4, 128, 4, 2048 + 128 + 50, 4), (2, 128, 8, 1280, 4),
                                             (8, 128, 3, 1664 + 7, 4), (4, 128, 6, 1536 + 128 + 9, 8), (2, 128, 2, 2304 + 1, 8), (8, 32, 4, 1500 + 9, 8), (2, 32, 8, 1056 + 32, 8),
                                             (4, 64, 5, 1344 + 3, 8), (8, 64, 8, 960, 8), (2, 64, 2, 2048 + 70, 8),
-                                            (4, 32, 4, 1120 + 31, 8), (4, 32, 2, 700, 2)])
+                                            (4, 32, 4, 1120 + 31, 8), (4, 32, 2, 700, 2),
+                                            # the remaining instances of the form with both mean terms inside the kernel
+                                            (4, 32, 6, 900 + 7, 8), (8, 32, 8, 1200 + 5, 4), (2, 32, 3, 1300, 4),
+                                            (4, 64, 4, 1100 + 64, 8), (4, 64, 2, 1000, 4), (2, 64, 7, 900 + 1, 4),
+                                            (8, 128, 6, 1536 + 20, 8), (4, 128, 3, 1400, 8), (8, 32, 7, 2100 + 3, 8)])
 def test_cross_head_mean_on_the_matrix_cores(kv, oracle, decode_path, bits, G, g, T, Hkv):
     """Cross-head mean with the deviations on the matrix-core kernel; the two dense mean terms inside
     that kernel (4 or 8 kv heads: a workgroup of 8 waves, of 4 waves, or two workgroups of 4 that share
