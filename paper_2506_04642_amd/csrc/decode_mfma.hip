@@ -257,15 +257,13 @@ template <int NW> __device__ __forceinline__ void progress_wait_all(uint32_t bas
 // Between the request and the hand-over the compiler takes the destination for a value that exists:
 // under register pressure it may move it (into another register, into the accumulation file), and
 // then the data arrives in a register that has been given to something else -- an address, say.
-// Where the destinations stay awaited across much of an iteration (ACC) they are therefore
-// accumulation registers, of which these kernels use few: nothing competes for them, they take no
-// part in the pressure on the ordinary file, and what needs the data in an ordinary register copies
-// it after the hand-over.  In every case the build reads the generated code and refuses it if any
-// instruction between a request and its hand-over names a destination.
-template <bool ACC> __device__ __forceinline__ void glb_get16(u32x4 &dst, const void *p)
+// The destinations are therefore accumulation registers, of which these kernels use few: nothing
+// competes for them, they take no part in the pressure on the ordinary file, and what needs the data
+// in an ordinary register copies it after the hand-over.  The build reads the generated code and
+// refuses it if any instruction between a request and its hand-over names a destination.
+__device__ __forceinline__ void glb_get16(u32x4 &dst, const void *p)
 {
-    if constexpr (ACC) asm volatile("global_load_dwordx4 %0, %1, off ; by hand" : "=a"(dst) : "v"(p));
-    else asm volatile("global_load_dwordx4 %0, %1, off ; by hand" : "=v"(dst) : "v"(p));
+    asm volatile("global_load_dwordx4 %0, %1, off ; by hand" : "=a"(dst) : "v"(p));
 }
 // (the wait and the hand-over of the registers are separate so that a wait chosen by a condition
 // is followed by ONE hand-over per register: registers handed over on either side of a branch would
@@ -275,11 +273,7 @@ template <int N> __device__ __forceinline__ void glb_wait_but()
     static_assert(N >= 0 && N < 64, "vmcnt is a six-bit counter");
     asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
 }
-template <bool ACC> __device__ __forceinline__ void glb_got(u32x4 &r)
-{
-    if constexpr (ACC) asm volatile("; by hand %0" : "+a"(r) : : "memory");
-    else asm volatile("; by hand %0" : "+v"(r) : : "memory");
-}
+__device__ __forceinline__ void glb_got(u32x4 &r) { asm volatile("; by hand %0" : "+a"(r) : : "memory"); }
 // Blocks of 128 tokens are read as two halves of 64: the pieces of half hf of the record at src
 // (its key codes, the block's key metadata, its runs of value codes -- 1 KiB per group of channel
 // tiles --, its value metadata, the block's value mean) are placed so that the staging buffer
@@ -347,7 +341,7 @@ template <> struct CodeOps<8> { // four words = one tile line; split into nibble
 //   XH == 1: the mean's share of every score comes in through a.xs, and the softmax weights go out
 //            through a.xp / a.xmc for the kernel that adds the value mean plane's share to the
 //            partial outputs (two more kernels and a round trip of scores and weights).
-//   XH == 2: both mean terms inside this kernel.  A workgroup is one (sequence, split) and NW kv
+//   XH == 2: both mean terms inside this kernel.  A workgroup is one (sequence, split) and four kv
 //            heads (all of them, or half: then two workgroups share the split), a wave per kv head:
 //            every wave takes the same chunks, each of its own head's records.  The mean rows of a
 //            chunk (64 tokens x 128 channels of binary16 for keys and for values, shared by all kv
@@ -356,7 +350,8 @@ template <> struct CodeOps<8> { // four words = one tile line; split into nibble
 //            its normal range; weights as a binary16 pair hi + lo; binary32 accumulation) that the
 //            waves share out among themselves -- the scores by (16 query heads, 16 tokens), the
 //            value share by 16-channel tile for all heads -- and whose small operands and results
-//            (scores, weights, rescale factors) they exchange through LDS, one barrier per chunk.
+//            (scores, weights, rescale factors) they exchange through LDS, paced by per-wave
+//            progress counters instead of barriers.
 // PG: paged placement (block slots through a table); the dense instances carry none of its state.
 // GS: tokens per block of the cache (32, 64, or 128 read as two halves of 64).
 template <int B, int GS, int GC, bool MEAN, int NW, int NHG, int XH, bool PG>
@@ -366,13 +361,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
     constexpr bool XF = XH == 2; // both mean terms in this kernel, a wave per kv head
     static_assert(!XF || !PG, "the fused cross-head form takes dense placement");
     constexpr int CW = XF ? 1 : NW;          // waves that share a unit's chunks
-    // fused cross-head form in workgroups of four waves: the waves exchange through counters instead of
-    // a barrier per chunk and may drift apart by one chunk.  These instances run one wave per SIMD (all
-    // but the 2-bit one with up to four query heads per kv head, which fits a compute unit twice, loses
-    // 6 of 160 us per layer to the barrier and gains nothing measurable from the counters): a wave that
-    // waits at a barrier for the slowest chunk of the round leaves its SIMD idle
-    constexpr bool DR = XF && NW == 4 && !(B == 2 && NHG == 1);
-    constexpr int XSL = DR ? 3 : 2;          // copies of every exchange buffer
+    static_assert(!XF || NW == 4, "the fused cross-head form runs in workgroups of four waves");
+    constexpr int XSL = 3;                   // copies of every exchange buffer of the fused cross-head form
     constexpr bool H2 = GS == 128;         // a block is worked on as two halves
     constexpr int G = H2 ? 64 : GS;        // tokens per block as the arithmetic sees it
     constexpr int HB = GS / G;             // such blocks per block of the cache
@@ -397,18 +387,17 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
     constexpr int HP = 4 * NHG, HQP = NW * HP, NRB = XF ? HQP / 16 : 1;
     constexpr int NCT = XF ? 8 / NW : 1;    // channel tiles of the value-mean product per wave
     constexpr int PB_ROW = 144;             // bytes of a row of 64 binary16 (+ 8 of padding)
-    // shared by the waves, all [parity of the chunk (chunk mod 3 with counters)]...: scores q . mean_K [head][64 tokens] binary32
-    // (the 16-token groups of a row rotated by the head so that writers and readers spread over the
-    // banks), softmax weights [hi | lo][head][64 + 8] binary16, rescale factors [head]; per wave: its
-    // strip of the value-mean tile, transposed, [NCT][16 channels][64 + 8 tokens] binary16
+    // shared by the waves, all [chunk mod 3]...: scores q . mean_K [head][64 tokens] binary32 (the
+    // 16-token groups of a row rotated by the head so that writers and readers spread over the banks),
+    // softmax weights [hi | lo][head][64 + 8] binary16, rescale factors [head]; and a progress counter
+    // per wave (the chunks it has finished)
     constexpr int XS_DW = XF ? XSL * HQP * 64 : 0, PB_DW = XF ? XSL * 2 * HQP * PB_ROW / 4 : 0, AL_DW = XF ? XSL * HQP : 0;
-    constexpr int VT_DW = XF ? NCT * 16 * PB_ROW / 4 : 0;
     constexpr int LDS_DW = NW * WAVE_DW;
 
     __shared__ __attribute__((aligned(16))) uint32_t lds_all[LDS_DW];
     // the exchange buffers of the fused cross-head form
     __shared__ __attribute__((aligned(16))) uint32_t lds_xs[XF ? XS_DW : 1], lds_pb[XF ? PB_DW : 1], lds_al[XF ? AL_DW : 1],
-        lds_vt[XF ? NW * VT_DW : 1], lds_ev[XF ? 16 : 1];
+        lds_ev[XF ? 16 : 1];
 
     const LayerGeom &gm = a.geom;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -573,8 +562,13 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
     // q . mean_K for all its query heads, 16 heads x 16 tokens per matrix product, dealt to the waves by
     // (head block, token tile) -- wave w takes the pairs w NHG + e --, and sum_t p_t mean_V[t] by
     // channel tile, every wave for all heads.  The waves exchange the small operands and results
-    // (scores, weights, rescale factors) through LDS, with one barrier per chunk: the scores of
-    // chunk i + 1 are worked out during chunk i, and every exchange buffer exists once per parity.
+    // (scores, weights, rescale factors) through LDS without a barrier: a wave publishes the number
+    // of chunks it has finished and waits, once per chunk, until every wave has finished the previous
+    // one.  The scores of chunk i + 2 are worked out at the end of chunk i, the value-mean product of
+    // chunk i - 1 runs at the end of chunk i, and every exchange buffer exists three times (chunk mod
+    // 3): no wave gets more than one chunk ahead of another, and none overwrites what another still
+    // reads.  (With a barrier per chunk a wave that waits for the slowest chunk of the round leaves
+    // its SIMD idle: 329 against 262 us per 8-bit layer on 16 sequences of 32768 tokens.)
     u32x4 qA[NHG][4];  // A operands of the score products: row = head of the block, binary16
     int xs_w[NHG], xs_t0[NHG], xs_r[NHG], xs_rot[NHG]; // where this lane's scores are written and read (float index)
     int km_row[NHG];   // this lane's row (token of the chunk) of the key-mean tile as B operand
@@ -583,10 +577,10 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
 #pragma unroll
         for (int e = 0; e < NHG; e++)
 #pragma unroll
-            for (int ks = 0; ks < 4; ks++) glb_get16<DR>(kb[e][ks], mean_row_src(0, blk0, km_row[e]) + 64 * ks + 16 * row);
+            for (int ks = 0; ks < 4; ks++) glb_get16(kb[e][ks], mean_row_src(0, blk0, km_row[e]) + 64 * ks + 16 * row);
     };
-    auto kmean_scores = [&](const u32x4 (&kb)[NHG][4], int par) {
-        float *xs = (float *)lds_xs + par * (HQP * 64);
+    auto kmean_scores = [&](const u32x4 (&kb)[NHG][4], int sl) {
+        float *xs = (float *)lds_xs + sl * (HQP * 64);
 #pragma unroll
         for (int e = 0; e < NHG; e++) {
             v4f acc = v4f{0.0f, 0.0f, 0.0f, 0.0f};
@@ -630,10 +624,9 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
         for (int rb = 0; rb < NRB; rb++)
 #pragma unroll
             for (int c = 0; c < NCT; c++) accv[rb][c] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
-        // the scores of the first chunk (of the first two when the waves drift: there the scores
-        // are worked out two chunks ahead)
+        // the scores of the first two chunks
 #pragma unroll
-        for (int c0 = 0; c0 < (DR ? 2 : 1); c0++)
+        for (int c0 = 0; c0 < 2; c0++)
             if (c0 < n_chunks) {
                 u32x4 kb[NHG][4];
                 kmean_fetch(kb, blk_of(c0));
@@ -641,47 +634,29 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
 #pragma unroll
                 for (int e = 0; e < NHG; e++)
 #pragma unroll
-                    for (int ks = 0; ks < 4; ks++) glb_got<DR>(kb[e][ks]);
+                    for (int ks = 0; ks < 4; ks++) glb_got(kb[e][ks]);
                 kmean_scores(kb, c0);
             }
-        if (DR && lane < 16) lds_ev[lane] = 0u;
+        if (lane < 16) lds_ev[lane] = 0u;
         wave_lds_fence();
         __builtin_amdgcn_s_barrier();
     }
-    // the value-mean product of one chunk: this wave's strip of the tile (as it came from memory, lane =
-    // token) goes through the wave's own LDS transposed, [channel][token], so that the token index is the
-    // contraction index of the B operand ...
-    auto vt_store = [&](const u32x4 (&vm_)[NCT][2]) {
-        uint16_t *vt = (uint16_t *)lds_vt + wave * (NCT * 16 * (PB_ROW / 2));
-#pragma unroll
-        for (int c = 0; c < NCT; c++)
-#pragma unroll
-            for (int hf = 0; hf < 2; hf++)
-#pragma unroll
-                for (int k = 0; k < 4; k++) {
-                    const uint32_t w = vm_[c][hf][k];
-                    vt[(c * 16 + 8 * hf + 2 * k) * (PB_ROW / 2) + lane] = (uint16_t)(w & 0xFFFFu);
-                    vt[(c * 16 + 8 * hf + 2 * k + 1) * (PB_ROW / 2) + lane] = (uint16_t)(w >> 16);
-                }
-        wave_lds_fence();
-    };
-    // ... and meets everybody's weights and rescale factors of that chunk (exchange buffers, copy sl)
-    auto vmean_add = [&](int sl) {
-        const uint16_t *vt = (const uint16_t *)lds_vt + wave * (NCT * 16 * (PB_ROW / 2));
+    // The value-mean product of one chunk (it runs after the value side of the next): this wave's strip
+    // of the tile, as it came from memory (lane = token), meets everybody's weights and rescale factors
+    // of that chunk (exchange buffers, copy sl).  The token index is the contraction index, so the strip
+    // is transposed on the way: through the wave's operand scratch, which is free then, a channel tile
+    // (2 KiB: [16 channels][64 tokens], the 16-byte groups of a row exchanged by the channel so that the
+    // operand reads spread over the banks) at a time; the rows of the scratch that the operand builders
+    // rely on as zero are cleared again.  (The LDS reads by hand: the wave's next chunk is on its way
+    // into LDS.)
+    auto vmean_add_late = [&](const u32x4 (&vm_)[NCT][2], int sl) {
+        static_assert(OPER_DW >= 512, "a channel tile of the value-mean strip fits the operand scratch");
+        static_assert(NCT <= 2 && NRB <= 2, "operand reads of the value-mean product are written out for these");
         const _Float16 *pb = (const _Float16 *)lds_pb + sl * (2 * HQP * (PB_ROW / 2));
         const float *al = (const float *)lds_al + sl * HQP;
-        // (the reads by hand: the wave's next chunk is on its way into LDS)
-        const uint32_t vta = lds_addr(vt) + n * PB_ROW + 16 * row; // channel n of a tile, tokens 8 row .. + 7
         const uint32_t pba = lds_addr(pb) + n * PB_ROW + 16 * row; // A operand: row n = head n of a block, tokens 8 row .. + 7
         const uint32_t ala = lds_addr(al) + 16 * row;              // factors of heads 4 row .. + 3 of a block
         u32x4 vb[NCT][2], ph[NRB][2], pl[NRB][2], al4[NRB];
-        lds_get16<0>(vb[0][0], vta);
-        lds_get16<64>(vb[0][1], vta);
-        if (NCT == 2) {
-            lds_get16<16 * PB_ROW>(vb[NCT - 1][0], vta);
-            lds_get16<16 * PB_ROW + 64>(vb[NCT - 1][1], vta);
-        }
-        static_assert(NCT <= 2 && NRB <= 2, "operand reads of the value-mean product are written out for these");
         lds_get16<0>(ph[0][0], pba);
         lds_get16<64>(ph[0][1], pba);
         lds_get16<HQP * PB_ROW>(pl[0][0], pba);
@@ -696,9 +671,32 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
         }
         lds_wait();
 #pragma unroll
-        for (int c = 0; c < NCT; c++) { lds_got(vb[c][0]); lds_got(vb[c][1]); }
-#pragma unroll
         for (int rb = 0; rb < NRB; rb++) { lds_got(ph[rb][0]); lds_got(ph[rb][1]); lds_got(pl[rb][0]); lds_got(pl[rb][1]); lds_got(al4[rb]); }
+        unsigned char *vt = (unsigned char *)ak;
+        // lane = token on the way in: 16-byte group lane / 8 of a channel's row, exchanged by the channel
+        const uint32_t vrd = lds_addr(vt) + n * 128 + ((row ^ (n & 7)) << 4);        // channel n, tokens 8 row .. + 7
+        const uint32_t vrd2 = lds_addr(vt) + n * 128 + (((row + 4) ^ (n & 7)) << 4); // ... tokens 32 + 8 row .. + 7
+#pragma unroll
+        for (int c = 0; c < NCT; c++) {
+#pragma unroll
+            for (int hf = 0; hf < 2; hf++)
+#pragma unroll
+                for (int k = 0; k < 4; k++) {
+                    const uint32_t w = vm_[c][hf][k];
+                    const int ch = 8 * hf + 2 * k;
+                    *(uint16_t *)(vt + ch * 128 + (((lane >> 3) ^ (ch & 7)) << 4) + (lane & 7) * 2) = (uint16_t)(w & 0xFFFFu);
+                    *(uint16_t *)(vt + (ch + 1) * 128 + (((lane >> 3) ^ ((ch + 1) & 7)) << 4) + (lane & 7) * 2) = (uint16_t)(w >> 16);
+                }
+            wave_lds_fence();
+            lds_get16<0>(vb[c][0], vrd);
+            lds_get16<0>(vb[c][1], vrd2);
+            lds_wait();
+            lds_got(vb[c][0]);
+            lds_got(vb[c][1]);
+        }
+        // words 16 j + 12 .. 15 of the scratch are the fourth limb's rows
+#pragma unroll
+        for (int j = 0; j < 2; j++) ak[((lane >> 2) + 16 * j) * 16 + 12 + (lane & 3)] = 0u;
 #pragma unroll
         for (int rb = 0; rb < NRB; rb++)
 #pragma unroll
@@ -709,8 +707,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
                 accv[rb][c] = acc;
             }
     };
-    // with counters: the strip of the previous chunk (its product runs one chunk late), and the copy of
-    // the exchange buffers that belongs to the chunk at hand (chunk mod 3)
+    // the strip of the previous chunk, and the copy of the exchange buffers that belongs to the chunk at
+    // hand (chunk mod 3)
     u32x4 vmq[NCT][2];
     int xsl = 0;
     const uint32_t eva = lds_addr(lds_ev);
@@ -763,22 +761,20 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
         // ---- staged chunk -> registers
         PHASE(0)
         const bool more = ci + CW < n_chunks;
-        const int par = itn & 1;
         u32x4 kmB[NHG][4], vmp[NCT][2]; // fused cross-head form: operands fetched by hand
         stage_wait(); // this wave's chunk has landed
         if (XF) {
             // Requested here, ahead of the next chunk's fetch (loads return in order: the wait for
             // these then leaves that fetch alone), and used after the key side, whose arithmetic
-            // covers the latency: the key-mean rows of the NEXT chunk (of this one again if it is
-            // the last: the scores are then worked out for nobody), and this wave's strip of this
+            // covers the latency: the key-mean rows of the chunk after the next (of this one again if
+            // there is none: the scores are then worked out for nobody), and this wave's strip of this
             // chunk's value-mean tile, lane = token, 32 bytes per channel tile.
-            // (with counters: of the chunk after the next)
-            kmean_fetch(kmB, DR ? (ci + 2 * CW < n_chunks ? blk_of(ci + 2 * CW) : blk0) : (more ? blk_of(ci + CW) : blk0));
+            kmean_fetch(kmB, ci + 2 * CW < n_chunks ? blk_of(ci + 2 * CW) : blk0);
 #pragma unroll
             for (int c = 0; c < NCT; c++)
 #pragma unroll
                 for (int hf = 0; hf < 2; hf++)
-                    glb_get16<DR>(vmp[c][hf], mean_row_src(1, blk0, lane) + 32 * (wave * NCT + c) + 16 * hf);
+                    glb_get16(vmp[c][hf], mean_row_src(1, blk0, lane) + 32 * (wave * NCT + c) + 16 * hf);
         }
         PHASE(1)
         uint4 kc[NKL], vc[NVL];
@@ -845,7 +841,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
         if (XF) {
             // q . mean_K of token 16 k + n for head `row` of each head group, worked out by the waves
             // together during the previous chunk
-            const float *xs = (const float *)lds_xs + (DR ? xsl : par) * (HQP * 64);
+            const float *xs = (const float *)lds_xs + xsl * (HQP * 64);
 #pragma unroll
             for (int hg = 0; hg < NHG; hg++)
 #pragma unroll
@@ -992,8 +988,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
             // this wave's weights, relative to the new running maximum and times 2^8 (so that the low
             // part of a small weight is still a normal binary16 number), as binary16 hi + lo; and the
             // factor that brings the old sums to the new maximum
-            _Float16 *pb = (_Float16 *)lds_pb + (DR ? xsl : par) * (2 * HQP * (PB_ROW / 2));
-            float *al = (float *)lds_al + (DR ? xsl : par) * HQP;
+            _Float16 *pb = (_Float16 *)lds_pb + xsl * (2 * HQP * (PB_ROW / 2));
+            float *al = (float *)lds_al + xsl * HQP;
 #pragma unroll
             for (int hg = 0; hg < NHG; hg++) {
                 const int hp = wave * HP + 4 * hg + row;
@@ -1015,20 +1011,11 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
 #pragma unroll
             for (int e = 0; e < NHG; e++)
 #pragma unroll
-                for (int ks = 0; ks < 4; ks++) glb_got<DR>(kmB[e][ks]);
+                for (int ks = 0; ks < 4; ks++) glb_got(kmB[e][ks]);
 #pragma unroll
             for (int c = 0; c < NCT; c++)
 #pragma unroll
-                for (int hf = 0; hf < 2; hf++) glb_got<DR>(vmp[c][hf]);
-            if (!DR) {
-                kmean_scores(kmB, par ^ 1); // the next chunk's scores
-                vt_store(vmp);
-                PHASE(8)
-                __builtin_amdgcn_s_barrier(); // everybody's weights, factors and scores are in place
-                PHASE(9)
-                vmean_add(par);
-                PHASE(10)
-            }
+                for (int hf = 0; hf < 2; hf++) glb_got(vmp[c][hf]);
         }
 
         // ---- value side in passes of NGP scale groups: p*scale as limbs -> LDS, matrix products
@@ -1093,16 +1080,15 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
                 }
             }
         }
-        if (DR) {
-            // With counters (a wave's counter = the chunks it has finished): the product of the PREVIOUS
+        if (XF) {
+            // (a wave's counter = the chunks it has finished) the product of the PREVIOUS
             // chunk, once every wave has finished that chunk -- its weights and factors, written half a
             // chunk ago at the latest, are then in place --, and the scores of the chunk after the next
             // into the copy whose scores (of the previous chunk) everybody has then read.  A copy is
             // written again three chunks later, and no wave gets more than one chunk ahead of another.
             if (itn > 0) {
                 progress_wait_all<NW>(eva, (uint32_t)itn, lane);
-                vt_store(vmq);
-                vmean_add(xsl == 0 ? 2 : xsl - 1);
+                vmean_add_late(vmq, xsl == 0 ? 2 : xsl - 1);
             }
             kmean_scores(kmB, xsl == 0 ? 2 : xsl - 1);
 #pragma unroll
@@ -1119,12 +1105,9 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
     // fused cross-head form: the value mean's share goes from the waves that summed it (all heads, a
     // channel tile) to the waves that own the heads, through the buffer the scores went through
     if (XF) {
-        if (DR) {
+        {
             __builtin_amdgcn_s_barrier(); // (everybody has left the loop: a barrier serves)
-            if (n_chunks > 0) { // the last chunk's product
-                vt_store(vmq);
-                vmean_add(xsl == 0 ? 2 : xsl - 1);
-            }
+            if (n_chunks > 0) vmean_add_late(vmq, xsl == 0 ? 2 : xsl - 1); // the last chunk's product
         }
         float *om = (float *)lds_xs; // [head][128]
 #pragma unroll
@@ -1395,19 +1378,12 @@ template <int B, int G, int GC, bool PG, class F> void pick_mean_heads_pg(const 
         else f.template run<B, G, GC, false, NW, 2, 0, PG>(a);
     }
 }
-// the fused cross-head instances: a wave per kv head.  Eight kv heads go to two workgroups of four
-// waves, except at 4 bits with up to four query heads per kv head, where one workgroup of eight is
-// faster (its four-wave twin needs more than 256 registers: one wave per SIMD; the 2-bit four-wave
-// instance fits a compute unit twice and beats its eight-wave twin, 159 against 168 us per layer
-// on 16 sequences of 32768 tokens; eight 8-bit chunk buffers do not fit the LDS).
+// the fused cross-head instances: a wave per kv head, workgroups of four waves (eight kv heads go to two
+// workgroups that share a sequence's split).  A workgroup of eight waves needs a barrier per chunk --
+// three copies of its exchange buffers do not fit the LDS -- and measured 200 against 193 us per 4-bit
+// layer on 16 sequences of 32768 tokens, 168 against 156 us per 2-bit layer.
 template <int B, int G, int GC, class F> void pick_fused(const DecodeArgs &a, F &f)
 {
-    if constexpr (B == 4) {
-        if (a.n_kv_heads == 8 && a.g <= 4) {
-            f.template run<B, G, GC, false, 8, 1, 2, false>(a);
-            return;
-        }
-    }
     if (a.g <= 4) f.template run<B, G, GC, false, 4, 1, 2, false>(a);
     else f.template run<B, G, GC, false, 4, 2, 2, false>(a);
 }

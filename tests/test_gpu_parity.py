@@ -524,8 +524,9 @@ def test_cross_head_mean_mixed_layers_bf16(kv, oracle):
                                             (8, 128, 6, 1536 + 20, 8), (4, 128, 3, 1400, 8), (8, 32, 7, 2100 + 3, 8)])
 def test_cross_head_mean_on_the_matrix_cores(kv, oracle, decode_path, bits, G, g, T, Hkv):
     """Cross-head mean with the deviations on the matrix-core kernel; the two dense mean terms inside
-    that kernel (4 or 8 kv heads: a workgroup of 8 waves, of 4 waves, or two workgroups of 4 that share
-    a sequence's split; blocks of 128 tokens as two halves) or in kernels of their own (other head counts);
+    that kernel (4 or 8 kv heads: a workgroup of 4 waves, or two that share a sequence's split, with one
+    or two groups of four query heads per kv head; blocks of 128 tokens as two halves) or in kernels of
+    their own (other head counts);
     several splits, an odd block count, a raw tail."""
     print("case cross_head_mfma bits=%d G=%d g=%d T=%d Hkv=%d" % (bits, G, g, T, Hkv), flush=True)
     gpu, orc = make_pair(kv, oracle, B=2, Hq=Hkv * g, Hkv=Hkv, T_max=(T // G + 2) * G, G=G, Gc=G, dtype=BF16, mode=CROSS,
