@@ -341,7 +341,7 @@ template <> struct CodeOps<8> { // four words = one tile line; split into nibble
 //   XH == 1: the mean's share of every score comes in through a.xs, and the softmax weights go out
 //            through a.xp / a.xmc for the kernel that adds the value mean plane's share to the
 //            partial outputs (two more kernels and a round trip of scores and weights).
-//   XH == 2: both mean terms inside this kernel.  A workgroup is one (sequence, split) and four kv
+//   XH == 2: both mean terms inside this kernel.  A workgroup is one (sequence, split) and NW kv
 //            heads (all of them, or half: then two workgroups share the split), a wave per kv head:
 //            every wave takes the same chunks, each of its own head's records.  The mean rows of a
 //            chunk (64 tokens x 128 channels of binary16 for keys and for values, shared by all kv
@@ -361,7 +361,6 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
     constexpr bool XF = XH == 2; // both mean terms in this kernel, a wave per kv head
     static_assert(!XF || !PG, "the fused cross-head form takes dense placement");
     constexpr int CW = XF ? 1 : NW;          // waves that share a unit's chunks
-    static_assert(!XF || NW == 4, "the fused cross-head form runs in workgroups of four waves");
     constexpr int XSL = 3;                   // copies of every exchange buffer of the fused cross-head form
     constexpr bool H2 = GS == 128;         // a block is worked on as two halves
     constexpr int G = H2 ? 64 : GS;        // tokens per block as the arithmetic sees it
@@ -1378,12 +1377,20 @@ template <int B, int G, int GC, bool PG, class F> void pick_mean_heads_pg(const 
         else f.template run<B, G, GC, false, NW, 2, 0, PG>(a);
     }
 }
-// the fused cross-head instances: a wave per kv head, workgroups of four waves (eight kv heads go to two
-// workgroups that share a sequence's split).  A workgroup of eight waves needs a barrier per chunk --
-// three copies of its exchange buffers do not fit the LDS -- and measured 200 against 193 us per 4-bit
-// layer on 16 sequences of 32768 tokens, 168 against 156 us per 2-bit layer.
+// the fused cross-head instances: a wave per kv head.  Eight kv heads go to two workgroups of four waves
+// that share a sequence's split, except at 4 bits with up to four query heads per kv head, where one
+// workgroup of eight is faster (177 against 193 us per layer on 16 sequences of 32768 tokens: every
+// mean row is fetched once per workgroup instead of once per pair that may have drifted apart in the
+// L2; at 2 bits the four-wave instance fits a compute unit twice and wins, 158 against 163 us; eight
+// 8-bit chunk buffers do not fit the LDS).
 template <int B, int G, int GC, class F> void pick_fused(const DecodeArgs &a, F &f)
 {
+    if constexpr (B == 4) {
+        if (a.n_kv_heads == 8 && a.g <= 4) {
+            f.template run<B, G, GC, false, 8, 1, 2, false>(a);
+            return;
+        }
+    }
     if (a.g <= 4) f.template run<B, G, GC, false, 4, 1, 2, false>(a);
     else f.template run<B, G, GC, false, 4, 2, 2, false>(a);
 }
