@@ -392,7 +392,7 @@ kv_status kv_decode_attn_static(const kv_cache *cache, int32_t layer, const void
  *       outside graph capture, after the prompts have been appended, and again after any other call
  *       that changes lengths (appends, resets).
  *   kv_decode_step_dev : as kv_append_decode_attn -- one token per sequence appended, then attention
- *       over everything cached -- with the same results bit for bit; enqueues three kernels (store the
+ *       over everything cached -- with the same results, bit for bit at the same split count; enqueues three kernels (store the
  *       token, write the lengths after the step and compress the raw buffers that the token filled,
  *       none on most steps; attention; merge, which also makes the new lengths current) and does NOT change
  *       the descriptor's lengths.  A sequence that has no room for the token keeps its state and
@@ -400,9 +400,10 @@ kv_status kv_decode_attn_static(const kv_cache *cache, int32_t layer, const void
  *       descriptor's lengths: re-record after a few hundred steps to keep them near the best.
  *   kv_cache_advance : the descriptor catches up with n_steps such steps of `layer` (-1: every
  *       layer), so that the other entry points see the cache as it is; host only.
- * Served: group_tokens == 32, k_bits == v_bits in {2, 4, 8}, KV_MEAN_CHANNEL_BLOCK or KV_MEAN_NONE,
- * dense placement, all sequences active, layers on the matrix-core kernels; otherwise
- * KV_E_UNSUPPORTED.  KV_E_BAD_CONFIG before kv_cache_lengths_to_device.  Other errors as
+ * Served: group_tokens == 32, k_bits == v_bits in {2, 4, 8}, dense placement, all sequences active,
+ * layers on the matrix-core kernels, every mean mode -- KV_MEAN_CROSS_HEAD (Eq. 1-2) with 4 or 8 kv
+ * heads (four kernels then: the mean rows of a block that is about to be compressed come first);
+ * otherwise KV_E_UNSUPPORTED.  KV_E_BAD_CONFIG before kv_cache_lengths_to_device.  Other errors as
  * kv_append_decode_attn. */
 kv_status kv_dev_lengths_bytes(const kv_config *cfg, size_t *bytes);
 kv_status kv_cache_lengths_to_device(kv_cache *cache, void *dev_lengths, void *stream);

@@ -491,7 +491,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 8))
                 for (int e = 0; e < 8; e++) x[j][e] = x[j][e] - m[e];
         } else if (gm.mean_mode == 1) {
             // mean over the kv heads per (token, channel), written by xhead_mean_kernel before this launch
-            const uint16_t *xm = (const uint16_t *)(a.layer + xmean_offset(gm, a.b0 + b, a.first_block + fb, which));
+            const uint16_t *xm = (const uint16_t *)(a.layer + xmean_offset(gm, a.b0 + b, first_block + fb, which));
 #pragma unroll
             for (int j = 0; j < 8; j++) {
                 const uint4 mv = *(const uint4 *)(xm + (8 * tg + j) * kHeadDim + c8 * 8);
@@ -836,7 +836,16 @@ __global__ __launch_bounds__(kThreads) void xhead_mean_kernel(AppendArgs a)
     const int fb = blockIdx.x, b = blockIdx.y, which = blockIdx.z;
     const int bits = which == 0 ? gm.k_bits : gm.v_bits;
     if (bits == 16) return;
-    uint16_t *dst = (uint16_t *)(a.layer + xmean_offset(gm, a.b0 + b, a.first_block + fb, which));
+    int first_block = a.first_block;
+    if (a.len_dev) {
+        // a decode step on device-resident lengths: only a sequence whose raw buffer the step's token
+        // fills gets the rows of its next block(s), as flush_wave_kernel, launched next, compresses only those
+        int nb, r;
+        dev_len(a.len_dev, a.batch, b, 0, gm.NB, gm.R, nb, r);
+        if (r + 1 != gm.R || nb * G + r + 1 > gm.NB * G) return;
+        first_block = nb;
+    }
+    uint16_t *dst = (uint16_t *)(a.layer + xmean_offset(gm, a.b0 + b, first_block + fb, which));
     if (!(a.rope != 0 && which == 0)) {
         // no rotation on this side: a thread takes eight channels of a token as 16-byte pieces
         for (int i = threadIdx.x; i < G * (kHeadDim / 8); i += kThreads) {
@@ -1043,8 +1052,8 @@ hipError_t launch_flush(const AppendArgs &a, hipStream_t s)
 
 bool step_store_supported(const LayerGeom &g)
 {
-    // the formats of the one-wavefront-per-item quantiser, dense placement, no mean over the heads
-    return g.G == 32 && g.k_bits == g.v_bits && g.k_bits != 16 && g.mean_mode != 1 && !g.table;
+    // the formats of the one-wavefront-per-item quantiser, dense placement
+    return g.G == 32 && g.k_bits == g.v_bits && g.k_bits != 16 && !g.table;
 }
 
 hipError_t launch_resid_copy(const AppendArgs &a, hipStream_t s)

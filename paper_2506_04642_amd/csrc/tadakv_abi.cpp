@@ -1028,6 +1028,9 @@ kv_status kv_decode_step_dev(const kv_cache *cache, int32_t layer, const void *k
         if (st != KV_OK) return st;
     }
     if (!use_mfma(cache, a)) return KV_E_UNSUPPORTED;
+    // (mean over the heads: the form with both mean terms inside the split kernel; the kernels of the
+    // other form take their lengths from the host)
+    if (c.mean_mode == KV_MEAN_CROSS_HEAD && !xhead_fused(a)) return KV_E_UNSUPPORTED;
     st = bind_workspace(cache, &a, workspace, workspace_bytes);
     if (st != KV_OK) return st;
     a.ragged = 0;

@@ -84,8 +84,8 @@ def test_calls_on_a_stream_of_their_own(kv, oracle):
     assert err <= ATTN_TOL
 
 
-@pytest.mark.parametrize("mode", [CHAN, 2], ids=["channel_mean", "no_mean"])
-def test_growing_decode_loop_replayed_from_one_graph(kv, oracle, mode):
+@pytest.mark.parametrize("mode,Hkv", [(CHAN, 2), (2, 2), (CROSS, 4), (CROSS, 8)], ids=["channel_mean", "no_mean", "cross_head_4", "cross_head_8"])
+def test_growing_decode_loop_replayed_from_one_graph(kv, oracle, mode, Hkv):
     """Two layers (4- and 2-bit), three sequences of different lengths: one recording of
     kv_decode_step_dev per layer is replayed for 40 steps, across at least one block flush of every
     sequence; every step's output equals that of the eager one-call step on a twin cache, bit for
@@ -93,8 +93,8 @@ def test_growing_decode_loop_replayed_from_one_graph(kv, oracle, mode):
     bytes are the oracle's."""
     import torch
 
-    print("case graph_steps mode=%d" % mode, flush=True)
-    B, Hq, Hkv, G, steps = 3, 8, 2, 32, 40
+    print("case graph_steps mode=%d Hkv=%d" % (mode, Hkv), flush=True)
+    B, Hq, G, steps = 3, 8, 32, 40
     bits = (4, 2)
     prompts = [5 * G + 30, 17, 2 * G + 3]  # sequence 0 fills its raw buffer on the second step
     mk = lambda: make_pair(kv, oracle, L=2, B=B, Hq=Hq, Hkv=Hkv, T_max=12 * G, dtype=BF16, mode=mode, k_bits=bits)
@@ -103,6 +103,10 @@ def test_growing_decode_loop_replayed_from_one_graph(kv, oracle, mode):
     warm, _ = mk()
     for c in (gpu, twin, warm):
         kv.kv_set_decode_path(c.handle, 2)
+        if mode == CROSS:
+            # a recorded step keeps the split count it was planned with while the eager call plans anew as
+            # the cache grows (here from 3 chunks to 4): pinned, so that the two sum in the same order
+            kv.kv_set_decode_splits(c.handle, 2)
     for l in range(2):
         for b, n in enumerate(prompts):
             k, v = synth.make_kv(2000 + 10 * l + b, 1, n, Hkv, 128, BF16)
