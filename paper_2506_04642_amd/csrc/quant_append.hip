@@ -688,13 +688,25 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ?
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_img[]; // [waves][IMG_BYTES], sized at launch
     unsigned char *img = lds_img + wave * IMG_BYTES;
 
+    // a decode step on device-resident lengths (as in flush_wave_kernel): the step's token and the
+    // lengths after the step first, then only the raw buffers that the token has filled
+    if (a.len_dev)
+        for (int su = (int)blockIdx.x * 8 + (int)(threadIdx.x >> 5); su < U; su += (int)gridDim.x * 8) step_store_unit(a, su);
+
     for (int it = (int)blockIdx.x * (kThreads / 64) + wave; it < n_items; it += workers) {
         const int which = (it ^ (it / workers)) & 1, u = (it >> 1) % U, fb = (it >> 1) / U;
         const int b = u / a.n_kv_heads, h = u % a.n_kv_heads;
-        unsigned char *rec = a.layer + record_offset(gm, a.n_kv_heads, a.b0 + b, h, a.first_block + fb);
+        int first_block = a.first_block;
+        if (a.len_dev) {
+            int nb, r;
+            dev_len(a.len_dev, a.batch, b, 0, gm.NB, gm.R, nb, r);
+            if (r + 1 != gm.R || nb * G + r + 1 > gm.NB * G) continue;
+            first_block = nb;
+        }
+        unsigned char *rec = a.layer + record_offset(gm, a.n_kv_heads, a.b0 + b, h, first_block + fb);
         const int base_off = which == 0 ? gm.k_codes : gm.v_codes;
         const int mode = gm.mean_mode;
-        const uint16_t *xm = mode == 1 ? (const uint16_t *)(a.layer + xmean_offset(gm, a.b0 + b, a.first_block + fb, which)) : nullptr;
+        const uint16_t *xm = mode == 1 ? (const uint16_t *)(a.layer + xmean_offset(gm, a.b0 + b, first_block + fb, which)) : nullptr;
 
         // rows 32 half + 8 tg .. + 7 of the block, channels 8 c8 .. + 7, widened; in cross-head
         // mode already as deviations from the (token, channel) mean
@@ -1052,8 +1064,9 @@ hipError_t launch_flush(const AppendArgs &a, hipStream_t s)
 
 bool step_store_supported(const LayerGeom &g)
 {
-    // the formats of the one-wavefront-per-item quantiser, dense placement
-    return g.G == 32 && g.k_bits == g.v_bits && g.k_bits != 16 && !g.table;
+    // the formats of the one-wavefront-per-item quantisers (launch_flush), dense placement
+    const bool blocks = g.G == 32 || g.G == 64 || (g.G == 128 && g.Gc == 128);
+    return blocks && g.k_bits == g.v_bits && g.k_bits != 16 && !g.table;
 }
 
 hipError_t launch_resid_copy(const AppendArgs &a, hipStream_t s)

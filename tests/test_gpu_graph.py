@@ -84,29 +84,32 @@ def test_calls_on_a_stream_of_their_own(kv, oracle):
     assert err <= ATTN_TOL
 
 
-@pytest.mark.parametrize("mode,Hkv", [(CHAN, 2), (2, 2), (CROSS, 4), (CROSS, 8)], ids=["channel_mean", "no_mean", "cross_head_4", "cross_head_8"])
-def test_growing_decode_loop_replayed_from_one_graph(kv, oracle, mode, Hkv):
+@pytest.mark.parametrize("mode,Hkv,G", [(CHAN, 2, 32), (2, 2, 32), (CROSS, 4, 32), (CROSS, 8, 32), (CHAN, 2, 64), (CROSS, 8, 128),
+                                        (2, 2, 128)],
+                         ids=["channel_mean", "no_mean", "cross_head_4", "cross_head_8", "channel_mean_g64", "cross_head_8_g128",
+                              "no_mean_g128"])
+def test_growing_decode_loop_replayed_from_one_graph(kv, oracle, mode, Hkv, G):
     """Two layers (4- and 2-bit), three sequences of different lengths: one recording of
-    kv_decode_step_dev per layer is replayed for 40 steps, across at least one block flush of every
-    sequence; every step's output equals that of the eager one-call step on a twin cache, bit for
+    kv_decode_step_dev per layer is replayed for 40 steps or more, across at least one block flush of
+    every sequence; every step's output equals that of the eager one-call step on a twin cache, bit for
     bit, and the oracle's within the tolerance; at the end the descriptor catches up and the cache's
     bytes are the oracle's."""
     import torch
 
-    print("case graph_steps mode=%d Hkv=%d" % (mode, Hkv), flush=True)
-    B, Hq, G, steps = 3, 8, 32, 40
+    print("case graph_steps mode=%d Hkv=%d G=%d" % (mode, Hkv, G), flush=True)
+    B, Hq, steps = 3, 8, max(40, G + 12)
     bits = (4, 2)
-    prompts = [5 * G + 30, 17, 2 * G + 3]  # sequence 0 fills its raw buffer on the second step
-    mk = lambda: make_pair(kv, oracle, L=2, B=B, Hq=Hq, Hkv=Hkv, T_max=12 * G, dtype=BF16, mode=mode, k_bits=bits)
+    # sequence 0 fills its raw buffer on the second step (and once more G steps later), sequence 1 on step 14
+    prompts = [5 * G + G - 2, G - 15, 2 * G + 3]
+    mk = lambda: make_pair(kv, oracle, L=2, B=B, Hq=Hq, Hkv=Hkv, T_max=12 * G, G=G, Gc=G, dtype=BF16, mode=mode, k_bits=bits)
     gpu, orc = mk()
     twin, _ = mk()
     warm, _ = mk()
     for c in (gpu, twin, warm):
         kv.kv_set_decode_path(c.handle, 2)
-        if mode == CROSS:
-            # a recorded step keeps the split count it was planned with while the eager call plans anew as
-            # the cache grows (here from 3 chunks to 4): pinned, so that the two sum in the same order
-            kv.kv_set_decode_splits(c.handle, 2)
+        # a recorded step keeps the split count it was planned with while the eager call plans anew as
+        # the cache grows: pinned, so that the two sum in the same order
+        kv.kv_set_decode_splits(c.handle, 2)
     for l in range(2):
         for b, n in enumerate(prompts):
             k, v = synth.make_kv(2000 + 10 * l + b, 1, n, Hkv, 128, BF16)
@@ -133,7 +136,7 @@ def test_growing_decode_loop_replayed_from_one_graph(kv, oracle, mode, Hkv):
         for l in range(2):
             gpu.step_dev(l, k_st[l], v_st[l], q_st[l], o_st[l])
     torch.cuda.synchronize()
-    assert gpu.lengths(0, 0) == (5 * G, 30)  # the recording enqueued nothing yet and the descriptor stays behind
+    assert gpu.lengths(0, 0) == (5 * G, G - 2)  # the recording enqueued nothing yet and the descriptor stays behind
     for s in range(steps):
         qs = [synth.make_q(2200 + 2 * s + l, B, Hq, 128, BF16) for l in range(2)]
         for l in range(2):
