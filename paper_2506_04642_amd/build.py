@@ -16,7 +16,7 @@ COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
 UNITS = [
     ("tadakv_abi.cpp", ["-x", "hip"]),
     ("quant_append.hip", ["-ffp-contract=off"]),
-    ("compressv.hip", ["-ffp-contract=off"]),
+    ("compressv.hip", ["-ffp-contract=off", "-save-temps=obj"]),
     ("decode_valu.hip", []),
     # matrix-instruction results go straight to ordinary vector registers; the direct-to-LDS fetches
     # are issued by hand and name M0 as clobbered, which the compiler remarks on at every use
@@ -65,13 +65,13 @@ def build_library(force: bool = True, verbose: bool = False) -> str:
     _v = importlib.util.module_from_spec(spec)
     spec.loader.exec_module(_v)  # (by path: this file also runs as a script)
 
-    asm = os.path.join(objdir, "decode_mfma-hip-amdgcn-amd-amdhsa-gfx950.s")
-    checked = _v.verify(asm)
-    if verbose:
-        print("verify_hand_loads: %d kernels, %d global requests, %d LDS reads" % checked)
-    for f in os.listdir(objdir):
-        if f.startswith("decode_mfma-") or f.startswith("decode_mfma.hip-"):
-            os.remove(os.path.join(objdir, f))
+    for unit, kernel, glob in (("decode_mfma", "decode_split_mfma_kernel", True), ("compressv", "compressv_gemm_kernel", False)):
+        checked = _v.verify(os.path.join(objdir, unit + "-hip-amdgcn-amd-amdhsa-gfx950.s"), kernel, glob)
+        if verbose:
+            print("verify_hand_loads: %s: %d kernels, %d global requests, %d LDS reads" % ((unit,) + checked))
+        for f in os.listdir(objdir):
+            if f.startswith(unit + "-") or f.startswith(unit + ".hip-"):
+                os.remove(os.path.join(objdir, f))
     cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
     subprocess.run(cmd, check=True)
     return LIB

@@ -1,7 +1,8 @@
-"""Build-time check of the matrix-core decode kernels' generated code (gfx950 assembly text).
+"""Build-time check of generated code (gfx950 assembly text) of the kernels that issue loads by hand.
 
-csrc/decode_mfma.hip issues some loads by hand: the request and the hand-over of the destination
-registers to the compiler are separate inline-assembly statements, with the wait between them.  In
+csrc/decode_mfma.hip (global loads and LDS reads) and csrc/compressv.hip (LDS reads) issue some loads
+by hand: the request and the hand-over of the destination registers to the compiler are separate
+inline-assembly statements, with the wait between them.  In
 between, the compiler believes that the destination already holds its value.  If it moves that value
 (a copy into another register, a spill into the accumulation file or to scratch memory), it copies
 stale contents, hands the register to something else, and the data then arrives on top of that --
@@ -12,11 +13,12 @@ build reads what the compiler produced and refuses it unless, in every kernel,
     (`; by hand <registers>`) under the same name, and no instruction between the request and the
     hand-over names any of its registers;
   * no instruction between a hand-issued `ds_read_b128` (inside an inline-assembly block) and the
-    inline `s_waitcnt lgkmcnt(0)` that follows names a destination of such a read;
+    next `s_waitcnt` with `lgkmcnt(0)` names a destination of such a read;
   * no scratch-memory instruction lies between a request and its hand-over.
 
 The check follows the text in order, as the requests and hand-overs are written in straight-line code
-(a wait may sit inside a branch, never a request or a hand-over)."""
+(a wait may sit inside a branch, never a request or a hand-over); from reads at the end of a loop body
+it follows the path that leaves the loop, not the back edge."""
 import re
 import sys
 
@@ -80,8 +82,8 @@ def check_kernel(name, lines):
             lds_pending[no] = _regs(m.group(1))
             n_lds += 1
             continue
-        if in_asm and code.startswith("s_waitcnt lgkmcnt(0)"):
-            lds_pending.clear()
+        if code.startswith("s_waitcnt") and "lgkmcnt(0)" in code:
+            lds_pending.clear()  # (whoever issued it: nothing read from LDS is still on its way)
             continue
         named = _regs(code)
         if pending:
@@ -98,10 +100,11 @@ def check_kernel(name, lines):
     return problems, n_requests, n_lds
 
 
-def check_text(text):
-    """(problems, kernels checked, hand-issued global requests, hand-issued LDS reads) of an assembly file."""
+def check_text(text, kernel="decode_split_mfma_kernel"):
+    """(problems, kernels checked, hand-issued global requests, hand-issued LDS reads) of an assembly file;
+    the kernels are the functions whose mangled name contains `kernel`."""
     lines = text.split("\n")
-    starts = [i for i, l in enumerate(lines) if re.match(r"_Z\S*decode_split_mfma_kernel\S*:\s*", l)]
+    starts = [i for i, l in enumerate(lines) if re.match(r"_Z\S*" + re.escape(kernel) + r"\S*:\s*", l)]
     problems, kernels, total, total_lds = [], 0, 0, 0
     for k, a in enumerate(starts):
         b = len(lines)
@@ -118,13 +121,14 @@ def check_text(text):
     return problems, kernels, total, total_lds
 
 
-def verify(path):
-    """Raises RuntimeError if the assembly file at `path` breaks a rule above."""
+def verify(path, kernel="decode_split_mfma_kernel", global_loads=True):
+    """Raises RuntimeError if the assembly file at `path` breaks a rule above.  global_loads: the kernels
+    are expected to hold hand-issued global loads (LDS reads are expected always)."""
     with open(path) as f:
-        problems, kernels, total, total_lds = check_text(f.read())
+        problems, kernels, total, total_lds = check_text(f.read(), kernel)
     if kernels == 0:
-        raise RuntimeError("%s: no decode_split_mfma_kernel found: nothing was checked" % path)
-    if total == 0 or total_lds == 0:
+        raise RuntimeError("%s: no %s found: nothing was checked" % (path, kernel))
+    if (global_loads and total == 0) or total_lds == 0:
         raise RuntimeError("%s: no hand-issued loads found in %d kernels: the check no longer sees them" % (path, kernels))
     if problems:
         raise RuntimeError("hand-issued loads: %d problem(s) in %s\n%s" % (len(problems), path, "\n".join(problems[:20])))
@@ -132,5 +136,5 @@ def verify(path):
 
 
 if __name__ == "__main__":
-    k, n, nl = verify(sys.argv[1])
+    k, n, nl = verify(sys.argv[1], *(sys.argv[2:3] or ["decode_split_mfma_kernel"]), global_loads=len(sys.argv) < 3)
     print("%d kernels, %d hand-issued global loads, %d hand-issued LDS reads: registers untouched until handed over" % (k, n, nl))
