@@ -59,7 +59,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--separate-append", dest="fused_step", action="store_false",
                     help="append and attend as two calls per layer instead of the one-call decode step")
-    ap.add_argument("--legs", default="c0,c1,c3,c4,cross,compressv,graph",
+    ap.add_argument("--legs", default="c0,c1,c3,c4,cross,cross128,compressv,graph",
                     help="other configurations measured after the headline one (comma list, or 'none')")
     ap.add_argument("--leg-steps", type=int, default=8, help="timed decode steps of each other configuration")
     return ap.parse_args()
@@ -316,7 +316,7 @@ def latency_leg(env, name, *, Hq, Hkv, T, dtype_name, reps=60):
     return res
 
 
-def graph_leg(env, fig, state, *, reps=4):
+def graph_leg(env, fig, state, *, reps=4, launches=3):
     """Decode steps replayed from one HIP graph (kv_decode_step_dev: the kernels take the lengths from
     device memory and advance them) on the cache of a finished decode workload, against that
     workload's eager steps."""
@@ -352,7 +352,7 @@ def graph_leg(env, fig, state, *, reps=4):
     nbytes = sum(kv.kv_decode_bytes(cache.handle, l) for l in range(L))
     return {"workload": "the decode steps of the leg before, every layer's step recorded once (kv_decode_step_dev: store and "
                         "quantise if the raw buffer fills, attention, merge) and replayed from one HIP graph",
-            "layers": L, "launches_per_step": 3 * L, "ms_per_step_graph": round(wall / reps * 1e3, 4),
+            "layers": L, "launches_per_step": launches * L, "ms_per_step_graph": round(wall / reps * 1e3, 4),
             "ms_per_step_eager": fig["ms_per_step"], "value_GBps_graph": round(nbytes * reps / wall / 1e9, 2),
             "value_GBps_eager": fig["value_GBps"]}
 
@@ -615,8 +615,17 @@ def main():
                 fx, sx = run_decode_workload(env, L=8, B=16, Hq=32, Hkv=8, G=32, T0=32768, steps=ks, warmup=kw,
                                              scheme="mixed248", seed=2000, mean_mode="cross", shared_inputs=True)
                 fx["workload"] = "headline shape with the mean over the kv heads (Eq. 1-2): first 8 layers of the bit map, batch 16, context 32768"
+                # the same steps replayed from one HIP graph (four launches per layer: the mean rows of a block about to be compressed first)
+                fx["graph_replay"] = graph_leg(env, fx, sx, launches=4)
                 other["cross_head_mean"] = fx
                 release(env, sx)
+            elif leg == "cross128":
+                fy, sy = run_decode_workload(env, L=8, B=16, Hq=32, Hkv=8, G=128, T0=32768, steps=ks, warmup=kw,
+                                             scheme="mixed248", seed=2000, mean_mode="cross", shared_inputs=True)
+                fy["workload"] = ("headline shape with the mean over the kv heads and groups of 128 (the format of the paper's Sec. 3 "
+                                  "storage example): first 8 layers of the bit map, batch 16, context 32768")
+                other["cross_head_mean_groups_of_128"] = fy
+                release(env, sy)
             elif leg == "graph":
                 # the headline shape's first 8 layers and the batch-1 long context, eager and replayed
                 fg, sg = run_decode_workload(env, L=8, B=16, Hq=32, Hkv=8, G=32, T0=32768, steps=ks, warmup=kw,
