@@ -428,20 +428,21 @@ def test_prefill_then_decode_full_size(kv, oracle, decode_path):
 
 
 @pytest.mark.parametrize("decode_path", [0], indirect=True, ids=["auto"])
-@pytest.mark.parametrize("bits", [4, 2, 8])
-def test_full_cache_shape_cross_head_sampled_units(kv, oracle, decode_path, bits):
-    """The same launch configuration with the mean over the kv heads (Eq. 1-2): one layer of each
-    width (4 bits: a workgroup of eight waves per sequence and split; 2 and 8 bits: two workgroups of
-    four that share the split's mean rows), records, mean plane and attention of sampled sequences
-    against the oracle."""
+@pytest.mark.parametrize("bits,G", [(4, 32), (2, 32), (8, 32), (4, 128), (2, 128), (8, 128)])
+def test_full_cache_shape_cross_head_sampled_units(kv, oracle, decode_path, bits, G):
+    """The same launch configuration with the mean over the kv heads (Eq. 1-2), with groups of 32 and of
+    128 (the format of the paper's Sec. 3 storage example): one layer of each width (4 bits: a workgroup
+    of eight waves per sequence and split; 2 and 8 bits: two workgroups of four that share the split's
+    mean rows), records, mean plane and attention of sampled sequences against the oracle."""
     import torch
 
-    print("case full_cache_shape_cross_head bits=%d" % bits, flush=True)
-    B, Hq, Hkv, d, G, T = 16, 32, 8, 128, 32, 32768 + 13
-    cfg = kv.make_config(1, B, Hq, Hkv, d, 32768 + 64, G, G, G, kv.KV_BF16, kv.KV_MEAN_CROSS_HEAD, [bits], [bits])
+    print("case full_cache_shape_cross_head bits=%d G=%d" % (bits, G), flush=True)
+    B, Hq, Hkv, d, T = 16, 32, 8, 128, 32768 + 13
+    cap = 32768 + 2 * G
+    cfg = kv.make_config(1, B, Hq, Hkv, d, cap, G, G, G, kv.KV_BF16, kv.KV_MEAN_CROSS_HEAD, [bits], [bits])
     gpu = kv.KVCache(cfg, zero=False)
     sample = (3, 15)
-    ocfg = oracle.OracleConfig(1, len(sample), Hq, Hkv, d, 32768 + 64, G, G, G, BF16, CROSS, [bits], [bits])
+    ocfg = oracle.OracleConfig(1, len(sample), Hq, Hkv, d, cap, G, G, G, BF16, CROSS, [bits], [bits])
     orc = oracle.OracleCache(ocfg)
     host_k, host_v = [], []
     for t0 in range(0, T, 8192):
@@ -457,7 +458,7 @@ def test_full_cache_shape_cross_head_sampled_units(kv, oracle, decode_path, bits
     assert gpu.lengths(0) == (orc.packed_len(0), orc.resid_len(0)) == (32768, 13)
     lay = kv.kv_cache_describe(gpu.handle, 0)
     img = orc.layer_image(0)
-    NB, n_rec = (32768 + 64) // G, 32768 // G
+    NB, n_rec = cap // G, 32768 // G
     dev = gpu.layers[0]
     olay = oracle.tada.record_layout(ocfg, 0)
     plane = 2 * G * d * 2  # bytes of one block's K and V mean rows
