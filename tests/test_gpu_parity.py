@@ -428,16 +428,19 @@ def test_prefill_then_decode_full_size(kv, oracle, decode_path):
 
 
 @pytest.mark.parametrize("decode_path", [0], indirect=True, ids=["auto"])
-@pytest.mark.parametrize("bits,G", [(4, 32), (2, 32), (8, 32), (4, 128), (2, 128), (8, 128)])
-def test_full_cache_shape_cross_head_sampled_units(kv, oracle, decode_path, bits, G):
+@pytest.mark.parametrize("bits,G,Hq,Hkv", [(4, 32, 32, 8), (2, 32, 32, 8), (8, 32, 32, 8), (4, 128, 32, 8), (2, 128, 32, 8),
+                                            (8, 128, 32, 8),
+                                            # eight query heads per kv head (two head groups per wave), four kv heads
+                                            (8, 32, 32, 4), (8, 32, 64, 8), (4, 32, 64, 8), (2, 32, 16, 4)])
+def test_full_cache_shape_cross_head_sampled_units(kv, oracle, decode_path, bits, G, Hq, Hkv):
     """The same launch configuration with the mean over the kv heads (Eq. 1-2), with groups of 32 and of
     128 (the format of the paper's Sec. 3 storage example): one layer of each width (4 bits: a workgroup
     of eight waves per sequence and split; 2 and 8 bits: two workgroups of four that share the split's
     mean rows), records, mean plane and attention of sampled sequences against the oracle."""
     import torch
 
-    print("case full_cache_shape_cross_head bits=%d G=%d" % (bits, G), flush=True)
-    B, Hq, Hkv, d, T = 16, 32, 8, 128, 32768 + 13
+    print("case full_cache_shape_cross_head bits=%d G=%d Hq=%d Hkv=%d" % (bits, G, Hq, Hkv), flush=True)
+    B, d, T = 16, 128, 32768 + 13
     cap = 32768 + 2 * G
     cfg = kv.make_config(1, B, Hq, Hkv, d, cap, G, G, G, kv.KV_BF16, kv.KV_MEAN_CROSS_HEAD, [bits], [bits])
     gpu = kv.KVCache(cfg, zero=False)
