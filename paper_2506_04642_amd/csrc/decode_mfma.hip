@@ -359,7 +359,6 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
 {
     static_assert(!(XH && MEAN), "cross-head layers store no per-record mean");
     constexpr bool XF = XH == 2; // both mean terms in this kernel, a wave per kv head
-    static_assert(!XF || !PG, "the fused cross-head form takes dense placement");
     constexpr int CW = XF ? 1 : NW;          // waves that share a unit's chunks
     constexpr int XSL = 3;                   // copies of every exchange buffer of the fused cross-head form
     constexpr bool H2 = GS == 128;         // a block is worked on as two halves
@@ -457,7 +456,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
     int slotv[NBC], slot_base = 0;
     auto load_slots = [&](int it0) {
         slot_base = it0;
-        const int blk0 = blk_of(wave + NW * (it0 + lane));
+        const int blk0 = blk_of(cw0 + CW * (it0 + lane));
 #pragma unroll
         for (int bi = 0; bi < NBC; bi++) {
             int blk = blk0 + bi < b_end ? blk0 + bi : blk0; // no second block: the first one again
@@ -471,8 +470,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
         const int blk0 = blk_of(ci);
         if (PG) {
             // every block of the chunk has a place of its own
-            const int it = (ci - wave) / NW;
-            if (it - slot_base >= 64) load_slots(it);
+            const int it = (ci - cw0) / CW;
+            if (it - slot_base >= 64) load_slots(it); // (the fused cross-head form moves the window itself)
 #pragma unroll
             for (int bi = 0; bi < NBC; bi++) {
                 const long long slot = __builtin_amdgcn_readlane(slotv[bi], it - slot_base);
@@ -507,13 +506,21 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
     if (cw0 < n_chunks) issue(cw0);
     // fused cross-head form: row r (token of the chunk that starts with block blk0) of the key (which
     // = 0) or value (1) mean plane.  The second block of a chunk that does not exist is read as the first.
-    auto mean_row_src = [&](int which, int blk0, int r) {
+    // (it: the number of that chunk among this wave's, for the slots under paged placement)
+    auto mean_row_src = [&](int which, int blk0, int r, int it) {
         int blk = blk0 + r / G;
         blk = blk < b_end ? blk : blk0;
-        // (dense placement: block slot = sequence * blocks per sequence + block; with blocks of 128
-        // tokens blk counts their halves)
-        return a.layer + gm.xmean_off +
-               ((((long long)b * gm.NB + blk / HB) * 2 + which) * GS + (blk % HB) * G + r % G) * (kHeadDim * 2);
+        // block slot = sequence * blocks per sequence + block, or what the table says; with blocks of
+        // 128 tokens blk counts their halves
+        long long slot;
+        if (PG) {
+            const int s0 = __builtin_amdgcn_readlane(slotv[0], it - slot_base);
+            const int s1 = __builtin_amdgcn_readlane(slotv[NBC - 1], it - slot_base);
+            slot = r / G == 0 ? s0 : s1;
+        } else {
+            slot = (long long)b * gm.NB + blk / HB;
+        }
+        return a.layer + gm.xmean_off + ((slot * 2 + which) * GS + (blk % HB) * G + r % G) * (kHeadDim * 2);
     };
 
     // ---- query of heads 4*hg + row: this lane's eight channels, widened and as binary16 pairs
@@ -572,11 +579,11 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
     int xs_w[NHG], xs_t0[NHG], xs_r[NHG], xs_rot[NHG]; // where this lane's scores are written and read (float index)
     int km_row[NHG];   // this lane's row (token of the chunk) of the key-mean tile as B operand
     v4f accv[NRB][NCT]; // sum_t p_t mean_V[t] (times 2^8) of heads 16 rb + 4 row + j, channel 16 (w NCT + c) + n
-    auto kmean_fetch = [&](u32x4 (&kb)[NHG][4], int blk0) {
+    auto kmean_fetch = [&](u32x4 (&kb)[NHG][4], int blk0, int it) {
 #pragma unroll
         for (int e = 0; e < NHG; e++)
 #pragma unroll
-            for (int ks = 0; ks < 4; ks++) glb_get16(kb[e][ks], mean_row_src(0, blk0, km_row[e]) + 64 * ks + 16 * row);
+            for (int ks = 0; ks < 4; ks++) glb_get16(kb[e][ks], mean_row_src(0, blk0, km_row[e], it) + 64 * ks + 16 * row);
     };
     auto kmean_scores = [&](const u32x4 (&kb)[NHG][4], int sl) {
         float *xs = (float *)lds_xs + sl * (HQP * 64);
@@ -628,7 +635,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
         for (int c0 = 0; c0 < 2; c0++)
             if (c0 < n_chunks) {
                 u32x4 kb[NHG][4];
-                kmean_fetch(kb, blk_of(c0));
+                kmean_fetch(kb, blk_of(c0), c0);
                 glb_wait_but<0>();
 #pragma unroll
                 for (int e = 0; e < NHG; e++)
@@ -768,12 +775,14 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
             // covers the latency: the key-mean rows of the chunk after the next (of this one again if
             // there is none: the scores are then worked out for nobody), and this wave's strip of this
             // chunk's value-mean tile, lane = token, 32 bytes per channel tile.
-            kmean_fetch(kmB, ci + 2 * CW < n_chunks ? blk_of(ci + 2 * CW) : blk0);
+            if (PG && itn + 2 - slot_base >= 64) load_slots(itn); // slots of this chunk and the next two
+            const bool two_on = ci + 2 * CW < n_chunks;
+            kmean_fetch(kmB, two_on ? blk_of(ci + 2 * CW) : blk0, two_on ? itn + 2 : itn);
 #pragma unroll
             for (int c = 0; c < NCT; c++)
 #pragma unroll
                 for (int hf = 0; hf < 2; hf++)
-                    glb_get16(vmp[c][hf], mean_row_src(1, blk0, lane) + 32 * (wave * NCT + c) + 16 * hf);
+                    glb_get16(vmp[c][hf], mean_row_src(1, blk0, lane, itn) + 32 * (wave * NCT + c) + 16 * hf);
         }
         PHASE(1)
         uint4 kc[NKL], vc[NVL];
@@ -1356,11 +1365,11 @@ struct DoMatch {
 };
 
 // Does the layer get the fused cross-head form (both mean terms inside the split kernel)?  It takes a
-// wave per kv head, 4 or 8 kv heads and dense placement.
+// wave per kv head, 4 or 8 kv heads.
 bool xhead_fused_fmt(const DecodeArgs &a)
 {
     const LayerGeom &g = a.geom;
-    return g.mean_mode == 1 && !g.table && (a.n_kv_heads == 4 || a.n_kv_heads == 8);
+    return g.mean_mode == 1 && (a.n_kv_heads == 4 || a.n_kv_heads == 8);
 }
 
 template <int B, int G, int GC, bool PG, class F> void pick_mean_heads_pg(const DecodeArgs &a, F &f)
@@ -1383,16 +1392,21 @@ template <int B, int G, int GC, bool PG, class F> void pick_mean_heads_pg(const 
 // mean row is fetched once per workgroup instead of once per pair that may have drifted apart in the
 // L2; at 2 bits the four-wave instance fits a compute unit twice and wins, 158 against 163 us; eight
 // 8-bit chunk buffers do not fit the LDS).
-template <int B, int G, int GC, class F> void pick_fused(const DecodeArgs &a, F &f)
+template <int B, int G, int GC, bool PG, class F> void pick_fused_pg(const DecodeArgs &a, F &f)
 {
     if constexpr (B == 4) {
         if (a.n_kv_heads == 8 && a.g <= 4) {
-            f.template run<B, G, GC, false, 8, 1, 2, false>(a);
+            f.template run<B, G, GC, false, 8, 1, 2, PG>(a);
             return;
         }
     }
-    if (a.g <= 4) f.template run<B, G, GC, false, 4, 1, 2, false>(a);
-    else f.template run<B, G, GC, false, 4, 2, 2, false>(a);
+    if (a.g <= 4) f.template run<B, G, GC, false, 4, 1, 2, PG>(a);
+    else f.template run<B, G, GC, false, 4, 2, 2, PG>(a);
+}
+template <int B, int G, int GC, class F> void pick_fused(const DecodeArgs &a, F &f)
+{
+    if (a.geom.table) pick_fused_pg<B, G, GC, true>(a, f);
+    else pick_fused_pg<B, G, GC, false>(a, f);
 }
 template <int B, int G, int GC, class F> void pick_mean_heads(const DecodeArgs &a, F &f)
 {

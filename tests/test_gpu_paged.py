@@ -92,17 +92,20 @@ def check_bytes_paged(kv, oracle, gpu, orc, table):
 
 
 @pytest.mark.parametrize("path", [0, 1], ids=["auto", "valu"])
-@pytest.mark.parametrize("bits,G,R,mode,g", [(4, 32, 32, CHAN, 4), (2, 64, 64, CHAN, 8), (8, 32, 64, NONE, 2),
-                                             (4, 32, 32, CROSS, 4), (2, 64, 64, CROSS, 2), (8, 128, 128, CHAN, 8),
-                                             (2, 128, 128, NONE, 3), (4, 128, 128, CROSS, 4)])
-def test_paged_prompts_then_decode_steps(kv, oracle, bits, G, R, mode, g, path):
+@pytest.mark.parametrize("bits,G,R,mode,g,Hkv", [(4, 32, 32, CHAN, 4, 2), (2, 64, 64, CHAN, 8, 2), (8, 32, 64, NONE, 2, 2),
+                                                 (4, 32, 32, CROSS, 4, 2), (2, 64, 64, CROSS, 2, 2), (8, 128, 128, CHAN, 8, 2),
+                                                 (2, 128, 128, NONE, 3, 2), (4, 128, 128, CROSS, 4, 2),
+                                                 # 4 or 8 kv heads: the cross-head mean's terms inside the matrix-core kernel
+                                                 (4, 32, 32, CROSS, 4, 8), (2, 64, 64, CROSS, 2, 4), (8, 128, 128, CROSS, 3, 4),
+                                                 (8, 32, 64, CROSS, 8, 8), (4, 128, 128, CROSS, 4, 8), (2, 32, 32, CROSS, 6, 4)])
+def test_paged_prompts_then_decode_steps(kv, oracle, bits, G, R, mode, g, Hkv, path):
     """Prompts of different lengths enter their slots one by one (slots handed out as needed, in a
     shuffled order, from a pool smaller than batch x capacity), then batch-wide one-call decode steps
     run across block boundaries while new slots are handed out."""
     import torch
 
-    print("case paged bits=%d G=%d R=%d mode=%d g=%d path=%d" % (bits, G, R, mode, g, path), flush=True)
-    B, Hkv = 4, 2
+    print("case paged bits=%d G=%d R=%d mode=%d g=%d Hkv=%d path=%d" % (bits, G, R, mode, g, Hkv, path), flush=True)
+    B = 4
     NB = 12
     gpu, orc, table, slots = make_paged(kv, oracle, B=B, Hkv=Hkv, g=g, T_max=NB * G, G=G, R=R, mode=mode, bits=bits,
                                         pool=26, seed=50 + bits + G, path=path)
@@ -172,6 +175,35 @@ def test_paged_bulk_append_with_rotation(kv, oracle):
     orc.append(0, k, v, rope_tables=(cos, sin, 0))
     check_bytes_paged(kv, oracle, gpu, orc, table)
     q = synth.make_q(881, B, Hkv * g, 128, BF16)
+    out = gpu.attend(0, to_dev(q, BF16))
+    torch.cuda.synchronize()
+    assert float(np.max(np.abs(out.cpu().numpy().astype(np.float64) - orc.attend(0, q)))) <= ATTN_TOL
+
+
+@pytest.mark.parametrize("bits,G,Hkv,g", [(4, 32, 8, 4), (2, 64, 4, 2), (8, 128, 4, 5)])
+def test_paged_cross_head_long_sequence_single_split(kv, oracle, bits, G, Hkv, g):
+    """Mean over the heads under paged placement, one split: a wave takes 80 chunks and more of its head,
+    so the window of block slots that it keeps (64 chunks) moves while the mean rows of the chunk after
+    the next are looked up through it."""
+    import torch
+
+    print("case paged cross long bits=%d G=%d Hkv=%d g=%d" % (bits, G, Hkv, g), flush=True)
+    B = 2
+    T = 64 * 83 + G // 2 + 3
+    NB = T // G + 2
+    gpu, orc, table, slots = make_paged(kv, oracle, B=B, Hkv=Hkv, g=g, T_max=NB * G, G=G, R=G, mode=CROSS, bits=bits,
+                                        pool=2 * NB - 1, seed=700 + bits, path=2)
+    for b, n in enumerate((T, T - 64 * 9 - 5)):
+        give_blocks(table, slots, b, n // G + 1)
+    push_table(gpu, table)
+    for b, n in enumerate((T, T - 64 * 9 - 5)):
+        k, v = synth.make_kv(710 + b, 1, n, Hkv, 128, BF16)
+        gpu.append_seq(0, b, to_dev(k[0], BF16), to_dev(v[0], BF16))
+        orc.append_seq(0, b, k[0], v[0])
+    check_bytes_paged(kv, oracle, gpu, orc, table)
+    kv.kv_set_decode_splits(gpu.handle, 1)
+    assert kv.kv_decode_splits(gpu.handle, 0) == 1
+    q = synth.make_q(720, B, Hkv * g, 128, BF16)
     out = gpu.attend(0, to_dev(q, BF16))
     torch.cuda.synchronize()
     assert float(np.max(np.abs(out.cpu().numpy().astype(np.float64) - orc.attend(0, q)))) <= ATTN_TOL
