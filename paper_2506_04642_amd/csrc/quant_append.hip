@@ -1066,7 +1066,7 @@ bool step_store_supported(const LayerGeom &g)
 {
     // the formats of the one-wavefront-per-item quantisers (launch_flush), dense placement
     const bool blocks = g.G == 32 || g.G == 64 || (g.G == 128 && g.Gc == 128);
-    return blocks && g.k_bits == g.v_bits && g.k_bits != 16 && !g.table;
+    return blocks && g.k_bits == g.v_bits && g.k_bits != 16;
 }
 
 hipError_t launch_resid_copy(const AppendArgs &a, hipStream_t s)

@@ -1015,7 +1015,8 @@ kv_status kv_decode_step_dev(const kv_cache *cache, int32_t layer, const void *k
     if (((uintptr_t)k_new % 16) || ((uintptr_t)v_new % 16) || ((uintptr_t)q % 16) || ((uintptr_t)out % 16)) return KV_E_ALIGN;
     if (stride_b % 8 || stride_h % 8) return KV_E_ALIGN;
     if (stride_h < c.head_dim || stride_b < 0) return KV_E_BAD_CONFIG;
-    if (!cache->active.empty() || c.pool_blocks > 0) return KV_E_UNSUPPORTED;
+    if (!cache->active.empty()) return KV_E_UNSUPPORTED;
+    if (c.pool_blocks > 0 && !cache->table) return KV_E_BAD_CONFIG; // paged placement without a block table
     if (!step_store_supported(cache->geom[layer]) || cache->decode_path == 1) return KV_E_UNSUPPORTED;
 
     // the launches are sized for the lengths the host knows, one step on (a recorded call is replayed
@@ -1040,6 +1041,8 @@ kv_status kv_decode_step_dev(const kv_cache *cache, int32_t layer, const void *k
 
     AppendArgs ap{};
     ap.geom = cache->geom[layer];
+    ap.geom.table = cache->table; // (paged placement: the blocks that replayed steps fill need their slots beforehand)
+    ap.geom.table_stride = cache->table_stride;
     ap.layer = cache->layers[layer];
     ap.k_new = (const uint16_t *)k_new;
     ap.v_new = (const uint16_t *)v_new;

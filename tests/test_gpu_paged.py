@@ -209,6 +209,69 @@ def test_paged_cross_head_long_sequence_single_split(kv, oracle, bits, G, Hkv, g
     assert float(np.max(np.abs(out.cpu().numpy().astype(np.float64) - orc.attend(0, q)))) <= ATTN_TOL
 
 
+@pytest.mark.parametrize("mode,Hkv,G", [(CHAN, 2, 32), (CROSS, 4, 32), (CROSS, 8, 64)])
+def test_paged_decode_steps_replayed_from_one_graph(kv, oracle, mode, Hkv, G):
+    """Decode steps on device-resident lengths over a paged cache: the blocks that the replayed steps will
+    fill have their slots beforehand; every replay equals the eager one-call step on a twin cache with
+    the same table bit for bit (same split count), the oracle within the tolerance, and at the end the
+    records gathered through the table are the oracle's."""
+    import torch
+
+    print("case paged graph steps mode=%d Hkv=%d G=%d" % (mode, Hkv, G), flush=True)
+    B, g, steps = 3, 2, G + 12
+    NB = 12
+    prompts = [5 * G + G - 2, G - 15, 2 * G + 3]
+    caches = []
+    for _ in range(3):  # the replayed cache, its eager twin, one for the one-time queries outside the capture
+        gpu, orc, table, slots = make_paged(kv, oracle, B=B, Hkv=Hkv, g=g, T_max=NB * G, G=G, R=G, mode=mode, bits=4,
+                                            pool=3 * NB - 4, seed=900 + G, path=2)
+        for b, n in enumerate(prompts):
+            give_blocks(table, slots, b, (n + steps) // G + 1)
+        push_table(gpu, table)
+        kv.kv_set_decode_splits(gpu.handle, 2)
+        caches.append((gpu, orc, table))
+    (gpu, orc, table), (twin, _, _), (warm, _, _) = caches
+    for b, n in enumerate(prompts):
+        k, v = synth.make_kv(910 + b, 1, n, Hkv, 128, BF16)
+        for c in (gpu, twin, warm):
+            c.append_seq(0, b, to_dev(k[0], BF16), to_dev(v[0], BF16))
+        orc.append_seq(0, b, k[0], v[0])
+    ks, vs = synth.make_kv(920, B, steps, Hkv, 128, BF16)
+    kd, vd = to_dev(ks, BF16), to_dev(vs, BF16)
+    k_st = torch.zeros((B, Hkv, 128), dtype=torch.bfloat16, device="cuda:0")
+    v_st = torch.zeros_like(k_st)
+    q_st = torch.zeros((B, Hkv * g, 128), dtype=torch.bfloat16, device="cuda:0")
+    o_st = torch.zeros((B, Hkv * g, 128), dtype=torch.float32, device="cuda:0")
+    warm.lengths_to_device()
+    warm.step_dev(0, k_st, v_st, q_st, o_st)
+    torch.cuda.synchronize()
+    gpu.lengths_to_device()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(graph, stream=side):
+        gpu.step_dev(0, k_st, v_st, q_st, o_st)
+    torch.cuda.synchronize()
+    for s_ in range(steps):
+        q = synth.make_q(930 + s_, B, Hkv * g, 128, BF16)
+        k_st.copy_(kd[:, s_])
+        v_st.copy_(vd[:, s_])
+        q_st.copy_(to_dev(q, BF16))
+        o_st.zero_()
+        graph.replay()
+        eager = twin.append_attend(0, kd[:, s_:s_ + 1], vd[:, s_:s_ + 1], to_dev(q, BF16))
+        torch.cuda.synchronize()
+        assert torch.equal(o_st, eager), "step %d differs from the eager step" % s_
+        orc.append(0, ks[:, s_:s_ + 1], vs[:, s_:s_ + 1])
+        if s_ % 9 == 0 or s_ == steps - 1:
+            assert float(np.max(np.abs(o_st.cpu().numpy().astype(np.float64) - orc.attend(0, q)))) <= ATTN_TOL, s_
+    gpu.advance(steps)
+    for b in range(B):
+        assert gpu.lengths(0, b) == twin.lengths(0, b) == (orc.packed_len(0, b), orc.resid_len(0, b))
+    check_bytes_paged(kv, oracle, gpu, orc, table)
+
+
 def test_paged_cache_needs_a_table(kv, oracle):
     import torch
 
