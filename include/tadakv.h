@@ -402,8 +402,9 @@ kv_status kv_decode_attn_static(const kv_cache *cache, int32_t layer, const void
  *       layer), so that the other entry points see the cache as it is; host only.
  * Served: group_tokens == group_channels in {32, 64, 128}, k_bits == v_bits in {2, 4, 8}, dense or
  * paged placement (the block table must already hold the slots of the blocks that replayed steps will
- * fill), all sequences active, layers on the matrix-core kernels, every mean mode -- KV_MEAN_CROSS_HEAD (Eq. 1-2) with 4 or 8 kv
- * heads (four kernels then: the mean rows of a block that is about to be compressed come first);
+ * fill), all sequences active, layers on the matrix-core kernels, every mean mode --
+ * KV_MEAN_CROSS_HEAD (Eq. 1-2) with a multiple of 4 kv heads (four kernels then: the mean rows of a
+ * block that is about to be compressed come first);
  * otherwise KV_E_UNSUPPORTED.  KV_E_BAD_CONFIG before kv_cache_lengths_to_device.  Other errors as
  * kv_append_decode_attn. */
 kv_status kv_dev_lengths_bytes(const kv_config *cfg, size_t *bytes);

@@ -405,18 +405,18 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
     uint32_t *stage = lds;                 // the chunk as it lies in the cache
     uint32_t *ak = lds + STAGE_DW, *av = ak;
 
-    // fused cross-head form: a workgroup takes NW kv heads of a sequence; with twice as many heads two
-    // workgroups share a (sequence, split) and read the same mean rows -- they sit 8 apart in the
-    // launch order when the split count allows (same XCD and so the same L2, resident together)
-    const int halves = XF ? a.n_kv_heads / NW : 1;
-    int sp = blockIdx.x, half = 0;
-    if (XF && halves == 2) {
+    // fused cross-head form: a workgroup takes NW kv heads of a sequence; with more heads several
+    // workgroups (parts) share a (sequence, split) and read the same mean rows -- they sit 8 apart in
+    // the launch order when the split count allows (same XCD and so the same L2, resident together)
+    const int parts = XF ? a.n_kv_heads / NW : 1;
+    int sp = blockIdx.x, half = 0; // half: which part
+    if (XF && parts > 1) {
         if (a.n_splits % 8 == 0) {
-            half = (sp >> 3) & 1;
-            sp = (sp & 7) | ((sp >> 4) << 3);
+            half = (sp >> 3) % parts;
+            sp = (sp & 7) | (((sp >> 3) / parts) << 3);
         } else {
-            half = sp & 1;
-            sp >>= 1;
+            half = sp % parts;
+            sp /= parts;
         }
     }
     const int u = XF ? (int)blockIdx.y * a.n_kv_heads + half * NW + wave : (int)blockIdx.y;
@@ -1322,7 +1322,7 @@ template <int B, int G, int GC, bool MEAN, int NW, int NHG, int XH, bool PG> int
 template <int B, int G, int GC, bool MEAN, int NW, int NHG, int XH, bool PG> hipError_t launch_inst(const DecodeArgs &a, hipStream_t s)
 {
     if (!RecLayout<B, G, GC, MEAN>::matches(a.geom)) return hipErrorInvalidValue;
-    if (XH == 2 && a.n_kv_heads != NW && a.n_kv_heads != 2 * NW) return hipErrorInvalidValue;
+    if (XH == 2 && (a.n_kv_heads < NW || a.n_kv_heads % NW != 0)) return hipErrorInvalidValue;
     dim3 grid(XH == 2 ? a.n_splits * (a.n_kv_heads / NW) : a.n_splits, XH == 2 ? a.batch : a.batch * a.n_kv_heads);
     (void)hipGetLastError(); // drop any stale error left by earlier runtime calls of this thread
     hipLaunchKernelGGL((decode_split_mfma_kernel<B, G, GC, MEAN, NW, NHG, XH, PG>), grid, dim3(64 * NW), 0, s, a);
@@ -1365,11 +1365,11 @@ struct DoMatch {
 };
 
 // Does the layer get the fused cross-head form (both mean terms inside the split kernel)?  It takes a
-// wave per kv head, 4 or 8 kv heads.
+// wave per kv head, a multiple of 4 kv heads.
 bool xhead_fused_fmt(const DecodeArgs &a)
 {
     const LayerGeom &g = a.geom;
-    return g.mean_mode == 1 && (a.n_kv_heads == 4 || a.n_kv_heads == 8);
+    return g.mean_mode == 1 && a.n_kv_heads % 4 == 0;
 }
 
 template <int B, int G, int GC, bool PG, class F> void pick_mean_heads_pg(const DecodeArgs &a, F &f)
@@ -1395,7 +1395,7 @@ template <int B, int G, int GC, bool PG, class F> void pick_mean_heads_pg(const 
 template <int B, int G, int GC, bool PG, class F> void pick_fused_pg(const DecodeArgs &a, F &f)
 {
     if constexpr (B == 4) {
-        if (a.n_kv_heads == 8 && a.g <= 4) {
+        if (a.n_kv_heads % 8 == 0 && a.g <= 4) {
             f.template run<B, G, GC, false, 8, 1, 2, PG>(a);
             return;
         }

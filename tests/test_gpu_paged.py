@@ -95,7 +95,7 @@ def check_bytes_paged(kv, oracle, gpu, orc, table):
 @pytest.mark.parametrize("bits,G,R,mode,g,Hkv", [(4, 32, 32, CHAN, 4, 2), (2, 64, 64, CHAN, 8, 2), (8, 32, 64, NONE, 2, 2),
                                                  (4, 32, 32, CROSS, 4, 2), (2, 64, 64, CROSS, 2, 2), (8, 128, 128, CHAN, 8, 2),
                                                  (2, 128, 128, NONE, 3, 2), (4, 128, 128, CROSS, 4, 2),
-                                                 # 4 or 8 kv heads: the cross-head mean's terms inside the matrix-core kernel
+                                                 # a multiple of 4 kv heads: the cross-head mean's terms inside the matrix-core kernel
                                                  (4, 32, 32, CROSS, 4, 8), (2, 64, 64, CROSS, 2, 4), (8, 128, 128, CROSS, 3, 4),
                                                  (8, 32, 64, CROSS, 8, 8), (4, 128, 128, CROSS, 4, 8), (2, 32, 32, CROSS, 6, 4)])
 def test_paged_prompts_then_decode_steps(kv, oracle, bits, G, R, mode, g, Hkv, path):

@@ -525,12 +525,15 @@ def test_cross_head_mean_mixed_layers_bf16(kv, oracle):
                                             # the remaining instances of the form with both mean terms inside the kernel
                                             (4, 32, 6, 900 + 7, 8), (8, 32, 8, 1200 + 5, 4), (2, 32, 3, 1300, 4),
                                             (4, 64, 4, 1100 + 64, 8), (4, 64, 2, 1000, 4), (2, 64, 7, 900 + 1, 4),
-                                            (8, 128, 6, 1536 + 20, 8), (4, 128, 3, 1400, 8), (8, 32, 7, 2100 + 3, 8)])
+                                            (8, 128, 6, 1536 + 20, 8), (4, 128, 3, 1400, 8), (8, 32, 7, 2100 + 3, 8),
+                                            # more kv heads: three, four or eight workgroups share a sequence's split
+                                            (4, 32, 1, 1100 + 7, 32), (2, 64, 2, 900, 16), (8, 32, 1, 1300, 32),
+                                            (4, 128, 3, 1500, 12), (4, 32, 2, 1000 + 5, 24), (8, 64, 5, 800, 12)])
 def test_cross_head_mean_on_the_matrix_cores(kv, oracle, decode_path, bits, G, g, T, Hkv):
     """Cross-head mean with the deviations on the matrix-core kernel; the two dense mean terms inside
-    that kernel (4 or 8 kv heads: a workgroup of 4 waves, or two that share a sequence's split, with one
-    or two groups of four query heads per kv head; blocks of 128 tokens as two halves) or in kernels of
-    their own (other head counts);
+    that kernel (a multiple of 4 kv heads: a workgroup of 4 or 8 waves, or several that share a sequence's
+    split, with one or two groups of four query heads per kv head; blocks of 128 tokens as two halves) or
+    in kernels of their own (other head counts);
     several splits, an odd block count, a raw tail."""
     print("case cross_head_mfma bits=%d G=%d g=%d T=%d Hkv=%d" % (bits, G, g, T, Hkv), flush=True)
     gpu, orc = make_pair(kv, oracle, B=2, Hq=Hkv * g, Hkv=Hkv, T_max=(T // G + 2) * G, G=G, Gc=G, dtype=BF16, mode=CROSS,
@@ -555,8 +558,8 @@ def test_cross_head_mean_with_a_forced_split_count(kv, oracle, decode_path):
     import torch
 
     print("case cross_head_forced_splits", flush=True)
-    B, Hkv, g, T = 16, 16, 2, 128 * 32 + 5
-    # (16 kv heads: a format whose dense mean terms run as kernels of their own and pass through the workspace)
+    B, Hkv, g, T = 16, 6, 4, 128 * 32 + 5
+    # (6 kv heads: a format whose dense mean terms run as kernels of their own and pass through the workspace)
     gpu, orc = make_pair(kv, oracle, B=B, Hq=Hkv * g, Hkv=Hkv, T_max=33 * 128, G=128, Gc=128, dtype=BF16, mode=CROSS,
                          k_bits=(4,))
     k, v = synth.make_kv(611, B, T, Hkv, 128, BF16)
@@ -574,7 +577,7 @@ def test_cross_head_mean_with_a_forced_split_count(kv, oracle, decode_path):
     assert e.value.status == kv.KV_E_WORKSPACE
     gpu.workspace = torch.empty(need, dtype=torch.uint8, device="cuda:0")
     gpu.ws_bytes = need
-    check_attention(gpu, orc, 0, q, BF16, units=[(0, 0), (7, 3), (15, 13)])
+    check_attention(gpu, orc, 0, q, BF16, units=[(0, 0), (7, 3), (15, 5)])
 
 
 # ------------------------------------------------------------------ matrix-core kernels, forced

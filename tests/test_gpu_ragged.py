@@ -43,7 +43,7 @@ def check_attend(gpu, orc, layer, q, dtype):
 @pytest.mark.parametrize("path", [0, 1, 2], ids=["auto", "valu", "mfma"])
 @pytest.mark.parametrize("bits,G,mode,Hkv", [(4, 32, CHAN, 2), (2, 64, CHAN, 2), (8, 32, NONE, 2), (4, 32, CROSS, 2),
                                               (4, 128, CHAN, 2), (2, 128, NONE, 2), (8, 128, CROSS, 2),
-                                              # 4 or 8 kv heads: the cross-head mean's terms inside the matrix-core kernel
+                                              # a multiple of 4 kv heads: the cross-head mean's terms inside the matrix-core kernel
                                               (2, 32, CROSS, 8), (4, 64, CROSS, 8), (8, 64, CROSS, 4), (4, 128, CROSS, 8),
                                               (2, 128, CROSS, 4)])
 def test_requests_join_step_and_leave(kv, oracle, path, bits, G, mode, Hkv):
