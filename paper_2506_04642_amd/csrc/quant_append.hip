@@ -401,7 +401,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 8))
     // the record) in LDS at the final offsets and then writes it out as one linear run of 16-byte
     // pieces; the words a lane produces are 4 to 16 bytes apart from its neighbours', and storing
     // them directly left partly written cache lines to be completed from memory.
-    constexpr int IMG_BYTES = G * kHeadDim * BITS / 8 + 768;
+    // (The same buffer first holds the block's raw rows, 8 KiB, for the token-order sum of the mean.)
+    constexpr int IMG_BYTES = G * kHeadDim * BITS / 8 + 768 > G * kHeadDim * 2 ? G * kHeadDim * BITS / 8 + 768 : G * kHeadDim * 2;
     __shared__ __attribute__((aligned(16))) unsigned char lds_img[kThreads / 64][IMG_BYTES];
     unsigned char *img = lds_img[wave];
 
@@ -442,6 +443,44 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 8))
             for (int j = 0; j < 8; j++) pre[j] = *(const uint4 *)(src_row(a, which, b, h, fb * G + 8 * tg + j) + c8 * 8);
         }
 
+        // ---- per-channel block mean, the sum: over the tokens in order
+        uint32_t mean_pair = 0u; // binary16 means of channels 2 lane and 2 lane + 1
+        if (gm.mean_mode == 0 && !ROPE) {
+            // The raw rows go through LDS ([token][sixteen 16-byte pieces], the pieces of a row
+            // rotated by four per eight tokens so that the four lanes of a quad, whose rows lie
+            // 2 KiB apart, write to different banks) and come back with a channel pair's 32 tokens
+            // in one lane (lane l: channels 2 l and 2 l + 1; one whole row per read instruction):
+            // every lane adds, instead of a quarter of them at a time.  The wave's LDS operations
+            // complete in the order issued.
+            const int piece_w = (c8 + 4 * tg) & 15;
+#pragma unroll
+            for (int j = 0; j < 8; j++) *(uint4 *)(img + (8 * tg + j) * 256 + piece_w * 16) = pre[j];
+            float s0 = 0.0f, s1 = 0.0f;
+            const unsigned char *rd = img + (lane & 3) * 4;
+            // (eight rows at a time: all 32 reads at once would hold 32 more registers)
+#pragma unroll 1
+            for (int tq = 0; tq < G / 8; tq++) {
+                const unsigned char *rq = rd + tq * 2048 + ((((lane >> 2) + 4 * tq) & 15) << 4);
+                uint32_t w[8];
+#pragma unroll
+                for (int k = 0; k < 8; k++) w[k] = *(const uint32_t *)(rq + k * 256);
+                if (gm.dtype == 1) {
+#pragma unroll
+                    for (int k = 0; k < 8; k++) {
+                        s0 = s0 + __uint_as_float(w[k] << 16);
+                        s1 = s1 + __uint_as_float(w[k] & 0xFFFF0000u);
+                    }
+                } else {
+#pragma unroll
+                    for (int k = 0; k < 8; k++) {
+                        s0 = s0 + f16_val((uint16_t)(w[k] & 0xFFFFu));
+                        s1 = s1 + f16_val((uint16_t)(w[k] >> 16));
+                    }
+                }
+            }
+            mean_pair = (uint32_t)f16_rne(s0 / (float)G) | ((uint32_t)f16_rne(s1 / (float)G) << 16);
+        }
+
         float x[8][8]; // [token j][channel e]
         widen_pieces(pre, gm.dtype, x);
 
@@ -453,38 +492,52 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 8))
 
         // ---- mean-centring
         if (gm.mean_mode == 0) {
-            // per channel over the block: the sum runs over the tokens in order, so the four lanes of
-            // a quad add their eight tokens one after the other and hand the running sum on
-            float acc[8];
+            // per channel over the block: the sum runs over the tokens in order
+            float m[8];
+            const int mean_off = (which == 0 ? gm.k_mean : gm.v_mean) - base_off;
+            if (ROPE) {
+                // (the instance that rotates the keys, which then exist in registers only) the four
+                // lanes of a quad add their eight tokens one after the other and hand the running sum on
+                float acc[8];
 #pragma unroll
-            for (int e = 0; e < 8; e++) acc[e] = 0.0f;
+                for (int e = 0; e < 8; e++) acc[e] = 0.0f;
 #pragma unroll
-            for (int p = 0; p < 4; p++) {
-                float cin[8];
+                for (int p = 0; p < 4; p++) {
+                    float cin[8];
 #pragma unroll
-                for (int e = 0; e < 8; e++)
-                    cin[e] = p == 0 ? 0.0f : (p == 1 ? quad_bcast_f<0>(acc[e]) : (p == 2 ? quad_bcast_f<1>(acc[e]) : quad_bcast_f<2>(acc[e])));
-                if (tg == p) {
+                    for (int e = 0; e < 8; e++)
+                        cin[e] = p == 0 ? 0.0f : (p == 1 ? quad_bcast_f<0>(acc[e]) : (p == 2 ? quad_bcast_f<1>(acc[e]) : quad_bcast_f<2>(acc[e])));
+                    if (tg == p) {
 #pragma unroll
-                    for (int e = 0; e < 8; e++) {
-                        float sacc = cin[e];
+                        for (int e = 0; e < 8; e++) {
+                            float sacc = cin[e];
 #pragma unroll
-                        for (int j = 0; j < 8; j++) sacc = sacc + x[j][e];
-                        acc[e] = sacc;
+                            for (int j = 0; j < 8; j++) sacc = sacc + x[j][e];
+                            acc[e] = sacc;
+                        }
                     }
                 }
-            }
-            uint32_t mpk[4];
-            float m[8];
+                uint32_t mpk[4];
 #pragma unroll
-            for (int e = 0; e < 8; e++) {
-                const uint32_t m16 = quad_bcast_u<3>((uint32_t)f16_rne(acc[e] / (float)G));
-                m[e] = f16_val((uint16_t)m16);
-                if (e & 1) mpk[e >> 1] |= m16 << 16;
-                else mpk[e >> 1] = m16;
+                for (int e = 0; e < 8; e++) {
+                    const uint32_t m16 = quad_bcast_u<3>((uint32_t)f16_rne(acc[e] / (float)G));
+                    m[e] = f16_val((uint16_t)m16);
+                    if (e & 1) mpk[e >> 1] |= m16 << 16;
+                    else mpk[e >> 1] = m16;
+                }
+                if (tg == 0) *(uint4 *)(img + mean_off + c8 * 16) = uint4{mpk[0], mpk[1], mpk[2], mpk[3]};
+            } else {
+                // (summed above, while only the raw rows were held) the record's mean row is the lanes'
+                // words in order
+                const uint32_t mp = mean_pair;
+                *(uint32_t *)(img + mean_off + lane * 4) = mp;
+                // channels 8 c8 + 2 k and + 2 k + 1 are quad lane k's
+                const uint32_t q0 = quad_bcast_u<0>(mp), q1 = quad_bcast_u<1>(mp), q2 = quad_bcast_u<2>(mp), q3 = quad_bcast_u<3>(mp);
+                m[0] = f16_val((uint16_t)(q0 & 0xFFFFu)); m[1] = f16_val((uint16_t)(q0 >> 16));
+                m[2] = f16_val((uint16_t)(q1 & 0xFFFFu)); m[3] = f16_val((uint16_t)(q1 >> 16));
+                m[4] = f16_val((uint16_t)(q2 & 0xFFFFu)); m[5] = f16_val((uint16_t)(q2 >> 16));
+                m[6] = f16_val((uint16_t)(q3 & 0xFFFFu)); m[7] = f16_val((uint16_t)(q3 >> 16));
             }
-            if (tg == 0)
-                *(uint4 *)(img + ((which == 0 ? gm.k_mean : gm.v_mean) - base_off) + c8 * 16) = uint4{mpk[0], mpk[1], mpk[2], mpk[3]};
 #pragma unroll
             for (int j = 0; j < 8; j++)
 #pragma unroll
