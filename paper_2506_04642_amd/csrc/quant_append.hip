@@ -891,6 +891,184 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ?
     }
 }
 
+// Blocks of 64 or 128 tokens, one read of the input: the G / 32 wavefronts of a workgroup share an
+// item, each with one part of 32 tokens in registers (the lane layout of flush_wave_kernel), and
+// exchange through LDS what spans the block.  The per-channel sum of the mean runs over the tokens in
+// order, so it passes from part to part: every wave first brings its rows into the layout of the sum
+// (through LDS: lane l holds the 32 tokens of channels 2 l and 2 l + 1), then the waves add one after
+// the other, each starting from the sum the wave before left in LDS (a barrier per part; the
+// workgroups that share the compute unit fill the gaps).  The keys' extrema are those of the parts'.
+// Codes, metadata and mean go into one image of the record's key or value part in LDS (it takes the
+// place of the raw rows, which nobody needs once the sums are formed), which the waves then write out
+// together as one linear run.  For the plain bulk append (no rotation, no device-resident lengths);
+// the other calls use flush_wave_parts_kernel, which reads the block twice.
+template <int G, int GC, int BITS>
+__global__ __launch_bounds__(64 * (G / 32)) __attribute__((amdgpu_waves_per_eu(3, 8))) void flush_coop_kernel(AppendArgs a, int n_items)
+{
+    constexpr int NP = G / 32; // parts of 32 tokens = waves of the workgroup
+    constexpr int NGV = kHeadDim / GC;
+    constexpr int qmax = (1 << BITS) - 1;
+    constexpr int IMG_BYTES = WaveImage<G, GC, BITS, false>::BYTES;
+    constexpr int UNI_BYTES = IMG_BYTES > NP * 8192 ? IMG_BYTES : NP * 8192;
+    __shared__ __attribute__((aligned(16))) unsigned char lds_uni[UNI_BYTES]; // raw rows [part][8 KiB], then the image
+    __shared__ __attribute__((aligned(16))) float lds_sum[kHeadDim];         // running sums, by channel
+    __shared__ __attribute__((aligned(16))) uint32_t lds_mean[kHeadDim / 2]; // the means as binary16 pairs
+    __shared__ __attribute__((aligned(16))) float lds_ext[NP][2][kHeadDim];  // the parts' minima and maxima (keys)
+    const LayerGeom &gm = a.geom;
+    const int lane = threadIdx.x & 63;
+    const int part = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int tg = lane & 3, c8 = lane >> 2;
+    const int U = a.batch * a.n_kv_heads;
+    const int mode = gm.mean_mode;
+    unsigned char *img = lds_uni;
+    unsigned char *raw = lds_uni + part * 8192;
+
+    // (the grid is even: a workgroup alternates between keys and values, which cost differently, and
+    // items 2 j and 2 j + 1 are the two sides of one block)
+    for (int it = (int)blockIdx.x; it < n_items; it += (int)gridDim.x) {
+        const int which = (it ^ (it / (int)gridDim.x)) & 1, u = (it >> 1) % U, fb = (it >> 1) / U;
+        const int b = u / a.n_kv_heads, h = u % a.n_kv_heads;
+        unsigned char *rec = a.layer + record_offset(gm, a.n_kv_heads, a.b0 + b, h, a.first_block + fb);
+        const int base_off = which == 0 ? gm.k_codes : gm.v_codes;
+
+        // ---- this wave's rows: 32 part + 8 tg .. + 7 of the block, channels 8 c8 .. + 7
+        uint4 pre[8];
+#pragma unroll
+        for (int j = 0; j < 8; j++) pre[j] = *(const uint4 *)(src_row(a, which, b, h, fb * G + 32 * part + 8 * tg + j) + c8 * 8);
+
+        float m[8];
+#pragma unroll
+        for (int e = 0; e < 8; e++) m[e] = 0.0f;
+        if (mode == 0) {
+            // the rows in the layout of the sum ([token][sixteen 16-byte pieces], the pieces of a row
+            // rotated by four per eight tokens: see flush_wave_kernel), widened
+            const int piece_w = (c8 + 4 * tg) & 15;
+#pragma unroll
+            for (int j = 0; j < 8; j++) *(uint4 *)(raw + (8 * tg + j) * 256 + piece_w * 16) = pre[j];
+            float xs0[32], xs1[32];
+            const unsigned char *rd = raw + (lane & 3) * 4;
+#pragma unroll
+            for (int tq = 0; tq < 4; tq++) {
+                const unsigned char *rq = rd + tq * 2048 + ((((lane >> 2) + 4 * tq) & 15) << 4);
+#pragma unroll
+                for (int k = 0; k < 8; k++) {
+                    const uint32_t w = *(const uint32_t *)(rq + k * 256);
+                    if (gm.dtype == 1) {
+                        xs0[8 * tq + k] = __uint_as_float(w << 16);
+                        xs1[8 * tq + k] = __uint_as_float(w & 0xFFFF0000u);
+                    } else {
+                        xs0[8 * tq + k] = f16_val((uint16_t)(w & 0xFFFFu));
+                        xs1[8 * tq + k] = f16_val((uint16_t)(w >> 16));
+                    }
+                }
+            }
+            // the waves add in turn
+#pragma unroll
+            for (int p = 0; p < NP; p++) {
+                if (part == p) {
+                    float s0 = 0.0f, s1 = 0.0f;
+                    if (p > 0) {
+                        const float2 v = *(const float2 *)&lds_sum[2 * lane];
+                        s0 = v.x;
+                        s1 = v.y;
+                    }
+#pragma unroll
+                    for (int t = 0; t < 32; t++) {
+                        s0 = s0 + xs0[t];
+                        s1 = s1 + xs1[t];
+                    }
+                    if (p < NP - 1) {
+                        *(float2 *)&lds_sum[2 * lane] = float2{s0, s1};
+                    } else {
+                        // (every wave is past its reads of the raw rows: the image may take their place)
+                        const uint32_t mp = (uint32_t)f16_rne(s0 / (float)G) | ((uint32_t)f16_rne(s1 / (float)G) << 16);
+                        lds_mean[lane] = mp;
+                        *(uint32_t *)(img + ((which == 0 ? gm.k_mean : gm.v_mean) - base_off) + lane * 4) = mp;
+                    }
+                }
+                __syncthreads();
+            }
+            const uint4 mv = *(const uint4 *)&lds_mean[c8 * 4];
+            const uint32_t mw[4] = {mv.x, mv.y, mv.z, mv.w};
+#pragma unroll
+            for (int k = 0; k < 4; k++) {
+                m[2 * k] = f16_val((uint16_t)(mw[k] & 0xFFFFu));
+                m[2 * k + 1] = f16_val((uint16_t)(mw[k] >> 16));
+            }
+        }
+
+        // ---- deviations
+        float x[8][8]; // [token j][channel e]
+        widen_pieces(pre, gm.dtype, x);
+        if (mode == 1) {
+            // mean over the kv heads per (token, channel), written by xhead_mean_kernel before this launch
+            const uint16_t *xm = (const uint16_t *)(a.layer + xmean_offset(gm, a.b0 + b, a.first_block + fb, which));
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                const uint4 mv = *(const uint4 *)(xm + (32 * part + 8 * tg + j) * kHeadDim + c8 * 8);
+                const uint32_t wv[4] = {mv.x, mv.y, mv.z, mv.w};
+#pragma unroll
+                for (int k = 0; k < 4; k++) {
+                    x[j][2 * k] = x[j][2 * k] - f16_val((uint16_t)(wv[k] & 0xFFFFu));
+                    x[j][2 * k + 1] = x[j][2 * k + 1] - f16_val((uint16_t)(wv[k] >> 16));
+                }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 8; j++)
+#pragma unroll
+            for (int e = 0; e < 8; e++) x[j][e] = x[j][e] - m[e];
+
+        if (which == 0) {
+            // ---- keys: one group per channel over the block's tokens: this part's extrema (eight
+            // tokens in the lane, four lanes), then all parts'
+            float mn[8], mx[8];
+#pragma unroll
+            for (int e = 0; e < 8; e++) {
+                float lo = vmin(vmin3(x[0][e], x[1][e], x[2][e]), vmin3(x[3][e], x[4][e], vmin3(x[5][e], x[6][e], x[7][e])));
+                float hi = vmax(vmax3(x[0][e], x[1][e], x[2][e]), vmax3(x[3][e], x[4][e], vmax3(x[5][e], x[6][e], x[7][e])));
+                lo = vmin(lo, dpp_f<0xB1>(lo));
+                hi = vmax(hi, dpp_f<0xB1>(hi));
+                mn[e] = vmin(lo, dpp_f<0x4E>(lo));
+                mx[e] = vmax(hi, dpp_f<0x4E>(hi));
+            }
+            if (tg == 0) {
+                *(float4 *)&lds_ext[part][0][8 * c8] = float4{mn[0], mn[1], mn[2], mn[3]};
+                *(float4 *)&lds_ext[part][0][8 * c8 + 4] = float4{mn[4], mn[5], mn[6], mn[7]};
+                *(float4 *)&lds_ext[part][1][8 * c8] = float4{mx[0], mx[1], mx[2], mx[3]};
+                *(float4 *)&lds_ext[part][1][8 * c8 + 4] = float4{mx[4], mx[5], mx[6], mx[7]};
+            }
+            __syncthreads();
+#pragma unroll
+            for (int q = 0; q < NP; q++) {
+                const float4 l0 = *(const float4 *)&lds_ext[q][0][8 * c8], l1 = *(const float4 *)&lds_ext[q][0][8 * c8 + 4];
+                const float4 h0 = *(const float4 *)&lds_ext[q][1][8 * c8], h1 = *(const float4 *)&lds_ext[q][1][8 * c8 + 4];
+                const float lv[8] = {l0.x, l0.y, l0.z, l0.w, l1.x, l1.y, l1.z, l1.w};
+                const float hv[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
+#pragma unroll
+                for (int e = 0; e < 8; e++) {
+                    mn[e] = q == 0 ? lv[e] : vmin(mn[e], lv[e]);
+                    mx[e] = q == 0 ? hv[e] : vmax(mx[e], hv[e]);
+                }
+            }
+            // (every wave works out the same metadata and stores the same scale / zero rows)
+            float sc[8], rs[8], z[8];
+            key_metadata(mn, mx, qmax, lane, img + (gm.k_scale - base_off), img + (gm.k_zero - base_off), sc, rs, z);
+            emit_key_words<BITS>(x, sc, rs, z, part, lane, img);
+        } else {
+            emit_value_half<GC, BITS, G / 16>(x, part, lane, img, img + (gm.v_meta - base_off));
+        }
+        __syncthreads(); // the image is complete
+
+        int part_bytes;
+        if (which == 0) part_bytes = (mode == 0 ? gm.k_mean : gm.k_zero) + 256 - base_off;
+        else part_bytes = (mode == 0 ? gm.v_mean + 256 : gm.v_meta + G * NGV * 4) - base_off;
+        for (int off = (int)threadIdx.x * 16; off < part_bytes; off += NP * 64 * 16)
+            *(uint4 *)(rec + base_off + off) = *(const uint4 *)(img + off);
+        __syncthreads(); // the image is in registers before the next item's rows overwrite it
+    }
+}
+
 // Cross-head mean (Eq. 1-2): for every token of a block and every channel, the mean over the kv
 // heads, m = f16_rne((x_0 + x_1 + ... + x_{H-1}) / H) with the sum taken in head order.
 // grid (blocks to flush, batch, K|V); written to the layer's mean plane.
@@ -1072,6 +1250,26 @@ template <int G, int GC, int BITS, bool ROPE> hipError_t launch_flush_wave_parts
     return note_launch(hipGetLastError());
 }
 
+template <int G, int GC, int BITS> hipError_t launch_flush_coop(const AppendArgs &a, hipStream_t s)
+{
+    const int U = a.batch * a.n_kv_heads;
+    const long long items = (long long)a.n_flush_blocks * U * 2;
+    if (items > 0x7FFFFFFF) return hipErrorInvalidValue;
+    constexpr int threads = 64 * (G / 32);
+    static const int slots = [] {
+        int per_cu = 0, dev = 0, cus = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, flush_coop_kernel<G, GC, BITS>, threads, 0) != hipSuccess ||
+            hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+            return 0;
+        return (per_cu * cus) & ~1; // even: see the kernel's item order
+    }();
+    if (slots < 2) return hipErrorInvalidValue;
+    const int grid = items < slots ? (int)items : slots; // (items is even)
+    hipLaunchKernelGGL((flush_coop_kernel<G, GC, BITS>), dim3(grid), dim3(threads), 0, s, a, (int)items);
+    return note_launch(hipGetLastError());
+}
+
 hipError_t launch_flush(const AppendArgs &a, hipStream_t s)
 {
     const int U = a.batch * a.n_kv_heads;
@@ -1096,6 +1294,14 @@ hipError_t launch_flush(const AppendArgs &a, hipStream_t s)
         return gc == 32 ? TADAKV_WAVE(32, false) : gc == 64 ? TADAKV_WAVE(64, false) : TADAKV_WAVE(128, false);
 #undef TADAKV_WAVE
     }
+    // the plain bulk append of blocks of 64 / 128 tokens: a workgroup per item, one read of the input
+    const bool coop = a.rope == 0 && a.len_dev == nullptr && a.sides == 0;
+#define TADAKV_COOP(GV, GCV) \
+    (kb == 2 ? launch_flush_coop<GV, GCV, 2>(a, s) : kb == 4 ? launch_flush_coop<GV, GCV, 4>(a, s) : launch_flush_coop<GV, GCV, 8>(a, s))
+    if (coop && a.geom.G == 64 && kb == a.geom.v_bits && kb != 16)
+        return a.geom.Gc == 32 ? TADAKV_COOP(64, 32) : a.geom.Gc == 64 ? TADAKV_COOP(64, 64) : TADAKV_COOP(64, 128);
+    if (coop && a.geom.G == 128 && a.geom.Gc == 128 && kb == a.geom.v_bits && kb != 16) return TADAKV_COOP(128, 128);
+#undef TADAKV_COOP
     if (a.geom.G == 64 && kb == a.geom.v_bits && kb != 16) {
         // blocks of 64 tokens: the same arithmetic in two passes over two parts of 32 tokens
         const int gc = a.geom.Gc;
