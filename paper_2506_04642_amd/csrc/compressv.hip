@@ -101,7 +101,7 @@ __device__ __forceinline__ GroupId group_of(const ProjectArgs &p, int f)
 // mean), or as raw rows into the residual buffer; and, if asked for, into the caller's tensor.
 template <int DT, int GC, int BITS>
 __device__ __forceinline__ void tile_out(const ProjectArgs &p, float (&x)[8][8], const GroupId &g, int h, int lane,
-                                         unsigned char *img)
+                                         unsigned char *img, uint32_t mean_pair)
 {
     constexpr int G = 32, NGV = kHeadDim / GC;
     const LayerGeom &gm = p.geom;
@@ -132,37 +132,17 @@ __device__ __forceinline__ void tile_out(const ProjectArgs &p, float (&x)[8][8],
     // ---- the quantiser's value side on the tile (Eq. 1-4 with the per-channel block mean, or no mean)
     const int base_off = gm.v_codes;
     if (gm.mean_mode == 0) {
-        // sum over the block's tokens in token order: the four lanes of a quad add their eight
-        // tokens one after the other and hand the running sum on
-        float acc[8];
-#pragma unroll
-        for (int e = 0; e < 8; e++) acc[e] = 0.0f;
-#pragma unroll
-        for (int q = 0; q < 4; q++) {
-            float cin[8];
-#pragma unroll
-            for (int e = 0; e < 8; e++)
-                cin[e] = q == 0 ? 0.0f : (q == 1 ? quad_bcast_f<0>(acc[e]) : (q == 2 ? quad_bcast_f<1>(acc[e]) : quad_bcast_f<2>(acc[e])));
-            if (tg == q) {
-#pragma unroll
-                for (int e = 0; e < 8; e++) {
-                    float sacc = cin[e];
-#pragma unroll
-                    for (int j = 0; j < 8; j++) sacc = sacc + x[j][e];
-                    acc[e] = sacc;
-                }
-            }
-        }
-        uint32_t mpk[4];
+        // mean_pair: the binary16 means of channels 2 lane and 2 lane + 1 (the caller formed the sums over
+        // the block's tokens, in token order, with a channel's 32 tokens in one lane); the record's mean
+        // row is the lanes' words in order, and channels 8 c8 + 2 k and + 2 k + 1 are quad lane k's
+        *(uint32_t *)(img + (gm.v_mean - base_off) + lane * 4) = mean_pair;
+        const uint32_t q0 = quad_bcast_u<0>(mean_pair), q1 = quad_bcast_u<1>(mean_pair), q2 = quad_bcast_u<2>(mean_pair),
+                       q3 = quad_bcast_u<3>(mean_pair);
         float m[8];
-#pragma unroll
-        for (int e = 0; e < 8; e++) {
-            const uint32_t m16 = quad_bcast_u<3>((uint32_t)f16_rne(acc[e] / (float)G));
-            m[e] = f16_val((uint16_t)m16);
-            if (e & 1) mpk[e >> 1] |= m16 << 16;
-            else mpk[e >> 1] = m16;
-        }
-        if (tg == 0) *(uint4 *)(img + (gm.v_mean - base_off) + c8 * 16) = uint4{mpk[0], mpk[1], mpk[2], mpk[3]};
+        m[0] = f16_val((uint16_t)(q0 & 0xFFFFu)); m[1] = f16_val((uint16_t)(q0 >> 16));
+        m[2] = f16_val((uint16_t)(q1 & 0xFFFFu)); m[3] = f16_val((uint16_t)(q1 >> 16));
+        m[4] = f16_val((uint16_t)(q2 & 0xFFFFu)); m[5] = f16_val((uint16_t)(q2 >> 16));
+        m[6] = f16_val((uint16_t)(q3 & 0xFFFFu)); m[7] = f16_val((uint16_t)(q3 >> 16));
 #pragma unroll
         for (int j = 0; j < 8; j++)
 #pragma unroll
@@ -336,8 +316,32 @@ __global__ __launch_bounds__(256 * NH) void compressv_gemm_kernel(ProjectArgs p)
                 x[2 * k + 1][e] = widen16((uint16_t)(wv[k] >> 16), DT);
             }
         }
+        // the per-channel sums of the block mean, over the tokens in order: a channel's 32 tokens are
+        // 64 contiguous bytes of the transposed tile, so lane l adds up channels 2 l and 2 l + 1 (every
+        // lane adds; in the quantiser's layout three quarters of a quad's adds would be masked)
+        uint32_t mean_pair = 0u;
+        if (p.geom.mean_mode == 0 && p.mode != 1) {
+            float sm[2];
+#pragma unroll
+            for (int c = 0; c < 2; c++) {
+                const unsigned char *col = tt + (2 * lane + c) * kTTStride;
+                float sacc = 0.0f;
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    const uint4 pcs = *(const uint4 *)(col + 16 * q);
+                    const uint32_t wv[4] = {pcs.x, pcs.y, pcs.z, pcs.w};
+#pragma unroll
+                    for (int k = 0; k < 4; k++) {
+                        sacc = sacc + widen16((uint16_t)(wv[k] & 0xFFFFu), DT);
+                        sacc = sacc + widen16((uint16_t)(wv[k] >> 16), DT);
+                    }
+                }
+                sm[c] = sacc;
+            }
+            mean_pair = (uint32_t)f16_rne(sm[0] / 32.0f) | ((uint32_t)f16_rne(sm[1] / 32.0f) << 16);
+        }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // the tile is in registers before the next group overwrites it
-        tile_out<DT, GC, BITS>(p, x, g, h, lane, img);
+        tile_out<DT, GC, BITS>(p, x, g, h, lane, img, mean_pair);
     }
 }
 

@@ -75,6 +75,23 @@ def test_bit_widths_and_groups(kv, oracle, bits, dtype, G, Gc):
     check_attention(gpu, orc, 0, synth.make_q(bits + G, 2, 8, 128, dtype), dtype)
 
 
+@pytest.mark.parametrize("mode", [CHAN, CROSS, NONE])
+@pytest.mark.parametrize("G,Gc,bits", [(64, 32, 4), (64, 64, 2), (64, 128, 8), (128, 128, 4), (128, 128, 2)])
+def test_bulk_append_of_long_blocks_in_uneven_calls(kv, oracle, G, Gc, bits, mode):
+    """Blocks of 64 / 128 tokens through the bulk append (a workgroup per item, a wave per 32-token
+    part): calls that leave raw tokens behind, calls whose first block takes rows from the raw buffer
+    and rows from the call, a call of many blocks, and more items than one launch holds workgroups."""
+    print("case long blocks G=%d Gc=%d bits=%d mode=%d" % (G, Gc, bits, mode), flush=True)
+    B, H = 4, 8
+    chunks = [G - 7, 2 * G + 3, 5, 27 * G + 1, G - 2]  # 30 blocks in all: 1920 items for 32 units
+    T = sum(chunks)
+    gpu, orc = make_pair(kv, oracle, B=B, Hq=H, Hkv=H, T_max=31 * G, G=G, Gc=Gc, dtype=BF16, mode=mode, k_bits=(bits,))
+    k, v = synth.make_kv(4100 + G + bits, B, T, H, 128, BF16)
+    append_both(gpu, orc, 0, k, v, BF16, chunks=chunks)
+    check_bytes(gpu, orc, 0)
+    check_attention(gpu, orc, 0, synth.make_q(4100 + G, B, H, 128, BF16), BF16)
+
+
 @pytest.mark.parametrize("G", [32, 64, 128])
 @pytest.mark.parametrize("bits", [2, 4, 8])
 def test_exact_ties_round_to_the_even_code(kv, oracle, bits, G):
