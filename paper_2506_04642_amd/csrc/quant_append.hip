@@ -902,8 +902,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROPE ?
 // place of the raw rows, which nobody needs once the sums are formed), which the waves then write out
 // together as one linear run.  For the plain bulk append (no rotation, no device-resident lengths);
 // the other calls use flush_wave_parts_kernel, which reads the block twice.
-template <int G, int GC, int BITS>
-__global__ __launch_bounds__(64 * (G / 32)) __attribute__((amdgpu_waves_per_eu(3, 8))) void flush_coop_kernel(AppendArgs a, int n_items)
+template <int G, int GC, int BITS, bool ROPE>
+__global__ __launch_bounds__(64 * (G / 32)) __attribute__((amdgpu_waves_per_eu(ROPE ? 2 : 3, 8))) void flush_coop_kernel(AppendArgs a, int n_items)
 {
     constexpr int NP = G / 32; // parts of 32 tokens = waves of the workgroup
     constexpr int NGV = kHeadDim / GC;
@@ -935,6 +935,26 @@ __global__ __launch_bounds__(64 * (G / 32)) __attribute__((amdgpu_waves_per_eu(3
         uint4 pre[8];
 #pragma unroll
         for (int j = 0; j < 8; j++) pre[j] = *(const uint4 *)(src_row(a, which, b, h, fb * G + 32 * part + 8 * tg + j) + c8 * 8);
+
+        if (ROPE && which == 0) {
+            // the key rows of the call are turned here, once (rows from the raw buffer were turned when
+            // they were stored), and go back into their 16-bit form, which holds them exactly: what
+            // follows takes them as it takes rows that need no turning, and no register keeps the
+            // widened values through the sums
+            float xr[8][8];
+            widen_pieces(pre, gm.dtype, xr);
+            const int tn0 = fb * G + 32 * part + 8 * tg - a.r_old; // this lane's first token in the call's input
+            if (gm.dtype == 1) rope_in_lanes<1>(xr, a, tn0, lane);
+            else rope_in_lanes<0>(xr, a, tn0, lane);
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                uint32_t w[4];
+#pragma unroll
+                for (int q = 0; q < 4; q++)
+                    w[q] = gm.dtype == 1 ? pack16_exact<1>(xr[j][2 * q], xr[j][2 * q + 1]) : pack16_exact<0>(xr[j][2 * q], xr[j][2 * q + 1]);
+                pre[j] = uint4{w[0], w[1], w[2], w[3]};
+            }
+        }
 
         float m[8];
 #pragma unroll
@@ -1250,7 +1270,7 @@ template <int G, int GC, int BITS, bool ROPE> hipError_t launch_flush_wave_parts
     return note_launch(hipGetLastError());
 }
 
-template <int G, int GC, int BITS> hipError_t launch_flush_coop(const AppendArgs &a, hipStream_t s)
+template <int G, int GC, int BITS, bool ROPE> hipError_t launch_flush_coop(const AppendArgs &a, hipStream_t s)
 {
     const int U = a.batch * a.n_kv_heads;
     const long long items = (long long)a.n_flush_blocks * U * 2;
@@ -1258,7 +1278,7 @@ template <int G, int GC, int BITS> hipError_t launch_flush_coop(const AppendArgs
     constexpr int threads = 64 * (G / 32);
     static const int slots = [] {
         int per_cu = 0, dev = 0, cus = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, flush_coop_kernel<G, GC, BITS>, threads, 0) != hipSuccess ||
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, flush_coop_kernel<G, GC, BITS, ROPE>, threads, 0) != hipSuccess ||
             hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
             return 0;
@@ -1266,7 +1286,7 @@ template <int G, int GC, int BITS> hipError_t launch_flush_coop(const AppendArgs
     }();
     if (slots < 2) return hipErrorInvalidValue;
     const int grid = items < slots ? (int)items : slots; // (items is even)
-    hipLaunchKernelGGL((flush_coop_kernel<G, GC, BITS>), dim3(grid), dim3(threads), 0, s, a, (int)items);
+    hipLaunchKernelGGL((flush_coop_kernel<G, GC, BITS, ROPE>), dim3(grid), dim3(threads), 0, s, a, (int)items);
     return note_launch(hipGetLastError());
 }
 
@@ -1294,13 +1314,16 @@ hipError_t launch_flush(const AppendArgs &a, hipStream_t s)
         return gc == 32 ? TADAKV_WAVE(32, false) : gc == 64 ? TADAKV_WAVE(64, false) : TADAKV_WAVE(128, false);
 #undef TADAKV_WAVE
     }
-    // the plain bulk append of blocks of 64 / 128 tokens: a workgroup per item, one read of the input
-    const bool coop = a.rope == 0 && a.len_dev == nullptr && a.sides == 0;
-#define TADAKV_COOP(GV, GCV) \
-    (kb == 2 ? launch_flush_coop<GV, GCV, 2>(a, s) : kb == 4 ? launch_flush_coop<GV, GCV, 4>(a, s) : launch_flush_coop<GV, GCV, 8>(a, s))
-    if (coop && a.geom.G == 64 && kb == a.geom.v_bits && kb != 16)
-        return a.geom.Gc == 32 ? TADAKV_COOP(64, 32) : a.geom.Gc == 64 ? TADAKV_COOP(64, 64) : TADAKV_COOP(64, 128);
-    if (coop && a.geom.G == 128 && a.geom.Gc == 128 && kb == a.geom.v_bits && kb != 16) return TADAKV_COOP(128, 128);
+    // the bulk append of blocks of 64 / 128 tokens: a workgroup per item, one read of the input
+    const bool coop = a.len_dev == nullptr && a.sides == 0;
+#define TADAKV_COOP(GV, GCV, R) \
+    (kb == 2 ? launch_flush_coop<GV, GCV, 2, R>(a, s) : kb == 4 ? launch_flush_coop<GV, GCV, 4, R>(a, s) : launch_flush_coop<GV, GCV, 8, R>(a, s))
+    if (coop && a.geom.G == 64 && kb == a.geom.v_bits && kb != 16) {
+        if (a.rope != 0) return a.geom.Gc == 32 ? TADAKV_COOP(64, 32, true) : a.geom.Gc == 64 ? TADAKV_COOP(64, 64, true) : TADAKV_COOP(64, 128, true);
+        return a.geom.Gc == 32 ? TADAKV_COOP(64, 32, false) : a.geom.Gc == 64 ? TADAKV_COOP(64, 64, false) : TADAKV_COOP(64, 128, false);
+    }
+    if (coop && a.geom.G == 128 && a.geom.Gc == 128 && kb == a.geom.v_bits && kb != 16)
+        return a.rope != 0 ? TADAKV_COOP(128, 128, true) : TADAKV_COOP(128, 128, false);
 #undef TADAKV_COOP
     if (a.geom.G == 64 && kb == a.geom.v_bits && kb != 16) {
         // blocks of 64 tokens: the same arithmetic in two passes over two parts of 32 tokens

@@ -40,6 +40,15 @@ template <int DT> __device__ __forceinline__ float round16(float f)
     return __half2float(__float2half_rn(f));
 }
 
+// Two values that the 16-bit type holds exactly (DT: 0 binary16, 1 bfloat16), as the type's bit patterns
+// in one word, a in the low half: one instruction.
+template <int DT> __device__ __forceinline__ uint32_t pack16_exact(float a, float b)
+{
+    if (DT == 1) return __builtin_amdgcn_perm(__float_as_uint(b), __float_as_uint(a), 0x07060302u);
+    typedef _Float16 h2_t __attribute__((ext_vector_type(2)));
+    return __builtin_bit_cast(uint32_t, (h2_t)__builtin_amdgcn_cvt_pkrtz(a, b)); // (exact values: no rounding takes place)
+}
+
 // One rotated pair: (a, b) -> (a cos - b sin, b cos + a sin), rounded to the 16-bit type and widened again.
 template <int DT>
 __device__ __forceinline__ void rope_pair_t(float xa, float xb, float c, float s, float &ya, float &yb)
@@ -205,13 +214,16 @@ __device__ __forceinline__ void rope_in_lanes(float (&x)[8][8], const AppendArgs
             const float cv[8] = {cs[d][0].x, cs[d][0].y, cs[d][0].z, cs[d][0].w, cs[d][1].x, cs[d][1].y, cs[d][1].z, cs[d][1].w};
             const float sv[8] = {sn[d][0].x, sn[d][0].y, sn[d][0].z, sn[d][0].w, sn[d][1].x, sn[d][1].y, sn[d][1].z, sn[d][1].w};
             if (half_mode) {
-                // lower channel of the pair: x cos - partner sin; upper: x cos + partner sin
+                // lower channel of the pair: x cos - partner sin; upper: x cos + partner sin.  The sign
+                // goes into the sine once per token (a product with the negated sine is the negated
+                // product, and adding that is the subtraction, bit for bit).
                 const bool lower = c8 < 8;
 #pragma unroll
                 for (int e = 0; e < 8; e++) {
+                    const float sg = lower ? -sv[e] : sv[e];
                     const float xp = from_lane_f(x[j][e], lane ^ 32);
-                    const float p1 = x[j][e] * cv[e], p2 = xp * sv[e];
-                    const float y = round16<DT>(lower ? p1 - p2 : p1 + p2);
+                    const float p1 = x[j][e] * cv[e], p2 = xp * sg;
+                    const float y = round16<DT>(p1 + p2);
                     x[j][e] = turn ? y : x[j][e];
                 }
             } else {
