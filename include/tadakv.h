@@ -423,6 +423,15 @@ kv_status kv_cache_advance(kv_cache *cache, int32_t layer, int32_t n_steps);
  * KV_E_BAD_CONFIG for fewer than 16 bytes. */
 kv_status kv_stream_read_probe(const void *buf, size_t bytes, void *sink8, void *stream);
 
+/* Measurement aid, not part of the method: the calling thread's next launch of the matrix-core split
+ * kernel (kv_decode_attn_split, kv_append_decode_attn_split and the calls built on them) records the
+ * kernel's own begin and end into the two HIP events (hipEvent_t, created with timing enabled; host
+ * handles), so that hipEventElapsedTime between them is the kernel's execution time as a profiler's
+ * kernel trace reports it -- events recorded on the stream before and after the call also count the
+ * dispatch gaps on either side (1 - 2 us).  One-shot: that launch clears the request; (NULL, NULL)
+ * cancels it; one of the two NULL: KV_E_NULL.  The vector-ALU kernels ignore it. */
+kv_status kv_time_next_split(void *begin_event, void *end_event);
+
 const char *kv_strerror(kv_status s);
 
 /* Text of the HIP error behind the calling thread's most recent KV_E_HIP ("no error" if none). */

@@ -30,7 +30,7 @@ KV_MEAN_CHANNEL_BLOCK, KV_MEAN_CROSS_HEAD, KV_MEAN_NONE = 0, 1, 2
 EXPORTS = [
     "kv_cache_bytes", "kv_workspace_bytes", "kv_cache_create", "kv_cache_destroy", "kv_cache_set_block_table", "kv_cache_set_active", "kv_cache_reset",
     "kv_cache_len", "kv_cache_len_seq", "kv_cache_reset_seq", "kv_cache_describe", "kv_quant_append", "kv_quant_append_seq", "kv_rope_quant_append", "kv_compressv_append", "kv_append_decode_attn", "kv_append_decode_attn_split", "kv_decode_attn", "kv_decode_attn_split",
-    "kv_decode_attn_merge", "kv_decode_attn_merge16", "kv_dequant", "kv_decode_splits", "kv_decode_bytes", "kv_set_decode_path", "kv_decode_path_used", "kv_set_decode_splits", "kv_decode_workspace_need", "kv_decode_attn_static", "kv_dev_lengths_bytes", "kv_cache_lengths_to_device", "kv_decode_step_dev", "kv_cache_advance", "kv_stream_read_probe", "kv_strerror", "kv_last_hip_error",
+    "kv_decode_attn_merge", "kv_decode_attn_merge16", "kv_dequant", "kv_decode_splits", "kv_decode_bytes", "kv_set_decode_path", "kv_decode_path_used", "kv_set_decode_splits", "kv_decode_workspace_need", "kv_decode_attn_static", "kv_dev_lengths_bytes", "kv_cache_lengths_to_device", "kv_decode_step_dev", "kv_cache_advance", "kv_stream_read_probe", "kv_time_next_split", "kv_strerror", "kv_last_hip_error",
 ]
 
 
@@ -92,6 +92,7 @@ _lib.kv_cache_lengths_to_device.argtypes = [_vp, _vp, _vp]
 _lib.kv_decode_step_dev.argtypes = [_vp, _i32, _vp, _vp, _i64, _i64, _vp, _vp, _vp, ctypes.c_size_t, _vp]
 _lib.kv_cache_advance.argtypes = [_vp, _i32, _i32]
 _lib.kv_stream_read_probe.argtypes = [_vp, ctypes.c_size_t, _vp, _vp]
+_lib.kv_time_next_split.argtypes = [_vp, _vp]
 _lib.kv_strerror.argtypes = [_i32]
 _lib.kv_strerror.restype = ctypes.c_char_p
 _lib.kv_last_hip_error.argtypes = []
@@ -321,6 +322,11 @@ def kv_decode_step_dev(cache: int, layer: int, k_ptr: int, v_ptr: int, stride_b:
 
 def kv_cache_advance(cache: int, layer: int, n_steps: int) -> None:
     _check(_lib.kv_cache_advance(cache, layer, n_steps), "kv_cache_advance")
+
+
+def kv_time_next_split(begin_event: int, end_event: int) -> None:
+    """hipEvent_t handles (torch.cuda.Event(enable_timing=True).cuda_event of events recorded once before)."""
+    _check(_lib.kv_time_next_split(begin_event or None, end_event or None), "kv_time_next_split")
 
 
 def kv_stream_read_probe(buf_ptr: int, nbytes: int, sink_ptr: int = 0, stream: int = 0) -> None:

@@ -33,6 +33,7 @@
 //   key-side producer  lane (row, vq, qa): head 4*hg + row, channels 32*vq + 16*ph + 4*qa + {0..3}.
 //   matrix operands    lane (row, n): operand row / column n, 16 consecutive k-slots of group `row`.
 #include "tadakv_internal.h"
+#include <hip/hip_ext.h>
 #include <hip/hip_fp16.h>
 
 namespace tadakv {
@@ -1318,6 +1319,9 @@ template <int B, int G, int GC, bool MEAN, int NW, int NHG, int XH, bool PG> int
     return n;
 }
 
+// Events that the calling thread's next split launch records its own begin and end into (set_split_timing_events)
+thread_local hipEvent_t t_ev_begin = nullptr, t_ev_end = nullptr;
+
 // XH == 2 (both cross-head mean terms inside the kernel): a workgroup per (sequence, split) and NW kv heads.
 template <int B, int G, int GC, bool MEAN, int NW, int NHG, int XH, bool PG> hipError_t launch_inst(const DecodeArgs &a, hipStream_t s)
 {
@@ -1325,7 +1329,14 @@ template <int B, int G, int GC, bool MEAN, int NW, int NHG, int XH, bool PG> hip
     if (XH == 2 && (a.n_kv_heads < NW || a.n_kv_heads % NW != 0)) return hipErrorInvalidValue;
     dim3 grid(XH == 2 ? a.n_splits * (a.n_kv_heads / NW) : a.n_splits, XH == 2 ? a.batch : a.batch * a.n_kv_heads);
     (void)hipGetLastError(); // drop any stale error left by earlier runtime calls of this thread
-    hipLaunchKernelGGL((decode_split_mfma_kernel<B, G, GC, MEAN, NW, NHG, XH, PG>), grid, dim3(64 * NW), 0, s, a);
+    if (t_ev_begin && t_ev_end) {
+        // the dispatch itself stamps the events: the kernel's execution, without the gaps before and after it
+        hipExtLaunchKernelGGL((decode_split_mfma_kernel<B, G, GC, MEAN, NW, NHG, XH, PG>), grid, dim3(64 * NW), 0, s, t_ev_begin,
+                              t_ev_end, 0, a);
+        t_ev_begin = t_ev_end = nullptr;
+    } else {
+        hipLaunchKernelGGL((decode_split_mfma_kernel<B, G, GC, MEAN, NW, NHG, XH, PG>), grid, dim3(64 * NW), 0, s, a);
+    }
     return note_launch(hipGetLastError());
 }
 
@@ -1474,6 +1485,12 @@ int decode_mfma_splits(const DecodeArgs &a)
     DoPlan p;
     pick(a, p);
     return p.result;
+}
+
+void set_split_timing_events(hipEvent_t begin, hipEvent_t end)
+{
+    t_ev_begin = begin;
+    t_ev_end = end;
 }
 
 hipError_t launch_decode_split_mfma(const DecodeArgs &a, hipStream_t s)

@@ -1062,6 +1062,13 @@ kv_status kv_decode_step_dev(const kv_cache *cache, int32_t layer, const void *k
     return launch_decode_merge(a, s) == hipSuccess ? KV_OK : KV_E_HIP;
 }
 
+kv_status kv_time_next_split(void *begin_event, void *end_event)
+{
+    if ((begin_event == nullptr) != (end_event == nullptr)) return KV_E_NULL;
+    set_split_timing_events((hipEvent_t)begin_event, (hipEvent_t)end_event);
+    return KV_OK;
+}
+
 kv_status kv_stream_read_probe(const void *buf, size_t bytes, void *sink8, void *stream)
 {
     if (!buf) return KV_E_NULL;

@@ -185,6 +185,8 @@ bool compressv_supported(const LayerGeom &g); // formats the fused value project
 hipError_t launch_compressv(const ProjectArgs &p, hipStream_t s);
 hipError_t launch_decode_split_valu(const DecodeArgs &a, hipStream_t s);
 hipError_t launch_decode_split_mfma(const DecodeArgs &a, hipStream_t s);
+// the calling thread's next matrix-core split launch records its begin and end into these (one-shot; null cancels)
+void set_split_timing_events(hipEvent_t begin, hipEvent_t end);
 bool decode_mfma_supported(const DecodeArgs &a);
 bool xhead_fused(const DecodeArgs &a); // cross-head mean: both mean terms inside the matrix-core split kernel
 int decode_mfma_splits(const DecodeArgs &a); // preferred split count of the matrix-core kernel
