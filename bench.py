@@ -616,7 +616,7 @@ def main():
                 f3, s3 = run_decode_workload(env, L=80, B=1, Hq=64, Hkv=8, G=64, T0=131072, steps=ks, warmup=kw,
                                              scheme="mixed24_8ends", seed=3000, shared_inputs=True, chunk=16384)
                 f3["workload"] = "config 3: 80 layers, batch 1, 64q/8kv heads, context 131072, bf16, G=Gc=64, mixed 2/4-bit map with 8-bit first and last two layers (seed 3000)"
-                # a layer is one launch of 30-60 us on 8 units there: the same steps replayed from one HIP graph
+                # the same steps replayed from one HIP graph (a layer is one launch of 30-60 us on 8 units there)
                 f3["graph_replay"] = graph_leg(env, f3, s3)
                 other["config3_long_context"] = f3
                 release(env, s3)
