@@ -92,6 +92,21 @@ def test_bulk_append_of_long_blocks_in_uneven_calls(kv, oracle, G, Gc, bits, mod
     check_attention(gpu, orc, 0, synth.make_q(4100 + G, B, H, 128, BF16), BF16)
 
 
+@pytest.mark.parametrize("G,R", [(64, 128), (64, 192), (128, 256)])
+def test_long_blocks_with_a_longer_raw_buffer(kv, oracle, G, R):
+    """Blocks of 64 / 128 tokens with a raw buffer of several blocks (R > G): a flush compresses R / G
+    blocks at once, most of whose rows come from the raw buffer and the rest from the call."""
+    print("case long blocks G=%d R=%d" % (G, R), flush=True)
+    B, H = 2, 4
+    chunks = [R - 3, 5, 2 * R + G + 1, 1, R - 1]
+    T = sum(chunks)
+    gpu, orc = make_pair(kv, oracle, B=B, Hq=2 * H, Hkv=H, T_max=8 * R, G=G, Gc=G, R=R, dtype=F16, k_bits=(4,))
+    k, v = synth.make_kv(5200 + G + R, B, T, H, 128, F16)
+    append_both(gpu, orc, 0, k, v, F16, chunks=chunks)
+    check_bytes(gpu, orc, 0)
+    check_attention(gpu, orc, 0, synth.make_q(5200 + G, B, 2 * H, 128, F16), F16)
+
+
 @pytest.mark.parametrize("G", [32, 64, 128])
 @pytest.mark.parametrize("bits", [2, 4, 8])
 def test_exact_ties_round_to_the_even_code(kv, oracle, bits, G):
