@@ -1444,7 +1444,16 @@ template <class F> void pick(const DecodeArgs &a, F &f)
         }
         return;
     }
-    if (a.geom.G == 32) {
+    if (a.geom.G == 32 && a.geom.Gc == 128) {
+        // (keys in groups of 32 tokens, one value group per token)
+        if (bits == 2) pick_mean_heads<2, 32, 128>(a, f);
+        else if (bits == 4) pick_mean_heads<4, 32, 128>(a, f);
+        else pick_mean_heads<8, 32, 128>(a, f);
+    } else if (a.geom.G == 128 && a.geom.Gc == 32) {
+        if (bits == 2) pick_mean_heads<2, 128, 32>(a, f);
+        else if (bits == 4) pick_mean_heads<4, 128, 32>(a, f);
+        else pick_mean_heads<8, 128, 32>(a, f);
+    } else if (a.geom.G == 32) {
         if (bits == 2) pick_mean_heads<2, 32, 32>(a, f);
         else if (bits == 4) pick_mean_heads<4, 32, 32>(a, f);
         else pick_mean_heads<8, 32, 32>(a, f);
@@ -1468,7 +1477,8 @@ bool decode_mfma_supported(const DecodeArgs &a)
     const LayerGeom &g = a.geom;
     if (g.k_bits != g.v_bits) return false;
     if (!(g.k_bits == 2 || g.k_bits == 4 || g.k_bits == 8)) return false;
-    if (!((g.G == 32 && g.Gc == 32) || (g.G == 64 && g.Gc == 64) || (g.G == 128 && g.Gc == 128)))
+    const bool mixed = (g.G == 32 && g.Gc == 128) || (g.G == 128 && g.Gc == 32); // (not with the cross-head mean)
+    if (!((g.G == 32 && g.Gc == 32) || (g.G == 64 && g.Gc == 64) || (g.G == 128 && g.Gc == 128) || (mixed && g.mean_mode != 1)))
         return false;
     if (a.g > 8) return false;
     if (g.mean_mode == 1 && a.n_q_heads > 64) return false; // the dense mean terms keep all query heads of a sequence in LDS

@@ -92,6 +92,25 @@ def test_bulk_append_of_long_blocks_in_uneven_calls(kv, oracle, G, Gc, bits, mod
     check_attention(gpu, orc, 0, synth.make_q(4100 + G, B, H, 128, BF16), BF16)
 
 
+@pytest.mark.parametrize("mode", [CHAN, NONE])
+@pytest.mark.parametrize("g", [4, 8])
+@pytest.mark.parametrize("bits", [2, 4, 8])
+@pytest.mark.parametrize("G,Gc", [(32, 128), (128, 32)])
+def test_mixed_group_sizes(kv, oracle, decode_path, G, Gc, bits, g, mode):
+    """Key groups of 32 tokens with one value group per token, and key groups of 128 tokens with value
+    groups of 32 channels: served by the matrix-core kernels under the automatic choice (several
+    chunks per wave, a ragged tail of raw tokens, one and two head groups)."""
+    print("case mixed groups G=%d Gc=%d bits=%d g=%d mode=%d" % (G, Gc, bits, g, mode), flush=True)
+    B, H = 2, 2
+    T = 9 * 128 + 77
+    gpu, orc = make_pair(kv, oracle, B=B, Hq=H * g, Hkv=H, T_max=10 * 128, G=G, Gc=Gc, dtype=BF16, mode=mode, k_bits=(bits,))
+    k, v = synth.make_kv(6100 + G + bits + g, B, T, H, 128, BF16)
+    append_both(gpu, orc, 0, k, v, BF16, chunks=[T - 1, 1])
+    assert kv.kv_decode_path_used(gpu.handle, 0) == (1 if decode_path == 1 else 2)
+    check_bytes(gpu, orc, 0)
+    check_attention(gpu, orc, 0, synth.make_q(6100 + G + g, B, H * g, 128, BF16), BF16)
+
+
 @pytest.mark.parametrize("G,R", [(64, 128), (64, 192), (128, 256)])
 def test_long_blocks_with_a_longer_raw_buffer(kv, oracle, G, R):
     """Blocks of 64 / 128 tokens with a raw buffer of several blocks (R > G): a flush compresses R / G
