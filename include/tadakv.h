@@ -341,8 +341,8 @@ kv_status kv_decode_bytes(const kv_cache *cache, int32_t layer, size_t *bytes);
 /* Select the decode kernel family: 0 = automatic (fastest available for the layer),
  * 1 = portable vector-ALU kernels, 2 = matrix-core (MFMA) kernels where supported.
  * The matrix-core kernels serve layers with k_bits == v_bits in {2, 4, 8}, group_tokens ==
- * group_channels in {32, 64, 128} -- and, except with KV_MEAN_CROSS_HEAD, (group_tokens,
- * group_channels) = (32, 128) and (128, 32) -- and up to 8 query heads per kv head (with KV_MEAN_CROSS_HEAD:
+ * group_channels in {32, 64, 128} -- and, except with KV_MEAN_CROSS_HEAD, any pair of these
+ * sizes -- and up to 8 query heads per kv head (with KV_MEAN_CROSS_HEAD:
  * at most 64 query heads); with path 2 a decode of any other layer returns KV_E_UNSUPPORTED.  The
  * vector-ALU kernels serve every format (about twenty times slower: use kv_decode_path_used to see
  * which family a layer gets).  Returns KV_E_BAD_CONFIG for other values.  Affects later calls on
@@ -351,8 +351,8 @@ kv_status kv_set_decode_path(kv_cache *cache, int32_t path);
 
 /* Which kernel family a decode call of `layer` would run on in the cache's present state:
  * *path = 1 (vector-ALU kernels) or 2 (matrix-core kernels).  A layer whose format the matrix-core
- * kernels do not take (different widths for keys and values, most pairs group_tokens != group_channels, a
- * 16-bit layer) is served by the vector-ALU kernels under the automatic choice, at a small fraction
+ * kernels do not take (different widths for keys and values, group_tokens != group_channels with
+ * KV_MEAN_CROSS_HEAD, a 16-bit layer) is served by the vector-ALU kernels under the automatic choice, at a small fraction
  * of the rate: this call makes that visible.  Errors as kv_decode_splits. */
 kv_status kv_decode_path_used(const kv_cache *cache, int32_t layer, int32_t *path);
 

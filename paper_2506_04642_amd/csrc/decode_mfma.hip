@@ -1444,28 +1444,24 @@ template <class F> void pick(const DecodeArgs &a, F &f)
         }
         return;
     }
-    if (a.geom.G == 32 && a.geom.Gc == 128) {
-        // (keys in groups of 32 tokens, one value group per token)
-        if (bits == 2) pick_mean_heads<2, 32, 128>(a, f);
-        else if (bits == 4) pick_mean_heads<4, 32, 128>(a, f);
-        else pick_mean_heads<8, 32, 128>(a, f);
-    } else if (a.geom.G == 128 && a.geom.Gc == 32) {
-        if (bits == 2) pick_mean_heads<2, 128, 32>(a, f);
-        else if (bits == 4) pick_mean_heads<4, 128, 32>(a, f);
-        else pick_mean_heads<8, 128, 32>(a, f);
-    } else if (a.geom.G == 32) {
-        if (bits == 2) pick_mean_heads<2, 32, 32>(a, f);
-        else if (bits == 4) pick_mean_heads<4, 32, 32>(a, f);
-        else pick_mean_heads<8, 32, 32>(a, f);
-    } else if (a.geom.G == 64) {
-        if (bits == 2) pick_mean_heads<2, 64, 64>(a, f);
-        else if (bits == 4) pick_mean_heads<4, 64, 64>(a, f);
-        else pick_mean_heads<8, 64, 64>(a, f);
-    } else {
-        if (bits == 2) pick_mean_heads<2, 128, 128>(a, f);
-        else if (bits == 4) pick_mean_heads<4, 128, 128>(a, f);
-        else pick_mean_heads<8, 128, 128>(a, f);
+    // every pair (tokens per key group, channels per value group) of 32, 64, 128
+#define TADAKV_PICK(GV, GCV)                                      \
+    if (a.geom.G == GV && a.geom.Gc == GCV) {                     \
+        if (bits == 2) pick_mean_heads<2, GV, GCV>(a, f);         \
+        else if (bits == 4) pick_mean_heads<4, GV, GCV>(a, f);    \
+        else pick_mean_heads<8, GV, GCV>(a, f);                   \
+        return;                                                   \
     }
+    TADAKV_PICK(32, 32)
+    TADAKV_PICK(64, 64)
+    TADAKV_PICK(128, 128)
+    TADAKV_PICK(32, 64)
+    TADAKV_PICK(32, 128)
+    TADAKV_PICK(64, 32)
+    TADAKV_PICK(64, 128)
+    TADAKV_PICK(128, 32)
+    TADAKV_PICK(128, 64)
+#undef TADAKV_PICK
 }
 
 } // namespace
@@ -1477,9 +1473,9 @@ bool decode_mfma_supported(const DecodeArgs &a)
     const LayerGeom &g = a.geom;
     if (g.k_bits != g.v_bits) return false;
     if (!(g.k_bits == 2 || g.k_bits == 4 || g.k_bits == 8)) return false;
-    const bool mixed = (g.G == 32 && g.Gc == 128) || (g.G == 128 && g.Gc == 32); // (not with the cross-head mean)
-    if (!((g.G == 32 && g.Gc == 32) || (g.G == 64 && g.Gc == 64) || (g.G == 128 && g.Gc == 128) || (mixed && g.mean_mode != 1)))
-        return false;
+    const bool sizes = (g.G == 32 || g.G == 64 || g.G == 128) && (g.Gc == 32 || g.Gc == 64 || g.Gc == 128);
+    if (!sizes) return false;
+    if (g.G != g.Gc && g.mean_mode == 1) return false; // the cross-head forms take equal sizes only
     if (a.g > 8) return false;
     if (g.mean_mode == 1 && a.n_q_heads > 64) return false; // the dense mean terms keep all query heads of a sequence in LDS
     if (a.batch * a.n_kv_heads > 65535) return false;

@@ -95,11 +95,11 @@ def test_bulk_append_of_long_blocks_in_uneven_calls(kv, oracle, G, Gc, bits, mod
 @pytest.mark.parametrize("mode", [CHAN, NONE])
 @pytest.mark.parametrize("g", [4, 8])
 @pytest.mark.parametrize("bits", [2, 4, 8])
-@pytest.mark.parametrize("G,Gc", [(32, 128), (128, 32)])
+@pytest.mark.parametrize("G,Gc", [(32, 64), (32, 128), (64, 32), (64, 128), (128, 32), (128, 64)])
 def test_mixed_group_sizes(kv, oracle, decode_path, G, Gc, bits, g, mode):
-    """Key groups of 32 tokens with one value group per token, and key groups of 128 tokens with value
-    groups of 32 channels: served by the matrix-core kernels under the automatic choice (several
-    chunks per wave, a ragged tail of raw tokens, one and two head groups)."""
+    """Key groups (tokens) and value groups (channels) of different sizes: served by the matrix-core
+    kernels under the automatic choice (several chunks per wave, a ragged tail of raw tokens, one and
+    two head groups)."""
     print("case mixed groups G=%d Gc=%d bits=%d g=%d mode=%d" % (G, Gc, bits, g, mode), flush=True)
     B, H = 2, 2
     T = 9 * 128 + 77
