@@ -1387,13 +1387,14 @@ template <int B, int G, int GC, bool PG, class F> void pick_mean_heads_pg(const 
 {
     constexpr int NW = kWavesPerBlock;
     const int mode = a.geom.mean_mode; // 0 per-channel block mean, 1 cross-head mean, 2 none
+    // (the cross-head forms exist for equal group sizes only: decode_mfma_supported)
     if (a.g <= 4) {
         if (mode == 0) f.template run<B, G, GC, true, NW, 1, 0, PG>(a);
-        else if (mode == 1) f.template run<B, G, GC, false, NW, 1, 1, PG>(a);
+        else if (mode == 1) { if constexpr (G == GC) f.template run<B, G, GC, false, NW, 1, 1, PG>(a); }
         else f.template run<B, G, GC, false, NW, 1, 0, PG>(a);
     } else {
         if (mode == 0) f.template run<B, G, GC, true, NW, 2, 0, PG>(a);
-        else if (mode == 1) f.template run<B, G, GC, false, NW, 2, 1, PG>(a);
+        else if (mode == 1) { if constexpr (G == GC) f.template run<B, G, GC, false, NW, 2, 1, PG>(a); }
         else f.template run<B, G, GC, false, NW, 2, 0, PG>(a);
     }
 }
