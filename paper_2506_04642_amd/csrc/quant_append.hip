@@ -1322,8 +1322,10 @@ hipError_t launch_flush(const AppendArgs &a, hipStream_t s)
         if (a.rope != 0) return a.geom.Gc == 32 ? TADAKV_COOP(64, 32, true) : a.geom.Gc == 64 ? TADAKV_COOP(64, 64, true) : TADAKV_COOP(64, 128, true);
         return a.geom.Gc == 32 ? TADAKV_COOP(64, 32, false) : a.geom.Gc == 64 ? TADAKV_COOP(64, 64, false) : TADAKV_COOP(64, 128, false);
     }
-    if (coop && a.geom.G == 128 && a.geom.Gc == 128 && kb == a.geom.v_bits && kb != 16)
-        return a.rope != 0 ? TADAKV_COOP(128, 128, true) : TADAKV_COOP(128, 128, false);
+    if (coop && a.geom.G == 128 && kb == a.geom.v_bits && kb != 16) {
+        if (a.rope != 0) return a.geom.Gc == 32 ? TADAKV_COOP(128, 32, true) : a.geom.Gc == 64 ? TADAKV_COOP(128, 64, true) : TADAKV_COOP(128, 128, true);
+        return a.geom.Gc == 32 ? TADAKV_COOP(128, 32, false) : a.geom.Gc == 64 ? TADAKV_COOP(128, 64, false) : TADAKV_COOP(128, 128, false);
+    }
 #undef TADAKV_COOP
     if (a.geom.G == 64 && kb == a.geom.v_bits && kb != 16) {
         // blocks of 64 tokens: the same arithmetic in two passes over two parts of 32 tokens

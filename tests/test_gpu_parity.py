@@ -76,7 +76,7 @@ def test_bit_widths_and_groups(kv, oracle, bits, dtype, G, Gc):
 
 
 @pytest.mark.parametrize("mode", [CHAN, CROSS, NONE])
-@pytest.mark.parametrize("G,Gc,bits", [(64, 32, 4), (64, 64, 2), (64, 128, 8), (128, 128, 4), (128, 128, 2)])
+@pytest.mark.parametrize("G,Gc,bits", [(64, 32, 4), (64, 64, 2), (64, 128, 8), (128, 128, 4), (128, 128, 2), (128, 32, 8), (128, 64, 2)])
 def test_bulk_append_of_long_blocks_in_uneven_calls(kv, oracle, G, Gc, bits, mode):
     """Blocks of 64 / 128 tokens through the bulk append (a workgroup per item, a wave per 32-token
     part): calls that leave raw tokens behind, calls whose first block takes rows from the raw buffer
