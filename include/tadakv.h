@@ -342,7 +342,8 @@ kv_status kv_decode_bytes(const kv_cache *cache, int32_t layer, size_t *bytes);
  * 1 = portable vector-ALU kernels, 2 = matrix-core (MFMA) kernels where supported.
  * The matrix-core kernels serve layers with k_bits == v_bits in {2, 4, 8}, group_tokens ==
  * group_channels in {32, 64, 128} -- and, except with KV_MEAN_CROSS_HEAD, any pair of these
- * sizes -- and up to 8 query heads per kv head (with KV_MEAN_CROSS_HEAD:
+ * sizes, and with groups of 32 / 32 under dense placement also k_bits != v_bits (both in {2, 4, 8})
+ * -- and up to 8 query heads per kv head (with KV_MEAN_CROSS_HEAD:
  * at most 64 query heads); with path 2 a decode of any other layer returns KV_E_UNSUPPORTED.  The
  * vector-ALU kernels serve every format (about twenty times slower: use kv_decode_path_used to see
  * which family a layer gets).  Returns KV_E_BAD_CONFIG for other values.  Affects later calls on
@@ -351,8 +352,8 @@ kv_status kv_set_decode_path(kv_cache *cache, int32_t path);
 
 /* Which kernel family a decode call of `layer` would run on in the cache's present state:
  * *path = 1 (vector-ALU kernels) or 2 (matrix-core kernels).  A layer whose format the matrix-core
- * kernels do not take (different widths for keys and values, group_tokens != group_channels with
- * KV_MEAN_CROSS_HEAD, a 16-bit layer) is served by the vector-ALU kernels under the automatic choice, at a small fraction
+ * kernels do not take (different widths for keys and values with other groups than 32 / 32 or with a
+ * block table, group_tokens != group_channels with KV_MEAN_CROSS_HEAD, a 16-bit layer) is served by the vector-ALU kernels under the automatic choice, at a small fraction
  * of the rate: this call makes that visible.  Errors as kv_decode_splits. */
 kv_status kv_decode_path_used(const kv_cache *cache, int32_t layer, int32_t *path);
 

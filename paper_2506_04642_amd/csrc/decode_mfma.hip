@@ -160,14 +160,19 @@ __device__ __forceinline__ void softmax_chunk(const float (&s)[4], State &st, fl
 }
 
 // Record layout for one template instance; must agree with the layer geometry built on the host.
+// B: the code width; layers whose keys and values differ in width carry both, keys' | values' << 4
+// (kbits_of, vbits_of)
+constexpr int kbits_of(int B) { return B & 15; }
+constexpr int vbits_of(int B) { return (B >> 4) ? (B >> 4) : (B & 15); }
 template <int B, int G, int GC, bool MEAN> struct RecLayout {
-    static constexpr int KC = G * kHeadDim * B / 8;          // bytes of key (and of value) codes
+    static constexpr int KC = G * kHeadDim * kbits_of(B) / 8; // bytes of key codes
+    static constexpr int VC = G * kHeadDim * vbits_of(B) / 8; // bytes of value codes
     static constexpr int K_CODES = 0;
     static constexpr int K_SCALE = KC;
     static constexpr int K_ZERO = KC + 256;
     static constexpr int K_MEAN = KC + 512;
     static constexpr int V_CODES = KC + 512 + (MEAN ? 256 : 0);
-    static constexpr int V_META = V_CODES + KC;
+    static constexpr int V_META = V_CODES + VC;
     static constexpr int V_MEAN = V_META + G * (kHeadDim / GC) * 4;
     static constexpr int REC = (V_MEAN + (MEAN ? 256 : 0) + 255) / 256 * 256;
     static bool matches(const LayerGeom &g)
@@ -287,7 +292,7 @@ __device__ __forceinline__ void stage_issue_half(const unsigned char *src, int h
     typedef RecLayout<B, 64, GC, MEAN> RL;   // the image
     typedef RecLayout<B, 128, GC, MEAN> RS;  // the record
     constexpr int NG = kHeadDim / GC;
-    static_assert(RS::KC == 2 * RL::KC && RL::KC % 1024 == 0, "code halves");
+    static_assert(RS::KC == 2 * RL::KC && RL::KC % 1024 == 0 && RL::KC == RL::VC, "code halves (one width for keys and values)");
     stage_issue<RL::KC>(src + RS::K_CODES + hf * RL::KC, dst + RL::K_CODES / 4, lane);
     if (shared) stage_issue<512 + (MEAN ? 256 : 0)>(src + RS::K_SCALE, dst + RL::K_SCALE / 4, lane);
 #pragma unroll
@@ -371,8 +376,9 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
     constexpr int TPB = G / 16;            // 16-token tiles per block
     constexpr int NG = kHeadDim / GC;      // value scale groups
     constexpr int TPG = GC / 16;           // channel tiles per value scale group
-    constexpr int NKL = (B == 4) ? 4 : (B == 2 ? 2 : 8); // key code pieces per lane and chunk
-    constexpr int NVL = (B == 4) ? 4 : (B == 2 ? 2 : 8); // value code pieces per lane and chunk
+    constexpr int KB = kbits_of(B), VB = vbits_of(B);       // code widths of keys and of values
+    constexpr int NKL = (KB == 4) ? 4 : (KB == 2 ? 2 : 8); // key code pieces per lane and chunk
+    constexpr int NVL = (VB == 4) ? 4 : (VB == 2 ? 2 : 8); // value code pieces per lane and chunk
     constexpr int REC = RL::REC;
     constexpr int CB = NBC * REC;          // bytes of one chunk
     constexpr int STAGE_DW = CB / 4;       // staging buffer of a wave
@@ -477,13 +483,13 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
             for (int bi = 0; bi < NBC; bi++) {
                 const long long slot = __builtin_amdgcn_readlane(slotv[bi], it - slot_base);
                 const unsigned char *rec = a.layer + (slot * a.n_kv_heads + h) * SREC;
-                if (H2) stage_issue_half<B, GC, MEAN>(rec, blk0 & 1, !(blk0 & 1), stage, lane);
+                if constexpr (H2) stage_issue_half<B, GC, MEAN>(rec, blk0 & 1, !(blk0 & 1), stage, lane);
                 else stage_issue<REC>(rec, stage + bi * (REC / 4), lane);
             }
             return;
         }
         const unsigned char *src = unit_base + (long long)(blk0 / HB) * SREC;
-        if (H2) {
+        if constexpr (H2) {
             stage_issue_half<B, GC, MEAN>(src, blk0 & 1, !(blk0 & 1), stage, lane);
         } else if (NBC == 1 || blk0 + 1 < b_end) {
             stage_issue<CB>(src, stage, lane);
@@ -749,7 +755,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
     PHASE_INIT
     for (int ci = cw0, itn = 0; ci < n_chunks; ci += CW, itn++) {
         PHASE_ITER
-        if (B != 8) { // the 8-bit instance runs one wave per SIMD: nothing to arbitrate
+        if (KB != 8 || VB != 8) { // the 8-bit instance runs one wave per SIMD: nothing to arbitrate
             const int quart = itn * 4 / my_iters;
             if (quart == 0) __builtin_amdgcn_s_setprio(3);
             else if (quart == 1) __builtin_amdgcn_s_setprio(2);
@@ -790,8 +796,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
 #pragma unroll
         for (int i = 0; i < NKL; i++) {
             int bi, off;
-            if (B == 4) { bi = i / TPB; off = (i % TPB) * 64; }
-            else if (B == 2) { bi = (2 * i) / TPB; off = (((2 * i) % TPB) / 2) * 64; }
+            if (KB == 4) { bi = i / TPB; off = (i % TPB) * 64; }
+            else if (KB == 2) { bi = (2 * i) / TPB; off = (((2 * i) % TPB) / 2) * 64; }
             else { bi = (i / 2) / TPB; off = (((i / 2) % TPB) * 2 + (i & 1)) * 64; }
             kc[i] = *(const uint4 *)(sb8 + bi * REC + RL::K_CODES + (off + lane) * 16);
         }
@@ -917,12 +923,12 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
 #pragma unroll
             for (int k = bi * TPB; k < (bi + 1) * TPB; k++) {
                 v4i acc[NHG];
-                if (B == 4) {
+                if (KB == 4) {
                     const uint4 w = kc[k];
                     const v4i b0 = CodeOps<4>::line(w.x, w.y), b1 = CodeOps<4>::line(w.z, w.w);
 #pragma unroll
                     for (int hg = 0; hg < NHG; hg++) acc[hg] = mfma(a1[hg], b1, mfma(a0[hg], b0, v4i{0, 0, 0, 0}));
-                } else if (B == 2) {
+                } else if (KB == 2) {
                     const uint4 w = kc[k >> 1];
                     const v4i b0 = CodeOps<2>::line((k & 1) ? w.z : w.x), b1 = CodeOps<2>::line((k & 1) ? w.w : w.y);
 #pragma unroll
@@ -1059,12 +1065,12 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
             for (int ct = vp * NGP * TPG; ct < (vp + 1) * NGP * TPG; ct++) {
                 const int gl = ct / TPG - vp * NGP;
                 v4i acc[NHG];
-                if (B == 4) {
+                if (VB == 4) {
                     const uint4 w = vc[ct >> 1];
                     const v4i bo = CodeOps<4>::line((ct & 1) ? w.z : w.x, (ct & 1) ? w.w : w.y);
 #pragma unroll
                     for (int hg = 0; hg < NHG; hg++) acc[hg] = mfma(avr[hg][gl], bo, v4i{0, 0, 0, 0});
-                } else if (B == 2) {
+                } else if (VB == 2) {
                     const uint4 w = vc[ct >> 2];
                     const uint32_t ww = (ct & 3) == 0 ? w.x : ((ct & 3) == 1 ? w.y : ((ct & 3) == 2 ? w.z : w.w));
                     const v4i bo = CodeOps<2>::line(ww);
@@ -1109,7 +1115,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((B == 2
     }
     PHASE(12)
 
-    if (B != 8) __builtin_amdgcn_s_setprio(0);
+    if (KB != 8 || VB != 8) __builtin_amdgcn_s_setprio(0);
 
     // fused cross-head form: the value mean's share goes from the waves that summed it (all heads, a
     // channel tile) to the waves that own the heads, through the buffer the scores went through
@@ -1390,11 +1396,11 @@ template <int B, int G, int GC, bool PG, class F> void pick_mean_heads_pg(const 
     // (the cross-head forms exist for equal group sizes only: decode_mfma_supported)
     if (a.g <= 4) {
         if (mode == 0) f.template run<B, G, GC, true, NW, 1, 0, PG>(a);
-        else if (mode == 1) { if constexpr (G == GC) f.template run<B, G, GC, false, NW, 1, 1, PG>(a); }
+        else if (mode == 1) { if constexpr (G == GC && B < 16) f.template run<B, G, GC, false, NW, 1, 1, PG>(a); }
         else f.template run<B, G, GC, false, NW, 1, 0, PG>(a);
     } else {
         if (mode == 0) f.template run<B, G, GC, true, NW, 2, 0, PG>(a);
-        else if (mode == 1) { if constexpr (G == GC) f.template run<B, G, GC, false, NW, 2, 1, PG>(a); }
+        else if (mode == 1) { if constexpr (G == GC && B < 16) f.template run<B, G, GC, false, NW, 2, 1, PG>(a); }
         else f.template run<B, G, GC, false, NW, 2, 0, PG>(a);
     }
 }
@@ -1445,6 +1451,18 @@ template <class F> void pick(const DecodeArgs &a, F &f)
         }
         return;
     }
+    if (a.geom.k_bits != a.geom.v_bits) {
+        // keys and values of different widths: groups of 32 tokens / 32 channels
+        const int kb = a.geom.k_bits, vb = a.geom.v_bits;
+        // (dense placement only: the paged instances of six more width pairs are not worth their compile time)
+        if (kb == 2 && vb == 4) pick_mean_heads_pg<2 | 4 << 4, 32, 32, false>(a, f);
+        else if (kb == 2 && vb == 8) pick_mean_heads_pg<2 | 8 << 4, 32, 32, false>(a, f);
+        else if (kb == 4 && vb == 2) pick_mean_heads_pg<4 | 2 << 4, 32, 32, false>(a, f);
+        else if (kb == 4 && vb == 8) pick_mean_heads_pg<4 | 8 << 4, 32, 32, false>(a, f);
+        else if (kb == 8 && vb == 2) pick_mean_heads_pg<8 | 2 << 4, 32, 32, false>(a, f);
+        else pick_mean_heads_pg<8 | 4 << 4, 32, 32, false>(a, f);
+        return;
+    }
     // every pair (tokens per key group, channels per value group) of 32, 64, 128
 #define TADAKV_PICK(GV, GCV)                                      \
     if (a.geom.G == GV && a.geom.Gc == GCV) {                     \
@@ -1472,8 +1490,8 @@ bool xhead_fused(const DecodeArgs &a) { return decode_mfma_supported(a) && xhead
 bool decode_mfma_supported(const DecodeArgs &a)
 {
     const LayerGeom &g = a.geom;
-    if (g.k_bits != g.v_bits) return false;
-    if (!(g.k_bits == 2 || g.k_bits == 4 || g.k_bits == 8)) return false;
+    if (!(g.k_bits == 2 || g.k_bits == 4 || g.k_bits == 8) || !(g.v_bits == 2 || g.v_bits == 4 || g.v_bits == 8)) return false;
+    if (g.k_bits != g.v_bits && !(g.G == 32 && g.Gc == 32 && g.mean_mode != 1 && g.table == nullptr)) return false; // different widths: one format, dense
     const bool sizes = (g.G == 32 || g.G == 64 || g.G == 128) && (g.Gc == 32 || g.Gc == 64 || g.Gc == 128);
     if (!sizes) return false;
     if (g.G != g.Gc && g.mean_mode == 1) return false; // the cross-head forms take equal sizes only

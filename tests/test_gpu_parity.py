@@ -168,6 +168,24 @@ def test_different_widths_for_keys_and_values(kv, oracle, kb, vb):
     check_attention(gpu, orc, 0, synth.make_q(3, 1, 4, 128, BF16), BF16)
 
 
+@pytest.mark.parametrize("mode", [CHAN, NONE])
+@pytest.mark.parametrize("g", [4, 8])
+@pytest.mark.parametrize("kb,vb", [(2, 4), (2, 8), (4, 2), (4, 8), (8, 2), (8, 4)])
+def test_different_widths_on_both_kernel_families(kv, oracle, decode_path, kb, vb, g, mode):
+    """Keys and values of different widths (groups of 32): the matrix-core kernels serve them under the
+    automatic choice; several chunks per wave, a ragged tail of raw tokens, one and two head groups, a
+    one-call decode step at the end."""
+    print("case kv_widths both kb=%d vb=%d g=%d mode=%d" % (kb, vb, g, mode), flush=True)
+    B, H = 2, 2
+    T = 40 * 32 + 19
+    gpu, orc = make_pair(kv, oracle, B=B, Hq=H * g, Hkv=H, T_max=42 * 32, dtype=BF16, mode=mode, k_bits=(kb,), v_bits=(vb,))
+    k, v = synth.make_kv(7100 + 10 * kb + vb + g, B, T, H, 128, BF16)
+    append_both(gpu, orc, 0, k, v, BF16, chunks=[T - 1, 1])
+    assert kv.kv_decode_path_used(gpu.handle, 0) == (1 if decode_path == 1 else 2)
+    check_bytes(gpu, orc, 0)
+    check_attention(gpu, orc, 0, synth.make_q(7100 + kb + g, B, H * g, 128, BF16), BF16)
+
+
 @pytest.mark.parametrize("mode", [CHAN, NONE, CROSS])
 @pytest.mark.parametrize("g", [1, 2, 4, 8])
 def test_mean_modes_and_query_groups(kv, oracle, mode, g):
@@ -188,12 +206,14 @@ def test_decode_path_used_reports_the_kernel_family(kv, oracle):
     k, v = synth.make_kv(91, 1, 40, 1, 128, BF16)
     for l in range(3):
         append_both(gpu, orc, l, k, v, BF16)
-    want = (1, 1, 1) if parity_util.DECODE_PATH == 1 else (2, 1, 1)
+    # (layer 1: keys and values of different widths, which the matrix-core kernels take with groups of 32;
+    # layer 2: a 16-bit layer, which they do not)
+    want = (1, 1, 1) if parity_util.DECODE_PATH == 1 else (2, 2, 1)
     assert tuple(kv.kv_decode_path_used(gpu.handle, l) for l in range(3)) == want
     kv.kv_set_decode_path(gpu.handle, 2)
-    assert kv.kv_decode_path_used(gpu.handle, 0) == 2
+    assert kv.kv_decode_path_used(gpu.handle, 0) == 2 and kv.kv_decode_path_used(gpu.handle, 1) == 2
     with pytest.raises(kv.KVError) as e:
-        kv.kv_decode_path_used(gpu.handle, 1)
+        kv.kv_decode_path_used(gpu.handle, 2)
     assert e.value.status == kv.KV_E_UNSUPPORTED
 
 
