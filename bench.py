@@ -59,7 +59,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--separate-append", dest="fused_step", action="store_false",
                     help="append and attend as two calls per layer instead of the one-call decode step")
-    ap.add_argument("--legs", default="c0,c1,c3,c4,cross,cross128,mixed,compressv,graph",
+    ap.add_argument("--legs", default="c0,c1,c3,c4,cross,cross128,mixed,widths,compressv,graph",
                     help="other configurations measured after the headline one (comma list, or 'none')")
     ap.add_argument("--leg-steps", type=int, default=8, help="timed decode steps of each other configuration")
     return ap.parse_args()
@@ -97,7 +97,7 @@ class Env:
         return self.torch.cuda.Event(enable_timing=True), self.torch.cuda.Event(enable_timing=True)
 
 
-def run_decode_workload(env, *, L, B, Hq, Hkv, G, T0, steps, warmup, scheme, seed, Gc=0, mean_mode="channel", path=0,
+def run_decode_workload(env, *, L, B, Hq, Hkv, G, T0, steps, warmup, scheme, seed, Gc=0, v_bits=None, mean_mode="channel", path=0,
                         paged=False, resid=0, splits=0, fused_step=True, sample_seqs=0, shared_inputs=False, chunk=4096):
     """Fill a cache by bulk quantise-append, then time `steps` decode steps (per layer: append one token
     per sequence, attend over the whole cache).  Returns (figures, state); state keeps the cache and the
@@ -112,7 +112,10 @@ def run_decode_workload(env, *, L, B, Hq, Hkv, G, T0, steps, warmup, scheme, see
     bits = synth.layer_bits(seed, L, scheme)
     mm = {"channel": kv.KV_MEAN_CHANNEL_BLOCK, "cross": kv.KV_MEAN_CROSS_HEAD, "none": kv.KV_MEAN_NONE}[mean_mode]
     pool = B * (max_tokens // G) if paged else 0
-    cfg = kv.make_config(L, B, Hq, Hkv, d, max_tokens, G, Gc or G, R, kv.KV_BF16, mm, bits, bits, pool_blocks=pool)  # (Gc = 0: Gc = G)
+    if v_bits is not None:  # keys and values of different widths: one pair for all layers
+        bits = [v_bits[0]] * L
+    cfg = kv.make_config(L, B, Hq, Hkv, d, max_tokens, G, Gc or G, R, kv.KV_BF16, mm, bits, [v_bits[1]] * L if v_bits else bits,
+                         pool_blocks=pool)  # (Gc = 0: Gc = G)
     cache = kv.KVCache(cfg, device=dev, zero=False)
     if paged:
         perm = np.random.default_rng(seed).permutation(pool).astype(np.int32).reshape(B, max_tokens // G)
@@ -649,6 +652,12 @@ def main():
                                   "first 8 layers of the bit map, batch 16, context 32768")
                 other["mixed_group_sizes"] = fm
                 release(env, sm)
+            elif leg == "widths":
+                fw, sw = run_decode_workload(env, L=8, B=16, Hq=32, Hkv=8, G=32, T0=32768, steps=ks, warmup=kw, v_bits=(4, 2),
+                                             scheme="mixed248", seed=2000, shared_inputs=True)
+                fw["workload"] = "headline shape with 4-bit keys and 2-bit values in all of 8 layers, batch 16, context 32768"
+                other["different_widths_k4_v2"] = fw
+                release(env, sw)
             elif leg == "graph":
                 # the headline shape's first 8 layers and the batch-1 long context, eager and replayed
                 fg, sg = run_decode_workload(env, L=8, B=16, Hq=32, Hkv=8, G=32, T0=32768, steps=ks, warmup=kw,
