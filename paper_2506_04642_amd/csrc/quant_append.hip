@@ -389,7 +389,7 @@ template <int GC, int BITS, bool ROPE>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 8))) void flush_wave_kernel(AppendArgs a, int n_items)
 {
     constexpr int G = 32;
-    constexpr int bits = BITS; // keys and values of the layer share the width in this instance
+    constexpr int bits = BITS; // the width of the items this launch handles (both sides of a layer with one width, or one side)
     constexpr int NGV = kHeadDim / GC;
     const LayerGeom &gm = a.geom;
     const int lane = threadIdx.x & 63;
@@ -1304,6 +1304,28 @@ hipError_t launch_flush(const AppendArgs &a, hipStream_t s)
         if (e != hipSuccess) return e;
     }
     const int kb = a.geom.k_bits;
+    {
+        // blocks of 32 tokens, keys and values of different widths (per-channel mean or none): the keys' side
+        // and the values' side as two launches of the one-wavefront-per-item quantiser, each at its own width
+        const int vb = a.geom.v_bits, gc = a.geom.Gc;
+        const bool widths = (kb == 2 || kb == 4 || kb == 8) && (vb == 2 || vb == 4 || vb == 8) && kb != vb;
+        if (a.geom.G == 32 && widths && a.geom.mean_mode != 1 && a.sides == 0 && a.len_dev == nullptr) {
+            auto side = [&](int which, int bits, bool rope) -> hipError_t {
+                AppendArgs x = a;
+                x.sides = which + 1;
+                if (!rope) x.rope = 0;
+#define TADAKV_SIDE(GCV, R)                                                                       \
+    (bits == 2 ? launch_flush_wave<GCV, 2, R>(x, s) : bits == 4 ? launch_flush_wave<GCV, 4, R>(x, s) \
+                                                               : launch_flush_wave<GCV, 8, R>(x, s))
+                if (rope) return gc == 32 ? TADAKV_SIDE(32, true) : gc == 64 ? TADAKV_SIDE(64, true) : TADAKV_SIDE(128, true);
+                return gc == 32 ? TADAKV_SIDE(32, false) : gc == 64 ? TADAKV_SIDE(64, false) : TADAKV_SIDE(128, false);
+#undef TADAKV_SIDE
+            };
+            const hipError_t e = side(0, kb, a.rope != 0);
+            if (e != hipSuccess) return e;
+            return side(1, vb, false);
+        }
+    }
     if (a.geom.G == 32 && kb == a.geom.v_bits && kb != 16) {
         // blocks of 32 tokens, one width for keys and values: one wavefront per item, registers only
         const int gc = a.geom.Gc;
